@@ -1,0 +1,331 @@
+"""Pins for the CPU oracle: it is checked against what the paper and the
+mathematics fix, by routes that do not go through the oracle's own formulas
+(hand-written loops, scipy's softmax, closed forms, the paper's printed
+worked example)."""
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+
+from oracle import tkphi_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand_problem(rng, L=200, d=16, dphi=24, Hq=4, Hkv=2, wscale=0.4, kscale=0.7):
+    q = rng.standard_normal((Hq, d))
+    K = kscale * rng.standard_normal((Hkv, L, d))
+    V = rng.standard_normal((Hkv, L, d))
+    Wk = wscale * rng.standard_normal((Hkv, dphi, d))
+    Wq = wscale * rng.standard_normal((Hq, dphi, d))       # phi_q != phi_k allowed
+    bk = 0.1 * rng.standard_normal((Hkv, dphi))
+    bq = 0.1 * rng.standard_normal((Hq, dphi))
+    return dict(q=q, K=K, V=V, Wk=Wk, Wq=Wq, bk=bk, bq=bq, a=0.5, c=0.125,
+                scale=1.0 / math.sqrt(d), n_sink=3, n_tail=7)
+
+
+def _run(P, k, **kw):
+    S, u = orc.build_summaries(P["K"], P["V"], P["Wk"], P["bk"], P["a"], P["c"],
+                               P["n_sink"], P["n_tail"])
+    return orc.decode_layer(P["q"], P["K"], P["V"], S, u, P["Wq"], P["bq"], P["Wk"], P["bk"],
+                            P["a"], P["c"], P["scale"], P["n_sink"], P["n_tail"], k, **kw), S, u
+
+
+def _dense_softmax_attention(q, K, V, scale):
+    # independent route: scipy's max-shifted softmax
+    w = scipy.special.softmax(scale * (K @ q))
+    return w @ V
+
+
+# --- worked example printed in the paper -----------------------------------
+def test_budget_rule_matches_paper_worked_example():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "budget_rule.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 3
+    for L, bp, ns, nt, K in rows:
+        assert orc.budget_paper(int(L), int(bp), int(ns), int(nt)) == int(K)
+    # the max{0, .} branch: 68 anchors exceed 1 % of 4096
+    assert orc.budget_paper(4096, 100, 4, 64) == 0
+    # the synthetic workloads' convention: 1 % of the 4028 mid tokens -> 40
+    assert orc.budget_mid(4096, 100, 4, 64) == 40
+    assert orc.budget_mid(32768, 100, 4, 64) == 327
+    assert [orc.budget_mid(131072, bp, 4, 64) for bp in (50, 100, 200, 400)] == [655, 1310, 2620, 5240]
+
+
+def test_summary_state_size_matches_paper():
+    row = [l.split() for l in open(os.path.join(GOLDEN, "summary_state_size.txt"))
+           if l.strip() and not l.startswith("#")][0]
+    Hkv, d, dphi, nl, eb = (int(x) for x in row[:5])
+    P = _rand_problem(np.random.default_rng(0), L=40, d=d, dphi=dphi, Hq=Hkv, Hkv=Hkv)
+    S, u = orc.build_summaries(P["K"], P["V"], P["Wk"], P["bk"], P["a"], P["c"], 3, 7)
+    per_layer = (S.size + u.size) * eb
+    assert per_layer == 66560
+    assert abs(per_layer / 1024 - float(row[5])) / float(row[5]) < 0.03
+    assert abs(per_layer * nl / 2 ** 20 - float(row[6])) / float(row[6]) < 0.03
+
+
+# --- partition -----------------------------------------------------------------
+def test_partition_sets():
+    A, M = orc.partition(10, 2, 3)
+    assert A.tolist() == [0, 1, 7, 8, 9] and M.tolist() == [2, 3, 4, 5, 6]
+    A, M = orc.partition(5, 2, 3)
+    assert A.tolist() == [0, 1, 2, 3, 4] and M.size == 0
+    A, M = orc.partition(4, 4, 64)
+    assert A.tolist() == [0, 1, 2, 3] and M.size == 0
+    A, M = orc.partition(6, 0, 0)
+    assert A.size == 0 and M.tolist() == list(range(6))
+
+
+# --- Top-K: brute force, with ties ---------------------------------------------
+def test_topk_equals_bruteforce_with_ties():
+    rng = np.random.default_rng(1)
+    for trial in range(50):
+        L = int(rng.integers(12, 200))
+        ns, nt = int(rng.integers(0, 4)), int(rng.integers(0, 6))
+        _, M = orc.partition(L, ns, nt)
+        # few distinct values -> many exact ties
+        s = rng.integers(-3, 4, size=L).astype(np.float64) * 0.25
+        k = int(rng.integers(0, M.size + 3))
+        got = orc.topk_mid(s, M, k)
+        brute = sorted(M.tolist(), key=lambda i: (-s[i], i))[:min(k, M.size)]
+        assert got.tolist() == brute
+        assert all(ns <= i < L - nt for i in got)
+
+
+def test_topk_never_returns_anchor_even_if_anchor_scores_highest():
+    s = np.array([9.0, 8.0, 0.1, 0.3, 0.2, 7.0])
+    _, M = orc.partition(6, 2, 1)
+    assert orc.topk_mid(s, M, 2).tolist() == [3, 4]
+
+
+# --- scores / GQA map / orientation --------------------------------------------
+def test_scores_and_gqa_mapping_by_hand():
+    rng = np.random.default_rng(2)
+    P = _rand_problem(rng, L=30, d=8, dphi=5, Hq=6, Hkv=2)
+    res, S, u = _run(P, 4)
+    G = 3
+    for g in range(6):
+        h = g // G
+        for i in (0, 7, 29):
+            s_hand = sum(P["q"][g][c] * P["K"][h][i][c] for c in range(8)) / math.sqrt(8)
+            assert abs(res[g]["s"][i] - s_hand) < 1e-13
+
+
+def test_summary_orientation_and_phi_formula_by_hand():
+    # one mid token: S must be the outer product phi(k) v^T, feature-major
+    rng = np.random.default_rng(3)
+    d, dphi = 4, 3
+    K = rng.standard_normal((1, 3, d))
+    V = rng.standard_normal((1, 3, d))
+    W = rng.standard_normal((1, dphi, d))
+    b = rng.standard_normal((1, dphi))
+    a, c = 0.7, 0.3
+    S, u = orc.build_summaries(K, V, W, b, a, c, 1, 1)      # M = {1}
+    k, v = K[0, 1], V[0, 1]
+    for j in range(dphi):
+        f_j = math.exp(a * sum(W[0, j, t] * k[t] for t in range(d)) - c * sum(x * x for x in k) + b[0, j])
+        assert abs(u[0, j] - f_j) < 1e-13 * max(1, f_j)
+        for ch in range(d):
+            assert abs(S[0, j, ch] - f_j * v[ch]) < 1e-13 * max(1, abs(f_j * v[ch]))
+
+
+# --- P1: dense limit -------------------------------------------------------------
+def test_dense_limit_full_support_equals_softmax_attention():
+    rng = np.random.default_rng(4)
+    P = _rand_problem(rng)
+    n_mid = 200 - 10
+    res, _, _ = _run(P, n_mid)
+    for g, r in enumerate(res):
+        ref = _dense_softmax_attention(P["q"][g], P["K"][g // 2], P["V"][g // 2], P["scale"])
+        assert orc.rel_l1(r["y"], ref) < 1e-12
+        assert orc.rel_l1(r["y_full"], ref) < 1e-13
+        assert orc.rel_l1(orc.full_attention(P["q"][g], P["K"][g // 2], P["V"][g // 2], P["scale"]), ref) < 1e-13
+        # with everything retrieved the residual summaries vanish
+        assert np.abs(r["S_R"]).max() < 1e-11 * np.abs(r["nu_M_hat"]).max() + 1e-12
+    # K larger than |M| is clipped
+    res2, _, _ = _run(P, n_mid + 50)
+    assert all(r2["idx"].size == n_mid for r2 in res2)
+
+
+# --- P2 / P3: subtraction equals brute force over unretrieved tokens; positivity -------
+def test_subtracted_summaries_equal_bruteforce_over_unretrieved():
+    rng = np.random.default_rng(5)
+    P = _rand_problem(rng, L=120)
+    res, S, u = _run(P, 11)
+    for g, r in enumerate(res):
+        h = g // 2
+        retrieved = set(r["idx"].tolist())
+        assert len(retrieved) == 11
+        S_bf = np.zeros_like(S[h])
+        u_bf = np.zeros_like(u[h])
+        for i in range(P["n_sink"], 120 - P["n_tail"]):
+            if i in retrieved:
+                continue
+            k = P["K"][h][i]
+            f = np.array([math.exp(P["a"] * float(P["Wk"][h][j] @ k) - P["c"] * float(k @ k) + P["bk"][h][j])
+                          for j in range(S.shape[1])])
+            S_bf += np.outer(f, P["V"][h][i])
+            u_bf += f
+        assert np.abs(r["S_R"] - S_bf).max() <= 1e-12 * np.abs(S[h]).max()
+        assert np.abs(r["u_R"] - u_bf).max() <= 1e-12 * np.abs(u[h]).max()
+        # positivity: features, residual denominator, merged denominator
+        assert (r["p"] > 0).all() and (r["f_K"] > 0).all() and (u_bf > 0).all()
+        Z_R_bf = float(r["p"] @ u_bf)
+        assert Z_R_bf > 0 and r["Z_R_hat"] > 0 and r["Z_E"] + r["Z_R_hat"] > 0
+        assert abs(r["Z_R_hat"] - Z_R_bf) <= 1e-12 * float(r["p"] @ u[h])
+        # and the output follows from the brute-forced residual summaries
+        y_bf = (r["nu_E"] + S_bf.T @ r["p"]) / (r["Z_E"] + Z_R_bf)
+        assert orc.rel_l1(r["y"], y_bf) < 1e-11
+
+
+# --- P5: subset-renormalisation bias identity --------------------------------------
+def test_subset_bias_identity():
+    rng = np.random.default_rng(6)
+    P = _rand_problem(rng)
+    res, _, _ = _run(P, 9)
+    for r in res:
+        y_R = r["nu_R"] / r["Z_R"]
+        lhs = r["y_full"] - r["y_topk"]
+        rhs = r["Z_R"] / (r["Z_E"] + r["Z_R"]) * (y_R - r["y_topk"])
+        assert np.abs(lhs - rhs).max() < 1e-12
+
+
+# --- P6 / P7: exact-residual estimators and partition sums --------------------------
+def test_exact_sub_recovers_full_and_nosub_double_counts():
+    rng = np.random.default_rng(7)
+    P = _rand_problem(rng)
+    res, _, _ = _run(P, 13)
+    for g, r in enumerate(res):
+        ref = _dense_softmax_attention(P["q"][g], P["K"][g // 2], P["V"][g // 2], P["scale"])
+        assert orc.rel_l1(r["y_exactsub"], ref) < 1e-12
+        assert orc.rel_l1(r["y_exactnosub"], ref) > 1e-6          # double counting is visible
+        assert np.allclose(r["nu_E"], r["nu_A"] + r["nu_K"], rtol=1e-12, atol=0)
+        assert np.allclose(r["nu_M"], r["nu_K"] + r["nu_R"], rtol=1e-12, atol=1e-13)
+        assert abs(r["Z_E"] - (r["Z_A"] + r["Z_K"])) < 1e-12 * r["Z_E"]
+        assert abs(r["Z_M"] - (r["Z_K"] + r["Z_R"])) < 1e-12 * r["Z_M"]
+        # selection-only output is the exact-support ratio
+        E = np.concatenate([np.arange(3), np.arange(193, 200), r["idx"]])
+        w = np.exp(r["s"][E])
+        assert orc.rel_l1(r["y_topk"], (w @ P["V"][g // 2][E]) / w.sum()) < 1e-12
+
+
+# --- P8: closed form with constant features -------------------------------------------
+def test_constant_feature_closed_form():
+    rng = np.random.default_rng(8)
+    P = _rand_problem(rng, dphi=16)
+    dphi = 16
+    P["Wk"][:] = 0.0
+    P["Wq"][:] = 0.0
+    P["c"] = 0.0
+    P["bk"][:] = -0.5 * math.log(dphi)
+    P["bq"][:] = -0.5 * math.log(dphi)
+    res, _, _ = _run(P, 17)                      # z(q,k) == 1 for every pair
+    for g, r in enumerate(res):
+        h = g // 2
+        R = [i for i in range(3, 193) if i not in set(r["idx"].tolist())]
+        y_closed = (r["nu_E"] + P["V"][h][R].sum(axis=0)) / (r["Z_E"] + len(R))
+        assert orc.rel_l1(r["y"], y_closed) < 1e-12
+        assert abs(r["Z_R_hat"] - len(R)) < 1e-10
+
+
+# --- P9: q = 0 makes the factorisation exact --------------------------------------------
+def test_zero_query_exact_factorisation_gives_mean_value():
+    rng = np.random.default_rng(9)
+    P = _rand_problem(rng, dphi=16)
+    P["Wk"][:] = 0.0
+    P["Wq"][:] = 0.0
+    P["c"] = 0.0
+    P["bk"][:] = -0.5 * math.log(16)
+    P["bq"][:] = -0.5 * math.log(16)
+    P["q"][:] = 0.0                               # exp(s_i) = 1 = z(q,k_i)
+    for k in (0, 5, 60, 190):
+        res, _, _ = _run(P, k)
+        for g, r in enumerate(res):
+            mean_v = P["V"][g // 2].mean(axis=0)
+            assert np.abs(r["y"] - mean_v).max() < 1e-12
+            assert np.abs(r["y_full"] - mean_v).max() < 1e-12
+
+
+# --- P10: positive random features converge to the softmax kernel ----------------------
+def test_random_feature_estimate_converges_to_exp_kernel():
+    # E_w exp(w.x - |x|^2/2) exp(w.y - |y|^2/2) = exp(x.y), w ~ N(0, I), with
+    # x = q d^(-1/4), y = k d^(-1/4); b = -ln(dphi)/2 on both maps averages the
+    # dphi features.  A dropped norm term, a wrong sign or a misplaced scale
+    # breaks the convergence.
+    rng = np.random.default_rng(10)
+    d, L = 8, 64
+    q = 0.6 * rng.standard_normal(d)
+    K = 0.6 * rng.standard_normal((L, d))
+    a, c = d ** -0.25, 1.0 / (2.0 * math.sqrt(d))
+    target = np.exp(K @ q / math.sqrt(d))
+    errs = []
+    for dphi in (2 ** 8, 2 ** 12, 2 ** 16):
+        W = rng.standard_normal((dphi, d))
+        b = np.full(dphi, -0.5 * math.log(dphi))
+        z = orc.phi(K, W, b, a, c) @ orc.phi(q, W, b, a, c)[0]
+        errs.append(np.abs(z / target - 1).mean())
+    assert errs[2] < 0.02
+    assert errs[2] < errs[1] < errs[0]
+    assert errs[0] / errs[2] > 6          # ~ sqrt(256) = 16 expected
+
+
+def test_ideal_factorisation_recovers_full_attention_any_k():
+    # With 2^16 random features on a short sequence the kernel estimate is nearly
+    # exact, so the Top-K+phi output approaches full attention for every K
+    # (Sec. "Single-normalization merge"), and far better than selection-only Top-K.
+    rng = np.random.default_rng(11)
+    d, L, dphi = 8, 96, 2 ** 16
+    q = 0.6 * rng.standard_normal((1, d))
+    K = 0.6 * rng.standard_normal((1, L, d))
+    V = rng.standard_normal((1, L, d))
+    W = rng.standard_normal((1, dphi, d))
+    b = np.full((1, dphi), -0.5 * math.log(dphi))
+    a, c, sc = d ** -0.25, 1.0 / (2.0 * math.sqrt(d)), 1.0 / math.sqrt(d)
+    S, u = orc.build_summaries(K, V, W, b, a, c, 2, 4)
+    ref = _dense_softmax_attention(q[0], K[0], V[0], sc)
+    for k in (0, 8, 40):
+        r = orc.decode_layer(q, K, V, S, u, W, b, W, b, a, c, sc, 2, 4, k)[0]
+        assert orc.rel_l1(r["y"], ref) < 0.05
+        assert orc.rel_l1(r["y"], ref) < 0.5 * orc.rel_l1(r["y_topk"], ref)
+
+
+# --- P12: K = 0 -----------------------------------------------------------------------
+def test_zero_budget_is_anchors_plus_unsubtracted_summaries():
+    rng = np.random.default_rng(12)
+    P = _rand_problem(rng)
+    res, S, u = _run(P, 0)
+    for g, r in enumerate(res):
+        h = g // 2
+        assert r["idx"].size == 0
+        A = list(range(3)) + list(range(193, 200))
+        w = np.exp(r["s"][A])
+        y0 = (w @ P["V"][h][A] + S[h].T @ r["p"]) / (w.sum() + r["p"] @ u[h])
+        assert orc.rel_l1(r["y"], y0) < 1e-12
+        assert orc.rel_l1(r["y"], r["y_nosub"]) < 1e-12
+
+
+def test_no_mid_region_reduces_to_dense_attention():
+    rng = np.random.default_rng(13)
+    P = _rand_problem(rng, L=9)            # 3 sink + 7 tail >= 9
+    res, S, u = _run(P, 5)
+    assert np.all(S == 0) and np.all(u == 0)
+    for g, r in enumerate(res):
+        ref = _dense_softmax_attention(P["q"][g], P["K"][g // 2], P["V"][g // 2], P["scale"])
+        assert orc.rel_l1(r["y"], ref) < 1e-12
+
+
+def test_fixed_retrieved_set_is_honoured():
+    rng = np.random.default_rng(14)
+    P = _rand_problem(rng)
+    forced = [np.array([5, 50, 100]) for _ in range(4)]
+    res, _, _ = _run(P, 3, retrieved=forced)
+    for r in res:
+        assert r["idx"].tolist() == [5, 50, 100]
+        assert orc.rel_l1(r["y_exactsub"], r["y_full"]) < 1e-12
+
+
+def test_rel_l1_definition():
+    assert abs(orc.rel_l1([1.0, -2.0], [1.5, -1.0]) - (0.5 + 1.0) / (2.5 + 1e-12)) < 1e-15
+    assert orc.rel_l1([0.0], [0.0]) == 0.0
