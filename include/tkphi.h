@@ -1,0 +1,196 @@
+/*
+ * tkphi.h -- C ABI of libtkphi: Top-K+phi residual-mass decode attention on one
+ * AMD MI355X (gfx950).
+ *
+ * The library implements, per attention layer, the per-decode-step attention over a
+ * long prefill KV cache described in "Residual-Mass Accounting for Partial-KV
+ * Decoding":
+ *
+ *   prefill   tkphi_build_summaries   S_M = sum_{i in M} phi_k(k_i) v_i^T,
+ *                                     u_M = sum_{i in M} phi_k(k_i)
+ *                                     (Sec. "Positive feature maps and summary
+ *                                     states", eq. (natural_cache))
+ *   decode    tkphi_decode            y = (nu_E + nu_R^) / (Z_E + Z_R^)
+ *                                     (Sec. "Single-normalization merge",
+ *                                     eq. (hybrid_merge)), with the exact support
+ *                                     E = A u TopK(M) (eq. (partition),
+ *                                     eq. (exact_terms)) chosen by an exhaustive
+ *                                     Top-K over the mid-region M, and the residual
+ *                                     read from (S_M, u_M) minus the retrieved
+ *                                     tokens' feature contributions
+ *                                     (eq. (subtraction)).
+ *
+ * Everything runs in hand-written HIP kernels enqueued on the caller's stream.  The
+ * library owns no device memory: every buffer, including scratch ("workspace"), is
+ * allocated by the caller.  Calls only enqueue work; they never synchronise the
+ * stream and never copy device data to the host (tkphi_read_device_status excepted).
+ *
+ * Pointer kinds.  Unless a parameter is marked HOST, pointers are DEVICE pointers.
+ * The tkphi_config struct itself and the outermost arguments are read on the host
+ * at call time; the tkphi_problem table is read by the kernels (DEVICE memory).
+ *
+ * Errors.  Every entry point returns a tkphi_status (or a size/count documented
+ * below); nothing throws or aborts across the boundary.  Host-visible arguments are
+ * validated before any launch, and a call that fails validation enqueues nothing.
+ * tkphi_last_error() returns a thread-local detail string for the last failure.
+ * Fields of the device-resident problem table cannot be seen by the host; kernels
+ * clip topk to min(topk, |M|, max_K) and skip a problem whose L exceeds max_L (or is < 1),
+ * recording TKPHI_DEV_BAD_LENGTH in the workspace status word.  tkphi_check_problems
+ * validates a HOST copy of the table.
+ */
+#ifndef TKPHI_H_
+#define TKPHI_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum tkphi_status {
+  TKPHI_OK = 0,
+  TKPHI_EINVAL = -1,       /* null pointer, negative count, bad enum value          */
+  TKPHI_ESHAPE = -2,       /* head counts / head_dim / d_phi / lengths unsupported  */
+  TKPHI_EALIGN = -3,       /* pointer or stride not 16-byte aligned                 */
+  TKPHI_EWORKSPACE = -4,   /* workspace null, misaligned or too small               */
+  TKPHI_EHIP = -5,         /* a HIP runtime call failed (see tkphi_last_error)      */
+  TKPHI_EUNSUPPORTED = -6  /* valid request the library has no kernel for           */
+} tkphi_status;
+
+typedef enum tkphi_dtype { TKPHI_F32 = 0, TKPHI_BF16 = 1 } tkphi_dtype;
+
+/* Accounting variants (Sec. "Models, tasks, and protocol"):
+ *   SUB        Top-K+phi, retrieved tokens subtracted from the summaries (the method)
+ *   NOSUB      ablation: summaries merged un-subtracted (double counts the retrieved set)
+ *   TOPK_ONLY  selection-only Top-K: y = nu_E / Z_E, no residual branch               */
+typedef enum tkphi_mode { TKPHI_MODE_SUB = 0, TKPHI_MODE_NOSUB = 1, TKPHI_MODE_TOPK_ONLY = 2 } tkphi_mode;
+
+/* bits of the device status word (tkphi_read_device_status) */
+#define TKPHI_DEV_BAD_LENGTH 1u   /* a problem had L < 1 or L > max_L and was skipped         */
+#define TKPHI_DEV_CLAMPED    2u   /* a residual denominator came out <= 0 after subtraction
+                                     and the residual branch was dropped for that head
+                                     (App. "Why positivity matters": numerical clamp)         */
+
+/* Fixed per model.  HOST struct.
+ * The feature maps have the form phi(x) = exp(phi_in_scale * W x - phi_norm_coef * |x|^2 + b)
+ * with per-head W, b (exponentiated affine output, App. "Head-wise phi architecture").
+ * Query head g uses KV head g / (n_q_heads / n_kv_heads).
+ * Supported: d_head in {64, 128}; d_phi a multiple of 16 in [16, 256];
+ * n_q_heads a multiple of n_kv_heads with ratio <= 8; bf16 storage additionally
+ * requires d_phi == d_head for the MFMA path (other d_phi run on the generic path). */
+typedef struct tkphi_config {
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t d_head;        /* d_h == d_v (Sec. "Setup and residual-mass bias")                */
+  int32_t d_phi;
+  int32_t n_sink;        /* anchors: first n_sink and last n_tail tokens (eq. (partition)) */
+  int32_t n_tail;
+  int32_t kv_dtype;      /* tkphi_dtype of q, K, V, Wq, Wk                                  */
+  float score_scale;     /* 1/sqrt(d_head) (eq. (full_attention))                           */
+  float phi_in_scale;    /* a                                                               */
+  float phi_norm_coef;   /* c                                                               */
+} tkphi_config;
+
+/* Optional per-query-head diagnostics / unnormalised outputs written by tkphi_decode,
+ * TKPHI_AUX_STRIDE(d_head) floats per query head:
+ *   [0] m        shift = max score over the exact support E
+ *   [1] Z_E      sum_{i in E} exp(s_i - m)
+ *   [2] Z_R^     phi_q . u_R (unshifted; 0 in TOPK_ONLY mode or if clamped)
+ *   [3] flags    1.0 if the clamp fired for this head, else 0.0
+ *   [4 .. 4+d)        nu_E  (shifted by m)
+ *   [4+d .. 4+2d)     nu_R^ (unshifted)
+ * so that y = (nu_E + exp(-m) nu_R^) / (Z_E + exp(-m) Z_R^); a caller can add further
+ * exact branches (e.g. generated tokens, eq. (implemented_decode)) before dividing. */
+#define TKPHI_AUX_STRIDE(d_head) (4 + 2 * (d_head))
+
+/* One problem = one (sequence, layer).  The table lives in DEVICE memory; all
+ * pointers inside are DEVICE pointers to caller-owned buffers that must stay valid
+ * until the enqueued work has finished.  16-byte alignment is required for K, V, q,
+ * Wq, Wk, S, u, out, and stride_tok * sizeof(elem) and stride_head * sizeof(elem)
+ * must be multiples of 16.  */
+typedef struct tkphi_problem {
+  const void* K;         /* keys   [n_kv_heads][L][d_head], strides below (elements)   */
+  const void* V;         /* values [n_kv_heads][L][d_head], same strides               */
+  int64_t stride_head;   /* elements between consecutive KV heads                      */
+  int64_t stride_tok;    /* elements between consecutive tokens (>= d_head)            */
+  const void* Wq;        /* [n_q_heads ][d_phi][d_head] kv_dtype                       */
+  const float* bq;       /* [n_q_heads ][d_phi]                                        */
+  const void* Wk;        /* [n_kv_heads][d_phi][d_head] kv_dtype                       */
+  const float* bk;       /* [n_kv_heads][d_phi]                                        */
+  float* S;              /* [n_kv_heads][d_phi][d_head] fp32: written by build, read by decode */
+  float* u;              /* [n_kv_heads][d_phi]         fp32: written by build, read by decode */
+  const void* q;         /* [n_q_heads][d_head] kv_dtype (decode only)                 */
+  float* out;            /* [n_q_heads][d_head] fp32 y (decode only)                   */
+  int32_t* topk_idx;     /* optional [n_q_heads][max_K]: retrieved token indices (absolute
+                            positions in [n_sink, L - n_tail)), ascending, first min(K,|M|)
+                            entries of each row valid; may be NULL                      */
+  float* aux;            /* optional [n_q_heads][TKPHI_AUX_STRIDE(d_head)]; may be NULL */
+  float* scores;         /* optional [n_q_heads][L - n_sink - n_tail] fp32 mid-region
+                            scores s_i, i in M (diagnostic copy); may be NULL           */
+  int32_t L;             /* prefill length, 1 <= L <= max_L                            */
+  int32_t topk;          /* the paper's K: retrieved mid-region tokens per query head (the
+                            budget); clipped to min(topk, |M|, max_K); 0 is legal      */
+} tkphi_problem;
+
+/* Bytes of DEVICE workspace tkphi_build_summaries / tkphi_decode need for the given
+ * launch bounds (the larger of the two).  Returns 0 if the config is invalid.
+ * The workspace must be 256-byte aligned.  Its contents need not be preserved between
+ * calls and need not be initialised.  Two calls that overlap in time (different
+ * streams) must not share a workspace. */
+size_t tkphi_workspace_bytes(const tkphi_config* cfg /*HOST*/, int32_t n_problems,
+                             int32_t max_L, int32_t max_K);
+
+/* Prefill: for every problem and KV head, S = sum_{i in M} phi_k(k_i) v_i^T and
+ * u = sum_{i in M} phi_k(k_i) over the mid-region M = [n_sink, L - n_tail)
+ * (eq. (natural_cache)); feature-major S[h][j][c] (j feature, c value channel).
+ * Reads K, V, Wk, bk, L; writes S, u (fully overwritten; zeros if M is empty).
+ * Deterministic: the same inputs give bit-identical S, u. */
+tkphi_status tkphi_build_summaries(const tkphi_config* cfg /*HOST*/,
+                                   const tkphi_problem* problems /*DEVICE table*/,
+                                   int32_t n_problems, int32_t max_L,
+                                   void* workspace, size_t workspace_bytes,
+                                   void* hip_stream);
+
+/* One decode step for every problem and query head: scores the mid-region, selects
+ * the K highest-scoring mid tokens (ties to the lower index), accumulates the exact
+ * max-shifted terms over anchors + retrieved tokens, evaluates the residual from
+ * (S, u) with the retrieved tokens' features subtracted, and merges under one
+ * normalisation (eq. (exact_terms), eq. (subtraction), eq. (hybrid_merge)).
+ * Reads q, K, V, Wq, bq, Wk, bk, S, u, L, topk; writes out (and topk_idx, aux, scores
+ * when non-NULL).  If L <= n_sink + n_tail the mid-region is empty and the result is
+ * dense attention over all L tokens.  Deterministic for fixed inputs. */
+tkphi_status tkphi_decode(const tkphi_config* cfg /*HOST*/,
+                          const tkphi_problem* problems /*DEVICE table*/,
+                          int32_t n_problems, int32_t max_L, int32_t max_K,
+                          int32_t mode /* tkphi_mode */,
+                          void* workspace, size_t workspace_bytes,
+                          void* hip_stream);
+
+/* Validates a HOST copy of a problem table against cfg and the launch bounds: non-null
+ * required pointers, alignment, strides, 1 <= L <= max_L, 0 <= topk <= max_K.
+ * for_decode != 0 additionally requires q and out.  Pure host code. */
+tkphi_status tkphi_check_problems(const tkphi_config* cfg /*HOST*/,
+                                  const tkphi_problem* problems_host /*HOST*/,
+                                  int32_t n_problems, int32_t max_L, int32_t max_K,
+                                  int32_t for_decode);
+
+/* Copies the device status word (TKPHI_DEV_* bits, accumulated by the kernels of the
+ * last call that used this workspace) to *status_out (HOST).  Synchronises the stream. */
+tkphi_status tkphi_read_device_status(const void* workspace, void* hip_stream,
+                                      uint32_t* status_out /*HOST*/);
+
+/* K = max(0, ceil(r L) - |A|): the paper's rule, anchors counted toward the total
+ * exact-support budget r (Sec. "Models, tasks, and protocol"); r in basis points. */
+int32_t tkphi_budget_paper(int64_t L, int32_t r_bp, int32_t n_sink, int32_t n_tail);
+/* K = floor(r |M|): budget as a fraction of the mid-region size; r in basis points. */
+int32_t tkphi_budget_mid(int64_t L, int32_t r_bp, int32_t n_sink, int32_t n_tail);
+
+/* Static, never-null strings. */
+const char* tkphi_status_string(int32_t status);
+const char* tkphi_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TKPHI_H_ */

@@ -1,0 +1,260 @@
+// Host layer of libtkphi: argument validation, launch geometry / workspace planning and
+// the extern "C" entry points declared in include/tkphi.h.
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+
+#include "tkphi_internal.h"
+
+namespace tkphi {
+
+static thread_local char g_last_error[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_last_error, sizeof(g_last_error), fmt, ap);
+  va_end(ap);
+}
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+static int env_int(const char* name, int dflt) {
+  const char* v = getenv(name);
+  if (!v || !*v) return dflt;
+  return atoi(v);
+}
+
+tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int max_K, Geom* g) {
+  if (!cfg) { set_error("cfg is null"); return TKPHI_EINVAL; }
+  if (n_problems < 0 || max_L < 1 || max_K < 0) {
+    set_error("n_problems=%d max_L=%d max_K=%d out of range", n_problems, max_L, max_K);
+    return TKPHI_EINVAL;
+  }
+  if (cfg->kv_dtype != TKPHI_F32 && cfg->kv_dtype != TKPHI_BF16) {
+    set_error("kv_dtype=%d is not a tkphi_dtype", cfg->kv_dtype);
+    return TKPHI_EINVAL;
+  }
+  if (cfg->n_kv_heads < 1 || cfg->n_q_heads < 1 || cfg->n_q_heads % cfg->n_kv_heads != 0 ||
+      cfg->n_q_heads / cfg->n_kv_heads > kMaxGroup) {
+    set_error("head counts %d/%d unsupported (need Hq %% Hkv == 0, ratio <= %d)", cfg->n_q_heads,
+              cfg->n_kv_heads, kMaxGroup);
+    return TKPHI_ESHAPE;
+  }
+  if (cfg->d_head != 64 && cfg->d_head != 128) {
+    set_error("d_head=%d unsupported (64 or 128)", cfg->d_head);
+    return TKPHI_ESHAPE;
+  }
+  if (cfg->d_phi < 16 || cfg->d_phi > kMaxDim || cfg->d_phi % 16 != 0) {
+    set_error("d_phi=%d unsupported (multiple of 16 in [16, %d])", cfg->d_phi, kMaxDim);
+    return TKPHI_ESHAPE;
+  }
+  if (n_problems > 65535) { set_error("n_problems=%d exceeds 65535", n_problems); return TKPHI_ESHAPE; }
+  if (cfg->n_sink < 0 || cfg->n_tail < 0) {
+    set_error("n_sink=%d n_tail=%d must be >= 0", cfg->n_sink, cfg->n_tail);
+    return TKPHI_EINVAL;
+  }
+  memset(g, 0, sizeof(*g));
+  g->Hq = cfg->n_q_heads; g->Hkv = cfg->n_kv_heads; g->G = g->Hq / g->Hkv;
+  g->d = cfg->d_head; g->dphi = cfg->d_phi; g->n_sink = cfg->n_sink; g->n_tail = cfg->n_tail;
+  g->dtype = cfg->kv_dtype;
+  g->n_problems = n_problems; g->max_L = max_L;
+  const int64_t mid = (int64_t)max_L - cfg->n_sink - cfg->n_tail;
+  g->max_mid = (int)std::max<int64_t>(mid, 0);
+  g->max_K = max_K;
+  g->mid_stride = (int)align_up((size_t)std::max(g->max_mid, 1), 64);
+  g->score_scale = cfg->score_scale; g->a = cfg->phi_in_scale; g->c = cfg->phi_norm_coef;
+
+  const int64_t units = (int64_t)g->max_mid * g->Hkv * std::max(n_problems, 1);
+  // score_mid: about 1024 workgroups, 512..8192 tokens each
+  int sc = (int)align_up((size_t)std::clamp<int64_t>(ceil_div(units, 1024), 512, 8192), 64);
+  sc = env_int("TKPHI_SCAN_CHUNK", sc);
+  g->scan_chunk = std::max(64, sc / 64 * 64);
+  g->n_scan_chunks = (int)std::max<int64_t>(1, ceil_div(g->max_mid, g->scan_chunk));
+  // select / gather slices: about 512 per launch, 1024..16384 tokens each
+  int sl = (int)align_up((size_t)std::clamp<int64_t>(ceil_div(units, 512), 1024, 16384), 256);
+  sl = env_int("TKPHI_SEL_CHUNK", sl);
+  g->sel_chunk = std::max(256, sl / 256 * 256);
+  while (ceil_div(g->max_mid, g->sel_chunk) > 1024) g->sel_chunk *= 2;   // select keeps per-slice counts in LDS
+  g->n_sel_slices = (int)std::max<int64_t>(1, ceil_div(g->max_mid, g->sel_chunk));
+  // summary_build: about 512 workgroups
+  int bc = (int)align_up((size_t)std::clamp<int64_t>(ceil_div(units, 512), 256, 1 << 20), 64);
+  bc = env_int("TKPHI_BUILD_CHUNK", bc);
+  g->build_chunk = std::max(64, bc / 64 * 64);
+  g->n_build_chunks = (int)std::max<int64_t>(1, ceil_div(g->max_mid, g->build_chunk));
+  g->part_stride = 2 * g->d + 4;
+
+  // workspace layout
+  size_t off = 0;
+  g->off_status = off; off += 256;
+  g->off_problem0 = off;
+  size_t p = 0;
+  g->off_scores = p;  p = align_up(p + (size_t)g->Hq * g->mid_stride * sizeof(float), 256);
+  g->off_hist = p;    p = align_up(p + (size_t)g->Hq * kBins * sizeof(uint32_t), 256);
+  g->off_state = p;   p = align_up(p + (size_t)g->Hq * sizeof(HeadState), 256);
+  g->off_cand = p;    p = align_up(p + (size_t)g->Hq * kCandCap * sizeof(uint2), 256);
+  g->off_above = p;   p = align_up(p + (size_t)g->Hq * g->n_sel_slices * sizeof(int32_t), 256);
+  g->off_offsets = p; p = align_up(p + (size_t)g->Hq * g->n_sel_slices * sizeof(int32_t), 256);
+  g->off_phiq = p;    p = align_up(p + (size_t)g->Hq * g->dphi * sizeof(float), 256);
+  g->off_part = p;
+  p = align_up(p + (size_t)g->Hkv * (g->n_sel_slices + 1) * g->G * g->part_stride * sizeof(float), 256);
+  g->per_problem = p;
+  const size_t decode_total = g->off_problem0 + (size_t)std::max(n_problems, 1) * g->per_problem;
+  g->off_bpart = g->off_problem0;
+  const size_t build_total = g->off_bpart + (size_t)std::max(n_problems, 1) * g->Hkv * g->n_build_chunks *
+                                                (size_t)g->dphi * (g->d + 1) * sizeof(float);
+  g->total_bytes = align_up(std::max(decode_total, build_total), 256);
+  return TKPHI_OK;
+}
+
+static tkphi_status check_call(const tkphi_problem* problems, int n_problems, const void* ws,
+                               size_t ws_bytes, const Geom& g) {
+  if (n_problems > 0 && !problems) { set_error("problems is null"); return TKPHI_EINVAL; }
+  if (!ws) { set_error("workspace is null"); return TKPHI_EWORKSPACE; }
+  if (((uintptr_t)ws) % 256 != 0) { set_error("workspace must be 256-byte aligned"); return TKPHI_EWORKSPACE; }
+  if (ws_bytes < g.total_bytes) {
+    set_error("workspace too small: %zu < %zu bytes", ws_bytes, g.total_bytes);
+    return TKPHI_EWORKSPACE;
+  }
+  if (((uintptr_t)problems) % 8 != 0) { set_error("problem table must be 8-byte aligned"); return TKPHI_EALIGN; }
+  return TKPHI_OK;
+}
+
+static tkphi_status hip_ok(hipError_t e, const char* what) {
+  if (e == hipSuccess) return TKPHI_OK;
+  set_error("%s: %s", what, hipGetErrorString(e));
+  return TKPHI_EHIP;
+}
+
+}  // namespace tkphi
+
+using namespace tkphi;
+
+extern "C" {
+
+size_t tkphi_workspace_bytes(const tkphi_config* cfg, int32_t n_problems, int32_t max_L, int32_t max_K) {
+  Geom g;
+  if (make_geom(cfg, n_problems, max_L, max_K, &g) != TKPHI_OK) return 0;
+  return g.total_bytes;
+}
+
+tkphi_status tkphi_build_summaries(const tkphi_config* cfg, const tkphi_problem* problems,
+                                   int32_t n_problems, int32_t max_L, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream) {
+  Geom g;
+  tkphi_status st = make_geom(cfg, n_problems, max_L, 0, &g);
+  if (st != TKPHI_OK) return st;
+  st = check_call(problems, n_problems, workspace, workspace_bytes, g);
+  if (st != TKPHI_OK) return st;
+  if (n_problems == 0) return TKPHI_OK;
+  hipStream_t s = (hipStream_t)hip_stream;
+  (void)hipGetLastError();
+  launch_build(g, problems, (char*)workspace, s);
+  return hip_ok(hipGetLastError(), "tkphi_build_summaries launch");
+}
+
+tkphi_status tkphi_decode(const tkphi_config* cfg, const tkphi_problem* problems, int32_t n_problems,
+                          int32_t max_L, int32_t max_K, int32_t mode, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+  if (mode != TKPHI_MODE_SUB && mode != TKPHI_MODE_NOSUB && mode != TKPHI_MODE_TOPK_ONLY) {
+    set_error("mode=%d is not a tkphi_mode", mode);
+    return TKPHI_EINVAL;
+  }
+  Geom g;
+  tkphi_status st = make_geom(cfg, n_problems, max_L, max_K, &g);
+  if (st != TKPHI_OK) return st;
+  st = check_call(problems, n_problems, workspace, workspace_bytes, g);
+  if (st != TKPHI_OK) return st;
+  if (n_problems == 0) return TKPHI_OK;
+  hipStream_t s = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
+  (void)hipGetLastError();
+  launch_prologue(g, problems, ws, s);
+  launch_score_mid(g, problems, ws, s);
+  launch_select(g, problems, ws, s);
+  launch_gather(g, problems, ws, s);
+  launch_merge(g, problems, ws, mode, s);
+  return hip_ok(hipGetLastError(), "tkphi_decode launch");
+}
+
+tkphi_status tkphi_check_problems(const tkphi_config* cfg, const tkphi_problem* ph, int32_t n_problems,
+                                  int32_t max_L, int32_t max_K, int32_t for_decode) {
+  Geom g;
+  tkphi_status st = make_geom(cfg, n_problems, max_L, max_K, &g);
+  if (st != TKPHI_OK) return st;
+  if (n_problems > 0 && !ph) { set_error("problems_host is null"); return TKPHI_EINVAL; }
+  const size_t es = cfg->kv_dtype == TKPHI_BF16 ? 2 : 4;
+  for (int p = 0; p < n_problems; ++p) {
+    const tkphi_problem& q = ph[p];
+    const void* req[] = {q.K, q.V, q.Wk, q.bk, q.S, q.u};
+    const char* names[] = {"K", "V", "Wk", "bk", "S", "u"};
+    for (int i = 0; i < 6; ++i) {
+      if (!req[i]) { set_error("problem %d: %s is null", p, names[i]); return TKPHI_EINVAL; }
+      if (((uintptr_t)req[i]) % 16 != 0) { set_error("problem %d: %s not 16-byte aligned", p, names[i]); return TKPHI_EALIGN; }
+    }
+    if (for_decode) {
+      const void* rq[] = {q.q, q.out, q.Wq, q.bq};
+      const char* nq[] = {"q", "out", "Wq", "bq"};
+      for (int i = 0; i < 4; ++i) {
+        if (!rq[i]) { set_error("problem %d: %s is null", p, nq[i]); return TKPHI_EINVAL; }
+        if (((uintptr_t)rq[i]) % 16 != 0) { set_error("problem %d: %s not 16-byte aligned", p, nq[i]); return TKPHI_EALIGN; }
+      }
+      if (q.topk < 0 || q.topk > max_K) { set_error("problem %d: topk=%d outside [0, max_K=%d]", p, q.topk, max_K); return TKPHI_ESHAPE; }
+      if (q.topk_idx && ((uintptr_t)q.topk_idx) % 4 != 0) { set_error("problem %d: topk_idx misaligned", p); return TKPHI_EALIGN; }
+      if (q.aux && ((uintptr_t)q.aux) % 4 != 0) { set_error("problem %d: aux misaligned", p); return TKPHI_EALIGN; }
+      if (q.scores && ((uintptr_t)q.scores) % 4 != 0) { set_error("problem %d: scores misaligned", p); return TKPHI_EALIGN; }
+    }
+    if (q.L < 1 || q.L > max_L) { set_error("problem %d: L=%d outside [1, max_L=%d]", p, q.L, max_L); return TKPHI_ESHAPE; }
+    if (q.stride_tok < cfg->d_head || (q.stride_tok * es) % 16 != 0) {
+      set_error("problem %d: stride_tok=%lld invalid (>= d_head, 16-byte multiple)", p, (long long)q.stride_tok);
+      return TKPHI_EALIGN;
+    }
+    if (q.stride_head < 0 || (q.stride_head * es) % 16 != 0 ||
+        (cfg->n_kv_heads > 1 && q.stride_head < cfg->d_head)) {
+      set_error("problem %d: stride_head=%lld invalid", p, (long long)q.stride_head);
+      return TKPHI_EALIGN;
+    }
+  }
+  return TKPHI_OK;
+}
+
+tkphi_status tkphi_read_device_status(const void* workspace, void* hip_stream, uint32_t* status_out) {
+  if (!workspace || !status_out) { set_error("null argument"); return TKPHI_EINVAL; }
+  hipStream_t s = (hipStream_t)hip_stream;
+  tkphi_status st = hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize");
+  if (st != TKPHI_OK) return st;
+  return hip_ok(hipMemcpy(status_out, workspace, sizeof(uint32_t), hipMemcpyDeviceToHost), "hipMemcpy status");
+}
+
+int32_t tkphi_budget_paper(int64_t L, int32_t r_bp, int32_t n_sink, int32_t n_tail) {
+  if (L < 0 || r_bp < 0 || n_sink < 0 || n_tail < 0) return 0;
+  const int64_t anchors = std::min<int64_t>(L, (int64_t)n_sink + n_tail);
+  const int64_t ceil_rL = (L * r_bp + 9999) / 10000;
+  return (int32_t)std::max<int64_t>(0, ceil_rL - anchors);
+}
+
+int32_t tkphi_budget_mid(int64_t L, int32_t r_bp, int32_t n_sink, int32_t n_tail) {
+  if (L < 0 || r_bp < 0 || n_sink < 0 || n_tail < 0) return 0;
+  const int64_t mid = std::max<int64_t>(0, L - n_sink - n_tail);
+  return (int32_t)(mid * r_bp / 10000);
+}
+
+const char* tkphi_status_string(int32_t status) {
+  switch (status) {
+    case TKPHI_OK: return "ok";
+    case TKPHI_EINVAL: return "invalid argument";
+    case TKPHI_ESHAPE: return "unsupported shape";
+    case TKPHI_EALIGN: return "misaligned pointer or stride";
+    case TKPHI_EWORKSPACE: return "workspace null, misaligned or too small";
+    case TKPHI_EHIP: return "HIP runtime error";
+    case TKPHI_EUNSUPPORTED: return "unsupported request";
+    default: return "unknown status";
+  }
+}
+
+const char* tkphi_last_error(void) { return g_last_error; }
+
+}  // extern "C"

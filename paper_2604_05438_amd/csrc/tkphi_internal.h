@@ -1,0 +1,141 @@
+// Internal definitions shared by the host layer and the HIP kernels of libtkphi.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tkphi.h"
+
+namespace tkphi {
+
+constexpr int kThreads = 256;          // every kernel uses 256-thread workgroups (4 wavefronts)
+constexpr int kMaxGroup = 8;           // query heads per KV head
+constexpr int kMaxDim = 256;           // d_head / d_phi upper bound of the generic kernels
+
+// ---- score histogram --------------------------------------------------------------
+// First-level bins of the radix select: a monotone non-decreasing map of the score to
+// [0, kBins).  Exponents 2^-6 .. 2^7 are resolved with 6 mantissa bits; everything
+// smaller in magnitude falls in one bin per sign, everything larger in the outermost
+// bins.  Only monotonicity matters for correctness; the resolution keeps the boundary
+// bin small for attention-like score ranges.
+constexpr int kExpLo = 121;
+constexpr int kExpHi = 133;
+constexpr int kMagBins = (kExpHi - kExpLo + 1) * 64 + 2;   // 834
+constexpr int kBins = 2 * kMagBins;                         // 1668
+constexpr int kCandCap = 4096;         // boundary-bin candidates resolved in LDS
+
+// ---- per-query-head selection state (device, in the workspace) -------------------
+struct HeadState {
+  uint32_t cand_count;   // candidates appended by the filter pass
+  uint32_t ticket;       // arrival counter of the filter workgroups
+  uint32_t thr_key;      // selection threshold: a token is retrieved iff
+  int32_t thr_idx;       //   key > thr_key || (key == thr_key && mid_index <= thr_idx)
+  int32_t bstar;         // boundary bin
+  int32_t krem;          // tokens still to take from the boundary bin
+  int32_t n_sel;         // K' = min(K, |M|, max_K)
+  int32_t pad;
+};
+
+// ---- launch geometry + workspace layout -------------------------------------------
+struct Geom {
+  int Hq, Hkv, G, d, dphi, n_sink, n_tail, dtype;
+  int n_problems, max_L, max_K, max_mid;
+  int mid_stride;        // floats per score row (multiple of 64)
+  int scan_chunk, n_scan_chunks;     // score_mid: mid tokens per workgroup
+  int sel_chunk, n_sel_slices;       // select / gather: mid tokens per slice
+  int build_chunk, n_build_chunks;   // summary_build: mid tokens per workgroup
+  int part_stride;       // floats per (slice, query head) partial: 2*d + 4
+  float score_scale, a, c;
+  // byte offsets inside the workspace
+  size_t off_status;     // uint32 device status word
+  size_t off_problem0;   // first per-problem block
+  size_t per_problem;    // bytes per problem block
+  // offsets inside a per-problem block
+  size_t off_scores;     // float    [Hq][mid_stride]
+  size_t off_hist;       // uint32   [Hq][kBins]
+  size_t off_state;      // HeadState[Hq]
+  size_t off_cand;       // uint2    [Hq][kCandCap]
+  size_t off_above;      // int32    [Hq][n_sel_slices]  tokens above the boundary bin per slice
+  size_t off_offsets;    // int32    [Hq][n_sel_slices]  output offset of each slice's selection
+  size_t off_phiq;       // float    [Hq][dphi]
+  size_t off_part;       // float    [Hkv][n_sel_slices + 1][G][part_stride]
+  size_t off_bpart;      // float    [Hkv][n_build_chunks][dphi*(d+1)]   (build only; aliases the block)
+  size_t total_bytes;
+};
+
+// Fills g for the given bounds; returns TKPHI_OK or the reason the config is unsupported.
+tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int max_K, Geom* g);
+void set_error(const char* fmt, ...);
+
+// kernel launchers (each defined next to its kernels)
+void launch_prologue(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
+void launch_score_mid(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
+void launch_select(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
+void launch_gather(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
+void launch_merge(const Geom& g, const tkphi_problem* probs, char* ws, int mode, hipStream_t s);
+void launch_build(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
+
+#ifdef __HIPCC__
+// ---- device helpers ------------------------------------------------------------------
+__device__ __forceinline__ uint32_t score_key(float s) {
+  // order-preserving map float -> uint32 (larger score <=> larger key)
+  uint32_t u = __float_as_uint(s);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ int key_bin(uint32_t key) {
+  const bool pos = (key & 0x80000000u) != 0;
+  const uint32_t mag = pos ? (key & 0x7fffffffu) : (~key & 0x7fffffffu);
+  const int e = (int)(mag >> 23);
+  const int m6 = (int)((mag >> 17) & 63u);
+  int mb;
+  if (e < kExpLo) mb = 0;
+  else if (e > kExpHi) mb = kMagBins - 1;
+  else mb = (e - kExpLo) * 64 + m6 + 1;
+  return pos ? (kMagBins + mb) : (kMagBins - 1 - mb);
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
+  return __uint_as_float(((uint32_t)b) << 16);
+}
+// round-to-nearest-even float -> bf16 bits (finite inputs)
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static constexpr int per16 = 4;
+  __device__ static __forceinline__ void unpack(const uint4& v, float* x) {
+    x[0] = __uint_as_float(v.x); x[1] = __uint_as_float(v.y);
+    x[2] = __uint_as_float(v.z); x[3] = __uint_as_float(v.w);
+  }
+  __device__ static __forceinline__ float load1(const void* p, int64_t i) { return ((const float*)p)[i]; }
+};
+template <> struct Elem<uint16_t> {   // bf16 bits
+  static constexpr int per16 = 8;
+  __device__ static __forceinline__ void unpack(const uint4& v, float* x) {
+    x[0] = __uint_as_float(v.x << 16); x[1] = __uint_as_float(v.x & 0xffff0000u);
+    x[2] = __uint_as_float(v.y << 16); x[3] = __uint_as_float(v.y & 0xffff0000u);
+    x[4] = __uint_as_float(v.z << 16); x[5] = __uint_as_float(v.z & 0xffff0000u);
+    x[6] = __uint_as_float(v.w << 16); x[7] = __uint_as_float(v.w & 0xffff0000u);
+  }
+  __device__ static __forceinline__ float load1(const void* p, int64_t i) {
+    return bf16_bits_to_float(((const uint16_t*)p)[i]);
+  }
+};
+
+// mid-region size of a problem; 0 if the anchors cover everything
+__device__ __forceinline__ int mid_size(int L, int n_sink, int n_tail) {
+  const int n = L - n_sink - n_tail;
+  return n > 0 ? n : 0;
+}
+
+__device__ __forceinline__ char* problem_block(const Geom& g, char* ws, int p) {
+  return ws + g.off_problem0 + (size_t)p * g.per_problem;
+}
+#endif  // __HIPCC__
+
+}  // namespace tkphi

@@ -1,0 +1,130 @@
+"""Comparison of the HIP path's results with the CPU oracle, element by element.
+
+Tolerances (the bar the path is held to):
+  * scores            |gpu - oracle| <= 1e-5 * max(1, |oracle|)
+  * Top-K index sets  identical, except that tokens may be exchanged across the selection
+                      boundary when their oracle scores lie within 1e-5 * max(1, |s_K|) of
+                      the K-th score s_K; when that happens the output is also checked
+                      against the oracle re-run on the GPU's set
+  * outputs y         max-abs <= 2e-3 and relative l1 <= 1e-2 per query head
+  * summaries S, u    relative Frobenius error <= 2e-3 (bf16 path: the features are rounded
+                      to bf16 before the MFMA contraction) / 2e-5 (fp32 storage)
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from oracle import tkphi_oracle as orc
+from paper_2604_05438_amd import inputs as I
+
+Y_MAX_ABS = 2e-3
+Y_REL_L1 = 1e-2
+SCORE_TOL = 1e-5
+SWAP_TOL = 1e-5
+
+
+def oracle_inputs(P: dict) -> dict:
+    return {k: I.to_f64(P[k]) for k in ("q", "K", "V", "Wq", "Wk", "bq", "bk")}
+
+
+def oracle_layer(w, P, k, heads=None, S=None, u=None, retrieved=None):
+    O = oracle_inputs(P)
+    if S is None:
+        S, u = orc.build_summaries(O["K"], O["V"], O["Wk"], O["bk"], w.phi_in_scale, w.phi_norm_coef,
+                                   w.n_sink, w.n_tail)
+    res = orc.decode_layer(O["q"], O["K"], O["V"], S, u, O["Wq"], O["bq"], O["Wk"], O["bk"],
+                           w.phi_in_scale, w.phi_norm_coef, w.score_scale, w.n_sink, w.n_tail, k,
+                           heads=heads, retrieved=retrieved)
+    return res, S, u, O
+
+
+def check_scores(gpu_scores_row: np.ndarray, r: dict, n_sink: int, n_mid: int):
+    s_or = r["s"][n_sink:n_sink + n_mid]
+    err = np.abs(gpu_scores_row[:n_mid].astype(np.float64) - s_or)
+    tol = SCORE_TOL * np.maximum(1.0, np.abs(s_or))
+    assert (err <= tol).all(), f"score mismatch: max err {err.max():.3e} (tol {tol.min():.1e})"
+
+
+def check_index_set(gpu_idx: np.ndarray, r: dict, n_sink: int, n_mid: int) -> bool:
+    """Returns True if the set equals the oracle's exactly, False if it differs only by
+    admissible boundary swaps; asserts otherwise."""
+    k = r["idx"].size
+    got = np.asarray(gpu_idx[:k], dtype=np.int64)
+    assert (got >= n_sink).all() and (got < n_sink + n_mid).all(), "index outside the mid-region"
+    assert np.unique(got).size == k, "duplicate retrieved index"
+    assert (np.diff(got) > 0).all(), "retrieved indices not ascending"
+    want = np.sort(r["idx"])
+    if np.array_equal(got, want):
+        return True
+    s = r["s"]
+    s_k = s[r["idx"][-1]]                      # K-th best oracle score
+    tol = SWAP_TOL * max(1.0, abs(s_k))
+    only_gpu = np.setdiff1d(got, want)
+    only_or = np.setdiff1d(want, got)
+    assert only_gpu.size == only_or.size
+    assert (np.abs(s[only_gpu] - s_k) <= tol).all() and (np.abs(s[only_or] - s_k) <= tol).all(), \
+        f"index sets differ beyond boundary swaps: gpu-only {only_gpu[:8]}, oracle-only {only_or[:8]}"
+    return False
+
+
+def check_output(y_gpu: np.ndarray, y_or: np.ndarray, what="y"):
+    y_gpu = y_gpu.astype(np.float64)
+    assert np.isfinite(y_gpu).all(), f"{what}: non-finite output"
+    max_abs = np.abs(y_gpu - y_or).max()
+    rel = orc.rel_l1(y_gpu, y_or)
+    assert max_abs <= Y_MAX_ABS and rel <= Y_REL_L1, f"{what}: max-abs {max_abs:.3e}, rel-l1 {rel:.3e}"
+    return max_abs, rel
+
+
+def check_summaries(S_gpu, u_gpu, S_or, u_or, tol):
+    for h in range(S_or.shape[0]):
+        eS = np.linalg.norm(S_gpu[h].astype(np.float64) - S_or[h]) / max(np.linalg.norm(S_or[h]), 1e-300)
+        eu = np.linalg.norm(u_gpu[h].astype(np.float64) - u_or[h]) / max(np.linalg.norm(u_or[h]), 1e-300)
+        assert eS <= tol and eu <= tol, f"head {h}: S rel-F {eS:.3e}, u rel {eu:.3e} (tol {tol:.1e})"
+
+
+def check_layer(w, P, k, batch, i, heads=None, sum_tol=None, mode="sub", check_aux=True):
+    """Full comparison of problem i of `batch` (already built + decoded, debug outputs on)."""
+    L = int(P["L"])
+    n_mid = max(0, L - w.n_sink - w.n_tail)
+    Hq = w.n_q_heads
+    heads = list(range(Hq)) if heads is None else list(heads)
+    res, S_or, u_or, O = oracle_layer(w, P, k, heads=heads)
+    if sum_tol is None:
+        sum_tol = 2e-3 if w.dtype == "bf16" else 2e-5
+    if n_mid > 0:
+        check_summaries(batch.result(i, "S"), batch.result(i, "u"), S_or, u_or, sum_tol)
+    y = batch.result(i, "out")
+    idx = batch.result(i, "topk_idx")
+    sc = batch.result(i, "scores")
+    aux = batch.result(i, "aux")
+    key = {"sub": "y", "nosub": "y_nosub", "topk": "y_topk"}[mode]
+    worst = (0.0, 0.0)
+    n_swapped = 0
+    d = w.d_head
+    for g, r in zip(heads, res):
+        if n_mid > 0:
+            check_scores(sc[g], r, w.n_sink, n_mid)
+        exact = check_index_set(idx[g], r, w.n_sink, n_mid)
+        a, b = check_output(y[g], r[key], f"head {g} {key}")
+        worst = (max(worst[0], a), max(worst[1], b))
+        if not exact:
+            n_swapped += 1
+            forced = {g: idx[g][: r["idx"].size].astype(np.int64)}
+            r2 = oracle_layer(w, P, k, heads=[g], S=S_or, u=u_or, retrieved=forced)[0][0]
+            check_output(y[g], r2[key], f"head {g} {key} (oracle on the GPU's set)")
+        if check_aux:
+            m = float(aux[g, 0])
+            E = np.concatenate([orc.partition(L, w.n_sink, w.n_tail)[0], r["idx"]])
+            m_or = r["s"][E].max() if E.size else 0.0
+            assert abs(m - m_or) <= 1e-5 * max(1.0, abs(m_or)), f"head {g}: shift {m} vs {m_or}"
+            Z_or = r["Z_E"] * np.exp(-m_or)
+            assert abs(aux[g, 1] - Z_or) <= 1e-4 * Z_or + 1e-30, f"head {g}: Z_E {aux[g, 1]} vs {Z_or}"
+            nu_or = r["nu_E"] * np.exp(-m_or)
+            assert np.abs(aux[g, 4:4 + d] - nu_or).max() <= 1e-4 * max(np.abs(nu_or).max(), 1e-30) + 1e-6
+            assert aux[g, 3] == 0.0, f"head {g}: residual clamp fired"
+            if mode == "sub" and n_mid > r["idx"].size:
+                # the residual denominator (unshifted) against the oracle's
+                assert abs(aux[g, 2] - r["Z_R_hat"]) <= 5e-3 * r["Z_R_hat"], \
+                    f"head {g}: Z_R_hat {aux[g, 2]} vs {r['Z_R_hat']}"
+    return {"max_abs": worst[0], "rel_l1": worst[1], "swapped_heads": n_swapped}
