@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the Top-K+phi decode step on one MI355X.
+
+Workload: the Llama-3.2-3B-shaped single layer at 128K context and a 1 % budget
+(24 query / 8 KV heads, head_dim 128, d_phi 128, 4 sink + 64 tail anchors, K = 1310), bf16
+K/V with fp32 accumulation, synthetic seeded inputs.  One "step" is one tkphi_decode call
+on one layer (prologue/phi_q, score_mid, topk_select, gather = exact branch + subtraction
+sums, merge).  The steps rotate over several distinct resident layers so that the keys
+are really streamed from HBM and not served by the 256 MB last-level cache.  The summary
+build (prefill side, once per prefix) is timed separately and reported under "build".
+
+Prints one JSON line (rank 0; this build is single-GPU).
+"""
+from __future__ import annotations
+
+import argparse
+import concurrent.futures
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="l3b_128k")
+    ap.add_argument("--budget-bp", type=int, default=100)
+    ap.add_argument("--rotate", type=int, default=4, help="distinct resident layers the steps rotate over")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(no collectives or sharding are part of it).", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2604_05438_amd import binding as B
+    from paper_2604_05438_amd import harness as H
+    from paper_2604_05438_amd import inputs as I
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = I.WORKLOADS[args.workload]
+    cfg = H.config_of(w)
+    L = w.L
+    n_mid = L - w.n_sink - w.n_tail
+    K = I.mid_budget(L, args.budget_bp, w.n_sink, w.n_tail)
+    esz = 2 if w.dtype == "bf16" else 4
+
+    # ---- inputs: `rotate` distinct layers, resident in HBM before anything is timed -------
+    t0 = time.time()
+    with concurrent.futures.ThreadPoolExecutor(max_workers=min(4, args.rotate)) as ex:
+        layers = list(ex.map(lambda r: I.make_layer(w, layer=r), range(args.rotate)))
+    batches = [H.Batch(cfg, [P], [K]) for P in layers]
+    t_gen = time.time() - t0
+    stream = torch.cuda.current_stream()
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    # ---- build (prefill side), timed on its own ------------------------------------------
+    for b in batches:
+        b.build()
+    torch.cuda.synchronize()
+    e0, e1 = ev(), ev()
+    e0.record(stream)
+    for b in batches:
+        b.build()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    build_ms = e0.elapsed_time(e1) / len(batches)
+    build_bytes = w.n_kv_heads * n_mid * w.d_head * esz * 2            # K and V rows of M, once
+    build_flops = w.n_kv_heads * n_mid * (2 * w.d_phi * w.d_head + 2 * w.d_phi * (w.d_head + 1))
+
+    # ---- decode: W warm-up steps, then exactly K timed steps ------------------------------
+    for i in range(args.warmup):
+        batches[i % len(batches)].decode()
+    torch.cuda.synchronize()
+    e0, e1 = ev(), ev()
+    t_wall = time.perf_counter()
+    e0.record(stream)
+    for i in range(args.steps):
+        batches[i % len(batches)].decode()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_wall) * 1e3
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    assert all(b.status() == 0 for b in batches)
+
+    # ---- per-stage kernel durations: HIP events on the launch stream, same steps ---------
+    stage = np.zeros(len(B.STAGES))
+    for i in range(args.steps):
+        stage += np.array(batches[i % len(batches)].decode_stage_times())
+    stage /= args.steps
+    stage_us = {n: float(v * 1e3) for n, v in zip(B.STAGES, stage)}
+
+    # algorithmic bytes of one step (what the method must move)
+    bytes_scan = w.n_kv_heads * n_mid * w.d_head * esz                  # every mid key row, once per KV head
+    bytes_gather = w.n_q_heads * K * 2 * w.d_head * esz                 # k and v rows of the retrieved tokens
+    bytes_anchor = w.n_kv_heads * (w.n_sink + w.n_tail) * 2 * w.d_head * esz
+    bytes_const = (w.n_kv_heads * w.d_phi * (w.d_head + 1) * 4          # S, u
+                   + (w.n_q_heads + w.n_kv_heads) * w.d_phi * w.d_head * esz)   # Wq, Wk
+    bytes_step = bytes_scan + bytes_gather + bytes_anchor + bytes_const
+    scan_s = stage_us["score_mid"] * 1e-6
+    achieved = bytes_scan / scan_s / 1e9
+
+    out = {
+        "metric": "mid_kv_tokens_per_s",
+        "value": n_mid / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "decode_step_us": ms_per_step * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.n_q_heads}q/{w.n_kv_heads}kv heads, head_dim {w.d_head}, "
+                               f"d_phi {w.d_phi}, L {L}, sink {w.n_sink} + tail {w.n_tail}, K {K} "
+                               f"({args.budget_bp} bp of the mid-region), one layer per step",
+                   "rotating_layers": args.rotate, "budget_bp": args.budget_bp, "K": K, "L": L},
+        "step_hbm": {"algorithmic_bytes": bytes_step, "achieved_GBs": bytes_step / (ms_per_step * 1e-3) / 1e9,
+                     "frac_of_peak": bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "stage_us": stage_us,
+        "wall_ms_per_step": wall_ms / args.steps,
+        "roofline": {"kernel": "score_mid", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": bytes_scan},
+        "build": {"ms_per_layer": build_ms, "algorithmic_bytes": build_bytes, "flops": build_flops,
+                  "hbm_GBs": build_bytes / (build_ms * 1e-3) / 1e9,
+                  "hbm_frac": build_bytes / (build_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                  "mfma_TFLOPs": build_flops / (build_ms * 1e-3) / 1e12,
+                  "mfma_frac": build_flops / (build_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+        "input_gen_s": t_gen,
+    }
+
+    # ---- CPU baseline: the float64 oracle, as it stands, on a bounded sample --------------
+    if not args.no_cpu_baseline:
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        import parity_utils as PU
+        from oracle import tkphi_oracle as orc
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        P = layers[0]
+        heads = list(range(min(w.n_q_heads, 2 * w.group)))      # the query heads of two KV heads
+        O = PU.oracle_inputs(P)
+        t0 = time.perf_counter()
+        S, u = orc.build_summaries(O["K"][: len(heads) // w.group], O["V"][: len(heads) // w.group],
+                                   O["Wk"], O["bk"], w.phi_in_scale, w.phi_norm_coef, w.n_sink, w.n_tail)
+        t_build = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        res = orc.decode_layer(O["q"], O["K"], O["V"], S, u, O["Wq"], O["bq"], O["Wk"], O["bk"],
+                               w.phi_in_scale, w.phi_norm_coef, w.score_scale, w.n_sink, w.n_tail, K, heads=heads)
+        t_dec = time.perf_counter() - t0
+        frac = len(heads) / w.n_q_heads
+        y = batches[0].result(0, "out")
+        batches[0].decode()
+        torch.cuda.synchronize()
+        y = batches[0].result(0, "out")
+        worst = max(float(np.abs(y[g] - r["y"]).max()) for g, r in zip(heads, res))
+        out["cpu_baseline"] = {
+            "value": n_mid * frac / t_dec, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"float64 numpy oracle, decode of {len(heads)} of {w.n_q_heads} query heads "
+                      f"({len(heads) // w.group} of {w.n_kv_heads} KV heads) of one layer-step of the same workload: "
+                      f"{t_dec:.2f} s (summary build of those KV heads: {t_build:.2f} s, not in value); "
+                      f"value = mid tokens x sampled fraction / decode seconds",
+            "decode_s": t_dec, "build_s": t_build,
+        }
+        out["parity_max_abs_vs_oracle"] = worst
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -21,7 +21,8 @@ TKPHI_MODE_SUB, TKPHI_MODE_NOSUB, TKPHI_MODE_TOPK_ONLY = 0, 1, 2
 TKPHI_DEV_BAD_LENGTH, TKPHI_DEV_CLAMPED = 1, 2
 
 EXPORTS = (
-    "tkphi_workspace_bytes", "tkphi_build_summaries", "tkphi_decode", "tkphi_check_problems",
+    "tkphi_workspace_bytes", "tkphi_build_summaries", "tkphi_decode", "tkphi_decode_stage_times",
+    "tkphi_check_problems",
     "tkphi_read_device_status", "tkphi_budget_paper", "tkphi_budget_mid", "tkphi_status_string",
     "tkphi_last_error",
 )
@@ -71,6 +72,9 @@ def lib() -> C.CDLL:
         L.tkphi_decode.restype = C.c_int
         L.tkphi_decode.argtypes = [cfgp, probp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                    C.c_size_t, C.c_void_p]
+        L.tkphi_decode_stage_times.restype = C.c_int
+        L.tkphi_decode_stage_times.argtypes = [cfgp, probp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                               C.c_size_t, C.c_void_p, C.POINTER(C.c_float)]
         L.tkphi_check_problems.restype = C.c_int
         L.tkphi_check_problems.argtypes = [cfgp, C.POINTER(tkphi_problem), C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         L.tkphi_read_device_status.restype = C.c_int
@@ -134,6 +138,17 @@ def tkphi_decode(cfg: tkphi_config, problems_dev_ptr: int, n_problems: int, max_
                  mode: int, workspace_ptr: int, workspace_bytes: int, stream: int) -> None:
     _check(lib().tkphi_decode(C.byref(cfg), problems_dev_ptr, n_problems, max_L, max_K, mode, workspace_ptr,
                               workspace_bytes, stream))
+
+
+STAGES = ("prologue", "score_mid", "topk_select", "gather", "merge")
+
+
+def tkphi_decode_stage_times(cfg: tkphi_config, problems_dev_ptr: int, n_problems: int, max_L: int, max_K: int,
+                             mode: int, workspace_ptr: int, workspace_bytes: int, stream: int) -> list:
+    out = (C.c_float * len(STAGES))()
+    _check(lib().tkphi_decode_stage_times(C.byref(cfg), problems_dev_ptr, n_problems, max_L, max_K, mode,
+                                          workspace_ptr, workspace_bytes, stream, out))
+    return list(out)
 
 
 def tkphi_read_device_status(workspace_ptr: int, stream: int) -> int:

@@ -180,6 +180,45 @@ tkphi_status tkphi_decode(const tkphi_config* cfg, const tkphi_problem* problems
   return hip_ok(hipGetLastError(), "tkphi_decode launch");
 }
 
+tkphi_status tkphi_decode_stage_times(const tkphi_config* cfg, const tkphi_problem* problems,
+                                      int32_t n_problems, int32_t max_L, int32_t max_K, int32_t mode,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream,
+                                      float* stage_ms_out) {
+  if (!stage_ms_out) { set_error("stage_ms_out is null"); return TKPHI_EINVAL; }
+  if (mode != TKPHI_MODE_SUB && mode != TKPHI_MODE_NOSUB && mode != TKPHI_MODE_TOPK_ONLY) {
+    set_error("mode=%d is not a tkphi_mode", mode);
+    return TKPHI_EINVAL;
+  }
+  Geom g;
+  tkphi_status st = make_geom(cfg, n_problems, max_L, max_K, &g);
+  if (st != TKPHI_OK) return st;
+  st = check_call(problems, n_problems, workspace, workspace_bytes, g);
+  if (st != TKPHI_OK) return st;
+  for (int i = 0; i < TKPHI_N_STAGES; ++i) stage_ms_out[i] = 0.f;
+  if (n_problems == 0) return TKPHI_OK;
+  hipStream_t s = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
+  hipEvent_t ev[TKPHI_N_STAGES + 1];
+  int made = 0;
+  for (; made <= TKPHI_N_STAGES; ++made)
+    if ((st = hip_ok(hipEventCreate(&ev[made]), "hipEventCreate")) != TKPHI_OK) break;
+  if (st == TKPHI_OK) {
+    (void)hipGetLastError();
+    hipEventRecord(ev[0], s);
+    launch_prologue(g, problems, ws, s);  hipEventRecord(ev[1], s);
+    launch_score_mid(g, problems, ws, s); hipEventRecord(ev[2], s);
+    launch_select(g, problems, ws, s);    hipEventRecord(ev[3], s);
+    launch_gather(g, problems, ws, s);    hipEventRecord(ev[4], s);
+    launch_merge(g, problems, ws, mode, s); hipEventRecord(ev[5], s);
+    st = hip_ok(hipGetLastError(), "tkphi_decode_stage_times launch");
+    if (st == TKPHI_OK) st = hip_ok(hipEventSynchronize(ev[TKPHI_N_STAGES]), "hipEventSynchronize");
+    for (int i = 0; st == TKPHI_OK && i < TKPHI_N_STAGES; ++i)
+      st = hip_ok(hipEventElapsedTime(&stage_ms_out[i], ev[i], ev[i + 1]), "hipEventElapsedTime");
+  }
+  for (int i = 0; i < made; ++i) hipEventDestroy(ev[i]);
+  return st;
+}
+
 tkphi_status tkphi_check_problems(const tkphi_config* cfg, const tkphi_problem* ph, int32_t n_problems,
                                   int32_t max_L, int32_t max_K, int32_t for_decode) {
   Geom g;

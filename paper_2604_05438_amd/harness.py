@@ -67,8 +67,19 @@ class Batch:
         B.tkphi_decode(self.cfg, self.table.data_ptr(), self.n, self.max_L, self.max_K, mode,
                        self.ws.data_ptr(), self.ws_bytes, B.current_stream_ptr())
 
+    def decode_stage_times(self, mode: int = B.TKPHI_MODE_SUB) -> list:
+        return B.tkphi_decode_stage_times(self.cfg, self.table.data_ptr(), self.n, self.max_L, self.max_K, mode,
+                                          self.ws.data_ptr(), self.ws_bytes, B.current_stream_ptr())
+
     def status(self) -> int:
         return B.tkphi_read_device_status(self.ws.data_ptr(), B.current_stream_ptr())
+
+    def set_topk(self, i: int, k: int) -> None:
+        """Changes problem i's budget (<= max_K) and re-uploads the table."""
+        assert 0 <= k <= self.max_K
+        self.host_table[i].topk = int(k)
+        raw = bytearray(bytes(memoryview(self.host_table).cast("B")))
+        self.table.copy_(torch.frombuffer(raw, dtype=torch.uint8))
 
     def set_query(self, i: int, q: np.ndarray) -> None:
         self.dev[i]["q"].copy_(to_device(q, self.device))

@@ -1,0 +1,63 @@
+"""GPU parity at the full sizes of the synthetic workloads, in the launch configuration
+bench.py times (single problem per call for the single-layer shapes).  The oracle computes
+whole heads one by one; for the larger shapes a sample of query heads is checked."""
+import numpy as np
+import pytest
+
+from paper_2604_05438_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+
+def test_l1b_32k_full_layer():
+    # 32q/8kv, head_dim 64, L 32768, K = 327 (1 % of the mid-region): every query head
+    import parity_utils as PU
+    from paper_2604_05438_amd import harness as H
+    w = I.WORKLOADS["l1b_32k"]
+    k = I.mid_budget(w.L, w.budget_bp, w.n_sink, w.n_tail)
+    assert k == 327
+    P = I.make_layer(w)
+    b = H.Batch(H.config_of(w), [P], [k], debug=True)
+    b.build(); b.decode()
+    assert b.status() == 0
+    rep = PU.check_layer(w, P, k, b, 0)
+    print("l1b_32k", rep)
+
+
+def test_l3b_128k_budget_sweep():
+    # 24q/8kv, head_dim 128, L 131072; budgets 0.5 / 1 / 2 / 4 % of the mid-region
+    import parity_utils as PU
+    from paper_2604_05438_amd import harness as H
+    w = I.WORKLOADS["l3b_128k"]
+    P = I.make_layer(w)
+    ks = [I.mid_budget(w.L, bp, w.n_sink, w.n_tail) for bp in (50, 100, 200, 400)]
+    assert ks == [655, 1310, 2620, 5240]
+    b = H.Batch(H.config_of(w), [P], [ks[-1]], debug=True)
+    b.build()
+    O = PU.oracle_inputs(P)
+    from oracle import tkphi_oracle as orc
+    S_or, u_or = orc.build_summaries(O["K"], O["V"], O["Wk"], O["bk"], w.phi_in_scale, w.phi_norm_coef,
+                                     w.n_sink, w.n_tail)
+    PU.check_summaries(b.result(0, "S"), b.result(0, "u"), S_or, u_or, 2e-3)
+    heads = [0, 4, 8, 11, 17, 23]
+    n_mid = w.L - w.n_sink - w.n_tail
+    for k in ks:
+        b.set_topk(0, k)
+        b.decode()
+        assert b.status() == 0
+        y = b.result(0, "out"); idx = b.result(0, "topk_idx"); sc = b.result(0, "scores")
+        res = orc.decode_layer(O["q"], O["K"], O["V"], S_or, u_or, O["Wq"], O["bq"], O["Wk"], O["bk"],
+                               w.phi_in_scale, w.phi_norm_coef, w.score_scale, w.n_sink, w.n_tail, k, heads=heads)
+        worst = 0.0
+        for g, r in zip(heads, res):
+            PU.check_scores(sc[g], r, w.n_sink, n_mid)
+            exact = PU.check_index_set(idx[g], r, w.n_sink, n_mid)
+            if exact:
+                a, _ = PU.check_output(y[g], r["y"], f"K={k} head {g}")
+            else:
+                r2 = orc.decode_layer(O["q"], O["K"], O["V"], S_or, u_or, O["Wq"], O["bq"], O["Wk"], O["bk"],
+                                      w.phi_in_scale, w.phi_norm_coef, w.score_scale, w.n_sink, w.n_tail, k,
+                                      heads=[g], retrieved={g: idx[g][:k].astype(np.int64)})[0]
+                a, _ = PU.check_output(y[g], r2["y"], f"K={k} head {g} (GPU's set)")
+            worst = max(worst, a)
+        print("l3b_128k K", k, "max_abs", worst)
