@@ -4,7 +4,7 @@
 Workload: the Llama-3.2-3B-shaped single layer at 128K context and a 1 % budget
 (24 query / 8 KV heads, head_dim 128, d_phi 128, 4 sink + 64 tail anchors, K = 1310), bf16
 K/V with fp32 accumulation, synthetic seeded inputs.  One "step" is one tkphi_decode call
-on one layer (prologue/phi_q, score_mid, topk_select, gather = exact branch + subtraction
+on one layer (score_mid, topk_select + phi_q, gather = exact branch + subtraction
 sums, merge).  The steps rotate over several distinct resident layers so that the keys
 are really streamed from HBM and not served by the 256 MB last-level cache.  The summary
 build (prefill side, once per prefix) is timed separately and reported under "build".

@@ -170,10 +170,9 @@ tkphi_status tkphi_decode(const tkphi_config* cfg /*HOST*/,
 /* Profiling helper: the same work as tkphi_decode, with a HIP event recorded on the stream
  * between the stages, then a stream synchronisation; stage_ms_out (HOST, TKPHI_N_STAGES
  * floats) receives the elapsed milliseconds of each stage's kernel(s), in order:
- * prologue (phi_q), score_mid, topk_select, gather (exact branch + subtraction sums),
- * merge.  Same validation and results as tkphi_decode; creates and destroys HIP events
+ * score_mid, topk_select (+ phi_q), gather (exact branch + subtraction sums), merge.  Same validation and results as tkphi_decode; creates and destroys HIP events
  * (no device memory). */
-#define TKPHI_N_STAGES 5
+#define TKPHI_N_STAGES 4
 tkphi_status tkphi_decode_stage_times(const tkphi_config* cfg /*HOST*/,
                                       const tkphi_problem* problems /*DEVICE table*/,
                                       int32_t n_problems, int32_t max_L, int32_t max_K,

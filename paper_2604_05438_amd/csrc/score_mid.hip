@@ -1,63 +1,123 @@
-// Decode front end: the prologue (query feature map phi_q, workspace reset) and score_mid,
-// the streaming pass s_i = q . k_i / sqrt(d_h) over the mid-region (eq. (full_attention)
-// restricted to M, eq. (partition)), which reads each KV head's keys once for all query
-// heads of its group and accumulates the first-level histogram of the Top-K radix select.
-#include "block_utils.h"
+// score_mid: the streaming pass s_i = q . k_i / sqrt(d_h) over the mid-region
+// (eq. (full_attention) restricted to M of eq. (partition)).  Every key row of a KV head is
+// read once for all G query heads of its group.  Besides the scores, each workgroup writes
+// the first-level histogram of its chunk (per query head, uint16 counts) for the Top-K
+// radix select; nothing is accumulated with atomics in global memory.
+//
+// Two kernels: a matrix-core one for bf16 caches and a generic fp32-arithmetic one for any
+// storage type.
 #include "tkphi_internal.h"
 
 namespace tkphi {
 
 // ------------------------------------------------------------------------------------
-// prologue: grid (Hq, n_problems)
-//   * clears the histogram and selection state of (problem, query head)
-//   * block (0,0) recomputes the device status word from the problem lengths
-//   * phi_q(q)[j] = exp(a * Wq[j] . q - c |q|^2 + bq[j])   (Sec. "Positive feature maps and
-//     summary states": phi_q is evaluated per query head at decode time)
+// bf16 on the matrix cores.
+//
+// The contraction [tokens x d] . [d x G] has a tiny N: the G query heads are padded to the
+// 16 columns of v_mfma_f32_16x16x32_bf16, whose A operand is exactly what a 16-byte row
+// segment load delivers (lane (r, kg) holds 8 consecutive bf16 of token r), so the keys go
+// from HBM to the MFMA without unpacking on the vector ALU.  Per wavefront and iteration:
+// TPI tiles of 16 tokens -> TPI * D/32 loads of 16 B per lane, the same number of MFMAs;
+// the G valid columns are transposed through a wave-private LDS strip so that score stores
+// are coalesced and every lane takes part in the histogram update.
 // ------------------------------------------------------------------------------------
-template <typename T>
-__global__ __launch_bounds__(kThreads) void prologue_kernel(Geom g, const tkphi_problem* __restrict__ probs,
-                                                            char* __restrict__ ws) {
-  __shared__ float qf[kMaxDim];
-  __shared__ int sh_i[4];
-  const int gq = blockIdx.x, p = blockIdx.y, tid = threadIdx.x;
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+union Frag {
+  u32x4 u;
+  bf16x8 v;
+};
+
+// grid (n_scan_chunks, Hkv, n_problems); dynamic LDS: hist [G][kBins] + strips [4][G][TPI*16]
+template <int D, int TPI>
+__global__ __launch_bounds__(kThreads) void score_mid_mfma_kernel(Geom g, const tkphi_problem* __restrict__ probs,
+                                                                  char* __restrict__ ws) {
+  constexpr int KS = D / 32;            // MFMA k-steps per token tile
+  constexpr int TOK = TPI * 16;         // tokens per wavefront iteration
+  extern __shared__ uint32_t lds[];
+  const int p = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
+  const tkphi_problem pr = probs[p];
+  if (pr.L < 1 || pr.L > g.max_L) return;
+  const int n = mid_size(pr.L, g.n_sink, g.n_tail);
+  const int c0 = blockIdx.x * g.scan_chunk;
+  if (c0 >= n) return;
+  const int c1 = min(n, c0 + g.scan_chunk);
+  const int G = g.G;
   char* blk = problem_block(g, ws, p);
 
-  if (gq == 0 && p == 0) {
-    int bad = 0;
-    for (int i = tid; i < g.n_problems; i += kThreads) {
-      const int L = probs[i].L;
-      bad |= (L < 1 || L > g.max_L) ? 1 : 0;
-    }
-    bad = block_sum_int(bad, sh_i);
-    if (tid == 0) *(uint32_t*)(ws + g.off_status) = bad ? TKPHI_DEV_BAD_LENGTH : 0u;
+  uint32_t* lds_hist = lds;
+  float* strips = (float*)(lds + G * kBins);
+  for (int i = tid; i < G * kBins; i += kThreads) lds_hist[i] = 0u;
+
+  const int lane = tid & 63, wv = tid >> 6;
+  const int r = lane & 15, kg = lane >> 4;
+
+  // B operand: column r = query head r of the group (zero for r >= G)
+  Frag bq[KS];
+#pragma unroll
+  for (int j = 0; j < KS; ++j) {
+    bq[j].u = (u32x4){0u, 0u, 0u, 0u};
+    if (r < G) bq[j].u = *(const u32x4*)((const uint16_t*)pr.q + (size_t)(h * G + r) * D + j * 32 + kg * 8);
   }
-
-  uint32_t* hist = (uint32_t*)(blk + g.off_hist) + (size_t)gq * kBins;
-  for (int i = tid; i < kBins; i += kThreads) hist[i] = 0u;
-  if (tid < (int)(sizeof(HeadState) / 4)) ((uint32_t*)((HeadState*)(blk + g.off_state) + gq))[tid] = 0u;
-
-  const tkphi_problem pr = probs[p];
-  float* phiq = (float*)(blk + g.off_phiq) + (size_t)gq * g.dphi;
-  if (pr.L < 1 || pr.L > g.max_L) return;
-  for (int c = tid; c < g.d; c += kThreads) qf[c] = Elem<T>::load1(pr.q, (int64_t)gq * g.d + c);
   __syncthreads();
-  for (int j = tid; j < g.dphi; j += kThreads) {
-    float dot = 0.f, nrm = 0.f;
-    const int64_t wbase = ((int64_t)gq * g.dphi + j) * g.d;
-    for (int c = 0; c < g.d; ++c) {
-      const float x = qf[c];
-      dot = fmaf(Elem<T>::load1(pr.Wq, wbase + c), x, dot);
-      nrm = fmaf(x, x, nrm);
+
+  const size_t row_bytes = (size_t)pr.stride_tok * 2;
+  const char* Kb = (const char*)pr.K + ((size_t)h * pr.stride_head + (size_t)g.n_sink * pr.stride_tok) * 2 +
+                   (size_t)kg * 16;
+  float* scores = (float*)(blk + g.off_scores) + (size_t)h * G * g.mid_stride;
+  float* strip = strips + (size_t)wv * G * TOK;
+  const float scale = g.score_scale;
+
+  for (int base = c0 + wv * TOK; base < c1; base += 4 * TOK) {
+    Frag a[TPI][KS];
+#pragma unroll
+    for (int t = 0; t < TPI; ++t) {
+      const int row = min(base + t * 16 + r, c1 - 1);
+      const char* rp = Kb + (size_t)row * row_bytes;
+#pragma unroll
+      for (int j = 0; j < KS; ++j) a[t][j].u = __builtin_nontemporal_load((const u32x4*)(rp + j * 64));
     }
-    phiq[j] = expf(g.a * dot - g.c * nrm + pr.bq[(int64_t)gq * g.dphi + j]);
+    floatx4 acc[TPI];
+#pragma unroll
+    for (int t = 0; t < TPI; ++t) {
+      acc[t] = (floatx4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int j = 0; j < KS; ++j)
+        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t][j].v, bq[j].v, acc[t], 0, 0, 0);
+    }
+    // acc[t][i] = score of token base + t*16 + 4*kg + i for query head r
+    if (r < G) {
+#pragma unroll
+      for (int t = 0; t < TPI; ++t)
+        *(floatx4*)(strip + r * TOK + t * 16 + kg * 4) = acc[t];
+    }
+    __builtin_amdgcn_wave_barrier();
+    for (int gl = 0; gl < G; ++gl) {
+#pragma unroll
+      for (int tt = lane; tt < TOK; tt += 64) {
+        const int tok = base + tt;
+        if (tok < c1) {
+          const float s = strip[gl * TOK + tt] * scale + 0.0f;   // + 0.0f: -0 -> +0, equal scores get equal keys
+          scores[(size_t)gl * g.mid_stride + tok] = s;
+          if (pr.scores) pr.scores[(size_t)(h * G + gl) * n + tok] = s;
+          atomicAdd(&lds_hist[gl * kBins + key_bin(score_key(s))], 1u);
+        }
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
   }
+  __syncthreads();
+  uint16_t* hist = (uint16_t*)(blk + g.off_hist) + ((size_t)blockIdx.x * g.Hq + (size_t)h * G) * kBins;
+  for (int i = tid; i < G * kBins; i += kThreads) hist[i] = (uint16_t)lds_hist[i];
 }
 
 // ------------------------------------------------------------------------------------
-// score_mid, generic (any storage type): grid (n_scan_chunks, Hkv, n_problems)
+// generic (any storage type, fp32 arithmetic): grid (n_scan_chunks, Hkv, n_problems)
 // A key row is split over LPR = d / (elements per 16 bytes) lanes, each lane loads 16
-// bytes and forms the partial dot products for all G query heads of the KV head; the
-// partials are summed across the LPR lanes with butterfly shuffles.
+// bytes and forms the partial dot products for all G query heads; the partials are summed
+// across the LPR lanes with butterfly shuffles.
 // ------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(kThreads) void score_mid_kernel(Geom g, const tkphi_problem* __restrict__ probs,
@@ -124,29 +184,26 @@ __global__ __launch_bounds__(kThreads) void score_mid_kernel(Geom g, const tkphi
     }
   }
   __syncthreads();
-  uint32_t* hist = (uint32_t*)(blk + g.off_hist) + (size_t)h * G * kBins;
-  for (int i = tid; i < G * kBins; i += kThreads) {
-    const uint32_t c = lds_hist[i];
-    if (c) atomicAdd(&hist[i], c);
-  }
-}
-
-void launch_prologue(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
-  dim3 grid(g.Hq, g.n_problems);
-  if (g.dtype == TKPHI_BF16)
-    hipLaunchKernelGGL(prologue_kernel<uint16_t>, grid, dim3(kThreads), 0, s, g, probs, ws);
-  else
-    hipLaunchKernelGGL(prologue_kernel<float>, grid, dim3(kThreads), 0, s, g, probs, ws);
+  uint16_t* hist = (uint16_t*)(blk + g.off_hist) + ((size_t)blockIdx.x * g.Hq + (size_t)h * G) * kBins;
+  for (int i = tid; i < G * kBins; i += kThreads) hist[i] = (uint16_t)lds_hist[i];
 }
 
 void launch_score_mid(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
   if (g.max_mid == 0) return;
   dim3 grid(g.n_scan_chunks, g.Hkv, g.n_problems);
-  const size_t lds = (size_t)g.G * kBins * sizeof(uint32_t);
-  if (g.dtype == TKPHI_BF16)
-    hipLaunchKernelGGL(score_mid_kernel<uint16_t>, grid, dim3(kThreads), lds, s, g, probs, ws);
-  else
-    hipLaunchKernelGGL(score_mid_kernel<float>, grid, dim3(kThreads), lds, s, g, probs, ws);
+  const size_t hist_lds = (size_t)g.G * kBins * sizeof(uint32_t);
+  if (g.use_mfma) {
+    if (g.d == 128)
+      hipLaunchKernelGGL((score_mid_mfma_kernel<128, 4>), grid, dim3(kThreads), hist_lds + (size_t)4 * g.G * 64 * 4, s,
+                         g, probs, ws);
+    else
+      hipLaunchKernelGGL((score_mid_mfma_kernel<64, 8>), grid, dim3(kThreads), hist_lds + (size_t)4 * g.G * 128 * 4, s,
+                         g, probs, ws);
+  } else if (g.dtype == TKPHI_BF16) {
+    hipLaunchKernelGGL(score_mid_kernel<uint16_t>, grid, dim3(kThreads), hist_lds, s, g, probs, ws);
+  } else {
+    hipLaunchKernelGGL(score_mid_kernel<float>, grid, dim3(kThreads), hist_lds, s, g, probs, ws);
+  }
 }
 
 }  // namespace tkphi

@@ -61,6 +61,8 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   g->Hq = cfg->n_q_heads; g->Hkv = cfg->n_kv_heads; g->G = g->Hq / g->Hkv;
   g->d = cfg->d_head; g->dphi = cfg->d_phi; g->n_sink = cfg->n_sink; g->n_tail = cfg->n_tail;
   g->dtype = cfg->kv_dtype;
+  g->dbg = env_int("TKPHI_DBG", 0);
+  g->use_mfma = (cfg->kv_dtype == TKPHI_BF16 && cfg->d_phi == cfg->d_head && !env_int("TKPHI_FORCE_GENERIC", 0)) ? 1 : 0;
   g->n_problems = n_problems; g->max_L = max_L;
   const int64_t mid = (int64_t)max_L - cfg->n_sink - cfg->n_tail;
   g->max_mid = (int)std::max<int64_t>(mid, 0);
@@ -69,17 +71,13 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   g->score_scale = cfg->score_scale; g->a = cfg->phi_in_scale; g->c = cfg->phi_norm_coef;
 
   const int64_t units = (int64_t)g->max_mid * g->Hkv * std::max(n_problems, 1);
-  // score_mid: about 1024 workgroups, 512..8192 tokens each
-  int sc = (int)align_up((size_t)std::clamp<int64_t>(ceil_div(units, 1024), 512, 8192), 64);
+  // score_mid: about 2048 workgroups, 256..8192 tokens each (uint16 chunk histograms: < 65536)
+  int sc = (int)align_up((size_t)std::clamp<int64_t>(ceil_div(units, 2048), 256, 8192), 256);
   sc = env_int("TKPHI_SCAN_CHUNK", sc);
-  g->scan_chunk = std::max(64, sc / 64 * 64);
+  g->scan_chunk = std::clamp(sc / 64 * 64, 64, 32768);
   g->n_scan_chunks = (int)std::max<int64_t>(1, ceil_div(g->max_mid, g->scan_chunk));
-  // select / gather slices: about 512 per launch, 1024..16384 tokens each
-  int sl = (int)align_up((size_t)std::clamp<int64_t>(ceil_div(units, 512), 1024, 16384), 256);
-  sl = env_int("TKPHI_SEL_CHUNK", sl);
-  g->sel_chunk = std::max(256, sl / 256 * 256);
-  while (ceil_div(g->max_mid, g->sel_chunk) > 1024) g->sel_chunk *= 2;   // select keeps per-slice counts in LDS
-  g->n_sel_slices = (int)std::max<int64_t>(1, ceil_div(g->max_mid, g->sel_chunk));
+  // gather: tiles of kPairsPerWG retrieved tokens per query head
+  g->n_tiles = (int)ceil_div(std::min<int64_t>(max_K, g->max_mid), kPairsPerWG);
   // summary_build: about 512 workgroups
   int bc = (int)align_up((size_t)std::clamp<int64_t>(ceil_div(units, 512), 256, 1 << 20), 64);
   bc = env_int("TKPHI_BUILD_CHUNK", bc);
@@ -93,14 +91,13 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   g->off_problem0 = off;
   size_t p = 0;
   g->off_scores = p;  p = align_up(p + (size_t)g->Hq * g->mid_stride * sizeof(float), 256);
-  g->off_hist = p;    p = align_up(p + (size_t)g->Hq * kBins * sizeof(uint32_t), 256);
-  g->off_state = p;   p = align_up(p + (size_t)g->Hq * sizeof(HeadState), 256);
-  g->off_cand = p;    p = align_up(p + (size_t)g->Hq * kCandCap * sizeof(uint2), 256);
-  g->off_above = p;   p = align_up(p + (size_t)g->Hq * g->n_sel_slices * sizeof(int32_t), 256);
-  g->off_offsets = p; p = align_up(p + (size_t)g->Hq * g->n_sel_slices * sizeof(int32_t), 256);
+  g->off_hist = p;    p = align_up(p + (size_t)g->n_scan_chunks * g->Hq * kBins * sizeof(uint16_t), 256);
+  g->off_nsel = p;    p = align_up(p + (size_t)g->Hq * sizeof(int32_t), 256);
+  g->off_selidx = p;  p = align_up(p + (size_t)g->Hq * std::max(max_K, 1) * sizeof(int32_t), 256);
+  g->off_selscore = p; p = align_up(p + (size_t)g->Hq * std::max(max_K, 1) * sizeof(float), 256);
   g->off_phiq = p;    p = align_up(p + (size_t)g->Hq * g->dphi * sizeof(float), 256);
   g->off_part = p;
-  p = align_up(p + (size_t)g->Hkv * (g->n_sel_slices + 1) * g->G * g->part_stride * sizeof(float), 256);
+  p = align_up(p + (size_t)g->Hq * (g->n_tiles + 1) * g->part_stride * sizeof(float), 256);
   g->per_problem = p;
   const size_t decode_total = g->off_problem0 + (size_t)std::max(n_problems, 1) * g->per_problem;
   g->off_bpart = g->off_problem0;
@@ -172,7 +169,6 @@ tkphi_status tkphi_decode(const tkphi_config* cfg, const tkphi_problem* problems
   hipStream_t s = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
   (void)hipGetLastError();
-  launch_prologue(g, problems, ws, s);
   launch_score_mid(g, problems, ws, s);
   launch_select(g, problems, ws, s);
   launch_gather(g, problems, ws, s);
@@ -204,18 +200,17 @@ tkphi_status tkphi_decode_stage_times(const tkphi_config* cfg, const tkphi_probl
     if ((st = hip_ok(hipEventCreate(&ev[made]), "hipEventCreate")) != TKPHI_OK) break;
   if (st == TKPHI_OK) {
     (void)hipGetLastError();
-    hipEventRecord(ev[0], s);
-    launch_prologue(g, problems, ws, s);  hipEventRecord(ev[1], s);
-    launch_score_mid(g, problems, ws, s); hipEventRecord(ev[2], s);
-    launch_select(g, problems, ws, s);    hipEventRecord(ev[3], s);
-    launch_gather(g, problems, ws, s);    hipEventRecord(ev[4], s);
-    launch_merge(g, problems, ws, mode, s); hipEventRecord(ev[5], s);
+    (void)hipEventRecord(ev[0], s);
+    launch_score_mid(g, problems, ws, s);   (void)hipEventRecord(ev[1], s);
+    launch_select(g, problems, ws, s);      (void)hipEventRecord(ev[2], s);
+    launch_gather(g, problems, ws, s);      (void)hipEventRecord(ev[3], s);
+    launch_merge(g, problems, ws, mode, s); (void)hipEventRecord(ev[4], s);
     st = hip_ok(hipGetLastError(), "tkphi_decode_stage_times launch");
     if (st == TKPHI_OK) st = hip_ok(hipEventSynchronize(ev[TKPHI_N_STAGES]), "hipEventSynchronize");
     for (int i = 0; st == TKPHI_OK && i < TKPHI_N_STAGES; ++i)
       st = hip_ok(hipEventElapsedTime(&stage_ms_out[i], ev[i], ev[i + 1]), "hipEventElapsedTime");
   }
-  for (int i = 0; i < made; ++i) hipEventDestroy(ev[i]);
+  for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
   return st;
 }
 

@@ -8,57 +8,47 @@
 
 namespace tkphi {
 
-constexpr int kThreads = 256;          // every kernel uses 256-thread workgroups (4 wavefronts)
+constexpr int kThreads = 256;          // default workgroup: 256 threads (4 wavefronts)
+constexpr int kSelThreads = 1024;      // topk_select: one 1024-thread workgroup per query head
 constexpr int kMaxGroup = 8;           // query heads per KV head
 constexpr int kMaxDim = 256;           // d_head / d_phi upper bound of the generic kernels
 
 // ---- score histogram --------------------------------------------------------------
 // First-level bins of the radix select: a monotone non-decreasing map of the score to
-// [0, kBins).  Exponents 2^-6 .. 2^7 are resolved with 6 mantissa bits; everything
-// smaller in magnitude falls in one bin per sign, everything larger in the outermost
-// bins.  Only monotonicity matters for correctness; the resolution keeps the boundary
-// bin small for attention-like score ranges.
-constexpr int kExpLo = 121;
-constexpr int kExpHi = 133;
-constexpr int kMagBins = (kExpHi - kExpLo + 1) * 64 + 2;   // 834
-constexpr int kBins = 2 * kMagBins;                         // 1668
+// [0, kBins): sign, 16 exponents (2^-8 .. 2^8, clamped outside) and 4 mantissa bits.
+// Only monotonicity matters for correctness; the resolution keeps the boundary bin (the
+// tokens whose exact rank must still be resolved) small for attention-like scores.
+constexpr int kExpLo = 119;
+constexpr int kExpHi = 134;
+constexpr int kMagBins = (kExpHi - kExpLo + 1) * 16;   // 256
+constexpr int kBins = 2 * kMagBins;                     // 512
 constexpr int kCandCap = 4096;         // boundary-bin candidates resolved in LDS
-
-// ---- per-query-head selection state (device, in the workspace) -------------------
-struct HeadState {
-  uint32_t cand_count;   // candidates appended by the filter pass
-  uint32_t ticket;       // arrival counter of the filter workgroups
-  uint32_t thr_key;      // selection threshold: a token is retrieved iff
-  int32_t thr_idx;       //   key > thr_key || (key == thr_key && mid_index <= thr_idx)
-  int32_t bstar;         // boundary bin
-  int32_t krem;          // tokens still to take from the boundary bin
-  int32_t n_sel;         // K' = min(K, |M|, max_K)
-  int32_t pad;
-};
+constexpr int kPairsPerWG = 64;        // gather: retrieved tokens per workgroup (16 per wavefront)
 
 // ---- launch geometry + workspace layout -------------------------------------------
 struct Geom {
   int Hq, Hkv, G, d, dphi, n_sink, n_tail, dtype;
+  int use_mfma;          // bf16 storage with d_phi == d_head: matrix-core kernels
+  int dbg;
   int n_problems, max_L, max_K, max_mid;
   int mid_stride;        // floats per score row (multiple of 64)
   int scan_chunk, n_scan_chunks;     // score_mid: mid tokens per workgroup
-  int sel_chunk, n_sel_slices;       // select / gather: mid tokens per slice
+  int n_tiles;           // gather: ceil(max_K / kPairsPerWG) retrieved-token tiles per query head
   int build_chunk, n_build_chunks;   // summary_build: mid tokens per workgroup
-  int part_stride;       // floats per (slice, query head) partial: 2*d + 4
+  int part_stride;       // floats per partial: 2*d + 4
   float score_scale, a, c;
   // byte offsets inside the workspace
   size_t off_status;     // uint32 device status word
   size_t off_problem0;   // first per-problem block
   size_t per_problem;    // bytes per problem block
   // offsets inside a per-problem block
-  size_t off_scores;     // float    [Hq][mid_stride]
-  size_t off_hist;       // uint32   [Hq][kBins]
-  size_t off_state;      // HeadState[Hq]
-  size_t off_cand;       // uint2    [Hq][kCandCap]
-  size_t off_above;      // int32    [Hq][n_sel_slices]  tokens above the boundary bin per slice
-  size_t off_offsets;    // int32    [Hq][n_sel_slices]  output offset of each slice's selection
+  size_t off_scores;     // float    [Hq][mid_stride]            mid-region scores
+  size_t off_hist;       // uint16   [n_scan_chunks][Hq][kBins]  per-chunk histograms
+  size_t off_nsel;       // int32    [Hq]                        retrieved tokens K' per head
+  size_t off_selidx;     // int32    [Hq][max_K]                 retrieved mid indices
+  size_t off_selscore;   // float    [Hq][max_K]                 their scores
   size_t off_phiq;       // float    [Hq][dphi]
-  size_t off_part;       // float    [Hkv][n_sel_slices + 1][G][part_stride]
+  size_t off_part;       // float    [Hq][n_tiles + 1][part_stride]  (+1: the anchors)
   size_t off_bpart;      // float    [Hkv][n_build_chunks][dphi*(d+1)]   (build only; aliases the block)
   size_t total_bytes;
 };
@@ -68,12 +58,15 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
 void set_error(const char* fmt, ...);
 
 // kernel launchers (each defined next to its kernels)
-void launch_prologue(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
 void launch_score_mid(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
+void launch_score_mid_mfma(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
 void launch_select(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
 void launch_gather(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
+void launch_gather_mfma(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
 void launch_merge(const Geom& g, const tkphi_problem* probs, char* ws, int mode, hipStream_t s);
 void launch_build(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
+void launch_build_mfma(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
+void launch_build_reduce(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
 
 #ifdef __HIPCC__
 // ---- device helpers ------------------------------------------------------------------
@@ -87,11 +80,11 @@ __device__ __forceinline__ int key_bin(uint32_t key) {
   const bool pos = (key & 0x80000000u) != 0;
   const uint32_t mag = pos ? (key & 0x7fffffffu) : (~key & 0x7fffffffu);
   const int e = (int)(mag >> 23);
-  const int m6 = (int)((mag >> 17) & 63u);
+  const int m4 = (int)((mag >> 19) & 15u);
   int mb;
   if (e < kExpLo) mb = 0;
   else if (e > kExpHi) mb = kMagBins - 1;
-  else mb = (e - kExpLo) * 64 + m6 + 1;
+  else mb = (e - kExpLo) * 16 + m4;
   return pos ? (kMagBins + mb) : (kMagBins - 1 - mb);
 }
 
@@ -103,6 +96,18 @@ __device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
   uint32_t u = __float_as_uint(f);
   u += 0x7fffu + ((u >> 16) & 1u);
   return (uint16_t)(u >> 16);
+}
+
+// A feature value as the sum of two bf16 numbers, hi = bf16(f) and lo = bf16(f - hi): 16
+// significant bits, which is what the matrix-core summary build contracts against the
+// values and what the decode side subtracts for a retrieved token.
+__device__ __forceinline__ void split_bf16(float f, uint32_t* hi, uint32_t* lo) {
+  const uint16_t h = float_to_bf16_bits(f);
+  *hi = h;
+  *lo = float_to_bf16_bits(f - bf16_bits_to_float(h));
+}
+__device__ __forceinline__ float join_bf16(uint32_t hi, uint32_t lo) {
+  return bf16_bits_to_float((uint16_t)hi) + bf16_bits_to_float((uint16_t)lo);
 }
 
 template <typename T> struct Elem;

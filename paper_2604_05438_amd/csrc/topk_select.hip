@@ -1,54 +1,74 @@
 // topk_select: exhaustive Top-K over the mid-region scores of one query head
-// (Sec. "Models, tasks, and protocol": the K highest-scoring mid-region tokens), as a
-// multi-workgroup radix select.
+// (Sec. "Models, tasks, and protocol": the K highest-scoring mid-region tokens), plus the
+// query feature map phi_q (Sec. "Positive feature maps and summary states": phi_q is
+// evaluated per query head at decode time).
 //
-//   level 1  (done by score_mid)  histogram of a monotone bin of the score
-//   this kernel, every workgroup  boundary bin b* = the bin holding the K-th largest
-//                                 score; count, per slice, the tokens in bins above b*
-//                                 and collect the tokens of bin b* as candidates
-//   last workgroup of the head    exact K_rem-th largest candidate by (score descending,
-//                                 index ascending) -> threshold (thr_key, thr_idx); per
-//                                 slice output offsets so the gather pass can emit the
-//                                 retrieved indices in ascending order
-//
-// The result is the selection predicate
-//   retrieved(i)  <=>  key_i > thr_key  ||  (key_i == thr_key && i <= thr_idx)
-// which is exact for any input (ties go to the lower index).  If the boundary bin holds
-// more than kCandCap tokens the last workgroup falls back to radix passes over the
-// head's score row in global memory: slower, same result.
-#include "block_utils.h"
+// One 1024-thread workgroup per (problem, query head) runs a two-level radix select:
+//   1. sum the per-chunk histograms written by score_mid -> boundary bin b*: the bin that
+//      holds the K-th largest score; every token in a higher bin is retrieved
+//   2. per chunk, count the tokens above b* (from the chunk histograms) so that each
+//      wavefront knows where its output starts: no atomics, the output order is fixed
+//   3. one ordered pass over the scores: tokens above b* go straight to the retrieved
+//      list, tokens in b* become candidates (in LDS)
+//   4. exact K_rem-th largest candidate by (score descending, index ascending) with an
+//      8-bit radix select in LDS; the winning candidates are appended to the list
+// The list holds (mid index, score): first the tokens above b* in ascending index order,
+// then the boundary-bin winners in ascending index order.  Ties go to the lower index.
+// If the boundary bin holds more than kCandCap tokens (e.g. all scores equal) steps 3-4
+// fall back to radix passes over the score row in global memory: slower, same result.
 #include "tkphi_internal.h"
 
 namespace tkphi {
 
-constexpr int kBinsPerThread = (kBins + kThreads - 1) / kThreads;   // 7
+constexpr int kSelWaves = kSelThreads / 64;
 
-// K-th largest (1-based rank `want`) 64-bit composite among `count` elements delivered
-// by get(j, &composite) -> bool (false: element does not take part).  8 radix passes of
-// 8 bits.  All threads must call; returns the composite in every thread.
+// inclusive prefix sum over the 1024 threads; sh must hold >= 16 ints; two barriers
+__device__ __forceinline__ int sel_scan_incl(int v, int* sh) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  int x = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int y = __shfl_up(x, o);
+    if (lane >= o) x += y;
+  }
+  if (lane == 63) sh[w] = x;
+  __syncthreads();
+  int add = 0;
+  for (int i = 0; i < w; ++i) add += sh[i];
+  __syncthreads();
+  return x + add;
+}
+
+__device__ __forceinline__ uint64_t composite(uint32_t key, uint32_t row) {
+  return ((uint64_t)key << 32) | (uint64_t)(0xffffffffu - row);
+}
+
+// `want`-th largest (1-based) 64-bit composite among `count` elements delivered by
+// get(j, &composite) -> bool (false: element does not take part).  8 radix passes of 8
+// bits.  All threads must call; returns the composite in every thread.
 template <typename Get>
 __device__ uint64_t radix_select_desc(int count, int want, Get get, uint32_t* sh_hist /*[256]*/,
-                                      int* sh_scan /*[4]*/, uint64_t* sh_prefix, int* sh_want) {
+                                      int* sh_scan /*[16]*/, uint64_t* sh_prefix, int* sh_want) {
   const int tid = threadIdx.x;
   if (tid == 0) { *sh_prefix = 0ull; *sh_want = want; }
   __syncthreads();
   for (int shift = 56; shift >= 0; shift -= 8) {
-    sh_hist[tid] = 0u;
+    if (tid < 256) sh_hist[tid] = 0u;
     __syncthreads();
     const uint64_t prefix = *sh_prefix;
     const int w = *sh_want;
     const uint64_t himask = shift == 56 ? 0ull : (~0ull << (shift + 8));
-    for (int j = tid; j < count; j += kThreads) {
+    for (int j = tid; j < count; j += kSelThreads) {
       uint64_t v;
       if (get(j, &v) && (v & himask) == prefix) atomicAdd(&sh_hist[(uint32_t)(v >> shift) & 255u], 1u);
     }
     __syncthreads();
-    // thread t looks at digit 255 - t: prefix scan over t == suffix scan over digits
+    // thread t < 256 looks at digit 255 - t: prefix scan over t == suffix scan over digits
     const int digit = 255 - tid;
-    const int c = (int)sh_hist[digit];
-    const int incl = block_scan_incl(c, sh_scan);
+    const int c = tid < 256 ? (int)sh_hist[digit] : 0;
+    const int incl = sel_scan_incl(c, sh_scan);
     const int excl = incl - c;
-    if (excl < w && w <= incl) {
+    if (tid < 256 && excl < w && w <= incl) {
       *sh_prefix = prefix | ((uint64_t)digit << shift);
       *sh_want = w - excl;
     }
@@ -57,168 +77,228 @@ __device__ uint64_t radix_select_desc(int count, int want, Get get, uint32_t* sh
   return *sh_prefix;
 }
 
-__device__ __forceinline__ uint64_t composite(uint32_t key, uint32_t row) {
-  return ((uint64_t)key << 32) | (uint64_t)(0xffffffffu - row);
-}
-
-// grid (n_sel_slices, Hq, n_problems)
-__global__ __launch_bounds__(kThreads) void select_kernel(Geom g, const tkphi_problem* __restrict__ probs,
-                                                          char* __restrict__ ws) {
+// grid (Hq, n_problems), 1024 threads; dynamic LDS: candidates uint2[kCandCap]
+template <typename T>
+__global__ __launch_bounds__(kSelThreads) void select_kernel(Geom g, const tkphi_problem* __restrict__ probs,
+                                                             char* __restrict__ ws) {
+  __shared__ float qf[kMaxDim];
+  __shared__ uint32_t sh_tot[kBins];
   __shared__ uint32_t sh_hist[256];
-  __shared__ int sh_scan[4];
+  __shared__ int sh_scan[kSelWaves];
+  __shared__ int sh_wabove[kSelWaves], sh_wcand[kSelWaves];
   __shared__ uint64_t sh_prefix;
-  __shared__ int sh_want, sh_bstar, sh_krem, sh_last;
-  __shared__ int sh_slice[1024];
-  extern __shared__ uint2 sh_cand[];     // [kCandCap] (key, row)
+  __shared__ int sh_want, sh_bstar, sh_krem, sh_chi;
+  extern __shared__ uint2 sh_cand[];     // [kCandCap] (key, row), ascending row
 
-  const int sl = blockIdx.x, gq = blockIdx.y, p = blockIdx.z, tid = threadIdx.x;
-  const int L = probs[p].L;
-  if (L < 1 || L > g.max_L) return;
-  const int n = mid_size(L, g.n_sink, g.n_tail);
-  const int Ksel = max(0, min(min(probs[p].topk, n), g.max_K));
-  const int n_slices = (n + g.sel_chunk - 1) / g.sel_chunk;
-  const int n_wg = max(n_slices, 1);
-  if (sl >= n_wg) return;
-
+  const int gq = blockIdx.x, p = blockIdx.y, tid = threadIdx.x;
+  const int lane = tid & 63, wv = tid >> 6;
   char* blk = problem_block(g, ws, p);
-  const uint32_t* hist = (const uint32_t*)(blk + g.off_hist) + (size_t)gq * kBins;
-  HeadState* st = (HeadState*)(blk + g.off_state) + gq;
+
+  // device status word: recomputed from the problem lengths by one workgroup
+  if (gq == 0 && p == 0) {
+    int bad = 0;
+    for (int i = tid; i < g.n_problems; i += kSelThreads) {
+      const int Li = probs[i].L;
+      bad |= (Li < 1 || Li > g.max_L) ? 1 : 0;
+    }
+    bad = __syncthreads_or(bad);
+    if (tid == 0) *(uint32_t*)(ws + g.off_status) = bad ? TKPHI_DEV_BAD_LENGTH : 0u;
+  }
+
+  const tkphi_problem pr = probs[p];
+  if (pr.L < 1 || pr.L > g.max_L) return;
+  const int n = mid_size(pr.L, g.n_sink, g.n_tail);
+  const int Ksel = max(0, min(min(pr.topk, n), g.max_K));
+  int32_t* nsel = (int32_t*)(blk + g.off_nsel);
+  if (tid == 0) nsel[gq] = Ksel;
+
+  // ---- phi_q(q)[j] = exp(a Wq[j] . q - c |q|^2 + bq[j]) ---------------------------------
+  {
+    float* phiq = (float*)(blk + g.off_phiq) + (size_t)gq * g.dphi;
+    for (int c = tid; c < g.d; c += kSelThreads) qf[c] = Elem<T>::load1(pr.q, (int64_t)gq * g.d + c);
+    __syncthreads();
+    if (tid < g.dphi) {
+      float dot = 0.f, nrm = 0.f;
+      const int64_t wbase = ((int64_t)gq * g.dphi + tid) * g.d;
+      for (int c = 0; c < g.d; ++c) {
+        const float x = qf[c];
+        dot = fmaf(Elem<T>::load1(pr.Wq, wbase + c), x, dot);
+        nrm = fmaf(x, x, nrm);
+      }
+      phiq[tid] = expf(g.a * dot - g.c * nrm + pr.bq[(int64_t)gq * g.dphi + tid]);
+    }
+  }
+  if (Ksel == 0) return;
+
+  const int n_chunks = (n + g.scan_chunk - 1) / g.scan_chunk;
+  const uint16_t* hist = (const uint16_t*)(blk + g.off_hist) + (size_t)gq * kBins;   // + chunk * Hq * kBins
+  const size_t hstep = (size_t)g.Hq * kBins;
   const float* scores = (const float*)(blk + g.off_scores) + (size_t)gq * g.mid_stride;
-  uint2* cand = (uint2*)(blk + g.off_cand) + (size_t)gq * kCandCap;
-  int32_t* above = (int32_t*)(blk + g.off_above) + (size_t)gq * g.n_sel_slices;
-  int32_t* offsets = (int32_t*)(blk + g.off_offsets) + (size_t)gq * g.n_sel_slices;
+  int32_t* sel_idx = (int32_t*)(blk + g.off_selidx) + (size_t)gq * g.max_K;
+  float* sel_score = (float*)(blk + g.off_selscore) + (size_t)gq * g.max_K;
 
-  // ---- boundary bin ----------------------------------------------------------------
-  if (tid == 0) { sh_bstar = kBins; sh_krem = 0; }
-  __syncthreads();
+  // ---- 1. total histogram, boundary bin ---------------------------------------------------
   {
-    const int grp = kThreads - 1 - tid;            // thread t owns the bin group 255 - t
-    const int lo = grp * kBinsPerThread;
-    int c[kBinsPerThread];
-    int tot = 0;
-#pragma unroll
-    for (int i = 0; i < kBinsPerThread; ++i) {
-      const int b = lo + i;
-      c[i] = b < kBins ? (int)hist[b] : 0;
-      tot += c[i];
+    const int b = tid & (kBins - 1), half = tid >> 9;      // 2 threads per bin: even / odd chunks
+    uint32_t t = 0;
+    for (int c = half; c < n_chunks; c += 2) t += hist[(size_t)c * hstep + b];
+    if (half == 1) sh_tot[b] = t;
+    __syncthreads();
+    if (half == 0) sh_tot[b] += t;
+    if (tid == 0) { sh_bstar = -1; sh_krem = 0; sh_chi = 0; }
+    __syncthreads();
+    // thread t < kBins looks at bin kBins-1-t: prefix over t == suffix over bins
+    const int bin = kBins - 1 - tid;
+    const int c = tid < kBins ? (int)sh_tot[bin] : 0;
+    const int incl = sel_scan_incl(c, sh_scan);
+    const int excl = incl - c;                              // tokens in bins above `bin`
+    if (tid < kBins && excl < Ksel && Ksel <= incl) { sh_bstar = bin; sh_krem = Ksel - excl; sh_chi = excl; }
+    __syncthreads();
+  }
+  const int bstar = sh_bstar, krem = sh_krem, c_hi = sh_chi;
+  if (bstar < 0) {                       // cannot happen for consistent histograms
+    if (tid == 0) nsel[gq] = 0;
+    return;
+  }
+  const int nb = (int)sh_tot[bstar];
+  const bool in_lds = nb <= kCandCap;
+
+  // ---- 2. where each wavefront's output starts ----------------------------------------------
+  // wavefront w owns chunks [w * cpw, (w+1) * cpw): a contiguous token range
+  const int cpw = (n_chunks + kSelWaves - 1) / kSelWaves;
+  const int ch0 = min(wv * cpw, n_chunks), ch1 = min(ch0 + cpw, n_chunks);
+  {
+    int above = 0, cand = 0;
+    for (int c = ch0; c < ch1; ++c) {
+      const uint16_t* hc = hist + (size_t)c * hstep;
+      for (int b = bstar + 1 + lane; b < kBins; b += 64) above += hc[b];
+      if (lane == 0) cand += hc[bstar];
     }
-    const int incl = block_scan_incl(tot, sh_scan);
-    int run = incl - tot;                          // tokens in bins above this group
-    if (Ksel > 0 && run < Ksel && Ksel <= incl) {
 #pragma unroll
-      for (int i = kBinsPerThread - 1; i >= 0; --i) {
-        if (run < Ksel && Ksel <= run + c[i]) { sh_bstar = lo + i; sh_krem = Ksel - run; }
-        run += c[i];
+    for (int o = 32; o >= 1; o >>= 1) above += __shfl_xor(above, o);
+    if (lane == 0) { sh_wabove[wv] = above; sh_wcand[wv] = cand; }
+  }
+  __syncthreads();
+  int a_pos = 0, c_pos = 0;              // this wavefront's running output positions
+  for (int i = 0; i < wv; ++i) { a_pos += sh_wabove[i]; c_pos += sh_wcand[i]; }
+
+  // ---- 3. ordered pass: 4 consecutive tokens per lane, 256 per wavefront instruction ----------
+  {
+    const int t0 = ch0 * g.scan_chunk, t1 = min(n, ch1 * g.scan_chunk);
+    constexpr int U = 4;                 // loads in flight per lane
+    for (int base = t0; base < t1; base += 256 * U) {
+      float4 v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int tok = base + u * 256 + lane * 4;
+        v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (tok + 3 < t1) v[u] = *(const float4*)(scores + tok);     // rows are 16-byte aligned (mid_stride % 64 == 0)
+        else {
+          if (tok < t1) v[u].x = scores[tok];
+          if (tok + 1 < t1) v[u].y = scores[tok + 1];
+          if (tok + 2 < t1) v[u].z = scores[tok + 2];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int tok = base + u * 256 + lane * 4;
+        const float sv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+        int fa[4], fc[4], na = 0, nc = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int b = (tok + e < t1) ? key_bin(score_key(sv[e])) : -1;
+          fa[e] = b > bstar ? 1 : 0;
+          fc[e] = b == bstar ? 1 : 0;
+          na += fa[e]; nc += fc[e];
+        }
+        // exclusive prefix over lanes of (na, nc) packed in one int (each <= 256)
+        int packed = na | (nc << 16), x = packed;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const int y = __shfl_up(x, o);
+          if (lane >= o) x += y;
+        }
+        const int total = __shfl(x, 63);
+        int pa = a_pos + ((x - packed) & 0xffff), pc = c_pos + ((x - packed) >> 16);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (fa[e]) { sel_idx[pa] = tok + e; sel_score[pa] = sv[e]; ++pa; }
+          if (fc[e]) { if (in_lds) sh_cand[pc] = make_uint2(score_key(sv[e]), (uint32_t)(tok + e)); ++pc; }
+        }
+        a_pos += total & 0xffff;
+        c_pos += total >> 16;
       }
     }
   }
   __syncthreads();
-  const int bstar = sh_bstar, krem = sh_krem;
 
-  // ---- filter pass over this slice -------------------------------------------------
-  const int t0 = sl * g.sel_chunk, t1 = min(n, t0 + g.sel_chunk);
-  int n_above = 0;
-  for (int base = t0; base < t1; base += kThreads) {
-    const int row = base + tid;
-    bool is_cand = false;
-    uint32_t key = 0;
-    if (row < t1) {
-      key = score_key(scores[row]);
-      const int b = key_bin(key);
-      n_above += (b > bstar) ? 1 : 0;
-      is_cand = (b == bstar);
+  // ---- 4. resolve the boundary bin ---------------------------------------------------------------
+  if (in_lds) {
+    auto get = [&](int j, uint64_t* v) { const uint2 e = sh_cand[j]; *v = composite(e.x, e.y); return true; };
+    const uint64_t thr = radix_select_desc(nb, krem, get, sh_hist, sh_scan, &sh_prefix, &sh_want);
+    // ordered append of the winners: thread t owns candidates [t*R, (t+1)*R)
+    const int R = (nb + kSelThreads - 1) / kSelThreads;
+    int cnt = 0;
+    for (int j = tid * R; j < min(nb, (tid + 1) * R); ++j) cnt += composite(sh_cand[j].x, sh_cand[j].y) >= thr ? 1 : 0;
+    int pos = c_hi + sel_scan_incl(cnt, sh_scan) - cnt;
+    for (int j = tid * R; j < min(nb, (tid + 1) * R); ++j) {
+      const uint2 e = sh_cand[j];
+      if (composite(e.x, e.y) >= thr) { sel_idx[pos] = (int)e.y; sel_score[pos] = scores[e.y]; ++pos; }
     }
-    const uint64_t mask = __ballot(is_cand);
-    if (mask) {
-      const int lane = tid & 63;
-      const int leader = __ffsll((long long)mask) - 1;
-      uint32_t basepos = 0;
-      if (lane == leader) basepos = atomicAdd(&st->cand_count, (uint32_t)__popcll(mask));
-      basepos = __shfl(basepos, leader);
-      if (is_cand) {
-        const uint32_t slot = basepos + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-        if (slot < (uint32_t)kCandCap) cand[slot] = make_uint2(key, (uint32_t)row);
+  } else {
+    auto get = [&](int j, uint64_t* v) {
+      const uint32_t key = score_key(scores[j]);
+      *v = composite(key, (uint32_t)j);
+      return key_bin(key) == bstar;
+    };
+    const uint64_t thr = radix_select_desc(n, krem, get, sh_hist, sh_scan, &sh_prefix, &sh_want);
+    int pos0 = c_hi;
+    for (int base = 0; base < n; base += kSelThreads) {
+      const int j = base + tid;
+      int f = 0;
+      float s = 0.f;
+      if (j < n) {
+        s = scores[j];
+        const uint32_t key = score_key(s);
+        f = (key_bin(key) == bstar && composite(key, (uint32_t)j) >= thr) ? 1 : 0;
       }
-    }
-  }
-  n_above = block_sum_int(n_above, sh_scan);
-  if (tid == 0 && n_slices > 0) above[sl] = n_above;
-
-  // ---- ticket: the last workgroup of this head resolves the boundary bin ------------
-  __threadfence();          // every thread publishes its candidate / count stores device-wide
-  __syncthreads();
-  if (tid == 0) {
-    const uint32_t t = atomicAdd(&st->ticket, 1u);
-    sh_last = (t == (uint32_t)(n_wg - 1)) ? 1 : 0;
-  }
-  __syncthreads();
-  if (!sh_last) return;
-  __threadfence();
-
-  uint32_t thr_key = 0xffffffffu;
-  int32_t thr_idx = -1;
-  for (int i = tid; i < 1024; i += kThreads) sh_slice[i] = 0;
-  __syncthreads();
-  const bool have_thr = Ksel > 0 && bstar < kBins;
-  if (have_thr) {
-    const int nb = (int)hist[bstar];
-    uint64_t T;
-    if (nb <= kCandCap) {
-      for (int j = tid; j < nb; j += kThreads) sh_cand[j] = cand[j];
+      const int incl = sel_scan_incl(f, sh_scan);
+      if (f) { sel_idx[pos0 + incl - 1] = j; sel_score[pos0 + incl - 1] = s; }
+      if (tid == kSelThreads - 1) sh_want = incl;
       __syncthreads();
-      auto get = [&](int j, uint64_t* v) { const uint2 e = sh_cand[j]; *v = composite(e.x, e.y); return true; };
-      T = radix_select_desc(nb, krem, get, sh_hist, sh_scan, &sh_prefix, &sh_want);
-      for (int j = tid; j < nb; j += kThreads) {
-        const uint2 e = sh_cand[j];
-        if (composite(e.x, e.y) >= T) atomicAdd(&sh_slice[e.y / g.sel_chunk], 1);
-      }
-    } else {
-      auto get = [&](int j, uint64_t* v) {
-        const uint32_t key = score_key(scores[j]);
-        *v = composite(key, (uint32_t)j);
-        return key_bin(key) == bstar;
-      };
-      T = radix_select_desc(n, krem, get, sh_hist, sh_scan, &sh_prefix, &sh_want);
-      for (int j = tid; j < n; j += kThreads) {
-        const uint32_t key = score_key(scores[j]);
-        if (key_bin(key) == bstar && composite(key, (uint32_t)j) >= T) atomicAdd(&sh_slice[j / g.sel_chunk], 1);
-      }
-    }
-    thr_key = (uint32_t)(T >> 32);
-    thr_idx = (int32_t)(0xffffffffu - (uint32_t)(T & 0xffffffffull));
-  }
-  __syncthreads();
-  // per-slice output offsets: exclusive prefix over slices of (above + selected in bin b*)
-  {
-    constexpr int PER = 1024 / kThreads;   // 4
-    int v[PER], tot = 0;
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int s = tid * PER + i;
-      v[i] = s < n_slices ? (sh_slice[s] + (have_thr ? above[s] : 0)) : 0;
-      tot += v[i];
-    }
-    const int incl = block_scan_incl(tot, sh_scan);
-    int run = incl - tot;
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int s = tid * PER + i;
-      if (s < n_slices) offsets[s] = run;
-      run += v[i];
+      pos0 += sh_want;
+      __syncthreads();
     }
   }
-  if (tid == 0) {
-    st->thr_key = thr_key;
-    st->thr_idx = thr_idx;
-    st->bstar = bstar;
-    st->krem = krem;
-    st->n_sel = Ksel;
+
+  // ---- optional export: retrieved token indices, ascending ---------------------------------------
+  if (pr.topk_idx) {
+    __syncthreads();
+    __threadfence_block();
+    int32_t* out = pr.topk_idx + (size_t)gq * g.max_K;
+    // merge of the two ascending runs [0, c_hi) and [c_hi, Ksel) by rank
+    for (int i = tid; i < Ksel; i += kSelThreads) {
+      const int v = sel_idx[i];
+      int lo, hi;
+      if (i < c_hi) { lo = c_hi; hi = Ksel; } else { lo = 0; hi = c_hi; }
+      const int lo0 = lo;
+      while (lo < hi) {                    // first element of the other run that is > v
+        const int mid = (lo + hi) >> 1;
+        if (sel_idx[mid] < v) lo = mid + 1; else hi = mid;
+      }
+      const int rank = (i < c_hi ? i : i - c_hi) + (lo - lo0);
+      out[rank] = g.n_sink + v;
+    }
   }
 }
 
 void launch_select(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
-  dim3 grid(g.n_sel_slices, g.Hq, g.n_problems);
-  hipLaunchKernelGGL(select_kernel, grid, dim3(kThreads), (size_t)kCandCap * sizeof(uint2), s, g, probs, ws);
+  dim3 grid(g.Hq, g.n_problems);
+  const size_t lds = (size_t)kCandCap * sizeof(uint2);
+  if (g.dtype == TKPHI_BF16)
+    hipLaunchKernelGGL(select_kernel<uint16_t>, grid, dim3(kSelThreads), lds, s, g, probs, ws);
+  else
+    hipLaunchKernelGGL(select_kernel<float>, grid, dim3(kSelThreads), lds, s, g, probs, ws);
 }
 
 }  // namespace tkphi

@@ -38,7 +38,7 @@ def test_l3b_128k_budget_sweep():
     from oracle import tkphi_oracle as orc
     S_or, u_or = orc.build_summaries(O["K"], O["V"], O["Wk"], O["bk"], w.phi_in_scale, w.phi_norm_coef,
                                      w.n_sink, w.n_tail)
-    PU.check_summaries(b.result(0, "S"), b.result(0, "u"), S_or, u_or, 2e-3)
+    PU.check_summaries(b.result(0, "S"), b.result(0, "u"), S_or, u_or, 2e-3, w=w, O=O)
     heads = [0, 4, 8, 11, 17, 23]
     n_mid = w.L - w.n_sink - w.n_tail
     for k in ks:
