@@ -15,6 +15,9 @@
 // merge: combines the partials of a query head in a fixed order (log-sum-exp rescaling),
 // evaluates the summary terms and applies the single-normalisation merge
 // (eq. (hybrid_merge)) with the exact branch's max shift applied to the residual branch.
+//
+// All loops over tokens issue their (independent) row loads before consuming them: these
+// kernels move little data and are bound by memory latency, not bandwidth.
 #include "block_utils.h"
 #include "tkphi_internal.h"
 
@@ -22,54 +25,146 @@ namespace tkphi {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 union Frag {
   u32x4 u;
   bf16x8 v;
 };
 
-// ---- anchors: exact terms over [0, n_sink) u [L - n_tail, L) (or every token if M is empty) --------
-// Whole workgroup; thread c < d owns value channel c.  Writes the partial of the anchor slot.
+// ---- weighted sums of value rows ------------------------------------------------------------
+// nu[c] = sum_i w[i] v_i[c], zv[c] = sum_i z[i] v_i[c] over `cnt` <= 64 rows given by tok[]
+// (absolute token indices), rows of d elements.  Each row is read by LPR = d / (elements per
+// 16 bytes) lanes with one 16-byte load; 256 threads cover 256 / LPR rows per pass and all
+// passes' loads are issued together.  Results land in part[4 .. 4+d) and part[4+d .. 4+2d).
+// LDS scratch `red` must hold 2 * 256 * 8 floats.
 template <typename T>
-__device__ void anchor_partial(const Geom& g, const tkphi_problem& pr, int gq, int n, float* part) {
-  __shared__ float a_q[kMaxDim];
-  __shared__ float a_s[kThreads];
-  __shared__ float a_red[4];
+__device__ __forceinline__ void weighted_value_sums(const Geom& g, const tkphi_problem& pr, int64_t head_off,
+                                                    const int* tok, const float* w, const float* z, int cnt,
+                                                    float* red, float* part, bool with_z) {
+  constexpr int EPL = Elem<T>::per16;
+  const int tid = threadIdx.x, d = g.d;
+  const int LPR = d / EPL, RPP = kThreads / LPR;      // rows per pass
+  const int seg = tid % LPR, rsub = tid / LPR;
+  constexpr int MAXP = 8;                              // 64 rows / (256 / 32 lanes) passes at most
+  const int n_pass = (cnt + RPP - 1) / RPP;
+  uint4 v[MAXP];
+#pragma unroll
+  for (int ps = 0; ps < MAXP; ++ps) {
+    if (ps < n_pass) {
+      const int i = min(ps * RPP + rsub, cnt - 1);
+      const u32x4 t = gload128((const char*)pr.V + (head_off + (int64_t)tok[i] * pr.stride_tok + seg * EPL) * sizeof(T));
+      v[ps] = make_uint4(t.x, t.y, t.z, t.w);
+    }
+  }
+  float an[EPL], az[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) { an[e] = 0.f; az[e] = 0.f; }
+#pragma unroll
+  for (int ps = 0; ps < MAXP; ++ps) {
+    if (ps < n_pass) {
+      const int i = ps * RPP + rsub;
+      if (i < cnt) {
+        float x[EPL];
+        Elem<T>::unpack(v[ps], x);
+        const float wi = w[i], zi = with_z ? z[i] : 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) { an[e] = fmaf(wi, x[e], an[e]); az[e] = fmaf(zi, x[e], az[e]); }
+      }
+    }
+  }
+  // reduce over the RPP row groups: red[rsub][channel]
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) {
+    red[rsub * d + seg * EPL + e] = an[e];
+    red[kThreads * 8 + rsub * d + seg * EPL + e] = az[e];
+  }
+  __syncthreads();
+  if (tid < d) {
+    float a0 = 0.f, a1 = 0.f;
+    for (int k = 0; k < RPP; ++k) { a0 += red[k * d + tid]; a1 += red[kThreads * 8 + k * d + tid]; }
+    part[4 + tid] += a0;
+    part[4 + d + tid] += a1;
+  }
+  __syncthreads();
+}
+
+// ---- anchors: exact terms over [0, n_sink) u [L - n_tail, L) (or every token if M is empty) --------
+// Batches of 64 anchors: scores with LPR lanes per key row (16-byte loads, butterfly sum),
+// running max / rescaling across batches in a fixed order.
+template <typename T>
+__device__ void anchor_partial(const Geom& g, const tkphi_problem& pr, int gq, int n, float* part, float* red) {
+  constexpr int EPL = Elem<T>::per16;
+  __shared__ int a_tok[64];
+  __shared__ float a_s[64], a_w[64];
+  __shared__ float a_acc[2 * kMaxDim + 4];           // running [m, Z, -, -, nu[d], zv[d]] in the partial's layout
   const int tid = threadIdx.x, d = g.d;
   const int h = gq / g.G;
   const int n_anchor = n > 0 ? g.n_sink + g.n_tail : pr.L;
   const int64_t head_off = (int64_t)h * pr.stride_head;
-  for (int c = tid; c < d; c += kThreads) a_q[c] = Elem<T>::load1(pr.q, (int64_t)gq * d + c);
+  const int LPR = d / EPL, RPP = kThreads / LPR;
+  const int seg = tid % LPR, rsub = tid / LPR;
+  float qreg[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) qreg[e] = Elem<T>::load1(pr.q, (int64_t)gq * d + seg * EPL + e);
+  for (int i = tid; i < 2 * d + 4; i += kThreads) a_acc[i] = 0.f;
+  float m = -INFINITY;
   __syncthreads();
-  float m = -INFINITY, Z = 0.f, nu = 0.f;
-  for (int base = 0; base < n_anchor; base += kThreads) {
-    const int cnt = min(kThreads, n_anchor - base);
-    // one anchor score per thread
-    float s = -INFINITY;
-    if (tid < cnt) {
-      const int a = base + tid;
-      const int tok = (n > 0 && a >= g.n_sink) ? (pr.L - g.n_tail + (a - g.n_sink)) : a;
-      float dot = 0.f;
-      const int64_t off = head_off + (int64_t)tok * pr.stride_tok;
-      for (int c = 0; c < d; ++c) dot = fmaf(Elem<T>::load1(pr.K, off + c), a_q[c], dot);
-      s = dot * g.score_scale + 0.0f;
-    }
-    a_s[tid] = s;
-    const float mb = block_max(s, a_red);          // barriers inside: a_s is visible afterwards
-    const float m_new = fmaxf(m, mb);
-    const float r = __expf(m - m_new);             // exp(-inf) = 0 on the first batch
-    nu *= r; Z *= r; m = m_new;
-    for (int i = 0; i < cnt; ++i) {
-      const int a = base + i;
-      const int tok = (n > 0 && a >= g.n_sink) ? (pr.L - g.n_tail + (a - g.n_sink)) : a;
-      const float w = __expf(a_s[i] - m);
-      Z += w;
-      if (tid < d) nu = fmaf(w, Elem<T>::load1(pr.V, head_off + (int64_t)tok * pr.stride_tok + tid), nu);
+  for (int base = 0; base < n_anchor; base += 64) {
+    const int cnt = min(64, n_anchor - base);
+    if (tid < 64) {
+      const int a = base + min(tid, cnt - 1);
+      a_tok[tid] = (n > 0 && a >= g.n_sink) ? (pr.L - g.n_tail + (a - g.n_sink)) : a;
     }
     __syncthreads();
+    // scores of the batch
+    constexpr int MAXP = 8;
+    const int n_pass = (cnt + RPP - 1) / RPP;
+    uint4 kv[MAXP];
+#pragma unroll
+    for (int ps = 0; ps < MAXP; ++ps) {
+      if (ps < n_pass) {
+        const int i = min(ps * RPP + rsub, cnt - 1);
+        const u32x4 t = gload128((const char*)pr.K + (head_off + (int64_t)a_tok[i] * pr.stride_tok + seg * EPL) * sizeof(T));
+        kv[ps] = make_uint4(t.x, t.y, t.z, t.w);
+      }
+    }
+#pragma unroll
+    for (int ps = 0; ps < MAXP; ++ps) {
+      if (ps < n_pass) {
+        float x[EPL];
+        Elem<T>::unpack(kv[ps], x);
+        float s = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) s = fmaf(x[e], qreg[e], s);
+        for (int o = LPR >> 1; o >= 1; o >>= 1) s += __shfl_xor(s, o);
+        const int i = ps * RPP + rsub;
+        if (seg == 0 && i < cnt) a_s[i] = s * g.score_scale + 0.0f;
+      }
+    }
+    __syncthreads();
+    // batch max -> rescale the running sums -> weights
+    float mb = tid < cnt ? a_s[tid] : -INFINITY;
+    if (tid < 64) {
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) mb = fmaxf(mb, __shfl_xor(mb, o));
+      if (tid == 0) a_w[0] = mb;                      // broadcast slot, overwritten below
+    }
+    __syncthreads();
+    const float m_new = fmaxf(m, a_w[0]);
+    const float r = __expf(m - m_new);                 // exp(-inf) = 0 on the first batch
+    __syncthreads();
+    if (tid < 64) a_w[tid] = tid < cnt ? __expf(a_s[tid] - m_new) : 0.f;
+    if (tid < d) a_acc[4 + tid] *= r;
+    m = m_new;
+    __syncthreads();
+    if (tid == 0) {
+      float Z = a_acc[1] * r;
+      for (int i = 0; i < cnt; ++i) Z += a_w[i];
+      a_acc[1] = Z;
+    }
+    weighted_value_sums<T>(g, pr, head_off, a_tok, a_w, a_w, cnt, red, a_acc, false);
   }
-  if (tid == 0) { part[0] = m; part[1] = Z; part[2] = 0.f; part[3] = (float)n_anchor; }
-  if (tid < d) { part[4 + tid] = nu; part[4 + d + tid] = 0.f; }
+  if (tid == 0) { part[0] = m; part[1] = a_acc[1]; part[2] = 0.f; part[3] = (float)n_anchor; }
+  if (tid < d) { part[4 + tid] = a_acc[4 + tid]; part[4 + d + tid] = 0.f; }
 }
 
 // ------------------------------------------------------------------------------------
@@ -87,7 +182,8 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
   __shared__ __attribute__((aligned(16))) char wk_lds[D * WROW];
   __shared__ int p_tok[kPairsPerWG];
   __shared__ float p_s[kPairsPerWG], p_w[kPairsPerWG], p_z[kPairsPerWG];
-  __shared__ float red[kThreads / D][2 * D];
+  __shared__ float red[2 * kThreads * 8];
+  __shared__ float acc_part[2 * D + 4];
   __shared__ float sh_m;
 
   const int tile = blockIdx.x, gq = blockIdx.y, p = blockIdx.z, tid = threadIdx.x;
@@ -96,7 +192,7 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
   const int n = mid_size(pr.L, g.n_sink, g.n_tail);
   char* blk = problem_block(g, ws, p);
   float* part = (float*)(blk + g.off_part) + ((size_t)gq * (g.n_tiles + 1) + tile) * g.part_stride;
-  if (tile == g.n_tiles) { anchor_partial<uint16_t>(g, pr, gq, n, part); return; }
+  if (tile == g.n_tiles) { anchor_partial<uint16_t>(g, pr, gq, n, part, red); return; }
   const int Ksel = ((const int32_t*)(blk + g.off_nsel))[gq];
   const int i0 = tile * kPairsPerWG;
   if (i0 >= Ksel) return;
@@ -110,13 +206,22 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
     p_tok[tid] = g.n_sink + ((const int32_t*)(blk + g.off_selidx))[(size_t)gq * g.max_K + i];
     p_s[tid] = tid < cnt ? ((const float*)(blk + g.off_selscore))[(size_t)gq * g.max_K + i] : -INFINITY;
   }
+  for (int i = tid; i < 2 * D + 4; i += kThreads) acc_part[i] = 0.f;
   // stage Wk[h] ([D features][D channels] bf16) with padded rows
   {
     const char* wsrc = (const char*)pr.Wk + (size_t)h * D * D * 2;
     constexpr int SEGS = D * 2 / 16;               // 16-byte segments per row
-    for (int i = tid; i < D * SEGS; i += kThreads) {
-      const int row = i / SEGS, seg = i % SEGS;
-      *(u32x4*)(wk_lds + row * WROW + seg * 16) = *(const u32x4*)(wsrc + (size_t)row * D * 2 + seg * 16);
+    constexpr int PER = D * SEGS / kThreads;
+    u32x4 t[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+      const int i = tid + k * kThreads;
+      t[k] = gload128(wsrc + (size_t)(i / SEGS) * D * 2 + (i % SEGS) * 16);
+    }
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+      const int i = tid + k * kThreads;
+      *(u32x4*)(wk_lds + (i / SEGS) * WROW + (i % SEGS) * 16) = t[k];
     }
   }
   __syncthreads();
@@ -134,13 +239,18 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
     const char* rp = (const char*)pr.K + (head_off + (int64_t)tok * pr.stride_tok) * 2 + kg * 16;
     Frag a[KS];
 #pragma unroll
-    for (int j = 0; j < KS; ++j) a[j].u = *(const u32x4*)(rp + j * 64);
+    for (int j = 0; j < KS; ++j) a[j].u = gload128(rp + j * 64);
+    const float* phiq = (const float*)(blk + g.off_phiq) + (size_t)gq * D;
+    const float* bk = pr.bk + (size_t)h * D;
+    float bj[NT], pj[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) { bj[nt] = bk[nt * 16 + r]; pj[nt] = phiq[nt * 16 + r]; }
     // |k|^2 of token r: this lane's 8*KS channels, then the 4 lanes of the row
     float nrm = 0.f;
 #pragma unroll
     for (int j = 0; j < KS; ++j) {
       float x[8];
-      Elem<uint16_t>::unpack(*(const uint4*)&a[j].u, x);
+      Elem<uint16_t>::unpack(make_uint4(a[j].u.x, a[j].u.y, a[j].u.z, a[j].u.w), x);
 #pragma unroll
       for (int e = 0; e < 8; ++e) nrm = fmaf(x[e], x[e], nrm);
     }
@@ -150,10 +260,8 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
 #pragma unroll
     for (int i = 0; i < 4; ++i) nr[i] = __shfl(nrm, 4 * kg + i);
 
-    const float* phiq = (const float*)(blk + g.off_phiq) + (size_t)gq * D;
-    const float* bk = pr.bk + (size_t)h * D;
     float zacc[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 2
+#pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
       floatx4 acc = (floatx4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -163,13 +271,12 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[j].v, b.v, acc, 0, 0, 0);
       }
       // acc[i] = Wk[feature nt*16 + r] . k(token 4kg + i)
-      const float bj = bk[nt * 16 + r], pj = phiq[nt * 16 + r];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float f = __expf(g.a * acc[i] - g.c * nr[i] + bj);
+        const float f = __expf(g.a * acc[i] - g.c * nr[i] + bj[nt]);
         uint32_t hi, lo;
         split_bf16(f, &hi, &lo);             // the 16 bits the summary build contracted
-        zacc[i] = fmaf(join_bf16(hi, lo), pj, zacc[i]);
+        zacc[i] = fmaf(join_bf16(hi, lo), pj[nt], zacc[i]);
       }
     }
 #pragma unroll
@@ -186,23 +293,8 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
   if (tid < kPairsPerWG) p_w[tid] = tid < cnt ? __expf(p_s[tid] - sh_m) : 0.f;
   __syncthreads();
 
-  // value accumulation: thread (c = tid % D, grp = tid / D) takes tokens grp, grp + NG, ...
-  constexpr int NG = kThreads / D;
-  const int c = tid % D, grp = tid / D;
-  float nu = 0.f, zv = 0.f;
-  for (int i = grp; i < cnt; i += NG) {
-    const float v = bf16_bits_to_float(((const uint16_t*)pr.V)[head_off + (int64_t)p_tok[i] * pr.stride_tok + c]);
-    nu = fmaf(p_w[i], v, nu);
-    zv = fmaf(p_z[i], v, zv);
-  }
-  red[grp][c] = nu; red[grp][D + c] = zv;
-  __syncthreads();
-  if (tid < D) {
-    float a0 = 0.f, a1 = 0.f;
-#pragma unroll
-    for (int k = 0; k < NG; ++k) { a0 += red[k][tid]; a1 += red[k][D + tid]; }
-    part[4 + tid] = a0; part[4 + D + tid] = a1;
-  }
+  weighted_value_sums<uint16_t>(g, pr, head_off, p_tok, p_w, p_z, cnt, red, acc_part, true);
+  if (tid < D) { part[4 + tid] = acc_part[4 + tid]; part[4 + D + tid] = acc_part[4 + D + tid]; }
   if (tid == 0) {
     float Z = 0.f, zs = 0.f;
     for (int i = 0; i < cnt; ++i) { Z += p_w[i]; zs += p_z[i]; }
@@ -219,13 +311,14 @@ __global__ __launch_bounds__(kThreads) void gather_kernel(Geom g, const tkphi_pr
                                                           char* __restrict__ ws) {
   __shared__ float kf[kMaxDim];
   __shared__ float red_f[4];
+  __shared__ float red[2 * kThreads * 8];
   const int tile = blockIdx.x, gq = blockIdx.y, p = blockIdx.z, tid = threadIdx.x;
   const tkphi_problem pr = probs[p];
   if (pr.L < 1 || pr.L > g.max_L) return;
   const int n = mid_size(pr.L, g.n_sink, g.n_tail);
   char* blk = problem_block(g, ws, p);
   float* part = (float*)(blk + g.off_part) + ((size_t)gq * (g.n_tiles + 1) + tile) * g.part_stride;
-  if (tile == g.n_tiles) { anchor_partial<T>(g, pr, gq, n, part); return; }
+  if (tile == g.n_tiles) { anchor_partial<T>(g, pr, gq, n, part, red); return; }
   const int Ksel = ((const int32_t*)(blk + g.off_nsel))[gq];
   const int i0 = tile * kPairsPerWG;
   if (i0 >= Ksel) return;
@@ -271,6 +364,8 @@ __global__ __launch_bounds__(kThreads) void gather_kernel(Geom g, const tkphi_pr
 __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_problem* __restrict__ probs,
                                                          char* __restrict__ ws, int mode) {
   __shared__ float red_f[4];
+  __shared__ float sh_phiq[kMaxDim], sh_u[kMaxDim];
+  __shared__ float sh_half[4][128];               // [thread group][value channel]
   const int gq = blockIdx.x, p = blockIdx.y, tid = threadIdx.x;
   const tkphi_problem pr = probs[p];
   if (pr.L < 1 || pr.L > g.max_L) return;
@@ -280,9 +375,15 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
   const int d = g.d, dphi = g.dphi;
   const int h = gq / g.G;
   char* blk = problem_block(g, ws, p);
-  const float* part0 = (const float*)(blk + g.off_part) + (size_t)gq * (g.n_tiles + 1) * g.part_stride;
-  const float* anchor = part0 + (size_t)g.n_tiles * g.part_stride;
+  const float* __restrict__ part0 = (const float*)(blk + g.off_part) + (size_t)gq * (g.n_tiles + 1) * g.part_stride;
+  const float* __restrict__ anchor = part0 + (size_t)g.n_tiles * g.part_stride;
+  const bool use_res = mode != TKPHI_MODE_TOPK_ONLY && n > 0 && !(mode == TKPHI_MODE_SUB && Ksel == n);
 
+  // stage phi_q and u while the partial headers are read
+  if (use_res) {
+    const float* phiq = (const float*)(blk + g.off_phiq) + (size_t)gq * dphi;
+    for (int j = tid; j < dphi; j += kThreads) { sh_phiq[j] = phiq[j]; sh_u[j] = pr.u[(size_t)h * dphi + j]; }
+  }
   // shift m = max over the exact support (anchor partial + tile partials)
   float ml = tid == 0 ? anchor[0] : -INFINITY;
   for (int t = tid; t < n_used; t += kThreads) ml = fmaxf(ml, part0[(size_t)t * g.part_stride]);
@@ -290,35 +391,64 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
   const bool empty_E = !(m > -INFINITY);
   if (empty_E) m = 0.f;
 
+  // combine the partials in a fixed order: anchors first, then the tiles in list order
   float nu = 0.f, zv = 0.f, Z = 0.f, zsum = 0.f;
   const int c = tid;
-  auto add_part = [&](const float* pp) {
-    const float mp = pp[0];
+  {
+    const float mp = anchor[0];
     if (mp > -INFINITY) {
       const float r = __expf(mp - m);
-      Z = fmaf(r, pp[1], Z);
-      if (c < d) nu = fmaf(r, pp[4 + c], nu);
+      Z = r * anchor[1];
+      if (c < d) nu = r * anchor[4 + c];
     }
-    zsum += pp[2];
-    if (c < d) zv += pp[4 + d + c];
-  };
-  add_part(anchor);                                    // anchors first, then the tiles in order
-  for (int t = 0; t < n_used; ++t) add_part(part0 + (size_t)t * g.part_stride);
+  }
+  constexpr int UN = 8;
+  for (int t0 = 0; t0 < n_used; t0 += UN) {
+    float hm[UN], hz[UN], hs[UN], vn[UN], vz[UN];
+#pragma unroll
+    for (int k = 0; k < UN; ++k) {
+      const float* pp = part0 + (size_t)min(t0 + k, n_used - 1) * g.part_stride;
+      hm[k] = pp[0]; hz[k] = pp[1]; hs[k] = pp[2];
+      vn[k] = c < d ? pp[4 + c] : 0.f;
+      vz[k] = c < d ? pp[4 + d + c] : 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < UN; ++k) {
+      if (t0 + k < n_used) {
+        const float r = __expf(hm[k] - m);
+        Z = fmaf(r, hz[k], Z);
+        nu = fmaf(r, vn[k], nu);
+        zsum += hs[k];
+        zv += vz[k];
+      }
+    }
+  }
 
   // residual branch from the summaries
   // (with every mid token retrieved in SUB mode the residual set is empty: exactly zero)
   float nuR = 0.f, ZR = 0.f;
   bool clamped = false;
-  if (mode != TKPHI_MODE_TOPK_ONLY && n > 0 && !(mode == TKPHI_MODE_SUB && Ksel == n)) {
-    const float* phiq = (const float*)(blk + g.off_phiq) + (size_t)gq * dphi;
-    const float* S = pr.S + (size_t)h * dphi * d;
-    const float* u = pr.u + (size_t)h * dphi;
-    float accn = 0.f, accz = 0.f;
-    for (int j = 0; j < dphi; ++j) {
-      const float pj = phiq[j];
-      accz = fmaf(pj, u[j], accz);
-      if (c < d) accn = fmaf(pj, S[(size_t)j * d + c], accn);
+  if (use_res) {
+    __syncthreads();
+    const float* __restrict__ S = pr.S + (size_t)h * dphi * d;
+    // threads split the feature range: half = tid / d handles features [half*dphi/NH, ...)
+    const int NH = kThreads / d;                    // 2 (d = 128) or 4 (d = 64)
+    const int half = tid / d, cc = tid % d;
+    const int j0 = half * (dphi / NH), j1 = (half == NH - 1) ? dphi : j0 + dphi / NH;
+    float pacc = 0.f;
+    for (int j = j0; j < j1; j += 8) {
+      float sv[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) sv[k] = (j + k < j1) ? S[(size_t)(j + k) * d + cc] : 0.f;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) if (j + k < j1) pacc = fmaf(sh_phiq[j + k], sv[k], pacc);
     }
+    sh_half[half][cc] = pacc;
+    float accz = 0.f;
+    for (int j = 0; j < dphi; ++j) accz = fmaf(sh_phiq[j], sh_u[j], accz);
+    __syncthreads();
+    float accn = 0.f;                               // fixed-order sum of the NH partial dot products
+    if (c < d) for (int k = 0; k < NH; ++k) accn += sh_half[k][c];
     if (mode == TKPHI_MODE_SUB) { accn -= zv; accz -= zsum; }
     nuR = accn; ZR = accz;
     if (!(ZR > 0.f)) {                     // numerical clamp: drop the residual branch
@@ -342,18 +472,18 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
 void launch_gather(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
   dim3 grid(g.n_tiles + 1, g.Hq, g.n_problems);
   if (g.use_mfma) {
-    if (g.d == 128) hipLaunchKernelGGL(gather_mfma_kernel<128>, grid, dim3(kThreads), 0, s, g, probs, ws);
-    else hipLaunchKernelGGL(gather_mfma_kernel<64>, grid, dim3(kThreads), 0, s, g, probs, ws);
+    if (g.d == 128) TKPHI_LAUNCH(gather_mfma_kernel<128>, grid, dim3(kThreads), 0, s, g, probs, ws);
+    else TKPHI_LAUNCH(gather_mfma_kernel<64>, grid, dim3(kThreads), 0, s, g, probs, ws);
   } else if (g.dtype == TKPHI_BF16) {
-    hipLaunchKernelGGL(gather_kernel<uint16_t>, grid, dim3(kThreads), 0, s, g, probs, ws);
+    TKPHI_LAUNCH(gather_kernel<uint16_t>, grid, dim3(kThreads), 0, s, g, probs, ws);
   } else {
-    hipLaunchKernelGGL(gather_kernel<float>, grid, dim3(kThreads), 0, s, g, probs, ws);
+    TKPHI_LAUNCH(gather_kernel<float>, grid, dim3(kThreads), 0, s, g, probs, ws);
   }
 }
 
 void launch_merge(const Geom& g, const tkphi_problem* probs, char* ws, int mode, hipStream_t s) {
   dim3 grid(g.Hq, g.n_problems);
-  hipLaunchKernelGGL(merge_kernel, grid, dim3(kThreads), 0, s, g, probs, ws, mode);
+  TKPHI_LAUNCH(merge_kernel, grid, dim3(kThreads), 0, s, g, probs, ws, mode);
 }
 
 }  // namespace tkphi

@@ -77,8 +77,9 @@ __global__ __launch_bounds__(kThreads) void score_mid_mfma_kernel(Geom g, const 
       const int row = min(base + t * 16 + r, c1 - 1);
       const char* rp = Kb + (size_t)row * row_bytes;
 #pragma unroll
-      for (int j = 0; j < KS; ++j) a[t][j].u = __builtin_nontemporal_load((const u32x4*)(rp + j * 64));
+      for (int j = 0; j < KS; ++j) a[t][j].u = (g.dbg & 4) ? gload128_stream(rp + j * 64) : gload128(rp + j * 64);
     }
+    __builtin_amdgcn_sched_barrier(0);   // all loads of the iteration are in flight before the first MFMA
     floatx4 acc[TPI];
 #pragma unroll
     for (int t = 0; t < TPI; ++t) {
@@ -100,9 +101,9 @@ __global__ __launch_bounds__(kThreads) void score_mid_mfma_kernel(Geom g, const 
         const int tok = base + tt;
         if (tok < c1) {
           const float s = strip[gl * TOK + tt] * scale + 0.0f;   // + 0.0f: -0 -> +0, equal scores get equal keys
-          scores[(size_t)gl * g.mid_stride + tok] = s;
+          if (!(g.dbg & 2)) scores[(size_t)gl * g.mid_stride + tok] = s;
           if (pr.scores) pr.scores[(size_t)(h * G + gl) * n + tok] = s;
-          atomicAdd(&lds_hist[gl * kBins + key_bin(score_key(s))], 1u);
+          if (!(g.dbg & 1)) atomicAdd(&lds_hist[gl * kBins + key_bin(score_key(s))], 1u);
         }
       }
     }
@@ -193,16 +194,22 @@ void launch_score_mid(const Geom& g, const tkphi_problem* probs, char* ws, hipSt
   dim3 grid(g.n_scan_chunks, g.Hkv, g.n_problems);
   const size_t hist_lds = (size_t)g.G * kBins * sizeof(uint32_t);
   if (g.use_mfma) {
-    if (g.d == 128)
-      hipLaunchKernelGGL((score_mid_mfma_kernel<128, 4>), grid, dim3(kThreads), hist_lds + (size_t)4 * g.G * 64 * 4, s,
+    if (g.d == 128 && (g.dbg & 8))
+      TKPHI_LAUNCH((score_mid_mfma_kernel<128, 2>), grid, dim3(kThreads), hist_lds + (size_t)4 * g.G * 32 * 4, s,
+                         g, probs, ws);
+    else if (g.d == 128 && (g.dbg & 16))
+      TKPHI_LAUNCH((score_mid_mfma_kernel<128, 8>), grid, dim3(kThreads), hist_lds + (size_t)4 * g.G * 128 * 4, s,
+                         g, probs, ws);
+    else if (g.d == 128)
+      TKPHI_LAUNCH((score_mid_mfma_kernel<128, 4>), grid, dim3(kThreads), hist_lds + (size_t)4 * g.G * 64 * 4, s,
                          g, probs, ws);
     else
-      hipLaunchKernelGGL((score_mid_mfma_kernel<64, 8>), grid, dim3(kThreads), hist_lds + (size_t)4 * g.G * 128 * 4, s,
+      TKPHI_LAUNCH((score_mid_mfma_kernel<64, 8>), grid, dim3(kThreads), hist_lds + (size_t)4 * g.G * 128 * 4, s,
                          g, probs, ws);
   } else if (g.dtype == TKPHI_BF16) {
-    hipLaunchKernelGGL(score_mid_kernel<uint16_t>, grid, dim3(kThreads), hist_lds, s, g, probs, ws);
+    TKPHI_LAUNCH(score_mid_kernel<uint16_t>, grid, dim3(kThreads), hist_lds, s, g, probs, ws);
   } else {
-    hipLaunchKernelGGL(score_mid_kernel<float>, grid, dim3(kThreads), hist_lds, s, g, probs, ws);
+    TKPHI_LAUNCH(score_mid_kernel<float>, grid, dim3(kThreads), hist_lds, s, g, probs, ws);
   }
 }
 

@@ -11,6 +11,7 @@
 namespace tkphi {
 
 static thread_local char g_last_error[512] = "";
+thread_local const KernelTimer* g_kernel_timer = nullptr;
 
 void set_error(const char* fmt, ...) {
   va_list ap;
@@ -194,21 +195,26 @@ tkphi_status tkphi_decode_stage_times(const tkphi_config* cfg, const tkphi_probl
   if (n_problems == 0) return TKPHI_OK;
   hipStream_t s = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
-  hipEvent_t ev[TKPHI_N_STAGES + 1];
+  // one (start, stop) event pair per stage, recorded at the kernel's own begin and end
+  hipEvent_t ev[2 * TKPHI_N_STAGES];
   int made = 0;
-  for (; made <= TKPHI_N_STAGES; ++made)
+  for (; made < 2 * TKPHI_N_STAGES; ++made)
     if ((st = hip_ok(hipEventCreate(&ev[made]), "hipEventCreate")) != TKPHI_OK) break;
   if (st == TKPHI_OK) {
+    KernelTimer t[TKPHI_N_STAGES];
+    for (int i = 0; i < TKPHI_N_STAGES; ++i) t[i] = KernelTimer{ev[2 * i], ev[2 * i + 1]};
     (void)hipGetLastError();
-    (void)hipEventRecord(ev[0], s);
-    launch_score_mid(g, problems, ws, s);   (void)hipEventRecord(ev[1], s);
-    launch_select(g, problems, ws, s);      (void)hipEventRecord(ev[2], s);
-    launch_gather(g, problems, ws, s);      (void)hipEventRecord(ev[3], s);
-    launch_merge(g, problems, ws, mode, s); (void)hipEventRecord(ev[4], s);
+    g_kernel_timer = &t[0]; launch_score_mid(g, problems, ws, s);
+    g_kernel_timer = &t[1]; launch_select(g, problems, ws, s);
+    g_kernel_timer = &t[2]; launch_gather(g, problems, ws, s);
+    g_kernel_timer = &t[3]; launch_merge(g, problems, ws, mode, s);
+    g_kernel_timer = nullptr;
     st = hip_ok(hipGetLastError(), "tkphi_decode_stage_times launch");
-    if (st == TKPHI_OK) st = hip_ok(hipEventSynchronize(ev[TKPHI_N_STAGES]), "hipEventSynchronize");
-    for (int i = 0; st == TKPHI_OK && i < TKPHI_N_STAGES; ++i)
-      st = hip_ok(hipEventElapsedTime(&stage_ms_out[i], ev[i], ev[i + 1]), "hipEventElapsedTime");
+    if (st == TKPHI_OK) st = hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize");
+    for (int i = 0; st == TKPHI_OK && i < TKPHI_N_STAGES; ++i) {
+      if (i == 0 && g.max_mid == 0) continue;           // score_mid is not launched without a mid-region
+      st = hip_ok(hipEventElapsedTime(&stage_ms_out[i], t[i].start, t[i].stop), "hipEventElapsedTime");
+    }
   }
   for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
   return st;

@@ -1,6 +1,7 @@
 // Internal definitions shared by the host layer and the HIP kernels of libtkphi.
 #pragma once
 
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -57,6 +58,21 @@ struct Geom {
 tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int max_K, Geom* g);
 void set_error(const char* fmt, ...);
 
+// Optional per-kernel timing: while g_kernel_timer is set (by tkphi_decode_stage_times, on
+// the calling thread) a launch records the kernel's own begin / end on the two events.
+struct KernelTimer {
+  hipEvent_t start, stop;
+};
+extern thread_local const KernelTimer* g_kernel_timer;
+#define TKPHI_LAUNCH(kernel, grid, block, lds, stream, ...)                                              \
+  do {                                                                                                   \
+    if (tkphi::g_kernel_timer)                                                                           \
+      hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, tkphi::g_kernel_timer->start,              \
+                            tkphi::g_kernel_timer->stop, 0, __VA_ARGS__);                                \
+    else                                                                                                 \
+      hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);                                 \
+  } while (0)
+
 // kernel launchers (each defined next to its kernels)
 void launch_score_mid(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
 void launch_score_mid_mfma(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
@@ -109,6 +125,14 @@ __device__ __forceinline__ void split_bf16(float f, uint32_t* hi, uint32_t* lo) 
 __device__ __forceinline__ float join_bf16(uint32_t hi, uint32_t lo) {
   return bf16_bits_to_float((uint16_t)hi) + bf16_bits_to_float((uint16_t)lo);
 }
+
+// 16-byte loads from global memory.  Pointers that come out of the problem table are
+// generic to the compiler; casting to the global address space gives global_load
+// instead of flat_load instructions.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef const __attribute__((address_space(1))) u32x4* gptr128;
+__device__ __forceinline__ u32x4 gload128(const void* p) { return *(gptr128)p; }
+__device__ __forceinline__ u32x4 gload128_stream(const void* p) { return __builtin_nontemporal_load((gptr128)p); }
 
 template <typename T> struct Elem;
 template <> struct Elem<float> {

@@ -117,15 +117,23 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Geom g, const tkphi
     float* phiq = (float*)(blk + g.off_phiq) + (size_t)gq * g.dphi;
     for (int c = tid; c < g.d; c += kSelThreads) qf[c] = Elem<T>::load1(pr.q, (int64_t)gq * g.d + c);
     __syncthreads();
-    if (tid < g.dphi) {
-      float dot = 0.f, nrm = 0.f;
-      const int64_t wbase = ((int64_t)gq * g.dphi + tid) * g.d;
-      for (int c = 0; c < g.d; ++c) {
-        const float x = qf[c];
-        dot = fmaf(Elem<T>::load1(pr.Wq, wbase + c), x, dot);
-        nrm = fmaf(x, x, nrm);
+    // LPR lanes per Wq row, one 16-byte load each (all rows of a pass in flight together)
+    constexpr int EPL = Elem<T>::per16;
+    const int LPR = g.d / EPL, seg = tid % LPR, rows_pp = kSelThreads / LPR;
+    float nrm = 0.f;
+    for (int c = 0; c < g.d; ++c) nrm = fmaf(qf[c], qf[c], nrm);
+    for (int j0 = 0; j0 < g.dphi; j0 += rows_pp) {
+      const int j = j0 + tid / LPR;
+      float dot = 0.f;
+      if (j < g.dphi) {
+        const u32x4 t = gload128((const char*)pr.Wq + (((int64_t)gq * g.dphi + j) * g.d + seg * EPL) * sizeof(T));
+        float x[EPL];
+        Elem<T>::unpack(make_uint4(t.x, t.y, t.z, t.w), x);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) dot = fmaf(x[e], qf[seg * EPL + e], dot);
       }
-      phiq[tid] = expf(g.a * dot - g.c * nrm + pr.bq[(int64_t)gq * g.dphi + tid]);
+      for (int o = LPR >> 1; o >= 1; o >>= 1) dot += __shfl_xor(dot, o);
+      if (j < g.dphi && seg == 0) phiq[j] = expf(g.a * dot - g.c * nrm + pr.bq[(int64_t)gq * g.dphi + j]);
     }
   }
   if (Ksel == 0) return;
@@ -139,13 +147,29 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Geom g, const tkphi
 
   // ---- 1. total histogram, boundary bin ---------------------------------------------------
   {
-    const int b = tid & (kBins - 1), half = tid >> 9;      // 2 threads per bin: even / odd chunks
-    uint32_t t = 0;
-    for (int c = half; c < n_chunks; c += 2) t += hist[(size_t)c * hstep + b];
-    if (half == 1) sh_tot[b] = t;
-    __syncthreads();
-    if (half == 0) sh_tot[b] += t;
+    // lane owns bins 8*lane .. 8*lane+7 (one 16-byte load per chunk), wavefront wv takes chunks
+    // wv, wv + 16, ...; the 16 wavefront sums are combined with LDS atomics
+    if (tid < kBins) sh_tot[tid] = 0u;
     if (tid == 0) { sh_bstar = -1; sh_krem = 0; sh_chi = 0; }
+    __syncthreads();
+    uint32_t t[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+    constexpr int UH = 4;
+    for (int c0 = wv; c0 < n_chunks; c0 += kSelWaves * UH) {
+      u32x4 v[UH];
+#pragma unroll
+      for (int k = 0; k < UH; ++k) {
+        const int c = c0 + k * kSelWaves;
+        v[k] = (u32x4){0u, 0u, 0u, 0u};
+        if (c < n_chunks) v[k] = gload128((const char*)(hist + (size_t)c * hstep) + lane * 16);
+      }
+#pragma unroll
+      for (int k = 0; k < UH; ++k) {
+        t[0] += v[k].x & 0xffffu; t[1] += v[k].x >> 16; t[2] += v[k].y & 0xffffu; t[3] += v[k].y >> 16;
+        t[4] += v[k].z & 0xffffu; t[5] += v[k].z >> 16; t[6] += v[k].w & 0xffffu; t[7] += v[k].w >> 16;
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) if (t[e]) atomicAdd(&sh_tot[lane * 8 + e], t[e]);
     __syncthreads();
     // thread t < kBins looks at bin kBins-1-t: prefix over t == suffix over bins
     const int bin = kBins - 1 - tid;
@@ -168,14 +192,30 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Geom g, const tkphi
   const int cpw = (n_chunks + kSelWaves - 1) / kSelWaves;
   const int ch0 = min(wv * cpw, n_chunks), ch1 = min(ch0 + cpw, n_chunks);
   {
+    // lane owns bins 8*lane .. 8*lane+7 of each chunk histogram (one 16-byte load per chunk)
     int above = 0, cand = 0;
-    for (int c = ch0; c < ch1; ++c) {
-      const uint16_t* hc = hist + (size_t)c * hstep;
-      for (int b = bstar + 1 + lane; b < kBins; b += 64) above += hc[b];
-      if (lane == 0) cand += hc[bstar];
+    constexpr int UC = 4;
+    for (int c0 = ch0; c0 < ch1; c0 += UC) {
+      u32x4 v[UC];
+#pragma unroll
+      for (int k = 0; k < UC; ++k) {
+        v[k] = (u32x4){0u, 0u, 0u, 0u};
+        if (c0 + k < ch1) v[k] = gload128((const char*)(hist + (size_t)(c0 + k) * hstep) + lane * 16);
+      }
+#pragma unroll
+      for (int k = 0; k < UC; ++k) {
+        const uint32_t cnt8[8] = {v[k].x & 0xffffu, v[k].x >> 16, v[k].y & 0xffffu, v[k].y >> 16,
+                                  v[k].z & 0xffffu, v[k].z >> 16, v[k].w & 0xffffu, v[k].w >> 16};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int b = lane * 8 + e;
+          above += b > bstar ? (int)cnt8[e] : 0;
+          cand += b == bstar ? (int)cnt8[e] : 0;
+        }
+      }
     }
 #pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) above += __shfl_xor(above, o);
+    for (int o = 32; o >= 1; o >>= 1) { above += __shfl_xor(above, o); cand += __shfl_xor(cand, o); }
     if (lane == 0) { sh_wabove[wv] = above; sh_wcand[wv] = cand; }
   }
   __syncthreads();
@@ -234,8 +274,21 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Geom g, const tkphi
 
   // ---- 4. resolve the boundary bin ---------------------------------------------------------------
   if (in_lds) {
-    auto get = [&](int j, uint64_t* v) { const uint2 e = sh_cand[j]; *v = composite(e.x, e.y); return true; };
-    const uint64_t thr = radix_select_desc(nb, krem, get, sh_hist, sh_scan, &sh_prefix, &sh_want);
+    uint64_t thr;
+    if (nb <= kSelThreads) {
+      // few candidates: rank each one by counting the larger ones (LDS broadcast reads, no barriers)
+      if (tid < nb) {
+        const uint64_t mine = composite(sh_cand[tid].x, sh_cand[tid].y);
+        int rank = 0;
+        for (int i = 0; i < nb; ++i) rank += composite(sh_cand[i].x, sh_cand[i].y) > mine ? 1 : 0;
+        if (rank == krem - 1) sh_prefix = mine;
+      }
+      __syncthreads();
+      thr = sh_prefix;
+    } else {
+      auto get = [&](int j, uint64_t* v) { const uint2 e = sh_cand[j]; *v = composite(e.x, e.y); return true; };
+      thr = radix_select_desc(nb, krem, get, sh_hist, sh_scan, &sh_prefix, &sh_want);
+    }
     // ordered append of the winners: thread t owns candidates [t*R, (t+1)*R)
     const int R = (nb + kSelThreads - 1) / kSelThreads;
     int cnt = 0;
@@ -296,9 +349,9 @@ void launch_select(const Geom& g, const tkphi_problem* probs, char* ws, hipStrea
   dim3 grid(g.Hq, g.n_problems);
   const size_t lds = (size_t)kCandCap * sizeof(uint2);
   if (g.dtype == TKPHI_BF16)
-    hipLaunchKernelGGL(select_kernel<uint16_t>, grid, dim3(kSelThreads), lds, s, g, probs, ws);
+    TKPHI_LAUNCH(select_kernel<uint16_t>, grid, dim3(kSelThreads), lds, s, g, probs, ws);
   else
-    hipLaunchKernelGGL(select_kernel<float>, grid, dim3(kSelThreads), lds, s, g, probs, ws);
+    TKPHI_LAUNCH(select_kernel<float>, grid, dim3(kSelThreads), lds, s, g, probs, ws);
 }
 
 }  // namespace tkphi
