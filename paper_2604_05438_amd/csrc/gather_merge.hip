@@ -88,17 +88,22 @@ __device__ __forceinline__ void weighted_value_sums(const Geom& g, const tkphi_p
 }
 
 // ---- anchors: exact terms over [0, n_sink) u [L - n_tail, L) (or every token if M is empty) --------
-// Batches of 64 anchors: scores with LPR lanes per key row (16-byte loads, butterfly sum),
-// running max / rescaling across batches in a fixed order.
+// One workgroup per batch of 64 anchors (`batch` = 0, 1, ...): scores with LPR lanes per key
+// row (16-byte loads, butterfly sum), then the same weighted value sums as a retrieved tile.
 template <typename T>
-__device__ void anchor_partial(const Geom& g, const tkphi_problem& pr, int gq, int n, float* part, float* red) {
+__device__ void anchor_partial(const Geom& g, const tkphi_problem& pr, int gq, int n, int batch, float* part,
+                               float* red) {
   constexpr int EPL = Elem<T>::per16;
   __shared__ int a_tok[64];
   __shared__ float a_s[64], a_w[64];
-  __shared__ float a_acc[2 * kMaxDim + 4];           // running [m, Z, -, -, nu[d], zv[d]] in the partial's layout
+  __shared__ float a_acc[2 * kMaxDim + 4];           // [-, -, -, -, nu[d], zv[d]] in the partial's layout
+  __shared__ float a_m;
   const int tid = threadIdx.x, d = g.d;
   const int h = gq / g.G;
   const int n_anchor = n > 0 ? g.n_sink + g.n_tail : pr.L;
+  const int base = batch * 64;
+  if (base >= n_anchor) return;
+  const int cnt = min(64, n_anchor - base);
   const int64_t head_off = (int64_t)h * pr.stride_head;
   const int LPR = d / EPL, RPP = kThreads / LPR;
   const int seg = tid % LPR, rsub = tid / LPR;
@@ -106,69 +111,56 @@ __device__ void anchor_partial(const Geom& g, const tkphi_problem& pr, int gq, i
 #pragma unroll
   for (int e = 0; e < EPL; ++e) qreg[e] = Elem<T>::load1(pr.q, (int64_t)gq * d + seg * EPL + e);
   for (int i = tid; i < 2 * d + 4; i += kThreads) a_acc[i] = 0.f;
-  float m = -INFINITY;
-  __syncthreads();
-  for (int base = 0; base < n_anchor; base += 64) {
-    const int cnt = min(64, n_anchor - base);
-    if (tid < 64) {
-      const int a = base + min(tid, cnt - 1);
-      a_tok[tid] = (n > 0 && a >= g.n_sink) ? (pr.L - g.n_tail + (a - g.n_sink)) : a;
-    }
-    __syncthreads();
-    // scores of the batch
-    constexpr int MAXP = 8;
-    const int n_pass = (cnt + RPP - 1) / RPP;
-    uint4 kv[MAXP];
-#pragma unroll
-    for (int ps = 0; ps < MAXP; ++ps) {
-      if (ps < n_pass) {
-        const int i = min(ps * RPP + rsub, cnt - 1);
-        const u32x4 t = gload128((const char*)pr.K + (head_off + (int64_t)a_tok[i] * pr.stride_tok + seg * EPL) * sizeof(T));
-        kv[ps] = make_uint4(t.x, t.y, t.z, t.w);
-      }
-    }
-#pragma unroll
-    for (int ps = 0; ps < MAXP; ++ps) {
-      if (ps < n_pass) {
-        float x[EPL];
-        Elem<T>::unpack(kv[ps], x);
-        float s = 0.f;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) s = fmaf(x[e], qreg[e], s);
-        for (int o = LPR >> 1; o >= 1; o >>= 1) s += __shfl_xor(s, o);
-        const int i = ps * RPP + rsub;
-        if (seg == 0 && i < cnt) a_s[i] = s * g.score_scale + 0.0f;
-      }
-    }
-    __syncthreads();
-    // batch max -> rescale the running sums -> weights
-    float mb = tid < cnt ? a_s[tid] : -INFINITY;
-    if (tid < 64) {
-#pragma unroll
-      for (int o = 32; o >= 1; o >>= 1) mb = fmaxf(mb, __shfl_xor(mb, o));
-      if (tid == 0) a_w[0] = mb;                      // broadcast slot, overwritten below
-    }
-    __syncthreads();
-    const float m_new = fmaxf(m, a_w[0]);
-    const float r = __expf(m - m_new);                 // exp(-inf) = 0 on the first batch
-    __syncthreads();
-    if (tid < 64) a_w[tid] = tid < cnt ? __expf(a_s[tid] - m_new) : 0.f;
-    if (tid < d) a_acc[4 + tid] *= r;
-    m = m_new;
-    __syncthreads();
-    if (tid == 0) {
-      float Z = a_acc[1] * r;
-      for (int i = 0; i < cnt; ++i) Z += a_w[i];
-      a_acc[1] = Z;
-    }
-    weighted_value_sums<T>(g, pr, head_off, a_tok, a_w, a_w, cnt, red, a_acc, false);
+  if (tid < 64) {
+    const int a = base + min(tid, cnt - 1);
+    a_tok[tid] = (n > 0 && a >= g.n_sink) ? (pr.L - g.n_tail + (a - g.n_sink)) : a;
   }
-  if (tid == 0) { part[0] = m; part[1] = a_acc[1]; part[2] = 0.f; part[3] = (float)n_anchor; }
+  __syncthreads();
+  // scores of the batch
+  constexpr int MAXP = 8;
+  const int n_pass = (cnt + RPP - 1) / RPP;
+  uint4 kv[MAXP];
+#pragma unroll
+  for (int ps = 0; ps < MAXP; ++ps) {
+    if (ps < n_pass) {
+      const int i = min(ps * RPP + rsub, cnt - 1);
+      const u32x4 t = gload128((const char*)pr.K + (head_off + (int64_t)a_tok[i] * pr.stride_tok + seg * EPL) * sizeof(T));
+      kv[ps] = make_uint4(t.x, t.y, t.z, t.w);
+    }
+  }
+#pragma unroll
+  for (int ps = 0; ps < MAXP; ++ps) {
+    if (ps < n_pass) {
+      float x[EPL];
+      Elem<T>::unpack(kv[ps], x);
+      float s = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) s = fmaf(x[e], qreg[e], s);
+      for (int o = LPR >> 1; o >= 1; o >>= 1) s += __shfl_xor(s, o);
+      const int i = ps * RPP + rsub;
+      if (seg == 0 && i < cnt) a_s[i] = s * g.score_scale + 0.0f;
+    }
+  }
+  __syncthreads();
+  if (tid < 64) {
+    float mb = tid < cnt ? a_s[tid] : -INFINITY;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) mb = fmaxf(mb, __shfl_xor(mb, o));
+    a_w[tid] = tid < cnt ? __expf(a_s[tid] - mb) : 0.f;
+    if (tid == 0) a_m = mb;
+  }
+  __syncthreads();
+  weighted_value_sums<T>(g, pr, head_off, a_tok, a_w, a_w, cnt, red, a_acc, false);
+  if (tid == 0) {
+    float Z = 0.f;
+    for (int i = 0; i < cnt; ++i) Z += a_w[i];
+    part[0] = a_m; part[1] = Z; part[2] = 0.f; part[3] = (float)cnt;
+  }
   if (tid < d) { part[4 + tid] = a_acc[4 + tid]; part[4 + d + tid] = 0.f; }
 }
 
 // ------------------------------------------------------------------------------------
-// gather, bf16 on the matrix cores: grid (n_tiles + 1, Hq, n_problems); D == d_head == d_phi.
+// gather, bf16 on the matrix cores: grid (n_tiles + n_atiles, Hq, n_problems); D == d_head == d_phi.
 // Wavefront w owns 16 retrieved tokens: their key rows are the A operand (lane (r, kg): token
 // r, 8 consecutive channels per k-step), Wk of the KV head is staged once per workgroup in
 // LDS (rows padded by 16 B: conflict-free ds_read_b128) and provides the B operand per
@@ -191,9 +183,9 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
   if (pr.L < 1 || pr.L > g.max_L) return;
   const int n = mid_size(pr.L, g.n_sink, g.n_tail);
   char* blk = problem_block(g, ws, p);
-  float* part = (float*)(blk + g.off_part) + ((size_t)gq * (g.n_tiles + 1) + tile) * g.part_stride;
-  if (tile == g.n_tiles) { anchor_partial<uint16_t>(g, pr, gq, n, part, red); return; }
-  const int Ksel = ((const int32_t*)(blk + g.off_nsel))[gq];
+  float* part = (float*)(blk + g.off_part) + ((size_t)gq * (g.n_tiles + g.n_atiles) + tile) * g.part_stride;
+  if (tile >= g.n_tiles) { anchor_partial<uint16_t>(g, pr, gq, n, tile - g.n_tiles, part, red); return; }
+  const int Ksel = ((const SelPlan*)(blk + g.off_plan))[gq].n_sel;
   const int i0 = tile * kPairsPerWG;
   if (i0 >= Ksel) return;
   const int cnt = min(kPairsPerWG, Ksel - i0);
@@ -317,9 +309,9 @@ __global__ __launch_bounds__(kThreads) void gather_kernel(Geom g, const tkphi_pr
   if (pr.L < 1 || pr.L > g.max_L) return;
   const int n = mid_size(pr.L, g.n_sink, g.n_tail);
   char* blk = problem_block(g, ws, p);
-  float* part = (float*)(blk + g.off_part) + ((size_t)gq * (g.n_tiles + 1) + tile) * g.part_stride;
-  if (tile == g.n_tiles) { anchor_partial<T>(g, pr, gq, n, part, red); return; }
-  const int Ksel = ((const int32_t*)(blk + g.off_nsel))[gq];
+  float* part = (float*)(blk + g.off_part) + ((size_t)gq * (g.n_tiles + g.n_atiles) + tile) * g.part_stride;
+  if (tile >= g.n_tiles) { anchor_partial<T>(g, pr, gq, n, tile - g.n_tiles, part, red); return; }
+  const int Ksel = ((const SelPlan*)(blk + g.off_plan))[gq].n_sel;
   const int i0 = tile * kPairsPerWG;
   if (i0 >= Ksel) return;
   const int cnt = min(kPairsPerWG, Ksel - i0);
@@ -365,56 +357,74 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
                                                          char* __restrict__ ws, int mode) {
   __shared__ float red_f[4];
   __shared__ float sh_phiq[kMaxDim], sh_u[kMaxDim];
-  __shared__ float sh_half[4][128];               // [thread group][value channel]
+  __shared__ float sh_grp[8][128];                 // [feature group][value channel]
   const int gq = blockIdx.x, p = blockIdx.y, tid = threadIdx.x;
   const tkphi_problem pr = probs[p];
   if (pr.L < 1 || pr.L > g.max_L) return;
   const int n = mid_size(pr.L, g.n_sink, g.n_tail);
   const int Ksel = max(0, min(min(pr.topk, n), g.max_K));
+  const int n_anchor = n > 0 ? g.n_sink + g.n_tail : pr.L;
   const int n_used = (Ksel + kPairsPerWG - 1) / kPairsPerWG;     // tiles holding retrieved tokens
+  const int na_used = (n_anchor + 63) / 64;                      // tiles holding anchors
   const int d = g.d, dphi = g.dphi;
   const int h = gq / g.G;
   char* blk = problem_block(g, ws, p);
-  const float* __restrict__ part0 = (const float*)(blk + g.off_part) + (size_t)gq * (g.n_tiles + 1) * g.part_stride;
-  const float* __restrict__ anchor = part0 + (size_t)g.n_tiles * g.part_stride;
+  const float* __restrict__ part0 = (const float*)(blk + g.off_part) + (size_t)gq * (g.n_tiles + g.n_atiles) * g.part_stride;
   const bool use_res = mode != TKPHI_MODE_TOPK_ONLY && n > 0 && !(mode == TKPHI_MODE_SUB && Ksel == n);
+  // partial k of this head, in combination order: anchor tiles first, then the retrieved tiles
+  const int n_parts = na_used + n_used;
+  auto part_ptr = [&](int k) { return part0 + (size_t)(k < na_used ? g.n_tiles + k : k - na_used) * g.part_stride; };
 
-  // stage phi_q and u while the partial headers are read
+  // ---- residual branch: S^T phi_q and u . phi_q, all loads of S issued together --------------
+  // thread (jg = tid / (d/4), c4 = tid % (d/4)) takes the features of group jg for 4 value channels
+  float4 sacc = make_float4(0.f, 0.f, 0.f, 0.f);
+  const int QPR = d / 4, NG = kThreads / QPR;      // float4 per row; feature groups (8 for d=128, 16 for d=64)
+  const int jg = tid / QPR, c4 = tid % QPR;
   if (use_res) {
     const float* phiq = (const float*)(blk + g.off_phiq) + (size_t)gq * dphi;
     for (int j = tid; j < dphi; j += kThreads) { sh_phiq[j] = phiq[j]; sh_u[j] = pr.u[(size_t)h * dphi + j]; }
+    const float* __restrict__ S = pr.S + (size_t)h * dphi * d;
+    const int per = (dphi + NG - 1) / NG;          // features per group (<= 32)
+    const int j0 = jg * per, j1 = min(dphi, j0 + per);
+    constexpr int MAXF = 32;
+    float4 sv[MAXF];
+#pragma unroll
+    for (int k = 0; k < MAXF; ++k)
+      if (j0 + k < j1) sv[k] = *(const float4*)(S + (size_t)(j0 + k) * d + c4 * 4);
+    __syncthreads();                               // phi_q staged
+#pragma unroll
+    for (int k = 0; k < MAXF; ++k) {
+      if (j0 + k < j1) {
+        const float pj = sh_phiq[j0 + k];
+        sacc.x = fmaf(pj, sv[k].x, sacc.x); sacc.y = fmaf(pj, sv[k].y, sacc.y);
+        sacc.z = fmaf(pj, sv[k].z, sacc.z); sacc.w = fmaf(pj, sv[k].w, sacc.w);
+      }
+    }
   }
-  // shift m = max over the exact support (anchor partial + tile partials)
-  float ml = tid == 0 ? anchor[0] : -INFINITY;
-  for (int t = tid; t < n_used; t += kThreads) ml = fmaxf(ml, part0[(size_t)t * g.part_stride]);
+
+  // ---- shift m = max over the exact support (all partial headers) ------------------------------
+  float ml = -INFINITY;
+  for (int k = tid; k < n_parts; k += kThreads) ml = fmaxf(ml, part_ptr(k)[0]);
   float m = block_max(ml, red_f);
   const bool empty_E = !(m > -INFINITY);
   if (empty_E) m = 0.f;
 
-  // combine the partials in a fixed order: anchors first, then the tiles in list order
+  // ---- combine the partials in a fixed order ---------------------------------------------------
   float nu = 0.f, zv = 0.f, Z = 0.f, zsum = 0.f;
   const int c = tid;
-  {
-    const float mp = anchor[0];
-    if (mp > -INFINITY) {
-      const float r = __expf(mp - m);
-      Z = r * anchor[1];
-      if (c < d) nu = r * anchor[4 + c];
-    }
-  }
   constexpr int UN = 8;
-  for (int t0 = 0; t0 < n_used; t0 += UN) {
+  for (int t0 = 0; t0 < n_parts; t0 += UN) {
     float hm[UN], hz[UN], hs[UN], vn[UN], vz[UN];
 #pragma unroll
     for (int k = 0; k < UN; ++k) {
-      const float* pp = part0 + (size_t)min(t0 + k, n_used - 1) * g.part_stride;
+      const float* pp = part_ptr(min(t0 + k, n_parts - 1));
       hm[k] = pp[0]; hz[k] = pp[1]; hs[k] = pp[2];
       vn[k] = c < d ? pp[4 + c] : 0.f;
       vz[k] = c < d ? pp[4 + d + c] : 0.f;
     }
 #pragma unroll
     for (int k = 0; k < UN; ++k) {
-      if (t0 + k < n_used) {
+      if (t0 + k < n_parts) {
         const float r = __expf(hm[k] - m);
         Z = fmaf(r, hz[k], Z);
         nu = fmaf(r, vn[k], nu);
@@ -424,31 +434,27 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
     }
   }
 
-  // residual branch from the summaries
   // (with every mid token retrieved in SUB mode the residual set is empty: exactly zero)
   float nuR = 0.f, ZR = 0.f;
   bool clamped = false;
   if (use_res) {
+    // fixed-order sum over the feature groups
+    float* row = &sh_grp[0][0];
+    if (jg < 8) { row[jg * 128 + c4 * 4 + 0] = sacc.x; row[jg * 128 + c4 * 4 + 1] = sacc.y;
+                  row[jg * 128 + c4 * 4 + 2] = sacc.z; row[jg * 128 + c4 * 4 + 3] = sacc.w; }
     __syncthreads();
-    const float* __restrict__ S = pr.S + (size_t)h * dphi * d;
-    // threads split the feature range: half = tid / d handles features [half*dphi/NH, ...)
-    const int NH = kThreads / d;                    // 2 (d = 128) or 4 (d = 64)
-    const int half = tid / d, cc = tid % d;
-    const int j0 = half * (dphi / NH), j1 = (half == NH - 1) ? dphi : j0 + dphi / NH;
-    float pacc = 0.f;
-    for (int j = j0; j < j1; j += 8) {
-      float sv[8];
-#pragma unroll
-      for (int k = 0; k < 8; ++k) sv[k] = (j + k < j1) ? S[(size_t)(j + k) * d + cc] : 0.f;
-#pragma unroll
-      for (int k = 0; k < 8; ++k) if (j + k < j1) pacc = fmaf(sh_phiq[j + k], sv[k], pacc);
+    if (jg >= 8) {                                 // d = 64: groups 8..15 add onto groups 0..7
+      row[(jg - 8) * 128 + 64 + c4 * 4 + 0] = sacc.x; row[(jg - 8) * 128 + 64 + c4 * 4 + 1] = sacc.y;
+      row[(jg - 8) * 128 + 64 + c4 * 4 + 2] = sacc.z; row[(jg - 8) * 128 + 64 + c4 * 4 + 3] = sacc.w;
     }
-    sh_half[half][cc] = pacc;
     float accz = 0.f;
     for (int j = 0; j < dphi; ++j) accz = fmaf(sh_phiq[j], sh_u[j], accz);
     __syncthreads();
-    float accn = 0.f;                               // fixed-order sum of the NH partial dot products
-    if (c < d) for (int k = 0; k < NH; ++k) accn += sh_half[k][c];
+    float accn = 0.f;
+    if (c < d) {
+      for (int k = 0; k < 8; ++k) accn += row[k * 128 + c];
+      if (NG == 16) for (int k = 0; k < 8; ++k) accn += row[k * 128 + 64 + c];
+    }
     if (mode == TKPHI_MODE_SUB) { accn -= zv; accz -= zsum; }
     nuR = accn; ZR = accz;
     if (!(ZR > 0.f)) {                     // numerical clamp: drop the residual branch
@@ -470,20 +476,20 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
 }
 
 void launch_gather(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
-  dim3 grid(g.n_tiles + 1, g.Hq, g.n_problems);
+  dim3 grid(g.n_tiles + g.n_atiles, g.Hq, g.n_problems);
   if (g.use_mfma) {
-    if (g.d == 128) TKPHI_LAUNCH(gather_mfma_kernel<128>, grid, dim3(kThreads), 0, s, g, probs, ws);
-    else TKPHI_LAUNCH(gather_mfma_kernel<64>, grid, dim3(kThreads), 0, s, g, probs, ws);
+    if (g.d == 128) TKPHI_LAUNCH(ST_GATHER, gather_mfma_kernel<128>, grid, dim3(kThreads), 0, s, g, probs, ws);
+    else TKPHI_LAUNCH(ST_GATHER, gather_mfma_kernel<64>, grid, dim3(kThreads), 0, s, g, probs, ws);
   } else if (g.dtype == TKPHI_BF16) {
-    TKPHI_LAUNCH(gather_kernel<uint16_t>, grid, dim3(kThreads), 0, s, g, probs, ws);
+    TKPHI_LAUNCH(ST_GATHER, gather_kernel<uint16_t>, grid, dim3(kThreads), 0, s, g, probs, ws);
   } else {
-    TKPHI_LAUNCH(gather_kernel<float>, grid, dim3(kThreads), 0, s, g, probs, ws);
+    TKPHI_LAUNCH(ST_GATHER, gather_kernel<float>, grid, dim3(kThreads), 0, s, g, probs, ws);
   }
 }
 
 void launch_merge(const Geom& g, const tkphi_problem* probs, char* ws, int mode, hipStream_t s) {
   dim3 grid(g.Hq, g.n_problems);
-  TKPHI_LAUNCH(merge_kernel, grid, dim3(kThreads), 0, s, g, probs, ws, mode);
+  TKPHI_LAUNCH(ST_MERGE, merge_kernel, grid, dim3(kThreads), 0, s, g, probs, ws, mode);
 }
 
 }  // namespace tkphi

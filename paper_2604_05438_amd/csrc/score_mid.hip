@@ -195,21 +195,21 @@ void launch_score_mid(const Geom& g, const tkphi_problem* probs, char* ws, hipSt
   const size_t hist_lds = (size_t)g.G * kBins * sizeof(uint32_t);
   if (g.use_mfma) {
     if (g.d == 128 && (g.dbg & 8))
-      TKPHI_LAUNCH((score_mid_mfma_kernel<128, 2>), grid, dim3(kThreads), hist_lds + (size_t)4 * g.G * 32 * 4, s,
+      TKPHI_LAUNCH(ST_SCORE, (score_mid_mfma_kernel<128, 2>), grid, dim3(kThreads), hist_lds + (size_t)4 * g.G * 32 * 4, s,
                          g, probs, ws);
     else if (g.d == 128 && (g.dbg & 16))
-      TKPHI_LAUNCH((score_mid_mfma_kernel<128, 8>), grid, dim3(kThreads), hist_lds + (size_t)4 * g.G * 128 * 4, s,
+      TKPHI_LAUNCH(ST_SCORE, (score_mid_mfma_kernel<128, 8>), grid, dim3(kThreads), hist_lds + (size_t)4 * g.G * 128 * 4, s,
                          g, probs, ws);
     else if (g.d == 128)
-      TKPHI_LAUNCH((score_mid_mfma_kernel<128, 4>), grid, dim3(kThreads), hist_lds + (size_t)4 * g.G * 64 * 4, s,
+      TKPHI_LAUNCH(ST_SCORE, (score_mid_mfma_kernel<128, 4>), grid, dim3(kThreads), hist_lds + (size_t)4 * g.G * 64 * 4, s,
                          g, probs, ws);
     else
-      TKPHI_LAUNCH((score_mid_mfma_kernel<64, 8>), grid, dim3(kThreads), hist_lds + (size_t)4 * g.G * 128 * 4, s,
+      TKPHI_LAUNCH(ST_SCORE, (score_mid_mfma_kernel<64, 8>), grid, dim3(kThreads), hist_lds + (size_t)4 * g.G * 128 * 4, s,
                          g, probs, ws);
   } else if (g.dtype == TKPHI_BF16) {
-    TKPHI_LAUNCH(score_mid_kernel<uint16_t>, grid, dim3(kThreads), hist_lds, s, g, probs, ws);
+    TKPHI_LAUNCH(ST_SCORE, score_mid_kernel<uint16_t>, grid, dim3(kThreads), hist_lds, s, g, probs, ws);
   } else {
-    TKPHI_LAUNCH(score_mid_kernel<float>, grid, dim3(kThreads), hist_lds, s, g, probs, ws);
+    TKPHI_LAUNCH(ST_SCORE, score_mid_kernel<float>, grid, dim3(kThreads), hist_lds, s, g, probs, ws);
   }
 }
 

@@ -331,17 +331,17 @@ void launch_build(const Geom& g, const tkphi_problem* probs, char* ws, hipStream
   if (g.max_mid > 0) {
     dim3 grid(g.n_build_chunks, g.Hkv, g.n_problems);
     if (g.use_mfma) {
-      if (g.d == 128) TKPHI_LAUNCH(build_mfma_kernel<128>, grid, dim3(kThreads), 0, s, g, probs, ws);
-      else TKPHI_LAUNCH(build_mfma_kernel<64>, grid, dim3(kThreads), 0, s, g, probs, ws);
+      if (g.d == 128) TKPHI_LAUNCH(ST_UNTIMED, build_mfma_kernel<128>, grid, dim3(kThreads), 0, s, g, probs, ws);
+      else TKPHI_LAUNCH(ST_UNTIMED, build_mfma_kernel<64>, grid, dim3(kThreads), 0, s, g, probs, ws);
     } else if (g.dtype == TKPHI_BF16) {
-      TKPHI_LAUNCH(build_kernel<uint16_t>, grid, dim3(kThreads), 0, s, g, probs, ws);
+      TKPHI_LAUNCH(ST_UNTIMED, build_kernel<uint16_t>, grid, dim3(kThreads), 0, s, g, probs, ws);
     } else {
-      TKPHI_LAUNCH(build_kernel<float>, grid, dim3(kThreads), 0, s, g, probs, ws);
+      TKPHI_LAUNCH(ST_UNTIMED, build_kernel<float>, grid, dim3(kThreads), 0, s, g, probs, ws);
     }
   }
   const int per = g.dphi * (g.d + 1);
   dim3 rgrid((per + kThreads - 1) / kThreads, g.Hkv, g.n_problems);
-  TKPHI_LAUNCH(build_reduce_kernel, rgrid, dim3(kThreads), 0, s, g, probs, ws);
+  TKPHI_LAUNCH(ST_UNTIMED, build_reduce_kernel, rgrid, dim3(kThreads), 0, s, g, probs, ws);
 }
 
 }  // namespace tkphi

@@ -11,7 +11,7 @@
 namespace tkphi {
 
 static thread_local char g_last_error[512] = "";
-thread_local const KernelTimer* g_kernel_timer = nullptr;
+thread_local KernelTimer* g_kernel_timer = nullptr;
 
 void set_error(const char* fmt, ...) {
   va_list ap;
@@ -72,13 +72,19 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   g->score_scale = cfg->score_scale; g->a = cfg->phi_in_scale; g->c = cfg->phi_norm_coef;
 
   const int64_t units = (int64_t)g->max_mid * g->Hkv * std::max(n_problems, 1);
-  // score_mid: about 2048 workgroups, 256..8192 tokens each (uint16 chunk histograms: < 65536)
-  int sc = (int)align_up((size_t)std::clamp<int64_t>(ceil_div(units, 2048), 256, 8192), 256);
+  // score_mid: about 1024 workgroups, 256..8192 tokens each (uint16 chunk histograms: < 65536)
+  int sc = (int)align_up((size_t)std::clamp<int64_t>(ceil_div(units, 1024), 256, 8192), 256);
   sc = env_int("TKPHI_SCAN_CHUNK", sc);
   g->scan_chunk = std::clamp(sc / 64 * 64, 64, 32768);
+  while (ceil_div(g->max_mid, g->scan_chunk) > kMaxScanChunks && g->scan_chunk < 32768) g->scan_chunk *= 2;
+  if (ceil_div(g->max_mid, g->scan_chunk) > kMaxScanChunks) {
+    set_error("max_L=%d too long: more than %d score chunks of 32768 tokens", max_L, kMaxScanChunks);
+    return TKPHI_ESHAPE;
+  }
   g->n_scan_chunks = (int)std::max<int64_t>(1, ceil_div(g->max_mid, g->scan_chunk));
   // gather: tiles of kPairsPerWG retrieved tokens per query head
   g->n_tiles = (int)ceil_div(std::min<int64_t>(max_K, g->max_mid), kPairsPerWG);
+  g->n_atiles = (int)std::max<int64_t>(1, ceil_div(std::min<int64_t>((int64_t)cfg->n_sink + cfg->n_tail, max_L), 64));
   // summary_build: about 512 workgroups
   int bc = (int)align_up((size_t)std::clamp<int64_t>(ceil_div(units, 512), 256, 1 << 20), 64);
   bc = env_int("TKPHI_BUILD_CHUNK", bc);
@@ -93,12 +99,14 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   size_t p = 0;
   g->off_scores = p;  p = align_up(p + (size_t)g->Hq * g->mid_stride * sizeof(float), 256);
   g->off_hist = p;    p = align_up(p + (size_t)g->n_scan_chunks * g->Hq * kBins * sizeof(uint16_t), 256);
-  g->off_nsel = p;    p = align_up(p + (size_t)g->Hq * sizeof(int32_t), 256);
+  g->off_plan = p;    p = align_up(p + (size_t)g->Hq * sizeof(SelPlan), 256);
+  g->off_chunkoff = p; p = align_up(p + (size_t)g->Hq * g->n_scan_chunks * 2 * sizeof(int32_t), 256);
+  g->off_cand = p;    p = align_up(p + (size_t)g->Hq * kCandCap * sizeof(uint2), 256);
   g->off_selidx = p;  p = align_up(p + (size_t)g->Hq * std::max(max_K, 1) * sizeof(int32_t), 256);
   g->off_selscore = p; p = align_up(p + (size_t)g->Hq * std::max(max_K, 1) * sizeof(float), 256);
   g->off_phiq = p;    p = align_up(p + (size_t)g->Hq * g->dphi * sizeof(float), 256);
   g->off_part = p;
-  p = align_up(p + (size_t)g->Hq * (g->n_tiles + 1) * g->part_stride * sizeof(float), 256);
+  p = align_up(p + (size_t)g->Hq * (g->n_tiles + g->n_atiles) * g->part_stride * sizeof(float), 256);
   g->per_problem = p;
   const size_t decode_total = g->off_problem0 + (size_t)std::max(n_problems, 1) * g->per_problem;
   g->off_bpart = g->off_problem0;
@@ -195,26 +203,26 @@ tkphi_status tkphi_decode_stage_times(const tkphi_config* cfg, const tkphi_probl
   if (n_problems == 0) return TKPHI_OK;
   hipStream_t s = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
-  // one (start, stop) event pair per stage, recorded at the kernel's own begin and end
-  hipEvent_t ev[2 * TKPHI_N_STAGES];
+  // one (start, stop) event pair per kernel, recorded at the kernel's own begin and end
+  static_assert(TKPHI_N_STAGES == ST_COUNT, "stage list out of sync with include/tkphi.h");
+  hipEvent_t ev[2 * ST_COUNT];
   int made = 0;
-  for (; made < 2 * TKPHI_N_STAGES; ++made)
+  for (; made < 2 * ST_COUNT; ++made)
     if ((st = hip_ok(hipEventCreate(&ev[made]), "hipEventCreate")) != TKPHI_OK) break;
   if (st == TKPHI_OK) {
-    KernelTimer t[TKPHI_N_STAGES];
-    for (int i = 0; i < TKPHI_N_STAGES; ++i) t[i] = KernelTimer{ev[2 * i], ev[2 * i + 1]};
+    KernelTimer t;
+    for (int i = 0; i < ST_COUNT; ++i) { t.start[i] = ev[2 * i]; t.stop[i] = ev[2 * i + 1]; t.used[i] = false; }
     (void)hipGetLastError();
-    g_kernel_timer = &t[0]; launch_score_mid(g, problems, ws, s);
-    g_kernel_timer = &t[1]; launch_select(g, problems, ws, s);
-    g_kernel_timer = &t[2]; launch_gather(g, problems, ws, s);
-    g_kernel_timer = &t[3]; launch_merge(g, problems, ws, mode, s);
+    g_kernel_timer = &t;
+    launch_score_mid(g, problems, ws, s);
+    launch_select(g, problems, ws, s);
+    launch_gather(g, problems, ws, s);
+    launch_merge(g, problems, ws, mode, s);
     g_kernel_timer = nullptr;
     st = hip_ok(hipGetLastError(), "tkphi_decode_stage_times launch");
     if (st == TKPHI_OK) st = hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize");
-    for (int i = 0; st == TKPHI_OK && i < TKPHI_N_STAGES; ++i) {
-      if (i == 0 && g.max_mid == 0) continue;           // score_mid is not launched without a mid-region
-      st = hip_ok(hipEventElapsedTime(&stage_ms_out[i], t[i].start, t[i].stop), "hipEventElapsedTime");
-    }
+    for (int i = 0; st == TKPHI_OK && i < ST_COUNT; ++i)
+      if (t.used[i]) st = hip_ok(hipEventElapsedTime(&stage_ms_out[i], t.start[i], t.stop[i]), "hipEventElapsedTime");
   }
   for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
   return st;

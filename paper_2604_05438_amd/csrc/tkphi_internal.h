@@ -35,6 +35,7 @@ struct Geom {
   int mid_stride;        // floats per score row (multiple of 64)
   int scan_chunk, n_scan_chunks;     // score_mid: mid tokens per workgroup
   int n_tiles;           // gather: ceil(max_K / kPairsPerWG) retrieved-token tiles per query head
+  int n_atiles;          // gather: ceil((n_sink + n_tail) / 64) anchor tiles per query head (>= 1)
   int build_chunk, n_build_chunks;   // summary_build: mid tokens per workgroup
   int part_stride;       // floats per partial: 2*d + 4
   float score_scale, a, c;
@@ -45,11 +46,13 @@ struct Geom {
   // offsets inside a per-problem block
   size_t off_scores;     // float    [Hq][mid_stride]            mid-region scores
   size_t off_hist;       // uint16   [n_scan_chunks][Hq][kBins]  per-chunk histograms
-  size_t off_nsel;       // int32    [Hq]                        retrieved tokens K' per head
+  size_t off_plan;       // SelPlan  [Hq]
+  size_t off_chunkoff;   // int32    [Hq][n_scan_chunks][2]      output offsets of each chunk (above b*, in b*)
+  size_t off_cand;       // uint2    [Hq][kCandCap]              boundary-bin candidates (key, mid index)
   size_t off_selidx;     // int32    [Hq][max_K]                 retrieved mid indices
   size_t off_selscore;   // float    [Hq][max_K]                 their scores
   size_t off_phiq;       // float    [Hq][dphi]
-  size_t off_part;       // float    [Hq][n_tiles + 1][part_stride]  (+1: the anchors)
+  size_t off_part;       // float    [Hq][n_tiles + n_atiles][part_stride]  (retrieved tiles, then anchor tiles)
   size_t off_bpart;      // float    [Hkv][n_build_chunks][dphi*(d+1)]   (build only; aliases the block)
   size_t total_bytes;
 };
@@ -60,18 +63,32 @@ void set_error(const char* fmt, ...);
 
 // Optional per-kernel timing: while g_kernel_timer is set (by tkphi_decode_stage_times, on
 // the calling thread) a launch records the kernel's own begin / end on the two events.
+enum Stage { ST_SCORE = 0, ST_PLAN, ST_EMIT, ST_RESOLVE, ST_GATHER, ST_MERGE, ST_COUNT, ST_UNTIMED = -1 };
 struct KernelTimer {
-  hipEvent_t start, stop;
+  hipEvent_t start[ST_COUNT], stop[ST_COUNT];
+  bool used[ST_COUNT];
 };
-extern thread_local const KernelTimer* g_kernel_timer;
-#define TKPHI_LAUNCH(kernel, grid, block, lds, stream, ...)                                              \
+extern thread_local KernelTimer* g_kernel_timer;
+#define TKPHI_LAUNCH(stage, kernel, grid, block, lds, stream, ...)                                       \
   do {                                                                                                   \
-    if (tkphi::g_kernel_timer)                                                                           \
-      hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, tkphi::g_kernel_timer->start,              \
-                            tkphi::g_kernel_timer->stop, 0, __VA_ARGS__);                                \
-    else                                                                                                 \
+    if (tkphi::g_kernel_timer && (stage) >= 0) {                                                         \
+      tkphi::g_kernel_timer->used[(stage)] = true;                                                       \
+      hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, tkphi::g_kernel_timer->start[(stage)],     \
+                            tkphi::g_kernel_timer->stop[(stage)], 0, __VA_ARGS__);                       \
+    } else {                                                                                             \
       hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);                                 \
+    }                                                                                                    \
   } while (0)
+
+// what `plan` hands to `emit` / `resolve` / gather for one query head
+struct SelPlan {
+  int32_t bstar;   // boundary bin, -1: nothing to retrieve
+  int32_t krem;    // tokens still to take from the boundary bin
+  int32_t c_hi;    // tokens in bins above the boundary bin
+  int32_t nb;      // tokens in the boundary bin
+  int32_t n_sel;   // retrieved tokens K' = min(topk, |M|, max_K)
+};
+constexpr int kMaxScanChunks = 2048;   // chunk offsets are scanned in LDS by `plan`
 
 // kernel launchers (each defined next to its kernels)
 void launch_score_mid(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
@@ -90,6 +107,10 @@ __device__ __forceinline__ uint32_t score_key(float s) {
   // order-preserving map float -> uint32 (larger score <=> larger key)
   uint32_t u = __float_as_uint(s);
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ float key_score(uint32_t key) {   // inverse of score_key
+  return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
 }
 
 __device__ __forceinline__ int key_bin(uint32_t key) {

@@ -1,21 +1,22 @@
-// topk_select: exhaustive Top-K over the mid-region scores of one query head
+// topk_select: exhaustive Top-K over the mid-region scores of every query head
 // (Sec. "Models, tasks, and protocol": the K highest-scoring mid-region tokens), plus the
 // query feature map phi_q (Sec. "Positive feature maps and summary states": phi_q is
 // evaluated per query head at decode time).
 //
-// One 1024-thread workgroup per (problem, query head) runs a two-level radix select:
-//   1. sum the per-chunk histograms written by score_mid -> boundary bin b*: the bin that
-//      holds the K-th largest score; every token in a higher bin is retrieved
-//   2. per chunk, count the tokens above b* (from the chunk histograms) so that each
-//      wavefront knows where its output starts: no atomics, the output order is fixed
-//   3. one ordered pass over the scores: tokens above b* go straight to the retrieved
-//      list, tokens in b* become candidates (in LDS)
-//   4. exact K_rem-th largest candidate by (score descending, index ascending) with an
-//      8-bit radix select in LDS; the winning candidates are appended to the list
+// A two-level radix select in three small kernels, with no atomics and a fixed output order:
+//   plan     one workgroup per query head: sums the per-chunk histograms written by
+//            score_mid -> boundary bin b* (the bin holding the K-th largest score; every token
+//            in a higher bin is retrieved); per chunk, the output offsets of its tokens above
+//            b* and of its tokens in b* (exclusive prefix sums of the chunk counts)
+//   emit     one wavefront per chunk, all heads in parallel: one ordered pass over the chunk's
+//            scores; tokens above b* go straight to the retrieved list, tokens in b* become
+//            candidates, both at the offsets computed by `plan`
+//   resolve  one workgroup per query head: exact K_rem-th largest candidate by (score
+//            descending, index ascending); the winners are appended to the list
 // The list holds (mid index, score): first the tokens above b* in ascending index order,
 // then the boundary-bin winners in ascending index order.  Ties go to the lower index.
-// If the boundary bin holds more than kCandCap tokens (e.g. all scores equal) steps 3-4
-// fall back to radix passes over the score row in global memory: slower, same result.
+// If the boundary bin holds more than kCandCap tokens (e.g. all scores equal) `resolve`
+// falls back to radix passes over the score row in global memory: slower, same result.
 #include "tkphi_internal.h"
 
 namespace tkphi {
@@ -77,18 +78,23 @@ __device__ uint64_t radix_select_desc(int count, int want, Get get, uint32_t* sh
   return *sh_prefix;
 }
 
-// grid (Hq, n_problems), 1024 threads; dynamic LDS: candidates uint2[kCandCap]
+// the 8 uint16 counts a lane holds after a 16-byte load of a chunk histogram row
+__device__ __forceinline__ void unpack_counts(const u32x4& v, uint32_t* c) {
+  c[0] = v.x & 0xffffu; c[1] = v.x >> 16; c[2] = v.y & 0xffffu; c[3] = v.y >> 16;
+  c[4] = v.z & 0xffffu; c[5] = v.z >> 16; c[6] = v.w & 0xffffu; c[7] = v.w >> 16;
+}
+
+// ------------------------------------------------------------------------------------
+// plan: grid (Hq, n_problems), 1024 threads
+// ------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(kSelThreads) void select_kernel(Geom g, const tkphi_problem* __restrict__ probs,
-                                                             char* __restrict__ ws) {
+__global__ __launch_bounds__(kSelThreads) void select_plan_kernel(Geom g, const tkphi_problem* __restrict__ probs,
+                                                                  char* __restrict__ ws) {
   __shared__ float qf[kMaxDim];
   __shared__ uint32_t sh_tot[kBins];
-  __shared__ uint32_t sh_hist[256];
   __shared__ int sh_scan[kSelWaves];
-  __shared__ int sh_wabove[kSelWaves], sh_wcand[kSelWaves];
-  __shared__ uint64_t sh_prefix;
-  __shared__ int sh_want, sh_bstar, sh_krem, sh_chi;
-  extern __shared__ uint2 sh_cand[];     // [kCandCap] (key, row), ascending row
+  __shared__ int sh_bstar, sh_krem, sh_chi;
+  __shared__ int sh_ca[kMaxScanChunks], sh_cc[kMaxScanChunks];
 
   const int gq = blockIdx.x, p = blockIdx.y, tid = threadIdx.x;
   const int lane = tid & 63, wv = tid >> 6;
@@ -109,8 +115,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Geom g, const tkphi
   if (pr.L < 1 || pr.L > g.max_L) return;
   const int n = mid_size(pr.L, g.n_sink, g.n_tail);
   const int Ksel = max(0, min(min(pr.topk, n), g.max_K));
-  int32_t* nsel = (int32_t*)(blk + g.off_nsel);
-  if (tid == 0) nsel[gq] = Ksel;
+  SelPlan* plan = (SelPlan*)(blk + g.off_plan) + gq;
 
   // ---- phi_q(q)[j] = exp(a Wq[j] . q - c |q|^2 + bq[j]) ---------------------------------
   {
@@ -136,24 +141,23 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Geom g, const tkphi
       if (j < g.dphi && seg == 0) phiq[j] = expf(g.a * dot - g.c * nrm + pr.bq[(int64_t)gq * g.dphi + j]);
     }
   }
-  if (Ksel == 0) return;
+  if (Ksel == 0) {
+    if (tid == 0) *plan = SelPlan{-1, 0, 0, 0, 0};
+    return;
+  }
 
   const int n_chunks = (n + g.scan_chunk - 1) / g.scan_chunk;
   const uint16_t* hist = (const uint16_t*)(blk + g.off_hist) + (size_t)gq * kBins;   // + chunk * Hq * kBins
   const size_t hstep = (size_t)g.Hq * kBins;
-  const float* scores = (const float*)(blk + g.off_scores) + (size_t)gq * g.mid_stride;
-  int32_t* sel_idx = (int32_t*)(blk + g.off_selidx) + (size_t)gq * g.max_K;
-  float* sel_score = (float*)(blk + g.off_selscore) + (size_t)gq * g.max_K;
 
-  // ---- 1. total histogram, boundary bin ---------------------------------------------------
+  // ---- total histogram: lane owns bins 8*lane .. 8*lane+7 (one 16-byte load per chunk),
+  // wavefront wv takes chunks wv, wv + 16, ...; the 16 wavefront sums meet in LDS ---------------
+  if (tid < kBins) sh_tot[tid] = 0u;
+  if (tid == 0) { sh_bstar = -1; sh_krem = 0; sh_chi = 0; }
+  __syncthreads();
   {
-    // lane owns bins 8*lane .. 8*lane+7 (one 16-byte load per chunk), wavefront wv takes chunks
-    // wv, wv + 16, ...; the 16 wavefront sums are combined with LDS atomics
-    if (tid < kBins) sh_tot[tid] = 0u;
-    if (tid == 0) { sh_bstar = -1; sh_krem = 0; sh_chi = 0; }
-    __syncthreads();
     uint32_t t[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
-    constexpr int UH = 4;
+    constexpr int UH = 8;                // row loads in flight per lane
     for (int c0 = wv; c0 < n_chunks; c0 += kSelWaves * UH) {
       u32x4 v[UH];
 #pragma unroll
@@ -164,13 +168,17 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Geom g, const tkphi
       }
 #pragma unroll
       for (int k = 0; k < UH; ++k) {
-        t[0] += v[k].x & 0xffffu; t[1] += v[k].x >> 16; t[2] += v[k].y & 0xffffu; t[3] += v[k].y >> 16;
-        t[4] += v[k].z & 0xffffu; t[5] += v[k].z >> 16; t[6] += v[k].w & 0xffffu; t[7] += v[k].w >> 16;
+        uint32_t c8[8];
+        unpack_counts(v[k], c8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t[e] += c8[e];
       }
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) if (t[e]) atomicAdd(&sh_tot[lane * 8 + e], t[e]);
-    __syncthreads();
+  }
+  __syncthreads();
+  {
     // thread t < kBins looks at bin kBins-1-t: prefix over t == suffix over bins
     const int bin = kBins - 1 - tid;
     const int c = tid < kBins ? (int)sh_tot[bin] : 0;
@@ -179,101 +187,166 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Geom g, const tkphi
     if (tid < kBins && excl < Ksel && Ksel <= incl) { sh_bstar = bin; sh_krem = Ksel - excl; sh_chi = excl; }
     __syncthreads();
   }
-  const int bstar = sh_bstar, krem = sh_krem, c_hi = sh_chi;
+  const int bstar = sh_bstar;
   if (bstar < 0) {                       // cannot happen for consistent histograms
-    if (tid == 0) nsel[gq] = 0;
+    if (tid == 0) *plan = SelPlan{-1, 0, 0, 0, 0};
     return;
   }
-  const int nb = (int)sh_tot[bstar];
-  const bool in_lds = nb <= kCandCap;
 
-  // ---- 2. where each wavefront's output starts ----------------------------------------------
-  // wavefront w owns chunks [w * cpw, (w+1) * cpw): a contiguous token range
-  const int cpw = (n_chunks + kSelWaves - 1) / kSelWaves;
-  const int ch0 = min(wv * cpw, n_chunks), ch1 = min(ch0 + cpw, n_chunks);
-  {
-    // lane owns bins 8*lane .. 8*lane+7 of each chunk histogram (one 16-byte load per chunk)
-    int above = 0, cand = 0;
-    constexpr int UC = 4;
-    for (int c0 = ch0; c0 < ch1; c0 += UC) {
-      u32x4 v[UC];
+  // ---- per chunk: tokens above b*, tokens in b* -> exclusive prefix sums = output offsets -------
+  constexpr int UC = 8;                  // row loads in flight per lane
+  for (int c0 = wv; c0 < n_chunks; c0 += kSelWaves * UC) {
+    u32x4 v[UC];
 #pragma unroll
-      for (int k = 0; k < UC; ++k) {
-        v[k] = (u32x4){0u, 0u, 0u, 0u};
-        if (c0 + k < ch1) v[k] = gload128((const char*)(hist + (size_t)(c0 + k) * hstep) + lane * 16);
-      }
-#pragma unroll
-      for (int k = 0; k < UC; ++k) {
-        const uint32_t cnt8[8] = {v[k].x & 0xffffu, v[k].x >> 16, v[k].y & 0xffffu, v[k].y >> 16,
-                                  v[k].z & 0xffffu, v[k].z >> 16, v[k].w & 0xffffu, v[k].w >> 16};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int b = lane * 8 + e;
-          above += b > bstar ? (int)cnt8[e] : 0;
-          cand += b == bstar ? (int)cnt8[e] : 0;
-        }
-      }
+    for (int k = 0; k < UC; ++k) {
+      const int c = c0 + k * kSelWaves;
+      v[k] = (u32x4){0u, 0u, 0u, 0u};
+      if (c < n_chunks) v[k] = gload128((const char*)(hist + (size_t)c * hstep) + lane * 16);
     }
 #pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) { above += __shfl_xor(above, o); cand += __shfl_xor(cand, o); }
-    if (lane == 0) { sh_wabove[wv] = above; sh_wcand[wv] = cand; }
-  }
-  __syncthreads();
-  int a_pos = 0, c_pos = 0;              // this wavefront's running output positions
-  for (int i = 0; i < wv; ++i) { a_pos += sh_wabove[i]; c_pos += sh_wcand[i]; }
-
-  // ---- 3. ordered pass: 4 consecutive tokens per lane, 256 per wavefront instruction ----------
-  {
-    const int t0 = ch0 * g.scan_chunk, t1 = min(n, ch1 * g.scan_chunk);
-    constexpr int U = 4;                 // loads in flight per lane
-    for (int base = t0; base < t1; base += 256 * U) {
-      float4 v[U];
+    for (int k = 0; k < UC; ++k) {
+      const int c = c0 + k * kSelWaves;
+      uint32_t c8[8];
+      unpack_counts(v[k], c8);
+      int above = 0, cand = 0;
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int tok = base + u * 256 + lane * 4;
-        v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (tok + 3 < t1) v[u] = *(const float4*)(scores + tok);     // rows are 16-byte aligned (mid_stride % 64 == 0)
-        else {
-          if (tok < t1) v[u].x = scores[tok];
-          if (tok + 1 < t1) v[u].y = scores[tok + 1];
-          if (tok + 2 < t1) v[u].z = scores[tok + 2];
-        }
+      for (int e = 0; e < 8; ++e) {
+        const int b = lane * 8 + e;
+        above += b > bstar ? (int)c8[e] : 0;
+        cand += b == bstar ? (int)c8[e] : 0;
       }
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int tok = base + u * 256 + lane * 4;
-        const float sv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-        int fa[4], fc[4], na = 0, nc = 0;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int b = (tok + e < t1) ? key_bin(score_key(sv[e])) : -1;
-          fa[e] = b > bstar ? 1 : 0;
-          fc[e] = b == bstar ? 1 : 0;
-          na += fa[e]; nc += fc[e];
-        }
-        // exclusive prefix over lanes of (na, nc) packed in one int (each <= 256)
-        int packed = na | (nc << 16), x = packed;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-          const int y = __shfl_up(x, o);
-          if (lane >= o) x += y;
-        }
-        const int total = __shfl(x, 63);
-        int pa = a_pos + ((x - packed) & 0xffff), pc = c_pos + ((x - packed) >> 16);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          if (fa[e]) { sel_idx[pa] = tok + e; sel_score[pa] = sv[e]; ++pa; }
-          if (fc[e]) { if (in_lds) sh_cand[pc] = make_uint2(score_key(sv[e]), (uint32_t)(tok + e)); ++pc; }
-        }
-        a_pos += total & 0xffff;
-        c_pos += total >> 16;
-      }
+      for (int o = 32; o >= 1; o >>= 1) { above += __shfl_xor(above, o); cand += __shfl_xor(cand, o); }
+      if (lane == 0 && c < n_chunks) { sh_ca[c] = above; sh_cc[c] = cand; }
     }
   }
   __syncthreads();
+  {
+    constexpr int PER = kMaxScanChunks / kSelThreads;      // 2 chunks per thread
+    int va[PER], vc[PER], ta = 0, tc = 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int c = tid * PER + i;
+      va[i] = c < n_chunks ? sh_ca[c] : 0;
+      vc[i] = c < n_chunks ? sh_cc[c] : 0;
+      ta += va[i]; tc += vc[i];
+    }
+    // both sums fit 2 x 20 bits? no: scan them separately (|M| can exceed 2^20)
+    const int ia = sel_scan_incl(ta, sh_scan);
+    const int ic = sel_scan_incl(tc, sh_scan);
+    int ra = ia - ta, rc = ic - tc;
+    int32_t* choff = (int32_t*)(blk + g.off_chunkoff) + (size_t)gq * g.n_scan_chunks * 2;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int c = tid * PER + i;
+      if (c < n_chunks) { choff[2 * c] = ra; choff[2 * c + 1] = rc; }
+      ra += va[i]; rc += vc[i];
+    }
+  }
+  if (tid == 0) *plan = SelPlan{bstar, sh_krem, sh_chi, (int)sh_tot[bstar], Ksel};
+}
 
-  // ---- 4. resolve the boundary bin ---------------------------------------------------------------
-  if (in_lds) {
+// ------------------------------------------------------------------------------------
+// emit: grid (ceil(n_scan_chunks / 4), Hq, n_problems), 256 threads; wavefront w <-> one chunk
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void select_emit_kernel(Geom g, const tkphi_problem* __restrict__ probs,
+                                                               char* __restrict__ ws) {
+  const int gq = blockIdx.y, p = blockIdx.z, tid = threadIdx.x;
+  const int lane = tid & 63, wv = tid >> 6;
+  const int L = probs[p].L;
+  if (L < 1 || L > g.max_L) return;
+  const int n = mid_size(L, g.n_sink, g.n_tail);
+  char* blk = problem_block(g, ws, p);
+  const SelPlan plan = ((const SelPlan*)(blk + g.off_plan))[gq];
+  const int bstar = plan.bstar;
+  if (bstar < 0) return;
+  const int chunk = blockIdx.x * 4 + wv;
+  const int t0 = chunk * g.scan_chunk;
+  if (t0 >= n) return;
+  const int t1 = min(n, t0 + g.scan_chunk);
+  const bool keep_cand = plan.nb <= kCandCap;
+  const float* scores = (const float*)(blk + g.off_scores) + (size_t)gq * g.mid_stride;
+  int32_t* sel_idx = (int32_t*)(blk + g.off_selidx) + (size_t)gq * g.max_K;
+  float* sel_score = (float*)(blk + g.off_selscore) + (size_t)gq * g.max_K;
+  uint2* cand = (uint2*)(blk + g.off_cand) + (size_t)gq * kCandCap;
+  const int32_t* choff = (const int32_t*)(blk + g.off_chunkoff) + ((size_t)gq * g.n_scan_chunks + chunk) * 2;
+  int a_pos = choff[0], c_pos = choff[1];
+
+  // 4 consecutive tokens per lane, 256 per wavefront instruction
+  constexpr int U = 2;                 // loads in flight per lane
+  for (int base = t0; base < t1; base += 256 * U) {
+    float4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int tok = base + u * 256 + lane * 4;
+      v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (tok + 3 < t1) v[u] = *(const float4*)(scores + tok);     // rows are 16-byte aligned (mid_stride % 64 == 0)
+      else {
+        if (tok < t1) v[u].x = scores[tok];
+        if (tok + 1 < t1) v[u].y = scores[tok + 1];
+        if (tok + 2 < t1) v[u].z = scores[tok + 2];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int tok = base + u * 256 + lane * 4;
+      const float sv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+      int fa[4], fc[4], na = 0, nc = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int b = (tok + e < t1) ? key_bin(score_key(sv[e])) : -1;
+        fa[e] = b > bstar ? 1 : 0;
+        fc[e] = b == bstar ? 1 : 0;
+        na += fa[e]; nc += fc[e];
+      }
+      // exclusive prefix over lanes of (na, nc) packed in one int (each <= 256)
+      const int packed = na | (nc << 16);
+      int x = packed;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int y = __shfl_up(x, o);
+        if (lane >= o) x += y;
+      }
+      const int total = __shfl(x, 63);
+      int pa = a_pos + ((x - packed) & 0xffff), pc = c_pos + ((x - packed) >> 16);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (fa[e]) { sel_idx[pa] = tok + e; sel_score[pa] = sv[e]; ++pa; }
+        if (fc[e]) { if (keep_cand) cand[pc] = make_uint2(score_key(sv[e]), (uint32_t)(tok + e)); ++pc; }
+      }
+      a_pos += total & 0xffff;
+      c_pos += total >> 16;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// resolve: grid (Hq, n_problems), 1024 threads; dynamic LDS: candidates uint2[kCandCap]
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kSelThreads) void select_resolve_kernel(Geom g, const tkphi_problem* __restrict__ probs,
+                                                                     char* __restrict__ ws) {
+  __shared__ uint32_t sh_hist[256];
+  __shared__ int sh_scan[kSelWaves];
+  __shared__ uint64_t sh_prefix;
+  __shared__ int sh_want;
+  extern __shared__ uint2 sh_cand[];     // [kCandCap] (key, row), ascending row
+
+  const int gq = blockIdx.x, p = blockIdx.y, tid = threadIdx.x;
+  const tkphi_problem pr = probs[p];
+  if (pr.L < 1 || pr.L > g.max_L) return;
+  const int n = mid_size(pr.L, g.n_sink, g.n_tail);
+  char* blk = problem_block(g, ws, p);
+  const SelPlan plan = ((const SelPlan*)(blk + g.off_plan))[gq];
+  const int bstar = plan.bstar, krem = plan.krem, c_hi = plan.c_hi, nb = plan.nb, Ksel = plan.n_sel;
+  if (bstar < 0 || Ksel == 0) return;
+  const float* scores = (const float*)(blk + g.off_scores) + (size_t)gq * g.mid_stride;
+  int32_t* sel_idx = (int32_t*)(blk + g.off_selidx) + (size_t)gq * g.max_K;
+  float* sel_score = (float*)(blk + g.off_selscore) + (size_t)gq * g.max_K;
+
+  if (nb <= kCandCap) {
+    const uint2* cand = (const uint2*)(blk + g.off_cand) + (size_t)gq * kCandCap;
+    for (int j = tid; j < nb; j += kSelThreads) sh_cand[j] = cand[j];
+    __syncthreads();
     uint64_t thr;
     if (nb <= kSelThreads) {
       // few candidates: rank each one by counting the larger ones (LDS broadcast reads, no barriers)
@@ -296,7 +369,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Geom g, const tkphi
     int pos = c_hi + sel_scan_incl(cnt, sh_scan) - cnt;
     for (int j = tid * R; j < min(nb, (tid + 1) * R); ++j) {
       const uint2 e = sh_cand[j];
-      if (composite(e.x, e.y) >= thr) { sel_idx[pos] = (int)e.y; sel_score[pos] = scores[e.y]; ++pos; }
+      if (composite(e.x, e.y) >= thr) { sel_idx[pos] = (int)e.y; sel_score[pos] = key_score(e.x); ++pos; }
     }
   } else {
     auto get = [&](int j, uint64_t* v) {
@@ -327,7 +400,6 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Geom g, const tkphi
   // ---- optional export: retrieved token indices, ascending ---------------------------------------
   if (pr.topk_idx) {
     __syncthreads();
-    __threadfence_block();
     int32_t* out = pr.topk_idx + (size_t)gq * g.max_K;
     // merge of the two ascending runs [0, c_hi) and [c_hi, Ksel) by rank
     for (int i = tid; i < Ksel; i += kSelThreads) {
@@ -346,12 +418,15 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Geom g, const tkphi
 }
 
 void launch_select(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
-  dim3 grid(g.Hq, g.n_problems);
-  const size_t lds = (size_t)kCandCap * sizeof(uint2);
+  dim3 hgrid(g.Hq, g.n_problems);
   if (g.dtype == TKPHI_BF16)
-    TKPHI_LAUNCH(select_kernel<uint16_t>, grid, dim3(kSelThreads), lds, s, g, probs, ws);
+    TKPHI_LAUNCH(ST_PLAN, select_plan_kernel<uint16_t>, hgrid, dim3(kSelThreads), 0, s, g, probs, ws);
   else
-    TKPHI_LAUNCH(select_kernel<float>, grid, dim3(kSelThreads), lds, s, g, probs, ws);
+    TKPHI_LAUNCH(ST_PLAN, select_plan_kernel<float>, hgrid, dim3(kSelThreads), 0, s, g, probs, ws);
+  if (g.max_mid == 0 || g.max_K == 0) return;
+  dim3 egrid((g.n_scan_chunks + 3) / 4, g.Hq, g.n_problems);
+  TKPHI_LAUNCH(ST_EMIT, select_emit_kernel, egrid, dim3(kThreads), 0, s, g, probs, ws);
+  TKPHI_LAUNCH(ST_RESOLVE, select_resolve_kernel, hgrid, dim3(kSelThreads), (size_t)kCandCap * sizeof(uint2), s, g, probs, ws);
 }
 
 }  // namespace tkphi
