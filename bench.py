@@ -24,6 +24,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+# HBM bytes per score_mid launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a
+# plain 256 MiB copy on the same counters), see profiles/decode_and_build_l3b_128k.md.
+# key: (workload, budget_bp) -> fetched + written bytes
+MEASURED_TRAFFIC = {("l3b_128k", 100): 269.10e6 + 15.72e6}
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
 
@@ -36,6 +40,9 @@ def main() -> int:
     ap.add_argument("--budget-bp", type=int, default=100)
     ap.add_argument("--rotate", type=int, default=4, help="distinct resident layers the steps rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain 256 MiB device copies (a known-size kernel to scale rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters with)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -132,7 +139,8 @@ def main() -> int:
         "stage_us": stage_us,
         "wall_ms_per_step": wall_ms / args.steps,
         "roofline": {"kernel": "score_mid", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC.get((w.name, args.budget_bp)),
                      "algorithmic_bytes_per_launch": bytes_scan},
         "build": {"ms_per_layer": build_ms, "algorithmic_bytes": build_bytes, "flops": build_flops,
                   "hbm_GBs": build_bytes / (build_ms * 1e-3) / 1e9,
@@ -152,32 +160,44 @@ def main() -> int:
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
         except Exception:
             cores = os.cpu_count() or 1
-        P = layers[0]
-        heads = list(range(min(w.n_q_heads, 2 * w.group)))      # the query heads of two KV heads
-        O = PU.oracle_inputs(P)
-        t0 = time.perf_counter()
-        S, u = orc.build_summaries(O["K"][: len(heads) // w.group], O["V"][: len(heads) // w.group],
-                                   O["Wk"], O["bk"], w.phi_in_scale, w.phi_norm_coef, w.n_sink, w.n_tail)
-        t_build = time.perf_counter() - t0
-        t0 = time.perf_counter()
-        res = orc.decode_layer(O["q"], O["K"], O["V"], S, u, O["Wq"], O["bq"], O["Wk"], O["bk"],
-                               w.phi_in_scale, w.phi_norm_coef, w.score_scale, w.n_sink, w.n_tail, K, heads=heads)
-        t_dec = time.perf_counter() - t0
-        frac = len(heads) / w.n_q_heads
-        y = batches[0].result(0, "out")
-        batches[0].decode()
-        torch.cuda.synchronize()
-        y = batches[0].result(0, "out")
-        worst = max(float(np.abs(y[g] - r["y"]).max()) for g, r in zip(heads, res))
+        # sample: whole layer-steps (every query head) of the first layers of the rotation
+        t_build = t_dec = 0.0
+        n_done = 0
+        worst = 0.0
+        for li, P in enumerate(layers):
+            O = PU.oracle_inputs(P)
+            t0 = time.perf_counter()
+            S, u = orc.build_summaries(O["K"], O["V"], O["Wk"], O["bk"], w.phi_in_scale, w.phi_norm_coef,
+                                       w.n_sink, w.n_tail)
+            t_build += time.perf_counter() - t0
+            t0 = time.perf_counter()
+            res = orc.decode_layer(O["q"], O["K"], O["V"], S, u, O["Wq"], O["bq"], O["Wk"], O["bk"],
+                                   w.phi_in_scale, w.phi_norm_coef, w.score_scale, w.n_sink, w.n_tail, K)
+            t_dec += time.perf_counter() - t0
+            n_done += 1
+            batches[li].decode()
+            torch.cuda.synchronize()
+            y = batches[li].result(0, "out")
+            worst = max([worst] + [float(np.abs(y[g] - r["y"]).max()) for g, r in enumerate(res)])
+            del O
+            if t_dec + t_build > 20.0:
+                break
         out["cpu_baseline"] = {
-            "value": n_mid * frac / t_dec, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"float64 numpy oracle, decode of {len(heads)} of {w.n_q_heads} query heads "
-                      f"({len(heads) // w.group} of {w.n_kv_heads} KV heads) of one layer-step of the same workload: "
-                      f"{t_dec:.2f} s (summary build of those KV heads: {t_build:.2f} s, not in value); "
-                      f"value = mid tokens x sampled fraction / decode seconds",
+            "value": n_done * n_mid / t_dec, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"float64 numpy oracle, {n_done} whole layer-step(s) (all {w.n_q_heads} query heads) of the same "
+                      f"workload: decode {t_dec:.2f} s (value = layers x mid tokens / decode seconds); the summary "
+                      f"build of those layers took {t_build:.2f} s and is not in value",
             "decode_s": t_dec, "build_s": t_build,
         }
         out["parity_max_abs_vs_oracle"] = worst
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        src.fill_(1)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["copy_calibration"] = {"bytes_read": 256 << 20, "bytes_written": 256 << 20, "copies": 4}
     print(json.dumps(out), flush=True)
     return 0
 
