@@ -171,10 +171,14 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
                                                                char* __restrict__ ws) {
   constexpr int KS = D / 32, NT = D / 16;
   constexpr int WROW = D * 2 + 16;                 // bytes per staged Wk row
-  __shared__ __attribute__((aligned(16))) char wk_lds[D * WROW];
+  // the staged Wk and the reduction scratch of the value sums are never live together
+  constexpr int kRedBytes = 2 * kThreads * 8 * (int)sizeof(float);
+  constexpr int kBufBytes = D * WROW > kRedBytes ? D * WROW : kRedBytes;
+  __shared__ __attribute__((aligned(16))) char lds_buf[kBufBytes];
+  char* wk_lds = lds_buf;
+  float* red = (float*)lds_buf;
   __shared__ int p_tok[kPairsPerWG];
   __shared__ float p_s[kPairsPerWG], p_w[kPairsPerWG], p_z[kPairsPerWG];
-  __shared__ float red[2 * kThreads * 8];
   __shared__ float acc_part[2 * D + 4];
   __shared__ float sh_m;
 
@@ -191,6 +195,7 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
   const int cnt = min(kPairsPerWG, Ksel - i0);
   const int h = gq / g.G;
   const int lane = tid & 63, wv = tid >> 6, r = lane & 15, kg = lane >> 4;
+  TKPHI_MARK(g, ws, 8);
 
   // the tile's retrieved tokens
   if (tid < kPairsPerWG) {
@@ -217,6 +222,7 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
     }
   }
   __syncthreads();
+  TKPHI_MARK(g, ws, 9);
   if (tid < 64) {                                  // m_loc = max score of the tile
     float m = p_s[tid];
 #pragma unroll
@@ -225,6 +231,7 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
   }
 
   const int64_t head_off = (int64_t)h * pr.stride_head;
+  TKPHI_MARK(g, ws, 10);
   if (wv * 16 < cnt) {
     // A operand: key rows of this wavefront's 16 tokens
     const int tok = p_tok[wv * 16 + r];
@@ -282,10 +289,12 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
     }
   }
   __syncthreads();
+  TKPHI_MARK(g, ws, 11);
   if (tid < kPairsPerWG) p_w[tid] = tid < cnt ? __expf(p_s[tid] - sh_m) : 0.f;
   __syncthreads();
 
   weighted_value_sums<uint16_t>(g, pr, head_off, p_tok, p_w, p_z, cnt, red, acc_part, true);
+  TKPHI_MARK(g, ws, 12);
   if (tid < D) { part[4 + tid] = acc_part[4 + tid]; part[4 + D + tid] = acc_part[4 + D + tid]; }
   if (tid == 0) {
     float Z = 0.f, zs = 0.f;

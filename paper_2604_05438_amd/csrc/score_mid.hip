@@ -1,7 +1,7 @@
 // score_mid: the streaming pass s_i = q . k_i / sqrt(d_h) over the mid-region
 // (eq. (full_attention) restricted to M of eq. (partition)).  Every key row of a KV head is
 // read once for all G query heads of its group.  Besides the scores, each workgroup writes
-// the first-level histogram of its chunk (per query head, uint16 counts) for the Top-K
+// the first-level histogram of its chunk (per query head, uint16 suffix counts) for the Top-K
 // radix select; nothing is accumulated with atomics in global memory.
 //
 // Two kernels: a matrix-core one for bf16 caches and a generic fp32-arithmetic one for any
@@ -9,6 +9,34 @@
 #include "tkphi_internal.h"
 
 namespace tkphi {
+
+// Chunk histogram write-out.  The row of a query head is stored as suffix sums,
+// row[b] = number of the chunk's tokens in bins >= b (uint16: a chunk has < 65536 tokens), so
+// that the select plan reads "tokens above bin b" with one load per chunk.  One wavefront per
+// head: lane l owns bins 8l .. 8l+7.
+__device__ __forceinline__ void write_suffix_hist(const uint32_t* lds_hist, uint16_t* out, int G) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  for (int gl = wv; gl < G; gl += kThreads / 64) {
+    const uint32_t* hrow = lds_hist + gl * kBins + lane * 8;
+    uint32_t s[8];
+    uint32_t run = 0;
+#pragma unroll
+    for (int e = 7; e >= 0; --e) { run += hrow[e]; s[e] = run; }     // suffix sums inside the lane
+    uint32_t x = run;                                                  // inclusive suffix over lanes
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t y = __shfl_down(x, o);
+      if (lane + o < 64) x += y;
+    }
+    const uint32_t above = x - run;                                    // tokens in the bins of higher lanes
+    u32x4 v;
+    v.x = (s[0] + above) | ((s[1] + above) << 16);
+    v.y = (s[2] + above) | ((s[3] + above) << 16);
+    v.z = (s[4] + above) | ((s[5] + above) << 16);
+    v.w = (s[6] + above) | ((s[7] + above) << 16);
+    *(u32x4*)(out + gl * kBins + lane * 8) = v;
+  }
+}
 
 // ------------------------------------------------------------------------------------
 // bf16 on the matrix cores.
@@ -110,8 +138,7 @@ __global__ __launch_bounds__(kThreads) void score_mid_mfma_kernel(Geom g, const 
     __builtin_amdgcn_wave_barrier();
   }
   __syncthreads();
-  uint16_t* hist = (uint16_t*)(blk + g.off_hist) + ((size_t)blockIdx.x * g.Hq + (size_t)h * G) * kBins;
-  for (int i = tid; i < G * kBins; i += kThreads) hist[i] = (uint16_t)lds_hist[i];
+  write_suffix_hist(lds_hist, (uint16_t*)(blk + g.off_hist) + ((size_t)blockIdx.x * g.Hq + (size_t)h * G) * kBins, G);
 }
 
 // ------------------------------------------------------------------------------------
@@ -185,8 +212,7 @@ __global__ __launch_bounds__(kThreads) void score_mid_kernel(Geom g, const tkphi
     }
   }
   __syncthreads();
-  uint16_t* hist = (uint16_t*)(blk + g.off_hist) + ((size_t)blockIdx.x * g.Hq + (size_t)h * G) * kBins;
-  for (int i = tid; i < G * kBins; i += kThreads) hist[i] = (uint16_t)lds_hist[i];
+  write_suffix_hist(lds_hist, (uint16_t*)(blk + g.off_hist) + ((size_t)blockIdx.x * g.Hq + (size_t)h * G) * kBins, G);
 }
 
 void launch_score_mid(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {

@@ -177,6 +177,13 @@ template <> struct Elem<uint16_t> {   // bf16 bits
   }
 };
 
+// debug timestamps (TKPHI_DBG bit 5): thread 0 of workgroup (0,0,0) stores the 100 MHz wall clock
+#define TKPHI_MARK(g, ws, k)                                                                              \
+  do {                                                                                                    \
+    if (((g).dbg & 32) && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0)      \
+      ((unsigned long long*)((ws) + 64))[(k)] = wall_clock64();                                           \
+  } while (0)
+
 // mid-region size of a problem; 0 if the anchors cover everything
 __device__ __forceinline__ int mid_size(int L, int n_sink, int n_tail) {
   const int n = L - n_sink - n_tail;

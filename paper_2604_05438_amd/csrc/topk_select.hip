@@ -4,8 +4,8 @@
 // evaluated per query head at decode time).
 //
 // A two-level radix select in three small kernels, with no atomics and a fixed output order:
-//   plan     one workgroup per query head: sums the per-chunk histograms written by
-//            score_mid -> boundary bin b* (the bin holding the K-th largest score; every token
+//   plan     one workgroup per query head: sums the per-chunk (suffix-count) histograms written
+//            by score_mid -> boundary bin b* (the bin holding the K-th largest score; every token
 //            in a higher bin is retrieved); per chunk, the output offsets of its tokens above
 //            b* and of its tokens in b* (exclusive prefix sums of the chunk counts)
 //   emit     one wavefront per chunk, all heads in parallel: one ordered pass over the chunk's
@@ -93,12 +93,13 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(Geom g, const 
   __shared__ float qf[kMaxDim];
   __shared__ uint32_t sh_tot[kBins];
   __shared__ int sh_scan[kSelWaves];
-  __shared__ int sh_bstar, sh_krem, sh_chi;
+  __shared__ int sh_bstar, sh_krem, sh_chi, sh_nb;
   __shared__ int sh_ca[kMaxScanChunks], sh_cc[kMaxScanChunks];
 
   const int gq = blockIdx.x, p = blockIdx.y, tid = threadIdx.x;
   const int lane = tid & 63, wv = tid >> 6;
   char* blk = problem_block(g, ws, p);
+  TKPHI_MARK(g, ws, 0);
 
   // device status word: recomputed from the problem lengths by one workgroup
   if (gq == 0 && p == 0) {
@@ -117,6 +118,7 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(Geom g, const 
   const int Ksel = max(0, min(min(pr.topk, n), g.max_K));
   SelPlan* plan = (SelPlan*)(blk + g.off_plan) + gq;
 
+  TKPHI_MARK(g, ws, 1);
   // ---- phi_q(q)[j] = exp(a Wq[j] . q - c |q|^2 + bq[j]) ---------------------------------
   {
     float* phiq = (float*)(blk + g.off_phiq) + (size_t)gq * g.dphi;
@@ -125,20 +127,21 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(Geom g, const 
     // LPR lanes per Wq row, one 16-byte load each (all rows of a pass in flight together)
     constexpr int EPL = Elem<T>::per16;
     const int LPR = g.d / EPL, seg = tid % LPR, rows_pp = kSelThreads / LPR;
-    float nrm = 0.f;
-    for (int c = 0; c < g.d; ++c) nrm = fmaf(qf[c], qf[c], nrm);
     for (int j0 = 0; j0 < g.dphi; j0 += rows_pp) {
-      const int j = j0 + tid / LPR;
-      float dot = 0.f;
-      if (j < g.dphi) {
-        const u32x4 t = gload128((const char*)pr.Wq + (((int64_t)gq * g.dphi + j) * g.d + seg * EPL) * sizeof(T));
-        float x[EPL];
-        Elem<T>::unpack(make_uint4(t.x, t.y, t.z, t.w), x);
+      const int j = min(j0 + tid / LPR, g.dphi - 1);          // clamped: every lane loads, extra rows are dropped
+      const u32x4 t = gload128((const char*)pr.Wq + (((int64_t)gq * g.dphi + j) * g.d + seg * EPL) * sizeof(T));
+      const float bj = pr.bq[(int64_t)gq * g.dphi + j];
+      float x[EPL];
+      Elem<T>::unpack(make_uint4(t.x, t.y, t.z, t.w), x);
+      float dot = 0.f, nrm = 0.f;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) dot = fmaf(x[e], qf[seg * EPL + e], dot);
+      for (int e = 0; e < EPL; ++e) {
+        const float qe = qf[seg * EPL + e];
+        dot = fmaf(x[e], qe, dot);
+        nrm = fmaf(qe, qe, nrm);
       }
-      for (int o = LPR >> 1; o >= 1; o >>= 1) dot += __shfl_xor(dot, o);
-      if (j < g.dphi && seg == 0) phiq[j] = expf(g.a * dot - g.c * nrm + pr.bq[(int64_t)gq * g.dphi + j]);
+      for (int o = LPR >> 1; o >= 1; o >>= 1) { dot += __shfl_xor(dot, o); nrm += __shfl_xor(nrm, o); }
+      if (j0 + tid / LPR < g.dphi && seg == 0) phiq[j] = expf(g.a * dot - g.c * nrm + bj);
     }
   }
   if (Ksel == 0) {
@@ -150,6 +153,7 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(Geom g, const 
   const uint16_t* hist = (const uint16_t*)(blk + g.off_hist) + (size_t)gq * kBins;   // + chunk * Hq * kBins
   const size_t hstep = (size_t)g.Hq * kBins;
 
+  TKPHI_MARK(g, ws, 2);
   // ---- total histogram: lane owns bins 8*lane .. 8*lane+7 (one 16-byte load per chunk),
   // wavefront wv takes chunks wv, wv + 16, ...; the 16 wavefront sums meet in LDS ---------------
   if (tid < kBins) sh_tot[tid] = 0u;
@@ -163,8 +167,9 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(Geom g, const 
 #pragma unroll
       for (int k = 0; k < UH; ++k) {
         const int c = c0 + k * kSelWaves;
-        v[k] = (u32x4){0u, 0u, 0u, 0u};
-        if (c < n_chunks) v[k] = gload128((const char*)(hist + (size_t)c * hstep) + lane * 16);
+        // unconditional load from a clamped row (a predicated load would be waited for on its own)
+        v[k] = gload128((const char*)(hist + (size_t)min(c, n_chunks - 1) * hstep) + lane * 16);
+        if (c >= n_chunks) v[k] = (u32x4){0u, 0u, 0u, 0u};
       }
 #pragma unroll
       for (int k = 0; k < UH; ++k) {
@@ -178,49 +183,31 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(Geom g, const 
     for (int e = 0; e < 8; ++e) if (t[e]) atomicAdd(&sh_tot[lane * 8 + e], t[e]);
   }
   __syncthreads();
-  {
-    // thread t < kBins looks at bin kBins-1-t: prefix over t == suffix over bins
-    const int bin = kBins - 1 - tid;
-    const int c = tid < kBins ? (int)sh_tot[bin] : 0;
-    const int incl = sel_scan_incl(c, sh_scan);
-    const int excl = incl - c;                              // tokens in bins above `bin`
-    if (tid < kBins && excl < Ksel && Ksel <= incl) { sh_bstar = bin; sh_krem = Ksel - excl; sh_chi = excl; }
-    __syncthreads();
+  TKPHI_MARK(g, ws, 3);
+  // the rows are suffix sums, so sh_tot[b] = tokens of this head in bins >= b: the boundary bin
+  // is the highest b with sh_tot[b] >= K
+  if (tid < kBins) {
+    const int ge = (int)sh_tot[tid];
+    const int gt = tid + 1 < kBins ? (int)sh_tot[tid + 1] : 0;
+    if (ge >= Ksel && gt < Ksel) { sh_bstar = tid; sh_krem = Ksel - gt; sh_chi = gt; sh_nb = ge - gt; }
   }
+  __syncthreads();
   const int bstar = sh_bstar;
   if (bstar < 0) {                       // cannot happen for consistent histograms
     if (tid == 0) *plan = SelPlan{-1, 0, 0, 0, 0};
     return;
   }
 
-  // ---- per chunk: tokens above b*, tokens in b* -> exclusive prefix sums = output offsets -------
-  constexpr int UC = 8;                  // row loads in flight per lane
-  for (int c0 = wv; c0 < n_chunks; c0 += kSelWaves * UC) {
-    u32x4 v[UC];
-#pragma unroll
-    for (int k = 0; k < UC; ++k) {
-      const int c = c0 + k * kSelWaves;
-      v[k] = (u32x4){0u, 0u, 0u, 0u};
-      if (c < n_chunks) v[k] = gload128((const char*)(hist + (size_t)c * hstep) + lane * 16);
-    }
-#pragma unroll
-    for (int k = 0; k < UC; ++k) {
-      const int c = c0 + k * kSelWaves;
-      uint32_t c8[8];
-      unpack_counts(v[k], c8);
-      int above = 0, cand = 0;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int b = lane * 8 + e;
-        above += b > bstar ? (int)c8[e] : 0;
-        cand += b == bstar ? (int)c8[e] : 0;
-      }
-#pragma unroll
-      for (int o = 32; o >= 1; o >>= 1) { above += __shfl_xor(above, o); cand += __shfl_xor(cand, o); }
-      if (lane == 0 && c < n_chunks) { sh_ca[c] = above; sh_cc[c] = cand; }
-    }
+  TKPHI_MARK(g, ws, 4);
+  // ---- per chunk: tokens above b*, tokens in b* (two suffix counts per chunk) ----------------------
+  for (int c = tid; c < n_chunks; c += kSelThreads) {
+    const uint16_t* row = hist + (size_t)c * hstep;
+    const int ge = row[bstar];
+    const int gt = bstar + 1 < kBins ? row[bstar + 1] : 0;
+    sh_ca[c] = gt; sh_cc[c] = ge - gt;
   }
   __syncthreads();
+  TKPHI_MARK(g, ws, 5);
   {
     constexpr int PER = kMaxScanChunks / kSelThreads;      // 2 chunks per thread
     int va[PER], vc[PER], ta = 0, tc = 0;
@@ -243,7 +230,8 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(Geom g, const 
       ra += va[i]; rc += vc[i];
     }
   }
-  if (tid == 0) *plan = SelPlan{bstar, sh_krem, sh_chi, (int)sh_tot[bstar], Ksel};
+  TKPHI_MARK(g, ws, 6);
+  if (tid == 0) *plan = SelPlan{bstar, sh_krem, sh_chi, sh_nb, Ksel};
 }
 
 // ------------------------------------------------------------------------------------
