@@ -243,7 +243,8 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
     const float* bk = pr.bk + (size_t)h * D;
     float bj[NT], pj[NT];
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) { bj[nt] = bk[nt * 16 + r]; pj[nt] = phiq[nt * 16 + r]; }
+    for (int nt = 0; nt < NT; ++nt) { bj[nt] = bk[nt * 16 + r] * kLog2e; pj[nt] = phiq[nt * 16 + r]; }
+    const float a2 = g.a * kLog2e, c2 = g.c * kLog2e;
     // |k|^2 of token r: this lane's 8*KS channels, then the 4 lanes of the row
     float nrm = 0.f;
 #pragma unroll
@@ -255,9 +256,9 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
     }
     nrm += __shfl_xor(nrm, 16);
     nrm += __shfl_xor(nrm, 32);
-    float nr[4];                                   // |k|^2 of tokens 4kg + i
+    float cn[4];                                   // c |k|^2 log2(e) of tokens 4kg + i
 #pragma unroll
-    for (int i = 0; i < 4; ++i) nr[i] = __shfl(nrm, 4 * kg + i);
+    for (int i = 0; i < 4; ++i) cn[i] = c2 * __shfl(nrm, 4 * kg + i);
 
     float zacc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -270,13 +271,16 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[j].v, b.v, acc, 0, 0, 0);
       }
       // acc[i] = Wk[feature nt*16 + r] . k(token 4kg + i)
+      float f[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float f = __expf(g.a * acc[i] - g.c * nr[i] + bj[nt]);
-        uint32_t hi, lo;
-        split_bf16(f, &hi, &lo);             // the 16 bits the summary build contracted
-        zacc[i] = fmaf(join_bf16(hi, lo), pj[nt], zacc[i]);
-      }
+      for (int i = 0; i < 4; ++i) f[i] = phi_exp2(acc[i], a2, bj[nt] - cn[i]);
+      uint32_t h01, l01, h23, l23;           // the 16 bits per feature that the summary build contracted
+      split_bf16_pair(f[0], f[1], &h01, &l01);
+      split_bf16_pair(f[2], f[3], &h23, &l23);
+      zacc[0] = fmaf(join_bf16_lo(h01, l01), pj[nt], zacc[0]);
+      zacc[1] = fmaf(join_bf16_hi(h01, l01), pj[nt], zacc[1]);
+      zacc[2] = fmaf(join_bf16_lo(h23, l23), pj[nt], zacc[2]);
+      zacc[3] = fmaf(join_bf16_hi(h23, l23), pj[nt], zacc[3]);
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {

@@ -25,28 +25,32 @@ union Frag {
 // ------------------------------------------------------------------------------------
 // bf16 on the matrix cores: grid (n_build_chunks, Hkv, n_problems); D == d_head == d_phi.
 //
-// Tiles of 64 tokens.  GEMM1 (features): wavefront w takes tokens [16w, 16w+16) of the tile;
-// the A operand is loaded straight from the key rows (lane (r, kg): token r, 8 consecutive
-// channels per k-step), the B operand (all of Wk) stays in registers for the whole chunk.
-// The exponentiated features are rounded to bf16 and written feature-major to LDS; the
-// value rows are transposed in registers (4 tokens x 8 channels per lane) and written
-// channel-major to LDS, so that both operands of GEMM2 (contraction over tokens) are plain
-// 16-byte LDS reads.  GEMM2: wavefront w owns value channels [w*D/4, (w+1)*D/4) of S for all
-// features, accumulated in registers over the chunk.  u is summed from the same rounded
-// features.  The next tile's global loads are issued before GEMM2 of the current tile.
+// Tiles of 64 tokens; the key and value tiles are staged in LDS once per workgroup (keys
+// row-major, values transposed in registers - 4 tokens x 8 channels per lane - and stored
+// channel-major), |k|^2 is reduced while staging.  Wavefront w owns the features
+// [w*D/4, (w+1)*D/4): its slice of Wk stays in registers for the whole chunk.
+//   GEMM1  P[64 tokens][own features] = K Wk^T : A = key rows from LDS, B = Wk slice
+//          -> exp -> bf16 hi + lo; the result registers (4 consecutive tokens per lane and
+//          16-token tile) are already the A operand of GEMM2 over a fixed permutation of
+//          the 32 tokens of a k-step, so the features never touch LDS
+//   GEMM2  S[own features][all channels] += Phi^T V : B = transposed value tile from LDS
+//          (two 8-byte reads per operand, same token permutation), hi and lo as two MFMAs
+// u is summed from the same features.  The next tile's global loads are issued as soon as the
+// current tile sits in LDS.
 // ------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(kThreads) void build_mfma_kernel(Geom g, const tkphi_problem* __restrict__ probs,
-                                                              char* __restrict__ ws) {
+__global__ __launch_bounds__(kThreads, 2) void build_mfma_kernel(Geom g, const tkphi_problem* __restrict__ probs,
+                                                                 char* __restrict__ ws) {
   constexpr int KS = D / 32;            // k-steps of GEMM1 (over channels)
-  constexpr int NT = D / 16;            // feature tiles
-  constexpr int CW = D / 64;            // channel tiles of S per wavefront
-  constexpr int TROW = 64 * 2 + 16;     // bytes per LDS row: 64 tokens of bf16 + pad
-  constexpr int PROW = 2 * 64 * 2 + 16; // feature row: 64 tokens hi, 64 tokens lo, pad
-  constexpr int VSEG = D / 8;           // 16-byte segments per value row
-  __shared__ __attribute__((aligned(16))) char phi_t[D * PROW];   // [feature][hi tokens | lo tokens]
+  constexpr int FT = D / 64;            // feature tiles per wavefront
+  constexpr int CT = D / 16;            // channel tiles of S
+  constexpr int SEGS = D / 8;           // 16-byte segments per row
+  constexpr int KLD = 64 * SEGS / kThreads;   // key-row loads per thread and tile (4 or 2)
+  constexpr int KROW = D * 2 + 16;      // bytes per staged key row
+  constexpr int TROW = 64 * 2 + 16;     // bytes per staged value-channel row (64 tokens)
+  __shared__ __attribute__((aligned(16))) char k_t[64 * KROW];    // [token][channel]
   __shared__ __attribute__((aligned(16))) char v_t[D * TROW];     // [channel][token]
-  __shared__ float u_red[4][D];
+  __shared__ __attribute__((aligned(16))) float nrm_t[64];        // c |k|^2 log2(e); +inf past the chunk end
 
   const int ch = blockIdx.x, h = blockIdx.y, p = blockIdx.z, tid = threadIdx.x;
   const tkphi_problem pr = probs[p];
@@ -56,94 +60,73 @@ __global__ __launch_bounds__(kThreads) void build_mfma_kernel(Geom g, const tkph
   if (c0 >= n) return;
   const int c1 = min(n, c0 + g.build_chunk);
   const int lane = tid & 63, wv = tid >> 6, r = lane & 15, kg = lane >> 4;
+  const float a2 = g.a * kLog2e, c2 = g.c * kLog2e;
 
-  // Wk fragments: wk[nt][j] = Wk[h][feature nt*16 + r][channels j*32 + kg*8 .. +8]
-  Frag wk[NT][KS];
+  // Wk slice: wk[ft][j] = Wk[h][feature wv*D/4 + ft*16 + r][channels j*32 + kg*8 .. +8]
+  Frag wk[FT][KS];
+  float bias[FT];
   {
     const uint16_t* wsrc = (const uint16_t*)pr.Wk + (size_t)h * D * D;
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
+    for (int ft = 0; ft < FT; ++ft) {
+      const int feat = wv * (D / 4) + ft * 16 + r;
 #pragma unroll
-      for (int j = 0; j < KS; ++j)
-        wk[nt][j].u = *(const u32x4*)(wsrc + (size_t)(nt * 16 + r) * D + j * 32 + kg * 8);
+      for (int j = 0; j < KS; ++j) wk[ft][j].u = gload128(wsrc + (size_t)feat * D + j * 32 + kg * 8);
+      bias[ft] = pr.bk[(size_t)h * D + feat] * kLog2e;
+    }
   }
-  float bias[NT];
+  floatx4 sacc[FT][CT];
 #pragma unroll
-  for (int nt = 0; nt < NT; ++nt) bias[nt] = pr.bk[(size_t)h * D + nt * 16 + r];
-
-  floatx4 sacc[NT][CW];
+  for (int ft = 0; ft < FT; ++ft)
 #pragma unroll
-  for (int mt = 0; mt < NT; ++mt)
+    for (int ct = 0; ct < CT; ++ct) sacc[ft][ct] = (floatx4){0.f, 0.f, 0.f, 0.f};
+  float uacc[FT];
 #pragma unroll
-    for (int ct = 0; ct < CW; ++ct) sacc[mt][ct] = (floatx4){0.f, 0.f, 0.f, 0.f};
-  float uacc[NT];
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) uacc[nt] = 0.f;
+  for (int ft = 0; ft < FT; ++ft) uacc[ft] = 0.f;
 
   const size_t row_bytes = (size_t)pr.stride_tok * 2;
   const size_t base_off = ((size_t)h * pr.stride_head + (size_t)g.n_sink * pr.stride_tok) * 2;
-  const char* Kb = (const char*)pr.K + base_off + (size_t)kg * 16;
+  // key loads: thread (krow = tid / SEGS, seg = tid % SEGS) takes rows krow + i * (256 / SEGS)
+  const int kseg = tid % SEGS, krow = tid / SEGS;
+  constexpr int KRP = kThreads / SEGS;  // key rows per pass
+  const char* Kb = (const char*)pr.K + base_off + (size_t)kseg * 16;
   // value loads: thread (tq, sg) takes tokens 4*tq .. 4*tq+3 of the tile, 16-byte segment sg
-  const bool v_active = tid < 16 * VSEG;
+  const bool v_active = tid < 16 * SEGS;
   const int tq = tid % 16, sg = tid / 16;
   const char* Vb = (const char*)pr.V + base_off + (size_t)sg * 16;
 
-  Frag ka[KS];
-  u32x4 vv[4];
+  u32x4 kk[KLD], vv[4];
   auto issue_loads = [&](int t0) {
-    const int row = min(t0 + wv * 16 + r, c1 - 1);
-    const char* rp = Kb + (size_t)row * row_bytes;
 #pragma unroll
-    for (int j = 0; j < KS; ++j) ka[j].u = __builtin_nontemporal_load((const u32x4*)(rp + j * 64));
+    for (int i = 0; i < KLD; ++i) {
+      const int row = min(t0 + krow + i * KRP, c1 - 1);
+      kk[i] = gload128_stream(Kb + (size_t)row * row_bytes);
+    }
     if (v_active) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int vrow = min(t0 + tq * 4 + i, c1 - 1);
-        vv[i] = __builtin_nontemporal_load((const u32x4*)(Vb + (size_t)vrow * row_bytes));
+        vv[i] = gload128_stream(Vb + (size_t)vrow * row_bytes);
       }
     }
   };
 
   issue_loads(c0);
   for (int t0 = c0; t0 < c1; t0 += 64) {
-    // ---- GEMM1 + exponent on this wavefront's 16 tokens -----------------------------------
-    float nrm = 0.f;
+    // ---- stage the tile: keys row-major (+ norms), values channel-major ---------------------
 #pragma unroll
-    for (int j = 0; j < KS; ++j) {
+    for (int i = 0; i < KLD; ++i) {
+      const int row = krow + i * KRP;
+      *(u32x4*)(k_t + row * KROW + kseg * 16) = kk[i];
       float x[8];
-      Elem<uint16_t>::unpack(*(const uint4*)&ka[j].u, x);
+      Elem<uint16_t>::unpack(make_uint4(kk[i].x, kk[i].y, kk[i].z, kk[i].w), x);
+      float s = 0.f;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) nrm = fmaf(x[e], x[e], nrm);
+      for (int e = 0; e < 8; ++e) s = fmaf(x[e], x[e], s);
+#pragma unroll
+      for (int o = SEGS / 2; o >= 1; o >>= 1) s += __shfl_xor(s, o);
+      if (kseg == 0) nrm_t[row] = (t0 + row < c1) ? c2 * s : INFINITY;
     }
-    nrm += __shfl_xor(nrm, 16);
-    nrm += __shfl_xor(nrm, 32);
-    float nr[4];
-    bool ok[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      nr[i] = __shfl(nrm, 4 * kg + i);
-      ok[i] = (t0 + wv * 16 + 4 * kg + i) < c1;
-    }
-    // 4 tokens (4kg .. 4kg+3) of feature nt*16 + r as bf16 pairs (hi, lo), hi + lo = 16 bits
-    u32x2 phi_hi[NT], phi_lo[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      floatx4 acc = (floatx4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int j = 0; j < KS; ++j) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[j].v, wk[nt][j].v, acc, 0, 0, 0);
-      uint32_t hi[4], lo[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float f = __expf(g.a * acc[i] - g.c * nr[i] + bias[nt]);
-        split_bf16(f, &hi[i], &lo[i]);
-        if (!ok[i]) { hi[i] = 0u; lo[i] = 0u; }
-        uacc[nt] += join_bf16(hi[i], lo[i]);
-      }
-      phi_hi[nt] = (u32x2){hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
-      phi_lo[nt] = (u32x2){lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
-    }
-    // ---- transpose the value block: 4 tokens x 8 channels -> 8 channels x 4 tokens ----------
-    u32x2 vt[8];
     if (v_active) {
       const bool vok[4] = {t0 + tq * 4 + 0 < c1, t0 + tq * 4 + 1 < c1, t0 + tq * 4 + 2 < c1, t0 + tq * 4 + 3 < c1};
       uint32_t w[4][4];
@@ -154,64 +137,83 @@ __global__ __launch_bounds__(kThreads) void build_mfma_kernel(Geom g, const tkph
       }
 #pragma unroll
       for (int q = 0; q < 4; ++q) {      // dword q of a token holds channels 2q (low half) and 2q+1 (high half)
-        vt[2 * q] = (u32x2){(w[0][q] & 0xffffu) | (w[1][q] << 16), (w[2][q] & 0xffffu) | (w[3][q] << 16)};
-        vt[2 * q + 1] = (u32x2){(w[0][q] >> 16) | (w[1][q] & 0xffff0000u), (w[2][q] >> 16) | (w[3][q] & 0xffff0000u)};
+        const u32x2 even = (u32x2){(w[0][q] & 0xffffu) | (w[1][q] << 16), (w[2][q] & 0xffffu) | (w[3][q] << 16)};
+        const u32x2 odd = (u32x2){(w[0][q] >> 16) | (w[1][q] & 0xffff0000u), (w[2][q] >> 16) | (w[3][q] & 0xffff0000u)};
+        *(u32x2*)(v_t + (sg * 8 + 2 * q) * TROW + tq * 8) = even;
+        *(u32x2*)(v_t + (sg * 8 + 2 * q + 1) * TROW + tq * 8) = odd;
       }
     }
-    // registers are free again: fetch the next tile while this one goes through LDS and GEMM2
-    if (t0 + 64 < c1) issue_loads(t0 + 64);
-
-    __syncthreads();                     // the previous tile's GEMM2 has finished reading LDS
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      *(u32x2*)(phi_t + (nt * 16 + r) * PROW + (wv * 16 + 4 * kg) * 2) = phi_hi[nt];
-      *(u32x2*)(phi_t + (nt * 16 + r) * PROW + 128 + (wv * 16 + 4 * kg) * 2) = phi_lo[nt];
-    }
-    if (v_active) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) *(u32x2*)(v_t + (sg * 8 + e) * TROW + tq * 8) = vt[e];
-    }
     __syncthreads();
+    if (t0 + 64 < c1) issue_loads(t0 + 64);        // the staging registers are free again
 
-    // ---- GEMM2: S[features][this wavefront's channels] += Phi^T V over the tile's 64 tokens ----
+    // ---- GEMM1 + exponent: all 64 tokens x this wavefront's features --------------------------
+    u32x2 phi_hi[4][FT], phi_lo[4][FT];            // [16-token tile][feature tile]: tokens 4kg .. 4kg+3
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+      Frag a[KS];
+#pragma unroll
+      for (int j = 0; j < KS; ++j) a[j].u = *(const u32x4*)(k_t + (mt * 16 + r) * KROW + j * 64 + kg * 16);
+      const floatx4 cn = *(const floatx4*)(nrm_t + mt * 16 + 4 * kg);
+#pragma unroll
+      for (int ft = 0; ft < FT; ++ft) {
+        floatx4 acc = (floatx4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < KS; ++j) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[j].v, wk[ft][j].v, acc, 0, 0, 0);
+        float f[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          f[i] = phi_exp2(acc[i], a2, bias[ft] - cn[i]);
+          uacc[ft] += f[i];
+        }
+        uint32_t h01, l01, h23, l23;
+        split_bf16_pair(f[0], f[1], &h01, &l01);
+        split_bf16_pair(f[2], f[3], &h23, &l23);
+        phi_hi[mt][ft] = (u32x2){h01, h23};
+        phi_lo[mt][ft] = (u32x2){l01, l23};
+      }
+    }
+
+    // ---- GEMM2: S[own features][all channels] += Phi^T V ------------------------------------------
+    // k-step ks contracts the 32 tokens of tiles 2ks and 2ks+1; lane (., kg) holds tokens
+    // 32ks + 4kg + {0..3} and 32ks + 16 + 4kg + {0..3} in both operands
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-      Frag vb[CW];
+      Frag ahi[FT], alo[FT];
 #pragma unroll
-      for (int ct = 0; ct < CW; ++ct)
-        vb[ct].u = *(const u32x4*)(v_t + (wv * (D / 4) + ct * 16 + r) * TROW + (ks * 32 + kg * 8) * 2);
+      for (int ft = 0; ft < FT; ++ft) {
+        ahi[ft].u = (u32x4){phi_hi[2 * ks][ft].x, phi_hi[2 * ks][ft].y, phi_hi[2 * ks + 1][ft].x, phi_hi[2 * ks + 1][ft].y};
+        alo[ft].u = (u32x4){phi_lo[2 * ks][ft].x, phi_lo[2 * ks][ft].y, phi_lo[2 * ks + 1][ft].x, phi_lo[2 * ks + 1][ft].y};
+      }
 #pragma unroll
-      for (int mt = 0; mt < NT; ++mt) {
-        Frag pa_hi, pa_lo;
-        pa_hi.u = *(const u32x4*)(phi_t + (mt * 16 + r) * PROW + (ks * 32 + kg * 8) * 2);
-        pa_lo.u = *(const u32x4*)(phi_t + (mt * 16 + r) * PROW + 128 + (ks * 32 + kg * 8) * 2);
+      for (int ct = 0; ct < CT; ++ct) {
+        const char* vp = v_t + (ct * 16 + r) * TROW + (32 * ks + 4 * kg) * 2;
+        const u32x2 b0 = *(const u32x2*)vp, b1 = *(const u32x2*)(vp + 32);
+        Frag vb;
+        vb.u = (u32x4){b0.x, b0.y, b1.x, b1.y};
 #pragma unroll
-        for (int ct = 0; ct < CW; ++ct) {
-          sacc[mt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_lo.v, vb[ct].v, sacc[mt][ct], 0, 0, 0);
-          sacc[mt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_hi.v, vb[ct].v, sacc[mt][ct], 0, 0, 0);
+        for (int ft = 0; ft < FT; ++ft) {
+          sacc[ft][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(alo[ft].v, vb.v, sacc[ft][ct], 0, 0, 0);
+          sacc[ft][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ahi[ft].v, vb.v, sacc[ft][ct], 0, 0, 0);
         }
       }
     }
+    __syncthreads();                     // everyone is done with this tile's LDS
   }
 
   // ---- write the chunk partial: S part [D][D] then u part [D] ----------------------------------
   float* bp = (float*)(ws + g.off_bpart) + ((size_t)(p * g.Hkv + h) * g.n_build_chunks + ch) * ((size_t)D * (D + 1));
 #pragma unroll
-  for (int mt = 0; mt < NT; ++mt)
+  for (int ft = 0; ft < FT; ++ft) {
 #pragma unroll
-    for (int ct = 0; ct < CW; ++ct)
+    for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        bp[(size_t)(mt * 16 + 4 * kg + i) * D + wv * (D / 4) + ct * 16 + r] = sacc[mt][ct][i];
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    float x = uacc[nt];
+        bp[(size_t)(wv * (D / 4) + ft * 16 + 4 * kg + i) * D + ct * 16 + r] = sacc[ft][ct][i];
+    float x = uacc[ft];
     x += __shfl_xor(x, 16);
     x += __shfl_xor(x, 32);
-    if (kg == 0) u_red[wv][nt * 16 + r] = x;
+    if (kg == 0) bp[(size_t)D * D + wv * (D / 4) + ft * 16 + r] = x;
   }
-  __syncthreads();
-  if (tid < D) bp[(size_t)D * D + tid] = (u_red[0][tid] + u_red[1][tid]) + (u_red[2][tid] + u_red[3][tid]);
 }
 
 // ------------------------------------------------------------------------------------

@@ -138,13 +138,29 @@ __device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
 // A feature value as the sum of two bf16 numbers, hi = bf16(f) and lo = bf16(f - hi): 16
 // significant bits, which is what the matrix-core summary build contracts against the
 // values and what the decode side subtracts for a retrieved token.
-__device__ __forceinline__ void split_bf16(float f, uint32_t* hi, uint32_t* lo) {
-  const uint16_t h = float_to_bf16_bits(f);
-  *hi = h;
-  *lo = float_to_bf16_bits(f - bf16_bits_to_float(h));
+// Two features at a time with the packed hardware conversion (v_cvt_pk_bf16_f32, round to
+// nearest even): *hi / *lo hold (f0, f1) in their (low, high) halves.
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+__device__ __forceinline__ void split_bf16_pair(float f0, float f1, uint32_t* hi, uint32_t* lo) {
+  const bf16x2_t h = {(__bf16)f0, (__bf16)f1};
+  const uint32_t hb = __builtin_bit_cast(uint32_t, h);
+  const bf16x2_t l = {(__bf16)(f0 - __uint_as_float(hb << 16)), (__bf16)(f1 - __uint_as_float(hb & 0xffff0000u))};
+  *hi = hb;
+  *lo = __builtin_bit_cast(uint32_t, l);
 }
-__device__ __forceinline__ float join_bf16(uint32_t hi, uint32_t lo) {
-  return bf16_bits_to_float((uint16_t)hi) + bf16_bits_to_float((uint16_t)lo);
+// hi + lo of the low half of a pair
+__device__ __forceinline__ float join_bf16_lo(uint32_t hi, uint32_t lo) {
+  return __uint_as_float(hi << 16) + __uint_as_float(lo << 16);
+}
+__device__ __forceinline__ float join_bf16_hi(uint32_t hi, uint32_t lo) {
+  return __uint_as_float(hi & 0xffff0000u) + __uint_as_float(lo & 0xffff0000u);
+}
+// phi(x)[j] = exp(a W_j.x - c |x|^2 + b_j) evaluated as exp2(a2 * (W_j.x) + t2) with
+// a2 = a log2(e) and t2 = (b_j - c |x|^2) log2(e): one FMA and one v_exp_f32.  The summary build
+// and the decode-side recompute both go through this function.
+constexpr float kLog2e = 1.4426950408889634f;
+__device__ __forceinline__ float phi_exp2(float dot, float a2, float t2) {
+  return __builtin_amdgcn_exp2f(fmaf(a2, dot, t2));
 }
 
 // 16-byte loads from global memory.  Pointers that come out of the problem table are
