@@ -59,16 +59,41 @@ def main() -> int:
     torch.cuda.set_device(0)
     w = I.WORKLOADS[args.workload]
     cfg = H.config_of(w)
-    L = w.L
-    n_mid = L - w.n_sink - w.n_tail
-    K = I.mid_budget(L, args.budget_bp, w.n_sink, w.n_tail)
     esz = 2 if w.dtype == "bf16" else 4
 
-    # ---- inputs: `rotate` distinct layers, resident in HBM before anything is timed -------
+    # ---- inputs, resident in HBM before anything is timed --------------------------------
+    # single-layer workloads: `rotate` distinct layers, one problem per call;
+    # model-level workloads: every (sequence, layer) problem of the model in ONE call.
     t0 = time.time()
-    with concurrent.futures.ThreadPoolExecutor(max_workers=min(4, args.rotate)) as ex:
-        layers = list(ex.map(lambda r: I.make_layer(w, layer=r), range(args.rotate)))
-    batches = [H.Batch(cfg, [P], [K]) for P in layers]
+    model_level = w.n_layers > 1
+    if model_level:
+        lens = I.ragged_lengths(w)
+        pairs = [(layer, seq) for layer in range(w.n_layers) for seq in range(w.n_seqs)]
+        Ls = [int(lens[seq]) for _, seq in pairs]
+    else:
+        pairs = [(r, 0) for r in range(args.rotate)]
+        Ls = [w.L] * len(pairs)
+    Ks = [I.mid_budget(L, args.budget_bp, w.n_sink, w.n_tail) for L in Ls]
+    n_keep = 1 if model_level else len(pairs)           # host copies kept for the CPU baseline
+    layers, dev_layers = [], []
+    with concurrent.futures.ThreadPoolExecutor(max_workers=8 if model_level else min(4, args.rotate)) as ex:
+        gen = ex.map(lambda a: I.make_layer(w, layer=a[0][0], seq=a[0][1], L=a[1]), zip(pairs, Ls))
+        for P in gen:
+            if len(layers) < n_keep:
+                layers.append(P)
+            dev_layers.append({k: (H.to_device(v) if isinstance(v, np.ndarray) and k != "needle_pos" else v)
+                               for k, v in P.items()})
+    if model_level:
+        batches = [H.Batch(cfg, dev_layers, Ks)]
+        probs_per_step = len(pairs)
+    else:
+        batches = [H.Batch(cfg, [P], [k]) for P, k in zip(dev_layers, Ks)]
+        probs_per_step = 1
+    del dev_layers
+    L, K = Ls[0], Ks[0]
+    mids = [max(0, l - w.n_sink - w.n_tail) for l in Ls]
+    n_mid = sum(mids) if model_level else mids[0]       # mid tokens scanned by one step
+    sum_K = sum(Ks) if model_level else K
     t_gen = time.time() - t0
     stream = torch.cuda.current_stream()
 
@@ -85,7 +110,7 @@ def main() -> int:
         b.build()
     e1.record(stream)
     torch.cuda.synchronize()
-    build_ms = e0.elapsed_time(e1) / len(batches)
+    build_ms = e0.elapsed_time(e1) / len(batches)                      # per call
     build_bytes = w.n_kv_heads * n_mid * w.d_head * esz * 2            # K and V rows of M, once
     build_flops = w.n_kv_heads * n_mid * (2 * w.d_phi * w.d_head + 2 * w.d_phi * (w.d_head + 1))
 
@@ -113,10 +138,10 @@ def main() -> int:
 
     # algorithmic bytes of one step (what the method must move)
     bytes_scan = w.n_kv_heads * n_mid * w.d_head * esz                  # every mid key row, once per KV head
-    bytes_gather = w.n_q_heads * K * 2 * w.d_head * esz                 # k and v rows of the retrieved tokens
-    bytes_anchor = w.n_kv_heads * (w.n_sink + w.n_tail) * 2 * w.d_head * esz
-    bytes_const = (w.n_kv_heads * w.d_phi * (w.d_head + 1) * 4          # S, u
-                   + (w.n_q_heads + w.n_kv_heads) * w.d_phi * w.d_head * esz)   # Wq, Wk
+    bytes_gather = w.n_q_heads * sum_K * 2 * w.d_head * esz             # k and v rows of the retrieved tokens
+    bytes_anchor = probs_per_step * w.n_kv_heads * (w.n_sink + w.n_tail) * 2 * w.d_head * esz
+    bytes_const = probs_per_step * (w.n_kv_heads * w.d_phi * (w.d_head + 1) * 4          # S, u
+                                    + (w.n_q_heads + w.n_kv_heads) * w.d_phi * w.d_head * esz)   # Wq, Wk
     bytes_step = bytes_scan + bytes_gather + bytes_anchor + bytes_const
     scan_s = stage_us["score_mid"] * 1e-6
     achieved = bytes_scan / scan_s / 1e9
@@ -131,9 +156,13 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.n_q_heads}q/{w.n_kv_heads}kv heads, head_dim {w.d_head}, "
-                               f"d_phi {w.d_phi}, L {L}, sink {w.n_sink} + tail {w.n_tail}, K {K} "
-                               f"({args.budget_bp} bp of the mid-region), one layer per step",
-                   "rotating_layers": args.rotate, "budget_bp": args.budget_bp, "K": K, "L": L},
+                               f"d_phi {w.d_phi}, sink {w.n_sink} + tail {w.n_tail}, budget {args.budget_bp} bp "
+                               f"of the mid-region, "
+                               + (f"{len(pairs)} (sequence, layer) problems per step ({w.n_seqs} sequences x "
+                                  f"{w.n_layers} layers), L {min(Ls)}..{max(Ls)}, K {min(Ks)}..{max(Ks)}"
+                                  if model_level else f"L {L}, K {K}, one layer per step"),
+                   "rotating_layers": 0 if model_level else args.rotate, "problems_per_step": probs_per_step,
+                   "budget_bp": args.budget_bp, "K": K, "L": L},
         "step_hbm": {"algorithmic_bytes": bytes_step, "achieved_GBs": bytes_step / (ms_per_step * 1e-3) / 1e9,
                      "frac_of_peak": bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "stage_us": stage_us,
@@ -142,7 +171,7 @@ def main() -> int:
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC.get((w.name, args.budget_bp)),
                      "algorithmic_bytes_per_launch": bytes_scan},
-        "build": {"ms_per_layer": build_ms, "algorithmic_bytes": build_bytes, "flops": build_flops,
+        "build": {"ms_per_call": build_ms, "problems_per_call": probs_per_step, "algorithmic_bytes": build_bytes, "flops": build_flops,
                   "hbm_GBs": build_bytes / (build_ms * 1e-3) / 1e9,
                   "hbm_frac": build_bytes / (build_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                   "mfma_TFLOPs": build_flops / (build_ms * 1e-3) / 1e12,
@@ -164,6 +193,7 @@ def main() -> int:
         t_build = t_dec = 0.0
         n_done = 0
         worst = 0.0
+        n_mid_done = 0
         for li, P in enumerate(layers):
             O = PU.oracle_inputs(P)
             t0 = time.perf_counter()
@@ -172,18 +202,20 @@ def main() -> int:
             t_build += time.perf_counter() - t0
             t0 = time.perf_counter()
             res = orc.decode_layer(O["q"], O["K"], O["V"], S, u, O["Wq"], O["bq"], O["Wk"], O["bk"],
-                                   w.phi_in_scale, w.phi_norm_coef, w.score_scale, w.n_sink, w.n_tail, K)
+                                   w.phi_in_scale, w.phi_norm_coef, w.score_scale, w.n_sink, w.n_tail, Ks[li])
             t_dec += time.perf_counter() - t0
             n_done += 1
-            batches[li].decode()
+            n_mid_done += mids[li]
+            bi, pi = (0, li) if model_level else (li, 0)
+            batches[bi].decode()
             torch.cuda.synchronize()
-            y = batches[li].result(0, "out")
+            y = batches[bi].result(pi, "out")
             worst = max([worst] + [float(np.abs(y[g] - r["y"]).max()) for g, r in enumerate(res)])
             del O
             if t_dec + t_build > 20.0:
                 break
         out["cpu_baseline"] = {
-            "value": n_done * n_mid / t_dec, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "value": n_mid_done / t_dec, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
             "sample": f"float64 numpy oracle, {n_done} whole layer-step(s) (all {w.n_q_heads} query heads) of the same "
                       f"workload: decode {t_dec:.2f} s (value = layers x mid tokens / decode seconds); the summary "
                       f"build of those layers took {t_build:.2f} s and is not in value",

@@ -148,6 +148,9 @@ __global__ __launch_bounds__(kThreads, 2) void build_mfma_kernel(Geom g, const t
 
     // ---- GEMM1 + exponent: all 64 tokens x this wavefront's features --------------------------
     u32x2 phi_hi[4][FT], phi_lo[4][FT];            // [16-token tile][feature tile]: tokens 4kg .. 4kg+3
+    float ut[FT];                                  // this tile's share of u, added to the running sum once
+#pragma unroll
+    for (int ft = 0; ft < FT; ++ft) ut[ft] = 0.f;
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
       Frag a[KS];
@@ -161,10 +164,8 @@ __global__ __launch_bounds__(kThreads, 2) void build_mfma_kernel(Geom g, const t
         for (int j = 0; j < KS; ++j) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[j].v, wk[ft][j].v, acc, 0, 0, 0);
         float f[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          f[i] = phi_exp2(acc[i], a2, bias[ft] - cn[i]);
-          uacc[ft] += f[i];
-        }
+        for (int i = 0; i < 4; ++i) f[i] = phi_exp2(acc[i], a2, bias[ft] - cn[i]);
+        ut[ft] += (f[0] + f[1]) + (f[2] + f[3]);
         uint32_t h01, l01, h23, l23;
         split_bf16_pair(f[0], f[1], &h01, &l01);
         split_bf16_pair(f[2], f[3], &h23, &l23);
@@ -172,6 +173,9 @@ __global__ __launch_bounds__(kThreads, 2) void build_mfma_kernel(Geom g, const t
         phi_lo[mt][ft] = (u32x2){l01, l23};
       }
     }
+
+#pragma unroll
+    for (int ft = 0; ft < FT; ++ft) uacc[ft] += ut[ft];
 
     // ---- GEMM2: S[own features][all channels] += Phi^T V ------------------------------------------
     // k-step ks contracts the 32 tokens of tiles 2ks and 2ks+1; lane (., kg) holds tokens
@@ -284,13 +288,15 @@ __global__ __launch_bounds__(kThreads) void build_kernel(Geom g, const tkphi_pro
     for (int a = 0; a < FJmax; ++a) {
       if (a < FJ) {
         const int j = tj * FJ + a;
+        float ub = 0.f;                    // this batch's share of u
         for (int t = 0; t < kTB; ++t) {
           const float f = ph[t][j];
-          if (tc == 0) uacc[a] += f;
+          ub += f;
 #pragma unroll
           for (int b = 0; b < FCmax; ++b)
             if (b < FC) acc[a][b] = fmaf(f, vf[t][tc * FC + b], acc[a][b]);
         }
+        uacc[a] += ub;
       }
     }
   }

@@ -87,6 +87,7 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   g->n_atiles = (int)std::max<int64_t>(1, ceil_div(std::min<int64_t>((int64_t)cfg->n_sink + cfg->n_tail, max_L), 64));
   // summary_build: about 512 workgroups
   int bc = (int)align_up((size_t)std::clamp<int64_t>(ceil_div(units, 512), 256, 1 << 20), 64);
+  if (!g->use_mfma) bc = std::min(bc, 4096);    // fp32 FMA chains stay short on the generic kernel
   bc = env_int("TKPHI_BUILD_CHUNK", bc);
   g->build_chunk = std::max(64, bc / 64 * 64);
   g->n_build_chunks = (int)std::max<int64_t>(1, ceil_div(g->max_mid, g->build_chunk));

@@ -7,8 +7,10 @@ Tolerances (the bar the path is held to):
                       the K-th score s_K; when that happens the output is also checked
                       against the oracle re-run on the GPU's set
   * outputs y         max-abs <= 2e-3 and relative l1 <= 1e-2 per query head
-  * summaries S, u    relative Frobenius error <= 2e-3 (bf16 path: the features are rounded
-                      to bf16 before the MFMA contraction) / 2e-5 (fp32 storage)
+  * summaries S, u    fp32 storage: relative Frobenius error <= 2e-5.  bf16 storage (matrix-core
+                      path, features carried as a bf16 hi + lo pair): element-wise
+                      |dS[j][c]| <= eps * sum_i phi_ij |v_ic|, |du[j]| <= eps * u[j],
+                      eps = 2^-16 + 2^-17 (see check_summaries)
 """
 from __future__ import annotations
 
@@ -101,16 +103,21 @@ def check_summaries(S_gpu, u_gpu, S_or, u_or, tol, w=None, O=None):
             assert (du <= eps * u_or[h]).all(), f"head {h}: u rel {eu:.3e}"
 
 
-def check_layer(w, P, k, batch, i, heads=None, sum_tol=None, mode="sub", check_aux=True):
-    """Full comparison of problem i of `batch` (already built + decoded, debug outputs on)."""
+def check_layer(w, P, k, batch, i, heads=None, sum_tol=None, mode="sub", check_aux=True, summaries=None):
+    """Full comparison of problem i of `batch` (already built + decoded, debug outputs on).
+    `summaries` = (S, u) from an earlier oracle build of the same cache skips both the oracle's
+    rebuild and the summary comparison (the caller has done it once)."""
     L = int(P["L"])
     n_mid = max(0, L - w.n_sink - w.n_tail)
     Hq = w.n_q_heads
     heads = list(range(Hq)) if heads is None else list(heads)
-    res, S_or, u_or, O = oracle_layer(w, P, k, heads=heads)
+    if summaries is None:
+        res, S_or, u_or, O = oracle_layer(w, P, k, heads=heads)
+    else:
+        res, S_or, u_or, O = oracle_layer(w, P, k, heads=heads, S=summaries[0], u=summaries[1])
     if sum_tol is None:
         sum_tol = 2e-3 if w.dtype == "bf16" else 2e-5
-    if n_mid > 0:
+    if n_mid > 0 and summaries is None:
         rounded_features = w.dtype == "bf16" and w.d_phi == w.d_head      # the matrix-core path
         check_summaries(batch.result(i, "S"), batch.result(i, "u"), S_or, u_or, sum_tol,
                         w=w if rounded_features else None, O=O)
