@@ -200,7 +200,7 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
   // the tile's retrieved tokens
   if (tid < kPairsPerWG) {
     const int i = i0 + min(tid, cnt - 1);
-    p_tok[tid] = g.n_sink + ((const int32_t*)(blk + g.off_selidx))[(size_t)gq * g.max_K + i];
+    p_tok[tid] = g.n_sink + min(max(((const int32_t*)(blk + g.off_selidx))[(size_t)gq * g.max_K + i], 0), n - 1);
     p_s[tid] = tid < cnt ? ((const float*)(blk + g.off_selscore))[(size_t)gq * g.max_K + i] : -INFINITY;
   }
   for (int i = tid; i < 2 * D + 4; i += kThreads) acc_part[i] = 0.f;
@@ -338,7 +338,7 @@ __global__ __launch_bounds__(kThreads) void gather_kernel(Geom g, const tkphi_pr
   for (int i = 0; i < cnt; ++i) m = fmaxf(m, sel_s[i]);
   float nu = 0.f, zv = 0.f, Z = 0.f, zsum = 0.f;
   for (int i = 0; i < cnt; ++i) {
-    const int64_t row_off = head_off + (int64_t)(g.n_sink + sel_idx[i]) * pr.stride_tok;
+    const int64_t row_off = head_off + (int64_t)(g.n_sink + min(max(sel_idx[i], 0), n - 1)) * pr.stride_tok;
     __syncthreads();                       // the previous token's readers of kf are done
     if (tid < d) kf[tid] = Elem<T>::load1(pr.K, row_off + tid);
     const float vc = tid < d ? Elem<T>::load1(pr.V, row_off + tid) : 0.f;

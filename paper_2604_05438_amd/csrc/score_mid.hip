@@ -129,9 +129,9 @@ __global__ __launch_bounds__(kThreads) void score_mid_mfma_kernel(Geom g, const 
         const int tok = base + tt;
         if (tok < c1) {
           const float s = strip[gl * TOK + tt] * scale + 0.0f;   // + 0.0f: -0 -> +0, equal scores get equal keys
-          if (!(g.dbg & 2)) scores[(size_t)gl * g.mid_stride + tok] = s;
+          scores[(size_t)gl * g.mid_stride + tok] = s;
           if (pr.scores) pr.scores[(size_t)(h * G + gl) * n + tok] = s;
-          if (!(g.dbg & 1)) atomicAdd(&lds_hist[gl * kBins + key_bin(score_key(s))], 1u);
+          atomicAdd(&lds_hist[gl * kBins + key_bin(score_key(s))], 1u);
         }
       }
     }

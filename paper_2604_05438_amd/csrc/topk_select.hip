@@ -253,6 +253,9 @@ __global__ __launch_bounds__(kThreads) void select_emit_kernel(Geom g, const tkp
   if (t0 >= n) return;
   const int t1 = min(n, t0 + g.scan_chunk);
   const bool keep_cand = plan.nb <= kCandCap;
+  // the histogram fixed how many tokens lie above / inside the threshold bin; the writes are
+  // bounded by those counts so that scores that disagree with it cannot leave the buffers
+  const int a_cap = min(plan.c_hi, g.max_K), c_cap = min(plan.nb, kCandCap);
   const float* scores = (const float*)(blk + g.off_scores) + (size_t)gq * g.mid_stride;
   int32_t* sel_idx = (int32_t*)(blk + g.off_selidx) + (size_t)gq * g.max_K;
   float* sel_score = (float*)(blk + g.off_selscore) + (size_t)gq * g.max_K;
@@ -299,8 +302,8 @@ __global__ __launch_bounds__(kThreads) void select_emit_kernel(Geom g, const tkp
       int pa = a_pos + ((x - packed) & 0xffff), pc = c_pos + ((x - packed) >> 16);
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        if (fa[e]) { sel_idx[pa] = tok + e; sel_score[pa] = sv[e]; ++pa; }
-        if (fc[e]) { if (keep_cand) cand[pc] = make_uint2(score_key(sv[e]), (uint32_t)(tok + e)); ++pc; }
+        if (fa[e]) { if (pa < a_cap) { sel_idx[pa] = tok + e; sel_score[pa] = sv[e]; } ++pa; }
+        if (fc[e]) { if (keep_cand && pc < c_cap) cand[pc] = make_uint2(score_key(sv[e]), (uint32_t)(tok + e)); ++pc; }
       }
       a_pos += total & 0xffff;
       c_pos += total >> 16;
