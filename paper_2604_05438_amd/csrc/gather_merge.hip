@@ -195,7 +195,6 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
   const int cnt = min(kPairsPerWG, Ksel - i0);
   const int h = gq / g.G;
   const int lane = tid & 63, wv = tid >> 6, r = lane & 15, kg = lane >> 4;
-  TKPHI_MARK(g, ws, 8);
 
   // the tile's retrieved tokens
   if (tid < kPairsPerWG) {
@@ -222,7 +221,6 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
     }
   }
   __syncthreads();
-  TKPHI_MARK(g, ws, 9);
   if (tid < 64) {                                  // m_loc = max score of the tile
     float m = p_s[tid];
 #pragma unroll
@@ -231,7 +229,6 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
   }
 
   const int64_t head_off = (int64_t)h * pr.stride_head;
-  TKPHI_MARK(g, ws, 10);
   if (wv * 16 < cnt) {
     // A operand: key rows of this wavefront's 16 tokens
     const int tok = p_tok[wv * 16 + r];
@@ -293,12 +290,10 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
     }
   }
   __syncthreads();
-  TKPHI_MARK(g, ws, 11);
   if (tid < kPairsPerWG) p_w[tid] = tid < cnt ? __expf(p_s[tid] - sh_m) : 0.f;
   __syncthreads();
 
   weighted_value_sums<uint16_t>(g, pr, head_off, p_tok, p_w, p_z, cnt, red, acc_part, true);
-  TKPHI_MARK(g, ws, 12);
   if (tid < D) { part[4 + tid] = acc_part[4 + tid]; part[4 + D + tid] = acc_part[4 + D + tid]; }
   if (tid == 0) {
     float Z = 0.f, zs = 0.f;
@@ -486,7 +481,44 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
     if (c < d) { ax[4 + c] = nu; ax[4 + d + c] = nuR; }
   }
   if (clamped && tid == 0) atomicOr((uint32_t*)(ws + g.off_status), TKPHI_DEV_CLAMPED);
+
+  // ---- optional export: retrieved token indices, ascending ---------------------------------------
+  // The list is an ascending run (tokens above the boundary bin) followed by the boundary-bin
+  // winners in no particular index order: rank = smaller ones in the run + smaller winners.
+  if (pr.topk_idx && Ksel > 0) {
+    __shared__ int sh_win[1024];
+    const int c_hi = min(max(((const SelPlan*)(blk + g.off_plan))[gq].c_hi, 0), Ksel);
+    const int32_t* sel_idx = (const int32_t*)(blk + g.off_selidx) + (size_t)gq * g.max_K;
+    int32_t* out = pr.topk_idx + (size_t)gq * g.max_K;
+    for (int base = 0; base < Ksel; base += kThreads) {
+      const int i = base + tid;
+      const bool active = i < Ksel;
+      const int v = active ? sel_idx[i] : 0;
+      int r = 0;
+      if (active) {
+        if (i < c_hi) r = i;
+        else {
+          int lo = 0, hi = c_hi;               // first element of the run that is >= v
+          while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (sel_idx[mid] < v) lo = mid + 1; else hi = mid;
+          }
+          r = lo;
+        }
+      }
+      for (int t0 = c_hi; t0 < Ksel; t0 += 1024) {
+        const int cnt = min(1024, Ksel - t0);
+        __syncthreads();
+        for (int j = tid; j < cnt; j += kThreads) sh_win[j] = sel_idx[t0 + j];
+        __syncthreads();
+        if (active)
+          for (int j = 0; j < cnt; ++j) r += sh_win[j] < v ? 1 : 0;
+      }
+      if (active) out[min(r, Ksel - 1)] = g.n_sink + v;
+    }
+  }
 }
+
 
 void launch_gather(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
   dim3 grid(g.n_tiles + g.n_atiles, g.Hq, g.n_problems);

@@ -105,7 +105,7 @@ __global__ __launch_bounds__(kThreads) void score_mid_mfma_kernel(Geom g, const 
       const int row = min(base + t * 16 + r, c1 - 1);
       const char* rp = Kb + (size_t)row * row_bytes;
 #pragma unroll
-      for (int j = 0; j < KS; ++j) a[t][j].u = (g.dbg & 4) ? gload128_stream(rp + j * 64) : gload128(rp + j * 64);
+      for (int j = 0; j < KS; ++j) a[t][j].u = gload128(rp + j * 64);
     }
     __builtin_amdgcn_sched_barrier(0);   // all loads of the iteration are in flight before the first MFMA
     floatx4 acc[TPI];
@@ -220,13 +220,7 @@ void launch_score_mid(const Geom& g, const tkphi_problem* probs, char* ws, hipSt
   dim3 grid(g.n_scan_chunks, g.Hkv, g.n_problems);
   const size_t hist_lds = (size_t)g.G * kBins * sizeof(uint32_t);
   if (g.use_mfma) {
-    if (g.d == 128 && (g.dbg & 8))
-      TKPHI_LAUNCH(ST_SCORE, (score_mid_mfma_kernel<128, 2>), grid, dim3(kThreads), hist_lds + (size_t)4 * g.G * 32 * 4, s,
-                         g, probs, ws);
-    else if (g.d == 128 && (g.dbg & 16))
-      TKPHI_LAUNCH(ST_SCORE, (score_mid_mfma_kernel<128, 8>), grid, dim3(kThreads), hist_lds + (size_t)4 * g.G * 128 * 4, s,
-                         g, probs, ws);
-    else if (g.d == 128)
+    if (g.d == 128)
       TKPHI_LAUNCH(ST_SCORE, (score_mid_mfma_kernel<128, 4>), grid, dim3(kThreads), hist_lds + (size_t)4 * g.G * 64 * 4, s,
                          g, probs, ws);
     else

@@ -62,7 +62,6 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   g->Hq = cfg->n_q_heads; g->Hkv = cfg->n_kv_heads; g->G = g->Hq / g->Hkv;
   g->d = cfg->d_head; g->dphi = cfg->d_phi; g->n_sink = cfg->n_sink; g->n_tail = cfg->n_tail;
   g->dtype = cfg->kv_dtype;
-  g->dbg = env_int("TKPHI_DBG", 0);
   g->use_mfma = (cfg->kv_dtype == TKPHI_BF16 && cfg->d_phi == cfg->d_head && !env_int("TKPHI_FORCE_GENERIC", 0)) ? 1 : 0;
   g->n_problems = n_problems; g->max_L = max_L;
   const int64_t mid = (int64_t)max_L - cfg->n_sink - cfg->n_tail;

@@ -30,7 +30,6 @@ constexpr int kPairsPerWG = 64;        // gather: retrieved tokens per workgroup
 struct Geom {
   int Hq, Hkv, G, d, dphi, n_sink, n_tail, dtype;
   int use_mfma;          // bf16 storage with d_phi == d_head: matrix-core kernels
-  int dbg;
   int n_problems, max_L, max_K, max_mid;
   int mid_stride;        // floats per score row (multiple of 64)
   int scan_chunk, n_scan_chunks;     // score_mid: mid tokens per workgroup
@@ -92,14 +91,10 @@ constexpr int kMaxScanChunks = 2048;   // chunk offsets are scanned in LDS by `p
 
 // kernel launchers (each defined next to its kernels)
 void launch_score_mid(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
-void launch_score_mid_mfma(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
 void launch_select(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
 void launch_gather(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
-void launch_gather_mfma(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
 void launch_merge(const Geom& g, const tkphi_problem* probs, char* ws, int mode, hipStream_t s);
 void launch_build(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
-void launch_build_mfma(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
-void launch_build_reduce(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
 
 #ifdef __HIPCC__
 // ---- device helpers ------------------------------------------------------------------
@@ -193,12 +188,6 @@ template <> struct Elem<uint16_t> {   // bf16 bits
   }
 };
 
-// debug timestamps (TKPHI_DBG bit 5): thread 0 of workgroup (0,0,0) stores the 100 MHz wall clock
-#define TKPHI_MARK(g, ws, k)                                                                              \
-  do {                                                                                                    \
-    if (((g).dbg & 32) && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0)      \
-      ((unsigned long long*)((ws) + 64))[(k)] = wall_clock64();                                           \
-  } while (0)
 
 // mid-region size of a problem; 0 if the anchors cover everything
 __device__ __forceinline__ int mid_size(int L, int n_sink, int n_tail) {

@@ -11,12 +11,13 @@
 //   emit     one wavefront per chunk, all heads in parallel: one ordered pass over the chunk's
 //            scores; tokens above b* go straight to the retrieved list, tokens in b* become
 //            candidates, both at the offsets computed by `plan`
-//   resolve  one workgroup per query head: exact K_rem-th largest candidate by (score
-//            descending, index ascending); the winners are appended to the list
+//   resolve  a few workgroups per query head: the K_rem best candidates by (score descending,
+//            index ascending) are appended to the list
 // The list holds (mid index, score): first the tokens above b* in ascending index order,
-// then the boundary-bin winners in ascending index order.  Ties go to the lower index.
-// If the boundary bin holds more than kCandCap tokens (e.g. all scores equal) `resolve`
-// falls back to radix passes over the score row in global memory: slower, same result.
+// then the boundary-bin winners (by rank, or in ascending index order on the radix paths).
+// Ties go to the lower index.  If the boundary bin holds more than kCandCap tokens (e.g. all
+// scores equal) `resolve` falls back to radix passes over the score row in global memory:
+// slower, same result.  The ascending export of the retrieved set is written by the merge kernel.
 #include "tkphi_internal.h"
 
 namespace tkphi {
@@ -99,7 +100,6 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(Geom g, const 
   const int gq = blockIdx.x, p = blockIdx.y, tid = threadIdx.x;
   const int lane = tid & 63, wv = tid >> 6;
   char* blk = problem_block(g, ws, p);
-  TKPHI_MARK(g, ws, 0);
 
   // device status word: recomputed from the problem lengths by one workgroup
   if (gq == 0 && p == 0) {
@@ -118,7 +118,6 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(Geom g, const 
   const int Ksel = max(0, min(min(pr.topk, n), g.max_K));
   SelPlan* plan = (SelPlan*)(blk + g.off_plan) + gq;
 
-  TKPHI_MARK(g, ws, 1);
   // ---- phi_q(q)[j] = exp(a Wq[j] . q - c |q|^2 + bq[j]) ---------------------------------
   {
     float* phiq = (float*)(blk + g.off_phiq) + (size_t)gq * g.dphi;
@@ -153,7 +152,6 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(Geom g, const 
   const uint16_t* hist = (const uint16_t*)(blk + g.off_hist) + (size_t)gq * kBins;   // + chunk * Hq * kBins
   const size_t hstep = (size_t)g.Hq * kBins;
 
-  TKPHI_MARK(g, ws, 2);
   // ---- total histogram: lane owns bins 8*lane .. 8*lane+7 (one 16-byte load per chunk),
   // wavefront wv takes chunks wv, wv + 16, ...; the 16 wavefront sums meet in LDS ---------------
   if (tid < kBins) sh_tot[tid] = 0u;
@@ -183,7 +181,6 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(Geom g, const 
     for (int e = 0; e < 8; ++e) if (t[e]) atomicAdd(&sh_tot[lane * 8 + e], t[e]);
   }
   __syncthreads();
-  TKPHI_MARK(g, ws, 3);
   // the rows are suffix sums, so sh_tot[b] = tokens of this head in bins >= b: the boundary bin
   // is the highest b with sh_tot[b] >= K
   if (tid < kBins) {
@@ -198,7 +195,6 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(Geom g, const 
     return;
   }
 
-  TKPHI_MARK(g, ws, 4);
   // ---- per chunk: tokens above b*, tokens in b* (two suffix counts per chunk) ----------------------
   for (int c = tid; c < n_chunks; c += kSelThreads) {
     const uint16_t* row = hist + (size_t)c * hstep;
@@ -207,7 +203,6 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(Geom g, const 
     sh_ca[c] = gt; sh_cc[c] = ge - gt;
   }
   __syncthreads();
-  TKPHI_MARK(g, ws, 5);
   {
     constexpr int PER = kMaxScanChunks / kSelThreads;      // 2 chunks per thread
     int va[PER], vc[PER], ta = 0, tc = 0;
@@ -230,7 +225,6 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(Geom g, const 
       ra += va[i]; rc += vc[i];
     }
   }
-  TKPHI_MARK(g, ws, 6);
   if (tid == 0) *plan = SelPlan{bstar, sh_krem, sh_chi, sh_nb, Ksel};
 }
 
@@ -312,17 +306,28 @@ __global__ __launch_bounds__(kThreads) void select_emit_kernel(Geom g, const tkp
 }
 
 // ------------------------------------------------------------------------------------
-// resolve: grid (Hq, n_problems), 1024 threads; dynamic LDS: candidates uint2[kCandCap]
+// resolve: grid (kResolveSplit, Hq, n_problems), 1024 threads; dynamic LDS: kCandCap x 8 bytes
+//
+// Up to kCountMax boundary-bin candidates (the usual case): the kResolveSplit workgroups of a
+// head share the work.  Each one stages all candidates (as 64-bit composites) in LDS and ranks
+// its own slice by counting the larger ones, 8 lanes per candidate; a candidate of rank
+// r < K_rem goes to list position c_hi + r, so the winners follow the tokens above b* in
+// descending (score, then ascending index) order and no scan is needed.  More candidates:
+// workgroup 0 alone runs radix passes (over the staged candidates, or over the score row if
+// they exceeded kCandCap) and appends the winners in ascending index order.
 // ------------------------------------------------------------------------------------
+constexpr int kResolveSplit = 16;
+constexpr int kCountMax = 1024;
+
 __global__ __launch_bounds__(kSelThreads) void select_resolve_kernel(Geom g, const tkphi_problem* __restrict__ probs,
                                                                      char* __restrict__ ws) {
   __shared__ uint32_t sh_hist[256];
   __shared__ int sh_scan[kSelWaves];
   __shared__ uint64_t sh_prefix;
   __shared__ int sh_want;
-  extern __shared__ uint2 sh_cand[];     // [kCandCap] (key, row), ascending row
+  extern __shared__ uint64_t sh_comp[];  // [kCandCap] composites of the candidates, ascending row
 
-  const int gq = blockIdx.x, p = blockIdx.y, tid = threadIdx.x;
+  const int part = blockIdx.x, gq = blockIdx.y, p = blockIdx.z, tid = threadIdx.x;
   const tkphi_problem pr = probs[p];
   if (pr.L < 1 || pr.L > g.max_L) return;
   const int n = mid_size(pr.L, g.n_sink, g.n_tail);
@@ -330,37 +335,54 @@ __global__ __launch_bounds__(kSelThreads) void select_resolve_kernel(Geom g, con
   const SelPlan plan = ((const SelPlan*)(blk + g.off_plan))[gq];
   const int bstar = plan.bstar, krem = plan.krem, c_hi = plan.c_hi, nb = plan.nb, Ksel = plan.n_sel;
   if (bstar < 0 || Ksel == 0) return;
+  if (nb > kCountMax && part != 0) return;
   const float* scores = (const float*)(blk + g.off_scores) + (size_t)gq * g.mid_stride;
   int32_t* sel_idx = (int32_t*)(blk + g.off_selidx) + (size_t)gq * g.max_K;
   float* sel_score = (float*)(blk + g.off_selscore) + (size_t)gq * g.max_K;
+  // list positions never leave [c_hi, Ksel) <= max_K whatever the candidates hold
+  const int k_cap = min(krem, max(0, min(Ksel, g.max_K) - c_hi));
 
   if (nb <= kCandCap) {
     const uint2* cand = (const uint2*)(blk + g.off_cand) + (size_t)gq * kCandCap;
-    for (int j = tid; j < nb; j += kSelThreads) sh_cand[j] = cand[j];
+    for (int j = tid; j < nb; j += kSelThreads) { const uint2 e = cand[j]; sh_comp[j] = composite(e.x, e.y); }
     __syncthreads();
-    uint64_t thr;
-    if (nb <= kSelThreads) {
-      // few candidates: rank each one by counting the larger ones (LDS broadcast reads, no barriers)
-      if (tid < nb) {
-        const uint64_t mine = composite(sh_cand[tid].x, sh_cand[tid].y);
+    if (nb <= kCountMax) {
+      const int per = (nb + kResolveSplit - 1) / kResolveSplit;       // candidates of this workgroup (<= 64)
+      const int sub = tid & 7, slot = tid >> 3;                       // 8 lanes per candidate, 128 slots
+      for (int k0 = 0; k0 < per; k0 += kSelThreads / 8) {
+        const int k = k0 + slot, j = part * per + k;
+        const bool valid = k < per && j < nb;
+        const uint64_t mine = valid ? sh_comp[j] : ~0ull;
         int rank = 0;
-        for (int i = 0; i < nb; ++i) rank += composite(sh_cand[i].x, sh_cand[i].y) > mine ? 1 : 0;
-        if (rank == krem - 1) sh_prefix = mine;
+        int i = sub;
+        for (; i + 24 < nb; i += 32) {
+          const uint64_t c0 = sh_comp[i], c1 = sh_comp[i + 8], c2 = sh_comp[i + 16], c3 = sh_comp[i + 24];
+          rank += (c0 > mine ? 1 : 0) + (c1 > mine ? 1 : 0) + (c2 > mine ? 1 : 0) + (c3 > mine ? 1 : 0);
+        }
+        for (; i < nb; i += 8) rank += sh_comp[i] > mine ? 1 : 0;
+        rank += __shfl_xor(rank, 1);
+        rank += __shfl_xor(rank, 2);
+        rank += __shfl_xor(rank, 4);
+        if (valid && sub == 0 && rank < k_cap) {
+          sel_idx[c_hi + rank] = (int)(0xffffffffu - (uint32_t)mine);
+          sel_score[c_hi + rank] = key_score((uint32_t)(mine >> 32));
+        }
       }
-      __syncthreads();
-      thr = sh_prefix;
-    } else {
-      auto get = [&](int j, uint64_t* v) { const uint2 e = sh_cand[j]; *v = composite(e.x, e.y); return true; };
-      thr = radix_select_desc(nb, krem, get, sh_hist, sh_scan, &sh_prefix, &sh_want);
+      return;
     }
+    auto get = [&](int j, uint64_t* v) { *v = sh_comp[j]; return true; };
+    const uint64_t thr = radix_select_desc(nb, krem, get, sh_hist, sh_scan, &sh_prefix, &sh_want);
     // ordered append of the winners: thread t owns candidates [t*R, (t+1)*R)
     const int R = (nb + kSelThreads - 1) / kSelThreads;
     int cnt = 0;
-    for (int j = tid * R; j < min(nb, (tid + 1) * R); ++j) cnt += composite(sh_cand[j].x, sh_cand[j].y) >= thr ? 1 : 0;
-    int pos = c_hi + sel_scan_incl(cnt, sh_scan) - cnt;
+    for (int j = tid * R; j < min(nb, (tid + 1) * R); ++j) cnt += sh_comp[j] >= thr ? 1 : 0;
+    int pos = sel_scan_incl(cnt, sh_scan) - cnt;
     for (int j = tid * R; j < min(nb, (tid + 1) * R); ++j) {
-      const uint2 e = sh_cand[j];
-      if (composite(e.x, e.y) >= thr) { sel_idx[pos] = (int)e.y; sel_score[pos] = key_score(e.x); ++pos; }
+      const uint64_t e = sh_comp[j];
+      if (e >= thr) {
+        if (pos < k_cap) { sel_idx[c_hi + pos] = (int)(0xffffffffu - (uint32_t)e); sel_score[c_hi + pos] = key_score((uint32_t)(e >> 32)); }
+        ++pos;
+      }
     }
   } else {
     auto get = [&](int j, uint64_t* v) {
@@ -369,7 +391,7 @@ __global__ __launch_bounds__(kSelThreads) void select_resolve_kernel(Geom g, con
       return key_bin(key) == bstar;
     };
     const uint64_t thr = radix_select_desc(n, krem, get, sh_hist, sh_scan, &sh_prefix, &sh_want);
-    int pos0 = c_hi;
+    int pos0 = 0;
     for (int base = 0; base < n; base += kSelThreads) {
       const int j = base + tid;
       int f = 0;
@@ -380,30 +402,11 @@ __global__ __launch_bounds__(kSelThreads) void select_resolve_kernel(Geom g, con
         f = (key_bin(key) == bstar && composite(key, (uint32_t)j) >= thr) ? 1 : 0;
       }
       const int incl = sel_scan_incl(f, sh_scan);
-      if (f) { sel_idx[pos0 + incl - 1] = j; sel_score[pos0 + incl - 1] = s; }
+      if (f && pos0 + incl - 1 < k_cap) { sel_idx[c_hi + pos0 + incl - 1] = j; sel_score[c_hi + pos0 + incl - 1] = s; }
       if (tid == kSelThreads - 1) sh_want = incl;
       __syncthreads();
       pos0 += sh_want;
       __syncthreads();
-    }
-  }
-
-  // ---- optional export: retrieved token indices, ascending ---------------------------------------
-  if (pr.topk_idx) {
-    __syncthreads();
-    int32_t* out = pr.topk_idx + (size_t)gq * g.max_K;
-    // merge of the two ascending runs [0, c_hi) and [c_hi, Ksel) by rank
-    for (int i = tid; i < Ksel; i += kSelThreads) {
-      const int v = sel_idx[i];
-      int lo, hi;
-      if (i < c_hi) { lo = c_hi; hi = Ksel; } else { lo = 0; hi = c_hi; }
-      const int lo0 = lo;
-      while (lo < hi) {                    // first element of the other run that is > v
-        const int mid = (lo + hi) >> 1;
-        if (sel_idx[mid] < v) lo = mid + 1; else hi = mid;
-      }
-      const int rank = (i < c_hi ? i : i - c_hi) + (lo - lo0);
-      out[rank] = g.n_sink + v;
     }
   }
 }
@@ -417,7 +420,8 @@ void launch_select(const Geom& g, const tkphi_problem* probs, char* ws, hipStrea
   if (g.max_mid == 0 || g.max_K == 0) return;
   dim3 egrid((g.n_scan_chunks + 3) / 4, g.Hq, g.n_problems);
   TKPHI_LAUNCH(ST_EMIT, select_emit_kernel, egrid, dim3(kThreads), 0, s, g, probs, ws);
-  TKPHI_LAUNCH(ST_RESOLVE, select_resolve_kernel, hgrid, dim3(kSelThreads), (size_t)kCandCap * sizeof(uint2), s, g, probs, ws);
+  dim3 rgrid(kResolveSplit, g.Hq, g.n_problems);
+  TKPHI_LAUNCH(ST_RESOLVE, select_resolve_kernel, rgrid, dim3(kSelThreads), (size_t)kCandCap * sizeof(uint64_t), s, g, probs, ws);
 }
 
 }  // namespace tkphi
