@@ -38,7 +38,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="l3b_128k")
     ap.add_argument("--budget-bp", type=int, default=100)
-    ap.add_argument("--rotate", type=int, default=4, help="distinct resident layers the steps rotate over")
+    ap.add_argument("--rotate", type=int, default=8, help="distinct resident layers the steps rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 256 MiB device copies (a known-size kernel to scale rocprofv3's "
@@ -76,7 +76,7 @@ def main() -> int:
     Ks = [I.mid_budget(L, args.budget_bp, w.n_sink, w.n_tail) for L in Ls]
     n_keep = 1 if model_level else len(pairs)           # host copies kept for the CPU baseline
     layers, dev_layers = [], []
-    with concurrent.futures.ThreadPoolExecutor(max_workers=8 if model_level else min(4, args.rotate)) as ex:
+    with concurrent.futures.ThreadPoolExecutor(max_workers=8) as ex:
         gen = ex.map(lambda a: I.make_layer(w, layer=a[0][0], seq=a[0][1], L=a[1]), zip(pairs, Ls))
         for P in gen:
             if len(layers) < n_keep:

@@ -315,24 +315,48 @@ __global__ __launch_bounds__(kThreads) void build_kernel(Geom g, const tkphi_pro
   }
 }
 
-// sums the chunk partials of each (problem, KV head) in chunk order.
-// grid (ceil(dphi*(d+1) / 256), Hkv, n_problems)
+// sums the chunk partials of each (problem, KV head) in a fixed order.
+// grid (ceil(dphi*(d+1)/4 / 64), Hkv, n_problems), 256 threads = 64 float4 elements x 4 chunk
+// groups: group q sums chunks q*16 .. q*16+15 of every 64 (16 loads in flight), then the four
+// group sums are added in group order.
 __global__ __launch_bounds__(kThreads) void build_reduce_kernel(Geom g, const tkphi_problem* __restrict__ probs,
                                                                 char* __restrict__ ws) {
+  __shared__ float4 sh[4][64];
   const int h = blockIdx.y, p = blockIdx.z;
   const int L = probs[p].L;
   if (L < 1 || L > g.max_L) return;
   const int n = mid_size(L, g.n_sink, g.n_tail);
   const int n_chunks = (n + g.build_chunk - 1) / g.build_chunk;
   const int d = g.d, dphi = g.dphi;
-  const size_t per = (size_t)dphi * (d + 1);
-  const size_t e = (size_t)blockIdx.x * kThreads + threadIdx.x;
-  if (e >= per) return;
-  const float* bp = (const float*)(ws + g.off_bpart) + ((size_t)(p * g.Hkv + h) * g.n_build_chunks) * per + e;
-  float s = 0.f;
-  for (int c = 0; c < n_chunks; ++c) s += bp[(size_t)c * per];
-  if (e < (size_t)dphi * d) probs[p].S[(size_t)h * dphi * d + e] = s;
-  else probs[p].u[(size_t)h * dphi + (e - (size_t)dphi * d)] = s;
+  const size_t per = (size_t)dphi * (d + 1);          // floats per partial (a multiple of 4)
+  const int el = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const size_t e4 = (size_t)blockIdx.x * 64 + el;     // float4 index inside a partial
+  const bool live = e4 * 4 < per;
+  const float4* bp = (const float4*)((const float*)(ws + g.off_bpart) + ((size_t)(p * g.Hkv + h) * g.n_build_chunks) * per) +
+                     (live ? e4 : 0);
+  const size_t per4 = per / 4;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int c0 = 0; c0 < n_chunks; c0 += 64) {
+    float4 v[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const int c = c0 + grp * 16 + k;
+      v[k] = bp[(size_t)min(c, n_chunks - 1) * per4];
+    }
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      if (c0 + grp * 16 + k < n_chunks) { acc.x += v[k].x; acc.y += v[k].y; acc.z += v[k].z; acc.w += v[k].w; }
+    }
+  }
+  sh[grp][el] = acc;
+  __syncthreads();
+  if (grp != 0 || !live) return;
+  float4 s = sh[0][el];
+#pragma unroll
+  for (int q = 1; q < 4; ++q) { s.x += sh[q][el].x; s.y += sh[q][el].y; s.z += sh[q][el].z; s.w += sh[q][el].w; }
+  const size_t e = e4 * 4;
+  if (e < (size_t)dphi * d) *(float4*)(probs[p].S + (size_t)h * dphi * d + e) = s;
+  else *(float4*)(probs[p].u + (size_t)h * dphi + (e - (size_t)dphi * d)) = s;
 }
 
 void launch_build(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
@@ -347,8 +371,8 @@ void launch_build(const Geom& g, const tkphi_problem* probs, char* ws, hipStream
       TKPHI_LAUNCH(ST_UNTIMED, build_kernel<float>, grid, dim3(kThreads), 0, s, g, probs, ws);
     }
   }
-  const int per = g.dphi * (g.d + 1);
-  dim3 rgrid((per + kThreads - 1) / kThreads, g.Hkv, g.n_problems);
+  const int per4 = g.dphi * (g.d + 1) / 4;
+  dim3 rgrid((per4 + 63) / 64, g.Hkv, g.n_problems);
   TKPHI_LAUNCH(ST_UNTIMED, build_reduce_kernel, rgrid, dim3(kThreads), 0, s, g, probs, ws);
 }
 
