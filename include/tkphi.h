@@ -171,11 +171,11 @@ tkphi_status tkphi_decode(const tkphi_config* cfg /*HOST*/,
  * every kernel launch (recorded at the kernel's own begin and end on the stream), then a
  * stream synchronisation; stage_ms_out (HOST, TKPHI_N_STAGES floats) receives the
  * duration in milliseconds of each kernel, in launch order:
- *   score_mid, select_scan (boundary bin + emit, phi_q), select_resolve,
+ *   score_mid, select_plan (+ phi_q), select_emit, select_resolve,
  *   gather (exact branch + subtraction sums), merge
  * (0 for a kernel that the given bounds do not launch).  Same validation and results as
  * tkphi_decode; creates and destroys HIP events (no device memory). */
-#define TKPHI_N_STAGES 5
+#define TKPHI_N_STAGES 6
 tkphi_status tkphi_decode_stage_times(const tkphi_config* cfg /*HOST*/,
                                       const tkphi_problem* problems /*DEVICE table*/,
                                       int32_t n_problems, int32_t max_L, int32_t max_K,

@@ -140,7 +140,7 @@ def tkphi_decode(cfg: tkphi_config, problems_dev_ptr: int, n_problems: int, max_
                               workspace_bytes, stream))
 
 
-STAGES = ("score_mid", "select_scan", "select_resolve", "gather", "merge")
+STAGES = ("score_mid", "select_plan", "select_emit", "select_resolve", "gather", "merge")
 
 
 def tkphi_decode_stage_times(cfg: tkphi_config, problems_dev_ptr: int, n_problems: int, max_L: int, max_K: int,

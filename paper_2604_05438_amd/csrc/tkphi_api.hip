@@ -100,6 +100,7 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   g->off_scores = p;  p = align_up(p + (size_t)g->Hq * g->mid_stride * sizeof(float), 256);
   g->off_hist = p;    p = align_up(p + (size_t)g->n_scan_chunks * g->Hq * kBins * sizeof(uint16_t), 256);
   g->off_plan = p;    p = align_up(p + (size_t)g->Hq * sizeof(SelPlan), 256);
+  g->off_chunkoff = p; p = align_up(p + (size_t)g->Hq * g->n_scan_chunks * 2 * sizeof(int32_t), 256);
   g->off_cand = p;    p = align_up(p + (size_t)g->Hq * kCandCap * sizeof(uint2), 256);
   g->off_selidx = p;  p = align_up(p + (size_t)g->Hq * std::max(max_K, 1) * sizeof(int32_t), 256);
   g->off_selscore = p; p = align_up(p + (size_t)g->Hq * std::max(max_K, 1) * sizeof(float), 256);

@@ -46,6 +46,7 @@ struct Geom {
   size_t off_scores;     // float    [Hq][mid_stride]            mid-region scores
   size_t off_hist;       // uint16   [n_scan_chunks][Hq][kBins]  per-chunk histograms
   size_t off_plan;       // SelPlan  [Hq]
+  size_t off_chunkoff;   // int32    [Hq][n_scan_chunks][2]      output offsets of each chunk (above b*, in b*)
   size_t off_cand;       // uint2    [Hq][kCandCap]              boundary-bin candidates (key, mid index)
   size_t off_selidx;     // int32    [Hq][max_K]                 retrieved mid indices
   size_t off_selscore;   // float    [Hq][max_K]                 their scores
@@ -61,7 +62,7 @@ void set_error(const char* fmt, ...);
 
 // Optional per-kernel timing: while g_kernel_timer is set (by tkphi_decode_stage_times, on
 // the calling thread) a launch records the kernel's own begin / end on the two events.
-enum Stage { ST_SCORE = 0, ST_SCAN, ST_RESOLVE, ST_GATHER, ST_MERGE, ST_COUNT, ST_UNTIMED = -1 };
+enum Stage { ST_SCORE = 0, ST_PLAN, ST_EMIT, ST_RESOLVE, ST_GATHER, ST_MERGE, ST_COUNT, ST_UNTIMED = -1 };
 struct KernelTimer {
   hipEvent_t start[ST_COUNT], stop[ST_COUNT];
   bool used[ST_COUNT];
@@ -86,7 +87,7 @@ struct SelPlan {
   int32_t nb;      // tokens in the boundary bin
   int32_t n_sel;   // retrieved tokens K' = min(topk, |M|, max_K)
 };
-constexpr int kMaxScanChunks = 2048;   // chunk offsets are scanned in LDS by the select scan kernel
+constexpr int kMaxScanChunks = 2048;   // chunk offsets are scanned in LDS by `plan`
 
 // kernel launchers (each defined next to its kernels)
 void launch_score_mid(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);

@@ -3,14 +3,14 @@
 // query feature map phi_q (Sec. "Positive feature maps and summary states": phi_q is
 // evaluated per query head at decode time).
 //
-// A two-level radix select in two small kernels, with no atomics in global memory:
-//   scan     16 chunks per workgroup, all heads in parallel.  Every workgroup first sums the
-//            per-chunk (suffix-count) histograms written by score_mid -> boundary bin b* (the
-//            bin holding the K-th largest score; every token in a higher bin is retrieved) and
-//            the output offsets of every chunk (exclusive prefix sums of the chunk counts);
-//            then each wavefront makes one ordered pass over the scores of its chunk: tokens
-//            above b* go straight to the retrieved list, tokens in b* become candidates.
-//            One more workgroup per head evaluates phi_q.
+// A two-level radix select in three small kernels, with no atomics and a fixed output order:
+//   plan     one workgroup per query head: sums the per-chunk (suffix-count) histograms written
+//            by score_mid -> boundary bin b* (the bin holding the K-th largest score; every token
+//            in a higher bin is retrieved); per chunk, the output offsets of its tokens above
+//            b* and of its tokens in b* (exclusive prefix sums of the chunk counts)
+//   emit     one wavefront per chunk, all heads in parallel: one ordered pass over the chunk's
+//            scores; tokens above b* go straight to the retrieved list, tokens in b* become
+//            candidates, both at the offsets computed by `plan`
 //   resolve  a few workgroups per query head: the K_rem best candidates by (score descending,
 //            index ascending) are appended to the list
 // The list holds (mid index, score): first the tokens above b* in ascending index order,
@@ -86,18 +86,21 @@ __device__ __forceinline__ void unpack_counts(const u32x4& v, uint32_t* c) {
 }
 
 // ------------------------------------------------------------------------------------
-// scan: grid (ceil(n_scan_chunks / 16) + 1, Hq, n_problems), 1024 threads
-//
-// Workgroup x < ceil(n_scan_chunks / 16) of a head: (1) sums the chunk histograms of the head
-// (every such workgroup repeats this: the rows come from L2, and no second kernel has to wait
-// for a first), finds the boundary bin and the output offsets of every chunk; (2) each of its
-// 16 wavefronts emits one chunk, 16x .. 16x + 15.  The last workgroup of a head evaluates
-// phi_q instead (and one of them recomputes the device status word).
+// plan: grid (Hq, n_problems), 1024 threads
 // ------------------------------------------------------------------------------------
 template <typename T>
-__device__ void phi_q_and_status(const Geom& g, const tkphi_problem* __restrict__ probs, char* __restrict__ ws,
-                                 int gq, int p, float* qf /*[kMaxDim] LDS*/) {
-  const int tid = threadIdx.x;
+__global__ __launch_bounds__(kSelThreads) void select_plan_kernel(Geom g, const tkphi_problem* __restrict__ probs,
+                                                                  char* __restrict__ ws) {
+  __shared__ float qf[kMaxDim];
+  __shared__ uint32_t sh_tot[kBins];
+  __shared__ int sh_scan[kSelWaves];
+  __shared__ int sh_bstar, sh_krem, sh_chi, sh_nb;
+  __shared__ int sh_ca[kMaxScanChunks], sh_cc[kMaxScanChunks];
+
+  const int gq = blockIdx.x, p = blockIdx.y, tid = threadIdx.x;
+  const int lane = tid & 63, wv = tid >> 6;
+  char* blk = problem_block(g, ws, p);
+
   // device status word: recomputed from the problem lengths by one workgroup
   if (gq == 0 && p == 0) {
     int bad = 0;
@@ -108,44 +111,152 @@ __device__ void phi_q_and_status(const Geom& g, const tkphi_problem* __restrict_
     bad = __syncthreads_or(bad);
     if (tid == 0) *(uint32_t*)(ws + g.off_status) = bad ? TKPHI_DEV_BAD_LENGTH : 0u;
   }
+
   const tkphi_problem pr = probs[p];
   if (pr.L < 1 || pr.L > g.max_L) return;
-  char* blk = problem_block(g, ws, p);
   const int n = mid_size(pr.L, g.n_sink, g.n_tail);
   const int Ksel = max(0, min(min(pr.topk, n), g.max_K));
-  if (Ksel == 0 && tid == 0) ((SelPlan*)(blk + g.off_plan))[gq] = SelPlan{-1, 0, 0, 0, 0};
+  SelPlan* plan = (SelPlan*)(blk + g.off_plan) + gq;
+
   // ---- phi_q(q)[j] = exp(a Wq[j] . q - c |q|^2 + bq[j]) ---------------------------------
-  float* phiq = (float*)(blk + g.off_phiq) + (size_t)gq * g.dphi;
-  for (int c = tid; c < g.d; c += kSelThreads) qf[c] = Elem<T>::load1(pr.q, (int64_t)gq * g.d + c);
-  __syncthreads();
-  // LPR lanes per Wq row, one 16-byte load each (all rows of a pass in flight together)
-  constexpr int EPL = Elem<T>::per16;
-  const int LPR = g.d / EPL, seg = tid % LPR, rows_pp = kSelThreads / LPR;
-  for (int j0 = 0; j0 < g.dphi; j0 += rows_pp) {
-    const int j = min(j0 + tid / LPR, g.dphi - 1);          // clamped: every lane loads, extra rows are dropped
-    const u32x4 t = gload128((const char*)pr.Wq + (((int64_t)gq * g.dphi + j) * g.d + seg * EPL) * sizeof(T));
-    const float bj = pr.bq[(int64_t)gq * g.dphi + j];
-    float x[EPL];
-    Elem<T>::unpack(make_uint4(t.x, t.y, t.z, t.w), x);
-    float dot = 0.f, nrm = 0.f;
+  {
+    float* phiq = (float*)(blk + g.off_phiq) + (size_t)gq * g.dphi;
+    for (int c = tid; c < g.d; c += kSelThreads) qf[c] = Elem<T>::load1(pr.q, (int64_t)gq * g.d + c);
+    __syncthreads();
+    // LPR lanes per Wq row, one 16-byte load each (all rows of a pass in flight together)
+    constexpr int EPL = Elem<T>::per16;
+    const int LPR = g.d / EPL, seg = tid % LPR, rows_pp = kSelThreads / LPR;
+    for (int j0 = 0; j0 < g.dphi; j0 += rows_pp) {
+      const int j = min(j0 + tid / LPR, g.dphi - 1);          // clamped: every lane loads, extra rows are dropped
+      const u32x4 t = gload128((const char*)pr.Wq + (((int64_t)gq * g.dphi + j) * g.d + seg * EPL) * sizeof(T));
+      const float bj = pr.bq[(int64_t)gq * g.dphi + j];
+      float x[EPL];
+      Elem<T>::unpack(make_uint4(t.x, t.y, t.z, t.w), x);
+      float dot = 0.f, nrm = 0.f;
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) {
-      const float qe = qf[seg * EPL + e];
-      dot = fmaf(x[e], qe, dot);
-      nrm = fmaf(qe, qe, nrm);
+      for (int e = 0; e < EPL; ++e) {
+        const float qe = qf[seg * EPL + e];
+        dot = fmaf(x[e], qe, dot);
+        nrm = fmaf(qe, qe, nrm);
+      }
+      for (int o = LPR >> 1; o >= 1; o >>= 1) { dot += __shfl_xor(dot, o); nrm += __shfl_xor(nrm, o); }
+      if (j0 + tid / LPR < g.dphi && seg == 0) phiq[j] = expf(g.a * dot - g.c * nrm + bj);
     }
-    for (int o = LPR >> 1; o >= 1; o >>= 1) { dot += __shfl_xor(dot, o); nrm += __shfl_xor(nrm, o); }
-    if (j0 + tid / LPR < g.dphi && seg == 0) phiq[j] = expf(g.a * dot - g.c * nrm + bj);
   }
+  if (Ksel == 0) {
+    if (tid == 0) *plan = SelPlan{-1, 0, 0, 0, 0};
+    return;
+  }
+
+  const int n_chunks = (n + g.scan_chunk - 1) / g.scan_chunk;
+  const uint16_t* hist = (const uint16_t*)(blk + g.off_hist) + (size_t)gq * kBins;   // + chunk * Hq * kBins
+  const size_t hstep = (size_t)g.Hq * kBins;
+
+  // ---- total histogram: lane owns bins 8*lane .. 8*lane+7 (one 16-byte load per chunk),
+  // wavefront wv takes chunks wv, wv + 16, ...; the 16 wavefront sums meet in LDS ---------------
+  if (tid < kBins) sh_tot[tid] = 0u;
+  if (tid == 0) { sh_bstar = -1; sh_krem = 0; sh_chi = 0; }
+  __syncthreads();
+  {
+    uint32_t t[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+    constexpr int UH = 8;                // row loads in flight per lane
+    for (int c0 = wv; c0 < n_chunks; c0 += kSelWaves * UH) {
+      u32x4 v[UH];
+#pragma unroll
+      for (int k = 0; k < UH; ++k) {
+        const int c = c0 + k * kSelWaves;
+        // unconditional load from a clamped row (a predicated load would be waited for on its own)
+        v[k] = gload128((const char*)(hist + (size_t)min(c, n_chunks - 1) * hstep) + lane * 16);
+        if (c >= n_chunks) v[k] = (u32x4){0u, 0u, 0u, 0u};
+      }
+#pragma unroll
+      for (int k = 0; k < UH; ++k) {
+        uint32_t c8[8];
+        unpack_counts(v[k], c8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t[e] += c8[e];
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) if (t[e]) atomicAdd(&sh_tot[lane * 8 + e], t[e]);
+  }
+  __syncthreads();
+  // the rows are suffix sums, so sh_tot[b] = tokens of this head in bins >= b: the boundary bin
+  // is the highest b with sh_tot[b] >= K
+  if (tid < kBins) {
+    const int ge = (int)sh_tot[tid];
+    const int gt = tid + 1 < kBins ? (int)sh_tot[tid + 1] : 0;
+    if (ge >= Ksel && gt < Ksel) { sh_bstar = tid; sh_krem = Ksel - gt; sh_chi = gt; sh_nb = ge - gt; }
+  }
+  __syncthreads();
+  const int bstar = sh_bstar;
+  if (bstar < 0) {                       // cannot happen for consistent histograms
+    if (tid == 0) *plan = SelPlan{-1, 0, 0, 0, 0};
+    return;
+  }
+
+  // ---- per chunk: tokens above b*, tokens in b* (two suffix counts per chunk) ----------------------
+  for (int c = tid; c < n_chunks; c += kSelThreads) {
+    const uint16_t* row = hist + (size_t)c * hstep;
+    const int ge = row[bstar];
+    const int gt = bstar + 1 < kBins ? row[bstar + 1] : 0;
+    sh_ca[c] = gt; sh_cc[c] = ge - gt;
+  }
+  __syncthreads();
+  {
+    constexpr int PER = kMaxScanChunks / kSelThreads;      // 2 chunks per thread
+    int va[PER], vc[PER], ta = 0, tc = 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int c = tid * PER + i;
+      va[i] = c < n_chunks ? sh_ca[c] : 0;
+      vc[i] = c < n_chunks ? sh_cc[c] : 0;
+      ta += va[i]; tc += vc[i];
+    }
+    // both sums fit 2 x 20 bits? no: scan them separately (|M| can exceed 2^20)
+    const int ia = sel_scan_incl(ta, sh_scan);
+    const int ic = sel_scan_incl(tc, sh_scan);
+    int ra = ia - ta, rc = ic - tc;
+    int32_t* choff = (int32_t*)(blk + g.off_chunkoff) + (size_t)gq * g.n_scan_chunks * 2;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int c = tid * PER + i;
+      if (c < n_chunks) { choff[2 * c] = ra; choff[2 * c + 1] = rc; }
+      ra += va[i]; rc += vc[i];
+    }
+  }
+  if (tid == 0) *plan = SelPlan{bstar, sh_krem, sh_chi, sh_nb, Ksel};
 }
 
-// one wavefront: ordered pass over the scores of chunk [t0, t1): tokens above b* go to the
-// retrieved list from position a_pos, tokens in b* to the candidate list from c_pos
-__device__ __forceinline__ void emit_chunk(const float* __restrict__ scores, int t0, int t1, int bstar, int a_pos,
-                                           int c_pos, int a_cap, int c_cap, bool keep_cand,
-                                           int32_t* __restrict__ sel_idx, float* __restrict__ sel_score,
-                                           uint2* __restrict__ cand) {
-  const int lane = threadIdx.x & 63;
+// ------------------------------------------------------------------------------------
+// emit: grid (ceil(n_scan_chunks / 4), Hq, n_problems), 256 threads; wavefront w <-> one chunk
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void select_emit_kernel(Geom g, const tkphi_problem* __restrict__ probs,
+                                                               char* __restrict__ ws) {
+  const int gq = blockIdx.y, p = blockIdx.z, tid = threadIdx.x;
+  const int lane = tid & 63, wv = tid >> 6;
+  const int L = probs[p].L;
+  if (L < 1 || L > g.max_L) return;
+  const int n = mid_size(L, g.n_sink, g.n_tail);
+  char* blk = problem_block(g, ws, p);
+  const SelPlan plan = ((const SelPlan*)(blk + g.off_plan))[gq];
+  const int bstar = plan.bstar;
+  if (bstar < 0) return;
+  const int chunk = blockIdx.x * 4 + wv;
+  const int t0 = chunk * g.scan_chunk;
+  if (t0 >= n) return;
+  const int t1 = min(n, t0 + g.scan_chunk);
+  const bool keep_cand = plan.nb <= kCandCap;
+  // the histogram fixed how many tokens lie above / inside the threshold bin; the writes are
+  // bounded by those counts so that scores that disagree with it cannot leave the buffers
+  const int a_cap = min(plan.c_hi, g.max_K), c_cap = min(plan.nb, kCandCap);
+  const float* scores = (const float*)(blk + g.off_scores) + (size_t)gq * g.mid_stride;
+  int32_t* sel_idx = (int32_t*)(blk + g.off_selidx) + (size_t)gq * g.max_K;
+  float* sel_score = (float*)(blk + g.off_selscore) + (size_t)gq * g.max_K;
+  uint2* cand = (uint2*)(blk + g.off_cand) + (size_t)gq * kCandCap;
+  const int32_t* choff = (const int32_t*)(blk + g.off_chunkoff) + ((size_t)gq * g.n_scan_chunks + chunk) * 2;
+  int a_pos = choff[0], c_pos = choff[1];
+
   // 4 consecutive tokens per lane, 256 per wavefront instruction
   constexpr int U = 2;                 // loads in flight per lane
   for (int base = t0; base < t1; base += 256 * U) {
@@ -185,8 +296,6 @@ __device__ __forceinline__ void emit_chunk(const float* __restrict__ scores, int
       int pa = a_pos + ((x - packed) & 0xffff), pc = c_pos + ((x - packed) >> 16);
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        // the histogram fixed how many tokens lie above / inside the boundary bin; the writes are
-        // bounded by those counts so that scores that disagree with it cannot leave the buffers
         if (fa[e]) { if (pa < a_cap) { sel_idx[pa] = tok + e; sel_score[pa] = sv[e]; } ++pa; }
         if (fc[e]) { if (keep_cand && pc < c_cap) cand[pc] = make_uint2(score_key(sv[e]), (uint32_t)(tok + e)); ++pc; }
       }
@@ -196,123 +305,10 @@ __device__ __forceinline__ void emit_chunk(const float* __restrict__ scores, int
   }
 }
 
-template <typename T>
-__global__ __launch_bounds__(kSelThreads) void select_scan_kernel(Geom g, const tkphi_problem* __restrict__ probs,
-                                                                  char* __restrict__ ws) {
-  __shared__ float qf[kMaxDim];
-  __shared__ uint32_t sh_tot[kBins];
-  __shared__ int sh_scan[kSelWaves];
-  __shared__ int sh_bstar, sh_krem, sh_chi, sh_nb;
-  __shared__ int sh_ca[kMaxScanChunks], sh_cc[kMaxScanChunks];
-
-  const int part = blockIdx.x, gq = blockIdx.y, p = blockIdx.z, tid = threadIdx.x;
-  const int lane = tid & 63, wv = tid >> 6;
-  if (part == (int)gridDim.x - 1) { phi_q_and_status<T>(g, probs, ws, gq, p, qf); return; }
-
-  char* blk = problem_block(g, ws, p);
-  const tkphi_problem pr = probs[p];
-  if (pr.L < 1 || pr.L > g.max_L) return;
-  const int n = mid_size(pr.L, g.n_sink, g.n_tail);
-  const int Ksel = max(0, min(min(pr.topk, n), g.max_K));
-  if (Ksel == 0) return;                 // (the phi_q workgroup writes the empty plan)
-  const int n_chunks = (n + g.scan_chunk - 1) / g.scan_chunk;
-  if (part * kSelWaves >= n_chunks) return;
-  SelPlan* plan = (SelPlan*)(blk + g.off_plan) + gq;
-  const uint16_t* hist = (const uint16_t*)(blk + g.off_hist) + (size_t)gq * kBins;   // + chunk * Hq * kBins
-  const size_t hstep = (size_t)g.Hq * kBins;
-
-  // ---- total histogram: lane owns bins 8*lane .. 8*lane+7 (one 16-byte load per chunk),
-  // wavefront wv takes chunks wv, wv + 16, ...; the 16 wavefront sums meet in LDS ---------------
-  if (tid < kBins) sh_tot[tid] = 0u;
-  if (tid == 0) { sh_bstar = -1; sh_krem = 0; sh_chi = 0; sh_nb = 0; }
-  __syncthreads();
-  {
-    uint32_t t[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
-    constexpr int UH = 8;                // row loads in flight per lane
-    for (int c0 = wv; c0 < n_chunks; c0 += kSelWaves * UH) {
-      u32x4 v[UH];
-#pragma unroll
-      for (int k = 0; k < UH; ++k) {
-        const int c = c0 + k * kSelWaves;
-        // unconditional load from a clamped row (a predicated load would be waited for on its own)
-        v[k] = gload128((const char*)(hist + (size_t)min(c, n_chunks - 1) * hstep) + lane * 16);
-        if (c >= n_chunks) v[k] = (u32x4){0u, 0u, 0u, 0u};
-      }
-#pragma unroll
-      for (int k = 0; k < UH; ++k) {
-        uint32_t c8[8];
-        unpack_counts(v[k], c8);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) t[e] += c8[e];
-      }
-    }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) if (t[e]) atomicAdd(&sh_tot[lane * 8 + e], t[e]);
-  }
-  __syncthreads();
-  // the rows are suffix sums, so sh_tot[b] = tokens of this head in bins >= b: the boundary bin
-  // is the highest b with sh_tot[b] >= K
-  if (tid < kBins) {
-    const int ge = (int)sh_tot[tid];
-    const int gt = tid + 1 < kBins ? (int)sh_tot[tid + 1] : 0;
-    if (ge >= Ksel && gt < Ksel) { sh_bstar = tid; sh_krem = Ksel - gt; sh_chi = gt; sh_nb = ge - gt; }
-  }
-  __syncthreads();
-  const int bstar = sh_bstar;
-  if (bstar < 0) {                       // cannot happen for consistent histograms
-    if (part == 0 && tid == 0) *plan = SelPlan{-1, 0, 0, 0, 0};
-    return;
-  }
-  const int c_hi = sh_chi, nb = sh_nb;
-  if (part == 0 && tid == 0) *plan = SelPlan{bstar, sh_krem, c_hi, nb, Ksel};
-
-  // ---- per chunk: tokens above b*, tokens in b* (two suffix counts per chunk); their exclusive
-  // prefix sums over the chunks are the output offsets of each chunk ----------------------------
-  for (int c = tid; c < n_chunks; c += kSelThreads) {
-    const uint16_t* row = hist + (size_t)c * hstep;
-    const int ge = row[bstar];
-    const int gt = bstar + 1 < kBins ? row[bstar + 1] : 0;
-    sh_ca[c] = gt; sh_cc[c] = ge - gt;
-  }
-  __syncthreads();
-  {
-    constexpr int PER = kMaxScanChunks / kSelThreads;      // 2 chunks per thread
-    int va[PER], vc[PER], ta = 0, tc = 0;
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int c = tid * PER + i;
-      va[i] = c < n_chunks ? sh_ca[c] : 0;
-      vc[i] = c < n_chunks ? sh_cc[c] : 0;
-      ta += va[i]; tc += vc[i];
-    }
-    // scanned separately: |M| can exceed what two packed 16-bit fields hold
-    const int ia = sel_scan_incl(ta, sh_scan);
-    const int ic = sel_scan_incl(tc, sh_scan);
-    int ra = ia - ta, rc = ic - tc;
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int c = tid * PER + i;
-      if (c < n_chunks) { sh_ca[c] = ra; sh_cc[c] = rc; }     // own entries only: in-place is safe
-      ra += va[i]; rc += vc[i];
-    }
-  }
-  __syncthreads();
-
-  // ---- emit: wavefront wv <-> chunk part * 16 + wv ---------------------------------------------
-  const int chunk = part * kSelWaves + wv;
-  const int t0 = chunk * g.scan_chunk;
-  if (chunk >= n_chunks || t0 >= n) return;
-  emit_chunk((const float*)(blk + g.off_scores) + (size_t)gq * g.mid_stride, t0, min(n, t0 + g.scan_chunk), bstar,
-             sh_ca[chunk], sh_cc[chunk], min(c_hi, g.max_K), min(nb, kCandCap), nb <= kCandCap,
-             (int32_t*)(blk + g.off_selidx) + (size_t)gq * g.max_K,
-             (float*)(blk + g.off_selscore) + (size_t)gq * g.max_K,
-             (uint2*)(blk + g.off_cand) + (size_t)gq * kCandCap);
-}
-
 // ------------------------------------------------------------------------------------
-// resolve: grid (kResolveSplit, Hq, n_problems), 1024 threads; dynamic LDS: kCandCap x 8 bytes
+// resolve: grid (split, Hq, n_problems), 1024 threads; dynamic LDS: kCandCap x 8 bytes
 //
-// Up to kCountMax boundary-bin candidates (the usual case): the kResolveSplit workgroups of a
+// Up to kCountMax boundary-bin candidates (the usual case): the `split` workgroups of a
 // head share the work.  Each one stages all candidates (as 64-bit composites) in LDS and ranks
 // its own slice by counting the larger ones, 8 lanes per candidate; a candidate of rank
 // r < K_rem goes to list position c_hi + r, so the winners follow the tokens above b* in
@@ -320,7 +316,7 @@ __global__ __launch_bounds__(kSelThreads) void select_scan_kernel(Geom g, const 
 // workgroup 0 alone runs radix passes (over the staged candidates, or over the score row if
 // they exceeded kCandCap) and appends the winners in ascending index order.
 // ------------------------------------------------------------------------------------
-constexpr int kResolveSplit = 16;
+constexpr int kResolveSplitMax = 16;      // workgroups per head when few heads are in flight
 constexpr int kCountMax = 1024;
 
 __global__ __launch_bounds__(kSelThreads) void select_resolve_kernel(Geom g, const tkphi_problem* __restrict__ probs,
@@ -351,7 +347,7 @@ __global__ __launch_bounds__(kSelThreads) void select_resolve_kernel(Geom g, con
     for (int j = tid; j < nb; j += kSelThreads) { const uint2 e = cand[j]; sh_comp[j] = composite(e.x, e.y); }
     __syncthreads();
     if (nb <= kCountMax) {
-      const int per = (nb + kResolveSplit - 1) / kResolveSplit;       // candidates of this workgroup (<= 64)
+      const int per = (nb + (int)gridDim.x - 1) / (int)gridDim.x;     // candidates of this workgroup
       const int sub = tid & 7, slot = tid >> 3;                       // 8 lanes per candidate, 128 slots
       for (int k0 = 0; k0 < per; k0 += kSelThreads / 8) {
         const int k = k0 + slot, j = part * per + k;
@@ -416,15 +412,17 @@ __global__ __launch_bounds__(kSelThreads) void select_resolve_kernel(Geom g, con
 }
 
 void launch_select(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
-  const bool selecting = g.max_mid > 0 && g.max_K > 0;
-  // emitting workgroups (16 chunks each) plus the phi_q workgroup of every head
-  dim3 sgrid((selecting ? (g.n_scan_chunks + kSelWaves - 1) / kSelWaves : 0) + 1, g.Hq, g.n_problems);
+  dim3 hgrid(g.Hq, g.n_problems);
   if (g.dtype == TKPHI_BF16)
-    TKPHI_LAUNCH(ST_SCAN, select_scan_kernel<uint16_t>, sgrid, dim3(kSelThreads), 0, s, g, probs, ws);
+    TKPHI_LAUNCH(ST_PLAN, select_plan_kernel<uint16_t>, hgrid, dim3(kSelThreads), 0, s, g, probs, ws);
   else
-    TKPHI_LAUNCH(ST_SCAN, select_scan_kernel<float>, sgrid, dim3(kSelThreads), 0, s, g, probs, ws);
-  if (!selecting) return;
-  dim3 rgrid(kResolveSplit, g.Hq, g.n_problems);
+    TKPHI_LAUNCH(ST_PLAN, select_plan_kernel<float>, hgrid, dim3(kSelThreads), 0, s, g, probs, ws);
+  if (g.max_mid == 0 || g.max_K == 0) return;
+  dim3 egrid((g.n_scan_chunks + 3) / 4, g.Hq, g.n_problems);
+  TKPHI_LAUNCH(ST_EMIT, select_emit_kernel, egrid, dim3(kThreads), 0, s, g, probs, ws);
+  // enough workgroups to spread the rank counting of one layer over the chip, one per head in big batches
+  const int split = std::clamp(512 / std::max(1, g.Hq * g.n_problems), 1, kResolveSplitMax);
+  dim3 rgrid(split, g.Hq, g.n_problems);
   TKPHI_LAUNCH(ST_RESOLVE, select_resolve_kernel, rgrid, dim3(kSelThreads), (size_t)kCandCap * sizeof(uint64_t), s, g, probs, ws);
 }
 
