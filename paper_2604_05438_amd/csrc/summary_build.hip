@@ -35,8 +35,8 @@ union Frag {
 //          the 32 tokens of a k-step, so the features never touch LDS
 //   GEMM2  S[own features][all channels] += Phi^T V : B = transposed value tile from LDS
 //          (two 8-byte reads per operand, same token permutation), hi and lo as two MFMAs
-// u is summed from the same features.  The next tile's global loads are issued as soon as the
-// current tile sits in LDS.
+// u is summed from the same features.  Two LDS tile buffers: tile t+1 is staged (and the
+// global loads of tile t+2 are issued) before tile t is contracted: one barrier per tile.
 // ------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void build_mfma_kernel(Geom g, const tkphi_problem* __restrict__ probs,
@@ -48,9 +48,10 @@ __global__ __launch_bounds__(kThreads, 2) void build_mfma_kernel(Geom g, const t
   constexpr int KLD = 64 * SEGS / kThreads;   // key-row loads per thread and tile (4 or 2)
   constexpr int KROW = D * 2 + 16;      // bytes per staged key row
   constexpr int TROW = 64 * 2 + 16;     // bytes per staged value-channel row (64 tokens)
-  __shared__ __attribute__((aligned(16))) char k_t[64 * KROW];    // [token][channel]
-  __shared__ __attribute__((aligned(16))) char v_t[D * TROW];     // [channel][token]
-  __shared__ __attribute__((aligned(16))) float nrm_t[64];        // c |k|^2 log2(e); +inf past the chunk end
+  // two tile buffers: tile t+1 is staged while tile t is contracted, one barrier per tile
+  __shared__ __attribute__((aligned(16))) char k_tb[2][64 * KROW];    // [token][channel]
+  __shared__ __attribute__((aligned(16))) char v_tb[2][D * TROW];     // [channel][token]
+  __shared__ __attribute__((aligned(16))) float nrm_tb[2][64];        // c |k|^2 log2(e); +inf past the chunk end
 
   const int ch = blockIdx.x, h = blockIdx.y, p = blockIdx.z, tid = threadIdx.x;
   const tkphi_problem pr = probs[p];
@@ -111,8 +112,7 @@ __global__ __launch_bounds__(kThreads, 2) void build_mfma_kernel(Geom g, const t
     }
   };
 
-  issue_loads(c0);
-  for (int t0 = c0; t0 < c1; t0 += 64) {
+  auto stage = [&](int t0, char* k_t, char* v_t, float* nrm_t) {
     // ---- stage the tile: keys row-major (+ norms), values channel-major ---------------------
 #pragma unroll
     for (int i = 0; i < KLD; ++i) {
@@ -143,9 +143,8 @@ __global__ __launch_bounds__(kThreads, 2) void build_mfma_kernel(Geom g, const t
         *(u32x2*)(v_t + (sg * 8 + 2 * q + 1) * TROW + tq * 8) = odd;
       }
     }
-    __syncthreads();
-    if (t0 + 64 < c1) issue_loads(t0 + 64);        // the staging registers are free again
-
+  };
+  auto contract = [&](const char* k_t, const char* v_t, const float* nrm_t) {
     // ---- GEMM1 + exponent: all 64 tokens x this wavefront's features --------------------------
     u32x2 phi_hi[4][FT], phi_lo[4][FT];            // [16-token tile][feature tile]: tokens 4kg .. 4kg+3
     float ut[FT];                                  // this tile's share of u, added to the running sum once
@@ -201,7 +200,21 @@ __global__ __launch_bounds__(kThreads, 2) void build_mfma_kernel(Geom g, const t
         }
       }
     }
-    __syncthreads();                     // everyone is done with this tile's LDS
+  };
+
+  issue_loads(c0);
+  stage(c0, k_tb[0], v_tb[0], nrm_tb[0]);
+  if (c0 + 64 < c1) issue_loads(c0 + 64);
+  __syncthreads();
+  int cur = 0;
+  for (int t0 = c0; t0 < c1; t0 += 64) {
+    if (t0 + 64 < c1) {                  // next tile: registers -> the other buffer, then refill the registers
+      stage(t0 + 64, k_tb[cur ^ 1], v_tb[cur ^ 1], nrm_tb[cur ^ 1]);
+      if (t0 + 128 < c1) issue_loads(t0 + 128);
+    }
+    contract(k_tb[cur], v_tb[cur], nrm_tb[cur]);
+    __syncthreads();                     // the other buffer is complete, this one is free
+    cur ^= 1;
   }
 
   // ---- write the chunk partial: S part [D][D] then u part [D] ----------------------------------

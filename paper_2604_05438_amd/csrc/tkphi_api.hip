@@ -84,8 +84,10 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   // gather: tiles of kPairsPerWG retrieved tokens per query head
   g->n_tiles = (int)ceil_div(std::min<int64_t>(max_K, g->max_mid), kPairsPerWG);
   g->n_atiles = (int)std::max<int64_t>(1, ceil_div(std::min<int64_t>((int64_t)cfg->n_sink + cfg->n_tail, max_L), 64));
-  // summary_build: about 512 workgroups
-  int bc = (int)align_up((size_t)std::clamp<int64_t>(ceil_div(units, 512), 256, 1 << 20), 64);
+  // summary_build: 512 workgroups fill the chip (2 per CU); larger jobs get about 2048 chunks of at
+  // least 2048 tokens so that the last, partly filled round of workgroups stays a small share
+  const int64_t bc_small = std::clamp<int64_t>(ceil_div(units, 512), 256, 2048);
+  int bc = (int)align_up((size_t)std::clamp<int64_t>(ceil_div(units, 2048), bc_small, 1 << 20), 64);
   if (!g->use_mfma) bc = std::min(bc, 4096);    // fp32 FMA chains stay short on the generic kernel
   bc = env_int("TKPHI_BUILD_CHUNK", bc);
   g->build_chunk = std::max(64, bc / 64 * 64);
