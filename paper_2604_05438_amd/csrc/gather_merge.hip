@@ -483,11 +483,10 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
   if (clamped && tid == 0) atomicOr((uint32_t*)(ws + g.off_status), TKPHI_DEV_CLAMPED);
 
   // ---- optional export: retrieved token indices, ascending ---------------------------------------
-  // The list is an ascending run (tokens above the boundary bin) followed by the boundary-bin
-  // winners in no particular index order: rank = smaller ones in the run + smaller winners.
+  // The list is in emission order (chunk by chunk, then the boundary-bin winners): rank every
+  // entry by counting the smaller ones, the list going through LDS in tiles.
   if (pr.topk_idx && Ksel > 0) {
     __shared__ int sh_win[1024];
-    const int c_hi = min(max(((const SelPlan*)(blk + g.off_plan))[gq].c_hi, 0), Ksel);
     const int32_t* sel_idx = (const int32_t*)(blk + g.off_selidx) + (size_t)gq * g.max_K;
     int32_t* out = pr.topk_idx + (size_t)gq * g.max_K;
     for (int base = 0; base < Ksel; base += kThreads) {
@@ -495,18 +494,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
       const bool active = i < Ksel;
       const int v = active ? sel_idx[i] : 0;
       int r = 0;
-      if (active) {
-        if (i < c_hi) r = i;
-        else {
-          int lo = 0, hi = c_hi;               // first element of the run that is >= v
-          while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (sel_idx[mid] < v) lo = mid + 1; else hi = mid;
-          }
-          r = lo;
-        }
-      }
-      for (int t0 = c_hi; t0 < Ksel; t0 += 1024) {
+      for (int t0 = 0; t0 < Ksel; t0 += 1024) {
         const int cnt = min(1024, Ksel - t0);
         __syncthreads();
         for (int j = tid; j < cnt; j += kThreads) sh_win[j] = sel_idx[t0 + j];
@@ -518,7 +506,6 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
     }
   }
 }
-
 
 void launch_gather(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
   dim3 grid(g.n_tiles + g.n_atiles, g.Hq, g.n_problems);

@@ -69,9 +69,9 @@ __global__ __launch_bounds__(kThreads) void score_mid_mfma_kernel(Geom g, const 
   const tkphi_problem pr = probs[p];
   if (pr.L < 1 || pr.L > g.max_L) return;
   const int n = mid_size(pr.L, g.n_sink, g.n_tail);
-  const int c0 = blockIdx.x * g.scan_chunk;
-  if (c0 >= n) return;
-  const int c1 = min(n, c0 + g.scan_chunk);
+  const int n_chunks = (n + g.scan_chunk - 1) / g.scan_chunk;
+  if ((int)blockIdx.x >= n_chunks) return;
+  const int c1 = n;                     // units of different chunks never overlap
   const int G = g.G;
   char* blk = problem_block(g, ws, p);
 
@@ -98,7 +98,10 @@ __global__ __launch_bounds__(kThreads) void score_mid_mfma_kernel(Geom g, const 
   float* strip = strips + (size_t)wv * G * TOK;
   const float scale = g.score_scale;
 
-  for (int base = c0 + wv * TOK; base < c1; base += 4 * TOK) {
+  const int n_units = g.scan_chunk / (4 * TOK);      // host guarantees scan_unit == 4 * TOK
+  for (int k = 0; k < n_units; ++k) {
+    const int base = chunk_unit_token(g, n_chunks, blockIdx.x, k) + wv * TOK;
+    if (base >= c1) { if (g.interleave) break; else continue; }
     Frag a[TPI][KS];
 #pragma unroll
     for (int t = 0; t < TPI; ++t) {
@@ -156,7 +159,7 @@ __global__ __launch_bounds__(kThreads) void score_mid_kernel(Geom g, const tkphi
   const tkphi_problem pr = probs[p];
   if (pr.L < 1 || pr.L > g.max_L) return;
   const int n = mid_size(pr.L, g.n_sink, g.n_tail);
-  const int c0 = blockIdx.x * g.scan_chunk;
+  const int c0 = blockIdx.x * g.scan_chunk;           // always one contiguous range here
   if (c0 >= n) return;
   const int c1 = min(n, c0 + g.scan_chunk);
   const int G = g.G;

@@ -33,6 +33,9 @@ struct Geom {
   int n_problems, max_L, max_K, max_mid;
   int mid_stride;        // floats per score row (multiple of 64)
   int scan_chunk, n_scan_chunks;     // score_mid: mid tokens per workgroup
+  int scan_unit;         // tokens a score_mid workgroup takes per iteration (scan_chunk is a multiple)
+  int interleave;        // 1: chunk c owns the units c, c + n_chunks, c + 2 n_chunks, ... of its problem
+                         // (all workgroups sweep the key cache together); 0: one contiguous range
   int n_tiles;           // gather: ceil(max_K / kPairsPerWG) retrieved-token tiles per query head
   int n_atiles;          // gather: ceil((n_sink + n_tail) / 64) anchor tiles per query head (>= 1)
   int build_chunk, n_build_chunks;   // summary_build: mid tokens per workgroup
@@ -193,6 +196,12 @@ template <> struct Elem<uint16_t> {   // bf16 bits
 __device__ __forceinline__ int mid_size(int L, int n_sink, int n_tail) {
   const int n = L - n_sink - n_tail;
   return n > 0 ? n : 0;
+}
+
+// first token of unit k (k = 0 .. scan_chunk / scan_unit - 1) of chunk `chunk`; n_chunks is the chunk
+// count of the problem at hand.  Units never overlap, so "token < n" is the only bound to check.
+__device__ __forceinline__ int chunk_unit_token(const Geom& g, int n_chunks, int chunk, int k) {
+  return g.interleave ? (chunk + k * n_chunks) * g.scan_unit : chunk * g.scan_chunk + k * g.scan_unit;
 }
 
 __device__ __forceinline__ char* problem_block(const Geom& g, char* ws, int p) {

@@ -13,8 +13,9 @@
 //            candidates, both at the offsets computed by `plan`
 //   resolve  a few workgroups per query head: the K_rem best candidates by (score descending,
 //            index ascending) are appended to the list
-// The list holds (mid index, score): first the tokens above b* in ascending index order,
-// then the boundary-bin winners (by rank, or in ascending index order on the radix paths).
+// The list holds (mid index, score): first the tokens above b* chunk by chunk (ascending
+// index order when chunks are contiguous), then the boundary-bin winners (by rank, or in
+// ascending index order on the radix paths).
 // Ties go to the lower index.  If the boundary bin holds more than kCandCap tokens (e.g. all
 // scores equal) `resolve` falls back to radix passes over the score row in global memory:
 // slower, same result.  The ascending export of the retrieved set is written by the merge kernel.
@@ -231,6 +232,7 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(Geom g, const 
 // ------------------------------------------------------------------------------------
 // emit: grid (ceil(n_scan_chunks / 4), Hq, n_problems), 256 threads; wavefront w <-> one chunk
 // ------------------------------------------------------------------------------------
+template <bool IL>     // IL: interleaved chunks (Geom::interleave)
 __global__ __launch_bounds__(kThreads) void select_emit_kernel(Geom g, const tkphi_problem* __restrict__ probs,
                                                                char* __restrict__ ws) {
   const int gq = blockIdx.y, p = blockIdx.z, tid = threadIdx.x;
@@ -243,9 +245,17 @@ __global__ __launch_bounds__(kThreads) void select_emit_kernel(Geom g, const tkp
   const int bstar = plan.bstar;
   if (bstar < 0) return;
   const int chunk = blockIdx.x * 4 + wv;
-  const int t0 = chunk * g.scan_chunk;
-  if (t0 >= n) return;
-  const int t1 = min(n, t0 + g.scan_chunk);
+  const int n_chunks = (n + g.scan_chunk - 1) / g.scan_chunk;
+  if (chunk >= n_chunks) return;
+  // the chunk's tokens in blocks of 256, in the order score_mid took them: block s lies in unit
+  // s / (scan_unit / 256) of the chunk (contiguous chunks: simply t0 + 256 s)
+  const int bpu = IL ? g.scan_unit / 256 : 1;
+  const int n_blocks = g.scan_chunk / 256;
+  const int t1 = IL ? n : min(n, (chunk + 1) * g.scan_chunk);
+  auto block_token = [&](int s) {
+    if (IL) return s < n_blocks ? (chunk + (s / bpu) * n_chunks) * g.scan_unit + (s % bpu) * 256 : t1;
+    return chunk * g.scan_chunk + s * 256;
+  };
   const bool keep_cand = plan.nb <= kCandCap;
   // the histogram fixed how many tokens lie above / inside the threshold bin; the writes are
   // bounded by those counts so that scores that disagree with it cannot leave the buffers
@@ -259,11 +269,12 @@ __global__ __launch_bounds__(kThreads) void select_emit_kernel(Geom g, const tkp
 
   // 4 consecutive tokens per lane, 256 per wavefront instruction
   constexpr int U = 2;                 // loads in flight per lane
-  for (int base = t0; base < t1; base += 256 * U) {
+  for (int s0 = 0; s0 < n_blocks; s0 += U) {
+    if (block_token(s0) >= t1) break;
     float4 v[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int tok = base + u * 256 + lane * 4;
+      const int tok = block_token(s0 + u) + lane * 4;
       v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
       if (tok + 3 < t1) v[u] = *(const float4*)(scores + tok);     // rows are 16-byte aligned (mid_stride % 64 == 0)
       else {
@@ -274,7 +285,7 @@ __global__ __launch_bounds__(kThreads) void select_emit_kernel(Geom g, const tkp
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int tok = base + u * 256 + lane * 4;
+      const int tok = block_token(s0 + u) + lane * 4;
       const float sv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
       int fa[4], fc[4], na = 0, nc = 0;
 #pragma unroll
@@ -419,7 +430,8 @@ void launch_select(const Geom& g, const tkphi_problem* probs, char* ws, hipStrea
     TKPHI_LAUNCH(ST_PLAN, select_plan_kernel<float>, hgrid, dim3(kSelThreads), 0, s, g, probs, ws);
   if (g.max_mid == 0 || g.max_K == 0) return;
   dim3 egrid((g.n_scan_chunks + 3) / 4, g.Hq, g.n_problems);
-  TKPHI_LAUNCH(ST_EMIT, select_emit_kernel, egrid, dim3(kThreads), 0, s, g, probs, ws);
+  if (g.interleave) TKPHI_LAUNCH(ST_EMIT, select_emit_kernel<true>, egrid, dim3(kThreads), 0, s, g, probs, ws);
+  else TKPHI_LAUNCH(ST_EMIT, select_emit_kernel<false>, egrid, dim3(kThreads), 0, s, g, probs, ws);
   // enough workgroups to spread the rank counting of one layer over the chip, one per head in big batches
   const int split = std::clamp(512 / std::max(1, g.Hq * g.n_problems), 1, kResolveSplitMax);
   dim3 rgrid(split, g.Hq, g.n_problems);
