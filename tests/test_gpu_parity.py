@@ -53,6 +53,28 @@ def test_l3b_shape_small(L, k):
     print("l3b", L, k, rep)
 
 
+@pytest.mark.parametrize("shape,L,k,chunk", [("l3b_128k", 20011, 200, 1024), ("l1b_32k", 9000, 90, 2048),
+                                             ("l3b_128k", 5000, 600, 512)])
+def test_interleaved_chunks(monkeypatch, shape, L, k, chunk):
+    """The chunk-to-row mapping used for long single sequences (every workgroup takes every
+    n_chunks-th unit of 256 / 512 rows), forced here at sizes the oracle checks in full; ragged
+    last units, and a single problem as well as a ragged batch."""
+    import parity_utils as PU
+    monkeypatch.setenv("TKPHI_INTERLEAVE", "1")
+    monkeypatch.setenv("TKPHI_SCAN_CHUNK", str(chunk))
+    w = I.WORKLOADS[shape]
+    rep, _, _ = _run_single(w, L, k)
+    print("interleaved", shape, L, k, rep)
+    Ls = [L, L // 2 + 3, 700]
+    ks = [k, 11, 5]
+    layers = [I.make_layer(w, L=l, seq=i) for i, l in enumerate(Ls)]
+    b = _batch(w, layers, ks)
+    b.build(); b.decode()
+    assert b.status() == 0
+    for i, (P, kk) in enumerate(zip(layers, ks)):
+        PU.check_layer(w, P, kk, b, i, heads=[0, w.n_q_heads // 2, w.n_q_heads - 1])
+
+
 @pytest.mark.parametrize("mode", ["nosub", "topk"])
 def test_accounting_variants(mode):
     w = I.WORKLOADS["l1b_32k"]
