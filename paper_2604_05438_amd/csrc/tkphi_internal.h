@@ -192,6 +192,62 @@ template <> struct Elem<uint16_t> {   // bf16 bits
 };
 
 
+// ---- query features and device status (side workgroups of the select plan launch) ----
+// phi_q(q_g)[j] = exp(a Wq[g][j] . q_g - c |q_g|^2 + bq[g][j]) for query head gq
+// (Sec. "Positive feature maps and summary states": phi_q is evaluated per query head at decode
+// time).  LPR lanes per Wq row with one 16-byte load each; all row loads of a head are in flight
+// together.  Works for any workgroup size that is a multiple of 64.  qf: LDS, >= kMaxDim floats.
+template <typename T>
+__device__ __forceinline__ void phi_q_head(const Geom& g, const tkphi_problem& pr, char* blk, int gq, float* qf) {
+  constexpr int EPL = Elem<T>::per16;
+  const int tid = threadIdx.x, nthr = blockDim.x;
+  const int LPR = g.d / EPL, seg = tid % LPR, rows_pp = nthr / LPR;
+  constexpr int MAXP = 8;                        // row passes held in flight (128 rows at 16 per pass)
+  {
+    float* phiq = (float*)(blk + g.off_phiq) + (size_t)gq * g.dphi;
+    for (int c = tid; c < g.d; c += nthr) qf[c] = Elem<T>::load1(pr.q, (int64_t)gq * g.d + c);
+    __syncthreads();
+    for (int j0 = 0; j0 < g.dphi; j0 += rows_pp * MAXP) {
+      u32x4 t[MAXP];
+      float bj[MAXP];
+#pragma unroll
+      for (int k = 0; k < MAXP; ++k) {
+        if (j0 + k * rows_pp >= g.dphi) break;                          // (uniform) no rows left for this pass
+        const int j = min(j0 + k * rows_pp + tid / LPR, g.dphi - 1);   // clamped: every lane loads
+        t[k] = gload128((const char*)pr.Wq + (((int64_t)gq * g.dphi + j) * g.d + seg * EPL) * sizeof(T));
+        bj[k] = pr.bq[(int64_t)gq * g.dphi + j];
+      }
+#pragma unroll
+      for (int k = 0; k < MAXP; ++k) {
+        if (j0 + k * rows_pp >= g.dphi) break;
+        const int jr = j0 + k * rows_pp + tid / LPR;
+        float x[EPL];
+        Elem<T>::unpack(make_uint4(t[k].x, t[k].y, t[k].z, t[k].w), x);
+        float dot = 0.f, nrm = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+          const float qe = qf[seg * EPL + e];
+          dot = fmaf(x[e], qe, dot);
+          nrm = fmaf(qe, qe, nrm);
+        }
+        for (int o = LPR >> 1; o >= 1; o >>= 1) { dot += __shfl_xor(dot, o); nrm += __shfl_xor(nrm, o); }
+        if (jr < g.dphi && seg == 0) phiq[jr] = expf(g.a * dot - g.c * nrm + bj[k]);
+      }
+    }
+  }
+}
+
+// device status word: recomputed from the problem lengths by one workgroup per decode call
+__device__ __forceinline__ void write_device_status(const Geom& g, const tkphi_problem* probs, char* ws) {
+  int bad = 0;
+  for (int i = threadIdx.x; i < g.n_problems; i += blockDim.x) {
+    const int Li = probs[i].L;
+    bad |= (Li < 1 || Li > g.max_L) ? 1 : 0;
+  }
+  bad = __syncthreads_or(bad);
+  if (threadIdx.x == 0) *(uint32_t*)(ws + g.off_status) = bad ? TKPHI_DEV_BAD_LENGTH : 0u;
+}
+
 // mid-region size of a problem; 0 if the anchors cover everything
 __device__ __forceinline__ int mid_size(int L, int n_sink, int n_tail) {
   const int n = L - n_sink - n_tail;

@@ -87,63 +87,39 @@ __device__ __forceinline__ void unpack_counts(const u32x4& v, uint32_t* c) {
 }
 
 // ------------------------------------------------------------------------------------
-// plan: grid (Hq, n_problems), 1024 threads
+// plan: grid (Hq or 2 Hq, n_problems), 1024 threads.  Workgroup x < Hq plans query head x; with
+// 2 Hq workgroups (few heads in flight) workgroup Hq + x evaluates phi_q of head x at the same
+// time, otherwise workgroup x does it first.  One workgroup also writes the device status word.
 // ------------------------------------------------------------------------------------
-template <typename T>
 __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(Geom g, const tkphi_problem* __restrict__ probs,
                                                                   char* __restrict__ ws) {
-  __shared__ float qf[kMaxDim];
   __shared__ uint32_t sh_tot[kBins];
   __shared__ int sh_scan[kSelWaves];
   __shared__ int sh_bstar, sh_krem, sh_chi, sh_nb;
   __shared__ int sh_ca[kMaxScanChunks], sh_cc[kMaxScanChunks];
 
-  const int gq = blockIdx.x, p = blockIdx.y, tid = threadIdx.x;
+  const int p = blockIdx.y, tid = threadIdx.x;
   const int lane = tid & 63, wv = tid >> 6;
   char* blk = problem_block(g, ws, p);
-
-  // device status word: recomputed from the problem lengths by one workgroup
-  if (gq == 0 && p == 0) {
-    int bad = 0;
-    for (int i = tid; i < g.n_problems; i += kSelThreads) {
-      const int Li = probs[i].L;
-      bad |= (Li < 1 || Li > g.max_L) ? 1 : 0;
-    }
-    bad = __syncthreads_or(bad);
-    if (tid == 0) *(uint32_t*)(ws + g.off_status) = bad ? TKPHI_DEV_BAD_LENGTH : 0u;
-  }
+  // few heads in flight (gridDim.x == 2 Hq): phi_q has workgroups of its own and leaves the
+  // critical path; many heads: every planning workgroup evaluates phi_q of its head first
+  const bool split = (int)gridDim.x > g.Hq;
+  const bool side_job = (int)blockIdx.x >= g.Hq;
+  const int gq = side_job ? (int)blockIdx.x - g.Hq : (int)blockIdx.x;
+  if ((side_job || !split) && gq == 0 && p == 0) write_device_status(g, probs, ws);
 
   const tkphi_problem pr = probs[p];
   if (pr.L < 1 || pr.L > g.max_L) return;
+  if (side_job || !split) {
+    if (g.dtype == TKPHI_BF16) phi_q_head<uint16_t>(g, pr, blk, gq, (float*)sh_tot);
+    else phi_q_head<float>(g, pr, blk, gq, (float*)sh_tot);
+    if (side_job) return;
+    __syncthreads();                     // sh_tot served as scratch
+  }
   const int n = mid_size(pr.L, g.n_sink, g.n_tail);
   const int Ksel = max(0, min(min(pr.topk, n), g.max_K));
   SelPlan* plan = (SelPlan*)(blk + g.off_plan) + gq;
 
-  // ---- phi_q(q)[j] = exp(a Wq[j] . q - c |q|^2 + bq[j]) ---------------------------------
-  {
-    float* phiq = (float*)(blk + g.off_phiq) + (size_t)gq * g.dphi;
-    for (int c = tid; c < g.d; c += kSelThreads) qf[c] = Elem<T>::load1(pr.q, (int64_t)gq * g.d + c);
-    __syncthreads();
-    // LPR lanes per Wq row, one 16-byte load each (all rows of a pass in flight together)
-    constexpr int EPL = Elem<T>::per16;
-    const int LPR = g.d / EPL, seg = tid % LPR, rows_pp = kSelThreads / LPR;
-    for (int j0 = 0; j0 < g.dphi; j0 += rows_pp) {
-      const int j = min(j0 + tid / LPR, g.dphi - 1);          // clamped: every lane loads, extra rows are dropped
-      const u32x4 t = gload128((const char*)pr.Wq + (((int64_t)gq * g.dphi + j) * g.d + seg * EPL) * sizeof(T));
-      const float bj = pr.bq[(int64_t)gq * g.dphi + j];
-      float x[EPL];
-      Elem<T>::unpack(make_uint4(t.x, t.y, t.z, t.w), x);
-      float dot = 0.f, nrm = 0.f;
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) {
-        const float qe = qf[seg * EPL + e];
-        dot = fmaf(x[e], qe, dot);
-        nrm = fmaf(qe, qe, nrm);
-      }
-      for (int o = LPR >> 1; o >= 1; o >>= 1) { dot += __shfl_xor(dot, o); nrm += __shfl_xor(nrm, o); }
-      if (j0 + tid / LPR < g.dphi && seg == 0) phiq[j] = expf(g.a * dot - g.c * nrm + bj);
-    }
-  }
   if (Ksel == 0) {
     if (tid == 0) *plan = SelPlan{-1, 0, 0, 0, 0};
     return;
@@ -423,11 +399,8 @@ __global__ __launch_bounds__(kSelThreads) void select_resolve_kernel(Geom g, con
 }
 
 void launch_select(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
-  dim3 hgrid(g.Hq, g.n_problems);
-  if (g.dtype == TKPHI_BF16)
-    TKPHI_LAUNCH(ST_PLAN, select_plan_kernel<uint16_t>, hgrid, dim3(kSelThreads), 0, s, g, probs, ws);
-  else
-    TKPHI_LAUNCH(ST_PLAN, select_plan_kernel<float>, hgrid, dim3(kSelThreads), 0, s, g, probs, ws);
+  dim3 pgrid((g.Hq * g.n_problems <= 128 ? 2 : 1) * g.Hq, g.n_problems);
+  TKPHI_LAUNCH(ST_PLAN, select_plan_kernel, pgrid, dim3(kSelThreads), 0, s, g, probs, ws);
   if (g.max_mid == 0 || g.max_K == 0) return;
   dim3 egrid((g.n_scan_chunks + 3) / 4, g.Hq, g.n_problems);
   if (g.interleave) TKPHI_LAUNCH(ST_EMIT, select_emit_kernel<true>, egrid, dim3(kThreads), 0, s, g, probs, ws);
