@@ -70,7 +70,11 @@ __global__ __launch_bounds__(kThreads) void score_mid_mfma_kernel(Geom g, const 
   if (pr.L < 1 || pr.L > g.max_L) return;
   const int n = mid_size(pr.L, g.n_sink, g.n_tail);
   const int n_chunks = (n + g.scan_chunk - 1) / g.scan_chunk;
-  if ((int)blockIdx.x >= n_chunks) return;
+  // Workgroups go to the 8 XCDs round-robin by linear index.  In a ragged batch the short
+  // sequences have no late chunks, so chunk indices are rotated per (head, problem): otherwise
+  // the XCDs that serve the early chunks get most of the work.
+  const int chunk = ((int)blockIdx.x + h + p * g.Hkv) % (int)gridDim.x;
+  if (chunk >= n_chunks) return;
   const int c1 = n;                     // units of different chunks never overlap
   const int G = g.G;
   char* blk = problem_block(g, ws, p);
@@ -100,7 +104,7 @@ __global__ __launch_bounds__(kThreads) void score_mid_mfma_kernel(Geom g, const 
 
   const int n_units = g.scan_chunk / (4 * TOK);      // host guarantees scan_unit == 4 * TOK
   for (int k = 0; k < n_units; ++k) {
-    const int base = chunk_unit_token(g, n_chunks, blockIdx.x, k) + wv * TOK;
+    const int base = chunk_unit_token(g, n_chunks, chunk, k) + wv * TOK;
     if (base >= c1) { if (g.interleave) break; else continue; }
     Frag a[TPI][KS];
 #pragma unroll
@@ -141,7 +145,7 @@ __global__ __launch_bounds__(kThreads) void score_mid_mfma_kernel(Geom g, const 
     __builtin_amdgcn_wave_barrier();
   }
   __syncthreads();
-  write_suffix_hist(lds_hist, (uint16_t*)(blk + g.off_hist) + ((size_t)blockIdx.x * g.Hq + (size_t)h * G) * kBins, G);
+  write_suffix_hist(lds_hist, (uint16_t*)(blk + g.off_hist) + ((size_t)chunk * g.Hq + (size_t)h * G) * kBins, G);
 }
 
 // ------------------------------------------------------------------------------------

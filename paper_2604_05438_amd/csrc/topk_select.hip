@@ -220,7 +220,9 @@ __global__ __launch_bounds__(kThreads) void select_emit_kernel(Geom g, const tkp
   const SelPlan plan = ((const SelPlan*)(blk + g.off_plan))[gq];
   const int bstar = plan.bstar;
   if (bstar < 0) return;
-  const int chunk = blockIdx.x * 4 + wv;
+  // (rotated per head and problem: in a ragged batch late chunks are rare, and workgroups go to
+  // the XCDs round-robin by linear index)
+  const int chunk = (((int)blockIdx.x + gq + p * g.Hq) % (int)gridDim.x) * 4 + wv;
   const int n_chunks = (n + g.scan_chunk - 1) / g.scan_chunk;
   if (chunk >= n_chunks) return;
   // the chunk's tokens in blocks of 256, in the order score_mid took them: block s lies in unit
