@@ -208,7 +208,7 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(Geom g, const 
 // ------------------------------------------------------------------------------------
 // emit: grid (ceil(n_scan_chunks / 4), Hq, n_problems), 256 threads; wavefront w <-> one chunk
 // ------------------------------------------------------------------------------------
-template <bool IL>     // IL: interleaved chunks (Geom::interleave)
+template <bool IL, int U>     // IL: interleaved chunks (Geom::interleave); U: loads in flight per lane
 __global__ __launch_bounds__(kThreads) void select_emit_kernel(Geom g, const tkphi_problem* __restrict__ probs,
                                                                char* __restrict__ ws) {
   const int gq = blockIdx.y, p = blockIdx.z, tid = threadIdx.x;
@@ -246,7 +246,6 @@ __global__ __launch_bounds__(kThreads) void select_emit_kernel(Geom g, const tkp
   int a_pos = choff[0], c_pos = choff[1];
 
   // 4 consecutive tokens per lane, 256 per wavefront instruction
-  constexpr int U = 2;                 // loads in flight per lane
   for (int s0 = 0; s0 < n_blocks; s0 += U) {
     if (block_token(s0) >= t1) break;
     float4 v[U];
@@ -405,8 +404,9 @@ void launch_select(const Geom& g, const tkphi_problem* probs, char* ws, hipStrea
   TKPHI_LAUNCH(ST_PLAN, select_plan_kernel, pgrid, dim3(kSelThreads), 0, s, g, probs, ws);
   if (g.max_mid == 0 || g.max_K == 0) return;
   dim3 egrid((g.n_scan_chunks + 3) / 4, g.Hq, g.n_problems);
-  if (g.interleave) TKPHI_LAUNCH(ST_EMIT, select_emit_kernel<true>, egrid, dim3(kThreads), 0, s, g, probs, ws);
-  else TKPHI_LAUNCH(ST_EMIT, select_emit_kernel<false>, egrid, dim3(kThreads), 0, s, g, probs, ws);
+  if (g.interleave) TKPHI_LAUNCH(ST_EMIT, (select_emit_kernel<true, 2>), egrid, dim3(kThreads), 0, s, g, probs, ws);
+  else if (g.scan_chunk >= 2048) TKPHI_LAUNCH(ST_EMIT, (select_emit_kernel<false, 4>), egrid, dim3(kThreads), 0, s, g, probs, ws);
+  else TKPHI_LAUNCH(ST_EMIT, (select_emit_kernel<false, 2>), egrid, dim3(kThreads), 0, s, g, probs, ws);
   // enough workgroups to spread the rank counting of one layer over the chip, one per head in big batches
   const int split = std::clamp(512 / std::max(1, g.Hq * g.n_problems), 1, kResolveSplitMax);
   dim3 rgrid(split, g.Hq, g.n_problems);
