@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 # HBM bytes per score_mid launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a
 # plain 256 MiB copy on the same counters), see profiles/decode_and_build_l3b_128k.md.
 # key: (workload, budget_bp) -> fetched + written bytes
-MEASURED_TRAFFIC = {("l3b_128k", 100): 269.10e6 + 15.72e6}
+MEASURED_TRAFFIC = {("l3b_128k", 100): 269.02e6 + 15.72e6}
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
 
