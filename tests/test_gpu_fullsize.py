@@ -61,3 +61,22 @@ def test_l3b_128k_budget_sweep():
                 a, _ = PU.check_output(y[g], r2["y"], f"K={k} head {g} (GPU's set)")
             worst = max(worst, a)
         print("l3b_128k K", k, "max_abs", worst)
+
+
+def test_million_token_context():
+    """One KV head with two query heads over 2^20 tokens (1024 score chunks: the select plan's
+    many-chunk path; K = 10485 retrieved tokens, 164 gather tiles; a boundary bin with thousands of
+    candidates: the radix paths of the resolve step)."""
+    import dataclasses
+    import parity_utils as PU
+    from paper_2604_05438_amd import harness as H
+    w = dataclasses.replace(I.WORKLOADS["l1b_32k"], name="long_1m", n_q_heads=2, n_kv_heads=1, L=1 << 20,
+                            n_needles=32, seed=31337)
+    k = I.mid_budget(w.L, w.budget_bp, w.n_sink, w.n_tail)
+    assert k == 10485
+    P = I.make_layer(w)
+    b = H.Batch(H.config_of(w), [P], [k], debug=True)
+    b.build(); b.decode()
+    assert b.status() == 0
+    rep = PU.check_layer(w, P, k, b, 0)
+    print("1M tokens", rep)
