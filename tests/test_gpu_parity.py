@@ -204,3 +204,47 @@ def test_bad_length_is_skipped_and_flagged():
     assert (b.result(1, "out") == -7.0).all()
     rep = PU.check_layer(w, layers[0], 9, b, 0, heads=[0, 31])
     print("bad length", rep)
+
+
+def test_decode_replays_from_a_hip_graph():
+    """Both entry points only enqueue kernels on the caller's stream: a captured decode step,
+    replayed several times with eager work and synchronisations in between, reproduces the eager
+    result bit for bit (and follows a changed query, since the table holds device pointers)."""
+    import torch
+    w = I.WORKLOADS["l3b_128k"]
+    L, k = 6000, 59
+    P = I.make_layer(w, L=L)
+    b = _batch(w, [P], [k])
+    b.build(); b.decode()
+    torch.cuda.synchronize()
+    y_eager = b.result(0, "out").copy()
+    idx_eager = b.result(0, "topk_idx").copy()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        b.decode()                                   # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            b.decode()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        b.dev[0]["out"].zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(b.result(0, "out"), y_eager), f"replay {rep} differs from the eager result"
+        assert np.array_equal(b.result(0, "topk_idx"), idx_eager)
+        # eager work between replays
+        b.decode()
+        torch.cuda.synchronize()
+    # a new query through the same captured graph
+    q2 = I.make_layer(w, L=L, query_index=5, with_kv=False)["q"]
+    b.set_query(0, q2)
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    y_graph = b.result(0, "out").copy()
+    b.decode()
+    torch.cuda.synchronize()
+    assert np.array_equal(b.result(0, "out"), y_graph)
+    assert not np.array_equal(y_graph, y_eager)
