@@ -303,15 +303,23 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
 }
 
 // ------------------------------------------------------------------------------------
-// gather, generic (any storage type, fp32 arithmetic): same grid; one retrieved token at a
-// time, threads j < dphi evaluate feature j, threads c < d own value channel c.
+// gather, generic (any storage type, fp32 arithmetic): same grid.  The key rows of the tile's
+// (at most 64) tokens are staged in LDS as fp32; thread (token t = tid % 64, group fg = tid / 64)
+// evaluates the features j = fg, fg + 4, ... of token t (Wk rows are read with 16-byte loads
+// that all 64 lanes of a wavefront share), so the 64 tokens advance together.
 // ------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(kThreads) void gather_kernel(Geom g, const tkphi_problem* __restrict__ probs,
                                                           char* __restrict__ ws) {
-  __shared__ float kf[kMaxDim];
-  __shared__ float red_f[4];
+  constexpr int EPL = Elem<T>::per16;
+  constexpr int KFS = 128 + 1;                     // padded row stride (d <= 128): conflict-free column reads
+  __shared__ float kf[kPairsPerWG * KFS];
   __shared__ float red[2 * kThreads * 8];
+  __shared__ int p_tok[kPairsPerWG];
+  __shared__ float p_s[kPairsPerWG], p_w[kPairsPerWG], p_z[kPairsPerWG];
+  __shared__ float z_part[4][kPairsPerWG];
+  __shared__ float acc_part[2 * 128 + 4];
+  __shared__ float sh_m;
   const int tile = blockIdx.x, gq = blockIdx.y, p = blockIdx.z, tid = threadIdx.x;
   const tkphi_problem pr = probs[p];
   if (pr.L < 1 || pr.L > g.max_L) return;
@@ -324,38 +332,70 @@ __global__ __launch_bounds__(kThreads) void gather_kernel(Geom g, const tkphi_pr
   if (i0 >= Ksel) return;
   const int cnt = min(kPairsPerWG, Ksel - i0);
   const int h = gq / g.G, d = g.d, dphi = g.dphi;
-  const int32_t* sel_idx = (const int32_t*)(blk + g.off_selidx) + (size_t)gq * g.max_K + i0;
-  const float* sel_s = (const float*)(blk + g.off_selscore) + (size_t)gq * g.max_K + i0;
   const float* phiq = (const float*)(blk + g.off_phiq) + (size_t)gq * dphi;
   const int64_t head_off = (int64_t)h * pr.stride_head;
 
-  float m = -INFINITY;
-  for (int i = 0; i < cnt; ++i) m = fmaxf(m, sel_s[i]);
-  float nu = 0.f, zv = 0.f, Z = 0.f, zsum = 0.f;
-  for (int i = 0; i < cnt; ++i) {
-    const int64_t row_off = head_off + (int64_t)(g.n_sink + min(max(sel_idx[i], 0), n - 1)) * pr.stride_tok;
-    __syncthreads();                       // the previous token's readers of kf are done
-    if (tid < d) kf[tid] = Elem<T>::load1(pr.K, row_off + tid);
-    const float vc = tid < d ? Elem<T>::load1(pr.V, row_off + tid) : 0.f;
-    __syncthreads();
-    float zj = 0.f;
-    if (tid < dphi) {
-      float dot = 0.f, nrm = 0.f;
-      const int64_t wbase = ((int64_t)h * dphi + tid) * d;
-      for (int c = 0; c < d; ++c) {
-        const float x = kf[c];
-        dot = fmaf(Elem<T>::load1(pr.Wk, wbase + c), x, dot);
-        nrm = fmaf(x, x, nrm);
-      }
-      zj = expf(g.a * dot - g.c * nrm + pr.bk[(int64_t)h * dphi + tid]) * phiq[tid];
-    }
-    const float z = block_sum(zj, red_f);
-    const float w = __expf(sel_s[i] - m);
-    nu = fmaf(w, vc, nu); Z += w;
-    zv = fmaf(z, vc, zv); zsum += z;
+  if (tid < kPairsPerWG) {
+    const int i = i0 + min(tid, cnt - 1);
+    p_tok[tid] = g.n_sink + min(max(((const int32_t*)(blk + g.off_selidx))[(size_t)gq * g.max_K + i], 0), n - 1);
+    p_s[tid] = tid < cnt ? ((const float*)(blk + g.off_selscore))[(size_t)gq * g.max_K + i] : -INFINITY;
   }
-  if (tid == 0) { part[0] = m; part[1] = Z; part[2] = zsum; part[3] = (float)cnt; }
-  if (tid < d) { part[4 + tid] = nu; part[4 + d + tid] = zv; }
+  for (int i = tid; i < 2 * d + 4; i += kThreads) acc_part[i] = 0.f;
+  __syncthreads();
+  {
+    // key rows -> LDS (fp32): 16-byte pieces, (row, segment) pairs dealt over the threads
+    const int SEGS = d / EPL;
+    for (int idx = tid; idx < kPairsPerWG * SEGS; idx += kThreads) {
+      const int row = idx / SEGS, seg = idx % SEGS;
+      const u32x4 t = gload128((const char*)pr.K + (head_off + (int64_t)p_tok[row] * pr.stride_tok + seg * EPL) * sizeof(T));
+      float x[EPL];
+      Elem<T>::unpack(make_uint4(t.x, t.y, t.z, t.w), x);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) kf[row * KFS + seg * EPL + e] = x[e];
+    }
+  }
+  __syncthreads();
+  if (tid < 64) {                                  // m_loc = max score of the tile
+    float m = p_s[tid];
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if (tid == 0) sh_m = m;
+  }
+  {
+    // z_t = phi_q . phi_k(k_t): thread (t, fg) sums its features in ascending order
+    const int t = tid % kPairsPerWG, fg = tid / kPairsPerWG;
+    const float* kt = kf + t * KFS;
+    float nrm = 0.f;
+    for (int c = 0; c < d; ++c) nrm = fmaf(kt[c], kt[c], nrm);
+    float z = 0.f;
+    for (int j = fg; j < dphi; j += kThreads / kPairsPerWG) {
+      const char* wrow = (const char*)pr.Wk + ((int64_t)h * dphi + j) * d * sizeof(T);
+      float dot = 0.f;
+      for (int c0 = 0; c0 < d; c0 += EPL) {
+        const u32x4 wv4 = gload128(wrow + c0 * sizeof(T));
+        float wx[EPL];
+        Elem<T>::unpack(make_uint4(wv4.x, wv4.y, wv4.z, wv4.w), wx);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) dot = fmaf(wx[e], kt[c0 + e], dot);
+      }
+      z = fmaf(expf(g.a * dot - g.c * nrm + pr.bk[(int64_t)h * dphi + j]), phiq[j], z);
+    }
+    z_part[fg][t] = z;
+  }
+  __syncthreads();
+  if (tid < kPairsPerWG) {
+    p_z[tid] = tid < cnt ? (z_part[0][tid] + z_part[1][tid]) + (z_part[2][tid] + z_part[3][tid]) : 0.f;
+    p_w[tid] = tid < cnt ? __expf(p_s[tid] - sh_m) : 0.f;
+  }
+  __syncthreads();
+
+  weighted_value_sums<T>(g, pr, head_off, p_tok, p_w, p_z, cnt, red, acc_part, true);
+  if (tid < d) { part[4 + tid] = acc_part[4 + tid]; part[4 + d + tid] = acc_part[4 + d + tid]; }
+  if (tid == 0) {
+    float Z = 0.f, zs = 0.f;
+    for (int i = 0; i < cnt; ++i) { Z += p_w[i]; zs += p_z[i]; }
+    part[0] = sh_m; part[1] = Z; part[2] = zs; part[3] = (float)cnt;
+  }
 }
 
 // ------------------------------------------------------------------------------------
