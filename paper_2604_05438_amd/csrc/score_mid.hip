@@ -185,37 +185,45 @@ __global__ __launch_bounds__(kThreads) void score_mid_kernel(Geom g, const tkphi
   const char* Kb = (const char*)pr.K + ((int64_t)h * pr.stride_head + (int64_t)g.n_sink * pr.stride_tok) * sizeof(T);
   float* scores = (float*)(blk + g.off_scores);
 
-  for (int base = c0; base < c1; base += RPI) {
-    const int row = base + rsub;
-    const bool valid = row < c1;
-    const int rr = valid ? row : c1 - 1;
-    const uint4 v = *(const uint4*)(Kb + ((int64_t)rr * pr.stride_tok + seg * EPL) * sizeof(T));
-    float x[EPL];
-    Elem<T>::unpack(v, x);
-    float acc[kMaxGroup];
+  constexpr int UNR = 8;               // row loads in flight per thread
+  for (int base0 = c0; base0 < c1; base0 += RPI * UNR) {
+    u32x4 v[UNR];
 #pragma unroll
-    for (int gl = 0; gl < kMaxGroup; ++gl) {
-      float s = 0.f;
-      if (gl < G) {
+    for (int u = 0; u < UNR; ++u) {
+      const int rr = min(base0 + u * RPI + rsub, c1 - 1);      // clamped: every lane loads
+      v[u] = gload128(Kb + ((int64_t)rr * pr.stride_tok + seg * EPL) * sizeof(T));
+    }
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) s = fmaf(x[e], qreg[gl][e], s);
+    for (int u = 0; u < UNR; ++u) {
+      const int row = base0 + u * RPI + rsub;
+      const bool valid = row < c1;
+      float x[EPL];
+      Elem<T>::unpack(make_uint4(v[u].x, v[u].y, v[u].z, v[u].w), x);
+      float acc[kMaxGroup];
+#pragma unroll
+      for (int gl = 0; gl < kMaxGroup; ++gl) {
+        float s = 0.f;
+        if (gl < G) {
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) s = fmaf(x[e], qreg[gl][e], s);
+        }
+        acc[gl] = s;
       }
-      acc[gl] = s;
-    }
-    for (int o = LPR >> 1; o >= 1; o >>= 1) {
+      for (int o = LPR >> 1; o >= 1; o >>= 1) {
 #pragma unroll
-      for (int gl = 0; gl < kMaxGroup; ++gl)
-        if (gl < G) acc[gl] += __shfl_xor(acc[gl], o);
-    }
-    if (valid && seg < G) {           // lane `seg` of the row finishes query head `seg`
-      float s = acc[0];
+        for (int gl = 0; gl < kMaxGroup; ++gl)
+          if (gl < G) acc[gl] += __shfl_xor(acc[gl], o);
+      }
+      if (valid && seg < G) {           // lane `seg` of the row finishes query head `seg`
+        float s = acc[0];
 #pragma unroll
-      for (int gl = 1; gl < kMaxGroup; ++gl) s = (seg == gl) ? acc[gl] : s;
-      s = s * g.score_scale + 0.0f;   // + 0.0f turns -0 into +0 so equal scores have equal keys
-      const int gq = h * G + seg;
-      scores[(size_t)gq * g.mid_stride + row] = s;
-      if (pr.scores) pr.scores[(size_t)gq * n + row] = s;
-      atomicAdd(&lds_hist[seg * kBins + key_bin(score_key(s))], 1u);
+        for (int gl = 1; gl < kMaxGroup; ++gl) s = (seg == gl) ? acc[gl] : s;
+        s = s * g.score_scale + 0.0f;   // + 0.0f turns -0 into +0 so equal scores have equal keys
+        const int gq = h * G + seg;
+        scores[(size_t)gq * g.mid_stride + row] = s;
+        if (pr.scores) pr.scores[(size_t)gq * n + row] = s;
+        atomicAdd(&lds_hist[seg * kBins + key_bin(score_key(s))], 1u);
+      }
     }
   }
   __syncthreads();
