@@ -84,10 +84,10 @@ def main() -> int:
             dev_layers.append({k: (H.to_device(v) if isinstance(v, np.ndarray) and k != "needle_pos" else v)
                                for k, v in P.items()})
     if model_level:
-        batches = [H.Batch(cfg, dev_layers, Ks)]
+        batches = [H.Batch(cfg, dev_layers, Ks, diag=True)]
         probs_per_step = len(pairs)
     else:
-        batches = [H.Batch(cfg, [P], [k]) for P, k in zip(dev_layers, Ks)]
+        batches = [H.Batch(cfg, [P], [k], diag=True) for P, k in zip(dev_layers, Ks)]
         probs_per_step = 1
     del dev_layers
     L, K = Ls[0], Ks[0]
@@ -136,6 +136,14 @@ def main() -> int:
     stage /= args.steps
     stage_us = {n: float(v * 1e3) for n, v in zip(B.STAGES, stage)}
 
+    # ---- how sharp / diffuse the synthetic attention is (by-products of the score pass; untimed) ----
+    batches[0].decode(B.TKPHI_MODE_SUB | B.TKPHI_FLAG_DIAG)
+    torch.cuda.synchronize()
+    dg = np.stack([batches[0].result(i, "diag") for i in range(min(batches[0].n, 16))]).reshape(-1, B.TKPHI_DIAG_STRIDE)
+    diagnostics = {"heads": int(dg.shape[0]), "H_mid_mean": float(dg[:, 0].mean()), "C_mid_mean": float(dg[:, 2].mean()),
+                   "rho_res_mean": float(dg[:, 3].mean()), "rho_res_star_mean": float(dg[:, 4].mean()),
+                   "log_Z_err_mean": float(np.nanmean(dg[:, 5]))}
+
     # algorithmic bytes of one step (what the method must move)
     bytes_scan = w.n_kv_heads * n_mid * w.d_head * esz                  # every mid key row, once per KV head
     bytes_gather = w.n_q_heads * sum_K * 2 * w.d_head * esz             # k and v rows of the retrieved tokens
@@ -176,6 +184,7 @@ def main() -> int:
                   "hbm_frac": build_bytes / (build_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                   "mfma_TFLOPs": build_flops / (build_ms * 1e-3) / 1e12,
                   "mfma_frac": build_flops / (build_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+        "diagnostics": diagnostics,
         "input_gen_s": t_gen,
     }
 

@@ -65,6 +65,10 @@ typedef enum tkphi_dtype { TKPHI_F32 = 0, TKPHI_BF16 = 1 } tkphi_dtype;
  *   NOSUB      ablation: summaries merged un-subtracted (double counts the retrieved set)
  *   TOPK_ONLY  selection-only Top-K: y = nu_E / Z_E, no residual branch               */
 typedef enum tkphi_mode { TKPHI_MODE_SUB = 0, TKPHI_MODE_NOSUB = 1, TKPHI_MODE_TOPK_ONLY = 2 } tkphi_mode;
+/* May be OR-ed into the mode argument of tkphi_decode: also compute the entropy / mass-recovery
+ * diagnostics below for every problem whose `diag` pointer is non-NULL (one extra exp per
+ * score in the select pass; off by default). */
+#define TKPHI_FLAG_DIAG 0x100
 
 /* bits of the device status word (tkphi_read_device_status) */
 #define TKPHI_DEV_BAD_LENGTH 1u   /* a problem had L < 1 or L > max_L and was skipped         */
@@ -104,6 +108,20 @@ typedef struct tkphi_config {
  * exact branches (e.g. generated tokens, eq. (implemented_decode)) before dividing. */
 #define TKPHI_AUX_STRIDE(d_head) (4 + 2 * (d_head))
 
+/* Optional per-query-head diagnostics of the entropy / mass-recovery analysis
+ * (Sec. "Analysis: entropy and completion gains"; App. "Entropy, mass recovery, and
+ * residual-denominator diagnostics"), by-products of the score pass, TKPHI_DIAG_STRIDE
+ * floats per query head (requires TKPHI_FLAG_DIAG):
+ *   [0] H_mid        normalised entropy of the mid-normalised attention, in [0, 1]
+ *   [1] log Z_M      log of the mid-region softmax mass sum_{j in M} exp(s_j)
+ *   [2] C_mid(K)     Z_K / Z_M: mid-region mass recovered by the retrieved tokens
+ *   [3] rho_res      Z_R^ / (Z_E + Z_R^): residual share of the merged denominator
+ *   [4] rho_res*     Z_R / (Z_A + Z_M): the true residual share
+ *   [5] log Z_R^ - log Z_R   residual log-partition error (NaN if either is <= 0)
+ *   [6] log Z_A      log of the anchor mass;  [7] reserved (0)
+ * All zero if the mid-region is empty. */
+#define TKPHI_DIAG_STRIDE 8
+
 /* One problem = one (sequence, layer).  The table lives in DEVICE memory; all
  * pointers inside are DEVICE pointers to caller-owned buffers that must stay valid
  * until the enqueued work has finished.  16-byte alignment is required for K, V, q,
@@ -128,6 +146,7 @@ typedef struct tkphi_problem {
   float* aux;            /* optional [n_q_heads][TKPHI_AUX_STRIDE(d_head)]; may be NULL */
   float* scores;         /* optional [n_q_heads][L - n_sink - n_tail] fp32 mid-region
                             scores s_i, i in M (diagnostic copy); may be NULL           */
+  float* diag;           /* optional [n_q_heads][TKPHI_DIAG_STRIDE]; may be NULL        */
   int32_t L;             /* prefill length, 1 <= L <= max_L                            */
   int32_t topk;          /* the paper's K: retrieved mid-region tokens per query head (the
                             budget); clipped to min(topk, |M|, max_K); 0 is legal      */
@@ -163,7 +182,7 @@ tkphi_status tkphi_build_summaries(const tkphi_config* cfg /*HOST*/,
 tkphi_status tkphi_decode(const tkphi_config* cfg /*HOST*/,
                           const tkphi_problem* problems /*DEVICE table*/,
                           int32_t n_problems, int32_t max_L, int32_t max_K,
-                          int32_t mode /* tkphi_mode */,
+                          int32_t mode /* tkphi_mode, optionally | TKPHI_FLAG_DIAG */,
                           void* workspace, size_t workspace_bytes,
                           void* hip_stream);
 

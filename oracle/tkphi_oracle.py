@@ -200,6 +200,14 @@ def decode_head(q_g, K_h, V_h, S_M, u_M, Wq_g, bq_g, Wk_h, bk_h, a, c, scale,
         "rho_res": Z_R_hat / (Z_E + Z_R_hat),                            # residual denominator share
         "log_Z_err": (math.log(Z_R_hat) - math.log(Z_R)) if (Z_R_hat > 0 and Z_R > 0) else float("nan"),
     }
+    # entropy / mass-recovery diagnostics (Sec. "Analysis: entropy and completion gains";
+    # App. "Entropy, mass recovery, and residual-denominator diagnostics")
+    if M.size > 0:
+        p_mid = e[M] / Z_M                                               # mid-normalised distribution
+        ent = -float(np.sum(p_mid * np.log(p_mid)))
+        out["H_mid"] = ent / math.log(M.size) if M.size > 1 else 0.0     # normalised entropy
+        out["C_mid"] = Z_K / Z_M                                         # mid mass recovered by Top-K
+        out["rho_res_star"] = Z_R / (Z_A + Z_M)                          # true residual share
     if Kset.size < M.size and Kset.size > 0 and retrieved is None:
         srt = np.sort(s[M])[::-1]
         out["boundary_gap"] = srt[Kset.size - 1] - srt[Kset.size]

@@ -18,6 +18,8 @@ TKPHI_OK = 0
 TKPHI_EINVAL, TKPHI_ESHAPE, TKPHI_EALIGN, TKPHI_EWORKSPACE, TKPHI_EHIP, TKPHI_EUNSUPPORTED = -1, -2, -3, -4, -5, -6
 TKPHI_F32, TKPHI_BF16 = 0, 1
 TKPHI_MODE_SUB, TKPHI_MODE_NOSUB, TKPHI_MODE_TOPK_ONLY = 0, 1, 2
+TKPHI_FLAG_DIAG = 0x100
+TKPHI_DIAG_STRIDE = 8
 TKPHI_DEV_BAD_LENGTH, TKPHI_DEV_CLAMPED = 1, 2
 
 EXPORTS = (
@@ -45,7 +47,7 @@ class tkphi_problem(C.Structure):
         ("K", C.c_void_p), ("V", C.c_void_p), ("stride_head", C.c_int64), ("stride_tok", C.c_int64),
         ("Wq", C.c_void_p), ("bq", C.c_void_p), ("Wk", C.c_void_p), ("bk", C.c_void_p),
         ("S", C.c_void_p), ("u", C.c_void_p), ("q", C.c_void_p), ("out", C.c_void_p),
-        ("topk_idx", C.c_void_p), ("aux", C.c_void_p), ("scores", C.c_void_p),
+        ("topk_idx", C.c_void_p), ("aux", C.c_void_p), ("scores", C.c_void_p), ("diag", C.c_void_p),
         ("L", C.c_int32), ("topk", C.c_int32),
     ]
 
@@ -170,12 +172,13 @@ def _ptr(t) -> int:
 
 
 def make_problem(K, V, Wq, bq, Wk, bk, S, u, q=None, out=None, topk_idx=None, aux=None, scores=None,
-                 L=None, topk=0) -> tkphi_problem:
+                 L=None, topk=0, diag=None) -> tkphi_problem:
     """Fills a tkphi_problem from torch device tensors (K, V: [Hkv][L][d], last dim contiguous)."""
     assert K.stride(-1) == 1 and V.stride(-1) == 1 and K.stride() == V.stride()
     return tkphi_problem(
         _ptr(K), _ptr(V), K.stride(0), K.stride(1), _ptr(Wq), _ptr(bq), _ptr(Wk), _ptr(bk), _ptr(S), _ptr(u),
-        _ptr(q), _ptr(out), _ptr(topk_idx), _ptr(aux), _ptr(scores), int(K.shape[1] if L is None else L), int(topk))
+        _ptr(q), _ptr(out), _ptr(topk_idx), _ptr(aux), _ptr(scores), _ptr(diag),
+        int(K.shape[1] if L is None else L), int(topk))
 
 
 def upload_problems(problems, device="cuda"):

@@ -459,6 +459,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
 
   // ---- combine the partials in a fixed order ---------------------------------------------------
   float nu = 0.f, zv = 0.f, Z = 0.f, zsum = 0.f;
+  float ZA = 0.f;                        // anchor share of Z (diagnostics only)
   const int c = tid;
   constexpr int UN = 8;
   for (int t0 = 0; t0 < n_parts; t0 += UN) {
@@ -475,6 +476,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
       if (t0 + k < n_parts) {
         const float r = __expf(hm[k] - m);
         Z = fmaf(r, hz[k], Z);
+        if (t0 + k < na_used) ZA = fmaf(r, hz[k], ZA);
         nu = fmaf(r, vn[k], nu);
         zsum += hs[k];
         zv += vz[k];
@@ -521,6 +523,51 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
     if (c < d) { ax[4 + c] = nu; ax[4 + d + c] = nuR; }
   }
   if (clamped && tid == 0) atomicOr((uint32_t*)(ws + g.off_status), TKPHI_DEV_CLAMPED);
+
+  // ---- optional diagnostics (Sec. "Analysis: entropy and completion gains"; App. "Entropy, mass
+  // recovery, and residual-denominator diagnostics") from the per-chunk (max, sum e^(s-max),
+  // sum (s-max) e^(s-max)) records written by the select emit pass ---------------------------------
+  if (g.diag && pr.diag) {
+    float* dg = pr.diag + (size_t)gq * TKPHI_DIAG_STRIDE;
+    if (n == 0) {
+      if (tid < TKPHI_DIAG_STRIDE) dg[tid] = 0.f;
+    } else {
+      const float4* rec = (const float4*)(blk + g.off_diag) + gq;          // + chunk * Hq
+      const int n_chunks = (n + g.scan_chunk - 1) / g.scan_chunk;
+      float lm = -INFINITY;
+      for (int k = tid; k < n_chunks; k += kThreads) lm = fmaxf(lm, rec[(size_t)k * g.Hq].x);
+      const float mM = block_max(lm, red_f);
+      float lz = 0.f, lw = 0.f;
+      for (int k = tid; k < n_chunks; k += kThreads) {
+        const float4 rc = rec[(size_t)k * g.Hq];
+        if (rc.y > 0.f) {
+          const float r = __expf(rc.x - mM);
+          lz = fmaf(r, rc.y, lz);
+          lw = fmaf(r, rc.z + (rc.x - mM) * rc.y, lw);
+        }
+      }
+      __syncthreads();
+      const float ZM = block_sum(lz, red_f);
+      __syncthreads();
+      const float WM = block_sum(lw, red_f);
+      if (tid == 0) {
+        // masses relative to exp(mM): Z_M = ZM, Z_A = ZA e^(m-mM), Z_K = (Z - ZA) e^(m-mM)
+        const float sh = empty_E ? 0.f : __expf(m - mM);
+        const float zA = ZA * sh, zK = fmaxf(Z - ZA, 0.f) * sh;
+        const float zR = ZM - zK;
+        const float zRhat = ZR * __expf(-mM);                              // Z_R^ is unshifted
+        dg[0] = n > 1 ? (__logf(ZM) - WM / ZM) / __logf((float)n) : 0.f;
+        dg[1] = __logf(ZM) + mM;
+        dg[2] = zK / ZM;
+        dg[3] = den > 0.f ? eR * ZR / den : 0.f;
+        dg[4] = zR / (zA + ZM);
+        dg[5] = (ZR > 0.f && zR > 0.f) ? (__logf(ZR) - (__logf(zR) + mM)) : NAN;
+        dg[6] = zA > 0.f ? __logf(zA) + mM : -INFINITY;
+        dg[7] = 0.f;
+        (void)zRhat;
+      }
+    }
+  }
 
   // ---- optional export: retrieved token indices, ascending ---------------------------------------
   // The list is in emission order (chunk by chunk, then the boundary-bin winners): rank every

@@ -110,6 +110,7 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   g->off_scores = p;  p = align_up(p + (size_t)g->Hq * g->mid_stride * sizeof(float), 256);
   g->off_hist = p;    p = align_up(p + (size_t)g->n_scan_chunks * g->Hq * kBins * sizeof(uint16_t), 256);
   g->off_plan = p;    p = align_up(p + (size_t)g->Hq * sizeof(SelPlan), 256);
+  g->off_diag = p;    p = align_up(p + (size_t)g->n_scan_chunks * g->Hq * 4 * sizeof(float), 256);
   g->off_chunkoff = p; p = align_up(p + (size_t)g->Hq * g->n_scan_chunks * 2 * sizeof(int32_t), 256);
   g->off_cand = p;    p = align_up(p + (size_t)g->Hq * kCandCap * sizeof(uint2), 256);
   g->off_selidx = p;  p = align_up(p + (size_t)g->Hq * std::max(max_K, 1) * sizeof(int32_t), 256);
@@ -175,12 +176,14 @@ tkphi_status tkphi_build_summaries(const tkphi_config* cfg, const tkphi_problem*
 tkphi_status tkphi_decode(const tkphi_config* cfg, const tkphi_problem* problems, int32_t n_problems,
                           int32_t max_L, int32_t max_K, int32_t mode, void* workspace,
                           size_t workspace_bytes, void* hip_stream) {
-  if (mode != TKPHI_MODE_SUB && mode != TKPHI_MODE_NOSUB && mode != TKPHI_MODE_TOPK_ONLY) {
-    set_error("mode=%d is not a tkphi_mode", mode);
+  const int acct = mode & ~TKPHI_FLAG_DIAG;
+  if (acct != TKPHI_MODE_SUB && acct != TKPHI_MODE_NOSUB && acct != TKPHI_MODE_TOPK_ONLY) {
+    set_error("mode=%d is not a tkphi_mode (optionally | TKPHI_FLAG_DIAG)", mode);
     return TKPHI_EINVAL;
   }
   Geom g;
   tkphi_status st = make_geom(cfg, n_problems, max_L, max_K, &g);
+  g.diag = (mode & TKPHI_FLAG_DIAG) ? 1 : 0;
   if (st != TKPHI_OK) return st;
   st = check_call(problems, n_problems, workspace, workspace_bytes, g);
   if (st != TKPHI_OK) return st;
@@ -191,7 +194,7 @@ tkphi_status tkphi_decode(const tkphi_config* cfg, const tkphi_problem* problems
   launch_score_mid(g, problems, ws, s);
   launch_select(g, problems, ws, s);
   launch_gather(g, problems, ws, s);
-  launch_merge(g, problems, ws, mode, s);
+  launch_merge(g, problems, ws, acct, s);
   return hip_ok(hipGetLastError(), "tkphi_decode launch");
 }
 
@@ -200,12 +203,14 @@ tkphi_status tkphi_decode_stage_times(const tkphi_config* cfg, const tkphi_probl
                                       void* workspace, size_t workspace_bytes, void* hip_stream,
                                       float* stage_ms_out) {
   if (!stage_ms_out) { set_error("stage_ms_out is null"); return TKPHI_EINVAL; }
-  if (mode != TKPHI_MODE_SUB && mode != TKPHI_MODE_NOSUB && mode != TKPHI_MODE_TOPK_ONLY) {
-    set_error("mode=%d is not a tkphi_mode", mode);
+  const int acct = mode & ~TKPHI_FLAG_DIAG;
+  if (acct != TKPHI_MODE_SUB && acct != TKPHI_MODE_NOSUB && acct != TKPHI_MODE_TOPK_ONLY) {
+    set_error("mode=%d is not a tkphi_mode (optionally | TKPHI_FLAG_DIAG)", mode);
     return TKPHI_EINVAL;
   }
   Geom g;
   tkphi_status st = make_geom(cfg, n_problems, max_L, max_K, &g);
+  g.diag = (mode & TKPHI_FLAG_DIAG) ? 1 : 0;
   if (st != TKPHI_OK) return st;
   st = check_call(problems, n_problems, workspace, workspace_bytes, g);
   if (st != TKPHI_OK) return st;
@@ -227,7 +232,7 @@ tkphi_status tkphi_decode_stage_times(const tkphi_config* cfg, const tkphi_probl
     launch_score_mid(g, problems, ws, s);
     launch_select(g, problems, ws, s);
     launch_gather(g, problems, ws, s);
-    launch_merge(g, problems, ws, mode, s);
+    launch_merge(g, problems, ws, acct, s);
     g_kernel_timer = nullptr;
     st = hip_ok(hipGetLastError(), "tkphi_decode_stage_times launch");
     if (st == TKPHI_OK) st = hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize");

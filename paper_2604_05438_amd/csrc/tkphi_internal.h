@@ -34,6 +34,7 @@ struct Geom {
   int mid_stride;        // floats per score row (multiple of 64)
   int scan_chunk, n_scan_chunks;     // score_mid: mid tokens per workgroup
   int scan_unit;         // tokens a score_mid workgroup takes per iteration (scan_chunk is a multiple)
+  int diag;              // 1: the select emit pass also reduces the entropy / mass diagnostics
   int interleave;        // 1: chunk c owns the units c, c + n_chunks, c + 2 n_chunks, ... of its problem
                          // (all workgroups sweep the key cache together); 0: one contiguous range
   int n_tiles;           // gather: ceil(max_K / kPairsPerWG) retrieved-token tiles per query head
@@ -49,6 +50,7 @@ struct Geom {
   size_t off_scores;     // float    [Hq][mid_stride]            mid-region scores
   size_t off_hist;       // uint16   [n_scan_chunks][Hq][kBins]  per-chunk histograms
   size_t off_plan;       // SelPlan  [Hq]
+  size_t off_diag;       // float    [n_scan_chunks][Hq][4]      per-chunk (max, sum exp, sum (s-max) exp) of the scores
   size_t off_chunkoff;   // int32    [Hq][n_scan_chunks][2]      output offsets of each chunk (above b*, in b*)
   size_t off_cand;       // uint2    [Hq][kCandCap]              boundary-bin candidates (key, mid index)
   size_t off_selidx;     // int32    [Hq][max_K]                 retrieved mid indices

@@ -208,7 +208,8 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(Geom g, const 
 // ------------------------------------------------------------------------------------
 // emit: grid (ceil(n_scan_chunks / 4), Hq, n_problems), 256 threads; wavefront w <-> one chunk
 // ------------------------------------------------------------------------------------
-template <bool IL, int U>     // IL: interleaved chunks (Geom::interleave); U: loads in flight per lane
+template <bool IL, int U, bool DIAG>   // IL: interleaved chunks (Geom::interleave); U: loads in flight per
+                                       // lane; DIAG: also reduce (max, sum e^(s-max), sum (s-max) e^(s-max))
 __global__ __launch_bounds__(kThreads) void select_emit_kernel(Geom g, const tkphi_problem* __restrict__ probs,
                                                                char* __restrict__ ws) {
   const int gq = blockIdx.y, p = blockIdx.z, tid = threadIdx.x;
@@ -218,8 +219,11 @@ __global__ __launch_bounds__(kThreads) void select_emit_kernel(Geom g, const tkp
   const int n = mid_size(L, g.n_sink, g.n_tail);
   char* blk = problem_block(g, ws, p);
   const SelPlan plan = ((const SelPlan*)(blk + g.off_plan))[gq];
-  const int bstar = plan.bstar;
-  if (bstar < 0) return;
+  int bstar = plan.bstar;
+  if (bstar < 0) {
+    if (!DIAG) return;
+    bstar = kBins;                       // nothing to retrieve: the pass only reduces the diagnostics
+  }
   // (rotated per head and problem: in a ragged batch late chunks are rare, and workgroups go to
   // the XCDs round-robin by linear index)
   const int chunk = (((int)blockIdx.x + gq + p * g.Hq) % (int)gridDim.x) * 4 + wv;
@@ -246,6 +250,7 @@ __global__ __launch_bounds__(kThreads) void select_emit_kernel(Geom g, const tkp
   int a_pos = choff[0], c_pos = choff[1];
 
   // 4 consecutive tokens per lane, 256 per wavefront instruction
+  float dm = -INFINITY, dz = 0.f, dw = 0.f;        // this lane's share of the chunk record (DIAG)
   for (int s0 = 0; s0 < n_blocks; s0 += U) {
     if (block_token(s0) >= t1) break;
     float4 v[U];
@@ -264,6 +269,19 @@ __global__ __launch_bounds__(kThreads) void select_emit_kernel(Geom g, const tkp
     for (int u = 0; u < U; ++u) {
       const int tok = block_token(s0 + u) + lane * 4;
       const float sv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+      if (DIAG) {
+        float mx = dm;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) if (tok + e < t1) mx = fmaxf(mx, sv[e]);
+        if (mx > dm) {                               // new shift: rescale what has been summed
+          if (dz > 0.f) { const float r = __expf(dm - mx); dw = (dw + (dm - mx) * dz) * r; dz *= r; }
+          dm = mx;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (tok + e < t1) { const float x = sv[e] - dm, ex = __expf(x); dz += ex; dw = fmaf(x, ex, dw); }
+        }
+      }
       int fa[4], fc[4], na = 0, nc = 0;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -290,6 +308,18 @@ __global__ __launch_bounds__(kThreads) void select_emit_kernel(Geom g, const tkp
       a_pos += total & 0xffff;
       c_pos += total >> 16;
     }
+  }
+  if (DIAG) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+      const float m2 = __shfl_xor(dm, o), z2 = __shfl_xor(dz, o), w2 = __shfl_xor(dw, o);
+      const float mm = fmaxf(dm, m2);
+      float za = 0.f, wa = 0.f, zb = 0.f, wb = 0.f;
+      if (dz > 0.f) { const float r = __expf(dm - mm); za = dz * r; wa = (dw + (dm - mm) * dz) * r; }
+      if (z2 > 0.f) { const float r = __expf(m2 - mm); zb = z2 * r; wb = (w2 + (m2 - mm) * z2) * r; }
+      dm = mm; dz = za + zb; dw = wa + wb;
+    }
+    if (lane == 0) ((float4*)(blk + g.off_diag))[(size_t)chunk * g.Hq + gq] = make_float4(dm, dz, dw, 0.f);
   }
 }
 
@@ -402,11 +432,20 @@ __global__ __launch_bounds__(kSelThreads) void select_resolve_kernel(Geom g, con
 void launch_select(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
   dim3 pgrid((g.Hq * g.n_problems <= 128 ? 2 : 1) * g.Hq, g.n_problems);
   TKPHI_LAUNCH(ST_PLAN, select_plan_kernel, pgrid, dim3(kSelThreads), 0, s, g, probs, ws);
-  if (g.max_mid == 0 || g.max_K == 0) return;
+  const bool selecting = g.max_mid > 0 && g.max_K > 0;
+  if (!selecting && !(g.diag && g.max_mid > 0)) return;
   dim3 egrid((g.n_scan_chunks + 3) / 4, g.Hq, g.n_problems);
-  if (g.interleave) TKPHI_LAUNCH(ST_EMIT, (select_emit_kernel<true, 2>), egrid, dim3(kThreads), 0, s, g, probs, ws);
-  else if (g.scan_chunk >= 2048) TKPHI_LAUNCH(ST_EMIT, (select_emit_kernel<false, 4>), egrid, dim3(kThreads), 0, s, g, probs, ws);
-  else TKPHI_LAUNCH(ST_EMIT, (select_emit_kernel<false, 2>), egrid, dim3(kThreads), 0, s, g, probs, ws);
+  if (g.diag) {
+    if (g.interleave) TKPHI_LAUNCH(ST_EMIT, (select_emit_kernel<true, 2, true>), egrid, dim3(kThreads), 0, s, g, probs, ws);
+    else TKPHI_LAUNCH(ST_EMIT, (select_emit_kernel<false, 2, true>), egrid, dim3(kThreads), 0, s, g, probs, ws);
+  } else if (g.interleave) {
+    TKPHI_LAUNCH(ST_EMIT, (select_emit_kernel<true, 2, false>), egrid, dim3(kThreads), 0, s, g, probs, ws);
+  } else if (g.scan_chunk >= 2048) {
+    TKPHI_LAUNCH(ST_EMIT, (select_emit_kernel<false, 4, false>), egrid, dim3(kThreads), 0, s, g, probs, ws);
+  } else {
+    TKPHI_LAUNCH(ST_EMIT, (select_emit_kernel<false, 2, false>), egrid, dim3(kThreads), 0, s, g, probs, ws);
+  }
+  if (!selecting) return;
   // enough workgroups to spread the rank counting of one layer over the chip, one per head in big batches
   const int split = std::clamp(512 / std::max(1, g.Hq * g.n_problems), 1, kResolveSplitMax);
   dim3 rgrid(split, g.Hq, g.n_problems);

@@ -27,7 +27,7 @@ class Batch:
     """A set of (sequence, layer) problems resident on the GPU, with outputs and workspace."""
 
     def __init__(self, cfg: B.tkphi_config, layers: list[dict], topk: list[int], debug: bool = False,
-                 device="cuda", max_L: int | None = None, max_K: int | None = None):
+                 device="cuda", max_L: int | None = None, max_K: int | None = None, diag: bool = False):
         self.cfg = cfg
         self.device = device
         self.n = len(layers)
@@ -48,10 +48,12 @@ class Batch:
                 t["topk_idx"] = torch.full((Hq, max(self.max_K, 1)), -1, dtype=torch.int32, device=device)
                 t["aux"] = torch.zeros((Hq, B.aux_stride(d)), dtype=torch.float32, device=device)
                 t["scores"] = torch.zeros((Hq, max(n_mid, 1)), dtype=torch.float32, device=device)
+            if debug or diag:
+                t["diag"] = torch.full((Hq, B.TKPHI_DIAG_STRIDE), -7.0, dtype=torch.float32, device=device)
             self.dev.append(t)
             probs.append(B.make_problem(t["K"], t["V"], t["Wq"], t["bq"], t["Wk"], t["bk"], t["S"], t["u"],
                                         q=t["q"], out=t["out"], topk_idx=t.get("topk_idx"), aux=t.get("aux"),
-                                        scores=t.get("scores"), L=L, topk=int(k)))
+                                        scores=t.get("scores"), L=L, topk=int(k), diag=t.get("diag")))
         self.host_table, self.table = B.upload_problems(probs, device)
         B.tkphi_check_problems(cfg, self.host_table, self.n, self.max_L, self.max_K, True)
         self.ws_bytes = B.tkphi_workspace_bytes(cfg, self.n, self.max_L, self.max_K)

@@ -248,3 +248,47 @@ def test_decode_replays_from_a_hip_graph():
     torch.cuda.synchronize()
     assert np.array_equal(b.result(0, "out"), y_graph)
     assert not np.array_equal(y_graph, y_eager)
+
+
+def _check_diag(w, P, k, b, i, heads):
+    import parity_utils as PU
+    res, _, _, _ = PU.oracle_layer(w, P, k, heads=heads)
+    dg = b.result(i, "diag")
+    for g, r in zip(heads, res):
+        row = dg[g].astype(np.float64)
+        assert abs(row[0] - r["H_mid"]) <= 2e-4, f"head {g}: H_mid {row[0]} vs {r['H_mid']}"
+        assert abs(row[1] - np.log(r["Z_M"])) <= 1e-4 * max(1.0, abs(np.log(r["Z_M"]))), f"head {g}: log Z_M"
+        assert abs(row[2] - r["C_mid"]) <= 1e-4 * max(r["C_mid"], 1e-3), f"head {g}: C_mid {row[2]} vs {r['C_mid']}"
+        assert abs(row[3] - r["rho_res"]) <= 5e-3 * max(r["rho_res"], 1e-6), f"head {g}: rho_res {row[3]} vs {r['rho_res']}"
+        assert abs(row[4] - r["rho_res_star"]) <= 1e-4 * max(r["rho_res_star"], 1e-6), f"head {g}: rho_res*"
+        if np.isfinite(r["log_Z_err"]):
+            assert abs(row[5] - r["log_Z_err"]) <= 5e-3, f"head {g}: log error {row[5]} vs {r['log_Z_err']}"
+        assert abs(row[6] - np.log(r["Z_A"])) <= 1e-4 * max(1.0, abs(np.log(r["Z_A"]))), f"head {g}: log Z_A"
+
+
+@pytest.mark.parametrize("shape,L,k,interleave", [("l3b_128k", 9000, 360, 0), ("l3b_128k", 20011, 200, 1),
+                                                  ("l1b_32k", 5000, 0, 0), ("tiny_f32", 4096, 40, 0)])
+def test_entropy_and_mass_diagnostics(monkeypatch, shape, L, k, interleave):
+    """The by-product diagnostics (normalised mid-region entropy, mid mass, Top-K mass recovery,
+    residual shares, residual log-partition error) against the oracle; K = 0 included (nothing is
+    retrieved but the score pass still runs); the output itself must not depend on the flag."""
+    from paper_2604_05438_amd import binding as B
+    import parity_utils as PU
+    if interleave:
+        monkeypatch.setenv("TKPHI_INTERLEAVE", "1")
+        monkeypatch.setenv("TKPHI_SCAN_CHUNK", "1024")
+    w = I.WORKLOADS[shape]
+    Ls = [L, max(L // 3, 100)]
+    ks = [k, min(k, 7)]
+    layers = [I.make_layer(w, L=l, seq=i) for i, l in enumerate(Ls)]
+    b = _batch(w, layers, ks)
+    b.build()
+    b.decode(B.TKPHI_MODE_SUB)
+    y_plain = [b.result(i, "out").copy() for i in range(2)]
+    b.decode(B.TKPHI_MODE_SUB | B.TKPHI_FLAG_DIAG)
+    assert b.status() == 0
+    heads = sorted({0, w.n_q_heads // 2, w.n_q_heads - 1})
+    for i, (P, kk) in enumerate(zip(layers, ks)):
+        assert np.array_equal(b.result(i, "out"), y_plain[i])
+        PU.check_layer(w, P, kk, b, i, heads=heads)
+        _check_diag(w, P, kk, b, i, heads)

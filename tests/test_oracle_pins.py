@@ -329,3 +329,35 @@ def test_fixed_retrieved_set_is_honoured():
 def test_rel_l1_definition():
     assert abs(orc.rel_l1([1.0, -2.0], [1.5, -1.0]) - (0.5 + 1.0) / (2.5 + 1e-12)) < 1e-15
     assert orc.rel_l1([0.0], [0.0]) == 0.0
+
+
+def test_entropy_and_mass_recovery_closed_forms():
+    """Diagnostics of the entropy / mass-recovery analysis against closed forms: with q = 0 every
+    score is 0, so the mid-normalised distribution is uniform (normalised entropy 1), Top-K
+    recovers K/|M| of the mid mass and the true residual share is (|M|-K)/(|A|+|M|); with one
+    dominant key the entropy tends to 0 and Top-1 recovers (almost) all of the mass."""
+    rng = np.random.default_rng(5)
+    L, d, dphi, n_sink, n_tail, k = 200, 8, 16, 3, 5, 17
+    K = rng.standard_normal((L, d)); V = rng.standard_normal((L, d))
+    W = rng.standard_normal((dphi, d)); b = np.zeros(dphi)
+    S, u = orc.build_summaries(K[None], V[None], W[None], b[None], 0.5, 0.1, n_sink, n_tail)
+    r = orc.decode_head(np.zeros(d), K, V, S[0], u[0], W, b, W, b, 0.5, 0.1, 0.35, n_sink, n_tail, k)
+    n_mid = L - n_sink - n_tail
+    assert abs(r["H_mid"] - 1.0) < 1e-12
+    assert abs(r["C_mid"] - k / n_mid) < 1e-12
+    assert abs(r["rho_res_star"] - (n_mid - k) / (n_sink + n_tail + n_mid)) < 1e-12
+    # one dominant key in the mid-region
+    q = rng.standard_normal(d)
+    K2 = 0.01 * K
+    K2[50] = 40.0 * q / np.linalg.norm(q)
+    r2 = orc.decode_head(q, K2, V, S[0], u[0], W, b, W, b, 0.5, 0.1, 1.0, n_sink, n_tail, 1)
+    assert r2["idx"][0] == 50
+    assert r2["H_mid"] < 1e-6 and r2["C_mid"] > 1 - 1e-9
+    # entropy from its definition on a small random case, by explicit loops
+    r3 = orc.decode_head(q, K, V, S[0], u[0], W, b, W, b, 0.5, 0.1, 0.35, n_sink, n_tail, k)
+    s = [0.35 * float(np.dot(q, K[i])) for i in range(n_sink, L - n_tail)]
+    z = sum(np.exp(x) for x in s)
+    h = -sum((np.exp(x) / z) * np.log(np.exp(x) / z) for x in s) / np.log(n_mid)
+    assert abs(r3["H_mid"] - h) < 1e-12
+    top = sorted(s, reverse=True)[:k]
+    assert abs(r3["C_mid"] - sum(np.exp(x) for x in top) / z) < 1e-12
