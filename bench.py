@@ -39,6 +39,8 @@ def main() -> int:
     ap.add_argument("--workload", default="l3b_128k")
     ap.add_argument("--budget-bp", type=int, default=100)
     ap.add_argument("--rotate", type=int, default=8, help="distinct resident layers the steps rotate over")
+    ap.add_argument("--cache-features", action="store_true",
+                    help="build stores the key features, decode gathers them instead of recomputing (not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 256 MiB device copies (a known-size kernel to scale rocprofv3's "
@@ -58,7 +60,7 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     w = I.WORKLOADS[args.workload]
-    cfg = H.config_of(w)
+    cfg = H.config_of(w, cache_features=args.cache_features)
     esz = 2 if w.dtype == "bf16" else 4
 
     # ---- inputs, resident in HBM before anything is timed --------------------------------
@@ -170,7 +172,7 @@ def main() -> int:
                                   f"{w.n_layers} layers), L {min(Ls)}..{max(Ls)}, K {min(Ks)}..{max(Ks)}"
                                   if model_level else f"L {L}, K {K}, one layer per step"),
                    "rotating_layers": 0 if model_level else args.rotate, "problems_per_step": probs_per_step,
-                   "budget_bp": args.budget_bp, "K": K, "L": L},
+                   "budget_bp": args.budget_bp, "K": K, "L": L, "cache_features": bool(args.cache_features)},
         "step_hbm": {"algorithmic_bytes": bytes_step, "achieved_GBs": bytes_step / (ms_per_step * 1e-3) / 1e9,
                      "frac_of_peak": bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "stage_us": stage_us,

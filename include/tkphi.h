@@ -94,6 +94,11 @@ typedef struct tkphi_config {
   float score_scale;     /* 1/sqrt(d_head) (eq. (full_attention))                           */
   float phi_in_scale;    /* a                                                               */
   float phi_norm_coef;   /* c                                                               */
+  int32_t cache_features; /* 0: decode recomputes phi_k of the retrieved keys (the paper's prototype);
+                             1: tkphi_build_summaries also stores phi_k(k_i) of every mid token in
+                             tkphi_problem::phi_cache and tkphi_decode gathers it instead (the cached
+                             variant named in Sec. "Retrieved-token subtraction": d_phi * 4 bytes per
+                             token and KV head of extra cache)                              */
 } tkphi_config;
 
 /* Optional per-query-head diagnostics / unnormalised outputs written by tkphi_decode,
@@ -147,6 +152,10 @@ typedef struct tkphi_problem {
   float* scores;         /* optional [n_q_heads][L - n_sink - n_tail] fp32 mid-region
                             scores s_i, i in M (diagnostic copy); may be NULL           */
   float* diag;           /* optional [n_q_heads][TKPHI_DIAG_STRIDE]; may be NULL        */
+  float* phi_cache;      /* [n_kv_heads][L - n_sink - n_tail][d_phi] fp32 key features of the
+                            mid-region, exactly the values the build contracted; written by
+                            build and read by decode when cfg.cache_features != 0 (then
+                            required), ignored otherwise                                */
   int32_t L;             /* prefill length, 1 <= L <= max_L                            */
   int32_t topk;          /* the paper's K: retrieved mid-region tokens per query head (the
                             budget); clipped to min(topk, |M|, max_K); 0 is legal      */

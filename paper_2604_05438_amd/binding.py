@@ -39,6 +39,7 @@ class tkphi_config(C.Structure):
         ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("d_head", C.c_int32), ("d_phi", C.c_int32),
         ("n_sink", C.c_int32), ("n_tail", C.c_int32), ("kv_dtype", C.c_int32),
         ("score_scale", C.c_float), ("phi_in_scale", C.c_float), ("phi_norm_coef", C.c_float),
+        ("cache_features", C.c_int32),
     ]
 
 
@@ -47,7 +48,7 @@ class tkphi_problem(C.Structure):
         ("K", C.c_void_p), ("V", C.c_void_p), ("stride_head", C.c_int64), ("stride_tok", C.c_int64),
         ("Wq", C.c_void_p), ("bq", C.c_void_p), ("Wk", C.c_void_p), ("bk", C.c_void_p),
         ("S", C.c_void_p), ("u", C.c_void_p), ("q", C.c_void_p), ("out", C.c_void_p),
-        ("topk_idx", C.c_void_p), ("aux", C.c_void_p), ("scores", C.c_void_p), ("diag", C.c_void_p),
+        ("topk_idx", C.c_void_p), ("aux", C.c_void_p), ("scores", C.c_void_p), ("diag", C.c_void_p), ("phi_cache", C.c_void_p),
         ("L", C.c_int32), ("topk", C.c_int32),
     ]
 
@@ -161,10 +162,10 @@ def tkphi_read_device_status(workspace_ptr: int, stream: int) -> int:
 
 # ---- marshalling helpers (device memory via torch) -----------------------------------------
 def make_config(n_q_heads, n_kv_heads, d_head, d_phi, n_sink, n_tail, dtype, score_scale, phi_in_scale,
-                phi_norm_coef) -> tkphi_config:
+                phi_norm_coef, cache_features=0) -> tkphi_config:
     kv = {"bf16": TKPHI_BF16, "f32": TKPHI_F32}[dtype] if isinstance(dtype, str) else int(dtype)
     return tkphi_config(n_q_heads, n_kv_heads, d_head, d_phi, n_sink, n_tail, kv, score_scale, phi_in_scale,
-                        phi_norm_coef)
+                        phi_norm_coef, int(cache_features))
 
 
 def _ptr(t) -> int:
@@ -172,12 +173,12 @@ def _ptr(t) -> int:
 
 
 def make_problem(K, V, Wq, bq, Wk, bk, S, u, q=None, out=None, topk_idx=None, aux=None, scores=None,
-                 L=None, topk=0, diag=None) -> tkphi_problem:
+                 L=None, topk=0, diag=None, phi_cache=None) -> tkphi_problem:
     """Fills a tkphi_problem from torch device tensors (K, V: [Hkv][L][d], last dim contiguous)."""
     assert K.stride(-1) == 1 and V.stride(-1) == 1 and K.stride() == V.stride()
     return tkphi_problem(
         _ptr(K), _ptr(V), K.stride(0), K.stride(1), _ptr(Wq), _ptr(bq), _ptr(Wk), _ptr(bk), _ptr(S), _ptr(u),
-        _ptr(q), _ptr(out), _ptr(topk_idx), _ptr(aux), _ptr(scores), _ptr(diag),
+        _ptr(q), _ptr(out), _ptr(topk_idx), _ptr(aux), _ptr(scores), _ptr(diag), _ptr(phi_cache),
         int(K.shape[1] if L is None else L), int(topk))
 
 

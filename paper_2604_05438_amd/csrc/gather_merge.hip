@@ -399,6 +399,90 @@ __global__ __launch_bounds__(kThreads) void gather_kernel(Geom g, const tkphi_pr
 }
 
 // ------------------------------------------------------------------------------------
+// gather from cached key features (cfg.cache_features): same grid and partial layout; instead
+// of reading the key rows and recomputing phi_k, every retrieved token's feature row (d_phi
+// fp32 values stored by the build) is read with 16-byte loads, d_phi / 4 lanes per row, all
+// rows of the tile in flight together, and z_i = phi_q . phi_k(k_i) is a butterfly sum.
+// ------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(kThreads) void gather_cached_kernel(Geom g, const tkphi_problem* __restrict__ probs,
+                                                                 char* __restrict__ ws) {
+  __shared__ float red[2 * kThreads * 8];
+  __shared__ int p_tok[kPairsPerWG];
+  __shared__ float p_s[kPairsPerWG], p_w[kPairsPerWG], p_z[kPairsPerWG];
+  __shared__ float acc_part[2 * 128 + 4];
+  __shared__ float sh_m;
+  const int tile = blockIdx.x, gq = blockIdx.y, p = blockIdx.z, tid = threadIdx.x;
+  const tkphi_problem pr = probs[p];
+  if (pr.L < 1 || pr.L > g.max_L) return;
+  const int n = mid_size(pr.L, g.n_sink, g.n_tail);
+  char* blk = problem_block(g, ws, p);
+  float* part = (float*)(blk + g.off_part) + ((size_t)gq * (g.n_tiles + g.n_atiles) + tile) * g.part_stride;
+  if (tile >= g.n_tiles) { anchor_partial<T>(g, pr, gq, n, tile - g.n_tiles, part, red); return; }
+  const int Ksel = ((const SelPlan*)(blk + g.off_plan))[gq].n_sel;
+  const int i0 = tile * kPairsPerWG;
+  if (i0 >= Ksel) return;
+  const int cnt = min(kPairsPerWG, Ksel - i0);
+  const int h = gq / g.G, d = g.d, dphi = g.dphi;
+  const int64_t head_off = (int64_t)h * pr.stride_head;
+
+  if (tid < kPairsPerWG) {
+    const int i = i0 + min(tid, cnt - 1);
+    p_tok[tid] = g.n_sink + min(max(((const int32_t*)(blk + g.off_selidx))[(size_t)gq * g.max_K + i], 0), n - 1);
+    p_s[tid] = tid < cnt ? ((const float*)(blk + g.off_selscore))[(size_t)gq * g.max_K + i] : -INFINITY;
+  }
+  for (int i = tid; i < 2 * d + 4; i += kThreads) acc_part[i] = 0.f;
+  __syncthreads();
+  if (tid < 64) {                                  // m_loc = max score of the tile
+    float m = p_s[tid];
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if (tid == 0) sh_m = m;
+  }
+  {
+    // LPR lanes per feature row (a power of two <= 64; d_phi is a multiple of 16), RPP rows per pass
+    int LPR = 4;
+    while (LPR * 2 <= min(dphi / 4, 64)) LPR *= 2;
+    const int RPP = kThreads / LPR, seg = tid % LPR, rsub = tid / LPR;
+    const float* phiq = (const float*)(blk + g.off_phiq) + (size_t)gq * dphi;
+    const float* cache_h = pr.phi_cache + (size_t)h * n * dphi;
+    for (int r0 = 0; r0 < kPairsPerWG; r0 += RPP * 4) {
+      float zz[4] = {0.f, 0.f, 0.f, 0.f};
+      for (int c4 = seg; c4 < dphi / 4; c4 += LPR) {        // (one round when d_phi <= 256)
+        const float4 pq = *(const float4*)(phiq + c4 * 4);
+        float4 f[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int row = min(r0 + k * RPP + rsub, kPairsPerWG - 1);
+          const u32x4 t = gload128(cache_h + (size_t)(p_tok[row] - g.n_sink) * dphi + c4 * 4);
+          f[k] = make_float4(__uint_as_float(t.x), __uint_as_float(t.y), __uint_as_float(t.z), __uint_as_float(t.w));
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+          zz[k] = fmaf(pq.x, f[k].x, fmaf(pq.y, f[k].y, fmaf(pq.z, f[k].z, fmaf(pq.w, f[k].w, zz[k]))));
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        for (int o = LPR >> 1; o >= 1; o >>= 1) zz[k] += __shfl_xor(zz[k], o);
+        const int row = r0 + k * RPP + rsub;
+        if (seg == 0 && row < kPairsPerWG) p_z[row] = row < cnt ? zz[k] : 0.f;
+      }
+    }
+  }
+  __syncthreads();
+  if (tid < kPairsPerWG) p_w[tid] = tid < cnt ? __expf(p_s[tid] - sh_m) : 0.f;
+  __syncthreads();
+
+  weighted_value_sums<T>(g, pr, head_off, p_tok, p_w, p_z, cnt, red, acc_part, true);
+  if (tid < d) { part[4 + tid] = acc_part[4 + tid]; part[4 + d + tid] = acc_part[4 + d + tid]; }
+  if (tid == 0) {
+    float Z = 0.f, zs = 0.f;
+    for (int i = 0; i < cnt; ++i) { Z += p_w[i]; zs += p_z[i]; }
+    part[0] = sh_m; part[1] = Z; part[2] = zs; part[3] = (float)cnt;
+  }
+}
+
+// ------------------------------------------------------------------------------------
 // merge: grid (Hq, n_problems)
 // ------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_problem* __restrict__ probs,
@@ -596,7 +680,10 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
 
 void launch_gather(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
   dim3 grid(g.n_tiles + g.n_atiles, g.Hq, g.n_problems);
-  if (g.use_mfma) {
+  if (g.cache) {
+    if (g.dtype == TKPHI_BF16) TKPHI_LAUNCH(ST_GATHER, gather_cached_kernel<uint16_t>, grid, dim3(kThreads), 0, s, g, probs, ws);
+    else TKPHI_LAUNCH(ST_GATHER, gather_cached_kernel<float>, grid, dim3(kThreads), 0, s, g, probs, ws);
+  } else if (g.use_mfma) {
     if (g.d == 128) TKPHI_LAUNCH(ST_GATHER, gather_mfma_kernel<128>, grid, dim3(kThreads), 0, s, g, probs, ws);
     else TKPHI_LAUNCH(ST_GATHER, gather_mfma_kernel<64>, grid, dim3(kThreads), 0, s, g, probs, ws);
   } else if (g.dtype == TKPHI_BF16) {

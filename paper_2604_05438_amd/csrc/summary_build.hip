@@ -38,7 +38,7 @@ union Frag {
 // u is summed from the same features.  Two LDS tile buffers: tile t+1 is staged (and the
 // global loads of tile t+2 are issued) before tile t is contracted: one barrier per tile.
 // ------------------------------------------------------------------------------------
-template <int D>
+template <int D, bool CACHE>        // CACHE: also store the contracted features in pr.phi_cache
 __global__ __launch_bounds__(kThreads, 2) void build_mfma_kernel(Geom g, const tkphi_problem* __restrict__ probs,
                                                                  char* __restrict__ ws) {
   constexpr int KS = D / 32;            // k-steps of GEMM1 (over channels)
@@ -144,7 +144,8 @@ __global__ __launch_bounds__(kThreads, 2) void build_mfma_kernel(Geom g, const t
       }
     }
   };
-  auto contract = [&](const char* k_t, const char* v_t, const float* nrm_t) {
+  float* cache_h = CACHE ? pr.phi_cache + (size_t)h * n * D : nullptr;   // [token of M][feature]
+  auto contract = [&](int t0, const char* k_t, const char* v_t, const float* nrm_t) {
     // ---- GEMM1 + exponent: all 64 tokens x this wavefront's features --------------------------
     u32x2 phi_hi[4][FT], phi_lo[4][FT];            // [16-token tile][feature tile]: tokens 4kg .. 4kg+3
     float ut[FT];                                  // this tile's share of u, added to the running sum once
@@ -170,6 +171,14 @@ __global__ __launch_bounds__(kThreads, 2) void build_mfma_kernel(Geom g, const t
         split_bf16_pair(f[2], f[3], &h23, &l23);
         phi_hi[mt][ft] = (u32x2){h01, h23};
         phi_lo[mt][ft] = (u32x2){l01, l23};
+        if (CACHE) {                     // the 16-bit values GEMM2 contracts, as fp32
+          const int tok = t0 + mt * 16 + 4 * kg;
+          float* cp = cache_h + (size_t)tok * D + wv * (D / 4) + ft * 16 + r;
+          if (tok + 0 < c1) cp[0] = join_bf16_lo(h01, l01);
+          if (tok + 1 < c1) cp[D] = join_bf16_hi(h01, l01);
+          if (tok + 2 < c1) cp[2 * D] = join_bf16_lo(h23, l23);
+          if (tok + 3 < c1) cp[3 * D] = join_bf16_hi(h23, l23);
+        }
       }
     }
 
@@ -212,7 +221,7 @@ __global__ __launch_bounds__(kThreads, 2) void build_mfma_kernel(Geom g, const t
       stage(t0 + 64, k_tb[cur ^ 1], v_tb[cur ^ 1], nrm_tb[cur ^ 1]);
       if (t0 + 128 < c1) issue_loads(t0 + 128);
     }
-    contract(k_tb[cur], v_tb[cur], nrm_tb[cur]);
+    contract(t0, k_tb[cur], v_tb[cur], nrm_tb[cur]);
     __syncthreads();                     // the other buffer is complete, this one is free
     cur ^= 1;
   }
@@ -291,9 +300,17 @@ __global__ __launch_bounds__(kThreads) void build_kernel(Geom g, const tkphi_pro
         const int j = (tid % 16) + 16 * i;
         const int64_t wbase = ((int64_t)h * dphi + j) * d;
         float dot = 0.f;
-        for (int c = 0; c < d; ++c) dot = fmaf(Elem<T>::load1(pr.Wk, wbase + c), kf[t][c], dot);
+        constexpr int EPL = Elem<T>::per16;
+        for (int c = 0; c < d; c += EPL) {       // 16-byte pieces of the Wk row
+          const u32x4 wv4 = gload128((const char*)pr.Wk + (wbase + c) * sizeof(T));
+          float wx[EPL];
+          Elem<T>::unpack(make_uint4(wv4.x, wv4.y, wv4.z, wv4.w), wx);
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) dot = fmaf(wx[e], kf[t][c + e], dot);
+        }
         const float f = expf(g.a * dot - g.c * nrm + pr.bk[(int64_t)h * dphi + j]);
         ph[t][j] = t < nt ? f : 0.f;
+        if (g.cache && t < nt) pr.phi_cache[((size_t)h * n + base + t) * dphi + j] = f;
       }
     }
     __syncthreads();
@@ -376,8 +393,10 @@ void launch_build(const Geom& g, const tkphi_problem* probs, char* ws, hipStream
   if (g.max_mid > 0) {
     dim3 grid(g.n_build_chunks, g.Hkv, g.n_problems);
     if (g.use_mfma) {
-      if (g.d == 128) TKPHI_LAUNCH(ST_UNTIMED, build_mfma_kernel<128>, grid, dim3(kThreads), 0, s, g, probs, ws);
-      else TKPHI_LAUNCH(ST_UNTIMED, build_mfma_kernel<64>, grid, dim3(kThreads), 0, s, g, probs, ws);
+      if (g.d == 128 && g.cache) TKPHI_LAUNCH(ST_UNTIMED, (build_mfma_kernel<128, true>), grid, dim3(kThreads), 0, s, g, probs, ws);
+      else if (g.d == 128) TKPHI_LAUNCH(ST_UNTIMED, (build_mfma_kernel<128, false>), grid, dim3(kThreads), 0, s, g, probs, ws);
+      else if (g.cache) TKPHI_LAUNCH(ST_UNTIMED, (build_mfma_kernel<64, true>), grid, dim3(kThreads), 0, s, g, probs, ws);
+      else TKPHI_LAUNCH(ST_UNTIMED, (build_mfma_kernel<64, false>), grid, dim3(kThreads), 0, s, g, probs, ws);
     } else if (g.dtype == TKPHI_BF16) {
       TKPHI_LAUNCH(ST_UNTIMED, build_kernel<uint16_t>, grid, dim3(kThreads), 0, s, g, probs, ws);
     } else {

@@ -62,6 +62,7 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   g->Hq = cfg->n_q_heads; g->Hkv = cfg->n_kv_heads; g->G = g->Hq / g->Hkv;
   g->d = cfg->d_head; g->dphi = cfg->d_phi; g->n_sink = cfg->n_sink; g->n_tail = cfg->n_tail;
   g->dtype = cfg->kv_dtype;
+  g->cache = cfg->cache_features ? 1 : 0;
   g->use_mfma = (cfg->kv_dtype == TKPHI_BF16 && cfg->d_phi == cfg->d_head && !env_int("TKPHI_FORCE_GENERIC", 0)) ? 1 : 0;
   g->n_problems = n_problems; g->max_L = max_L;
   const int64_t mid = (int64_t)max_L - cfg->n_sink - cfg->n_tail;
@@ -258,6 +259,11 @@ tkphi_status tkphi_check_problems(const tkphi_config* cfg, const tkphi_problem* 
       if (!req[i]) { set_error("problem %d: %s is null", p, names[i]); return TKPHI_EINVAL; }
       if (((uintptr_t)req[i]) % 16 != 0) { set_error("problem %d: %s not 16-byte aligned", p, names[i]); return TKPHI_EALIGN; }
     }
+    if (cfg->cache_features) {
+      if (!q.phi_cache) { set_error("problem %d: phi_cache is null (cfg.cache_features is set)", p); return TKPHI_EINVAL; }
+      if (((uintptr_t)q.phi_cache) % 16 != 0) { set_error("problem %d: phi_cache not 16-byte aligned", p); return TKPHI_EALIGN; }
+    }
+    if (q.diag && ((uintptr_t)q.diag) % 4 != 0) { set_error("problem %d: diag misaligned", p); return TKPHI_EALIGN; }
     if (for_decode) {
       const void* rq[] = {q.q, q.out, q.Wq, q.bq};
       const char* nq[] = {"q", "out", "Wq", "bq"};

@@ -34,6 +34,7 @@ struct Geom {
   int mid_stride;        // floats per score row (multiple of 64)
   int scan_chunk, n_scan_chunks;     // score_mid: mid tokens per workgroup
   int scan_unit;         // tokens a score_mid workgroup takes per iteration (scan_chunk is a multiple)
+  int cache;             // 1: key features are stored by the build and gathered by decode (cfg.cache_features)
   int diag;              // 1: the select emit pass also reduces the entropy / mass diagnostics
   int interleave;        // 1: chunk c owns the units c, c + n_chunks, c + 2 n_chunks, ... of its problem
                          // (all workgroups sweep the key cache together); 0: one contiguous range

@@ -18,9 +18,9 @@ def to_device(a: np.ndarray, device="cuda") -> torch.Tensor:
     return t.to(device)
 
 
-def config_of(w: Workload) -> B.tkphi_config:
+def config_of(w: Workload, cache_features: bool = False) -> B.tkphi_config:
     return B.make_config(w.n_q_heads, w.n_kv_heads, w.d_head, w.d_phi, w.n_sink, w.n_tail, w.dtype,
-                         w.score_scale, w.phi_in_scale, w.phi_norm_coef)
+                         w.score_scale, w.phi_in_scale, w.phi_norm_coef, int(cache_features))
 
 
 class Batch:
@@ -48,12 +48,14 @@ class Batch:
                 t["topk_idx"] = torch.full((Hq, max(self.max_K, 1)), -1, dtype=torch.int32, device=device)
                 t["aux"] = torch.zeros((Hq, B.aux_stride(d)), dtype=torch.float32, device=device)
                 t["scores"] = torch.zeros((Hq, max(n_mid, 1)), dtype=torch.float32, device=device)
+            if cfg.cache_features:
+                t["phi_cache"] = torch.empty((Hkv, max(n_mid, 1), dphi), dtype=torch.float32, device=device)
             if debug or diag:
                 t["diag"] = torch.full((Hq, B.TKPHI_DIAG_STRIDE), -7.0, dtype=torch.float32, device=device)
             self.dev.append(t)
             probs.append(B.make_problem(t["K"], t["V"], t["Wq"], t["bq"], t["Wk"], t["bk"], t["S"], t["u"],
                                         q=t["q"], out=t["out"], topk_idx=t.get("topk_idx"), aux=t.get("aux"),
-                                        scores=t.get("scores"), L=L, topk=int(k), diag=t.get("diag")))
+                                        scores=t.get("scores"), L=L, topk=int(k), diag=t.get("diag"), phi_cache=t.get("phi_cache")))
         self.host_table, self.table = B.upload_problems(probs, device)
         B.tkphi_check_problems(cfg, self.host_table, self.n, self.max_L, self.max_K, True)
         self.ws_bytes = B.tkphi_workspace_bytes(cfg, self.n, self.max_L, self.max_K)

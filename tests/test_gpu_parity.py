@@ -11,9 +11,9 @@ from paper_2604_05438_amd import inputs as I
 pytestmark = pytest.mark.gpu
 
 
-def _batch(w, layers, topk, **kw):
+def _batch(w, layers, topk, cache_features=False, **kw):
     from paper_2604_05438_amd import harness as H
-    return H.Batch(H.config_of(w), layers, topk, debug=True, **kw)
+    return H.Batch(H.config_of(w, cache_features=cache_features), layers, topk, debug=True, **kw)
 
 
 def _run_single(w, L, k, mode="sub", heads=None, **kw):
@@ -292,3 +292,34 @@ def test_entropy_and_mass_diagnostics(monkeypatch, shape, L, k, interleave):
         assert np.array_equal(b.result(i, "out"), y_plain[i])
         PU.check_layer(w, P, kk, b, i, heads=heads)
         _check_diag(w, P, kk, b, i, heads)
+
+
+@pytest.mark.parametrize("shape,L,k", [("l3b_128k", 9000, 360), ("l1b_32k", 5000, 49), ("tiny_f32", 4096, 40),
+                                       ("f32_gqa", 1500, 33)])
+def test_cached_key_features(shape, L, k):
+    """cfg.cache_features: the build also stores phi_k(k_i) of the mid-region, decode gathers the
+    stored rows instead of recomputing them from the keys.  Same parity bar as the recomputing
+    path, single problem and ragged batch; the cache itself against the oracle's features."""
+    import parity_utils as PU
+    from oracle import tkphi_oracle as orc
+    if shape == "f32_gqa":
+        w = dataclasses.replace(I.WORKLOADS["tiny_f32"], n_q_heads=4, n_kv_heads=2, d_head=128, d_phi=48,
+                                name="f32_gqa", seed=77)
+    else:
+        w = I.WORKLOADS[shape]
+    Ls = [L, L // 2 + 1, w.n_sink + w.n_tail + 1, 40]
+    ks = [k, 9, 1, 3]
+    layers = [I.make_layer(w, L=l, seq=i) for i, l in enumerate(Ls)]
+    b = _batch(w, layers, ks, cache_features=True)
+    b.build(); b.decode()
+    assert b.status() == 0
+    for i, (P, kk) in enumerate(zip(layers, ks)):
+        PU.check_layer(w, P, kk, b, i, heads=sorted({0, w.n_q_heads // 2, w.n_q_heads - 1}))
+    # the cache of problem 0, KV head 0, against the oracle's features (bf16 path: 16-bit values)
+    O = PU.oracle_inputs(layers[0])
+    _, M = orc.partition(Ls[0], w.n_sink, w.n_tail)
+    F = orc.phi(O["K"][0, M], O["Wk"][0], O["bk"][0], w.phi_in_scale, w.phi_norm_coef)
+    C = b.result(0, "phi_cache")[0].astype(np.float64)
+    assert C.shape == F.shape
+    rel = np.abs(C - F) / F
+    assert rel.max() <= (2.0 ** -15 if w.dtype == "bf16" else 2e-5), f"cache rel err {rel.max():.3e}"
