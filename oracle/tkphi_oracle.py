@@ -29,7 +29,9 @@ softmax, subtraction against brute force over unretrieved tokens, positivity,
 brute-force Top-K with ties, subset-bias identity, exact-subtraction identity,
 partition sums, constant-feature closed form, q = 0 special case, random
 feature convergence to exp(q.k/sqrt d), the paper's K = 21/144/636 worked
-example, K = 0.  Parity unpinned: nothing in this file; the *quality* of the
+example, K = 0; entropy / mass-recovery diagnostics against closed forms; the MLP feature map
+against the printed per-head parameter counts, its alpha = 0 and W1 = 0 reductions and GeLU's
+defining values.  Parity unpinned: nothing in this file; the *quality* of the
 estimate for the synthetic random-feature phi has no published value and is
 reported as a diagnostic only.
 """
@@ -87,22 +89,52 @@ def phi(x, W, b, a, c):
     return np.exp(F64(a) * (x @ W.T) - F64(c) * sq + b[None, :])
 
 
+def gelu(x):
+    """GeLU(x) = x Phi(x) with the exact Gaussian cdf, Phi(x) = (1 + erf(x / sqrt 2)) / 2."""
+    from scipy.special import erf
+    x = np.asarray(x, dtype=F64)
+    return 0.5 * x * (1.0 + erf(x / math.sqrt(2.0)))
+
+
+def phi_mlp(x, P):
+    """The head-wise one-block ReZero MLP feature map (App. "Head-wise phi architecture"):
+        g0 = Ws x + bs;  Delta = W2 GeLU(W1 g0 + b1) + b2;  g1 = g0 + alpha Delta;
+        phi(x) = exp(Wo g1 + bo)
+    for rows x [n][d]; P holds one head's Ws [E][d], bs [E], W1, W2 [E][E], b1, b2 [E],
+    alpha (scalar), Wo [dphi][E], bo [dphi].  Returns [n][dphi], strictly positive."""
+    x = np.atleast_2d(np.asarray(x, dtype=F64))
+    g0 = x @ np.asarray(P["Ws"], dtype=F64).T + np.asarray(P["bs"], dtype=F64)
+    hid = gelu(g0 @ np.asarray(P["W1"], dtype=F64).T + np.asarray(P["b1"], dtype=F64))
+    delta = hid @ np.asarray(P["W2"], dtype=F64).T + np.asarray(P["b2"], dtype=F64)
+    g1 = g0 + F64(P["alpha"]) * delta
+    return np.exp(g1 @ np.asarray(P["Wo"], dtype=F64).T + np.asarray(P["bo"], dtype=F64))
+
+
+def mlp_param_count(d, d_emb, dphi):
+    """Parameters of one head's map as printed in the architecture equations: the four affine
+    layers and the scalar alpha."""
+    return (d_emb * d + d_emb) + 2 * (d_emb * d_emb + d_emb) + (dphi * d_emb + dphi) + 1
+
+
 # ---------------------------------------------------------------------------
 # prefill: summary states, eq. (natural_cache)
 # ---------------------------------------------------------------------------
-def build_summaries(K, V, Wk, bk, a, c, n_sink, n_tail):
-    """S_M[h] = sum_{i in M} phi_k(k_i) v_i^T  ([dphi][d]),  u_M[h] = sum_{i in M} phi_k(k_i)."""
+def build_summaries(K, V, Wk, bk, a, c, n_sink, n_tail, phi_k_fns=None):
+    """S_M[h] = sum_{i in M} phi_k(k_i) v_i^T  ([dphi][d]),  u_M[h] = sum_{i in M} phi_k(k_i).
+    phi_k_fns: optional list of per-KV-head feature maps (rows -> features) used instead of
+    the exp-affine map (Wk, bk, a, c)."""
     K = np.asarray(K, dtype=F64)
     V = np.asarray(V, dtype=F64)
     Hkv, L, d = K.shape
-    dphi = np.asarray(Wk).shape[1]
     _, M = partition(L, n_sink, n_tail)
+    feat = (lambda h, x: phi(x, Wk[h], bk[h], a, c)) if phi_k_fns is None else (lambda h, x: phi_k_fns[h](x))
+    dphi = feat(0, K[0, :1]).shape[1]
     S = np.zeros((Hkv, dphi, d), dtype=F64)
     u = np.zeros((Hkv, dphi), dtype=F64)
     for h in range(Hkv):
         if M.size == 0:
             continue
-        f = phi(K[h, M], Wk[h], bk[h], a, c)          # [|M|][dphi]
+        f = feat(h, K[h, M])                          # [|M|][dphi]
         S[h] = f.T @ V[h, M]
         u[h] = f.sum(axis=0)
     return S, u
@@ -136,13 +168,15 @@ def full_attention(q_g, K_h, V_h, scale):
 
 
 def decode_head(q_g, K_h, V_h, S_M, u_M, Wq_g, bq_g, Wk_h, bk_h, a, c, scale,
-                n_sink, n_tail, k, retrieved=None):
+                n_sink, n_tail, k, retrieved=None, phi_q_fn=None, phi_k_fn=None):
     """One query head.  Returns a dict with the Top-K+phi output `y`, every
     intermediate of the method and the paper's comparison estimators.
 
     `retrieved`: optional explicit retrieved set (token indices in M) to use
     instead of the Top-K selection (for accounting checks under a fixed set,
     Sec. "Analysis: validating residual accounting").
+    `phi_q_fn`, `phi_k_fn`: optional feature maps (rows -> features) of this query head / its KV
+    head, used instead of the exp-affine maps (Wq_g, bq_g) / (Wk_h, bk_h).
     """
     K_h = np.asarray(K_h, dtype=F64)
     V_h = np.asarray(V_h, dtype=F64)
@@ -165,8 +199,10 @@ def decode_head(q_g, K_h, V_h, S_M, u_M, Wq_g, bq_g, Wk_h, bk_h, a, c, scale,
     Z_E = e[Eset].sum()
 
     # feature maps: query, and retrieved keys recomputed (Sec. "Retrieved-token subtraction")
-    p = phi(q_g, Wq_g, bq_g, a, c)[0]                  # phi_q(q)  [dphi]
-    f_K = phi(K_h[Kset], Wk_h, bk_h, a, c) if Kset.size else np.zeros((0, p.size))
+    fq = (lambda x: phi(x, Wq_g, bq_g, a, c)) if phi_q_fn is None else phi_q_fn
+    fk = (lambda x: phi(x, Wk_h, bk_h, a, c)) if phi_k_fn is None else phi_k_fn
+    p = fq(q_g)[0]                                     # phi_q(q)  [dphi]
+    f_K = fk(K_h[Kset]) if Kset.size else np.zeros((0, p.size))
 
     # subtraction, eq. (subtraction), materialised
     S_R = np.asarray(S_M, dtype=F64) - f_K.T @ V_h[Kset]
@@ -223,7 +259,7 @@ def rel_l1(y_hat, y_ref):
 
 
 def decode_layer(q, K, V, S, u, Wq, bq, Wk, bk, a, c, scale, n_sink, n_tail, k,
-                 heads=None, retrieved=None):
+                 heads=None, retrieved=None, phi_q_fns=None, phi_k_fns=None):
     """All (or the listed) query heads of one layer; returns a list of per-head dicts."""
     Hq = np.asarray(q).shape[0]
     Hkv = np.asarray(K).shape[0]
@@ -231,7 +267,11 @@ def decode_layer(q, K, V, S, u, Wq, bq, Wk, bk, a, c, scale, n_sink, n_tail, k,
     res = []
     for g in (range(Hq) if heads is None else heads):
         h = g // G
-        res.append(decode_head(q[g], K[h], V[h], S[h], u[h], Wq[g], bq[g], Wk[h], bk[h],
+        res.append(decode_head(q[g], K[h], V[h], S[h], u[h],
+                               None if Wq is None else Wq[g], None if bq is None else bq[g],
+                               None if Wk is None else Wk[h], None if bk is None else bk[h],
                                a, c, scale, n_sink, n_tail, k,
-                               retrieved=None if retrieved is None else retrieved[g]))
+                               retrieved=None if retrieved is None else retrieved[g],
+                               phi_q_fn=None if phi_q_fns is None else phi_q_fns[g],
+                               phi_k_fn=None if phi_k_fns is None else phi_k_fns[h]))
     return res

@@ -25,7 +25,7 @@ import numpy as np
 
 __all__ = [
     "Workload", "WORKLOADS", "f32_to_bf16_bits", "bf16_bits_to_f32", "to_f64",
-    "make_layer", "ragged_lengths", "mid_budget",
+    "make_layer", "make_mlp_phi", "ragged_lengths", "mid_budget",
 ]
 
 
@@ -225,4 +225,37 @@ def make_layer(w: Workload, layer: int = 0, seq: int = 0, L: int | None = None,
     # values: N(0,1)
     V32 = gen(7).standard_normal((Hkv, L, d), dtype=np.float32)
     out["V"] = _store(V32, w.dtype)
+    return out
+
+
+def make_mlp_phi(w: Workload, layer: int = 0, d_emb: int = 512) -> dict:
+    """Random weights of the shapes of the head-wise one-block ReZero MLP feature maps
+    (stem d -> d_emb, gated residual MLP d_emb -> d_emb -> d_emb, output d_emb -> d_phi, then
+    exp), one map per query head ("q") and one per KV head ("k").
+
+    Returns {"q": {...}, "k": {...}} with stacked per-head tensors
+      Ws [H][d_emb][d], W1, W2 [H][d_emb][d_emb], Wo [H][d_phi][d_emb]   (storage type of w)
+      bs, b1, b2 [H][d_emb], bo [H][d_phi], alpha [H]                     (float32)
+    Weight entries are N(0, 1/fan_in) so that activations stay O(1) for N(0,1) inputs; biases
+    N(0, 0.1^2); bo is centred on -0.5 ln d_phi; alpha = 0.5.  No trained weights exist for
+    these shapes: the maps are not calibrated to exp(q.k), only their cost and arithmetic matter."""
+    d, dphi = w.d_head, w.d_phi
+    out = {}
+    for side, H, tid in (("q", w.n_q_heads, 40), ("k", w.n_kv_heads, 50)):
+        key = (w.seed * 1_000_003 + layer * 10_007 + tid) % (2 ** 63)
+        rng = np.random.Generator(np.random.Philox(key=[key, d_emb]))
+
+        def mat(rows, cols):
+            return _store((rng.standard_normal((H, rows, cols), dtype=np.float32) / np.float32(math.sqrt(cols))), w.dtype)
+
+        def vec(n, centre=0.0):
+            return (np.float32(centre) + np.float32(0.1) * rng.standard_normal((H, n), dtype=np.float32)).astype(np.float32)
+
+        out[side] = {
+            "Ws": mat(d_emb, d), "bs": vec(d_emb),
+            "W1": mat(d_emb, d_emb), "b1": vec(d_emb),
+            "W2": mat(d_emb, d_emb), "b2": vec(d_emb),
+            "Wo": mat(dphi, d_emb), "bo": vec(dphi, -0.5 * math.log(dphi)),
+            "alpha": np.full((H,), 0.5, dtype=np.float32),
+        }
     return out

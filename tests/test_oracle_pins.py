@@ -361,3 +361,58 @@ def test_entropy_and_mass_recovery_closed_forms():
     assert abs(r3["H_mid"] - h) < 1e-12
     top = sorted(s, reverse=True)[:k]
     assert abs(r3["C_mid"] - sum(np.exp(x) for x in top) / z) < 1e-12
+
+
+def test_mlp_feature_map_shapes_and_reductions():
+    """The one-block ReZero MLP feature map: (1) the layer shapes reproduce the paper's per-head
+    parameter counts (the printed equations account for all but one scalar in every row);
+    (2) alpha = 0 reduces the map to an exponentiated affine map, which must agree with `phi`
+    for the composed weights; (3) W1 = 0 makes the residual update the constant
+    W2 GeLU(b1) + b2; (4) GeLU's defining values; (5) positivity."""
+    import os
+    rows = [l.split() for l in open(os.path.join(os.path.dirname(__file__), "golden", "phi_param_counts.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 4
+    for d, dphi, demb, count in rows:
+        assert orc.mlp_param_count(int(d), int(demb), int(dphi)) + 1 == int(count)
+    rng = np.random.default_rng(11)
+    d, E, dphi, n = 8, 32, 16, 5
+    P = {"Ws": rng.standard_normal((E, d)), "bs": rng.standard_normal(E), "W1": rng.standard_normal((E, E)) / 6,
+         "b1": rng.standard_normal(E), "W2": rng.standard_normal((E, E)) / 6, "b2": rng.standard_normal(E),
+         "alpha": 0.7, "Wo": rng.standard_normal((dphi, E)) / 6, "bo": rng.standard_normal(dphi)}
+    x = rng.standard_normal((n, d))
+    f = orc.phi_mlp(x, P)
+    assert f.shape == (n, dphi) and (f > 0).all()
+    # (2) alpha = 0: exp(Wo (Ws x + bs) + bo) = phi(x; W = Wo Ws, b = Wo bs + bo, a = 1, c = 0)
+    P0 = dict(P, alpha=0.0)
+    ref = orc.phi(x, P["Wo"] @ P["Ws"], P["Wo"] @ P["bs"] + P["bo"], 1.0, 0.0)
+    assert np.abs(orc.phi_mlp(x, P0) / ref - 1).max() < 1e-12
+    # (3) W1 = 0: Delta is the constant W2 GeLU(b1) + b2, written out with scalar loops
+    Pz = dict(P, W1=np.zeros((E, E)))
+    import math
+    gb = np.array([0.5 * v * (1 + math.erf(v / math.sqrt(2))) for v in P["b1"]])
+    delta = np.array([sum(P["W2"][i, j] * gb[j] for j in range(E)) + P["b2"][i] for i in range(E)])
+    for r in range(n):
+        g1 = P["Ws"] @ x[r] + P["bs"] + 0.7 * delta
+        assert np.abs(orc.phi_mlp(x[r], Pz)[0] / np.exp(P["Wo"] @ g1 + P["bo"]) - 1).max() < 1e-12
+    # (4) GeLU(0) = 0, GeLU(x) -> x and GeLU(-x) -> 0 for large x, GeLU(x) - GeLU(-x) = x
+    assert orc.gelu(0.0) == 0.0
+    assert abs(orc.gelu(12.0) - 12.0) < 1e-12 and abs(orc.gelu(-12.0)) < 1e-12
+    t = rng.standard_normal(50)
+    assert np.abs(orc.gelu(t) - orc.gelu(-t) - t).max() < 1e-14
+    assert abs(orc.gelu(1.0) - 0.8413447460685429) < 1e-15          # = Phi(1), the standard normal cdf at 1
+    # the method with MLP maps still satisfies the dense limit (exact support = every token)
+    L, n_sink, n_tail = 60, 2, 3
+    K = rng.standard_normal((1, L, d)); V = rng.standard_normal((1, L, d)); q = rng.standard_normal((1, d))
+    fk = [lambda z: orc.phi_mlp(z, P)]; fq = [lambda z: orc.phi_mlp(z, P0)]
+    S, u = orc.build_summaries(K, V, None, None, 0, 0, n_sink, n_tail, phi_k_fns=fk)
+    r = orc.decode_layer(q, K, V, S, u, None, None, None, None, 0, 0, 0.3, n_sink, n_tail, L, phi_q_fns=fq, phi_k_fns=fk)[0]
+    # (the subtracted summaries cancel to rounding relative to |S|, which these unscaled random
+    # maps make large next to Z_E)
+    assert orc.rel_l1(r["y"], r["y_full"]) < 1e-7
+    r = orc.decode_layer(q, K, V, S, u, None, None, None, None, 0, 0, 0.3, n_sink, n_tail, 7, phi_q_fns=fq, phi_k_fns=fk)[0]
+    # subtraction = brute force over the unretrieved tokens, with the MLP features
+    _, M = orc.partition(L, n_sink, n_tail)
+    rest = np.setdiff1d(M, r["idx"])
+    fr = orc.phi_mlp(K[0, rest], P)
+    assert np.abs(r["S_R"] - fr.T @ V[0, rest]).max() < 1e-10 * np.abs(S).max()
