@@ -76,6 +76,32 @@ typedef enum tkphi_mode { TKPHI_MODE_SUB = 0, TKPHI_MODE_NOSUB = 1, TKPHI_MODE_T
                                      and the residual branch was dropped for that head
                                      (App. "Why positivity matters": numerical clamp)         */
 
+/* Feature-map families.
+ *   EXP_AFFINE  phi(x) = exp(phi_in_scale * W x - phi_norm_coef * |x|^2 + b), per-head W, b
+ *               (tkphi_problem::Wq, bq, Wk, bk)
+ *   MLP         the head-wise one-block ReZero MLP of App. "Head-wise phi architecture":
+ *                 g0 = Ws x + bs;  Delta = W2 GeLU(W1 g0 + b1) + b2;  g1 = g0 + alpha Delta;
+ *                 phi(x) = exp(Wo g1 + bo)
+ *               with internal width cfg.d_emb (the paper: 512), one tkphi_mlp per query head
+ *               (tkphi_problem::mlp_q) and per KV head (mlp_k).  Requires bf16 storage and
+ *               cfg.cache_features = 1: the key features are evaluated once, at build time. */
+typedef enum tkphi_phi_kind { TKPHI_PHI_EXP_AFFINE = 0, TKPHI_PHI_MLP = 1 } tkphi_phi_kind;
+
+/* One head's MLP feature map.  DEVICE struct (arrays of it live in device memory); weights are
+ * row-major [out][in] in the storage type (bf16), biases fp32; all pointers 16-byte aligned. */
+typedef struct tkphi_mlp {
+  const void* Ws;        /* [d_emb][d_head]  */
+  const float* bs;       /* [d_emb]          */
+  const void* W1;        /* [d_emb][d_emb]   */
+  const float* b1;       /* [d_emb]          */
+  const void* W2;        /* [d_emb][d_emb]   */
+  const float* b2;       /* [d_emb]          */
+  const void* Wo;        /* [d_phi][d_emb]   */
+  const float* bo;       /* [d_phi]          */
+  float alpha;           /* residual gate    */
+  int32_t reserved;      /* 0                */
+} tkphi_mlp;
+
 /* Fixed per model.  HOST struct.
  * The feature maps have the form phi(x) = exp(phi_in_scale * W x - phi_norm_coef * |x|^2 + b)
  * with per-head W, b (exponentiated affine output, App. "Head-wise phi architecture").
@@ -99,6 +125,8 @@ typedef struct tkphi_config {
                              tkphi_problem::phi_cache and tkphi_decode gathers it instead (the cached
                              variant named in Sec. "Retrieved-token subtraction": d_phi * 4 bytes per
                              token and KV head of extra cache)                              */
+  int32_t phi_kind;      /* tkphi_phi_kind; 0 = EXP_AFFINE                                  */
+  int32_t d_emb;         /* MLP only: internal width, a multiple of 64 in [64, 1024]        */
 } tkphi_config;
 
 /* Optional per-query-head diagnostics / unnormalised outputs written by tkphi_decode,
@@ -156,6 +184,9 @@ typedef struct tkphi_problem {
                             mid-region, exactly the values the build contracted; written by
                             build and read by decode when cfg.cache_features != 0 (then
                             required), ignored otherwise                                */
+  const tkphi_mlp* mlp_q; /* [n_q_heads]  feature maps of the query heads (TKPHI_PHI_MLP only) */
+  const tkphi_mlp* mlp_k; /* [n_kv_heads] feature maps of the KV heads    (TKPHI_PHI_MLP only);
+                             with TKPHI_PHI_MLP the fields Wq, bq, Wk, bk are ignored          */
   int32_t L;             /* prefill length, 1 <= L <= max_L                            */
   int32_t topk;          /* the paper's K: retrieved mid-region tokens per query head (the
                             budget); clipped to min(topk, |M|, max_K); 0 is legal      */

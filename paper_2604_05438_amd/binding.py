@@ -19,6 +19,7 @@ TKPHI_EINVAL, TKPHI_ESHAPE, TKPHI_EALIGN, TKPHI_EWORKSPACE, TKPHI_EHIP, TKPHI_EU
 TKPHI_F32, TKPHI_BF16 = 0, 1
 TKPHI_MODE_SUB, TKPHI_MODE_NOSUB, TKPHI_MODE_TOPK_ONLY = 0, 1, 2
 TKPHI_FLAG_DIAG = 0x100
+TKPHI_PHI_EXP_AFFINE, TKPHI_PHI_MLP = 0, 1
 TKPHI_DIAG_STRIDE = 8
 TKPHI_DEV_BAD_LENGTH, TKPHI_DEV_CLAMPED = 1, 2
 
@@ -39,7 +40,15 @@ class tkphi_config(C.Structure):
         ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("d_head", C.c_int32), ("d_phi", C.c_int32),
         ("n_sink", C.c_int32), ("n_tail", C.c_int32), ("kv_dtype", C.c_int32),
         ("score_scale", C.c_float), ("phi_in_scale", C.c_float), ("phi_norm_coef", C.c_float),
-        ("cache_features", C.c_int32),
+        ("cache_features", C.c_int32), ("phi_kind", C.c_int32), ("d_emb", C.c_int32),
+    ]
+
+
+class tkphi_mlp(C.Structure):
+    _fields_ = [
+        ("Ws", C.c_void_p), ("bs", C.c_void_p), ("W1", C.c_void_p), ("b1", C.c_void_p),
+        ("W2", C.c_void_p), ("b2", C.c_void_p), ("Wo", C.c_void_p), ("bo", C.c_void_p),
+        ("alpha", C.c_float), ("reserved", C.c_int32),
     ]
 
 
@@ -49,6 +58,7 @@ class tkphi_problem(C.Structure):
         ("Wq", C.c_void_p), ("bq", C.c_void_p), ("Wk", C.c_void_p), ("bk", C.c_void_p),
         ("S", C.c_void_p), ("u", C.c_void_p), ("q", C.c_void_p), ("out", C.c_void_p),
         ("topk_idx", C.c_void_p), ("aux", C.c_void_p), ("scores", C.c_void_p), ("diag", C.c_void_p), ("phi_cache", C.c_void_p),
+        ("mlp_q", C.c_void_p), ("mlp_k", C.c_void_p),
         ("L", C.c_int32), ("topk", C.c_int32),
     ]
 
@@ -162,10 +172,10 @@ def tkphi_read_device_status(workspace_ptr: int, stream: int) -> int:
 
 # ---- marshalling helpers (device memory via torch) -----------------------------------------
 def make_config(n_q_heads, n_kv_heads, d_head, d_phi, n_sink, n_tail, dtype, score_scale, phi_in_scale,
-                phi_norm_coef, cache_features=0) -> tkphi_config:
+                phi_norm_coef, cache_features=0, phi_kind=0, d_emb=0) -> tkphi_config:
     kv = {"bf16": TKPHI_BF16, "f32": TKPHI_F32}[dtype] if isinstance(dtype, str) else int(dtype)
     return tkphi_config(n_q_heads, n_kv_heads, d_head, d_phi, n_sink, n_tail, kv, score_scale, phi_in_scale,
-                        phi_norm_coef, int(cache_features))
+                        phi_norm_coef, int(cache_features), int(phi_kind), int(d_emb))
 
 
 def _ptr(t) -> int:
@@ -173,13 +183,27 @@ def _ptr(t) -> int:
 
 
 def make_problem(K, V, Wq, bq, Wk, bk, S, u, q=None, out=None, topk_idx=None, aux=None, scores=None,
-                 L=None, topk=0, diag=None, phi_cache=None) -> tkphi_problem:
+                 L=None, topk=0, diag=None, phi_cache=None, mlp_q=None, mlp_k=None) -> tkphi_problem:
     """Fills a tkphi_problem from torch device tensors (K, V: [Hkv][L][d], last dim contiguous)."""
     assert K.stride(-1) == 1 and V.stride(-1) == 1 and K.stride() == V.stride()
     return tkphi_problem(
         _ptr(K), _ptr(V), K.stride(0), K.stride(1), _ptr(Wq), _ptr(bq), _ptr(Wk), _ptr(bk), _ptr(S), _ptr(u),
-        _ptr(q), _ptr(out), _ptr(topk_idx), _ptr(aux), _ptr(scores), _ptr(diag), _ptr(phi_cache),
+        _ptr(q), _ptr(out), _ptr(topk_idx), _ptr(aux), _ptr(scores), _ptr(diag), _ptr(phi_cache), _ptr(mlp_q), _ptr(mlp_k),
         int(K.shape[1] if L is None else L), int(topk))
+
+
+def upload_mlp(maps: dict, device="cuda"):
+    """One side ("q" or "k") of inputs.make_mlp_phi, already on the device as torch tensors ->
+    (device uint8 tensor holding the tkphi_mlp array [H], list of tensors to keep alive)."""
+    import torch
+    H = maps["alpha"].shape[0]
+    arr = (tkphi_mlp * H)()
+    for h in range(H):
+        arr[h] = tkphi_mlp(_ptr(maps["Ws"][h]), _ptr(maps["bs"][h]), _ptr(maps["W1"][h]), _ptr(maps["b1"][h]),
+                           _ptr(maps["W2"][h]), _ptr(maps["b2"][h]), _ptr(maps["Wo"][h]), _ptr(maps["bo"][h]),
+                           float(maps["alpha"][h]), 0)
+    raw = bytes(memoryview(arr).cast("B"))
+    return torch.frombuffer(bytearray(raw), dtype=torch.uint8).to(device)
 
 
 def upload_problems(problems, device="cuda"):

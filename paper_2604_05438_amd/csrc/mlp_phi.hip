@@ -1,0 +1,349 @@
+// MLP feature maps (App. "Head-wise phi architecture"): the one-block ReZero MLP
+//   g0 = Ws x + bs;  Delta = W2 GeLU(W1 g0 + b1) + b2;  g1 = g0 + alpha Delta;  phi(x) = exp(Wo g1 + bo)
+// evaluated for the keys of the mid-region at build time, and the summary contraction
+// S = Phi^T V, u = sum Phi (eq. (natural_cache)) from the stored features.
+//
+// Keys: four launches of one tiled matrix-core GEMM per block of kMlpBlock tokens
+//   stem  G = X Ws^T + bs            (X = bf16 key rows: exact, single MFMA pass)
+//   hid   H = GeLU(G W1^T + b1)
+//   res   G = G + alpha (H W2^T + b2)    (in place: a tile reads only its own G entries)
+//   out   Phi = exp(G Wo^T + bo)     -> tkphi_problem::phi_cache
+// Activations are fp32 in the workspace; as MFMA operands they are split into a bf16 hi + lo
+// pair (16 significant bits, two MFMAs per product), weights are bf16 as stored, accumulation
+// is fp32.  With ~1.3 MFLOP per token and KV head against ~14 KB of activation traffic the
+// chain is bound by the matrix cores, not by HBM.
+#include "tkphi_internal.h"
+
+namespace tkphi {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+union Frag {
+  u32x4 u;
+  bf16x8 v;
+};
+
+enum { EPI_STEM = 0, EPI_HID = 1, EPI_RES = 2, EPI_OUT = 3 };
+
+// ------------------------------------------------------------------------------------
+// grid (kMlpBlock / 64, ceil(Nout / 128), Hkv), 256 threads: a 64-token x 128-output tile,
+// wavefront w owns outputs [32w, 32w + 32) (2 MFMA column tiles) of all four 16-token row
+// tiles.  K loop in stages of 64: the A tile goes through LDS as bf16 hi / lo planes (row
+// stride padded by 16 B: conflict-free 16-byte operand reads), the weights go straight from
+// global memory into the B operand (lane (r, kg): 8 consecutive inputs of output r).  Two LDS
+// buffers, one barrier per stage; the next stage's global loads are issued before the MFMAs.
+// ------------------------------------------------------------------------------------
+template <int EPI>
+__global__ __launch_bounds__(kThreads) void mlp_gemm_kernel(Geom g, const tkphi_problem* __restrict__ probs,
+                                                            char* __restrict__ ws, int p, int t0) {
+  constexpr int BM = 64, BN = 128, KB = 64;
+  constexpr int AROW = KB * 2 + 16;
+  constexpr bool A_BF16 = EPI == EPI_STEM;
+  __shared__ __attribute__((aligned(16))) char a_hi[2][BM * AROW];
+  __shared__ __attribute__((aligned(16))) char a_lo[2][A_BF16 ? 16 : BM * AROW];
+
+  const int h = blockIdx.z, tid = threadIdx.x;
+  const int lane = tid & 63, wv = tid >> 6, r = lane & 15, kg = lane >> 4;
+  const tkphi_problem pr = probs[p];
+  if (pr.L < 1 || pr.L > g.max_L) return;
+  const int n = mid_size(pr.L, g.n_sink, g.n_tail);
+  const int row0 = blockIdx.x * BM;                    // first row of the tile inside the token block
+  if (t0 + row0 >= n) return;
+  const int rows_valid = min(BM, n - (t0 + row0));
+  const tkphi_mlp mp = pr.mlp_k[h];
+  const int E = g.d_emb;
+  const int Kd = EPI == EPI_STEM ? g.d : E;
+  const int Nout = EPI == EPI_OUT ? g.dphi : E;
+  const int n0 = blockIdx.y * BN;
+  if (n0 >= Nout) return;
+  const char* W = (const char*)(EPI == EPI_STEM ? mp.Ws : EPI == EPI_HID ? mp.W1 : EPI == EPI_RES ? mp.W2 : mp.Wo);
+  const float* bias = EPI == EPI_STEM ? mp.bs : EPI == EPI_HID ? mp.b1 : EPI == EPI_RES ? mp.b2 : mp.bo;
+  float* Gb = (float*)(ws + g.off_act) + (size_t)h * kMlpBlock * E;
+  float* Hb = Gb + (size_t)g.Hkv * kMlpBlock * E;
+
+  // A rows: thread (srow = tid / 4, sseg = tid % 4) stages 16 consecutive inputs of row srow
+  const int srow = tid >> 2, sseg = tid & 3;
+  const int arow = row0 + min(srow, rows_valid - 1);   // clamped: rows past the end repeat the last one
+  const char* a_src;
+  if (A_BF16) a_src = (const char*)pr.K + ((size_t)h * pr.stride_head + (size_t)(g.n_sink + t0 + arow) * pr.stride_tok) * 2;
+  else a_src = (const char*)((EPI == EPI_RES ? Hb : Gb) + (size_t)arow * E);
+  // B rows: column tiles nt = 0, 1 of this wavefront
+  bool nvalid[2];
+  const char* w_src[2];
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt) {
+    const int col = n0 + wv * 32 + nt * 16;
+    nvalid[nt] = col < Nout;
+    w_src[nt] = W + ((size_t)min(col + r, Nout - 1) * Kd + kg * 8) * 2;
+  }
+
+  floatx4 acc[4][2];
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = (floatx4){0.f, 0.f, 0.f, 0.f};
+
+  u32x4 ar[4];          // fp32: 16 floats; bf16: ar[0..1] = 16 bf16
+  Frag br[2][2];        // [nt][ks]
+  auto issue = [&](int k0) {
+    if (A_BF16) {
+      ar[0] = gload128(a_src + (size_t)(k0 + sseg * 16) * 2);
+      ar[1] = gload128(a_src + (size_t)(k0 + sseg * 16) * 2 + 16);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) ar[i] = gload128(a_src + (size_t)(k0 + sseg * 16 + i * 4) * 4);
+    }
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) br[nt][ks].u = gload128(w_src[nt] + (size_t)(k0 + ks * 32) * 2);
+  };
+
+  const int n_stages = Kd / KB;
+  issue(0);
+  for (int st = 0; st < n_stages; ++st) {
+    const int buf = st & 1;
+    // ---- stage the A tile (split into hi / lo planes) ------------------------------------------
+    if (A_BF16) {
+      *(u32x4*)(a_hi[buf] + srow * AROW + sseg * 32) = ar[0];
+      *(u32x4*)(a_hi[buf] + srow * AROW + sseg * 32 + 16) = ar[1];
+    } else {
+      uint32_t hh[8], ll[8];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        split_bf16_pair(__uint_as_float(ar[i].x), __uint_as_float(ar[i].y), &hh[2 * i], &ll[2 * i]);
+        split_bf16_pair(__uint_as_float(ar[i].z), __uint_as_float(ar[i].w), &hh[2 * i + 1], &ll[2 * i + 1]);
+      }
+      *(u32x4*)(a_hi[buf] + srow * AROW + sseg * 32) = (u32x4){hh[0], hh[1], hh[2], hh[3]};
+      *(u32x4*)(a_hi[buf] + srow * AROW + sseg * 32 + 16) = (u32x4){hh[4], hh[5], hh[6], hh[7]};
+      *(u32x4*)(a_lo[buf] + srow * AROW + sseg * 32) = (u32x4){ll[0], ll[1], ll[2], ll[3]};
+      *(u32x4*)(a_lo[buf] + srow * AROW + sseg * 32 + 16) = (u32x4){ll[4], ll[5], ll[6], ll[7]};
+    }
+    Frag bcur[2][2];
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) bcur[nt][ks] = br[nt][ks];
+    __syncthreads();
+    if (st + 1 < n_stages) issue((st + 1) * KB);
+    // ---- MFMA ------------------------------------------------------------------------------------
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) {
+        Frag ahi, alo;
+        ahi.u = *(const u32x4*)(a_hi[buf] + (mt * 16 + r) * AROW + ks * 64 + kg * 16);
+        if (!A_BF16) alo.u = *(const u32x4*)(a_lo[buf] + (mt * 16 + r) * AROW + ks * 64 + kg * 16);
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+          if (!A_BF16) acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(alo.v, bcur[nt][ks].v, acc[mt][nt], 0, 0, 0);
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ahi.v, bcur[nt][ks].v, acc[mt][nt], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  // ---- epilogue: acc[mt][nt][i] <-> row mt*16 + 4kg + i, output n0 + wv*32 + nt*16 + r ---------
+  float* cache_h = pr.phi_cache + ((size_t)h * n + t0 + row0) * g.dphi;
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt) {
+    if (!nvalid[nt]) continue;
+    const int col = n0 + wv * 32 + nt * 16 + r;
+    const float b = bias[col];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = mt * 16 + 4 * kg + i;
+        if (row >= rows_valid) continue;
+        const float v = acc[mt][nt][i] + b;
+        if (EPI == EPI_STEM) Gb[(size_t)(row0 + row) * E + col] = v;
+        if (EPI == EPI_HID) Hb[(size_t)(row0 + row) * E + col] = gelu_erf(v);
+        if (EPI == EPI_RES) { float* gp = Gb + (size_t)(row0 + row) * E + col; *gp = fmaf(mp.alpha, v, *gp); }
+        if (EPI == EPI_OUT) cache_h[(size_t)row * g.dphi + col] = expf(v);
+      }
+    }
+  }
+}
+
+// the key features of every problem's mid-region -> phi_cache, block by block
+void launch_mlp_features(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
+  if (g.max_mid == 0) return;
+  const int E = g.d_emb;
+  for (int p = 0; p < g.n_problems; ++p) {
+    for (int t0 = 0; t0 < g.max_mid; t0 += kMlpBlock) {
+      const int rows = std::min(kMlpBlock, g.max_mid - t0);
+      dim3 ge((rows + 63) / 64, (E + 127) / 128, g.Hkv), go((rows + 63) / 64, (g.dphi + 127) / 128, g.Hkv);
+      hipLaunchKernelGGL(mlp_gemm_kernel<EPI_STEM>, ge, dim3(kThreads), 0, s, g, probs, ws, p, t0);
+      hipLaunchKernelGGL(mlp_gemm_kernel<EPI_HID>, ge, dim3(kThreads), 0, s, g, probs, ws, p, t0);
+      hipLaunchKernelGGL(mlp_gemm_kernel<EPI_RES>, ge, dim3(kThreads), 0, s, g, probs, ws, p, t0);
+      hipLaunchKernelGGL(mlp_gemm_kernel<EPI_OUT>, go, dim3(kThreads), 0, s, g, probs, ws, p, t0);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// summary contraction from stored features: grid (n_build_chunks, Hkv, n_problems), 256
+// threads; writes the same chunk partials as the other build kernels.
+// Tiles of 64 tokens: the feature rows (fp32) are split into bf16 hi / lo and transposed
+// in registers (4 tokens x 4 features per load group) into feature-major LDS planes, the
+// value tile is transposed as in the fused build; wavefront w owns the feature tiles
+// w, w + 4, ...  (FTW = ceil(d_phi / 64) of them); hi and lo are two MFMAs per product.
+// ------------------------------------------------------------------------------------
+template <int D, int FTW>
+__global__ __launch_bounds__(kThreads) void summary_from_cache_kernel(Geom g, const tkphi_problem* __restrict__ probs,
+                                                                      char* __restrict__ ws) {
+  constexpr int CT = D / 16, SEGS = D / 8;
+  constexpr int TROW = 64 * 2 + 16;                // bytes per staged row of 64 tokens
+  constexpr int QMAX = FTW * 4 / 4;                // feature quads per thread: dphi / 4 / 16 <= FTW
+  extern __shared__ __attribute__((aligned(16))) char lds[];   // f_hi [dphi][TROW], f_lo [dphi][TROW], v_t [D][TROW]
+  const int ch = blockIdx.x, h = blockIdx.y, p = blockIdx.z, tid = threadIdx.x;
+  const tkphi_problem pr = probs[p];
+  if (pr.L < 1 || pr.L > g.max_L) return;
+  const int n = mid_size(pr.L, g.n_sink, g.n_tail);
+  const int c0 = ch * g.build_chunk;
+  if (c0 >= n) return;
+  const int c1 = min(n, c0 + g.build_chunk);
+  const int dphi = g.dphi, NFT = dphi / 16;
+  char* f_hi = lds;
+  char* f_lo = lds + (size_t)dphi * TROW;
+  char* v_t = lds + (size_t)2 * dphi * TROW;
+  const int lane = tid & 63, wv = tid >> 6, r = lane & 15, kg = lane >> 4;
+
+  floatx4 sacc[FTW][CT];
+#pragma unroll
+  for (int k = 0; k < FTW; ++k)
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) sacc[k][ct] = (floatx4){0.f, 0.f, 0.f, 0.f};
+  float usum[QMAX][4];
+#pragma unroll
+  for (int k = 0; k < QMAX; ++k)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) usum[k][e] = 0.f;
+
+  const int tq = tid % 16, fs = tid / 16;          // tokens 4tq .. 4tq+3 of the tile; feature quads fs, fs + 16, ...
+  const float* cache_h = pr.phi_cache + (size_t)h * n * dphi;
+  const size_t row_bytes = (size_t)pr.stride_tok * 2;
+  const bool v_active = tid < 16 * SEGS;
+  const int sg = tid / 16;
+  const char* Vb = (const char*)pr.V + ((size_t)h * pr.stride_head + (size_t)g.n_sink * pr.stride_tok) * 2 + (size_t)sg * 16;
+
+  for (int t0 = c0; t0 < c1; t0 += 64) {
+    // ---- loads: 4 tokens x (QMAX feature quads + one 16-byte value segment) ----------------------
+    u32x4 fq[QMAX][4], vv[4];
+#pragma unroll
+    for (int k = 0; k < QMAX; ++k) {
+      const int q4 = min(fs + 16 * k, dphi / 4 - 1);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) fq[k][i] = gload128(cache_h + (size_t)min(t0 + tq * 4 + i, c1 - 1) * dphi + q4 * 4);
+    }
+    if (v_active) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) vv[i] = gload128(Vb + (size_t)min(t0 + tq * 4 + i, c1 - 1) * row_bytes);
+    }
+    const bool ok[4] = {t0 + tq * 4 + 0 < c1, t0 + tq * 4 + 1 < c1, t0 + tq * 4 + 2 < c1, t0 + tq * 4 + 3 < c1};
+    __syncthreads();                                // the previous tile's readers are done
+#pragma unroll
+    for (int k = 0; k < QMAX; ++k) {
+      const int q4 = fs + 16 * k;
+      if (q4 < dphi / 4) {
+        float f[4][4];                              // [token][feature of the quad]
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          f[i][0] = ok[i] ? __uint_as_float(fq[k][i].x) : 0.f; f[i][1] = ok[i] ? __uint_as_float(fq[k][i].y) : 0.f;
+          f[i][2] = ok[i] ? __uint_as_float(fq[k][i].z) : 0.f; f[i][3] = ok[i] ? __uint_as_float(fq[k][i].w) : 0.f;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          usum[k][e] += (f[0][e] + f[1][e]) + (f[2][e] + f[3][e]);
+          uint32_t h01, l01, h23, l23;
+          split_bf16_pair(f[0][e], f[1][e], &h01, &l01);
+          split_bf16_pair(f[2][e], f[3][e], &h23, &l23);
+          *(u32x2*)(f_hi + (q4 * 4 + e) * TROW + tq * 8) = (u32x2){h01, h23};
+          *(u32x2*)(f_lo + (q4 * 4 + e) * TROW + tq * 8) = (u32x2){l01, l23};
+        }
+      }
+    }
+    if (v_active) {
+      uint32_t w[4][4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        w[i][0] = ok[i] ? vv[i].x : 0u; w[i][1] = ok[i] ? vv[i].y : 0u;
+        w[i][2] = ok[i] ? vv[i].z : 0u; w[i][3] = ok[i] ? vv[i].w : 0u;
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {      // dword q of a token holds channels 2q (low half) and 2q+1 (high half)
+        const u32x2 even = (u32x2){(w[0][q] & 0xffffu) | (w[1][q] << 16), (w[2][q] & 0xffffu) | (w[3][q] << 16)};
+        const u32x2 odd = (u32x2){(w[0][q] >> 16) | (w[1][q] & 0xffff0000u), (w[2][q] >> 16) | (w[3][q] & 0xffff0000u)};
+        *(u32x2*)(v_t + (sg * 8 + 2 * q) * TROW + tq * 8) = even;
+        *(u32x2*)(v_t + (sg * 8 + 2 * q + 1) * TROW + tq * 8) = odd;
+      }
+    }
+    __syncthreads();
+    // ---- S[own feature tiles][all channels] += Phi^T V over the tile's 64 tokens -------------------
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+      for (int k = 0; k < FTW; ++k) {
+        const int ft = wv + 4 * k;
+        if (ft < NFT) {
+          Frag ahi, alo;
+          ahi.u = *(const u32x4*)(f_hi + (ft * 16 + r) * TROW + (32 * ks + 8 * kg) * 2);
+          alo.u = *(const u32x4*)(f_lo + (ft * 16 + r) * TROW + (32 * ks + 8 * kg) * 2);
+#pragma unroll
+          for (int ct = 0; ct < CT; ++ct) {
+            Frag vb;
+            vb.u = *(const u32x4*)(v_t + (ct * 16 + r) * TROW + (32 * ks + 8 * kg) * 2);
+            sacc[k][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(alo.v, vb.v, sacc[k][ct], 0, 0, 0);
+            sacc[k][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ahi.v, vb.v, sacc[k][ct], 0, 0, 0);
+          }
+        }
+      }
+    }
+  }
+
+  // ---- chunk partial: S part [dphi][D] then u part [dphi] ------------------------------------------
+  float* bp = (float*)(ws + g.off_bpart) + ((size_t)(p * g.Hkv + h) * g.n_build_chunks + ch) * ((size_t)dphi * (D + 1));
+#pragma unroll
+  for (int k = 0; k < FTW; ++k) {
+    const int ft = wv + 4 * k;
+    if (ft < NFT) {
+#pragma unroll
+      for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) bp[(size_t)(ft * 16 + 4 * kg + i) * D + ct * 16 + r] = sacc[k][ct][i];
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < QMAX; ++k) {
+    const int q4 = fs + 16 * k;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float x = usum[k][e];
+      x += __shfl_xor(x, 1); x += __shfl_xor(x, 2); x += __shfl_xor(x, 4); x += __shfl_xor(x, 8);
+      if (tq == 0 && q4 < dphi / 4) bp[(size_t)dphi * D + q4 * 4 + e] = x;
+    }
+  }
+}
+
+template <int D, int FTW>
+static void launch_sfc(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
+  dim3 grid(g.n_build_chunks, g.Hkv, g.n_problems);
+  const size_t lds = (size_t)(2 * g.dphi + g.d) * (64 * 2 + 16);
+  if (lds > 48 * 1024) {
+    const hipError_t e = hipFuncSetAttribute((const void*)summary_from_cache_kernel<D, FTW>,
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) { set_error("hipFuncSetAttribute(%zu bytes of LDS): %s", lds, hipGetErrorString(e)); return; }
+  }
+  hipLaunchKernelGGL((summary_from_cache_kernel<D, FTW>), grid, dim3(kThreads), lds, s, g, probs, ws);
+}
+
+void launch_summary_from_cache(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
+  if (g.max_mid == 0) return;
+  const int ftw = (g.dphi + 63) / 64;              // feature tiles per wavefront: 1, 2 or (3, 4 ->) 4
+  if (g.d == 128) { if (ftw <= 1) launch_sfc<128, 1>(g, probs, ws, s); else if (ftw == 2) launch_sfc<128, 2>(g, probs, ws, s); else launch_sfc<128, 4>(g, probs, ws, s); }
+  else { if (ftw <= 1) launch_sfc<64, 1>(g, probs, ws, s); else if (ftw == 2) launch_sfc<64, 2>(g, probs, ws, s); else launch_sfc<64, 4>(g, probs, ws, s); }
+}
+
+}  // namespace tkphi

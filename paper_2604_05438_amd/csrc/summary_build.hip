@@ -392,7 +392,10 @@ __global__ __launch_bounds__(kThreads) void build_reduce_kernel(Geom g, const tk
 void launch_build(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
   if (g.max_mid > 0) {
     dim3 grid(g.n_build_chunks, g.Hkv, g.n_problems);
-    if (g.use_mfma) {
+    if (g.phi_kind == TKPHI_PHI_MLP) {
+      launch_mlp_features(g, probs, ws, s);         // phi_k of the mid-region -> phi_cache
+      launch_summary_from_cache(g, probs, ws, s);   // S, u chunk partials from the stored features
+    } else if (g.use_mfma) {
       if (g.d == 128 && g.cache) TKPHI_LAUNCH(ST_UNTIMED, (build_mfma_kernel<128, true>), grid, dim3(kThreads), 0, s, g, probs, ws);
       else if (g.d == 128) TKPHI_LAUNCH(ST_UNTIMED, (build_mfma_kernel<128, false>), grid, dim3(kThreads), 0, s, g, probs, ws);
       else if (g.cache) TKPHI_LAUNCH(ST_UNTIMED, (build_mfma_kernel<64, true>), grid, dim3(kThreads), 0, s, g, probs, ws);

@@ -53,6 +53,20 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
     set_error("d_phi=%d unsupported (multiple of 16 in [16, %d])", cfg->d_phi, kMaxDim);
     return TKPHI_ESHAPE;
   }
+  if (cfg->phi_kind != TKPHI_PHI_EXP_AFFINE && cfg->phi_kind != TKPHI_PHI_MLP) {
+    set_error("phi_kind=%d is not a tkphi_phi_kind", cfg->phi_kind);
+    return TKPHI_EINVAL;
+  }
+  if (cfg->phi_kind == TKPHI_PHI_MLP) {
+    if (cfg->kv_dtype != TKPHI_BF16 || !cfg->cache_features) {
+      set_error("the MLP feature maps need bf16 storage and cache_features = 1");
+      return TKPHI_EUNSUPPORTED;
+    }
+    if (cfg->d_emb < 64 || cfg->d_emb > 1024 || (cfg->d_emb & (cfg->d_emb - 1)) != 0) {
+      set_error("d_emb=%d unsupported (a power of two in [64, 1024])", cfg->d_emb);
+      return TKPHI_ESHAPE;
+    }
+  }
   if (n_problems > 65535) { set_error("n_problems=%d exceeds 65535", n_problems); return TKPHI_ESHAPE; }
   if (cfg->n_sink < 0 || cfg->n_tail < 0) {
     set_error("n_sink=%d n_tail=%d must be >= 0", cfg->n_sink, cfg->n_tail);
@@ -63,6 +77,7 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   g->d = cfg->d_head; g->dphi = cfg->d_phi; g->n_sink = cfg->n_sink; g->n_tail = cfg->n_tail;
   g->dtype = cfg->kv_dtype;
   g->cache = cfg->cache_features ? 1 : 0;
+  g->phi_kind = cfg->phi_kind; g->d_emb = cfg->d_emb;
   g->use_mfma = (cfg->kv_dtype == TKPHI_BF16 && cfg->d_phi == cfg->d_head && !env_int("TKPHI_FORCE_GENERIC", 0)) ? 1 : 0;
   g->n_problems = n_problems; g->max_L = max_L;
   const int64_t mid = (int64_t)max_L - cfg->n_sink - cfg->n_tail;
@@ -124,7 +139,12 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   g->off_bpart = g->off_problem0;
   const size_t build_total = g->off_bpart + (size_t)std::max(n_problems, 1) * g->Hkv * g->n_build_chunks *
                                                 (size_t)g->dphi * (g->d + 1) * sizeof(float);
-  g->total_bytes = align_up(std::max(decode_total, build_total), 256);
+  size_t build_all = build_total;
+  if (cfg->phi_kind == TKPHI_PHI_MLP) {
+    g->off_act = align_up(build_total, 256);
+    build_all = g->off_act + (size_t)2 * g->Hkv * kMlpBlock * g->d_emb * sizeof(float);
+  }
+  g->total_bytes = align_up(std::max(decode_total, build_all), 256);
   return TKPHI_OK;
 }
 
@@ -253,11 +273,16 @@ tkphi_status tkphi_check_problems(const tkphi_config* cfg, const tkphi_problem* 
   const size_t es = cfg->kv_dtype == TKPHI_BF16 ? 2 : 4;
   for (int p = 0; p < n_problems; ++p) {
     const tkphi_problem& q = ph[p];
-    const void* req[] = {q.K, q.V, q.Wk, q.bk, q.S, q.u};
-    const char* names[] = {"K", "V", "Wk", "bk", "S", "u"};
-    for (int i = 0; i < 6; ++i) {
+    const bool mlp = cfg->phi_kind == TKPHI_PHI_MLP;     // then Wq, bq, Wk, bk are not read
+    const void* req[] = {q.K, q.V, q.S, q.u, q.Wk, q.bk};
+    const char* names[] = {"K", "V", "S", "u", "Wk", "bk"};
+    for (int i = 0; i < (mlp ? 4 : 6); ++i) {
       if (!req[i]) { set_error("problem %d: %s is null", p, names[i]); return TKPHI_EINVAL; }
       if (((uintptr_t)req[i]) % 16 != 0) { set_error("problem %d: %s not 16-byte aligned", p, names[i]); return TKPHI_EALIGN; }
+    }
+    if (cfg->phi_kind == TKPHI_PHI_MLP) {
+      if (!q.mlp_k || (for_decode && !q.mlp_q)) { set_error("problem %d: mlp_k / mlp_q is null", p); return TKPHI_EINVAL; }
+      if (((uintptr_t)q.mlp_k) % 8 != 0 || ((uintptr_t)q.mlp_q) % 8 != 0) { set_error("problem %d: mlp table misaligned", p); return TKPHI_EALIGN; }
     }
     if (cfg->cache_features) {
       if (!q.phi_cache) { set_error("problem %d: phi_cache is null (cfg.cache_features is set)", p); return TKPHI_EINVAL; }
@@ -267,7 +292,7 @@ tkphi_status tkphi_check_problems(const tkphi_config* cfg, const tkphi_problem* 
     if (for_decode) {
       const void* rq[] = {q.q, q.out, q.Wq, q.bq};
       const char* nq[] = {"q", "out", "Wq", "bq"};
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < (mlp ? 2 : 4); ++i) {
         if (!rq[i]) { set_error("problem %d: %s is null", p, nq[i]); return TKPHI_EINVAL; }
         if (((uintptr_t)rq[i]) % 16 != 0) { set_error("problem %d: %s not 16-byte aligned", p, nq[i]); return TKPHI_EALIGN; }
       }

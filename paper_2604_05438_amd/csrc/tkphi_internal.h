@@ -34,6 +34,7 @@ struct Geom {
   int mid_stride;        // floats per score row (multiple of 64)
   int scan_chunk, n_scan_chunks;     // score_mid: mid tokens per workgroup
   int scan_unit;         // tokens a score_mid workgroup takes per iteration (scan_chunk is a multiple)
+  int phi_kind, d_emb;   // tkphi_phi_kind; MLP width
   int cache;             // 1: key features are stored by the build and gathered by decode (cfg.cache_features)
   int diag;              // 1: the select emit pass also reduces the entropy / mass diagnostics
   int interleave;        // 1: chunk c owns the units c, c + n_chunks, c + 2 n_chunks, ... of its problem
@@ -59,6 +60,7 @@ struct Geom {
   size_t off_phiq;       // float    [Hq][dphi]
   size_t off_part;       // float    [Hq][n_tiles + n_atiles][part_stride]  (retrieved tiles, then anchor tiles)
   size_t off_bpart;      // float    [Hkv][n_build_chunks][dphi*(d+1)]   (build only; aliases the block)
+  size_t off_act;        // float    2 x [Hkv][kMlpBlock][d_emb]         (MLP build only: activations g, h of a token block)
   size_t total_bytes;
 };
 
@@ -93,6 +95,7 @@ struct SelPlan {
   int32_t nb;      // tokens in the boundary bin
   int32_t n_sel;   // retrieved tokens K' = min(topk, |M|, max_K)
 };
+constexpr int kMlpBlock = 8192;        // tokens per KV head whose MLP activations are held at once
 constexpr int kMaxScanChunks = 2048;   // chunk offsets are scanned in LDS by `plan`
 
 // kernel launchers (each defined next to its kernels)
@@ -101,6 +104,8 @@ void launch_select(const Geom& g, const tkphi_problem* probs, char* ws, hipStrea
 void launch_gather(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
 void launch_merge(const Geom& g, const tkphi_problem* probs, char* ws, int mode, hipStream_t s);
 void launch_build(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
+void launch_mlp_features(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);     // -> phi_cache
+void launch_summary_from_cache(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s); // -> chunk partials
 
 #ifdef __HIPCC__
 // ---- device helpers ------------------------------------------------------------------
@@ -238,6 +243,71 @@ __device__ __forceinline__ void phi_q_head(const Geom& g, const tkphi_problem& p
       }
     }
   }
+}
+
+// out[j] = W[j] . in for a bf16 matrix W [N][Kd] (row-major, 16-byte aligned rows) and an fp32
+// vector `in` in LDS; epi(j, dot) consumes row j.  min(Kd / 8, 64) lanes share a row with one or
+// two 16-byte loads each; eight loads per lane are in flight.  Kd / 8 is a power of two <= 128.
+template <int SPL, typename F>   // SPL: 16-byte segments per lane, 1 or 2
+__device__ __forceinline__ void gemv_bf16_rows_impl(const void* W, int N, int Kd, const float* in, F&& epi) {
+  const int tid = threadIdx.x, nthr = blockDim.x;
+  const int LPR = Kd / 8 / SPL;
+  const int rows_pp = nthr / LPR, row_in = tid / LPR, sl = tid % LPR;
+  constexpr int PASS = 8 / SPL;                                      // row passes in flight
+  for (int j0 = 0; j0 < N; j0 += rows_pp * PASS) {
+    u32x4 t[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int pass = k / SPL, sg = sl + (k % SPL) * LPR;
+      if (j0 + pass * rows_pp >= N) break;                           // (uniform) no rows left for this pass
+      const int j = min(j0 + pass * rows_pp + row_in, N - 1);        // clamped: every lane loads
+      t[k] = gload128((const char*)W + ((size_t)j * Kd + sg * 8) * 2);
+    }
+    float dot = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int pass = k / SPL, sg = sl + (k % SPL) * LPR;
+      if (j0 + pass * rows_pp >= N) break;
+      float x[8];
+      Elem<uint16_t>::unpack(make_uint4(t[k].x, t[k].y, t[k].z, t[k].w), x);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dot = fmaf(x[e], in[sg * 8 + e], dot);
+      if (k % SPL == SPL - 1) {                                      // the row's last segment of this lane
+        for (int o = LPR >> 1; o >= 1; o >>= 1) dot += __shfl_xor(dot, o);
+        const int jr = j0 + pass * rows_pp + row_in;
+        if (sl == 0 && jr < N) epi(jr, dot);
+        dot = 0.f;
+      }
+    }
+  }
+}
+
+template <typename F>
+__device__ __forceinline__ void gemv_bf16_rows(const void* W, int N, int Kd, const float* in, F&& epi) {
+  if (Kd / 8 <= 64) gemv_bf16_rows_impl<1>(W, N, Kd, in, epi);
+  else gemv_bf16_rows_impl<2>(W, N, Kd, in, epi);
+}
+
+__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+
+// phi_q of query head gq with the one-block ReZero MLP (App. "Head-wise phi architecture"):
+//   g0 = Ws q + bs;  g1 = g0 + alpha (W2 GeLU(W1 g0 + b1) + b2);  phi_q = exp(Wo g1 + bo)
+// as four matrix-vector products in fp32 by one workgroup.  xs: LDS, >= d_head floats; gs, hs:
+// LDS, >= d_emb floats each.
+__device__ __forceinline__ void phi_q_mlp_head(const Geom& g, const tkphi_problem& pr, char* blk, int gq,
+                                               float* xs, float* gs, float* hs) {
+  const tkphi_mlp mp = pr.mlp_q[gq];
+  const int E = g.d_emb;
+  float* phiq = (float*)(blk + g.off_phiq) + (size_t)gq * g.dphi;
+  for (int c = threadIdx.x; c < g.d; c += blockDim.x) xs[c] = Elem<uint16_t>::load1(pr.q, (int64_t)gq * g.d + c);
+  __syncthreads();
+  gemv_bf16_rows(mp.Ws, E, g.d, xs, [&](int j, float dot) { gs[j] = dot + mp.bs[j]; });
+  __syncthreads();
+  gemv_bf16_rows(mp.W1, E, E, gs, [&](int j, float dot) { hs[j] = gelu_erf(dot + mp.b1[j]); });
+  __syncthreads();
+  gemv_bf16_rows(mp.W2, E, E, hs, [&](int j, float dot) { gs[j] = fmaf(mp.alpha, dot + mp.b2[j], gs[j]); });
+  __syncthreads();
+  gemv_bf16_rows(mp.Wo, g.dphi, E, gs, [&](int j, float dot) { phiq[j] = expf(dot + mp.bo[j]); });
 }
 
 // device status word: recomputed from the problem lengths by one workgroup per decode call

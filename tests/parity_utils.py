@@ -29,14 +29,29 @@ def oracle_inputs(P: dict) -> dict:
     return {k: I.to_f64(P[k]) for k in ("q", "K", "V", "Wq", "Wk", "bq", "bk")}
 
 
+def mlp_feature_fns(P: dict):
+    """(phi_q_fns, phi_k_fns) of a layer that carries MLP feature maps under P["mlp"]
+    (inputs.make_mlp_phi), else (None, None): the exp-affine map of Wq / Wk applies."""
+    if "mlp" not in P:
+        return None, None
+
+    def head_fns(side):
+        T = {k: I.to_f64(v) for k, v in P["mlp"][side].items()}
+        return [(lambda x, hh=hh: orc.phi_mlp(x, {k: v[hh] for k, v in T.items()})) for hh in range(T["alpha"].shape[0])]
+
+    return head_fns("q"), head_fns("k")
+
+
 def oracle_layer(w, P, k, heads=None, S=None, u=None, retrieved=None):
     O = oracle_inputs(P)
+    fq, fk = mlp_feature_fns(P)
+    O["phi_k_fns"] = fk
     if S is None:
         S, u = orc.build_summaries(O["K"], O["V"], O["Wk"], O["bk"], w.phi_in_scale, w.phi_norm_coef,
-                                   w.n_sink, w.n_tail)
+                                   w.n_sink, w.n_tail, phi_k_fns=fk)
     res = orc.decode_layer(O["q"], O["K"], O["V"], S, u, O["Wq"], O["bq"], O["Wk"], O["bk"],
                            w.phi_in_scale, w.phi_norm_coef, w.score_scale, w.n_sink, w.n_tail, k,
-                           heads=heads, retrieved=retrieved)
+                           heads=heads, retrieved=retrieved, phi_q_fns=fq, phi_k_fns=fk)
     return res, S, u, O
 
 
@@ -78,14 +93,21 @@ def check_output(y_gpu: np.ndarray, y_or: np.ndarray, what="y"):
     return max_abs, rel
 
 
-def check_summaries(S_gpu, u_gpu, S_or, u_or, tol, w=None, O=None):
+MLP_FEATURE_EPS = 2.0 ** -12
+
+
+def check_summaries(S_gpu, u_gpu, S_or, u_or, tol, w=None, O=None, eps=None):
     """fp32 storage: relative Frobenius error <= tol.
     bf16 storage (w, O given): the kernel keeps every feature phi_k(k_i)[j] as a bf16 hi + lo
     pair before the contraction (16 significant bits: unit roundoff 2^-16 per term; the fp32
     exponent adds ~2^-20), so element-wise
         |S_gpu - S|[j][c] <= eps * sum_i phi_ij |v_ic|   and   |u_gpu - u|[j] <= eps * u[j]
-    with eps = 2^-16 + 2^-17, the second term covering fp32 accumulation over the tokens."""
-    eps = 2.0 ** -16 + 2.0 ** -17
+    with eps = 2^-16 + 2^-17, the second term covering fp32 accumulation over the tokens.
+    MLP feature maps (eps = MLP_FEATURE_EPS): the logit of a feature passes three contractions over
+    d_emb terms whose left operands carry 2^-17 relative error (bf16 hi + lo) and whose sums are
+    fp32; by Cauchy-Schwarz each adds at most 2^-17 |g|_2 |w|_2 ~ 2^-17 * 27 to the logit for unit-norm
+    weight rows and O(1) activations, so 2^-12 bounds the relative error of exp(logit) with margin."""
+    eps = 2.0 ** -16 + 2.0 ** -17 if eps is None else eps
     for h in range(S_or.shape[0]):
         dS = np.abs(S_gpu[h].astype(np.float64) - S_or[h])
         du = np.abs(u_gpu[h].astype(np.float64) - u_or[h])
@@ -96,7 +118,10 @@ def check_summaries(S_gpu, u_gpu, S_or, u_or, tol, w=None, O=None):
         else:
             L = O["K"].shape[1]
             _, M = orc.partition(L, w.n_sink, w.n_tail)
-            F = orc.phi(O["K"][h, M], O["Wk"][h], O["bk"][h], w.phi_in_scale, w.phi_norm_coef)
+            if O.get("phi_k_fns") is not None:
+                F = O["phi_k_fns"][h](O["K"][h, M])
+            else:
+                F = orc.phi(O["K"][h, M], O["Wk"][h], O["bk"][h], w.phi_in_scale, w.phi_norm_coef)
             bound = eps * (F.T @ np.abs(O["V"][h, M]))
             assert (dS <= bound + 1e-30).all(), \
                 f"head {h}: S error exceeds the bf16-feature bound by x{(dS / (bound + 1e-300)).max():.3f} (rel-F {eS:.3e})"
@@ -118,9 +143,9 @@ def check_layer(w, P, k, batch, i, heads=None, sum_tol=None, mode="sub", check_a
     if sum_tol is None:
         sum_tol = 2e-3 if w.dtype == "bf16" else 2e-5
     if n_mid > 0 and summaries is None:
-        rounded_features = w.dtype == "bf16" and w.d_phi == w.d_head      # the matrix-core path
+        rounded_features = (w.dtype == "bf16" and w.d_phi == w.d_head) or "mlp" in P   # the matrix-core paths
         check_summaries(batch.result(i, "S"), batch.result(i, "u"), S_or, u_or, sum_tol,
-                        w=w if rounded_features else None, O=O)
+                        w=w if rounded_features else None, O=O, eps=MLP_FEATURE_EPS if "mlp" in P else None)
     y = batch.result(i, "out")
     idx = batch.result(i, "topk_idx")
     sc = batch.result(i, "scores")

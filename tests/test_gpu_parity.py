@@ -323,3 +323,47 @@ def test_cached_key_features(shape, L, k):
     assert C.shape == F.shape
     rel = np.abs(C - F) / F
     assert rel.max() <= (2.0 ** -15 if w.dtype == "bf16" else 2e-5), f"cache rel err {rel.max():.3e}"
+
+
+@pytest.mark.parametrize("shape,d_emb,L,k", [("l3b_128k", 512, 9000, 360), ("l1b_32k", 128, 10000, 49),
+                                             ("bf16_wide_phi", 256, 1500, 33)])
+def test_mlp_feature_maps(shape, d_emb, L, k):
+    """Learned feature maps (App. "Head-wise phi architecture"): the build evaluates the one-block
+    ReZero MLP phi_k on the mid-region keys with the tiled matrix-core GEMM chain, stores the
+    features and contracts them into S, u; decode evaluates phi_q per query head with the GEMV
+    chain and gathers the stored key features.  Compared with the oracle run with phi_mlp on
+    both sides: stored features, summaries, index sets, outputs; single problem and ragged batch
+    (the 10000-token case crosses the 8192-token activation block)."""
+    import parity_utils as PU
+    from oracle import tkphi_oracle as orc
+    from paper_2604_05438_amd import harness as H
+    if shape == "bf16_wide_phi":
+        w = dataclasses.replace(I.WORKLOADS["l1b_32k"], n_q_heads=4, n_kv_heads=2, d_head=64, d_phi=192,
+                                name="bf16_wide_phi", seed=78)
+    else:
+        w = I.WORKLOADS[shape]
+    Ls = [L, L // 2 + 1, w.n_sink + w.n_tail + 1, 40]
+    ks = [k, 9, 1, 3]
+    layers = []
+    for i, l in enumerate(Ls):
+        P = I.make_layer(w, L=l, seq=i)
+        P["mlp"] = I.make_mlp_phi(w, layer=i, d_emb=d_emb)
+        layers.append(P)
+    b = H.Batch(H.config_of(w, d_emb=d_emb), layers, ks, debug=True)
+    b.build(); b.decode()
+    assert b.status() == 0
+    for i, (P, kk) in enumerate(zip(layers, ks)):
+        rep = PU.check_layer(w, P, kk, b, i, heads=sorted({0, w.n_q_heads // 2, w.n_q_heads - 1}))
+        print(f"mlp {shape} problem {i}: {rep}", flush=True)
+    # stored features of problem 0 against the oracle's, every KV head
+    O = PU.oracle_inputs(layers[0])
+    _, fk = PU.mlp_feature_fns(layers[0])
+    _, M = orc.partition(Ls[0], w.n_sink, w.n_tail)
+    C = b.result(0, "phi_cache").astype(np.float64)
+    worst = 0.0
+    for h in range(w.n_kv_heads):
+        F = fk[h](O["K"][h, M])
+        assert C[h].shape == F.shape
+        worst = max(worst, float((np.abs(C[h] - F) / F).max()))
+    print(f"mlp {shape}: stored features, worst relative error {worst:.3e}", flush=True)
+    assert worst <= PU.MLP_FEATURE_EPS
