@@ -41,6 +41,9 @@ def main() -> int:
     ap.add_argument("--rotate", type=int, default=8, help="distinct resident layers the steps rotate over")
     ap.add_argument("--cache-features", action="store_true",
                     help="build stores the key features, decode gathers them instead of recomputing (not the headline)")
+    ap.add_argument("--mlp-d-emb", type=int, default=0,
+                    help="width of the one-block ReZero MLP feature maps (512 in the paper's appendix); 0 = the "
+                         "exp-affine maps of the headline.  Implies the feature cache")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 256 MiB device copies (a known-size kernel to scale rocprofv3's "
@@ -60,7 +63,7 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     w = I.WORKLOADS[args.workload]
-    cfg = H.config_of(w, cache_features=args.cache_features)
+    cfg = H.config_of(w, cache_features=args.cache_features, d_emb=args.mlp_d_emb)
     esz = 2 if w.dtype == "bf16" else 4
 
     # ---- inputs, resident in HBM before anything is timed --------------------------------
@@ -79,7 +82,13 @@ def main() -> int:
     n_keep = 1 if model_level else len(pairs)           # host copies kept for the CPU baseline
     layers, dev_layers = [], []
     with concurrent.futures.ThreadPoolExecutor(max_workers=8) as ex:
-        gen = ex.map(lambda a: I.make_layer(w, layer=a[0][0], seq=a[0][1], L=a[1]), zip(pairs, Ls))
+        def make(a):
+            P = I.make_layer(w, layer=a[0][0], seq=a[0][1], L=a[1])
+            if args.mlp_d_emb:
+                P["mlp"] = I.make_mlp_phi(w, layer=a[0][0], d_emb=args.mlp_d_emb)
+            return P
+
+        gen = ex.map(make, zip(pairs, Ls))
         for P in gen:
             if len(layers) < n_keep:
                 layers.append(P)
@@ -115,6 +124,9 @@ def main() -> int:
     build_ms = e0.elapsed_time(e1) / len(batches)                      # per call
     build_bytes = w.n_kv_heads * n_mid * w.d_head * esz * 2            # K and V rows of M, once
     build_flops = w.n_kv_heads * n_mid * (2 * w.d_phi * w.d_head + 2 * w.d_phi * (w.d_head + 1))
+    if args.mlp_d_emb:      # stem, two hidden contractions, output layer, then Phi^T [V 1]; one bf16 pass each
+        E = args.mlp_d_emb
+        build_flops = w.n_kv_heads * n_mid * (2 * (w.d_head * E + 2 * E * E + w.d_phi * E) + 2 * w.d_phi * (w.d_head + 1))
 
     # ---- decode: W warm-up steps, then exactly K timed steps ------------------------------
     for i in range(args.warmup):
@@ -172,7 +184,8 @@ def main() -> int:
                                   f"{w.n_layers} layers), L {min(Ls)}..{max(Ls)}, K {min(Ks)}..{max(Ks)}"
                                   if model_level else f"L {L}, K {K}, one layer per step"),
                    "rotating_layers": 0 if model_level else args.rotate, "problems_per_step": probs_per_step,
-                   "budget_bp": args.budget_bp, "K": K, "L": L, "cache_features": bool(args.cache_features)},
+                   "budget_bp": args.budget_bp, "K": K, "L": L, "cache_features": bool(cfg.cache_features),
+                   "phi": f"one-block ReZero MLP, d_emb {args.mlp_d_emb}" if args.mlp_d_emb else "exp-affine"},
         "step_hbm": {"algorithmic_bytes": bytes_step, "achieved_GBs": bytes_step / (ms_per_step * 1e-3) / 1e9,
                      "frac_of_peak": bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "stage_us": stage_us,
@@ -208,12 +221,14 @@ def main() -> int:
         for li, P in enumerate(layers):
             O = PU.oracle_inputs(P)
             t0 = time.perf_counter()
+            fq, fk = PU.mlp_feature_fns(P)
             S, u = orc.build_summaries(O["K"], O["V"], O["Wk"], O["bk"], w.phi_in_scale, w.phi_norm_coef,
-                                       w.n_sink, w.n_tail)
+                                       w.n_sink, w.n_tail, phi_k_fns=fk)
             t_build += time.perf_counter() - t0
             t0 = time.perf_counter()
             res = orc.decode_layer(O["q"], O["K"], O["V"], S, u, O["Wq"], O["bq"], O["Wk"], O["bk"],
-                                   w.phi_in_scale, w.phi_norm_coef, w.score_scale, w.n_sink, w.n_tail, Ks[li])
+                                   w.phi_in_scale, w.phi_norm_coef, w.score_scale, w.n_sink, w.n_tail, Ks[li],
+                                   phi_q_fns=fq, phi_k_fns=fk)
             t_dec += time.perf_counter() - t0
             n_done += 1
             n_mid_done += mids[li]

@@ -229,12 +229,13 @@ tkphi_status tkphi_decode(const tkphi_config* cfg /*HOST*/,
 /* Profiling helper: the same work as tkphi_decode, with a pair of HIP events attached to
  * every kernel launch (recorded at the kernel's own begin and end on the stream), then a
  * stream synchronisation; stage_ms_out (HOST, TKPHI_N_STAGES floats) receives the
- * duration in milliseconds of each kernel, in launch order:
- *   score_mid, select_plan (+ phi_q), select_emit, select_resolve,
- *   gather (exact branch + subtraction sums), merge
- * (0 for a kernel that the given bounds do not launch).  Same validation and results as
+ * duration in milliseconds of each stage:
+ *   score_mid, select_plan (+ the exp-affine phi_q), select_emit, select_resolve,
+ *   gather (exact branch + subtraction sums), merge, and last the three phi_q launches of
+ *   the MLP feature maps (they run first; begin of the first to end of the third)
+ * (0 for a stage that the given configuration and bounds do not launch).  Same validation and results as
  * tkphi_decode; creates and destroys HIP events (no device memory). */
-#define TKPHI_N_STAGES 6
+#define TKPHI_N_STAGES 7
 tkphi_status tkphi_decode_stage_times(const tkphi_config* cfg /*HOST*/,
                                       const tkphi_problem* problems /*DEVICE table*/,
                                       int32_t n_problems, int32_t max_L, int32_t max_K,

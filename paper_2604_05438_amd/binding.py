@@ -153,7 +153,7 @@ def tkphi_decode(cfg: tkphi_config, problems_dev_ptr: int, n_problems: int, max_
                               workspace_bytes, stream))
 
 
-STAGES = ("score_mid", "select_plan", "select_emit", "select_resolve", "gather", "merge")
+STAGES = ("score_mid", "select_plan", "select_emit", "select_resolve", "gather", "merge", "phi_q_mlp")
 
 
 def tkphi_decode_stage_times(cfg: tkphi_config, problems_dev_ptr: int, n_problems: int, max_L: int, max_K: int,

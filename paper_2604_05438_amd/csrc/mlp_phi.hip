@@ -3,7 +3,7 @@
 // evaluated for the keys of the mid-region at build time, and the summary contraction
 // S = Phi^T V, u = sum Phi (eq. (natural_cache)) from the stored features.
 //
-// Keys: four launches of one tiled matrix-core GEMM per block of kMlpBlock tokens
+// Keys: four launches of one tiled matrix-core GEMM per block of Geom::mlp_block tokens
 //   stem  G = X Ws^T + bs            (X = bf16 key rows: exact, single MFMA pass)
 //   hid   H = GeLU(G W1^T + b1)
 //   res   G = G + alpha (H W2^T + b2)    (in place: a tile reads only its own G entries)
@@ -27,7 +27,7 @@ union Frag {
 enum { EPI_STEM = 0, EPI_HID = 1, EPI_RES = 2, EPI_OUT = 3 };
 
 // ------------------------------------------------------------------------------------
-// grid (kMlpBlock / 64, ceil(Nout / 128), Hkv), 256 threads: a 64-token x 128-output tile,
+// grid (mlp_block / 64, ceil(Nout / 128), Hkv), 256 threads: a 64-token x 128-output tile,
 // wavefront w owns outputs [32w, 32w + 32) (2 MFMA column tiles) of all four 16-token row
 // tiles.  K loop in stages of 64: the A tile goes through LDS as bf16 hi / lo planes (row
 // stride padded by 16 B: conflict-free 16-byte operand reads), the weights go straight from
@@ -59,8 +59,8 @@ __global__ __launch_bounds__(kThreads) void mlp_gemm_kernel(Geom g, const tkphi_
   if (n0 >= Nout) return;
   const char* W = (const char*)(EPI == EPI_STEM ? mp.Ws : EPI == EPI_HID ? mp.W1 : EPI == EPI_RES ? mp.W2 : mp.Wo);
   const float* bias = EPI == EPI_STEM ? mp.bs : EPI == EPI_HID ? mp.b1 : EPI == EPI_RES ? mp.b2 : mp.bo;
-  float* Gb = (float*)(ws + g.off_act) + (size_t)h * kMlpBlock * E;
-  float* Hb = Gb + (size_t)g.Hkv * kMlpBlock * E;
+  float* Gb = (float*)(ws + g.off_act) + (size_t)h * g.mlp_block * E;
+  float* Hb = Gb + (size_t)g.Hkv * g.mlp_block * E;
 
   // A rows: thread (srow = tid / 4, sseg = tid % 4) stages 16 consecutive inputs of row srow
   const int srow = tid >> 2, sseg = tid & 3;
@@ -172,8 +172,8 @@ void launch_mlp_features(const Geom& g, const tkphi_problem* probs, char* ws, hi
   if (g.max_mid == 0) return;
   const int E = g.d_emb;
   for (int p = 0; p < g.n_problems; ++p) {
-    for (int t0 = 0; t0 < g.max_mid; t0 += kMlpBlock) {
-      const int rows = std::min(kMlpBlock, g.max_mid - t0);
+    for (int t0 = 0; t0 < g.max_mid; t0 += g.mlp_block) {
+      const int rows = std::min(g.mlp_block, g.max_mid - t0);
       dim3 ge((rows + 63) / 64, (E + 127) / 128, g.Hkv), go((rows + 63) / 64, (g.dphi + 127) / 128, g.Hkv);
       hipLaunchKernelGGL(mlp_gemm_kernel<EPI_STEM>, ge, dim3(kThreads), 0, s, g, probs, ws, p, t0);
       hipLaunchKernelGGL(mlp_gemm_kernel<EPI_HID>, ge, dim3(kThreads), 0, s, g, probs, ws, p, t0);
@@ -325,6 +325,61 @@ __global__ __launch_bounds__(kThreads) void summary_from_cache_kernel(Geom g, co
       if (tq == 0 && q4 < dphi / 4) bp[(size_t)dphi * D + q4 * 4 + e] = x;
     }
   }
+}
+
+// ------------------------------------------------------------------------------------
+// phi_q of every query head (decode side): the same chain as matrix-vector products in fp32,
+// three launches so that each layer is spread over the chip.  grid (slices, Hq, n_problems),
+// 1024 threads; a workgroup owns 64 output rows of its layer:
+//   stage 0: g0 = Ws q + bs (every workgroup of the head recomputes it: 2 d d_emb bytes from L2),
+//            h[rows] = GeLU(W1[rows] g0 + b1[rows]); slice 0 also stores g0
+//   stage 1: g[rows] = g0[rows] + alpha (W2[rows] h + b2[rows])
+//   stage 2: phi_q[rows] = exp(Wo[rows] g + bo[rows])
+// ------------------------------------------------------------------------------------
+template <int STAGE>
+__global__ __launch_bounds__(kSelThreads) void mlp_phi_q_kernel(Geom g, const tkphi_problem* __restrict__ probs,
+                                                                char* __restrict__ ws) {
+  __shared__ float xs[128];
+  __shared__ float vin[1024];
+  const int gq = blockIdx.y, p = blockIdx.z, tid = threadIdx.x;
+  const tkphi_problem pr = probs[p];
+  if (pr.L < 1 || pr.L > g.max_L) return;
+  char* blk = problem_block(g, ws, p);
+  const int E = g.d_emb;
+  float* gbuf = (float*)(blk + g.off_mlpq) + (size_t)gq * 2 * E;
+  float* hbuf = gbuf + E;
+  const tkphi_mlp mp = pr.mlp_q[gq];
+  const int j0 = blockIdx.x * 64;
+  if (STAGE == 0) {
+    for (int c = tid; c < g.d; c += kSelThreads) xs[c] = Elem<uint16_t>::load1(pr.q, (int64_t)gq * g.d + c);
+    __syncthreads();
+    gemv_bf16_rows(mp.Ws, E, g.d, xs, [&](int j, float dot) { vin[j] = dot + mp.bs[j]; });
+    __syncthreads();
+    if (blockIdx.x == 0)
+      for (int j = tid; j < E; j += kSelThreads) gbuf[j] = vin[j];
+    gemv_bf16_rows((const char*)mp.W1 + (size_t)j0 * E * 2, min(64, E - j0), E, vin,
+                   [&](int j, float dot) { hbuf[j0 + j] = gelu_erf(dot + mp.b1[j0 + j]); });
+  } else if (STAGE == 1) {
+    for (int j = tid; j < E; j += kSelThreads) vin[j] = hbuf[j];
+    __syncthreads();
+    gemv_bf16_rows((const char*)mp.W2 + (size_t)j0 * E * 2, min(64, E - j0), E, vin,
+                   [&](int j, float dot) { gbuf[j0 + j] = fmaf(mp.alpha, dot + mp.b2[j0 + j], gbuf[j0 + j]); });
+  } else {
+    for (int j = tid; j < E; j += kSelThreads) vin[j] = gbuf[j];
+    __syncthreads();
+    float* phiq = (float*)(blk + g.off_phiq) + (size_t)gq * g.dphi;
+    gemv_bf16_rows((const char*)mp.Wo + (size_t)j0 * E * 2, min(64, g.dphi - j0), E, vin,
+                   [&](int j, float dot) { phiq[j0 + j] = expf(dot + mp.bo[j0 + j]); });
+  }
+}
+
+void launch_mlp_phi_q(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
+  dim3 ge(g.d_emb / 64, g.Hq, g.n_problems), go((g.dphi + 63) / 64, g.Hq, g.n_problems);
+  KernelTimer* t = g_kernel_timer;            // the three launches are one timed stage
+  if (t) t->used[ST_PHIQ] = true;
+  hipExtLaunchKernelGGL(mlp_phi_q_kernel<0>, ge, dim3(kSelThreads), 0, s, t ? t->start[ST_PHIQ] : nullptr, nullptr, 0, g, probs, ws);
+  hipLaunchKernelGGL(mlp_phi_q_kernel<1>, ge, dim3(kSelThreads), 0, s, g, probs, ws);
+  hipExtLaunchKernelGGL(mlp_phi_q_kernel<2>, go, dim3(kSelThreads), 0, s, nullptr, t ? t->stop[ST_PHIQ] : nullptr, 0, g, probs, ws);
 }
 
 template <int D, int FTW>

@@ -132,6 +132,7 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   g->off_selidx = p;  p = align_up(p + (size_t)g->Hq * std::max(max_K, 1) * sizeof(int32_t), 256);
   g->off_selscore = p; p = align_up(p + (size_t)g->Hq * std::max(max_K, 1) * sizeof(float), 256);
   g->off_phiq = p;    p = align_up(p + (size_t)g->Hq * g->dphi * sizeof(float), 256);
+  g->off_mlpq = p;    p = align_up(p + (size_t)g->Hq * 2 * g->d_emb * sizeof(float), 256);
   g->off_part = p;
   p = align_up(p + (size_t)g->Hq * (g->n_tiles + g->n_atiles) * g->part_stride * sizeof(float), 256);
   g->per_problem = p;
@@ -141,8 +142,12 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
                                                 (size_t)g->dphi * (g->d + 1) * sizeof(float);
   size_t build_all = build_total;
   if (cfg->phi_kind == TKPHI_PHI_MLP) {
+    // the fp32 activations of a token block (g and h, every KV head) are written by one GEMM launch and
+    // read by the next: about 64 MB of them stay in the 256 MB last-level cache between the launches
+    const int64_t blk = ((int64_t)64 << 20) / ((int64_t)2 * g->Hkv * g->d_emb * sizeof(float));
+    g->mlp_block = (int)std::clamp<int64_t>(env_int("TKPHI_MLP_BLOCK", (int)blk) / 64 * 64, 64, 8192);
     g->off_act = align_up(build_total, 256);
-    build_all = g->off_act + (size_t)2 * g->Hkv * kMlpBlock * g->d_emb * sizeof(float);
+    build_all = g->off_act + (size_t)2 * g->Hkv * g->mlp_block * g->d_emb * sizeof(float);
   }
   g->total_bytes = align_up(std::max(decode_total, build_all), 256);
   return TKPHI_OK;
@@ -212,6 +217,7 @@ tkphi_status tkphi_decode(const tkphi_config* cfg, const tkphi_problem* problems
   hipStream_t s = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
   (void)hipGetLastError();
+  if (g.phi_kind == TKPHI_PHI_MLP) launch_mlp_phi_q(g, problems, ws, s);
   launch_score_mid(g, problems, ws, s);
   launch_select(g, problems, ws, s);
   launch_gather(g, problems, ws, s);
@@ -250,6 +256,7 @@ tkphi_status tkphi_decode_stage_times(const tkphi_config* cfg, const tkphi_probl
     for (int i = 0; i < ST_COUNT; ++i) { t.start[i] = ev[2 * i]; t.stop[i] = ev[2 * i + 1]; t.used[i] = false; }
     (void)hipGetLastError();
     g_kernel_timer = &t;
+    if (g.phi_kind == TKPHI_PHI_MLP) launch_mlp_phi_q(g, problems, ws, s);
     launch_score_mid(g, problems, ws, s);
     launch_select(g, problems, ws, s);
     launch_gather(g, problems, ws, s);

@@ -35,6 +35,7 @@ struct Geom {
   int scan_chunk, n_scan_chunks;     // score_mid: mid tokens per workgroup
   int scan_unit;         // tokens a score_mid workgroup takes per iteration (scan_chunk is a multiple)
   int phi_kind, d_emb;   // tkphi_phi_kind; MLP width
+  int mlp_block;         // MLP build: tokens per KV head whose activations are held at once (multiple of 64)
   int cache;             // 1: key features are stored by the build and gathered by decode (cfg.cache_features)
   int diag;              // 1: the select emit pass also reduces the entropy / mass diagnostics
   int interleave;        // 1: chunk c owns the units c, c + n_chunks, c + 2 n_chunks, ... of its problem
@@ -58,9 +59,10 @@ struct Geom {
   size_t off_selidx;     // int32    [Hq][max_K]                 retrieved mid indices
   size_t off_selscore;   // float    [Hq][max_K]                 their scores
   size_t off_phiq;       // float    [Hq][dphi]
+  size_t off_mlpq;       // float    [Hq][2][d_emb]                  MLP phi_q: stem / residual stream g, hidden h
   size_t off_part;       // float    [Hq][n_tiles + n_atiles][part_stride]  (retrieved tiles, then anchor tiles)
   size_t off_bpart;      // float    [Hkv][n_build_chunks][dphi*(d+1)]   (build only; aliases the block)
-  size_t off_act;        // float    2 x [Hkv][kMlpBlock][d_emb]         (MLP build only: activations g, h of a token block)
+  size_t off_act;        // float    2 x [Hkv][mlp_block][d_emb]          (MLP build only: activations g, h of a token block)
   size_t total_bytes;
 };
 
@@ -70,7 +72,7 @@ void set_error(const char* fmt, ...);
 
 // Optional per-kernel timing: while g_kernel_timer is set (by tkphi_decode_stage_times, on
 // the calling thread) a launch records the kernel's own begin / end on the two events.
-enum Stage { ST_SCORE = 0, ST_PLAN, ST_EMIT, ST_RESOLVE, ST_GATHER, ST_MERGE, ST_COUNT, ST_UNTIMED = -1 };
+enum Stage { ST_SCORE = 0, ST_PLAN, ST_EMIT, ST_RESOLVE, ST_GATHER, ST_MERGE, ST_PHIQ, ST_COUNT, ST_UNTIMED = -1 };
 struct KernelTimer {
   hipEvent_t start[ST_COUNT], stop[ST_COUNT];
   bool used[ST_COUNT];
@@ -95,7 +97,6 @@ struct SelPlan {
   int32_t nb;      // tokens in the boundary bin
   int32_t n_sel;   // retrieved tokens K' = min(topk, |M|, max_K)
 };
-constexpr int kMlpBlock = 8192;        // tokens per KV head whose MLP activations are held at once
 constexpr int kMaxScanChunks = 2048;   // chunk offsets are scanned in LDS by `plan`
 
 // kernel launchers (each defined next to its kernels)
@@ -105,6 +106,7 @@ void launch_gather(const Geom& g, const tkphi_problem* probs, char* ws, hipStrea
 void launch_merge(const Geom& g, const tkphi_problem* probs, char* ws, int mode, hipStream_t s);
 void launch_build(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
 void launch_mlp_features(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);     // -> phi_cache
+void launch_mlp_phi_q(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);        // -> phi_q of every query head
 void launch_summary_from_cache(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s); // -> chunk partials
 
 #ifdef __HIPCC__
@@ -289,26 +291,6 @@ __device__ __forceinline__ void gemv_bf16_rows(const void* W, int N, int Kd, con
 }
 
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
-
-// phi_q of query head gq with the one-block ReZero MLP (App. "Head-wise phi architecture"):
-//   g0 = Ws q + bs;  g1 = g0 + alpha (W2 GeLU(W1 g0 + b1) + b2);  phi_q = exp(Wo g1 + bo)
-// as four matrix-vector products in fp32 by one workgroup.  xs: LDS, >= d_head floats; gs, hs:
-// LDS, >= d_emb floats each.
-__device__ __forceinline__ void phi_q_mlp_head(const Geom& g, const tkphi_problem& pr, char* blk, int gq,
-                                               float* xs, float* gs, float* hs) {
-  const tkphi_mlp mp = pr.mlp_q[gq];
-  const int E = g.d_emb;
-  float* phiq = (float*)(blk + g.off_phiq) + (size_t)gq * g.dphi;
-  for (int c = threadIdx.x; c < g.d; c += blockDim.x) xs[c] = Elem<uint16_t>::load1(pr.q, (int64_t)gq * g.d + c);
-  __syncthreads();
-  gemv_bf16_rows(mp.Ws, E, g.d, xs, [&](int j, float dot) { gs[j] = dot + mp.bs[j]; });
-  __syncthreads();
-  gemv_bf16_rows(mp.W1, E, E, gs, [&](int j, float dot) { hs[j] = gelu_erf(dot + mp.b1[j]); });
-  __syncthreads();
-  gemv_bf16_rows(mp.W2, E, E, hs, [&](int j, float dot) { gs[j] = fmaf(mp.alpha, dot + mp.b2[j], gs[j]); });
-  __syncthreads();
-  gemv_bf16_rows(mp.Wo, g.dphi, E, gs, [&](int j, float dot) { phiq[j] = expf(dot + mp.bo[j]); });
-}
 
 // device status word: recomputed from the problem lengths by one workgroup per decode call
 __device__ __forceinline__ void write_device_status(const Geom& g, const tkphi_problem* probs, char* ws) {

@@ -111,11 +111,11 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(Geom g, const 
   const tkphi_problem pr = probs[p];
   if (pr.L < 1 || pr.L > g.max_L) return;
   if (side_job || !split) {
-    if (g.phi_kind == TKPHI_PHI_MLP) phi_q_mlp_head(g, pr, blk, gq, (float*)sh_tot, (float*)sh_ca, (float*)sh_cc);
+    if (g.phi_kind == TKPHI_PHI_MLP) { if (side_job) return; }    // phi_q came from the MLP launches
     else if (g.dtype == TKPHI_BF16) phi_q_head<uint16_t>(g, pr, blk, gq, (float*)sh_tot);
     else phi_q_head<float>(g, pr, blk, gq, (float*)sh_tot);
     if (side_job) return;
-    __syncthreads();                     // sh_tot (and, for the MLP, sh_ca / sh_cc) served as scratch
+    __syncthreads();                     // sh_tot served as scratch
   }
   const int n = mid_size(pr.L, g.n_sink, g.n_tail);
   const int Ksel = max(0, min(min(pr.topk, n), g.max_K));
@@ -431,7 +431,7 @@ __global__ __launch_bounds__(kSelThreads) void select_resolve_kernel(Geom g, con
 }
 
 void launch_select(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
-  dim3 pgrid((g.Hq * g.n_problems <= 128 || g.phi_kind == TKPHI_PHI_MLP ? 2 : 1) * g.Hq, g.n_problems);   // the MLP phi_q is long: always beside the planning
+  dim3 pgrid((g.Hq * g.n_problems <= 128 && g.phi_kind != TKPHI_PHI_MLP ? 2 : 1) * g.Hq, g.n_problems);
   TKPHI_LAUNCH(ST_PLAN, select_plan_kernel, pgrid, dim3(kSelThreads), 0, s, g, probs, ws);
   const bool selecting = g.max_mid > 0 && g.max_K > 0;
   if (!selecting && !(g.diag && g.max_mid > 0)) return;
