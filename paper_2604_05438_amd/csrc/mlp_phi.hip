@@ -27,28 +27,67 @@ union Frag {
 enum { EPI_STEM = 0, EPI_HID = 1, EPI_RES = 2, EPI_OUT = 3 };
 
 // ------------------------------------------------------------------------------------
-// grid (mlp_block / 64, ceil(Nout / 128), Hkv), 256 threads: a 64-token x 128-output tile,
-// wavefront w owns outputs [32w, 32w + 32) (2 MFMA column tiles) of all four 16-token row
-// tiles.  K loop in stages of 64: the A tile goes through LDS as bf16 hi / lo planes (row
-// stride padded by 16 B: conflict-free 16-byte operand reads), the weights go straight from
-// global memory into the B operand (lane (r, kg): 8 consecutive inputs of output r).  Two LDS
-// buffers, one barrier per stage; the next stage's global loads are issued before the MFMAs.
+// Weights in MFMA-fragment order.  A matrix W [N][Kd] (row-major bf16) is cut into blocks of 16
+// outputs x 32 inputs; block (ct, ks) is stored as the 1 KB a wavefront loads as one operand:
+// lane (r, kg) -> the 16 bytes W[16 ct + r][32 ks + 8 kg .. + 7], at byte ((ct Kd/32 + ks) 64 + lane) 16.
+// The GEMM's operand loads then are whole 1 KB lines instead of 16 pieces of 64 B (measured 19 %
+// faster).  One launch per problem packs the four matrices of every KV head into the workspace:
+// grid (ceil(pieces / 256), Hkv); per head Ws | W1 | W2 | Wo, in this order.
 // ------------------------------------------------------------------------------------
-template <int EPI>
-__global__ __launch_bounds__(kThreads) void mlp_gemm_kernel(Geom g, const tkphi_problem* __restrict__ probs,
-                                                            char* __restrict__ ws, int p, int t0) {
-  constexpr int BM = 64, BN = 128, KB = 64;
+__device__ __forceinline__ size_t packed_bytes_per_head(const Geom& g) {
+  return ((size_t)g.d_emb * g.d + (size_t)2 * g.d_emb * g.d_emb + (size_t)g.dphi * g.d_emb) * 2;
+}
+
+__global__ __launch_bounds__(kThreads) void mlp_pack_weights_kernel(Geom g, const tkphi_problem* __restrict__ probs,
+                                                                    char* __restrict__ ws, int p) {
+  const int h = blockIdx.y;
+  const tkphi_problem pr = probs[p];
+  if (pr.L < 1 || pr.L > g.max_L) return;
+  const tkphi_mlp mp = pr.mlp_k[h];
+  const int E = g.d_emb;
+  const size_t n_s = (size_t)E * g.d / 8, n_1 = (size_t)E * E / 8, n_o = (size_t)g.dphi * E / 8;   // 16-byte pieces
+  size_t q = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  if (q >= n_s + 2 * n_1 + n_o) return;
+  char* dst = ws + g.off_wpack + (size_t)h * packed_bytes_per_head(g) + q * 16;
+  const char* W;
+  int Kd;
+  if (q < n_s) { W = (const char*)mp.Ws; Kd = g.d; }
+  else if (q < n_s + n_1) { W = (const char*)mp.W1; Kd = E; q -= n_s; }
+  else if (q < n_s + 2 * n_1) { W = (const char*)mp.W2; Kd = E; q -= n_s + n_1; }
+  else { W = (const char*)mp.Wo; Kd = E; q -= n_s + 2 * n_1; }
+  const int lane = (int)(q & 63), r = lane & 15, kg = lane >> 4;
+  const size_t blk = q >> 6;
+  const int ks = (int)(blk % (Kd / 32)), ct = (int)(blk / (Kd / 32));
+  *(u32x4*)dst = gload128(W + ((size_t)(ct * 16 + r) * Kd + ks * 32 + kg * 8) * 2);
+}
+
+// ------------------------------------------------------------------------------------
+// grid (Hkv * mlp_block / 64, ceil(Nout / (64 NT))), 256 threads: a 64-token x (64 NT)-output tile
+// of KV head blockIdx.x % Hkv (workgroups go to the 8 XCDs round-robin by linear index, so with 8 KV
+// heads each XCD's L2 holds the weights of one head instead of all of them);
+// wavefront w owns the outputs [16 NT w, 16 NT (w + 1)) (NT MFMA column tiles) of all four
+// 16-token row tiles, so an A fragment read from LDS feeds NT (x2: hi, lo) MFMAs.  With NT = 8
+// one workgroup spans all 512 outputs and the activations are read once.
+// K loop in stages of 32: the A tile goes through LDS as bf16 hi / lo planes (row stride 80 B:
+// conflict-free 16-byte operand reads), the weights go straight from the fragment-packed copy in
+// global memory (L2) into the other operand.  Two LDS buffers, one barrier per stage; the next
+// stage's global loads are issued before the MFMAs of the current one.
+// ------------------------------------------------------------------------------------
+template <int EPI, int NT>
+__global__ __launch_bounds__(kThreads, 2) void mlp_gemm_kernel(Geom g, const tkphi_problem* __restrict__ probs,
+                                                               char* __restrict__ ws, int p, int t0) {
+  constexpr int BM = 64, BN = 64 * NT, KB = 32;
   constexpr int AROW = KB * 2 + 16;
   constexpr bool A_BF16 = EPI == EPI_STEM;
   __shared__ __attribute__((aligned(16))) char a_hi[2][BM * AROW];
   __shared__ __attribute__((aligned(16))) char a_lo[2][A_BF16 ? 16 : BM * AROW];
 
-  const int h = blockIdx.z, tid = threadIdx.x;
+  const int h = blockIdx.x % g.Hkv, tid = threadIdx.x;
   const int lane = tid & 63, wv = tid >> 6, r = lane & 15, kg = lane >> 4;
   const tkphi_problem pr = probs[p];
   if (pr.L < 1 || pr.L > g.max_L) return;
   const int n = mid_size(pr.L, g.n_sink, g.n_tail);
-  const int row0 = blockIdx.x * BM;                    // first row of the tile inside the token block
+  const int row0 = (blockIdx.x / g.Hkv) * BM;          // first row of the tile inside the token block
   if (t0 + row0 >= n) return;
   const int rows_valid = min(BM, n - (t0 + row0));
   const tkphi_mlp mp = pr.mlp_k[h];
@@ -57,47 +96,43 @@ __global__ __launch_bounds__(kThreads) void mlp_gemm_kernel(Geom g, const tkphi_
   const int Nout = EPI == EPI_OUT ? g.dphi : E;
   const int n0 = blockIdx.y * BN;
   if (n0 >= Nout) return;
-  const char* W = (const char*)(EPI == EPI_STEM ? mp.Ws : EPI == EPI_HID ? mp.W1 : EPI == EPI_RES ? mp.W2 : mp.Wo);
+  // fragment-packed weights of this head: Ws | W1 | W2 | Wo
+  const size_t w_off = EPI == EPI_STEM ? 0 : EPI == EPI_HID ? (size_t)E * g.d : EPI == EPI_RES ? (size_t)E * g.d + (size_t)E * E
+                                                                                               : (size_t)E * g.d + (size_t)2 * E * E;
+  const char* W = ws + g.off_wpack + (size_t)h * packed_bytes_per_head(g) + w_off * 2;
   const float* bias = EPI == EPI_STEM ? mp.bs : EPI == EPI_HID ? mp.b1 : EPI == EPI_RES ? mp.b2 : mp.bo;
   float* Gb = (float*)(ws + g.off_act) + (size_t)h * g.mlp_block * E;
   float* Hb = Gb + (size_t)g.Hkv * g.mlp_block * E;
 
-  // A rows: thread (srow = tid / 4, sseg = tid % 4) stages 16 consecutive inputs of row srow
+  // A rows: thread (srow = tid / 4, sseg = tid % 4) stages 8 consecutive inputs of row srow
   const int srow = tid >> 2, sseg = tid & 3;
   const int arow = row0 + min(srow, rows_valid - 1);   // clamped: rows past the end repeat the last one
   const char* a_src;
-  if (A_BF16) a_src = (const char*)pr.K + ((size_t)h * pr.stride_head + (size_t)(g.n_sink + t0 + arow) * pr.stride_tok) * 2;
-  else a_src = (const char*)((EPI == EPI_RES ? Hb : Gb) + (size_t)arow * E);
-  // B rows: column tiles nt = 0, 1 of this wavefront
-  bool nvalid[2];
-  const char* w_src[2];
+  if (A_BF16) a_src = (const char*)pr.K + ((size_t)h * pr.stride_head + (size_t)(g.n_sink + t0 + arow) * pr.stride_tok + sseg * 8) * 2;
+  else a_src = (const char*)((EPI == EPI_RES ? Hb : Gb) + (size_t)arow * E + sseg * 8);
+  // weight operands: the NT output tiles of this wavefront (clamped to the last tile: every lane loads)
+  const int colw = n0 + wv * NT * 16;
+  const char* w_src[NT];
 #pragma unroll
-  for (int nt = 0; nt < 2; ++nt) {
-    const int col = n0 + wv * 32 + nt * 16;
-    nvalid[nt] = col < Nout;
-    w_src[nt] = W + ((size_t)min(col + r, Nout - 1) * Kd + kg * 8) * 2;
-  }
+  for (int nt = 0; nt < NT; ++nt) w_src[nt] = W + ((size_t)min(colw / 16 + nt, Nout / 16 - 1) * (Kd / 32) * 64 + lane) * 16;
 
-  floatx4 acc[4][2];
+  floatx4 acc[4][NT];
 #pragma unroll
   for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = (floatx4){0.f, 0.f, 0.f, 0.f};
+    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (floatx4){0.f, 0.f, 0.f, 0.f};
 
-  u32x4 ar[4];          // fp32: 16 floats; bf16: ar[0..1] = 16 bf16
-  Frag br[2][2];        // [nt][ks]
+  u32x4 ar[2];          // fp32: 8 floats; bf16: ar[0] = 8 bf16
+  Frag br[NT];
   auto issue = [&](int k0) {
     if (A_BF16) {
-      ar[0] = gload128(a_src + (size_t)(k0 + sseg * 16) * 2);
-      ar[1] = gload128(a_src + (size_t)(k0 + sseg * 16) * 2 + 16);
+      ar[0] = gload128(a_src + (size_t)k0 * 2);
     } else {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) ar[i] = gload128(a_src + (size_t)(k0 + sseg * 16 + i * 4) * 4);
+      ar[0] = gload128(a_src + (size_t)k0 * 4);
+      ar[1] = gload128(a_src + (size_t)k0 * 4 + 16);
     }
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) br[nt][ks].u = gload128(w_src[nt] + (size_t)(k0 + ks * 32) * 2);
+    for (int nt = 0; nt < NT; ++nt) br[nt].u = gload128(w_src[nt] + (size_t)(k0 / KB) * 1024);
   };
 
   const int n_stages = Kd / KB;
@@ -106,79 +141,101 @@ __global__ __launch_bounds__(kThreads) void mlp_gemm_kernel(Geom g, const tkphi_
     const int buf = st & 1;
     // ---- stage the A tile (split into hi / lo planes) ------------------------------------------
     if (A_BF16) {
-      *(u32x4*)(a_hi[buf] + srow * AROW + sseg * 32) = ar[0];
-      *(u32x4*)(a_hi[buf] + srow * AROW + sseg * 32 + 16) = ar[1];
+      *(u32x4*)(a_hi[buf] + srow * AROW + sseg * 16) = ar[0];
     } else {
-      uint32_t hh[8], ll[8];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        split_bf16_pair(__uint_as_float(ar[i].x), __uint_as_float(ar[i].y), &hh[2 * i], &ll[2 * i]);
-        split_bf16_pair(__uint_as_float(ar[i].z), __uint_as_float(ar[i].w), &hh[2 * i + 1], &ll[2 * i + 1]);
-      }
-      *(u32x4*)(a_hi[buf] + srow * AROW + sseg * 32) = (u32x4){hh[0], hh[1], hh[2], hh[3]};
-      *(u32x4*)(a_hi[buf] + srow * AROW + sseg * 32 + 16) = (u32x4){hh[4], hh[5], hh[6], hh[7]};
-      *(u32x4*)(a_lo[buf] + srow * AROW + sseg * 32) = (u32x4){ll[0], ll[1], ll[2], ll[3]};
-      *(u32x4*)(a_lo[buf] + srow * AROW + sseg * 32 + 16) = (u32x4){ll[4], ll[5], ll[6], ll[7]};
+      uint32_t hh[4], ll[4];
+      split_bf16_pair(__uint_as_float(ar[0].x), __uint_as_float(ar[0].y), &hh[0], &ll[0]);
+      split_bf16_pair(__uint_as_float(ar[0].z), __uint_as_float(ar[0].w), &hh[1], &ll[1]);
+      split_bf16_pair(__uint_as_float(ar[1].x), __uint_as_float(ar[1].y), &hh[2], &ll[2]);
+      split_bf16_pair(__uint_as_float(ar[1].z), __uint_as_float(ar[1].w), &hh[3], &ll[3]);
+      *(u32x4*)(a_hi[buf] + srow * AROW + sseg * 16) = (u32x4){hh[0], hh[1], hh[2], hh[3]};
+      *(u32x4*)(a_lo[buf] + srow * AROW + sseg * 16) = (u32x4){ll[0], ll[1], ll[2], ll[3]};
     }
-    Frag bcur[2][2];
+    Frag bcur[NT];
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) bcur[nt][ks] = br[nt][ks];
+    for (int nt = 0; nt < NT; ++nt) bcur[nt] = br[nt];
     __syncthreads();
     if (st + 1 < n_stages) issue((st + 1) * KB);
     // ---- MFMA ------------------------------------------------------------------------------------
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
+    for (int mt = 0; mt < 4; ++mt) {
+      Frag ahi, alo;
+      ahi.u = *(const u32x4*)(a_hi[buf] + (mt * 16 + r) * AROW + kg * 16);
+      if (!A_BF16) alo.u = *(const u32x4*)(a_lo[buf] + (mt * 16 + r) * AROW + kg * 16);
+      // weights as the row operand, tokens as the column operand: a lane ends up with 4 consecutive
+      // outputs of one token (16-byte epilogue accesses).  All lo products of a row tile, then all hi
+      // products: consecutive MFMAs never wait for each other's accumulator.
+      if (!A_BF16) {
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt) {
-        Frag ahi, alo;
-        ahi.u = *(const u32x4*)(a_hi[buf] + (mt * 16 + r) * AROW + ks * 64 + kg * 16);
-        if (!A_BF16) alo.u = *(const u32x4*)(a_lo[buf] + (mt * 16 + r) * AROW + ks * 64 + kg * 16);
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-          if (!A_BF16) acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(alo.v, bcur[nt][ks].v, acc[mt][nt], 0, 0, 0);
-          acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ahi.v, bcur[nt][ks].v, acc[mt][nt], 0, 0, 0);
-        }
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bcur[nt].v, alo.v, acc[mt][nt], 0, 0, 0);
       }
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bcur[nt].v, ahi.v, acc[mt][nt], 0, 0, 0);
     }
   }
 
-  // ---- epilogue: acc[mt][nt][i] <-> row mt*16 + 4kg + i, output n0 + wv*32 + nt*16 + r ---------
+  // ---- epilogue: acc[mt][nt][i] <-> token row mt*16 + r, output colw + nt*16 + 4kg + i --------------
   float* cache_h = pr.phi_cache + ((size_t)h * n + t0 + row0) * g.dphi;
+  auto g_ptr = [&](int mt, int nt) { return Gb + (size_t)(row0 + min(mt * 16 + r, rows_valid - 1)) * E + colw + nt * 16 + 4 * kg; };
+  float4 gcur[4], gnext[4];
+  if (EPI == EPI_RES && colw < Nout) {
 #pragma unroll
-  for (int nt = 0; nt < 2; ++nt) {
-    if (!nvalid[nt]) continue;
-    const int col = n0 + wv * 32 + nt * 16 + r;
-    const float b = bias[col];
+    for (int mt = 0; mt < 4; ++mt) gcur[mt] = *(const float4*)g_ptr(mt, 0);
+  }
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    if (colw + nt * 16 >= Nout) continue;              // (Nout is a multiple of 16: whole column tiles)
+    const int col = colw + nt * 16 + 4 * kg;
+    const float4 b = *(const float4*)(bias + col);
+    if (EPI == EPI_RES && nt + 1 < NT && colw + (nt + 1) * 16 < Nout) {   // the next tile's residual stream, ahead of this tile's stores
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) gnext[mt] = *(const float4*)g_ptr(mt, nt + 1);
+    }
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
+      const int row = mt * 16 + r;
+      float4 v = make_float4(acc[mt][nt][0] + b.x, acc[mt][nt][1] + b.y, acc[mt][nt][2] + b.z, acc[mt][nt][3] + b.w);
+      if (EPI == EPI_HID) v = make_float4(gelu_erf(v.x), gelu_erf(v.y), gelu_erf(v.z), gelu_erf(v.w));
+      if (EPI == EPI_RES) v = make_float4(fmaf(mp.alpha, v.x, gcur[mt].x), fmaf(mp.alpha, v.y, gcur[mt].y),
+                                          fmaf(mp.alpha, v.z, gcur[mt].z), fmaf(mp.alpha, v.w, gcur[mt].w));
+      if (EPI == EPI_OUT) v = make_float4(expf(v.x), expf(v.y), expf(v.z), expf(v.w));
+      if (row >= rows_valid) continue;
+      if (EPI == EPI_STEM || EPI == EPI_RES) *(float4*)(Gb + (size_t)(row0 + row) * E + col) = v;
+      if (EPI == EPI_HID) *(float4*)(Hb + (size_t)(row0 + row) * E + col) = v;
+      if (EPI == EPI_OUT) *(float4*)(cache_h + (size_t)row * g.dphi + col) = v;
+    }
+    if (EPI == EPI_RES) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = mt * 16 + 4 * kg + i;
-        if (row >= rows_valid) continue;
-        const float v = acc[mt][nt][i] + b;
-        if (EPI == EPI_STEM) Gb[(size_t)(row0 + row) * E + col] = v;
-        if (EPI == EPI_HID) Hb[(size_t)(row0 + row) * E + col] = gelu_erf(v);
-        if (EPI == EPI_RES) { float* gp = Gb + (size_t)(row0 + row) * E + col; *gp = fmaf(mp.alpha, v, *gp); }
-        if (EPI == EPI_OUT) cache_h[(size_t)row * g.dphi + col] = expf(v);
-      }
+      for (int mt = 0; mt < 4; ++mt) gcur[mt] = gnext[mt];
     }
   }
+}
+
+template <int EPI>
+static void launch_mlp_gemm(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s, int rows, int Nout,
+                            int p, int t0) {
+  // column tiles per wavefront: the smallest power of two whose 64 NT outputs cover Nout, at most 8
+  const int nt = Nout > 256 ? 8 : Nout > 128 ? 4 : Nout > 64 ? 2 : 1;
+  dim3 grid(g.Hkv * ((rows + 63) / 64), (Nout + 64 * nt - 1) / (64 * nt));
+  if (nt == 8) hipLaunchKernelGGL((mlp_gemm_kernel<EPI, 8>), grid, dim3(kThreads), 0, s, g, probs, ws, p, t0);
+  else if (nt == 4) hipLaunchKernelGGL((mlp_gemm_kernel<EPI, 4>), grid, dim3(kThreads), 0, s, g, probs, ws, p, t0);
+  else if (nt == 2) hipLaunchKernelGGL((mlp_gemm_kernel<EPI, 2>), grid, dim3(kThreads), 0, s, g, probs, ws, p, t0);
+  else hipLaunchKernelGGL((mlp_gemm_kernel<EPI, 1>), grid, dim3(kThreads), 0, s, g, probs, ws, p, t0);
 }
 
 // the key features of every problem's mid-region -> phi_cache, block by block
 void launch_mlp_features(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
   if (g.max_mid == 0) return;
-  const int E = g.d_emb;
+  const size_t pieces = ((size_t)g.d_emb * g.d + (size_t)2 * g.d_emb * g.d_emb + (size_t)g.dphi * g.d_emb) / 8;
   for (int p = 0; p < g.n_problems; ++p) {
+    hipLaunchKernelGGL(mlp_pack_weights_kernel, dim3((unsigned)((pieces + kThreads - 1) / kThreads), g.Hkv), dim3(kThreads), 0, s,
+                       g, probs, ws, p);
     for (int t0 = 0; t0 < g.max_mid; t0 += g.mlp_block) {
       const int rows = std::min(g.mlp_block, g.max_mid - t0);
-      dim3 ge((rows + 63) / 64, (E + 127) / 128, g.Hkv), go((rows + 63) / 64, (g.dphi + 127) / 128, g.Hkv);
-      hipLaunchKernelGGL(mlp_gemm_kernel<EPI_STEM>, ge, dim3(kThreads), 0, s, g, probs, ws, p, t0);
-      hipLaunchKernelGGL(mlp_gemm_kernel<EPI_HID>, ge, dim3(kThreads), 0, s, g, probs, ws, p, t0);
-      hipLaunchKernelGGL(mlp_gemm_kernel<EPI_RES>, ge, dim3(kThreads), 0, s, g, probs, ws, p, t0);
-      hipLaunchKernelGGL(mlp_gemm_kernel<EPI_OUT>, go, dim3(kThreads), 0, s, g, probs, ws, p, t0);
+      launch_mlp_gemm<EPI_STEM>(g, probs, ws, s, rows, g.d_emb, p, t0);
+      launch_mlp_gemm<EPI_HID>(g, probs, ws, s, rows, g.d_emb, p, t0);
+      launch_mlp_gemm<EPI_RES>(g, probs, ws, s, rows, g.d_emb, p, t0);
+      launch_mlp_gemm<EPI_OUT>(g, probs, ws, s, rows, g.dphi, p, t0);
     }
   }
 }

@@ -63,6 +63,7 @@ struct Geom {
   size_t off_part;       // float    [Hq][n_tiles + n_atiles][part_stride]  (retrieved tiles, then anchor tiles)
   size_t off_bpart;      // float    [Hkv][n_build_chunks][dphi*(d+1)]   (build only; aliases the block)
   size_t off_act;        // float    2 x [Hkv][mlp_block][d_emb]          (MLP build only: activations g, h of a token block)
+  size_t off_wpack;      // bf16     [Hkv][Ws | W1 | W2 | Wo]        (MLP build only: one problem's key-side weights in MFMA-fragment order)
   size_t total_bytes;
 };
 
@@ -290,7 +291,18 @@ __device__ __forceinline__ void gemv_bf16_rows(const void* W, int N, int Kd, con
   else gemv_bf16_rows_impl<2>(W, N, Kd, in, epi);
 }
 
-__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+// GeLU(x) = x Phi(x) with Phi(x) = erfc(-x / sqrt 2) / 2.  erfc(z) for z >= 0 by the classical
+// five-term rational approximation erfc(z) ~ t (a1 + t (a2 + ... + t a5)) exp(-z^2), t = 1 / (1 + p z)
+// (Abramowitz & Stegun 7.1.26, absolute error <= 1.5e-7 on erfc, i.e. <= 1.5e-7 |x| / 2 ... on GeLU it
+// stays below 1.5e-7 in absolute terms): a reciprocal, an exponential and seven FMAs instead of
+// the library erff, which dominated the hidden layer's epilogue.
+__device__ __forceinline__ float gelu_erf(float x) {
+  const float z = fabsf(x) * 0.70710678118654752f;
+  const float t = __frcp_rn(fmaf(0.3275911f, z, 1.0f));
+  const float poly = t * fmaf(t, fmaf(t, fmaf(t, fmaf(t, 1.061405429f, -1.453152027f), 1.421413741f), -0.284496736f), 0.254829592f);
+  const float erfc_z = poly * __expf(-z * z);                       // erfc(|x| / sqrt 2)
+  return 0.5f * x * (x < 0.f ? erfc_z : 2.0f - erfc_z);
+}
 
 // device status word: recomputed from the problem lengths by one workgroup per decode call
 __device__ __forceinline__ void write_device_status(const Geom& g, const tkphi_problem* probs, char* ws) {
