@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "tkphi_internal.h"
 
@@ -201,6 +202,71 @@ tkphi_status tkphi_build_summaries(const tkphi_config* cfg, const tkphi_problem*
   return hip_ok(hipGetLastError(), "tkphi_build_summaries launch");
 }
 
+// The kernels of one decode call in stream order.  With the MLP feature maps the three phi_q
+// launches (a chain of small cold-weight matrix-vector products, ~30 us if serialised) go to a
+// second stream of the library's own that forks from `s` at the start of the call and joins
+// before the gather, so that they run beside the score pass.  One such stream and event pair per
+// device, created on first use at the default priority and kept until the process ends; MLP decode
+// calls hold a mutex while they enqueue (the events are shared).
+struct SideStream {
+  hipStream_t stream = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
+};
+static std::mutex g_side_mutex;
+static SideStream g_side[64];
+
+static tkphi_status side_stream(SideStream** out) {
+  int dev = 0;
+  tkphi_status st = hip_ok(hipGetDevice(&dev), "hipGetDevice");
+  if (st != TKPHI_OK) return st;
+  if (dev < 0 || dev >= 64) { set_error("device ordinal %d out of range", dev); return TKPHI_EINVAL; }
+  SideStream& ss = g_side[dev];
+  if (!ss.stream) {
+    hipStream_t str = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    st = hip_ok(hipStreamCreateWithFlags(&str, hipStreamNonBlocking), "hipStreamCreateWithFlags");
+    if (st == TKPHI_OK) st = hip_ok(hipEventCreateWithFlags(&e0, hipEventDisableTiming), "hipEventCreateWithFlags");
+    if (st == TKPHI_OK) st = hip_ok(hipEventCreateWithFlags(&e1, hipEventDisableTiming), "hipEventCreateWithFlags");
+    if (st != TKPHI_OK) {
+      if (e0) (void)hipEventDestroy(e0);
+      if (e1) (void)hipEventDestroy(e1);
+      if (str) (void)hipStreamDestroy(str);
+      return st;
+    }
+    ss.stream = str; ss.fork = e0; ss.join = e1;
+  }
+  *out = &ss;
+  return TKPHI_OK;
+}
+
+static tkphi_status enqueue_decode(const Geom& g, const tkphi_problem* problems, char* ws, int acct, hipStream_t s) {
+  if (g.phi_kind != TKPHI_PHI_MLP) {
+    launch_score_mid(g, problems, ws, s);
+    launch_select(g, problems, ws, s);
+    launch_gather(g, problems, ws, s);
+    launch_merge(g, problems, ws, acct, s);
+    return TKPHI_OK;
+  }
+  std::lock_guard<std::mutex> lock(g_side_mutex);
+  SideStream* ss = nullptr;
+  tkphi_status st = side_stream(&ss);
+  if (st != TKPHI_OK) return st;
+  st = hip_ok(hipEventRecord(ss->fork, s), "hipEventRecord");
+  if (st == TKPHI_OK) st = hip_ok(hipStreamWaitEvent(ss->stream, ss->fork, 0), "hipStreamWaitEvent");
+  if (st != TKPHI_OK) return st;
+  launch_mlp_phi_q(g, problems, ws, ss->stream);
+  st = hip_ok(hipEventRecord(ss->join, ss->stream), "hipEventRecord");
+  launch_score_mid(g, problems, ws, s);
+  launch_select(g, problems, ws, s);
+  // (the join is enqueued even after an error above: the side stream must not be left forked)
+  const tkphi_status st2 = hip_ok(hipStreamWaitEvent(s, ss->join, 0), "hipStreamWaitEvent");
+  if (st != TKPHI_OK) return st;
+  if (st2 != TKPHI_OK) return st2;
+  launch_gather(g, problems, ws, s);
+  launch_merge(g, problems, ws, acct, s);
+  return TKPHI_OK;
+}
+
 tkphi_status tkphi_decode(const tkphi_config* cfg, const tkphi_problem* problems, int32_t n_problems,
                           int32_t max_L, int32_t max_K, int32_t mode, void* workspace,
                           size_t workspace_bytes, void* hip_stream) {
@@ -219,11 +285,8 @@ tkphi_status tkphi_decode(const tkphi_config* cfg, const tkphi_problem* problems
   hipStream_t s = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
   (void)hipGetLastError();
-  if (g.phi_kind == TKPHI_PHI_MLP) launch_mlp_phi_q(g, problems, ws, s);
-  launch_score_mid(g, problems, ws, s);
-  launch_select(g, problems, ws, s);
-  launch_gather(g, problems, ws, s);
-  launch_merge(g, problems, ws, acct, s);
+  st = enqueue_decode(g, problems, ws, acct, s);
+  if (st != TKPHI_OK) return st;
   return hip_ok(hipGetLastError(), "tkphi_decode launch");
 }
 
@@ -258,13 +321,9 @@ tkphi_status tkphi_decode_stage_times(const tkphi_config* cfg, const tkphi_probl
     for (int i = 0; i < ST_COUNT; ++i) { t.start[i] = ev[2 * i]; t.stop[i] = ev[2 * i + 1]; t.used[i] = false; }
     (void)hipGetLastError();
     g_kernel_timer = &t;
-    if (g.phi_kind == TKPHI_PHI_MLP) launch_mlp_phi_q(g, problems, ws, s);
-    launch_score_mid(g, problems, ws, s);
-    launch_select(g, problems, ws, s);
-    launch_gather(g, problems, ws, s);
-    launch_merge(g, problems, ws, acct, s);
+    st = enqueue_decode(g, problems, ws, acct, s);
     g_kernel_timer = nullptr;
-    st = hip_ok(hipGetLastError(), "tkphi_decode_stage_times launch");
+    if (st == TKPHI_OK) st = hip_ok(hipGetLastError(), "tkphi_decode_stage_times launch");
     if (st == TKPHI_OK) st = hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize");
     for (int i = 0; st == TKPHI_OK && i < ST_COUNT; ++i)
       if (t.used[i]) st = hip_ok(hipEventElapsedTime(&stage_ms_out[i], t.start[i], t.stop[i]), "hipEventElapsedTime");

@@ -249,53 +249,64 @@ __device__ __forceinline__ void phi_q_head(const Geom& g, const tkphi_problem& p
 }
 
 // out[j] = W[j] . in for a bf16 matrix W [N][Kd] (row-major, 16-byte aligned rows) and an fp32
-// vector `in` in LDS; epi(j, dot) consumes row j.  min(Kd / 8, 64) lanes share a row with one or
-// two 16-byte loads each; eight loads per lane are in flight.  Kd / 8 is a power of two <= 128.
-template <int SPL, typename F>   // SPL: 16-byte segments per lane, 1 or 2
-__device__ __forceinline__ void gemv_bf16_rows_impl(const void* W, int N, int Kd, const float* in, F&& epi) {
+// vector `in` in LDS; epi(j, dot) consumes row j.  Kd / 8 / SPL lanes share a row with SPL (1 or 2)
+// 16-byte loads each; eight loads per lane are in flight and cover rows [j0, j0 + rows_pp 8 / SPL).
+// gemv_load issues the loads of one such row group, gemv_consume reduces them: a caller can issue
+// the first group early (before `in` is ready) and hand it to gemv_bf16_rows as `pre`.
+template <int SPL>
+__device__ __forceinline__ void gemv_load(const void* W, int N, int Kd, int j0, u32x4 (&t)[8]) {
   const int tid = threadIdx.x, nthr = blockDim.x;
   const int LPR = Kd / 8 / SPL;
   const int rows_pp = nthr / LPR, row_in = tid / LPR, sl = tid % LPR;
-  constexpr int PASS = 8 / SPL;                                      // row passes in flight
-  for (int j0 = 0; j0 < N; j0 += rows_pp * PASS) {
-    u32x4 t[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const int pass = k / SPL, sg = sl + (k % SPL) * LPR;
-      if (j0 + pass * rows_pp >= N) break;                           // (uniform) no rows left for this pass
-      const int j = min(j0 + pass * rows_pp + row_in, N - 1);        // clamped: every lane loads
-      t[k] = gload128((const char*)W + ((size_t)j * Kd + sg * 8) * 2);
-    }
-    float dot = 0.f;
+  for (int k = 0; k < 8; ++k) {
+    const int pass = k / SPL, sg = sl + (k % SPL) * LPR;
+    if (j0 + pass * rows_pp >= N) break;                             // (uniform) no rows left for this pass
+    const int j = min(j0 + pass * rows_pp + row_in, N - 1);          // clamped: every lane loads
+    t[k] = gload128((const char*)W + ((size_t)j * Kd + sg * 8) * 2);
+  }
+}
+
+template <int SPL, typename F>
+__device__ __forceinline__ void gemv_consume(int N, int Kd, int j0, const u32x4 (&t)[8], const float* in, F&& epi) {
+  const int tid = threadIdx.x, nthr = blockDim.x;
+  const int LPR = Kd / 8 / SPL;
+  const int rows_pp = nthr / LPR, row_in = tid / LPR, sl = tid % LPR;
+  float dot = 0.f;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const int pass = k / SPL, sg = sl + (k % SPL) * LPR;
-      if (j0 + pass * rows_pp >= N) break;
-      float x[8];
-      Elem<uint16_t>::unpack(make_uint4(t[k].x, t[k].y, t[k].z, t[k].w), x);
+  for (int k = 0; k < 8; ++k) {
+    const int pass = k / SPL, sg = sl + (k % SPL) * LPR;
+    if (j0 + pass * rows_pp >= N) break;
+    float x[8];
+    Elem<uint16_t>::unpack(make_uint4(t[k].x, t[k].y, t[k].z, t[k].w), x);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) dot = fmaf(x[e], in[sg * 8 + e], dot);
-      if (k % SPL == SPL - 1) {                                      // the row's last segment of this lane
-        for (int o = LPR >> 1; o >= 1; o >>= 1) dot += __shfl_xor(dot, o);
-        const int jr = j0 + pass * rows_pp + row_in;
-        if (sl == 0 && jr < N) epi(jr, dot);
-        dot = 0.f;
-      }
+    for (int e = 0; e < 8; ++e) dot = fmaf(x[e], in[sg * 8 + e], dot);
+    if (k % SPL == SPL - 1) {                                        // the row's last segment of this lane
+      for (int o = LPR >> 1; o >= 1; o >>= 1) dot += __shfl_xor(dot, o);
+      const int jr = j0 + pass * rows_pp + row_in;
+      if (sl == 0 && jr < N) epi(jr, dot);
+      dot = 0.f;
     }
   }
 }
 
-template <typename F>
-__device__ __forceinline__ void gemv_bf16_rows(const void* W, int N, int Kd, const float* in, F&& epi) {
-  if (Kd / 8 <= 64) gemv_bf16_rows_impl<1>(W, N, Kd, in, epi);
-  else gemv_bf16_rows_impl<2>(W, N, Kd, in, epi);
+// `pre`: the row group j0 = 0, already loaded with gemv_load<SPL>(W, N, Kd, 0, pre)
+template <int SPL, typename F>
+__device__ __forceinline__ void gemv_bf16_rows(const void* W, int N, int Kd, const float* in, const u32x4 (&pre)[8], F&& epi) {
+  const int rows_pi = (int)blockDim.x / (Kd / 8 / SPL) * (8 / SPL);
+  gemv_consume<SPL>(N, Kd, 0, pre, in, epi);
+  for (int j0 = rows_pi; j0 < N; j0 += rows_pi) {
+    u32x4 t[8];
+    gemv_load<SPL>(W, N, Kd, j0, t);
+    gemv_consume<SPL>(N, Kd, j0, t, in, epi);
+  }
 }
 
 // GeLU(x) = x Phi(x) with Phi(x) = erfc(-x / sqrt 2) / 2.  erfc(z) for z >= 0 by the classical
 // five-term rational approximation erfc(z) ~ t (a1 + t (a2 + ... + t a5)) exp(-z^2), t = 1 / (1 + p z)
-// (Abramowitz & Stegun 7.1.26, absolute error <= 1.5e-7 on erfc, i.e. <= 1.5e-7 |x| / 2 ... on GeLU it
-// stays below 1.5e-7 in absolute terms): a reciprocal, an exponential and seven FMAs instead of
-// the library erff, which dominated the hidden layer's epilogue.
+// (Abramowitz & Stegun 7.1.26: absolute error <= 1.5e-7 on erfc, hence <= 0.75e-7 |x| on GeLU, and
+// no cancellation for x < 0): a reciprocal, an exponential and seven FMAs instead of the library
+// erff, which dominated the hidden layer's epilogue.
 __device__ __forceinline__ float gelu_erf(float x) {
   const float z = fabsf(x) * 0.70710678118654752f;
   const float t = __frcp_rn(fmaf(0.3275911f, z, 1.0f));

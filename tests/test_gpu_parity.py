@@ -206,15 +206,21 @@ def test_bad_length_is_skipped_and_flagged():
     print("bad length", rep)
 
 
-def test_decode_replays_from_a_hip_graph():
-    """Both entry points only enqueue kernels on the caller's stream: a captured decode step,
-    replayed several times with eager work and synchronisations in between, reproduces the eager
-    result bit for bit (and follows a changed query, since the table holds device pointers)."""
+@pytest.mark.parametrize("d_emb", [0, 128])
+def test_decode_replays_from_a_hip_graph(d_emb):
+    """Both entry points only enqueue kernels on the caller's stream (with the MLP feature maps,
+    d_emb > 0, also on the library's second stream, forked from and joined to the caller's): a
+    captured decode step, replayed several times with eager work and synchronisations in between,
+    reproduces the eager result bit for bit (and follows a changed query, since the table holds
+    device pointers)."""
     import torch
+    from paper_2604_05438_amd import harness as H
     w = I.WORKLOADS["l3b_128k"]
     L, k = 6000, 59
     P = I.make_layer(w, L=L)
-    b = _batch(w, [P], [k])
+    if d_emb:
+        P["mlp"] = I.make_mlp_phi(w, d_emb=d_emb)
+    b = H.Batch(H.config_of(w, d_emb=d_emb), [P], [k], debug=True)
     b.build(); b.decode()
     torch.cuda.synchronize()
     y_eager = b.result(0, "out").copy()
