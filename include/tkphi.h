@@ -84,7 +84,14 @@ typedef enum tkphi_mode { TKPHI_MODE_SUB = 0, TKPHI_MODE_NOSUB = 1, TKPHI_MODE_T
  *                 phi(x) = exp(Wo g1 + bo)
  *               with internal width cfg.d_emb (the paper: 512), one tkphi_mlp per query head
  *               (tkphi_problem::mlp_q) and per KV head (mlp_k).  Requires bf16 storage and
- *               cfg.cache_features = 1: the key features are evaluated once, at build time. */
+ *               cfg.cache_features = 1: the key features are evaluated once, at build time
+ *               (a chain of matrix-core GEMMs whose fp32 activations enter as bf16 hi + lo
+ *               pairs; GeLU uses erfc to 1.5e-7 absolute).  tkphi_decode evaluates phi_q with
+ *               three small launches on a second stream that the library creates per device
+ *               on first use (default priority, kept until the process ends): forked from the
+ *               caller's stream at the start of the call and joined to it before the gather, so
+ *               the caller still sees one in-order unit of work; such calls serialise on a
+ *               mutex while they enqueue. */
 typedef enum tkphi_phi_kind { TKPHI_PHI_EXP_AFFINE = 0, TKPHI_PHI_MLP = 1 } tkphi_phi_kind;
 
 /* One head's MLP feature map.  DEVICE struct (arrays of it live in device memory); weights are
@@ -126,7 +133,7 @@ typedef struct tkphi_config {
                              variant named in Sec. "Retrieved-token subtraction": d_phi * 4 bytes per
                              token and KV head of extra cache)                              */
   int32_t phi_kind;      /* tkphi_phi_kind; 0 = EXP_AFFINE                                  */
-  int32_t d_emb;         /* MLP only: internal width, a multiple of 64 in [64, 1024]        */
+  int32_t d_emb;         /* MLP only: internal width, a power of two in [64, 1024]          */
 } tkphi_config;
 
 /* Optional per-query-head diagnostics / unnormalised outputs written by tkphi_decode,

@@ -50,6 +50,28 @@ def test_workspace_query_and_config_validation():
     assert B.tkphi_workspace_bytes(_cfg(), 1, 0, 0) == 0
 
 
+def test_mlp_feature_map_config_validation():
+    mlp = dict(phi_kind=B.TKPHI_PHI_MLP, cache_features=1, d_emb=512)
+    base = B.tkphi_workspace_bytes(_cfg(cache_features=1), 1, 32768, 327)
+    with_mlp = B.tkphi_workspace_bytes(_cfg(**mlp), 1, 32768, 327)
+    assert with_mlp > base > 0                     # activation block + packed weights of the MLP build
+    for bad in (dict(mlp, d_emb=96), dict(mlp, d_emb=32), dict(mlp, d_emb=2048), dict(mlp, cache_features=0),
+                dict(mlp, dtype="f32"), dict(phi_kind=7)):
+        assert B.tkphi_workspace_bytes(_cfg(**bad), 1, 4096, 40) == 0
+        assert B.tkphi_last_error() != ""
+    # the problem table must carry the MLP tables instead of Wq / Wk
+    cfg = _cfg(**mlp)
+    p = B.tkphi_problem(K=4096, V=8192, stride_head=1000 * 64, stride_tok=64, Wq=0, bq=0, Wk=0, bk=0, S=4096, u=4096,
+                        q=4096, out=4096, topk_idx=0, aux=0, scores=0, phi_cache=4096, mlp_q=4096, mlp_k=4096,
+                        L=1000, topk=9)
+    B.tkphi_check_problems(cfg, (B.tkphi_problem * 1)(p), 1, 1000, 9, True)
+    for field in ("mlp_q", "mlp_k", "phi_cache"):
+        q = B.tkphi_problem.from_buffer_copy(p)
+        setattr(q, field, 0)
+        with pytest.raises(B.TkphiError):
+            B.tkphi_check_problems(cfg, (B.tkphi_problem * 1)(q), 1, 1000, 9, True)
+
+
 def test_status_strings():
     seen = {B.tkphi_status_string(s) for s in range(-6, 1)}
     assert len(seen) == 7 and B.tkphi_status_string(-99) == "unknown status"
