@@ -24,7 +24,7 @@ union Frag {
   bf16x8 v;
 };
 
-enum { EPI_STEM = 0, EPI_HID = 1, EPI_RES = 2, EPI_OUT = 3 };
+enum { EPI_STEM = 0, EPI_HID = 1, EPI_RES = 2, EPI_OUT = 3, EPI_RESOUT = 4 };
 
 // ------------------------------------------------------------------------------------
 // Weights in MFMA-fragment order.  A matrix W [N][Kd] (row-major bf16) is cut into blocks of 16
@@ -73,14 +73,20 @@ __global__ __launch_bounds__(kThreads) void mlp_pack_weights_kernel(Geom g, cons
 // global memory (L2) into the other operand.  Two LDS buffers, one barrier per stage; the next
 // stage's global loads are issued before the MFMAs of the current one.
 // ------------------------------------------------------------------------------------
-template <int EPI, int NT>
+// EPI_RESOUT (d_emb == 64 NT, d_phi == 64 NTO): residual and output layer in one launch.  The
+// workgroup holds complete rows of g1 = g0 + alpha Delta in its accumulators; wavefront c's 16 NT
+// features at a time go through LDS (bf16 hi / lo planes, token-major) and every wavefront multiplies
+// them with its NTO output tiles of Wo.  g1 is never written to memory.
+template <int EPI, int NT, int NTO = 0>
 __global__ __launch_bounds__(kThreads, 2) void mlp_gemm_kernel(Geom g, const tkphi_problem* __restrict__ probs,
                                                                char* __restrict__ ws, int p, int t0) {
   constexpr int BM = 64, BN = 64 * NT, KB = 32;
   constexpr int AROW = KB * 2 + 16;
   constexpr bool A_BF16 = EPI == EPI_STEM;
-  __shared__ __attribute__((aligned(16))) char a_hi[2][BM * AROW];
-  __shared__ __attribute__((aligned(16))) char a_lo[2][A_BF16 ? 16 : BM * AROW];
+  constexpr int KC = 16 * NT, RS = KC * 2 + 16;        // EPI_RESOUT: features per chunk, bytes per token row of a plane
+  constexpr int LDS_STAGE = 4 * BM * AROW, LDS_G1 = EPI == EPI_RESOUT ? 2 * BM * RS : 0;
+  __shared__ __attribute__((aligned(16))) char lds_raw[LDS_STAGE > LDS_G1 ? LDS_STAGE : LDS_G1];
+  // staging planes: hi of buffer b at b BM AROW, lo at (2 + b) BM AROW
 
   const int h = blockIdx.x % g.Hkv, tid = threadIdx.x;
   const int lane = tid & 63, wv = tid >> 6, r = lane & 15, kg = lane >> 4;
@@ -94,13 +100,14 @@ __global__ __launch_bounds__(kThreads, 2) void mlp_gemm_kernel(Geom g, const tkp
   const int E = g.d_emb;
   const int Kd = EPI == EPI_STEM ? g.d : E;
   const int Nout = EPI == EPI_OUT ? g.dphi : E;
+  constexpr int EPI_W = EPI == EPI_RESOUT ? EPI_RES : EPI;     // which layer's weights the main loop multiplies
   const int n0 = blockIdx.y * BN;
   if (n0 >= Nout) return;
   // fragment-packed weights of this head: Ws | W1 | W2 | Wo
-  const size_t w_off = EPI == EPI_STEM ? 0 : EPI == EPI_HID ? (size_t)E * g.d : EPI == EPI_RES ? (size_t)E * g.d + (size_t)E * E
-                                                                                               : (size_t)E * g.d + (size_t)2 * E * E;
+  const size_t w_off = EPI_W == EPI_STEM ? 0 : EPI_W == EPI_HID ? (size_t)E * g.d : EPI_W == EPI_RES ? (size_t)E * g.d + (size_t)E * E
+                                                                                                   : (size_t)E * g.d + (size_t)2 * E * E;
   const char* W = ws + g.off_wpack + (size_t)h * packed_bytes_per_head(g) + w_off * 2;
-  const float* bias = EPI == EPI_STEM ? mp.bs : EPI == EPI_HID ? mp.b1 : EPI == EPI_RES ? mp.b2 : mp.bo;
+  const float* bias = EPI_W == EPI_STEM ? mp.bs : EPI_W == EPI_HID ? mp.b1 : EPI_W == EPI_RES ? mp.b2 : mp.bo;
   float* Gb = (float*)(ws + g.off_act) + (size_t)h * g.mlp_block * E;
   float* Hb = Gb + (size_t)g.Hkv * g.mlp_block * E;
 
@@ -109,7 +116,7 @@ __global__ __launch_bounds__(kThreads, 2) void mlp_gemm_kernel(Geom g, const tkp
   const int arow = row0 + min(srow, rows_valid - 1);   // clamped: rows past the end repeat the last one
   const char* a_src;
   if (A_BF16) a_src = (const char*)pr.K + ((size_t)h * pr.stride_head + (size_t)(g.n_sink + t0 + arow) * pr.stride_tok + sseg * 8) * 2;
-  else a_src = (const char*)((EPI == EPI_RES ? Hb : Gb) + (size_t)arow * E + sseg * 8);
+  else a_src = (const char*)((EPI_W == EPI_RES ? Hb : Gb) + (size_t)arow * E + sseg * 8);
   // weight operands: the NT output tiles of this wavefront (clamped to the last tile: every lane loads)
   const int colw = n0 + wv * NT * 16;
   const char* w_src[NT];
@@ -141,15 +148,15 @@ __global__ __launch_bounds__(kThreads, 2) void mlp_gemm_kernel(Geom g, const tkp
     const int buf = st & 1;
     // ---- stage the A tile (split into hi / lo planes) ------------------------------------------
     if (A_BF16) {
-      *(u32x4*)(a_hi[buf] + srow * AROW + sseg * 16) = ar[0];
+      *(u32x4*)(lds_raw + buf * (BM * AROW) + srow * AROW + sseg * 16) = ar[0];
     } else {
       uint32_t hh[4], ll[4];
       split_bf16_pair(__uint_as_float(ar[0].x), __uint_as_float(ar[0].y), &hh[0], &ll[0]);
       split_bf16_pair(__uint_as_float(ar[0].z), __uint_as_float(ar[0].w), &hh[1], &ll[1]);
       split_bf16_pair(__uint_as_float(ar[1].x), __uint_as_float(ar[1].y), &hh[2], &ll[2]);
       split_bf16_pair(__uint_as_float(ar[1].z), __uint_as_float(ar[1].w), &hh[3], &ll[3]);
-      *(u32x4*)(a_hi[buf] + srow * AROW + sseg * 16) = (u32x4){hh[0], hh[1], hh[2], hh[3]};
-      *(u32x4*)(a_lo[buf] + srow * AROW + sseg * 16) = (u32x4){ll[0], ll[1], ll[2], ll[3]};
+      *(u32x4*)(lds_raw + buf * (BM * AROW) + srow * AROW + sseg * 16) = (u32x4){hh[0], hh[1], hh[2], hh[3]};
+      *(u32x4*)(lds_raw + (2 + buf) * (BM * AROW) + srow * AROW + sseg * 16) = (u32x4){ll[0], ll[1], ll[2], ll[3]};
     }
     Frag bcur[NT];
 #pragma unroll
@@ -160,8 +167,8 @@ __global__ __launch_bounds__(kThreads, 2) void mlp_gemm_kernel(Geom g, const tkp
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
       Frag ahi, alo;
-      ahi.u = *(const u32x4*)(a_hi[buf] + (mt * 16 + r) * AROW + kg * 16);
-      if (!A_BF16) alo.u = *(const u32x4*)(a_lo[buf] + (mt * 16 + r) * AROW + kg * 16);
+      ahi.u = *(const u32x4*)(lds_raw + buf * (BM * AROW) + (mt * 16 + r) * AROW + kg * 16);
+      if (!A_BF16) alo.u = *(const u32x4*)(lds_raw + (2 + buf) * (BM * AROW) + (mt * 16 + r) * AROW + kg * 16);
       // weights as the row operand, tokens as the column operand: a lane ends up with 4 consecutive
       // outputs of one token (16-byte epilogue accesses).  All lo products of a row tile, then all hi
       // products: consecutive MFMAs never wait for each other's accumulator.
@@ -177,6 +184,96 @@ __global__ __launch_bounds__(kThreads, 2) void mlp_gemm_kernel(Geom g, const tkp
   // ---- epilogue: acc[mt][nt][i] <-> token row mt*16 + r, output colw + nt*16 + 4kg + i --------------
   float* cache_h = pr.phi_cache + ((size_t)h * n + t0 + row0) * g.dphi;
   auto g_ptr = [&](int mt, int nt) { return Gb + (size_t)(row0 + min(mt * 16 + r, rows_valid - 1)) * E + colw + nt * 16 + 4 * kg; };
+  if constexpr (EPI == EPI_RESOUT) {
+    // g1 in place of the accumulators (the old residual stream is loaded a few tiles at a time)
+    constexpr int HB = NT >= 8 ? 2 : NT > 1 ? NT / 2 : 1;
+#pragma unroll
+    for (int nb = 0; nb < NT; nb += HB) {
+      float4 gv[HB][4];
+#pragma unroll
+      for (int j = 0; j < HB; ++j)
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) gv[j][mt] = *(const float4*)g_ptr(mt, nb + j);
+#pragma unroll
+      for (int j = 0; j < HB; ++j) {
+        const float4 b = *(const float4*)(bias + colw + (nb + j) * 16 + 4 * kg);
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+          acc[mt][nb + j][0] = fmaf(mp.alpha, acc[mt][nb + j][0] + b.x, gv[j][mt].x);
+          acc[mt][nb + j][1] = fmaf(mp.alpha, acc[mt][nb + j][1] + b.y, gv[j][mt].y);
+          acc[mt][nb + j][2] = fmaf(mp.alpha, acc[mt][nb + j][2] + b.z, gv[j][mt].z);
+          acc[mt][nb + j][3] = fmaf(mp.alpha, acc[mt][nb + j][3] + b.w, gv[j][mt].w);
+        }
+      }
+    }
+    char* const p_hi = lds_raw;
+    char* const p_lo = lds_raw + BM * RS;
+    const char* Wo = ws + g.off_wpack + (size_t)h * packed_bytes_per_head(g) + ((size_t)E * g.d + (size_t)2 * E * E) * 2;
+    const int n_otiles = g.dphi / 16;
+    floatx4 acco[4][NTO];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+      for (int j = 0; j < NTO; ++j) acco[mt][j] = (floatx4){0.f, 0.f, 0.f, 0.f};
+    __syncthreads();                                   // the staging buffers are free
+#pragma unroll 1
+    for (int c = 0; c < 4; ++c) {
+      if (wv == c) {                                   // this wavefront's features -> planes [token][16 NT features]
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int mt = 0; mt < 4; ++mt) {
+            uint32_t h01, l01, h23, l23;
+            split_bf16_pair(acc[mt][nt][0], acc[mt][nt][1], &h01, &l01);
+            split_bf16_pair(acc[mt][nt][2], acc[mt][nt][3], &h23, &l23);
+            *(u32x2*)(p_hi + (mt * 16 + r) * RS + (nt * 16 + 4 * kg) * 2) = (u32x2){h01, h23};
+            *(u32x2*)(p_lo + (mt * 16 + r) * RS + (nt * 16 + 4 * kg) * 2) = (u32x2){l01, l23};
+          }
+      }
+      // (the output weights of this chunk are requested before the barrier: they do not depend on the planes)
+      Frag wnext[NTO];
+#pragma unroll
+      for (int j = 0; j < NTO; ++j)
+        wnext[j].u = gload128(Wo + ((size_t)(min(wv * NTO + j, n_otiles - 1) * (E / 32) + c * (KC / 32)) * 64 + lane) * 16);
+      __syncthreads();
+#pragma unroll 1
+      for (int ksl = 0; ksl < KC / 32; ++ksl) {
+        Frag wf[NTO];
+#pragma unroll
+        for (int j = 0; j < NTO; ++j) wf[j] = wnext[j];
+        if (ksl + 1 < KC / 32) {
+#pragma unroll
+          for (int j = 0; j < NTO; ++j)
+            wnext[j].u = gload128(Wo + ((size_t)(min(wv * NTO + j, n_otiles - 1) * (E / 32) + c * (KC / 32) + ksl + 1) * 64 + lane) * 16);
+        }
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+          Frag bhi, blo;
+          bhi.u = *(const u32x4*)(p_hi + (mt * 16 + r) * RS + (ksl * 32 + kg * 8) * 2);
+          blo.u = *(const u32x4*)(p_lo + (mt * 16 + r) * RS + (ksl * 32 + kg * 8) * 2);
+#pragma unroll
+          for (int j = 0; j < NTO; ++j) acco[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[j].v, blo.v, acco[mt][j], 0, 0, 0);
+#pragma unroll
+          for (int j = 0; j < NTO; ++j) acco[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[j].v, bhi.v, acco[mt][j], 0, 0, 0);
+        }
+      }
+      __syncthreads();                                 // planes are rewritten by the next chunk
+    }
+#pragma unroll
+    for (int j = 0; j < NTO; ++j) {
+      if (wv * NTO + j >= n_otiles) continue;
+      const int col = (wv * NTO + j) * 16 + 4 * kg;
+      const float4 b = *(const float4*)(mp.bo + col);
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) {
+        const int row = mt * 16 + r;
+        if (row >= rows_valid) continue;
+        *(float4*)(cache_h + (size_t)row * g.dphi + col) =
+            make_float4(expf(acco[mt][j][0] + b.x), expf(acco[mt][j][1] + b.y), expf(acco[mt][j][2] + b.z), expf(acco[mt][j][3] + b.w));
+      }
+    }
+    return;
+  }
   float4 gcur[4], gnext[4];
   if (EPI == EPI_RES && colw < Nout) {
 #pragma unroll
@@ -223,10 +320,25 @@ static void launch_mlp_gemm(const Geom& g, const tkphi_problem* probs, char* ws,
   else hipLaunchKernelGGL((mlp_gemm_kernel<EPI, 1>), grid, dim3(kThreads), 0, s, g, probs, ws, p, t0);
 }
 
+// residual + output layer in one launch: d_emb == 64 NT (one workgroup spans all of g1; a wavefront's
+// 16 NT features are at least one MFMA K step of 32) and d_phi == 64 NTO
+static bool resout_fusable(const Geom& g) {
+  return (g.d_emb == 128 || g.d_emb == 256 || g.d_emb == 512) && (g.dphi == 64 || g.dphi == 128 || g.dphi == 256);
+}
+
+template <int NT>
+static void launch_mlp_resout_nt(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s, int rows, int p, int t0) {
+  dim3 grid(g.Hkv * ((rows + 63) / 64));
+  if (g.dphi == 64) hipLaunchKernelGGL((mlp_gemm_kernel<EPI_RESOUT, NT, 1>), grid, dim3(kThreads), 0, s, g, probs, ws, p, t0);
+  else if (g.dphi == 128) hipLaunchKernelGGL((mlp_gemm_kernel<EPI_RESOUT, NT, 2>), grid, dim3(kThreads), 0, s, g, probs, ws, p, t0);
+  else hipLaunchKernelGGL((mlp_gemm_kernel<EPI_RESOUT, NT, 4>), grid, dim3(kThreads), 0, s, g, probs, ws, p, t0);
+}
+
 // the key features of every problem's mid-region -> phi_cache, block by block
 void launch_mlp_features(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
   if (g.max_mid == 0) return;
   const size_t pieces = ((size_t)g.d_emb * g.d + (size_t)2 * g.d_emb * g.d_emb + (size_t)g.dphi * g.d_emb) / 8;
+  const bool fused = resout_fusable(g) && !getenv("TKPHI_MLP_UNFUSED");
   for (int p = 0; p < g.n_problems; ++p) {
     hipLaunchKernelGGL(mlp_pack_weights_kernel, dim3((unsigned)((pieces + kThreads - 1) / kThreads), g.Hkv), dim3(kThreads), 0, s,
                        g, probs, ws, p);
@@ -234,8 +346,14 @@ void launch_mlp_features(const Geom& g, const tkphi_problem* probs, char* ws, hi
       const int rows = std::min(g.mlp_block, g.max_mid - t0);
       launch_mlp_gemm<EPI_STEM>(g, probs, ws, s, rows, g.d_emb, p, t0);
       launch_mlp_gemm<EPI_HID>(g, probs, ws, s, rows, g.d_emb, p, t0);
-      launch_mlp_gemm<EPI_RES>(g, probs, ws, s, rows, g.d_emb, p, t0);
-      launch_mlp_gemm<EPI_OUT>(g, probs, ws, s, rows, g.dphi, p, t0);
+      if (fused) {
+        if (g.d_emb == 512) launch_mlp_resout_nt<8>(g, probs, ws, s, rows, p, t0);
+        else if (g.d_emb == 256) launch_mlp_resout_nt<4>(g, probs, ws, s, rows, p, t0);
+        else launch_mlp_resout_nt<2>(g, probs, ws, s, rows, p, t0);
+      } else {
+        launch_mlp_gemm<EPI_RES>(g, probs, ws, s, rows, g.d_emb, p, t0);
+        launch_mlp_gemm<EPI_OUT>(g, probs, ws, s, rows, g.dphi, p, t0);
+      }
     }
   }
 }
