@@ -3,10 +3,11 @@
 // evaluated for the keys of the mid-region at build time, and the summary contraction
 // S = Phi^T V, u = sum Phi (eq. (natural_cache)) from the stored features.
 //
-// Keys: four launches of one tiled matrix-core GEMM per block of Geom::mlp_block tokens
+// Keys: launches of one tiled matrix-core GEMM per block of Geom::mlp_block tokens
 //   stem  G = X Ws^T + bs            (X = bf16 key rows: exact, single MFMA pass)
 //   hid   H = GeLU(G W1^T + b1)
 //   res   G = G + alpha (H W2^T + b2)    (in place: a tile reads only its own G entries)
+//         [res and out run as one launch when the widths allow: g1 then stays on chip]
 //   out   Phi = exp(G Wo^T + bo)     -> tkphi_problem::phi_cache
 // Activations are fp32 in the workspace; as MFMA operands they are split into a bf16 hi + lo
 // pair (16 significant bits, two MFMAs per product), weights are bf16 as stored, accumulation
