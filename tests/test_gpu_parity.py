@@ -373,3 +373,12 @@ def test_mlp_feature_maps(shape, d_emb, L, k):
         worst = max(worst, float((np.abs(C[h] - F) / F).max()))
     print(f"mlp {shape}: stored features, worst relative error {worst:.3e}", flush=True)
     assert worst <= PU.MLP_FEATURE_EPS
+    # the other accounting modes and the diagnostics run on the same summaries
+    from paper_2604_05438_amd import binding as B
+    y_sub = b.result(0, "out").copy()
+    b.decode(B.TKPHI_MODE_SUB | B.TKPHI_FLAG_DIAG)
+    assert b.status() == 0
+    assert np.array_equal(b.result(0, "out"), y_sub)
+    _check_diag(w, layers[0], ks[0], b, 0, heads=[0, w.n_q_heads - 1])
+    b.decode(B.TKPHI_MODE_NOSUB)
+    PU.check_layer(w, layers[0], ks[0], b, 0, heads=[w.n_q_heads - 1], mode="nosub")
