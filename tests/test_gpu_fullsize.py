@@ -80,3 +80,35 @@ def test_million_token_context():
     assert b.status() == 0
     rep = PU.check_layer(w, P, k, b, 0)
     print("1M tokens", rep)
+
+
+def test_l3b_128k_mlp_feature_maps():
+    """The 128K / 1 % layer with the one-block ReZero MLP maps of width 512, as `bench.py
+    --mlp-d-emb 512` runs it (32 token blocks of 4096 through the GEMM chain): summaries against
+    the oracle's build, stored features on a sample of tokens of every KV head, outputs and index
+    sets of a sample of query heads."""
+    import parity_utils as PU
+    from oracle import tkphi_oracle as orc
+    from paper_2604_05438_amd import harness as H
+    w = I.WORKLOADS["l3b_128k"]
+    k = I.mid_budget(w.L, w.budget_bp, w.n_sink, w.n_tail)
+    assert k == 1310
+    P = I.make_layer(w)
+    P["mlp"] = I.make_mlp_phi(w, d_emb=512)
+    b = H.Batch(H.config_of(w, d_emb=512), [P], [k], debug=True)
+    b.build(); b.decode()
+    assert b.status() == 0
+    rep = PU.check_layer(w, P, k, b, 0, heads=[0, 10, 23])
+    print("l3b_128k mlp", rep, flush=True)
+    O = PU.oracle_inputs(P)
+    _, fk = PU.mlp_feature_fns(P)
+    n_mid = w.L - w.n_sink - w.n_tail
+    rng = np.random.default_rng(11)
+    sample = np.unique(np.concatenate([rng.integers(0, n_mid, size=1500), [0, 4095, 4096, n_mid - 1]]))
+    C = b.result(0, "phi_cache")
+    worst = 0.0
+    for h in range(w.n_kv_heads):
+        F = fk[h](O["K"][h, w.n_sink + sample])
+        worst = max(worst, float((np.abs(C[h, sample].astype(np.float64) - F) / F).max()))
+    print(f"l3b_128k mlp: stored features (sample), worst relative error {worst:.3e}", flush=True)
+    assert worst <= PU.MLP_FEATURE_EPS
