@@ -13,6 +13,10 @@
 // pair (16 significant bits, two MFMAs per product), weights are bf16 as stored, accumulation
 // is fp32.  With ~1.3 MFLOP per token and KV head against ~14 KB of activation traffic the
 // chain is bound by the matrix cores, not by HBM.
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+
 #include "tkphi_internal.h"
 
 namespace tkphi {
@@ -78,46 +82,44 @@ __global__ __launch_bounds__(kThreads) void mlp_pack_weights_kernel(Geom g, cons
 // workgroup holds complete rows of g1 = g0 + alpha Delta in its accumulators; wavefront c's 16 NT
 // features at a time go through LDS (bf16 hi / lo planes, token-major) and every wavefront multiplies
 // them with its NTO output tiles of Wo.  g1 is never written to memory.
-template <int EPI, int NT, int NTO = 0>
-__global__ __launch_bounds__(kThreads, 2) void mlp_gemm_kernel(Geom g, const tkphi_problem* __restrict__ probs,
-                                                               char* __restrict__ ws, int p, int t0) {
-  constexpr int BM = 64, BN = 64 * NT, KB = 32;
+template <int NT>
+constexpr int mlp_lds_bytes() {
+  constexpr int stage = 4 * 64 * (32 * 2 + 16), planes = 2 * 64 * (16 * NT * 2 + 16);
+  return stage > planes ? stage : planes;
+}
+
+// One 64-token tile of one layer.  tok0: first mid-region token of the tile; Gt, Ht: the tile's fp32
+// activations g and h, [64][d_emb]; lds_raw: mlp_lds_bytes<NT>() bytes, free on entry (the caller
+// puts a barrier between two calls); n0: first output of the workgroup (0 unless the layer is wider
+// than 64 NT).
+template <int EPI, int NT, int NTO>
+__device__ __forceinline__ void mlp_gemm_tile(const Geom& g, const tkphi_problem& pr, const tkphi_mlp& mp, char* __restrict__ ws,
+                                              char* lds_raw, int h, int n, int tok0, int rows_valid, float* Gt, float* Ht, int n0) {
+  constexpr int BM = 64, KB = 32;
   constexpr int AROW = KB * 2 + 16;
   constexpr bool A_BF16 = EPI == EPI_STEM;
   constexpr int KC = 16 * NT, RS = KC * 2 + 16;        // EPI_RESOUT: features per chunk, bytes per token row of a plane
-  constexpr int LDS_STAGE = 4 * BM * AROW, LDS_G1 = EPI == EPI_RESOUT ? 2 * BM * RS : 0;
-  __shared__ __attribute__((aligned(16))) char lds_raw[LDS_STAGE > LDS_G1 ? LDS_STAGE : LDS_G1];
   // staging planes: hi of buffer b at b BM AROW, lo at (2 + b) BM AROW
-
-  const int h = blockIdx.x % g.Hkv, tid = threadIdx.x;
-  const int lane = tid & 63, wv = tid >> 6, r = lane & 15, kg = lane >> 4;
-  const tkphi_problem pr = probs[p];
-  if (pr.L < 1 || pr.L > g.max_L) return;
-  const int n = mid_size(pr.L, g.n_sink, g.n_tail);
-  const int row0 = (blockIdx.x / g.Hkv) * BM;          // first row of the tile inside the token block
-  if (t0 + row0 >= n) return;
-  const int rows_valid = min(BM, n - (t0 + row0));
-  const tkphi_mlp mp = pr.mlp_k[h];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, r = lane & 15, kg = lane >> 4;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);     // wavefront index as a scalar: per-wavefront addresses stay in SGPRs
   const int E = g.d_emb;
   const int Kd = EPI == EPI_STEM ? g.d : E;
   const int Nout = EPI == EPI_OUT ? g.dphi : E;
   constexpr int EPI_W = EPI == EPI_RESOUT ? EPI_RES : EPI;     // which layer's weights the main loop multiplies
-  const int n0 = blockIdx.y * BN;
   if (n0 >= Nout) return;
   // fragment-packed weights of this head: Ws | W1 | W2 | Wo
   const size_t w_off = EPI_W == EPI_STEM ? 0 : EPI_W == EPI_HID ? (size_t)E * g.d : EPI_W == EPI_RES ? (size_t)E * g.d + (size_t)E * E
                                                                                                    : (size_t)E * g.d + (size_t)2 * E * E;
   const char* W = ws + g.off_wpack + (size_t)h * packed_bytes_per_head(g) + w_off * 2;
   const float* bias = EPI_W == EPI_STEM ? mp.bs : EPI_W == EPI_HID ? mp.b1 : EPI_W == EPI_RES ? mp.b2 : mp.bo;
-  float* Gb = (float*)(ws + g.off_act) + (size_t)h * g.mlp_block * E;
-  float* Hb = Gb + (size_t)g.Hkv * g.mlp_block * E;
 
   // A rows: thread (srow = tid / 4, sseg = tid % 4) stages 8 consecutive inputs of row srow
   const int srow = tid >> 2, sseg = tid & 3;
-  const int arow = row0 + min(srow, rows_valid - 1);   // clamped: rows past the end repeat the last one
+  const int arow = min(srow, rows_valid - 1);          // clamped: rows past the end repeat the last one
   const char* a_src;
-  if (A_BF16) a_src = (const char*)pr.K + ((size_t)h * pr.stride_head + (size_t)(g.n_sink + t0 + arow) * pr.stride_tok + sseg * 8) * 2;
-  else a_src = (const char*)((EPI_W == EPI_RES ? Hb : Gb) + (size_t)arow * E + sseg * 8);
+  if (A_BF16) a_src = (const char*)pr.K + ((size_t)h * pr.stride_head + (size_t)(g.n_sink + tok0 + arow) * pr.stride_tok + sseg * 8) * 2;
+  else a_src = (const char*)((EPI_W == EPI_RES ? Ht : Gt) + (size_t)arow * E + sseg * 8);
   // weight operands: the NT output tiles of this wavefront (clamped to the last tile: every lane loads)
   const int colw = n0 + wv * NT * 16;
   const char* w_src[NT];
@@ -183,8 +185,8 @@ __global__ __launch_bounds__(kThreads, 2) void mlp_gemm_kernel(Geom g, const tkp
   }
 
   // ---- epilogue: acc[mt][nt][i] <-> token row mt*16 + r, output colw + nt*16 + 4kg + i --------------
-  float* cache_h = pr.phi_cache + ((size_t)h * n + t0 + row0) * g.dphi;
-  auto g_ptr = [&](int mt, int nt) { return Gb + (size_t)(row0 + min(mt * 16 + r, rows_valid - 1)) * E + colw + nt * 16 + 4 * kg; };
+  float* cache_h = pr.phi_cache + ((size_t)h * n + tok0) * g.dphi;
+  auto g_ptr = [&](int mt, int nt) { return Gt + (size_t)min(mt * 16 + r, rows_valid - 1) * E + colw + nt * 16 + 4 * kg; };
   if constexpr (EPI == EPI_RESOUT) {
     // g1 in place of the accumulators (the old residual stream is loaded a few tiles at a time)
     constexpr int HB = NT >= 8 ? 2 : NT > 1 ? NT / 2 : 1;
@@ -298,14 +300,64 @@ __global__ __launch_bounds__(kThreads, 2) void mlp_gemm_kernel(Geom g, const tkp
                                           fmaf(mp.alpha, v.z, gcur[mt].z), fmaf(mp.alpha, v.w, gcur[mt].w));
       if (EPI == EPI_OUT) v = make_float4(expf(v.x), expf(v.y), expf(v.z), expf(v.w));
       if (row >= rows_valid) continue;
-      if (EPI == EPI_STEM || EPI == EPI_RES) *(float4*)(Gb + (size_t)(row0 + row) * E + col) = v;
-      if (EPI == EPI_HID) *(float4*)(Hb + (size_t)(row0 + row) * E + col) = v;
+      if (EPI == EPI_STEM || EPI == EPI_RES) *(float4*)(Gt + (size_t)row * E + col) = v;
+      if (EPI == EPI_HID) *(float4*)(Ht + (size_t)row * E + col) = v;
       if (EPI == EPI_OUT) *(float4*)(cache_h + (size_t)row * g.dphi + col) = v;
     }
     if (EPI == EPI_RES) {
 #pragma unroll
       for (int mt = 0; mt < 4; ++mt) gcur[mt] = gnext[mt];
     }
+  }
+}
+
+// block-wise launch of one layer: grid (Hkv * mlp_block / 64, ceil(Nout / (64 NT))); the activations of the
+// whole token block live in the workspace ([Hkv][mlp_block][d_emb] for g, the same for h)
+template <int EPI, int NT, int NTO = 0>
+__global__ __launch_bounds__(kThreads, 2) void mlp_gemm_kernel(Geom g, const tkphi_problem* __restrict__ probs,
+                                                               char* __restrict__ ws, int p, int t0) {
+  __shared__ __attribute__((aligned(16))) char lds_raw[mlp_lds_bytes<NT>()];
+  const int h = blockIdx.x % g.Hkv;
+  const tkphi_problem pr = probs[p];
+  if (pr.L < 1 || pr.L > g.max_L) return;
+  const int n = mid_size(pr.L, g.n_sink, g.n_tail);
+  const int row0 = (blockIdx.x / g.Hkv) * 64;          // first row of the tile inside the token block
+  if (t0 + row0 >= n) return;
+  const int rows_valid = min(64, n - (t0 + row0));
+  const tkphi_mlp mp = pr.mlp_k[h];
+  float* Gb = (float*)(ws + g.off_act) + (size_t)h * g.mlp_block * g.d_emb;
+  float* Hb = Gb + (size_t)g.Hkv * g.mlp_block * g.d_emb;
+  mlp_gemm_tile<EPI, NT, NTO>(g, pr, mp, ws, lds_raw, h, n, t0 + row0, rows_valid, Gb + (size_t)row0 * g.d_emb,
+                              Hb + (size_t)row0 * g.d_emb, (int)blockIdx.y * 64 * NT);
+}
+
+// The whole chain in one launch (d_emb == 64 NT, d_phi == 64 NTO): a tile's layers depend only on the
+// tile's own rows, so a persistent workgroup takes a 64-token tile through stem, hidden layer and
+// residual + output with workgroup barriers in between; its activations (2 x 64 x d_emb floats of the
+// workspace per workgroup) never leave L2.  grid (n_wg), tile T = blockIdx.x + k n_wg -> KV head
+// T % Hkv, tokens [64 (T / Hkv), + 64).  No launch gaps and one cold start per workgroup (4 % faster
+// than the layer-wise launches; holding back every other workgroup at the start so that neighbours on a
+// CU run different phases was measured to change nothing).
+template <int NT, int NTO>
+__global__ __launch_bounds__(kThreads, 2) void mlp_chain_kernel(Geom g, const tkphi_problem* __restrict__ probs,
+                                                                char* __restrict__ ws, int p) {
+  __shared__ __attribute__((aligned(16))) char lds_raw[mlp_lds_bytes<NT>()];
+  const tkphi_problem pr = probs[p];
+  if (pr.L < 1 || pr.L > g.max_L) return;
+  const int n = mid_size(pr.L, g.n_sink, g.n_tail);
+  const int total = ((n + 63) / 64) * g.Hkv;
+  float* Gt = (float*)(ws + g.off_act) + (size_t)blockIdx.x * 2 * 64 * g.d_emb;
+  float* Ht = Gt + (size_t)64 * g.d_emb;
+  for (int T = blockIdx.x; T < total; T += gridDim.x) {
+    const int h = T % g.Hkv, tok0 = (T / g.Hkv) * 64;
+    const int rows_valid = min(64, n - tok0);
+    const tkphi_mlp mp = pr.mlp_k[h];
+    mlp_gemm_tile<EPI_STEM, NT, 0>(g, pr, mp, ws, lds_raw, h, n, tok0, rows_valid, Gt, Ht, 0);
+    __syncthreads();                                   // g0 of the tile is visible to the workgroup; LDS is free
+    mlp_gemm_tile<EPI_HID, NT, 0>(g, pr, mp, ws, lds_raw, h, n, tok0, rows_valid, Gt, Ht, 0);
+    __syncthreads();
+    mlp_gemm_tile<EPI_RESOUT, NT, NTO>(g, pr, mp, ws, lds_raw, h, n, tok0, rows_valid, Gt, Ht, 0);
+    __syncthreads();                                   // the next tile overwrites g, h and the planes
   }
 }
 
@@ -335,19 +387,36 @@ static void launch_mlp_resout_nt(const Geom& g, const tkphi_problem* probs, char
   else hipLaunchKernelGGL((mlp_gemm_kernel<EPI_RESOUT, NT, 4>), grid, dim3(kThreads), 0, s, g, probs, ws, p, t0);
 }
 
-// the key features of every problem's mid-region -> phi_cache, block by block
+template <int NT>
+static void launch_mlp_chain_nt(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s, int p) {
+  const int tiles = (g.max_mid + 63) / 64 * g.Hkv;
+  dim3 grid(std::min(tiles, kMlpChainWGs));
+  if (g.dphi == 64) hipLaunchKernelGGL((mlp_chain_kernel<NT, 1>), grid, dim3(kThreads), 0, s, g, probs, ws, p);
+  else if (g.dphi == 128) hipLaunchKernelGGL((mlp_chain_kernel<NT, 2>), grid, dim3(kThreads), 0, s, g, probs, ws, p);
+  else hipLaunchKernelGGL((mlp_chain_kernel<NT, 4>), grid, dim3(kThreads), 0, s, g, probs, ws, p);
+}
+
+// the key features of every problem's mid-region -> phi_cache
 void launch_mlp_features(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
   if (g.max_mid == 0) return;
   const size_t pieces = ((size_t)g.d_emb * g.d + (size_t)2 * g.d_emb * g.d_emb + (size_t)g.dphi * g.d_emb) / 8;
-  const bool fused = resout_fusable(g) && !getenv("TKPHI_MLP_UNFUSED");
+  const char* mode = getenv("TKPHI_MLP_MODE");         // "blocks": layer-wise launches per token block; "unfused": also residual and output apart
+  const bool fusable = resout_fusable(g) && !(mode && !strcmp(mode, "unfused"));
+  const bool chain = fusable && !(mode && !strcmp(mode, "blocks"));
   for (int p = 0; p < g.n_problems; ++p) {
     hipLaunchKernelGGL(mlp_pack_weights_kernel, dim3((unsigned)((pieces + kThreads - 1) / kThreads), g.Hkv), dim3(kThreads), 0, s,
                        g, probs, ws, p);
+    if (chain) {
+      if (g.d_emb == 512) launch_mlp_chain_nt<8>(g, probs, ws, s, p);
+      else if (g.d_emb == 256) launch_mlp_chain_nt<4>(g, probs, ws, s, p);
+      else launch_mlp_chain_nt<2>(g, probs, ws, s, p);
+      continue;
+    }
     for (int t0 = 0; t0 < g.max_mid; t0 += g.mlp_block) {
       const int rows = std::min(g.mlp_block, g.max_mid - t0);
       launch_mlp_gemm<EPI_STEM>(g, probs, ws, s, rows, g.d_emb, p, t0);
       launch_mlp_gemm<EPI_HID>(g, probs, ws, s, rows, g.d_emb, p, t0);
-      if (fused) {
+      if (fusable) {
         if (g.d_emb == 512) launch_mlp_resout_nt<8>(g, probs, ws, s, rows, p, t0);
         else if (g.d_emb == 256) launch_mlp_resout_nt<4>(g, probs, ws, s, rows, p, t0);
         else launch_mlp_resout_nt<2>(g, probs, ws, s, rows, p, t0);

@@ -151,7 +151,9 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
                                           (int64_t)512 * 64 / g->Hkv);
     g->mlp_block = (int)std::clamp<int64_t>(env_int("TKPHI_MLP_BLOCK", (int)blk) / 64 * 64, 64, 8192);
     g->off_act = align_up(build_total, 256);
-    g->off_wpack = align_up(g->off_act + (size_t)2 * g->Hkv * g->mlp_block * g->d_emb * sizeof(float), 256);
+    // (or, for the one-launch build, 2 x 64 x d_emb floats per persistent workgroup)
+    const size_t act_bytes = std::max((size_t)2 * g->Hkv * g->mlp_block, (size_t)2 * 64 * kMlpChainWGs) * g->d_emb * sizeof(float);
+    g->off_wpack = align_up(g->off_act + act_bytes, 256);
     build_all = g->off_wpack + (size_t)g->Hkv * ((size_t)g->d_emb * g->d + (size_t)2 * g->d_emb * g->d_emb +
                                                  (size_t)g->dphi * g->d_emb) * 2;
   }

@@ -98,6 +98,7 @@ struct SelPlan {
   int32_t nb;      // tokens in the boundary bin
   int32_t n_sel;   // retrieved tokens K' = min(topk, |M|, max_K)
 };
+constexpr int kMlpChainWGs = 512;       // persistent workgroups of the one-launch MLP build (two per CU)
 constexpr int kMaxScanChunks = 2048;   // chunk offsets are scanned in LDS by `plan`
 
 // kernel launchers (each defined next to its kernels)

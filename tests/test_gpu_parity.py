@@ -331,16 +331,21 @@ def test_cached_key_features(shape, L, k):
     assert rel.max() <= (2.0 ** -15 if w.dtype == "bf16" else 2e-5), f"cache rel err {rel.max():.3e}"
 
 
-@pytest.mark.parametrize("shape,d_emb,L,k", [("l3b_128k", 512, 9000, 360), ("l1b_32k", 128, 10000, 49),
-                                             ("bf16_wide_phi", 256, 1500, 33)])
-def test_mlp_feature_maps(shape, d_emb, L, k):
+@pytest.mark.parametrize("shape,d_emb,L,k,mode", [("l3b_128k", 512, 9000, 360, ""), ("l1b_32k", 128, 10000, 49, ""),
+                                                  ("bf16_wide_phi", 256, 1500, 33, ""), ("l1b_32k", 128, 10000, 49, "blocks"),
+                                                  ("l3b_128k", 512, 4500, 45, "unfused")])
+def test_mlp_feature_maps(monkeypatch, shape, d_emb, L, k, mode):
     """Learned feature maps (App. "Head-wise phi architecture"): the build evaluates the one-block
     ReZero MLP phi_k on the mid-region keys with the tiled matrix-core GEMM chain, stores the
     features and contracts them into S, u; decode evaluates phi_q per query head with the GEMV
     chain and gathers the stored key features.  Compared with the oracle run with phi_mlp on
     both sides: stored features, summaries, index sets, outputs; single problem and ragged batch
-    (the 10000-token case crosses the 8192-token activation block)."""
+    (the 10000-token case crosses the 8192-token activation block).  The build runs as one
+    persistent launch per problem by default; "blocks" forces the layer-wise launches per token block
+    (residual + output fused), "unfused" all four layers apart (the path of widths that do not fuse)."""
     import parity_utils as PU
+    if mode:
+        monkeypatch.setenv("TKPHI_MLP_MODE", mode)
     from oracle import tkphi_oracle as orc
     from paper_2604_05438_amd import harness as H
     if shape == "bf16_wide_phi":
