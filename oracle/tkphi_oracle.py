@@ -119,13 +119,15 @@ def mlp_param_count(d, d_emb, dphi):
 # ---------------------------------------------------------------------------
 # prefill: summary states, eq. (natural_cache)
 # ---------------------------------------------------------------------------
-def build_summaries(K, V, Wk, bk, a, c, n_sink, n_tail, phi_k_fns=None):
+def build_summaries(K, V, Wk, bk, a, c, n_sink, n_tail, phi_k_fns=None, n_gen=0):
     """S_M[h] = sum_{i in M} phi_k(k_i) v_i^T  ([dphi][d]),  u_M[h] = sum_{i in M} phi_k(k_i).
     phi_k_fns: optional list of per-KV-head feature maps (rows -> features) used instead of
-    the exp-affine map (Wk, bk, a, c)."""
+    the exp-affine map (Wk, bk, a, c).  n_gen: the last n_gen rows of K, V are generated tokens,
+    not part of the prefill segment the partition is defined on."""
     K = np.asarray(K, dtype=F64)
     V = np.asarray(V, dtype=F64)
     Hkv, L, d = K.shape
+    L -= int(n_gen)
     _, M = partition(L, n_sink, n_tail)
     feat = (lambda h, x: phi(x, Wk[h], bk[h], a, c)) if phi_k_fns is None else (lambda h, x: phi_k_fns[h](x))
     dphi = feat(0, K[0, :1]).shape[1]
@@ -168,7 +170,7 @@ def full_attention(q_g, K_h, V_h, scale):
 
 
 def decode_head(q_g, K_h, V_h, S_M, u_M, Wq_g, bq_g, Wk_h, bk_h, a, c, scale,
-                n_sink, n_tail, k, retrieved=None, phi_q_fn=None, phi_k_fn=None):
+                n_sink, n_tail, k, retrieved=None, phi_q_fn=None, phi_k_fn=None, n_gen=0):
     """One query head.  Returns a dict with the Top-K+phi output `y`, every
     intermediate of the method and the paper's comparison estimators.
 
@@ -177,18 +179,23 @@ def decode_head(q_g, K_h, V_h, S_M, u_M, Wq_g, bq_g, Wk_h, bk_h, a, c, scale,
     Sec. "Analysis: validating residual accounting").
     `phi_q_fn`, `phi_k_fn`: optional feature maps (rows -> features) of this query head / its KV
     head, used instead of the exp-affine maps (Wq_g, bq_g) / (Wk_h, bk_h).
+    `n_gen`: the last n_gen rows of K_h, V_h are the generated-token prefix G: exact, outside the
+    partition of the prefill segment, added to the same numerator and denominator
+    (eq. (implemented_decode)); with n_gen = 0 every output is that of eq. (hybrid_merge).
     """
     K_h = np.asarray(K_h, dtype=F64)
     V_h = np.asarray(V_h, dtype=F64)
-    L = K_h.shape[0]
+    n_gen = int(n_gen)
+    L = K_h.shape[0] - n_gen                           # prefill segment
     A, M = partition(L, n_sink, n_tail)
+    Gset = np.arange(L, L + n_gen, dtype=np.int64)
 
     s = scores(q_g, K_h, scale)
     if retrieved is None:
         Kset = topk_mid(s, M, k)
     else:
         Kset = np.asarray(retrieved, dtype=np.int64)
-    inK = np.zeros(L, dtype=bool)
+    inK = np.zeros(L + n_gen, dtype=bool)
     inK[Kset] = True
     Rset = M[~inK[M]]                                  # R = M \ K
     Eset = np.concatenate([A, Kset])                   # E = A U K
@@ -211,7 +218,9 @@ def decode_head(q_g, K_h, V_h, S_M, u_M, Wq_g, bq_g, Wk_h, bk_h, a, c, scale,
     # residual completion and single-normalisation merge, eq. (hybrid_merge)
     nu_R_hat = S_R.T @ p
     Z_R_hat = p @ u_R
-    y = (nu_E + nu_R_hat) / (Z_E + Z_R_hat)
+    # generated tokens: another exact branch under the same normalisation, eq. (implemented_decode)
+    nu_G, Z_G = e[Gset] @ V_h[Gset], e[Gset].sum()
+    y = (nu_E + nu_R_hat + nu_G) / (Z_E + Z_R_hat + Z_G)
 
     # ---- comparison estimators and diagnostics --------------------------
     nu_M_hat = np.asarray(S_M, dtype=F64).T @ p        # un-subtracted mid estimates
@@ -223,17 +232,17 @@ def decode_head(q_g, K_h, V_h, S_M, u_M, Wq_g, bq_g, Wk_h, bk_h, a, c, scale,
     y_full = (e @ V_h) / e.sum()
     out = {
         "y": y, "idx": Kset, "s": s,
-        "nu_E": nu_E, "Z_E": Z_E, "p": p, "f_K": f_K,
+        "nu_E": nu_E, "Z_E": Z_E, "nu_G": nu_G, "Z_G": Z_G, "p": p, "f_K": f_K,
         "S_R": S_R, "u_R": u_R, "nu_R_hat": nu_R_hat, "Z_R_hat": Z_R_hat,
         "nu_M_hat": nu_M_hat, "Z_M_hat": Z_M_hat,
         "nu_A": nu_A, "Z_A": Z_A, "nu_K": nu_K, "Z_K": Z_K,
         "nu_R": nu_R, "Z_R": Z_R, "nu_M": nu_M, "Z_M": Z_M,
         "y_full": y_full,
-        "y_topk": nu_E / Z_E,                                            # selection-only Top-K
-        "y_nosub": (nu_E + nu_M_hat) / (Z_E + Z_M_hat),                  # NoSub ablation
-        "y_exactsub": (nu_E + nu_R) / (Z_E + Z_R),                       # eq. (exact_sub_oracle)
-        "y_exactnosub": (nu_E + nu_M) / (Z_E + Z_M),                     # eq. (exact_nosub_oracle)
-        "rho_res": Z_R_hat / (Z_E + Z_R_hat),                            # residual denominator share
+        "y_topk": (nu_E + nu_G) / (Z_E + Z_G),                           # selection-only Top-K
+        "y_nosub": (nu_E + nu_M_hat + nu_G) / (Z_E + Z_M_hat + Z_G),     # NoSub ablation
+        "y_exactsub": (nu_E + nu_R + nu_G) / (Z_E + Z_R + Z_G),          # eq. (exact_sub_oracle)
+        "y_exactnosub": (nu_E + nu_M + nu_G) / (Z_E + Z_M + Z_G),        # eq. (exact_nosub_oracle)
+        "rho_res": Z_R_hat / (Z_E + Z_G + Z_R_hat),                      # residual denominator share
         "log_Z_err": (math.log(Z_R_hat) - math.log(Z_R)) if (Z_R_hat > 0 and Z_R > 0) else float("nan"),
     }
     # entropy / mass-recovery diagnostics (Sec. "Analysis: entropy and completion gains";
@@ -243,7 +252,7 @@ def decode_head(q_g, K_h, V_h, S_M, u_M, Wq_g, bq_g, Wk_h, bk_h, a, c, scale,
         ent = -float(np.sum(p_mid * np.log(p_mid)))
         out["H_mid"] = ent / math.log(M.size) if M.size > 1 else 0.0     # normalised entropy
         out["C_mid"] = Z_K / Z_M                                         # mid mass recovered by Top-K
-        out["rho_res_star"] = Z_R / (Z_A + Z_M)                          # true residual share
+        out["rho_res_star"] = Z_R / (Z_A + Z_M + Z_G)                    # true residual share
     if Kset.size < M.size and Kset.size > 0 and retrieved is None:
         srt = np.sort(s[M])[::-1]
         out["boundary_gap"] = srt[Kset.size - 1] - srt[Kset.size]
@@ -259,7 +268,7 @@ def rel_l1(y_hat, y_ref):
 
 
 def decode_layer(q, K, V, S, u, Wq, bq, Wk, bk, a, c, scale, n_sink, n_tail, k,
-                 heads=None, retrieved=None, phi_q_fns=None, phi_k_fns=None):
+                 heads=None, retrieved=None, phi_q_fns=None, phi_k_fns=None, n_gen=0):
     """All (or the listed) query heads of one layer; returns a list of per-head dicts."""
     Hq = np.asarray(q).shape[0]
     Hkv = np.asarray(K).shape[0]
@@ -273,5 +282,5 @@ def decode_layer(q, K, V, S, u, Wq, bq, Wk, bk, a, c, scale, n_sink, n_tail, k,
                                a, c, scale, n_sink, n_tail, k,
                                retrieved=None if retrieved is None else retrieved[g],
                                phi_q_fn=None if phi_q_fns is None else phi_q_fns[g],
-                               phi_k_fn=None if phi_k_fns is None else phi_k_fns[h]))
+                               phi_k_fn=None if phi_k_fns is None else phi_k_fns[h], n_gen=n_gen))
     return res

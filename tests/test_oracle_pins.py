@@ -416,3 +416,50 @@ def test_mlp_feature_map_shapes_and_reductions():
     rest = np.setdiff1d(M, r["idx"])
     fr = orc.phi_mlp(K[0, rest], P)
     assert np.abs(r["S_R"] - fr.T @ V[0, rest]).max() < 1e-10 * np.abs(S).max()
+
+
+# --- generated tokens: eq. (implemented_decode) ----------------------------------------
+def test_generated_tokens_are_one_more_exact_branch():
+    """The generated-token prefix G is exact and outside the prefill partition.  Pinned by routes
+    that do not use the branch's own formula: (a) G appended to the tail anchors of a longer
+    "prefill" gives the same mid-region, hence the same summaries, selection and output;
+    (b) with every mid token retrieved the output is dense softmax attention over prefill + G
+    (scipy); (c) a brute-force loop over the token classes; (d) n_gen = 0 changes nothing."""
+    rng = np.random.default_rng(21)
+    P = _rand_problem(rng, L=230)
+    n_gen, k = 9, 17
+    L = 230 - n_gen
+    kw = dict(a=P["a"], c=P["c"], n_sink=P["n_sink"])
+    S, u = orc.build_summaries(P["K"], P["V"], P["Wk"], P["bk"], n_tail=P["n_tail"], n_gen=n_gen, **kw)
+    S2, u2 = orc.build_summaries(P["K"], P["V"], P["Wk"], P["bk"], n_tail=P["n_tail"] + n_gen, **kw)
+    assert np.array_equal(S, S2) and np.array_equal(u, u2)
+    args = (P["q"], P["K"], P["V"], S, u, P["Wq"], P["bq"], P["Wk"], P["bk"], P["a"], P["c"], P["scale"], P["n_sink"])
+    res = orc.decode_layer(*args, P["n_tail"], k, n_gen=n_gen)
+    res2 = orc.decode_layer(*args, P["n_tail"] + n_gen, k)                       # (a)
+    for g, (r, r2) in enumerate(zip(res, res2)):
+        h = g // 2
+        assert np.array_equal(r["idx"], r2["idx"])
+        assert orc.rel_l1(r["y"], r2["y"]) < 1e-13
+        assert orc.rel_l1(r["y_topk"], r2["y_topk"]) < 1e-13 and orc.rel_l1(r["y_nosub"], r2["y_nosub"]) < 1e-13
+        assert abs(r["Z_E"] + r["Z_G"] - r2["Z_E"]) < 1e-12 * r2["Z_E"]
+        # (c) brute force: exact weights on sink, tail, retrieved and generated tokens; feature estimate elsewhere
+        q, Kh, Vh = P["q"][g], P["K"][h], P["V"][h]
+        num, den = np.zeros(Kh.shape[1]), 0.0
+        pq = orc.phi(q, P["Wq"][g], P["bq"][g], P["a"], P["c"])[0]
+        sel = set(r["idx"].tolist())
+        for i in range(L + n_gen):
+            exact = i < P["n_sink"] or i >= L - P["n_tail"] or i in sel
+            w = math.exp(P["scale"] * float(Kh[i] @ q)) if exact else \
+                float(pq @ orc.phi(Kh[i], P["Wk"][h], P["bk"][h], P["a"], P["c"])[0])
+            num += w * Vh[i]
+            den += w
+        assert orc.rel_l1(r["y"], num / den) < 1e-11
+        assert all(L - P["n_tail"] > i >= P["n_sink"] for i in sel)              # G is never retrieved
+    n_mid = L - P["n_sink"] - P["n_tail"]
+    for g, r in enumerate(orc.decode_layer(*args, P["n_tail"], n_mid, n_gen=n_gen)):     # (b)
+        ref = _dense_softmax_attention(P["q"][g], P["K"][g // 2], P["V"][g // 2], P["scale"])
+        assert orc.rel_l1(r["y"], ref) < 1e-12 and orc.rel_l1(r["y_full"], ref) < 1e-13
+    Pz = _rand_problem(np.random.default_rng(22))
+    rz, _, _ = _run(Pz, 11)
+    rz0, _, _ = _run(Pz, 11, n_gen=0)                                             # (d)
+    assert all(np.array_equal(x["y"], y["y"]) and x["Z_G"] == 0.0 for x, y in zip(rz0, rz))
