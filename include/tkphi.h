@@ -71,7 +71,8 @@ typedef enum tkphi_mode { TKPHI_MODE_SUB = 0, TKPHI_MODE_NOSUB = 1, TKPHI_MODE_T
 #define TKPHI_FLAG_DIAG 0x100
 
 /* bits of the device status word (tkphi_read_device_status) */
-#define TKPHI_DEV_BAD_LENGTH 1u   /* a problem had L < 1 or L > max_L and was skipped         */
+#define TKPHI_DEV_BAD_LENGTH 1u   /* a problem had L < 1 or L > max_L and was skipped, or an
+                                     n_gen outside [0, cfg.max_gen] that was clamped           */
 #define TKPHI_DEV_CLAMPED    2u   /* a residual denominator came out <= 0 after subtraction
                                      and the residual branch was dropped for that head
                                      (App. "Why positivity matters": numerical clamp)         */
@@ -134,6 +135,8 @@ typedef struct tkphi_config {
                              token and KV head of extra cache)                              */
   int32_t phi_kind;      /* tkphi_phi_kind; 0 = EXP_AFFINE                                  */
   int32_t d_emb;         /* MLP only: internal width, a power of two in [64, 1024]          */
+  int32_t max_gen;       /* upper bound of tkphi_problem::n_gen (generated tokens kept exact,
+                            eq. (implemented_decode)); 0 if the feature is not used          */
 } tkphi_config;
 
 /* Optional per-query-head diagnostics / unnormalised outputs written by tkphi_decode,
@@ -197,6 +200,14 @@ typedef struct tkphi_problem {
   int32_t L;             /* prefill length, 1 <= L <= max_L                            */
   int32_t topk;          /* the paper's K: retrieved mid-region tokens per query head (the
                             budget); clipped to min(topk, |M|, max_K); 0 is legal      */
+  int32_t n_gen;         /* generated tokens at the current step, 0 <= n_gen <= cfg.max_gen: rows
+                            [L, L + n_gen) of K and V.  They are outside the prefill partition
+                            (never retrieved, not in S, u) and enter the output as one more exact
+                            branch under the same normalisation (eq. (implemented_decode)); in the
+                            aux / diag outputs they count with the exact support (Z_E, nu_E, Z_A).
+                            A value outside the range is clamped to it by the kernels and sets
+                            TKPHI_DEV_BAD_LENGTH in the device status word.              */
+  int32_t reserved;      /* 0                                                          */
 } tkphi_problem;
 
 /* Bytes of DEVICE workspace tkphi_build_summaries / tkphi_decode need for the given

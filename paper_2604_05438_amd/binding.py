@@ -40,7 +40,7 @@ class tkphi_config(C.Structure):
         ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("d_head", C.c_int32), ("d_phi", C.c_int32),
         ("n_sink", C.c_int32), ("n_tail", C.c_int32), ("kv_dtype", C.c_int32),
         ("score_scale", C.c_float), ("phi_in_scale", C.c_float), ("phi_norm_coef", C.c_float),
-        ("cache_features", C.c_int32), ("phi_kind", C.c_int32), ("d_emb", C.c_int32),
+        ("cache_features", C.c_int32), ("phi_kind", C.c_int32), ("d_emb", C.c_int32), ("max_gen", C.c_int32),
     ]
 
 
@@ -59,7 +59,7 @@ class tkphi_problem(C.Structure):
         ("S", C.c_void_p), ("u", C.c_void_p), ("q", C.c_void_p), ("out", C.c_void_p),
         ("topk_idx", C.c_void_p), ("aux", C.c_void_p), ("scores", C.c_void_p), ("diag", C.c_void_p), ("phi_cache", C.c_void_p),
         ("mlp_q", C.c_void_p), ("mlp_k", C.c_void_p),
-        ("L", C.c_int32), ("topk", C.c_int32),
+        ("L", C.c_int32), ("topk", C.c_int32), ("n_gen", C.c_int32), ("reserved", C.c_int32),
     ]
 
 
@@ -172,10 +172,10 @@ def tkphi_read_device_status(workspace_ptr: int, stream: int) -> int:
 
 # ---- marshalling helpers (device memory via torch) -----------------------------------------
 def make_config(n_q_heads, n_kv_heads, d_head, d_phi, n_sink, n_tail, dtype, score_scale, phi_in_scale,
-                phi_norm_coef, cache_features=0, phi_kind=0, d_emb=0) -> tkphi_config:
+                phi_norm_coef, cache_features=0, phi_kind=0, d_emb=0, max_gen=0) -> tkphi_config:
     kv = {"bf16": TKPHI_BF16, "f32": TKPHI_F32}[dtype] if isinstance(dtype, str) else int(dtype)
     return tkphi_config(n_q_heads, n_kv_heads, d_head, d_phi, n_sink, n_tail, kv, score_scale, phi_in_scale,
-                        phi_norm_coef, int(cache_features), int(phi_kind), int(d_emb))
+                        phi_norm_coef, int(cache_features), int(phi_kind), int(d_emb), int(max_gen))
 
 
 def _ptr(t) -> int:
@@ -183,13 +183,13 @@ def _ptr(t) -> int:
 
 
 def make_problem(K, V, Wq, bq, Wk, bk, S, u, q=None, out=None, topk_idx=None, aux=None, scores=None,
-                 L=None, topk=0, diag=None, phi_cache=None, mlp_q=None, mlp_k=None) -> tkphi_problem:
-    """Fills a tkphi_problem from torch device tensors (K, V: [Hkv][L][d], last dim contiguous)."""
+                 L=None, topk=0, diag=None, phi_cache=None, mlp_q=None, mlp_k=None, n_gen=0) -> tkphi_problem:
+    """Fills a tkphi_problem from torch device tensors (K, V: [Hkv][L + n_gen][d], last dim contiguous)."""
     assert K.stride(-1) == 1 and V.stride(-1) == 1 and K.stride() == V.stride()
     return tkphi_problem(
         _ptr(K), _ptr(V), K.stride(0), K.stride(1), _ptr(Wq), _ptr(bq), _ptr(Wk), _ptr(bk), _ptr(S), _ptr(u),
         _ptr(q), _ptr(out), _ptr(topk_idx), _ptr(aux), _ptr(scores), _ptr(diag), _ptr(phi_cache), _ptr(mlp_q), _ptr(mlp_k),
-        int(K.shape[1] if L is None else L), int(topk))
+        int(K.shape[1] - n_gen if L is None else L), int(topk), int(n_gen), 0)
 
 
 def upload_mlp(maps: dict, device="cuda"):

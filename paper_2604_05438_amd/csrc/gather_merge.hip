@@ -100,7 +100,8 @@ __device__ void anchor_partial(const Geom& g, const tkphi_problem& pr, int gq, i
   __shared__ float a_m;
   const int tid = threadIdx.x, d = g.d;
   const int h = gq / g.G;
-  const int n_anchor = n > 0 ? g.n_sink + g.n_tail : pr.L;
+  const int n_prefill = n > 0 ? g.n_sink + g.n_tail : pr.L;             // exact anchors of the prefill segment
+  const int n_anchor = n_prefill + min(max(pr.n_gen, 0), g.max_gen);    // + generated tokens, rows [L, L + n_gen)
   const int base = batch * 64;
   if (base >= n_anchor) return;
   const int cnt = min(64, n_anchor - base);
@@ -113,7 +114,7 @@ __device__ void anchor_partial(const Geom& g, const tkphi_problem& pr, int gq, i
   for (int i = tid; i < 2 * d + 4; i += kThreads) a_acc[i] = 0.f;
   if (tid < 64) {
     const int a = base + min(tid, cnt - 1);
-    a_tok[tid] = (n > 0 && a >= g.n_sink) ? (pr.L - g.n_tail + (a - g.n_sink)) : a;
+    a_tok[tid] = a >= n_prefill ? pr.L + (a - n_prefill) : (n > 0 && a >= g.n_sink) ? (pr.L - g.n_tail + (a - g.n_sink)) : a;
   }
   __syncthreads();
   // scores of the batch
@@ -495,7 +496,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
   if (pr.L < 1 || pr.L > g.max_L) return;
   const int n = mid_size(pr.L, g.n_sink, g.n_tail);
   const int Ksel = max(0, min(min(pr.topk, n), g.max_K));
-  const int n_anchor = n > 0 ? g.n_sink + g.n_tail : pr.L;
+  const int n_anchor = (n > 0 ? g.n_sink + g.n_tail : pr.L) + min(max(pr.n_gen, 0), g.max_gen);   // anchors + generated tokens
   const int n_used = (Ksel + kPairsPerWG - 1) / kPairsPerWG;     // tiles holding retrieved tokens
   const int na_used = (n_anchor + 63) / 64;                      // tiles holding anchors
   const int d = g.d, dphi = g.dphi;

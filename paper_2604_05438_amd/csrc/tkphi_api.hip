@@ -68,6 +68,7 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
       return TKPHI_ESHAPE;
     }
   }
+  if (cfg->max_gen < 0 || cfg->max_gen > (1 << 20)) { set_error("max_gen=%d out of range [0, 2^20]", cfg->max_gen); return TKPHI_EINVAL; }
   if (n_problems > 65535) { set_error("n_problems=%d exceeds 65535", n_problems); return TKPHI_ESHAPE; }
   if (cfg->n_sink < 0 || cfg->n_tail < 0) {
     set_error("n_sink=%d n_tail=%d must be >= 0", cfg->n_sink, cfg->n_tail);
@@ -79,6 +80,7 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   g->dtype = cfg->kv_dtype;
   g->cache = cfg->cache_features ? 1 : 0;
   g->phi_kind = cfg->phi_kind; g->d_emb = cfg->d_emb;
+  g->max_gen = cfg->max_gen;
   g->use_mfma = (cfg->kv_dtype == TKPHI_BF16 && cfg->d_phi == cfg->d_head && !env_int("TKPHI_FORCE_GENERIC", 0)) ? 1 : 0;
   g->n_problems = n_problems; g->max_L = max_L;
   const int64_t mid = (int64_t)max_L - cfg->n_sink - cfg->n_tail;
@@ -108,7 +110,7 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   if (!g->use_mfma || g->scan_unit >= g->scan_chunk) g->interleave = 0;
   // gather: tiles of kPairsPerWG retrieved tokens per query head
   g->n_tiles = (int)ceil_div(std::min<int64_t>(max_K, g->max_mid), kPairsPerWG);
-  g->n_atiles = (int)std::max<int64_t>(1, ceil_div(std::min<int64_t>((int64_t)cfg->n_sink + cfg->n_tail, max_L), 64));
+  g->n_atiles = (int)std::max<int64_t>(1, ceil_div(std::min<int64_t>((int64_t)cfg->n_sink + cfg->n_tail, max_L) + cfg->max_gen, 64));
   // summary_build: 512 workgroups fill the chip (2 per CU); larger jobs get about 2048 chunks of at
   // least 2048 tokens so that the last, partly filled round of workgroups stays a small share
   const int64_t bc_small = std::clamp<int64_t>(ceil_div(units, 512), 256, 2048);
@@ -369,6 +371,7 @@ tkphi_status tkphi_check_problems(const tkphi_config* cfg, const tkphi_problem* 
         if (!rq[i]) { set_error("problem %d: %s is null", p, nq[i]); return TKPHI_EINVAL; }
         if (((uintptr_t)rq[i]) % 16 != 0) { set_error("problem %d: %s not 16-byte aligned", p, nq[i]); return TKPHI_EALIGN; }
       }
+      if (q.n_gen < 0 || q.n_gen > cfg->max_gen) { set_error("problem %d: n_gen=%d outside [0, cfg.max_gen=%d]", p, q.n_gen, cfg->max_gen); return TKPHI_ESHAPE; }
       if (q.topk < 0 || q.topk > max_K) { set_error("problem %d: topk=%d outside [0, max_K=%d]", p, q.topk, max_K); return TKPHI_ESHAPE; }
       if (q.topk_idx && ((uintptr_t)q.topk_idx) % 4 != 0) { set_error("problem %d: topk_idx misaligned", p); return TKPHI_EALIGN; }
       if (q.aux && ((uintptr_t)q.aux) % 4 != 0) { set_error("problem %d: aux misaligned", p); return TKPHI_EALIGN; }

@@ -35,13 +35,14 @@ struct Geom {
   int scan_chunk, n_scan_chunks;     // score_mid: mid tokens per workgroup
   int scan_unit;         // tokens a score_mid workgroup takes per iteration (scan_chunk is a multiple)
   int phi_kind, d_emb;   // tkphi_phi_kind; MLP width
+  int max_gen;           // bound of tkphi_problem::n_gen (generated tokens, exact)
   int mlp_block;         // MLP build: tokens per KV head whose activations are held at once (multiple of 64)
   int cache;             // 1: key features are stored by the build and gathered by decode (cfg.cache_features)
   int diag;              // 1: the select emit pass also reduces the entropy / mass diagnostics
   int interleave;        // 1: chunk c owns the units c, c + n_chunks, c + 2 n_chunks, ... of its problem
                          // (all workgroups sweep the key cache together); 0: one contiguous range
   int n_tiles;           // gather: ceil(max_K / kPairsPerWG) retrieved-token tiles per query head
-  int n_atiles;          // gather: ceil((n_sink + n_tail) / 64) anchor tiles per query head (>= 1)
+  int n_atiles;          // gather: ceil((n_sink + n_tail + max_gen) / 64) tiles of exact anchors + generated tokens per query head (>= 1)
   int build_chunk, n_build_chunks;   // summary_build: mid tokens per workgroup
   int part_stride;       // floats per partial: 2*d + 4
   float score_scale, a, c;
@@ -320,8 +321,8 @@ __device__ __forceinline__ float gelu_erf(float x) {
 __device__ __forceinline__ void write_device_status(const Geom& g, const tkphi_problem* probs, char* ws) {
   int bad = 0;
   for (int i = threadIdx.x; i < g.n_problems; i += blockDim.x) {
-    const int Li = probs[i].L;
-    bad |= (Li < 1 || Li > g.max_L) ? 1 : 0;
+    const int Li = probs[i].L, gi = probs[i].n_gen;
+    bad |= (Li < 1 || Li > g.max_L || gi < 0 || gi > g.max_gen) ? 1 : 0;
   }
   bad = __syncthreads_or(bad);
   if (threadIdx.x == 0) *(uint32_t*)(ws + g.off_status) = bad ? TKPHI_DEV_BAD_LENGTH : 0u;

@@ -18,11 +18,12 @@ def to_device(a: np.ndarray, device="cuda") -> torch.Tensor:
     return t.to(device)
 
 
-def config_of(w: Workload, cache_features: bool = False, d_emb: int = 0) -> B.tkphi_config:
-    """d_emb > 0 selects the MLP feature maps (which need the feature cache)."""
+def config_of(w: Workload, cache_features: bool = False, d_emb: int = 0, max_gen: int = 0) -> B.tkphi_config:
+    """d_emb > 0 selects the MLP feature maps (which need the feature cache); max_gen bounds the
+    generated tokens a problem may append after its prefill rows."""
     return B.make_config(w.n_q_heads, w.n_kv_heads, w.d_head, w.d_phi, w.n_sink, w.n_tail, w.dtype,
                          w.score_scale, w.phi_in_scale, w.phi_norm_coef, int(cache_features or d_emb > 0),
-                         B.TKPHI_PHI_MLP if d_emb > 0 else B.TKPHI_PHI_EXP_AFFINE, d_emb)
+                         B.TKPHI_PHI_MLP if d_emb > 0 else B.TKPHI_PHI_EXP_AFFINE, d_emb, max_gen)
 
 
 class Batch:
@@ -46,7 +47,7 @@ class Batch:
                     t["mlp_" + side + "_w"] = {kk: (vv if kk == "alpha" else to_device(vv, device))
                                                for kk, vv in lay["mlp"][side].items()}
                     t["mlp_" + side] = B.upload_mlp(t["mlp_" + side + "_w"], device)
-            L = int(lay["L"])
+            L = int(lay["L"])                      # prefill length; K, V hold L + lay["n_gen"] rows
             n_mid = max(0, L - cfg.n_sink - cfg.n_tail)
             t["S"] = torch.empty((Hkv, dphi, d), dtype=torch.float32, device=device)
             t["u"] = torch.empty((Hkv, dphi), dtype=torch.float32, device=device)
@@ -63,7 +64,7 @@ class Batch:
             probs.append(B.make_problem(t["K"], t["V"], t["Wq"], t["bq"], t["Wk"], t["bk"], t["S"], t["u"],
                                         q=t["q"], out=t["out"], topk_idx=t.get("topk_idx"), aux=t.get("aux"),
                                         scores=t.get("scores"), L=L, topk=int(k), diag=t.get("diag"), phi_cache=t.get("phi_cache"),
-                                        mlp_q=t.get("mlp_q"), mlp_k=t.get("mlp_k")))
+                                        mlp_q=t.get("mlp_q"), mlp_k=t.get("mlp_k"), n_gen=int(lay.get("n_gen", 0))))
         self.host_table, self.table = B.upload_problems(probs, device)
         B.tkphi_check_problems(cfg, self.host_table, self.n, self.max_L, self.max_K, True)
         self.ws_bytes = B.tkphi_workspace_bytes(cfg, self.n, self.max_L, self.max_K)

@@ -46,12 +46,14 @@ def oracle_layer(w, P, k, heads=None, S=None, u=None, retrieved=None):
     O = oracle_inputs(P)
     fq, fk = mlp_feature_fns(P)
     O["phi_k_fns"] = fk
+    O["n_gen"] = int(P.get("n_gen", 0))
+    n_gen = int(P.get("n_gen", 0))                     # generated tokens: the last n_gen rows of K, V
     if S is None:
         S, u = orc.build_summaries(O["K"], O["V"], O["Wk"], O["bk"], w.phi_in_scale, w.phi_norm_coef,
-                                   w.n_sink, w.n_tail, phi_k_fns=fk)
+                                   w.n_sink, w.n_tail, phi_k_fns=fk, n_gen=n_gen)
     res = orc.decode_layer(O["q"], O["K"], O["V"], S, u, O["Wq"], O["bq"], O["Wk"], O["bk"],
                            w.phi_in_scale, w.phi_norm_coef, w.score_scale, w.n_sink, w.n_tail, k,
-                           heads=heads, retrieved=retrieved, phi_q_fns=fq, phi_k_fns=fk)
+                           heads=heads, retrieved=retrieved, phi_q_fns=fq, phi_k_fns=fk, n_gen=n_gen)
     return res, S, u, O
 
 
@@ -116,7 +118,7 @@ def check_summaries(S_gpu, u_gpu, S_or, u_or, tol, w=None, O=None, eps=None):
         if w is None:
             assert eS <= tol and eu <= tol, f"head {h}: S rel-F {eS:.3e}, u rel {eu:.3e} (tol {tol:.1e})"
         else:
-            L = O["K"].shape[1]
+            L = O["K"].shape[1] - int(O.get("n_gen", 0))
             _, M = orc.partition(L, w.n_sink, w.n_tail)
             if O.get("phi_k_fns") is not None:
                 F = O["phi_k_fns"][h](O["K"][h, M])
@@ -167,12 +169,13 @@ def check_layer(w, P, k, batch, i, heads=None, sum_tol=None, mode="sub", check_a
             check_output(y[g], r2[key], f"head {g} {key} (oracle on the GPU's set)")
         if check_aux:
             m = float(aux[g, 0])
-            E = np.concatenate([orc.partition(L, w.n_sink, w.n_tail)[0], r["idx"]])
+            n_gen = int(P.get("n_gen", 0))            # generated tokens count with the exact support
+            E = np.concatenate([orc.partition(L, w.n_sink, w.n_tail)[0], r["idx"], np.arange(L, L + n_gen)])
             m_or = r["s"][E].max() if E.size else 0.0
             assert abs(m - m_or) <= 1e-5 * max(1.0, abs(m_or)), f"head {g}: shift {m} vs {m_or}"
-            Z_or = r["Z_E"] * np.exp(-m_or)
+            Z_or = (r["Z_E"] + r["Z_G"]) * np.exp(-m_or)
             assert abs(aux[g, 1] - Z_or) <= 1e-4 * Z_or + 1e-30, f"head {g}: Z_E {aux[g, 1]} vs {Z_or}"
-            nu_or = r["nu_E"] * np.exp(-m_or)
+            nu_or = (r["nu_E"] + r["nu_G"]) * np.exp(-m_or)
             assert np.abs(aux[g, 4:4 + d] - nu_or).max() <= 1e-4 * max(np.abs(nu_or).max(), 1e-30) + 1e-6
             assert aux[g, 3] == 0.0, f"head {g}: residual clamp fired"
             if mode == "sub" and n_mid > r["idx"].size:

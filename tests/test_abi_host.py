@@ -72,6 +72,21 @@ def test_mlp_feature_map_config_validation():
             B.tkphi_check_problems(cfg, (B.tkphi_problem * 1)(q), 1, 1000, 9, True)
 
 
+def test_generated_token_bounds_are_validated():
+    assert B.tkphi_workspace_bytes(_cfg(max_gen=64), 1, 4096, 40) >= B.tkphi_workspace_bytes(_cfg(), 1, 4096, 40) > 0
+    assert B.tkphi_workspace_bytes(_cfg(max_gen=-1), 1, 4096, 40) == 0
+    cfg = _cfg(max_gen=32)
+    p = B.tkphi_problem(K=4096, V=8192, stride_head=1100 * 64, stride_tok=64, Wq=4096, bq=4096, Wk=4096, bk=4096,
+                        S=4096, u=4096, q=4096, out=4096, L=1000, topk=9, n_gen=32)
+    B.tkphi_check_problems(cfg, (B.tkphi_problem * 1)(p), 1, 1000, 9, True)
+    for bad in (33, -1):
+        q = B.tkphi_problem.from_buffer_copy(p)
+        q.n_gen = bad
+        with pytest.raises(B.TkphiError) as e:
+            B.tkphi_check_problems(cfg, (B.tkphi_problem * 1)(q), 1, 1000, 9, True)
+        assert e.value.status == B.TKPHI_ESHAPE
+
+
 def test_status_strings():
     seen = {B.tkphi_status_string(s) for s in range(-6, 1)}
     assert len(seen) == 7 and B.tkphi_status_string(-99) == "unknown status"

@@ -269,7 +269,8 @@ def _check_diag(w, P, k, b, i, heads):
         assert abs(row[4] - r["rho_res_star"]) <= 1e-4 * max(r["rho_res_star"], 1e-6), f"head {g}: rho_res*"
         if np.isfinite(r["log_Z_err"]):
             assert abs(row[5] - r["log_Z_err"]) <= 5e-3, f"head {g}: log error {row[5]} vs {r['log_Z_err']}"
-        assert abs(row[6] - np.log(r["Z_A"])) <= 1e-4 * max(1.0, abs(np.log(r["Z_A"]))), f"head {g}: log Z_A"
+        Z_A = r["Z_A"] + r["Z_G"]                      # generated tokens count with the exact anchors
+        assert abs(row[6] - np.log(Z_A)) <= 1e-4 * max(1.0, abs(np.log(Z_A))), f"head {g}: log Z_A"
 
 
 @pytest.mark.parametrize("shape,L,k,interleave", [("l3b_128k", 9000, 360, 0), ("l3b_128k", 20011, 200, 1),
@@ -387,3 +388,49 @@ def test_mlp_feature_maps(monkeypatch, shape, d_emb, L, k, mode):
     _check_diag(w, layers[0], ks[0], b, 0, heads=[0, w.n_q_heads - 1])
     b.decode(B.TKPHI_MODE_NOSUB)
     PU.check_layer(w, layers[0], ks[0], b, 0, heads=[w.n_q_heads - 1], mode="nosub")
+
+
+@pytest.mark.parametrize("shape,d_emb", [("l3b_128k", 0), ("l1b_32k", 0), ("tiny_f32", 0), ("l1b_32k", 128)])
+def test_generated_tokens_stay_exact(shape, d_emb):
+    """eq. (implemented_decode): rows [L, L + n_gen) of K, V are the generated-token prefix, exact
+    and outside the prefill partition.  A ragged batch with n_gen = 0, 1, 64 (a whole extra tile),
+    70 and the bound max_gen, one of them with an empty mid-region; every accounting mode; and the
+    equivalence the oracle is pinned by: appending the generated tokens to the tail anchors of a
+    longer prefill gives the same output."""
+    import parity_utils as PU
+    from paper_2604_05438_amd import binding as B
+    from paper_2604_05438_amd import harness as H
+    w = I.WORKLOADS[shape]
+    max_gen = 100
+    A = w.n_sink + w.n_tail
+    cases = [(3000, 29, 0), (2500, 24, 1), (1800, 18, 64), (2200, 0, 70), (2600, 40, max_gen), (A - 5, 3, 33)]
+    layers = []
+    for i, (L, k, ng) in enumerate(cases):
+        P = I.make_layer(w, L=L + ng, seq=i)
+        P["L"], P["n_gen"] = L, ng
+        if d_emb:
+            P["mlp"] = I.make_mlp_phi(w, layer=i, d_emb=d_emb)
+        layers.append(P)
+    ks = [k for _, k, _ in cases]
+    b = H.Batch(H.config_of(w, d_emb=d_emb, max_gen=max_gen), layers, ks, debug=True)
+    b.build()
+    heads = sorted({0, w.n_q_heads // 2, w.n_q_heads - 1})
+    for mode, flag in (("sub", B.TKPHI_MODE_SUB), ("nosub", B.TKPHI_MODE_NOSUB), ("topk", B.TKPHI_MODE_TOPK_ONLY)):
+        b.decode(flag)
+        assert b.status() == 0
+        for i, (P, kk) in enumerate(zip(layers, ks)):
+            rep = PU.check_layer(w, P, kk, b, i, heads=heads, mode=mode)
+        print("generated tokens", shape, mode, rep, flush=True)
+    b.decode(B.TKPHI_MODE_SUB | B.TKPHI_FLAG_DIAG)
+    for i in (1, 4):
+        _check_diag(w, layers[i], ks[i], b, i, heads=heads)
+    # the same rows as a longer tail: n_tail' = n_tail + n_gen on a prefill of L + n_gen rows
+    L, k, ng = cases[2]
+    w2 = dataclasses.replace(w, n_tail=w.n_tail + ng)
+    P2 = dict(layers[2]); P2["L"], P2["n_gen"] = L + ng, 0
+    b2 = H.Batch(H.config_of(w2, d_emb=d_emb), [P2], [k], debug=True)
+    b2.build(); b2.decode()
+    b.decode()
+    d1, d2 = b.result(2, "out").astype(np.float64), b2.result(0, "out").astype(np.float64)
+    assert np.abs(d1 - d2).max() <= 2e-6 * max(1.0, np.abs(d2).max()), np.abs(d1 - d2).max()
+    assert np.array_equal(b.result(2, "topk_idx")[:, :k], b2.result(0, "topk_idx")[:, :k])
