@@ -18,12 +18,16 @@
  *                                     Top-K over the mid-region M, and the residual
  *                                     read from (S_M, u_M) minus the retrieved
  *                                     tokens' feature contributions
- *                                     (eq. (subtraction)).
+ *                                     (eq. (subtraction)); already generated tokens
+ *                                     are one more exact branch under the same
+ *                                     normalisation (eq. (implemented_decode)).
  *
- * Everything runs in hand-written HIP kernels enqueued on the caller's stream.  The
- * library owns no device memory: every buffer, including scratch ("workspace"), is
- * allocated by the caller.  Calls only enqueue work; they never synchronise the
- * stream and never copy device data to the host (tkphi_read_device_status excepted).
+ * Everything runs in hand-written HIP kernels enqueued on the caller's stream (with the
+ * MLP feature maps, decode also uses one stream of the library's own per device, forked
+ * from and joined to the caller's: see tkphi_phi_kind).  The library owns no device
+ * memory: every buffer, including scratch ("workspace"), is allocated by the caller.
+ * Calls only enqueue work; they never synchronise the stream and never copy device data
+ * to the host (tkphi_read_device_status and tkphi_decode_stage_times excepted).
  *
  * Pointer kinds.  Unless a parameter is marked HOST, pointers are DEVICE pointers.
  * The tkphi_config struct itself and the outermost arguments are read on the host
@@ -221,8 +225,10 @@ size_t tkphi_workspace_bytes(const tkphi_config* cfg /*HOST*/, int32_t n_problem
 /* Prefill: for every problem and KV head, S = sum_{i in M} phi_k(k_i) v_i^T and
  * u = sum_{i in M} phi_k(k_i) over the mid-region M = [n_sink, L - n_tail)
  * (eq. (natural_cache)); feature-major S[h][j][c] (j feature, c value channel).
- * Reads K, V, Wk, bk, L; writes S, u (fully overwritten; zeros if M is empty).
- * Deterministic: the same inputs give bit-identical S, u. */
+ * Reads K, V, L and Wk, bk (TKPHI_PHI_MLP: mlp_k instead); writes S, u (fully overwritten;
+ * zeros if M is empty) and, with cfg.cache_features, phi_cache (the features of the mid
+ * tokens, exactly the values that were contracted).  Rows past L (generated tokens) are
+ * not read.  Deterministic: the same inputs give bit-identical S, u. */
 tkphi_status tkphi_build_summaries(const tkphi_config* cfg /*HOST*/,
                                    const tkphi_problem* problems /*DEVICE table*/,
                                    int32_t n_problems, int32_t max_L,
@@ -233,10 +239,12 @@ tkphi_status tkphi_build_summaries(const tkphi_config* cfg /*HOST*/,
  * the K highest-scoring mid tokens (ties to the lower index), accumulates the exact
  * max-shifted terms over anchors + retrieved tokens, evaluates the residual from
  * (S, u) with the retrieved tokens' features subtracted, and merges under one
- * normalisation (eq. (exact_terms), eq. (subtraction), eq. (hybrid_merge)).
- * Reads q, K, V, Wq, bq, Wk, bk, S, u, L, topk; writes out (and topk_idx, aux, scores
- * when non-NULL).  If L <= n_sink + n_tail the mid-region is empty and the result is
- * dense attention over all L tokens.  Deterministic for fixed inputs. */
+ * normalisation (eq. (exact_terms), eq. (subtraction), eq. (hybrid_merge)); the n_gen
+ * generated tokens after the prefill rows are added as exact terms (eq. (implemented_decode)).
+ * Reads q, K, V, Wq, bq, Wk, bk, S, u, L, topk, n_gen (with cfg.cache_features phi_cache
+ * instead of Wk, bk; TKPHI_PHI_MLP: mlp_q instead of Wq, bq); writes out (and topk_idx,
+ * aux, scores, diag when non-NULL).  If L <= n_sink + n_tail the mid-region is empty and
+ * the result is dense attention over all L + n_gen tokens.  Deterministic for fixed inputs. */
 tkphi_status tkphi_decode(const tkphi_config* cfg /*HOST*/,
                           const tkphi_problem* problems /*DEVICE table*/,
                           int32_t n_problems, int32_t max_L, int32_t max_K,
@@ -261,7 +269,8 @@ tkphi_status tkphi_decode_stage_times(const tkphi_config* cfg /*HOST*/,
                                       void* hip_stream, float* stage_ms_out /*HOST*/);
 
 /* Validates a HOST copy of a problem table against cfg and the launch bounds: non-null
- * required pointers, alignment, strides, 1 <= L <= max_L, 0 <= topk <= max_K.
+ * required pointers, alignment, strides, 1 <= L <= max_L, 0 <= topk <= max_K,
+ * 0 <= n_gen <= cfg.max_gen.
  * for_decode != 0 additionally requires q and out.  Pure host code. */
 tkphi_status tkphi_check_problems(const tkphi_config* cfg /*HOST*/,
                                   const tkphi_problem* problems_host /*HOST*/,
