@@ -96,7 +96,9 @@ typedef enum tkphi_mode { TKPHI_MODE_SUB = 0, TKPHI_MODE_NOSUB = 1, TKPHI_MODE_T
  *               on first use (default priority, kept until the process ends): forked from the
  *               caller's stream at the start of the call and joined to it before the gather, so
  *               the caller still sees one in-order unit of work; such calls serialise on a
- *               mutex while they enqueue. */
+ *               mutex while they enqueue.  The device of hip_stream must be the current device;
+ *               a caller that captures decode calls into a HIP graph makes one call outside the
+ *               capture first (the stream and its two events are created then). */
 typedef enum tkphi_phi_kind { TKPHI_PHI_EXP_AFFINE = 0, TKPHI_PHI_MLP = 1 } tkphi_phi_kind;
 
 /* One head's MLP feature map.  DEVICE struct (arrays of it live in device memory); weights are
