@@ -490,7 +490,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
                                                          char* __restrict__ ws, int mode) {
   __shared__ float red_f[4];
   __shared__ float sh_phiq[kMaxDim], sh_u[kMaxDim];
-  __shared__ float sh_grp[8][128];                 // [feature group][value channel]
+  __shared__ float sh_grp[9][128];                 // [feature group][value channel]; row 8: scalars of the partial combine
   const int gq = blockIdx.x, p = blockIdx.y, tid = threadIdx.x;
   const tkphi_problem pr = probs[p];
   if (pr.L < 1 || pr.L > g.max_L) return;
@@ -543,18 +543,20 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
   if (empty_E) m = 0.f;
 
   // ---- combine the partials in a fixed order ---------------------------------------------------
+  // kThreads / d thread groups (2 for d = 128, 4 for d = 64) take the batches of UN partials round-robin,
+  // thread c of a group one value channel; the group sums are then added in group order.
   float nu = 0.f, zv = 0.f, Z = 0.f, zsum = 0.f;
   float ZA = 0.f;                        // anchor share of Z (diagnostics only)
-  const int c = tid;
-  constexpr int UN = 8;
-  for (int t0 = 0; t0 < n_parts; t0 += UN) {
+  const int NGRP = kThreads / d, grp = tid / d, c = tid % d;
+  constexpr int UN = 16;
+  for (int t0 = grp * UN; t0 < n_parts; t0 += NGRP * UN) {
     float hm[UN], hz[UN], hs[UN], vn[UN], vz[UN];
 #pragma unroll
     for (int k = 0; k < UN; ++k) {
       const float* pp = part_ptr(min(t0 + k, n_parts - 1));
       hm[k] = pp[0]; hz[k] = pp[1]; hs[k] = pp[2];
-      vn[k] = c < d ? pp[4 + c] : 0.f;
-      vz[k] = c < d ? pp[4 + d + c] : 0.f;
+      vn[k] = pp[4 + c];
+      vz[k] = pp[4 + d + c];
     }
 #pragma unroll
     for (int k = 0; k < UN; ++k) {
@@ -567,6 +569,21 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
         zv += vz[k];
       }
     }
+  }
+  {
+    // sh_grp is free until the residual sums below: [0] nu, [1] zv per (group, channel); [2] Z, zsum, ZA per group
+    float* cmb = &sh_grp[0][0];
+    __syncthreads();
+    cmb[grp * 128 + c] = nu;
+    cmb[512 + grp * 128 + c] = zv;
+    if (c == 0) { cmb[1024 + grp * 4 + 0] = Z; cmb[1024 + grp * 4 + 1] = zsum; cmb[1024 + grp * 4 + 2] = ZA; }
+    __syncthreads();
+    nu = 0.f; zv = 0.f; Z = 0.f; zsum = 0.f; ZA = 0.f;
+    for (int q = 0; q < NGRP; ++q) {
+      nu += cmb[q * 128 + c]; zv += cmb[512 + q * 128 + c];
+      Z += cmb[1024 + q * 4 + 0]; zsum += cmb[1024 + q * 4 + 1]; ZA += cmb[1024 + q * 4 + 2];
+    }
+    __syncthreads();                               // before sh_grp is reused
   }
 
   // (with every mid token retrieved in SUB mode the residual set is empty: exactly zero)
@@ -601,11 +618,11 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
   const float ms = fmaxf(m, 0.f);
   const float eE = __expf(m - ms), eR = __expf(-ms);
   const float den = eE * Z + eR * ZR;
-  if (c < d) pr.out[(size_t)gq * d + c] = (eE * nu + eR * nuR) / den;
+  if (tid < d) pr.out[(size_t)gq * d + c] = (eE * nu + eR * nuR) / den;
   if (pr.aux) {
     float* ax = pr.aux + (size_t)gq * TKPHI_AUX_STRIDE(d);
     if (tid == 0) { ax[0] = m; ax[1] = Z; ax[2] = ZR; ax[3] = clamped ? 1.f : 0.f; }
-    if (c < d) { ax[4 + c] = nu; ax[4 + d + c] = nuR; }
+    if (tid < d) { ax[4 + c] = nu; ax[4 + d + c] = nuR; }
   }
   if (clamped && tid == 0) atomicOr((uint32_t*)(ws + g.off_status), TKPHI_DEV_CLAMPED);
 

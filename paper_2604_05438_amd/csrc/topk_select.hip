@@ -327,8 +327,9 @@ __global__ __launch_bounds__(kThreads) void select_emit_kernel(Geom g, const tkp
 // ------------------------------------------------------------------------------------
 // resolve: grid (split, Hq, n_problems), 1024 threads; dynamic LDS: kCandCap x 8 bytes
 //
-// Up to kCountMax boundary-bin candidates (the usual case): the `split` workgroups of a
-// head share the work.  Each one stages all candidates (as 64-bit composites) in LDS and ranks
+// Boundary-bin candidates that fit the LDS stage and whose rank counting is short enough for the
+// workgroups at hand (rounds of 128 candidates x nb <= kCountWork: 1024 candidates for one workgroup
+// per head, all kCandCap = 4096 for 16): the `split` workgroups of a head share the work.  Each one stages all candidates (as 64-bit composites) in LDS and ranks
 // its own slice by counting the larger ones, 8 lanes per candidate; a candidate of rank
 // r < K_rem goes to list position c_hi + r, so the winners follow the tokens above b* in
 // descending (score, then ascending index) order and no scan is needed.  More candidates:
@@ -336,7 +337,7 @@ __global__ __launch_bounds__(kThreads) void select_emit_kernel(Geom g, const tkp
 // they exceeded kCandCap) and appends the winners in ascending index order.
 // ------------------------------------------------------------------------------------
 constexpr int kResolveSplitMax = 16;      // workgroups per head when few heads are in flight
-constexpr int kCountMax = 1024;
+constexpr int kCountWork = 16384;
 
 __global__ __launch_bounds__(kSelThreads) void select_resolve_kernel(Geom g, const tkphi_problem* __restrict__ probs,
                                                                      char* __restrict__ ws) {
@@ -354,7 +355,9 @@ __global__ __launch_bounds__(kSelThreads) void select_resolve_kernel(Geom g, con
   const SelPlan plan = ((const SelPlan*)(blk + g.off_plan))[gq];
   const int bstar = plan.bstar, krem = plan.krem, c_hi = plan.c_hi, nb = plan.nb, Ksel = plan.n_sel;
   if (bstar < 0 || Ksel == 0) return;
-  if (nb > kCountMax && part != 0) return;
+  const int per = (nb + (int)gridDim.x - 1) / (int)gridDim.x;         // candidates per workgroup when they are counted
+  const bool count_path = nb <= kCandCap && ((per + kSelThreads / 8 - 1) / (kSelThreads / 8)) * nb <= kCountWork;
+  if (!count_path && part != 0) return;
   const float* scores = (const float*)(blk + g.off_scores) + (size_t)gq * g.mid_stride;
   int32_t* sel_idx = (int32_t*)(blk + g.off_selidx) + (size_t)gq * g.max_K;
   float* sel_score = (float*)(blk + g.off_selscore) + (size_t)gq * g.max_K;
@@ -365,8 +368,7 @@ __global__ __launch_bounds__(kSelThreads) void select_resolve_kernel(Geom g, con
     const uint2* cand = (const uint2*)(blk + g.off_cand) + (size_t)gq * kCandCap;
     for (int j = tid; j < nb; j += kSelThreads) { const uint2 e = cand[j]; sh_comp[j] = composite(e.x, e.y); }
     __syncthreads();
-    if (nb <= kCountMax) {
-      const int per = (nb + (int)gridDim.x - 1) / (int)gridDim.x;     // candidates of this workgroup
+    if (count_path) {
       const int sub = tid & 7, slot = tid >> 3;                       // 8 lanes per candidate, 128 slots
       for (int k0 = 0; k0 < per; k0 += kSelThreads / 8) {
         const int k = k0 + slot, j = part * per + k;
