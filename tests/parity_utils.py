@@ -4,8 +4,8 @@ Tolerances (the bar the path is held to):
   * scores            |gpu - oracle| <= 1e-5 * max(1, |oracle|)
   * Top-K index sets  identical, except that tokens may be exchanged across the selection
                       boundary when their oracle scores lie within 1e-5 * max(1, |s_K|) of
-                      the K-th score s_K; when that happens the output is also checked
-                      against the oracle re-run on the GPU's set
+                      the K-th score s_K; when that happens the output (and the unnormalised
+                      terms) are checked against the oracle re-run on the GPU's set
   * outputs y         max-abs <= 2e-3 and relative l1 <= 1e-2 per query head
   * summaries S, u    fp32 storage: relative Frobenius error <= 2e-5.  bf16 storage (matrix-core
                       path, features carried as a bf16 hi + lo pair): element-wise
@@ -160,13 +160,15 @@ def check_layer(w, P, k, batch, i, heads=None, sum_tol=None, mode="sub", check_a
         if n_mid > 0:
             check_scores(sc[g], r, w.n_sink, n_mid)
         exact = check_index_set(idx[g], r, w.n_sink, n_mid)
-        a, b = check_output(y[g], r[key], f"head {g} {key}")
-        worst = (max(worst[0], a), max(worst[1], b))
         if not exact:
+            # admissible swaps of (near-)tied tokens at the selection boundary: both sets are correct
+            # selections; the output is unique only given the set, so it is compared with the oracle
+            # run on the GPU's set (tied tokens can carry large weights, e.g. planted needles at K = 1)
             n_swapped += 1
             forced = {g: idx[g][: r["idx"].size].astype(np.int64)}
-            r2 = oracle_layer(w, P, k, heads=[g], S=S_or, u=u_or, retrieved=forced)[0][0]
-            check_output(y[g], r2[key], f"head {g} {key} (oracle on the GPU's set)")
+            r = oracle_layer(w, P, k, heads=[g], S=S_or, u=u_or, retrieved=forced)[0][0]
+        a, b = check_output(y[g], r[key], f"head {g} {key}" + ("" if exact else " (oracle on the GPU's set)"))
+        worst = (max(worst[0], a), max(worst[1], b))
         if check_aux:
             m = float(aux[g, 0])
             n_gen = int(P.get("n_gen", 0))            # generated tokens count with the exact support
