@@ -182,6 +182,8 @@ def check_layer(w, P, k, batch, i, heads=None, sum_tol=None, mode="sub", check_a
             assert aux[g, 3] == 0.0, f"head {g}: residual clamp fired"
             if mode == "sub" and n_mid > r["idx"].size:
                 # the residual denominator (unshifted) against the oracle's
-                assert abs(aux[g, 2] - r["Z_R_hat"]) <= 5e-3 * r["Z_R_hat"], \
-                    f"head {g}: Z_R_hat {aux[g, 2]} vs {r['Z_R_hat']}"
+                # (a difference of two fp32 sums of size Z_M_hat: with nearly every mid token retrieved the
+                # small remainder carries their rounding, ~1e-6 Z_M_hat)
+                assert abs(aux[g, 2] - r["Z_R_hat"]) <= 5e-3 * r["Z_R_hat"] + 1e-5 * r["Z_M_hat"], \
+                    f"head {g}: Z_R_hat {aux[g, 2]} vs {r['Z_R_hat']} (Z_M_hat {r['Z_M_hat']})"
     return {"max_abs": worst[0], "rel_l1": worst[1], "swapped_heads": n_swapped}

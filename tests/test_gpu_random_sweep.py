@@ -1,5 +1,5 @@
 """GPU parity on seeded random configurations: shapes, anchor sizes, ragged batches, budgets from 0
-to an eighth of the mid-region, accounting modes, the feature cache, the MLP maps and generated
+to the whole mid-region, accounting modes, the feature cache, the MLP maps and generated
 tokens in random combination.  Complements the hand-picked cases of the other GPU tests."""
 import dataclasses
 
@@ -27,10 +27,12 @@ def test_random_configurations(seed):
         d_emb = int(rng.choice([0, 0, 0, 128])) if w.dtype == "bf16" else 0
         layers, ks = [], []
         for i in range(int(rng.integers(1, 5))):
-            L = int(rng.choice([rng.integers(1, 200), rng.integers(200, 3000), rng.integers(3000, 12000)]))
+            L = int(rng.choice([rng.integers(1, 200), rng.integers(200, 3000), rng.integers(3000, 12000),
+                                rng.integers(12000, 40000)], p=[0.3, 0.4, 0.25, 0.05]))
             ng = int(rng.integers(0, max_gen + 1)) if max_gen else 0
             n_mid = max(0, L - w.n_sink - w.n_tail)
-            k = int(rng.choice([0, 1, rng.integers(0, max(2, n_mid // 50 + 2)), rng.integers(0, max(2, n_mid // 8 + 2))]))
+            k = int(rng.choice([0, 1, rng.integers(0, max(2, n_mid // 50 + 2)), rng.integers(0, max(2, n_mid // 8 + 2)),
+                                rng.integers(0, n_mid + 10), n_mid], p=[0.2, 0.2, 0.3, 0.2, 0.05, 0.05]))
             P = I.make_layer(w, L=L + ng, seq=i, layer=int(rng.integers(0, 100)))
             P["L"], P["n_gen"] = L, ng
             if d_emb:
