@@ -11,7 +11,7 @@ from paper_2604_05438_amd import inputs as I
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("seed", [11, 12, 13])
+@pytest.mark.parametrize("seed", [11, 12, 13, 14])
 def test_random_configurations(seed):
     import parity_utils as PU
     from paper_2604_05438_amd import binding as B
@@ -22,9 +22,12 @@ def test_random_configurations(seed):
         w = I.WORKLOADS[str(rng.choice(["l1b_32k", "l3b_128k", "tiny_f32"]))]
         if rng.random() < 0.3:
             w = dataclasses.replace(w, n_sink=int(rng.integers(0, 9)), n_tail=int(rng.integers(0, 130)), name=w.name + "_a")
+        if seed % 2 == 0 and rng.random() < 0.6:        # feature widths and GQA ratios off the tuned shapes
+            w = dataclasses.replace(w, d_phi=int(rng.choice([16, 48, 64, 96, 128, 192, 256])), name=w.name + "_p",
+                                    n_q_heads=int(w.n_kv_heads * rng.choice([1, 2, 4])) if w.n_kv_heads > 1 else w.n_q_heads)
         cache = bool(rng.random() < 0.3)
         max_gen = int(rng.choice([0, 0, 17, 100]))
-        d_emb = int(rng.choice([0, 0, 0, 128])) if w.dtype == "bf16" else 0
+        d_emb = int(rng.choice([0, 0, 0, 128] if seed % 2 else [0, 0, 64, 128, 256])) if w.dtype == "bf16" else 0
         layers, ks = [], []
         for i in range(int(rng.integers(1, 5))):
             L = int(rng.choice([rng.integers(1, 200), rng.integers(200, 3000), rng.integers(3000, 12000),
@@ -40,7 +43,7 @@ def test_random_configurations(seed):
             layers.append(P)
             ks.append(k)
         mode = str(rng.choice(["sub", "sub", "nosub", "topk"]))
-        print(f"seed {seed} case {case}: {w.name} sink={w.n_sink} tail={w.n_tail} cache={cache} d_emb={d_emb} "
+        print(f"seed {seed} case {case}: {w.name} Hq={w.n_q_heads} d_phi={w.d_phi} sink={w.n_sink} tail={w.n_tail} cache={cache} d_emb={d_emb} "
               f"max_gen={max_gen} mode={mode} " + " ".join(f"(L={int(P['L'])},g={P['n_gen']},k={k})" for P, k in zip(layers, ks)),
               flush=True)
         b = H.Batch(H.config_of(w, cache_features=cache, d_emb=d_emb, max_gen=max_gen), layers, ks, debug=True)
