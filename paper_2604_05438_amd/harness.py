@@ -94,6 +94,14 @@ class Batch:
         raw = bytearray(bytes(memoryview(self.host_table).cast("B")))
         self.table.copy_(torch.frombuffer(raw, dtype=torch.uint8))
 
+    def set_n_gen(self, i: int, n_gen: int) -> None:
+        """Changes the number of generated tokens of problem i (<= cfg.max_gen; the rows must already be
+        in its K, V buffers) and re-uploads the table."""
+        assert 0 <= n_gen <= self.cfg.max_gen
+        self.host_table[i].n_gen = int(n_gen)
+        raw = bytearray(bytes(memoryview(self.host_table).cast("B")))
+        self.table.copy_(torch.frombuffer(raw, dtype=torch.uint8))
+
     def set_query(self, i: int, q: np.ndarray) -> None:
         self.dev[i]["q"].copy_(to_device(q, self.device))
 

@@ -26,7 +26,12 @@ SWAP_TOL = 1e-5
 
 
 def oracle_inputs(P: dict) -> dict:
-    return {k: I.to_f64(P[k]) for k in ("q", "K", "V", "Wq", "Wk", "bq", "bk")}
+    """float64 copies of a layer's tensors; K, V cut to the rows the problem uses (prefill length P["L"] plus
+    P["n_gen"] generated tokens: the buffers may hold rows of later steps)."""
+    O = {k: I.to_f64(P[k]) for k in ("q", "K", "V", "Wq", "Wk", "bq", "bk")}
+    rows = int(P["L"]) + int(P.get("n_gen", 0))
+    O["K"], O["V"] = O["K"][:, :rows], O["V"][:, :rows]
+    return O
 
 
 def mlp_feature_fns(P: dict):

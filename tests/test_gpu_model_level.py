@@ -132,3 +132,34 @@ def test_model_build_then_64_queries():
             for g in (1, 22):
                 _check_topk_property(w, w.L, k, idx[g], sc[g])
     print("model-level: 28 layers x 64 queries, worst sampled max_abs", worst)
+
+
+def test_decode_loop_with_growing_generated_prefix():
+    """A decode loop as a caller runs it: summaries built once over the prefill, then eight steps,
+    each with a new query and one more generated token after the prefill rows (the rows are in
+    the K/V buffers from the start; only n_gen in the problem table and q change).  Every step is
+    compared with the oracle's eq. (implemented_decode) on the same rows."""
+    import parity_utils as PU
+    from paper_2604_05438_amd import harness as H
+    w = I.WORKLOADS["l1b_32k"]
+    L, steps, k = 6000, 8, 59
+    P = I.make_layer(w, L=L + steps)
+    P["L"], P["n_gen"] = L, 0
+    b = H.Batch(H.config_of(w, max_gen=steps), [P], [k], debug=True)
+    b.build()
+    S0, u0 = b.result(0, "S").copy(), b.result(0, "u").copy()
+    summaries = None
+    for t in range(steps + 1):
+        q = I.make_layer(w, L=L + steps, query_index=t, with_kv=False)["q"]
+        P["q"], P["n_gen"] = q, t
+        b.set_query(0, q)
+        b.set_n_gen(0, t)
+        b.decode()
+        assert b.status() == 0
+        if summaries is None:
+            _, S_or, u_or, _ = PU.oracle_layer(w, P, k, heads=[0])
+            summaries = (S_or, u_or)
+            PU.check_layer(w, P, k, b, 0, heads=[0, 17, 31])                    # also checks S, u once
+        else:
+            PU.check_layer(w, P, k, b, 0, heads=[0, 17, 31], summaries=summaries)
+    assert np.array_equal(S0, b.result(0, "S")) and np.array_equal(u0, b.result(0, "u"))   # decode never writes them
