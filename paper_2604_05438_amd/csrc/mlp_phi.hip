@@ -3,16 +3,19 @@
 // evaluated for the keys of the mid-region at build time, and the summary contraction
 // S = Phi^T V, u = sum Phi (eq. (natural_cache)) from the stored features.
 //
-// Keys: launches of one tiled matrix-core GEMM per block of Geom::mlp_block tokens
+// Keys: every 64-token tile runs the chain
 //   stem  G = X Ws^T + bs            (X = bf16 key rows: exact, single MFMA pass)
 //   hid   H = GeLU(G W1^T + b1)
 //   res   G = G + alpha (H W2^T + b2)    (in place: a tile reads only its own G entries)
-//         [res and out run as one launch when the widths allow: g1 then stays on chip]
 //   out   Phi = exp(G Wo^T + bo)     -> tkphi_problem::phi_cache
+// with one tiled matrix-core GEMM (mlp_gemm_tile).  A tile's layers depend only on the tile's own
+// rows: by default one persistent launch per problem takes each workgroup's tiles through stem,
+// hid and res + out (g1 stays on chip); widths that do not fuse run the layers as separate launches
+// per block of Geom::mlp_block tokens.
 // Activations are fp32 in the workspace; as MFMA operands they are split into a bf16 hi + lo
 // pair (16 significant bits, two MFMAs per product), weights are bf16 as stored, accumulation
-// is fp32.  With ~1.3 MFLOP per token and KV head against ~14 KB of activation traffic the
-// chain is bound by the matrix cores, not by HBM.
+// is fp32.  With ~1.3 MFLOP per token and KV head against 256 bytes of key the chain is bound by
+// the matrix cores, not by HBM.
 #include <algorithm>
 #include <cstdlib>
 #include <cstring>
@@ -67,8 +70,8 @@ __global__ __launch_bounds__(kThreads) void mlp_pack_weights_kernel(Geom g, cons
 }
 
 // ------------------------------------------------------------------------------------
-// grid (Hkv * mlp_block / 64, ceil(Nout / (64 NT))), 256 threads: a 64-token x (64 NT)-output tile
-// of KV head blockIdx.x % Hkv (workgroups go to the 8 XCDs round-robin by linear index, so with 8 KV
+// The tile GEMM: 256 threads, a 64-token x (64 NT)-output tile of one KV head (the launchers give
+// workgroup i the head i % Hkv: workgroups go to the 8 XCDs round-robin by linear index, so with 8 KV
 // heads each XCD's L2 holds the weights of one head instead of all of them);
 // wavefront w owns the outputs [16 NT w, 16 NT (w + 1)) (NT MFMA column tiles) of all four
 // 16-token row tiles, so an A fragment read from LDS feeds NT (x2: hi, lo) MFMAs.  With NT = 8
