@@ -184,8 +184,12 @@ def check_layer(w, P, k, batch, i, heads=None, sum_tol=None, mode="sub", check_a
             assert abs(aux[g, 1] - Z_or) <= 1e-4 * Z_or + 1e-30, f"head {g}: Z_E {aux[g, 1]} vs {Z_or}"
             nu_or = (r["nu_E"] + r["nu_G"]) * np.exp(-m_or)
             assert np.abs(aux[g, 4:4 + d] - nu_or).max() <= 1e-4 * max(np.abs(nu_or).max(), 1e-30) + 1e-6
-            assert aux[g, 3] == 0.0, f"head {g}: residual clamp fired"
-            if mode == "sub" and n_mid > r["idx"].size:
+            # the numerical clamp (residual denominator <= 0 after the subtraction) may only fire where the
+            # true remainder is below the rounding of the two fp32 sums it is the difference of
+            clamped = aux[g, 3] != 0.0
+            assert not clamped or (mode == "sub" and r["Z_R_hat"] <= 1e-5 * r["Z_M_hat"]), \
+                f"head {g}: residual clamp fired (Z_R_hat {r['Z_R_hat']}, Z_M_hat {r['Z_M_hat']})"
+            if mode == "sub" and n_mid > r["idx"].size and not clamped:
                 # the residual denominator (unshifted) against the oracle's
                 # (a difference of two fp32 sums of size Z_M_hat: with nearly every mid token retrieved the
                 # small remainder carries their rounding, ~1e-6 Z_M_hat)
