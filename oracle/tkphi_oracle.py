@@ -29,9 +29,11 @@ softmax, subtraction against brute force over unretrieved tokens, positivity,
 brute-force Top-K with ties, subset-bias identity, exact-subtraction identity,
 partition sums, constant-feature closed form, q = 0 special case, random
 feature convergence to exp(q.k/sqrt d), the paper's K = 21/144/636 worked
-example, K = 0; entropy / mass-recovery diagnostics against closed forms; the MLP feature map
-against the printed per-head parameter counts, its alpha = 0 and W1 = 0 reductions and GeLU's
-defining values.  Parity unpinned: nothing in this file; the *quality* of the
+example, K = 0; entropy / mass-recovery diagnostics against closed forms; the residual
+denominator share rho_res, the residual log-partition error and the boundary gap against the
+constant-feature closed form (Z_R^ = |R|) and scalar loops over the token classes, with and
+without generated tokens; the MLP feature map against the printed per-head parameter counts,
+its alpha = 0 and W1 = 0 reductions and GeLU's defining values.  Parity unpinned: nothing in this file; the *quality* of the
 estimate for the synthetic random-feature phi has no published value and is
 reported as a diagnostic only.
 """

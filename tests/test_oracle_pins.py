@@ -463,3 +463,67 @@ def test_generated_tokens_are_one_more_exact_branch():
     rz, _, _ = _run(Pz, 11)
     rz0, _, _ = _run(Pz, 11, n_gen=0)                                             # (d)
     assert all(np.array_equal(x["y"], y["y"]) and x["Z_G"] == 0.0 for x, y in zip(rz0, rz))
+
+
+# --- residual-denominator share and residual log-partition error ------------------------------
+def test_residual_share_and_log_partition_error_closed_forms():
+    """rho_res = Z_R^ / (Z_E + Z_R^) (App. "Entropy, mass recovery, and residual-denominator
+    diagnostics") and the residual log-partition error log Z_R^ - log Z_R (Sec. "Analysis: validating
+    residual accounting"), pinned by routes that do not use the oracle's expressions:
+    (a) the constant feature map (W = 0, c = 0, b = -0.5 ln d_phi, so z = 1 for every pair) makes
+        Z_R^ = |R| exactly; with q = 0 every exp(s_i) = 1, so Z_E = |A| + K, Z_G = n_gen, Z_R = |R|:
+        rho_res = |R| / (|A| + K + n_gen + |R|) and the log error is 0, with and without generated tokens;
+    (b) the same map with a random query: Z_R^ = |R| still, the exact masses come from explicit loops;
+    (c) a general random problem with n_gen > 0, every term by scalar loops over the token classes;
+    (d) the boundary gap is the difference between the K-th and (K+1)-th largest mid score."""
+    rng = np.random.default_rng(33)
+    d, dphi, n_sink, n_tail = 8, 16, 3, 5
+    W0 = np.zeros((dphi, d)); b0 = np.full(dphi, -0.5 * math.log(dphi))
+    for n_gen in (0, 6):
+        L, k = 150, 13
+        K = rng.standard_normal((L + n_gen, d)); V = rng.standard_normal((L + n_gen, d))
+        S, u = orc.build_summaries(K[None], V[None], W0[None], b0[None], 0.5, 0.0, n_sink, n_tail, n_gen=n_gen)
+        n_mid = L - n_sink - n_tail
+        nR = n_mid - k
+        # (a) q = 0
+        r = orc.decode_head(np.zeros(d), K, V, S[0], u[0], W0, b0, W0, b0, 0.5, 0.0, 0.35, n_sink, n_tail, k, n_gen=n_gen)
+        assert abs(r["rho_res"] - nR / (n_sink + n_tail + k + n_gen + nR)) < 1e-13
+        assert abs(r["log_Z_err"]) < 1e-12
+        # (b) random q: the estimate stays |R|, the exact side by loops
+        q = rng.standard_normal(d)
+        r = orc.decode_head(q, K, V, S[0], u[0], W0, b0, W0, b0, 0.5, 0.0, 0.35, n_sink, n_tail, k, n_gen=n_gen)
+        s = [0.35 * float(np.dot(q, K[i])) for i in range(L + n_gen)]
+        mid = list(range(n_sink, L - n_tail))
+        sel = sorted(mid, key=lambda i: (-s[i], i))[:k]
+        Z_exact = sum(math.exp(s[i]) for i in range(L + n_gen) if i < n_sink or i >= L - n_tail or i in sel)
+        Z_R = sum(math.exp(s[i]) for i in mid if i not in sel)
+        assert abs(r["rho_res"] - nR / (Z_exact + nR)) < 1e-12
+        assert abs(r["log_Z_err"] - (math.log(nR) - math.log(Z_R))) < 1e-12
+    # (c) general maps, generated tokens, scalar loops
+    P = _rand_problem(np.random.default_rng(34), L=120)
+    n_gen, k = 7, 9
+    L = 120 - n_gen
+    S, u = orc.build_summaries(P["K"], P["V"], P["Wk"], P["bk"], P["a"], P["c"], P["n_sink"], P["n_tail"], n_gen=n_gen)
+    res = orc.decode_layer(P["q"], P["K"], P["V"], S, u, P["Wq"], P["bq"], P["Wk"], P["bk"], P["a"], P["c"], P["scale"],
+                           P["n_sink"], P["n_tail"], k, n_gen=n_gen)
+    for g, r in enumerate(res):
+        h = g // 2
+        q, Kh = P["q"][g], P["K"][h]
+        s = [P["scale"] * float(np.dot(q, Kh[i])) for i in range(L + n_gen)]
+        mid = list(range(P["n_sink"], L - P["n_tail"]))
+        sel = set(r["idx"].tolist())
+        pq = orc.phi(q, P["Wq"][g], P["bq"][g], P["a"], P["c"])[0]
+        Z_hat = 0.0                                    # estimate over the unretrieved mid tokens, one token at a time
+        Z_true = 0.0
+        for i in mid:
+            if i in sel:
+                continue
+            Z_hat += float(pq @ orc.phi(Kh[i], P["Wk"][h], P["bk"][h], P["a"], P["c"])[0])
+            Z_true += math.exp(s[i])
+        Z_exact = sum(math.exp(s[i]) for i in range(L + n_gen) if i not in mid or i in sel)
+        assert abs(r["rho_res"] - Z_hat / (Z_exact + Z_hat)) < 1e-12
+        assert abs(r["log_Z_err"] - (math.log(Z_hat) - math.log(Z_true))) < 1e-11
+        # (d)
+        ranked = sorted((s[i] for i in mid), reverse=True)
+        assert abs(r["boundary_gap"] - (ranked[k - 1] - ranked[k])) < 1e-15
+        assert r["boundary_gap"] >= 0.0
