@@ -39,8 +39,9 @@
  * tkphi_last_error() returns a thread-local detail string for the last failure.
  * Fields of the device-resident problem table cannot be seen by the host; kernels
  * clip topk to min(topk, |M|, max_K) and skip a problem whose L exceeds max_L (or is < 1),
- * recording TKPHI_DEV_BAD_LENGTH in the workspace status word.  tkphi_check_problems
- * validates a HOST copy of the table.
+ * recording TKPHI_DEV_BAD_LENGTH in the workspace status word (both tkphi_build_summaries and
+ * tkphi_decode rewrite the word on every call; the outputs of a skipped problem, S and u
+ * included, are left untouched).  tkphi_check_problems validates a HOST copy of the table.
  */
 #ifndef TKPHI_H_
 #define TKPHI_H_
@@ -116,6 +117,24 @@ typedef struct tkphi_mlp {
   int32_t reserved;      /* 0                */
 } tkphi_mlp;
 
+/* Launch-geometry overrides: for tests that must reach a particular kernel variant at small
+ * sizes, and for tuning sweeps.  Every field 0 = the library's own choice (what production callers
+ * pass).  Part of tkphi_config, so tkphi_workspace_bytes, tkphi_build_summaries and tkphi_decode
+ * always see the same values; out-of-range values are rejected with TKPHI_EINVAL. */
+typedef struct tkphi_tuning {
+  int32_t force_generic;  /* 1: run the generic fp32-arithmetic kernels where the matrix-core ones apply  */
+  int32_t scan_chunk;     /* score_mid: mid tokens per workgroup (rounded up to the kernel's unit of
+                             256 / 512 rows, at most 32768); 0 = about 1024 workgroups per call           */
+  int32_t interleave;     /* score_mid chunk-to-row mapping: 1 = chunk c takes the units c, c + n_chunks,
+                             ..., 2 = one contiguous range per chunk; 0 = by the number of chunks         */
+  int32_t build_chunk;    /* summary build: mid tokens per workgroup (multiple of 64); 0 = auto          */
+  int32_t mlp_block;      /* MLP build, layer-wise launches: tokens per KV head held at once; 0 = auto   */
+  int32_t mlp_mode;       /* MLP build: 0 = one persistent launch where the widths allow it,
+                             1 = layer-wise launches per token block (residual + output fused),
+                             2 = all four layers as separate launches                                    */
+  int32_t reserved[6];    /* 0                                                                            */
+} tkphi_tuning;
+
 /* Fixed per model.  HOST struct.
  * The feature maps have the form phi(x) = exp(phi_in_scale * W x - phi_norm_coef * |x|^2 + b)
  * with per-head W, b (exponentiated affine output, App. "Head-wise phi architecture").
@@ -143,6 +162,7 @@ typedef struct tkphi_config {
   int32_t d_emb;         /* MLP only: internal width, a power of two in [64, 1024]          */
   int32_t max_gen;       /* upper bound of tkphi_problem::n_gen (generated tokens kept exact,
                             eq. (implemented_decode)); 0 if the feature is not used          */
+  tkphi_tuning tuning;   /* all zero = defaults                                             */
 } tkphi_config;
 
 /* Optional per-query-head diagnostics / unnormalised outputs written by tkphi_decode,

@@ -35,12 +35,24 @@ def aux_stride(d_head: int) -> int:
     return 4 + 2 * d_head
 
 
+class tkphi_tuning(C.Structure):
+    _fields_ = [
+        ("force_generic", C.c_int32), ("scan_chunk", C.c_int32), ("interleave", C.c_int32),
+        ("build_chunk", C.c_int32), ("mlp_block", C.c_int32), ("mlp_mode", C.c_int32),
+        ("reserved", C.c_int32 * 6),
+    ]
+
+
+MLP_MODES = {"": 0, "chain": 0, "blocks": 1, "unfused": 2}
+
+
 class tkphi_config(C.Structure):
     _fields_ = [
         ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("d_head", C.c_int32), ("d_phi", C.c_int32),
         ("n_sink", C.c_int32), ("n_tail", C.c_int32), ("kv_dtype", C.c_int32),
         ("score_scale", C.c_float), ("phi_in_scale", C.c_float), ("phi_norm_coef", C.c_float),
         ("cache_features", C.c_int32), ("phi_kind", C.c_int32), ("d_emb", C.c_int32), ("max_gen", C.c_int32),
+        ("tuning", tkphi_tuning),
     ]
 
 
@@ -172,10 +184,14 @@ def tkphi_read_device_status(workspace_ptr: int, stream: int) -> int:
 
 # ---- marshalling helpers (device memory via torch) -----------------------------------------
 def make_config(n_q_heads, n_kv_heads, d_head, d_phi, n_sink, n_tail, dtype, score_scale, phi_in_scale,
-                phi_norm_coef, cache_features=0, phi_kind=0, d_emb=0, max_gen=0) -> tkphi_config:
+                phi_norm_coef, cache_features=0, phi_kind=0, d_emb=0, max_gen=0, tuning=None) -> tkphi_config:
+    """tuning: optional dict of tkphi_tuning fields (launch-geometry overrides; omitted fields stay 0 = default)."""
     kv = {"bf16": TKPHI_BF16, "f32": TKPHI_F32}[dtype] if isinstance(dtype, str) else int(dtype)
-    return tkphi_config(n_q_heads, n_kv_heads, d_head, d_phi, n_sink, n_tail, kv, score_scale, phi_in_scale,
-                        phi_norm_coef, int(cache_features), int(phi_kind), int(d_emb), int(max_gen))
+    cfg = tkphi_config(n_q_heads, n_kv_heads, d_head, d_phi, n_sink, n_tail, kv, score_scale, phi_in_scale,
+                       phi_norm_coef, int(cache_features), int(phi_kind), int(d_emb), int(max_gen))
+    for name, value in (tuning or {}).items():
+        setattr(cfg.tuning, name, int(value))
+    return cfg
 
 
 def _ptr(t) -> int:

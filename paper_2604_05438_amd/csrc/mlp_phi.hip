@@ -17,8 +17,6 @@
 // is fp32.  With ~1.3 MFLOP per token and KV head against 256 bytes of key the chain is bound by
 // the matrix cores, not by HBM.
 #include <algorithm>
-#include <cstdlib>
-#include <cstring>
 
 #include "tkphi_internal.h"
 
@@ -403,9 +401,9 @@ static void launch_mlp_chain_nt(const Geom& g, const tkphi_problem* probs, char*
 void launch_mlp_features(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
   if (g.max_mid == 0) return;
   const size_t pieces = ((size_t)g.d_emb * g.d + (size_t)2 * g.d_emb * g.d_emb + (size_t)g.dphi * g.d_emb) / 8;
-  const char* mode = getenv("TKPHI_MLP_MODE");         // "blocks": layer-wise launches per token block; "unfused": also residual and output apart
-  const bool fusable = resout_fusable(g) && !(mode && !strcmp(mode, "unfused"));
-  const bool chain = fusable && !(mode && !strcmp(mode, "blocks"));
+  // tkphi_tuning::mlp_mode 1: layer-wise launches per token block; 2: also residual and output apart
+  const bool fusable = resout_fusable(g) && g.mlp_mode != 2;
+  const bool chain = fusable && g.mlp_mode != 1;
   for (int p = 0; p < g.n_problems; ++p) {
     hipLaunchKernelGGL(mlp_pack_weights_kernel, dim3((unsigned)((pieces + kThreads - 1) / kThreads), g.Hkv), dim3(kThreads), 0, s,
                        g, probs, ws, p);

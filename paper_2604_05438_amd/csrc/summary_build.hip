@@ -353,6 +353,7 @@ __global__ __launch_bounds__(kThreads) void build_reduce_kernel(Geom g, const tk
                                                                 char* __restrict__ ws) {
   __shared__ float4 sh[4][64];
   const int h = blockIdx.y, p = blockIdx.z;
+  if (blockIdx.x == 0 && h == 0 && p == 0) write_device_status(g, probs, ws, false);
   const int L = probs[p].L;
   if (L < 1 || L > g.max_L) return;
   const int n = mid_size(L, g.n_sink, g.n_tail);

@@ -3,7 +3,6 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
-#include <cstdlib>
 #include <cstring>
 #include <mutex>
 
@@ -23,12 +22,6 @@ void set_error(const char* fmt, ...) {
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
-
-static int env_int(const char* name, int dflt) {
-  const char* v = getenv(name);
-  if (!v || !*v) return dflt;
-  return atoi(v);
-}
 
 tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int max_K, Geom* g) {
   if (!cfg) { set_error("cfg is null"); return TKPHI_EINVAL; }
@@ -69,6 +62,16 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
     }
   }
   if (cfg->max_gen < 0 || cfg->max_gen > (1 << 20)) { set_error("max_gen=%d out of range [0, 2^20]", cfg->max_gen); return TKPHI_EINVAL; }
+  const tkphi_tuning& tn = cfg->tuning;
+  if (tn.force_generic < 0 || tn.force_generic > 1 || tn.scan_chunk < 0 || tn.scan_chunk > 32768 || tn.interleave < 0 ||
+      tn.interleave > 2 || tn.build_chunk < 0 || tn.build_chunk > (1 << 20) || tn.mlp_block < 0 || tn.mlp_block > 8192 ||
+      tn.mlp_mode < 0 || tn.mlp_mode > 2) {
+    set_error("tuning field out of range (force_generic=%d scan_chunk=%d interleave=%d build_chunk=%d mlp_block=%d mlp_mode=%d)",
+              tn.force_generic, tn.scan_chunk, tn.interleave, tn.build_chunk, tn.mlp_block, tn.mlp_mode);
+    return TKPHI_EINVAL;
+  }
+  for (int i = 0; i < 6; ++i)
+    if (tn.reserved[i] != 0) { set_error("tuning.reserved[%d] must be 0", i); return TKPHI_EINVAL; }
   if (n_problems > 65535) { set_error("n_problems=%d exceeds 65535", n_problems); return TKPHI_ESHAPE; }
   if (cfg->n_sink < 0 || cfg->n_tail < 0) {
     set_error("n_sink=%d n_tail=%d must be >= 0", cfg->n_sink, cfg->n_tail);
@@ -81,7 +84,8 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   g->cache = cfg->cache_features ? 1 : 0;
   g->phi_kind = cfg->phi_kind; g->d_emb = cfg->d_emb;
   g->max_gen = cfg->max_gen;
-  g->use_mfma = (cfg->kv_dtype == TKPHI_BF16 && cfg->d_phi == cfg->d_head && !env_int("TKPHI_FORCE_GENERIC", 0)) ? 1 : 0;
+  g->mlp_mode = tn.mlp_mode;
+  g->use_mfma = (cfg->kv_dtype == TKPHI_BF16 && cfg->d_phi == cfg->d_head && !tn.force_generic) ? 1 : 0;
   g->n_problems = n_problems; g->max_L = max_L;
   const int64_t mid = (int64_t)max_L - cfg->n_sink - cfg->n_tail;
   g->max_mid = (int)std::max<int64_t>(mid, 0);
@@ -92,7 +96,7 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   const int64_t units = (int64_t)g->max_mid * g->Hkv * std::max(n_problems, 1);
   // score_mid: about 1024 workgroups, 256..8192 tokens each (uint16 chunk histograms: < 65536)
   int sc = (int)align_up((size_t)std::clamp<int64_t>(ceil_div(units, 1024), 256, 8192), 256);
-  sc = env_int("TKPHI_SCAN_CHUNK", sc);
+  if (tn.scan_chunk > 0) sc = tn.scan_chunk;
   // matrix-core score kernel: 4 wavefronts x 64 (d = 128) or 128 (d = 64) tokens per iteration;
   // a chunk is a whole number of such units
   g->scan_unit = g->use_mfma ? (g->d == 128 ? 256 : 512) : 256;
@@ -106,7 +110,7 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   // with many chunks per head (one long sequence) the workgroups read neighbouring rows at any
   // moment instead of 1024 far-apart ranges: measured 5 % faster; with few chunks per head
   // (many problems) contiguous ranges are faster
-  g->interleave = env_int("TKPHI_INTERLEAVE", (g->use_mfma && g->scan_unit < g->scan_chunk && g->n_scan_chunks >= 64) ? 1 : 0);
+  g->interleave = tn.interleave ? (tn.interleave == 1 ? 1 : 0) : (g->use_mfma && g->scan_unit < g->scan_chunk && g->n_scan_chunks >= 64) ? 1 : 0;
   if (!g->use_mfma || g->scan_unit >= g->scan_chunk) g->interleave = 0;
   // gather: tiles of kPairsPerWG retrieved tokens per query head
   g->n_tiles = (int)ceil_div(std::min<int64_t>(max_K, g->max_mid), kPairsPerWG);
@@ -116,7 +120,7 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   const int64_t bc_small = std::clamp<int64_t>(ceil_div(units, 512), 256, 2048);
   int bc = (int)align_up((size_t)std::clamp<int64_t>(ceil_div(units, 2048), bc_small, 1 << 20), 64);
   if (!g->use_mfma) bc = std::min(bc, 4096);    // fp32 FMA chains stay short on the generic kernel
-  bc = env_int("TKPHI_BUILD_CHUNK", bc);
+  if (tn.build_chunk > 0) bc = tn.build_chunk;
   g->build_chunk = std::max(64, bc / 64 * 64);
   g->n_build_chunks = (int)std::max<int64_t>(1, ceil_div(g->max_mid, g->build_chunk));
   g->part_stride = 2 * g->d + 4;
@@ -140,6 +144,7 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   p = align_up(p + (size_t)g->Hq * (g->n_tiles + g->n_atiles) * g->part_stride * sizeof(float), 256);
   g->per_problem = p;
   const size_t decode_total = g->off_problem0 + (size_t)std::max(n_problems, 1) * g->per_problem;
+  g->decode_bytes = align_up(decode_total, 256);
   g->off_bpart = g->off_problem0;
   const size_t build_total = g->off_bpart + (size_t)std::max(n_problems, 1) * g->Hkv * g->n_build_chunks *
                                                 (size_t)g->dphi * (g->d + 1) * sizeof(float);
@@ -151,7 +156,7 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
     // measured faster than the smaller block (4.6 against 6.5 ms for 8 KV heads of 131004 tokens)
     const int64_t blk = std::max<int64_t>(((int64_t)64 << 20) / ((int64_t)2 * g->Hkv * g->d_emb * sizeof(float)),
                                           (int64_t)512 * 64 / g->Hkv);
-    g->mlp_block = (int)std::clamp<int64_t>(env_int("TKPHI_MLP_BLOCK", (int)blk) / 64 * 64, 64, 8192);
+    g->mlp_block = (int)std::clamp<int64_t>((tn.mlp_block > 0 ? tn.mlp_block : (int)blk) / 64 * 64, 64, 8192);
     g->off_act = align_up(build_total, 256);
     // (or, for the one-launch build, 2 x 64 x d_emb floats per persistent workgroup)
     const size_t act_bytes = std::max((size_t)2 * g->Hkv * g->mlp_block, (size_t)2 * 64 * kMlpChainWGs) * g->d_emb * sizeof(float);
@@ -164,12 +169,13 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
 }
 
 static tkphi_status check_call(const tkphi_problem* problems, int n_problems, const void* ws,
-                               size_t ws_bytes, const Geom& g) {
+                               size_t ws_bytes, const Geom& g, size_t need = 0) {
+  if (need == 0) need = g.total_bytes;
   if (n_problems > 0 && !problems) { set_error("problems is null"); return TKPHI_EINVAL; }
   if (!ws) { set_error("workspace is null"); return TKPHI_EWORKSPACE; }
   if (((uintptr_t)ws) % 256 != 0) { set_error("workspace must be 256-byte aligned"); return TKPHI_EWORKSPACE; }
-  if (ws_bytes < g.total_bytes) {
-    set_error("workspace too small: %zu < %zu bytes", ws_bytes, g.total_bytes);
+  if (ws_bytes < need) {
+    set_error("workspace too small: %zu < %zu bytes", ws_bytes, need);
     return TKPHI_EWORKSPACE;
   }
   if (((uintptr_t)problems) % 8 != 0) { set_error("problem table must be 8-byte aligned"); return TKPHI_EALIGN; }

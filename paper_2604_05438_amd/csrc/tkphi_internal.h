@@ -36,6 +36,7 @@ struct Geom {
   int scan_unit;         // tokens a score_mid workgroup takes per iteration (scan_chunk is a multiple)
   int phi_kind, d_emb;   // tkphi_phi_kind; MLP width
   int max_gen;           // bound of tkphi_problem::n_gen (generated tokens, exact)
+  int mlp_mode;          // MLP build: tkphi_tuning::mlp_mode
   int mlp_block;         // MLP build: tokens per KV head whose activations are held at once (multiple of 64)
   int cache;             // 1: key features are stored by the build and gathered by decode (cfg.cache_features)
   int diag;              // 1: the select emit pass also reduces the entropy / mass diagnostics
@@ -65,7 +66,8 @@ struct Geom {
   size_t off_bpart;      // float    [Hkv][n_build_chunks][dphi*(d+1)]   (build only; aliases the block)
   size_t off_act;        // float    2 x [Hkv][mlp_block][d_emb]          (MLP build only: activations g, h of a token block)
   size_t off_wpack;      // bf16     [Hkv][Ws | W1 | W2 | Wo]        (MLP build only: one problem's key-side weights in MFMA-fragment order)
-  size_t total_bytes;
+  size_t decode_bytes;   // what a decode call alone uses (status word + per-problem blocks)
+  size_t total_bytes;    // the larger of decode and build
 };
 
 // Fills g for the given bounds; returns TKPHI_OK or the reason the config is unsupported.
@@ -207,8 +209,8 @@ template <> struct Elem<uint16_t> {   // bf16 bits
 
 // ---- query features and device status (side workgroups of the select plan launch) ----
 // phi_q(q_g)[j] = exp(a Wq[g][j] . q_g - c |q_g|^2 + bq[g][j]) for query head gq
-// (Sec. "Positive feature maps and summary states": phi_q is evaluated per query head at decode
-// time).  LPR lanes per Wq row with one 16-byte load each; all row loads of a head are in flight
+// (App. "Head-wise phi architecture": the query-side map belongs to the query head and runs once per
+// decode step).  LPR lanes per Wq row with one 16-byte load each; all row loads of a head are in flight
 // together.  Works for any workgroup size that is a multiple of 64.  qf: LDS, >= kMaxDim floats.
 template <typename T>
 __device__ __forceinline__ void phi_q_head(const Geom& g, const tkphi_problem& pr, char* blk, int gq, float* qf) {
@@ -317,12 +319,13 @@ __device__ __forceinline__ float gelu_erf(float x) {
   return 0.5f * x * (x < 0.f ? erfc_z : 2.0f - erfc_z);
 }
 
-// device status word: recomputed from the problem lengths by one workgroup per decode call
-__device__ __forceinline__ void write_device_status(const Geom& g, const tkphi_problem* probs, char* ws) {
+// device status word: recomputed from the problem lengths by one workgroup per call (decode also
+// checks the generated-token counts, which the build does not read)
+__device__ __forceinline__ void write_device_status(const Geom& g, const tkphi_problem* probs, char* ws, bool check_gen) {
   int bad = 0;
   for (int i = threadIdx.x; i < g.n_problems; i += blockDim.x) {
     const int Li = probs[i].L, gi = probs[i].n_gen;
-    bad |= (Li < 1 || Li > g.max_L || gi < 0 || gi > g.max_gen) ? 1 : 0;
+    bad |= (Li < 1 || Li > g.max_L || (check_gen && (gi < 0 || gi > g.max_gen))) ? 1 : 0;
   }
   bad = __syncthreads_or(bad);
   if (threadIdx.x == 0) *(uint32_t*)(ws + g.off_status) = bad ? TKPHI_DEV_BAD_LENGTH : 0u;

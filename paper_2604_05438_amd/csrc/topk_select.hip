@@ -1,7 +1,7 @@
 // topk_select: exhaustive Top-K over the mid-region scores of every query head
 // (Sec. "Models, tasks, and protocol": the K highest-scoring mid-region tokens), plus the
-// query feature map phi_q (Sec. "Positive feature maps and summary states": phi_q is
-// evaluated per query head at decode time).
+// query feature map phi_q (App. "Head-wise phi architecture": one map per query head, run once
+// per decode step).
 //
 // A two-level radix select in three small kernels, with no atomics and a fixed output order:
 //   plan     one workgroup per query head: sums the per-chunk (suffix-count) histograms written
@@ -106,7 +106,7 @@ __global__ __launch_bounds__(kSelThreads) void select_plan_kernel(Geom g, const 
   const bool split = (int)gridDim.x > g.Hq;
   const bool side_job = (int)blockIdx.x >= g.Hq;
   const int gq = side_job ? (int)blockIdx.x - g.Hq : (int)blockIdx.x;
-  if ((side_job || !split) && gq == 0 && p == 0) write_device_status(g, probs, ws);
+  if ((side_job || !split) && gq == 0 && p == 0) write_device_status(g, probs, ws, true);
 
   const tkphi_problem pr = probs[p];
   if (pr.L < 1 || pr.L > g.max_L) return;

@@ -50,6 +50,18 @@ def test_workspace_query_and_config_validation():
     assert B.tkphi_workspace_bytes(_cfg(), 1, 0, 0) == 0
 
 
+def test_tuning_overrides_are_validated_and_change_the_geometry():
+    base = B.tkphi_workspace_bytes(_cfg(), 1, 32768, 327)
+    assert B.tkphi_workspace_bytes(_cfg(tuning={"build_chunk": 64}), 1, 32768, 327) > base   # more chunk partials
+    for bad in ({"scan_chunk": -1}, {"scan_chunk": 1 << 20}, {"interleave": 3}, {"force_generic": 2}, {"mlp_mode": 5},
+                {"build_chunk": -64}):
+        assert B.tkphi_workspace_bytes(_cfg(tuning=bad), 1, 32768, 327) == 0
+        assert "tuning" in B.tkphi_last_error()
+    cfg = _cfg()
+    cfg.tuning.reserved[2] = 1
+    assert B.tkphi_workspace_bytes(cfg, 1, 32768, 327) == 0
+
+
 def test_mlp_feature_map_config_validation():
     mlp = dict(phi_kind=B.TKPHI_PHI_MLP, cache_features=1, d_emb=512)
     base = B.tkphi_workspace_bytes(_cfg(cache_features=1), 1, 32768, 327)

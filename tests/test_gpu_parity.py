@@ -11,9 +11,9 @@ from paper_2604_05438_amd import inputs as I
 pytestmark = pytest.mark.gpu
 
 
-def _batch(w, layers, topk, cache_features=False, **kw):
+def _batch(w, layers, topk, cache_features=False, tuning=None, **kw):
     from paper_2604_05438_amd import harness as H
-    return H.Batch(H.config_of(w, cache_features=cache_features), layers, topk, debug=True, **kw)
+    return H.Batch(H.config_of(w, cache_features=cache_features, tuning=tuning), layers, topk, debug=True, **kw)
 
 
 def _run_single(w, L, k, mode="sub", heads=None, **kw):
@@ -55,20 +55,19 @@ def test_l3b_shape_small(L, k):
 
 @pytest.mark.parametrize("shape,L,k,chunk", [("l3b_128k", 20011, 200, 1024), ("l1b_32k", 9000, 90, 2048),
                                              ("l3b_128k", 5000, 600, 512)])
-def test_interleaved_chunks(monkeypatch, shape, L, k, chunk):
+def test_interleaved_chunks(shape, L, k, chunk):
     """The chunk-to-row mapping used for long single sequences (every workgroup takes every
     n_chunks-th unit of 256 / 512 rows), forced here at sizes the oracle checks in full; ragged
     last units, and a single problem as well as a ragged batch."""
     import parity_utils as PU
-    monkeypatch.setenv("TKPHI_INTERLEAVE", "1")
-    monkeypatch.setenv("TKPHI_SCAN_CHUNK", str(chunk))
+    tuning = {"interleave": 1, "scan_chunk": chunk}
     w = I.WORKLOADS[shape]
-    rep, _, _ = _run_single(w, L, k)
+    rep, _, _ = _run_single(w, L, k, tuning=tuning)
     print("interleaved", shape, L, k, rep)
     Ls = [L, L // 2 + 3, 700]
     ks = [k, 11, 5]
     layers = [I.make_layer(w, L=l, seq=i) for i, l in enumerate(Ls)]
-    b = _batch(w, layers, ks)
+    b = _batch(w, layers, ks, tuning=tuning)
     b.build(); b.decode()
     assert b.status() == 0
     for i, (P, kk) in enumerate(zip(layers, ks)):
@@ -80,6 +79,13 @@ def test_accounting_variants(mode):
     w = I.WORKLOADS["l1b_32k"]
     rep, _, _ = _run_single(w, 3000, 29, mode=mode)
     print(mode, rep)
+
+
+def test_generic_kernels_forced_on_a_matrix_core_shape():
+    """tkphi_tuning::force_generic: the fp32-arithmetic kernels on bf16 storage with d_phi == d_head."""
+    w = I.WORKLOADS["l1b_32k"]
+    rep, _, _ = _run_single(w, 2100, 21, heads=[0, 9, 31], tuning={"force_generic": 1})
+    print("forced generic", rep)
 
 
 def test_f32_gqa_and_dphi_not_equal_d():
@@ -199,7 +205,12 @@ def test_bad_length_is_skipped_and_flagged():
     b.max_L = 1200
     b.ws_bytes = B.tkphi_workspace_bytes(b.cfg, b.n, 1500, b.max_K)
     b.dev[1]["out"].fill_(-7.0)
-    b.build(); b.decode()
+    b.dev[1]["S"].fill_(-3.0); b.dev[1]["u"].fill_(-3.0)
+    b.ws.fill_(0xEE)                                   # the workspace need not be initialised
+    b.build()
+    assert b.status() == B.TKPHI_DEV_BAD_LENGTH        # the build records the skipped problem too ...
+    assert (b.result(1, "S") == -3.0).all() and (b.result(1, "u") == -3.0).all()   # ... and leaves its S, u alone
+    b.decode()
     assert b.status() & B.TKPHI_DEV_BAD_LENGTH
     assert (b.result(1, "out") == -7.0).all()
     rep = PU.check_layer(w, layers[0], 9, b, 0, heads=[0, 31])
@@ -275,20 +286,18 @@ def _check_diag(w, P, k, b, i, heads):
 
 @pytest.mark.parametrize("shape,L,k,interleave", [("l3b_128k", 9000, 360, 0), ("l3b_128k", 20011, 200, 1),
                                                   ("l1b_32k", 5000, 0, 0), ("tiny_f32", 4096, 40, 0)])
-def test_entropy_and_mass_diagnostics(monkeypatch, shape, L, k, interleave):
+def test_entropy_and_mass_diagnostics(shape, L, k, interleave):
     """The by-product diagnostics (normalised mid-region entropy, mid mass, Top-K mass recovery,
     residual shares, residual log-partition error) against the oracle; K = 0 included (nothing is
     retrieved but the score pass still runs); the output itself must not depend on the flag."""
     from paper_2604_05438_amd import binding as B
     import parity_utils as PU
-    if interleave:
-        monkeypatch.setenv("TKPHI_INTERLEAVE", "1")
-        monkeypatch.setenv("TKPHI_SCAN_CHUNK", "1024")
+    tuning = {"interleave": 1, "scan_chunk": 1024} if interleave else None
     w = I.WORKLOADS[shape]
     Ls = [L, max(L // 3, 100)]
     ks = [k, min(k, 7)]
     layers = [I.make_layer(w, L=l, seq=i) for i, l in enumerate(Ls)]
-    b = _batch(w, layers, ks)
+    b = _batch(w, layers, ks, tuning=tuning)
     b.build()
     b.decode(B.TKPHI_MODE_SUB)
     y_plain = [b.result(i, "out").copy() for i in range(2)]
@@ -335,7 +344,7 @@ def test_cached_key_features(shape, L, k):
 @pytest.mark.parametrize("shape,d_emb,L,k,mode", [("l3b_128k", 512, 9000, 360, ""), ("l1b_32k", 128, 10000, 49, ""),
                                                   ("bf16_wide_phi", 256, 1500, 33, ""), ("l1b_32k", 128, 10000, 49, "blocks"),
                                                   ("l3b_128k", 512, 4500, 45, "unfused")])
-def test_mlp_feature_maps(monkeypatch, shape, d_emb, L, k, mode):
+def test_mlp_feature_maps(shape, d_emb, L, k, mode):
     """Learned feature maps (App. "Head-wise phi architecture"): the build evaluates the one-block
     ReZero MLP phi_k on the mid-region keys with the tiled matrix-core GEMM chain, stores the
     features and contracts them into S, u; decode evaluates phi_q per query head with the GEMV
@@ -345,8 +354,6 @@ def test_mlp_feature_maps(monkeypatch, shape, d_emb, L, k, mode):
     persistent launch per problem by default; "blocks" forces the layer-wise launches per token block
     (residual + output fused), "unfused" all four layers apart (the path of widths that do not fuse)."""
     import parity_utils as PU
-    if mode:
-        monkeypatch.setenv("TKPHI_MLP_MODE", mode)
     from oracle import tkphi_oracle as orc
     from paper_2604_05438_amd import harness as H
     if shape == "bf16_wide_phi":
@@ -361,7 +368,8 @@ def test_mlp_feature_maps(monkeypatch, shape, d_emb, L, k, mode):
         P = I.make_layer(w, L=l, seq=i)
         P["mlp"] = I.make_mlp_phi(w, layer=i, d_emb=d_emb)
         layers.append(P)
-    b = H.Batch(H.config_of(w, d_emb=d_emb), layers, ks, debug=True)
+    from paper_2604_05438_amd import binding as B
+    b = H.Batch(H.config_of(w, d_emb=d_emb, tuning={"mlp_mode": B.MLP_MODES[mode]}), layers, ks, debug=True)
     b.build(); b.decode()
     assert b.status() == 0
     for i, (P, kk) in enumerate(zip(layers, ks)):
