@@ -274,6 +274,27 @@ tkphi_status tkphi_decode(const tkphi_config* cfg /*HOST*/,
                           void* workspace, size_t workspace_bytes,
                           void* hip_stream);
 
+/* tkphi_decode for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (minus
+ * the workspace), same validation, same kernels and bit-identical results; the scratch memory is a
+ * static device array of TKPHI_STATIC_SCRATCH_BYTES inside the library, of which every GPU the
+ * library runs on holds one copy until the process ends.  A request whose decode scratch does not
+ * fit (tkphi_workspace_bytes is an upper bound of it; one 128K-token layer of 24 query heads needs
+ * about 17 MiB) fails with TKPHI_EWORKSPACE and enqueues nothing; TKPHI_PHI_MLP is refused with
+ * TKPHI_EUNSUPPORTED (that path creates a stream on first use).  The call allocates nothing and frees
+ * nothing.  The first call on a device resolves the array's address (with that device current: the
+ * device of hip_stream must be the current device); a caller that captures calls into a HIP graph makes
+ * one call outside the capture first.  All calls on one GPU share the array, which keeps the last call's contents
+ * (nothing in it needs to start at zero): two calls that overlap in time on one GPU, on different
+ * streams or threads, race; calls on one stream are ordered and safe.  tkphi_read_device_status
+ * cannot be used with it (the status word lives in the array). */
+#define TKPHI_STATIC_SCRATCH_BYTES (32u << 20)
+tkphi_status tkphi_decode_static(const tkphi_config* cfg /*HOST*/,
+                                 const tkphi_problem* problems /*DEVICE table*/,
+                                 int32_t n_problems, int32_t max_L, int32_t max_K,
+                                 int32_t mode /* tkphi_mode, optionally | TKPHI_FLAG_DIAG */,
+                                 void* hip_stream);
+
 /* Profiling helper: the same work as tkphi_decode, with a pair of HIP events attached to
  * every kernel launch (recorded at the kernel's own begin and end on the stream), then a
  * stream synchronisation; stage_ms_out (HOST, TKPHI_N_STAGES floats) receives the

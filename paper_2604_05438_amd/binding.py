@@ -24,7 +24,7 @@ TKPHI_DIAG_STRIDE = 8
 TKPHI_DEV_BAD_LENGTH, TKPHI_DEV_CLAMPED = 1, 2
 
 EXPORTS = (
-    "tkphi_workspace_bytes", "tkphi_build_summaries", "tkphi_decode", "tkphi_decode_stage_times",
+    "tkphi_workspace_bytes", "tkphi_build_summaries", "tkphi_decode", "tkphi_decode_static", "tkphi_decode_stage_times",
     "tkphi_check_problems",
     "tkphi_read_device_status", "tkphi_budget_paper", "tkphi_budget_mid", "tkphi_status_string",
     "tkphi_last_error",
@@ -97,6 +97,8 @@ def lib() -> C.CDLL:
         L.tkphi_decode.restype = C.c_int
         L.tkphi_decode.argtypes = [cfgp, probp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                    C.c_size_t, C.c_void_p]
+        L.tkphi_decode_static.restype = C.c_int
+        L.tkphi_decode_static.argtypes = [cfgp, probp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
         L.tkphi_decode_stage_times.restype = C.c_int
         L.tkphi_decode_stage_times.argtypes = [cfgp, probp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                                C.c_size_t, C.c_void_p, C.POINTER(C.c_float)]
@@ -163,6 +165,14 @@ def tkphi_decode(cfg: tkphi_config, problems_dev_ptr: int, n_problems: int, max_
                  mode: int, workspace_ptr: int, workspace_bytes: int, stream: int) -> None:
     _check(lib().tkphi_decode(C.byref(cfg), problems_dev_ptr, n_problems, max_L, max_K, mode, workspace_ptr,
                               workspace_bytes, stream))
+
+
+def tkphi_decode_static(cfg: tkphi_config, problems_dev_ptr: int, n_problems: int, max_L: int, max_K: int,
+                        mode: int, stream: int) -> None:
+    _check(lib().tkphi_decode_static(C.byref(cfg), problems_dev_ptr, n_problems, max_L, max_K, mode, stream))
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
 
 
 STAGES = ("score_mid", "select_plan", "select_emit", "select_resolve", "gather", "merge", "phi_q_mlp")

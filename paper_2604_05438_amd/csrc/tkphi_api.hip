@@ -303,6 +303,65 @@ tkphi_status tkphi_decode(const tkphi_config* cfg, const tkphi_problem* problems
   return hip_ok(hipGetLastError(), "tkphi_decode launch");
 }
 
+// ---- decode for callers that cannot allocate ------------------------------------------------
+// The scratch memory of a decode call (everything tkphi_decode keeps in the caller's workspace)
+// in a file-scope device array.  Each GPU the library runs on holds its own copy of the array,
+// at its own address, until the process ends; the address is resolved once per device, with that
+// device current, and kept.  Host code never uses the array's name for anything else: kernels,
+// like every other consumer, get the resolved pointer.
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[TKPHI_STATIC_SCRATCH_BYTES];
+static std::mutex g_scratch_mutex;
+static char* g_scratch_ptr[64];
+
+static tkphi_status static_scratch(char** out) {
+  int dev = 0;
+  tkphi_status st = hip_ok(hipGetDevice(&dev), "hipGetDevice");
+  if (st != TKPHI_OK) return st;
+  if (dev < 0 || dev >= 64) { set_error("device ordinal %d out of range", dev); return TKPHI_EINVAL; }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    st = hip_ok(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+    if (st != TKPHI_OK) return st;
+    if (!ptr || ((uintptr_t)ptr) % 256 != 0) { set_error("static scratch resolved to %p", ptr); return TKPHI_EHIP; }
+    g_scratch_ptr[dev] = (char*)ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return TKPHI_OK;
+}
+
+tkphi_status tkphi_decode_static(const tkphi_config* cfg, const tkphi_problem* problems, int32_t n_problems,
+                                 int32_t max_L, int32_t max_K, int32_t mode, void* hip_stream) {
+  const int acct = mode & ~TKPHI_FLAG_DIAG;
+  if (acct != TKPHI_MODE_SUB && acct != TKPHI_MODE_NOSUB && acct != TKPHI_MODE_TOPK_ONLY) {
+    set_error("mode=%d is not a tkphi_mode (optionally | TKPHI_FLAG_DIAG)", mode);
+    return TKPHI_EINVAL;
+  }
+  Geom g;
+  tkphi_status st = make_geom(cfg, n_problems, max_L, max_K, &g);
+  if (st != TKPHI_OK) return st;
+  g.diag = (mode & TKPHI_FLAG_DIAG) ? 1 : 0;
+  if (g.phi_kind == TKPHI_PHI_MLP) {      // that path creates a stream and events on first use
+    set_error("tkphi_decode_static does not run the MLP feature maps");
+    return TKPHI_EUNSUPPORTED;
+  }
+  if (g.decode_bytes > (size_t)TKPHI_STATIC_SCRATCH_BYTES) {
+    set_error("decode scratch of %zu bytes exceeds the static array of %zu bytes (n_problems=%d max_L=%d max_K=%d)",
+              g.decode_bytes, (size_t)TKPHI_STATIC_SCRATCH_BYTES, n_problems, max_L, max_K);
+    return TKPHI_EWORKSPACE;
+  }
+  char* ws = nullptr;
+  st = static_scratch(&ws);
+  if (st != TKPHI_OK) return st;
+  st = check_call(problems, n_problems, ws, g.decode_bytes, g, g.decode_bytes);
+  if (st != TKPHI_OK) return st;
+  if (n_problems == 0) return TKPHI_OK;
+  (void)hipGetLastError();
+  st = enqueue_decode(g, problems, ws, acct, (hipStream_t)hip_stream);
+  if (st != TKPHI_OK) return st;
+  return hip_ok(hipGetLastError(), "tkphi_decode_static launch");
+}
+
 tkphi_status tkphi_decode_stage_times(const tkphi_config* cfg, const tkphi_problem* problems,
                                       int32_t n_problems, int32_t max_L, int32_t max_K, int32_t mode,
                                       void* workspace, size_t workspace_bytes, void* hip_stream,
