@@ -132,7 +132,15 @@ typedef struct tkphi_tuning {
   int32_t mlp_mode;       /* MLP build: 0 = one persistent launch where the widths allow it,
                              1 = layer-wise launches per token block (residual + output fused),
                              2 = all four layers as separate launches                                    */
-  int32_t reserved[6];    /* 0                                                                            */
+  int32_t select_mode;    /* decode pipeline of the bf16 matrix-core shapes: 0 = by the bounds (filtered unless
+                             max_K exceeds an eighth of the largest mid-region), 1 = spill (score_mid writes
+                             every score and chunk histograms; plan / emit / resolve select from them),
+                             2 = filtered (a sampled lower bound of the K-th score prunes what the score pass
+                             writes; one select kernel per step).  Ignored where only the spill pipeline applies
+                             (fp32 storage, d_phi != d_head, MLP maps, TKPHI_FLAG_DIAG)                    */
+  int32_t select_test;    /* filtered pipeline, tests only: 1 = the sampled bound is replaced by one no score
+                             passes (every head takes the rescan), 2 = by one every score passes           */
+  int32_t reserved[4];    /* 0                                                                            */
 } tkphi_tuning;
 
 /* Fixed per model.  HOST struct.
@@ -299,12 +307,14 @@ tkphi_status tkphi_decode_static(const tkphi_config* cfg /*HOST*/,
  * every kernel launch (recorded at the kernel's own begin and end on the stream), then a
  * stream synchronisation; stage_ms_out (HOST, TKPHI_N_STAGES floats) receives the
  * duration in milliseconds of each stage:
- *   score_mid, select_plan (+ the exp-affine phi_q), select_emit, select_resolve,
- *   gather (exact branch + subtraction sums), merge, and last the three phi_q launches of
- *   the MLP feature maps (they run first; begin of the first to end of the third)
+ *   score_mid (either pipeline's score pass), select_plan (+ the exp-affine phi_q), select_emit,
+ *   select_resolve, gather (exact branch + subtraction sums), merge, the three phi_q launches of
+ *   the MLP feature maps (they run first; begin of the first to end of the third), and the two
+ *   kernels only the filtered pipeline has: prep (sampled score bound, phi_q and the summary terms,
+ *   anchors; runs first) and select
  * (0 for a stage that the given configuration and bounds do not launch).  Same validation and results as
  * tkphi_decode; creates and destroys HIP events (no device memory). */
-#define TKPHI_N_STAGES 7
+#define TKPHI_N_STAGES 9
 tkphi_status tkphi_decode_stage_times(const tkphi_config* cfg /*HOST*/,
                                       const tkphi_problem* problems /*DEVICE table*/,
                                       int32_t n_problems, int32_t max_L, int32_t max_K,

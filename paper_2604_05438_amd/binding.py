@@ -39,7 +39,8 @@ class tkphi_tuning(C.Structure):
     _fields_ = [
         ("force_generic", C.c_int32), ("scan_chunk", C.c_int32), ("interleave", C.c_int32),
         ("build_chunk", C.c_int32), ("mlp_block", C.c_int32), ("mlp_mode", C.c_int32),
-        ("reserved", C.c_int32 * 6),
+        ("select_mode", C.c_int32), ("select_test", C.c_int32),
+        ("reserved", C.c_int32 * 4),
     ]
 
 
@@ -175,7 +176,8 @@ def tkphi_decode_static(cfg: tkphi_config, problems_dev_ptr: int, n_problems: in
 STATIC_SCRATCH_BYTES = 32 << 20
 
 
-STAGES = ("score_mid", "select_plan", "select_emit", "select_resolve", "gather", "merge", "phi_q_mlp")
+STAGES = ("score_mid", "select_plan", "select_emit", "select_resolve", "gather", "merge", "phi_q_mlp", "prep", "select")
+SELECT_SPILL, SELECT_FILTERED = 1, 2          # tkphi_tuning::select_mode
 
 
 def tkphi_decode_stage_times(cfg: tkphi_config, problems_dev_ptr: int, n_problems: int, max_L: int, max_K: int,

@@ -19,16 +19,12 @@
 // All loops over tokens issue their (independent) row loads before consuming them: these
 // kernels move little data and are bound by memory latency, not bandwidth.
 #include "block_utils.h"
+#include "gather_tile.h"
 #include "tkphi_internal.h"
 
 namespace tkphi {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
-union Frag {
-  u32x4 u;
-  bf16x8 v;
-};
+typedef GatherFrag Frag;
 
 // ---- weighted sums of value rows ------------------------------------------------------------
 // nu[c] = sum_i w[i] v_i[c], zv[c] = sum_i z[i] v_i[c] over `cnt` <= 64 rows given by tok[]
@@ -170,8 +166,8 @@ __device__ void anchor_partial(const Geom& g, const tkphi_problem& pr, int gq, i
 template <int D>
 __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkphi_problem* __restrict__ probs,
                                                                char* __restrict__ ws) {
-  constexpr int KS = D / 32, NT = D / 16;
-  constexpr int WROW = D * 2 + 16;                 // bytes per staged Wk row
+  constexpr int KS = D / 32;
+  constexpr int WROW = wk_row_bytes(D);            // bytes per staged Wk row
   // the staged Wk and the reduction scratch of the value sums are never live together
   constexpr int kRedBytes = 2 * kThreads * 8 * (int)sizeof(float);
   constexpr int kBufBytes = D * WROW > kRedBytes ? D * WROW : kRedBytes;
@@ -238,53 +234,8 @@ __global__ __launch_bounds__(kThreads) void gather_mfma_kernel(Geom g, const tkp
 #pragma unroll
     for (int j = 0; j < KS; ++j) a[j].u = gload128(rp + j * 64);
     const float* phiq = (const float*)(blk + g.off_phiq) + (size_t)gq * D;
-    const float* bk = pr.bk + (size_t)h * D;
-    float bj[NT], pj[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) { bj[nt] = bk[nt * 16 + r] * kLog2e; pj[nt] = phiq[nt * 16 + r]; }
-    const float a2 = g.a * kLog2e, c2 = g.c * kLog2e;
-    // |k|^2 of token r: this lane's 8*KS channels, then the 4 lanes of the row
-    float nrm = 0.f;
-#pragma unroll
-    for (int j = 0; j < KS; ++j) {
-      float x[8];
-      Elem<uint16_t>::unpack(make_uint4(a[j].u.x, a[j].u.y, a[j].u.z, a[j].u.w), x);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) nrm = fmaf(x[e], x[e], nrm);
-    }
-    nrm += __shfl_xor(nrm, 16);
-    nrm += __shfl_xor(nrm, 32);
-    float cn[4];                                   // c |k|^2 log2(e) of tokens 4kg + i
-#pragma unroll
-    for (int i = 0; i < 4; ++i) cn[i] = c2 * __shfl(nrm, 4 * kg + i);
-
-    float zacc[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      floatx4 acc = (floatx4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int j = 0; j < KS; ++j) {
-        Frag b;
-        b.u = *(const u32x4*)(wk_lds + (nt * 16 + r) * WROW + j * 64 + kg * 16);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[j].v, b.v, acc, 0, 0, 0);
-      }
-      // acc[i] = Wk[feature nt*16 + r] . k(token 4kg + i)
-      float f[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) f[i] = phi_exp2(acc[i], a2, bj[nt] - cn[i]);
-      uint32_t h01, l01, h23, l23;           // the 16 bits per feature that the summary build contracted
-      split_bf16_pair(f[0], f[1], &h01, &l01);
-      split_bf16_pair(f[2], f[3], &h23, &l23);
-      zacc[0] = fmaf(join_bf16_lo(h01, l01), pj[nt], zacc[0]);
-      zacc[1] = fmaf(join_bf16_hi(h01, l01), pj[nt], zacc[1]);
-      zacc[2] = fmaf(join_bf16_lo(h23, l23), pj[nt], zacc[2]);
-      zacc[3] = fmaf(join_bf16_hi(h23, l23), pj[nt], zacc[3]);
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-#pragma unroll
-      for (int o = 8; o >= 1; o >>= 1) zacc[i] += __shfl_xor(zacc[i], o);
-    }
+    float zacc[4];
+    wave_feature_dots<D>(a, wk_lds, pr.bk + (size_t)h * D, phiq, g.a, g.c, zacc);
     if (r == 0) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) p_z[wv * 16 + 4 * kg + i] = zacc[i];
@@ -486,6 +437,7 @@ __global__ __launch_bounds__(kThreads) void gather_cached_kernel(Geom g, const t
 // ------------------------------------------------------------------------------------
 // merge: grid (Hq, n_problems)
 // ------------------------------------------------------------------------------------
+template <bool PRE>   // PRE: S_M^T phi_q and phi_q . u_M come from the prep kernel (workspace), not from S, u
 __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_problem* __restrict__ probs,
                                                          char* __restrict__ ws, int mode) {
   __shared__ float red_f[4];
@@ -497,7 +449,8 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
   const int n = mid_size(pr.L, g.n_sink, g.n_tail);
   const int Ksel = max(0, min(min(pr.topk, n), g.max_K));
   const int n_anchor = (n > 0 ? g.n_sink + g.n_tail : pr.L) + min(max(pr.n_gen, 0), g.max_gen);   // anchors + generated tokens
-  const int n_used = (Ksel + kPairsPerWG - 1) / kPairsPerWG;     // tiles holding retrieved tokens
+  // partials holding retrieved tokens: tiles of 64, or (PRE) one per workgroup of the fused select + gather kernel
+  const int n_used = PRE ? (Ksel > 0 ? g.n_tiles : 0) : (Ksel + kPairsPerWG - 1) / kPairsPerWG;
   const int na_used = (n_anchor + 63) / 64;                      // tiles holding anchors
   const int d = g.d, dphi = g.dphi;
   const int h = gq / g.G;
@@ -513,7 +466,12 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
   float4 sacc = make_float4(0.f, 0.f, 0.f, 0.f);
   const int QPR = d / 4, NG = kThreads / QPR;      // float4 per row; feature groups (8 for d=128, 16 for d=64)
   const int jg = tid / QPR, c4 = tid % QPR;
-  if (use_res) {
+  float pre_n = 0.f, pre_z = 0.f;
+  if (PRE && use_res) {
+    pre_z = ((const float*)(blk + g.off_uphi))[gq];
+    if (tid < d) pre_n = ((const float*)(blk + g.off_sphi))[(size_t)gq * d + tid];
+  }
+  if (!PRE && use_res) {
     const float* phiq = (const float*)(blk + g.off_phiq) + (size_t)gq * dphi;
     for (int j = tid; j < dphi; j += kThreads) { sh_phiq[j] = phiq[j]; sh_u[j] = pr.u[(size_t)h * dphi + j]; }
     const float* __restrict__ S = pr.S + (size_t)h * dphi * d;
@@ -589,7 +547,16 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
   // (with every mid token retrieved in SUB mode the residual set is empty: exactly zero)
   float nuR = 0.f, ZR = 0.f;
   bool clamped = false;
-  if (use_res) {
+  if (PRE && use_res) {
+    float accn = pre_n, accz = pre_z;
+    if (mode == TKPHI_MODE_SUB) { accn -= zv; accz -= zsum; }
+    nuR = accn; ZR = accz;
+    if (!(ZR > 0.f)) {                     // numerical clamp: drop the residual branch
+      clamped = true;
+      nuR = 0.f; ZR = 0.f;
+    }
+  }
+  if (!PRE && use_res) {
     // fixed-order sum over the feature groups
     float* row = &sh_grp[0][0];
     if (jg < 8) { row[jg * 128 + c4 * 4 + 0] = sacc.x; row[jg * 128 + c4 * 4 + 1] = sacc.y;
@@ -711,9 +678,10 @@ void launch_gather(const Geom& g, const tkphi_problem* probs, char* ws, hipStrea
   }
 }
 
-void launch_merge(const Geom& g, const tkphi_problem* probs, char* ws, int mode, hipStream_t s) {
+void launch_merge(const Geom& g, const tkphi_problem* probs, char* ws, int mode, bool pre, hipStream_t s) {
   dim3 grid(g.Hq, g.n_problems);
-  TKPHI_LAUNCH(ST_MERGE, merge_kernel, grid, dim3(kThreads), 0, s, g, probs, ws, mode);
+  if (pre) TKPHI_LAUNCH(ST_MERGE, merge_kernel<true>, grid, dim3(kThreads), 0, s, g, probs, ws, mode);
+  else TKPHI_LAUNCH(ST_MERGE, merge_kernel<false>, grid, dim3(kThreads), 0, s, g, probs, ws, mode);
 }
 
 }  // namespace tkphi

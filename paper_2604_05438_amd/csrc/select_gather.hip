@@ -1,0 +1,482 @@
+// Fused Top-K select + gather of the filtered pipeline (bf16 caches on the matrix cores):
+// topk_select, exact_branch and residual_correct for the retrieved tokens in one launch.
+// grid (split, Hq, n_problems), 1024 threads: `split` workgroups share a query head.
+//
+// The score pass left, per query head, every token whose score key reaches the head's lower bound, in
+// per-wavefront lists (score_tile.h): the first cand_T entries of a list in a compact array, the rest in
+// the list's full-capacity region.  If at least K candidates exist, the K best mid tokens
+// (Sec. "Models, tasks, and protocol": exhaustive Top-K, ties to the lower index) are all among them.
+//
+// Every workgroup of a head first finds the same selection threshold, on its own (the candidates of a
+// head are ~100 KB and the search is a few thousand instructions: cheaper than a launch boundary):
+//   * the candidates are visited in "sweeps" in which a thread owns kSweepEntries consecutive entries of
+//     one list; the first sweep's addresses depend on the launch geometry only and are loaded together
+//     with the problem record, so the common case is one memory round trip
+//   * histogram of a fine monotone binning of the score keys -> boundary bin b* (tokens in higher bins
+//     are retrieved); the candidates in b* are ranked by counting (or, beyond kBCap of them, by radix
+//     passes over the sweeps) -> the K-th best composite (score key, lower index first), `thr`
+//   * fewer than K candidates (the sampled bound was too high: a ~1e-5 event per head by design, and what
+//     tkphi_tuning::select_test = 1 forces): the workgroup first rescans its head's keys with no bound,
+//     which makes every mid token a candidate
+// Then workgroup `part` takes the lists [part, part + 1) n_lists / split: their winners (composite >=
+// thr), in list order, are written to the head's retrieved list at the offset given by the winners in
+// earlier lists, and gathered 256 at a time (16 tokens per wavefront):
+//     m_loc = max s_i,  Z_loc = sum exp(s_i - m_loc),  nu_loc = sum exp(s_i - m_loc) v_i     (eq. (exact_terms))
+//     zsum = sum z_i,  zv = sum z_i v_i,  z_i = phi_q . phi_k(k_i) recomputed                (eq. (subtraction))
+// into one partial per workgroup, [m, Z, zsum, count, nu[d], zv[d]], which the merge kernel combines in
+// part order.  No atomics on global memory; every sum runs in a fixed order.
+#include "gather_tile.h"
+#include "score_tile.h"
+#include "select_utils.h"
+#include "tkphi_internal.h"
+
+namespace tkphi {
+
+constexpr int kBCap = 1024;            // boundary-bin candidates ranked in LDS
+constexpr int kSweepEntries = 12;      // entries per thread and sweep (Geom::cand_T is a multiple)
+constexpr int kSweepLoads = kSweepEntries / 2;
+constexpr int kBatch = 256;            // winners gathered per round: 16 per wavefront
+constexpr int kWinLds = 512;           // winners of a workgroup kept in LDS (the rest are re-read from the retrieved list)
+
+// every mid token of query head gq becomes a candidate: the head's lists are rewritten with no bound
+// (one 16-token tile in flight per wavefront: the rare path must not cost the common one registers)
+template <int D, int TPI>
+__device__ __forceinline__ void rescan_head(const Geom& g, const tkphi_problem& pr, char* blk, int gq, int n, int n_chunks) {
+  const int h = gq / g.G, wv = threadIdx.x >> 6;
+  ScoreFrag bq[D / 32];
+  load_query_frags<D>(g, pr, h, bq);
+  for (int reg = wv; reg < n_chunks * 4; reg += kSelWaves)
+    scan_wave_slot<D, TPI, 1>(g, pr, blk, h, n, n_chunks, reg >> 2, reg & 3, bq, 0u, gq % g.G);
+}
+
+template <int D, int TPI>
+__global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, const tkphi_problem* __restrict__ probs,
+                                                                    char* __restrict__ ws) {
+  constexpr int KS = D / 32;
+  constexpr int WROW = wk_row_bytes(D);
+  // select phase: histogram (8 KB) + boundary candidates (8 KB); gather phase: reduction scratch of the value sums
+  __shared__ __attribute__((aligned(16))) char lds_a[16384];
+  __shared__ __attribute__((aligned(16))) char wk_lds[D * WROW];
+  __shared__ int w_tok[kWinLds];
+  __shared__ float w_s[kWinLds];
+  __shared__ float b_w[kBatch], b_z[kBatch];
+  __shared__ int sh_scan[kSelWaves];
+  __shared__ uint64_t sh_prefix, sh_thr;
+  __shared__ int sh_want, sh_tot;
+  __shared__ int sh_bstar, sh_krem, sh_chi, sh_nb, sh_nbc;
+  __shared__ uint32_t sh_total, sh_ovp;
+  __shared__ float sh_m, sh_Z, sh_zs;
+  uint32_t* sh_hist = (uint32_t*)lds_a;
+  uint64_t* bcand = (uint64_t*)(lds_a + 8192);
+  float* red = (float*)lds_a;                       // [16 wavefronts][2][128]
+
+  const int part = blockIdx.x, gq = blockIdx.y, p = blockIdx.z, tid = threadIdx.x;
+  const int lane = tid & 63, wv = tid >> 6;
+  TKPHI_PHASE(ws, 10);
+  char* blk = problem_block(g, ws, p);
+  const int T = g.cand_T;
+  const int n_reg_max = g.n_scan_chunks * 4;
+  const uint32_t cap_w = (uint32_t)(g.scan_chunk / 4);
+  const uint32_t* ccount = (const uint32_t*)(blk + g.off_ccount) + (size_t)gq * n_reg_max;
+  const uint2* compact = (const uint2*)(blk + g.off_candc) + (size_t)gq * n_reg_max * T;
+  const uint2* sparse = (const uint2*)(blk + g.off_candf) + (size_t)gq * n_reg_max * cap_w;
+
+  // ---- first sweep, speculatively: addresses depend on the launch geometry only --------------------------
+  u32x4 e0[kSweepLoads];
+  uint32_t c0 = 0;
+  {
+    const int s = kSweepEntries * tid, list = s / T;
+    if (list < n_reg_max) {
+      c0 = ccount[list];
+#pragma unroll
+      for (int u = 0; u < kSweepLoads; ++u) e0[u] = gload128(compact + s + 2 * u);
+    }
+  }
+  const tkphi_problem pr = probs[p];
+  if (pr.L < 1 || pr.L > g.max_L) return;
+  const int n = mid_size(pr.L, g.n_sink, g.n_tail);
+  const int Ksel = max(0, min(min(pr.topk, n), g.max_K));
+  SelPlan* plan = (SelPlan*)(blk + g.off_plan) + gq;
+  if (Ksel == 0) {
+    if (tid == 0 && part == 0) *plan = SelPlan{-1, 0, 0, 0, 0};
+    return;
+  }
+  const int h = gq / g.G;
+  stage_wk<D>(pr.Wk, h, wk_lds);                    // (visible after the barriers of the select phase)
+  const int n_chunks = (n + g.scan_chunk - 1) / g.scan_chunk;
+  const int n_reg = n_chunks * 4;
+  const int rounds = (n_reg * T + kSelThreads * kSweepEntries - 1) / (kSelThreads * kSweepEntries);
+  int32_t* sel_idx = (int32_t*)(blk + g.off_selidx) + (size_t)gq * g.max_K;
+  float* sel_score = (float*)(blk + g.off_selscore) + (size_t)gq * g.max_K;
+
+  // entries [0, nvalid) at src are the share of thread t in sweep sw; they belong to list `list`
+  struct Share { const uint2* src; int nvalid; int list; };
+  int max_passes = 0;                               // overflow sweeps per round (set below)
+  auto share_of = [&](int sw, int t, int known = -1) -> Share {   // known: the list's length if the caller has it
+    const int r = sw < rounds ? sw : (sw - rounds) / max_passes;
+    const int s = kSweepEntries * (t + kSelThreads * r), list = s / T, pos = s % T;
+    if (list >= n_reg) return Share{compact, 0, list};
+    const int c = (int)min(known >= 0 ? (uint32_t)known : ccount[list], cap_w);
+    if (sw < rounds) return Share{compact + s, max(0, min(min(c, T) - pos, kSweepEntries)), list};
+    const int k = (sw - rounds) % max_passes;
+    const int start = T + (k * (T / kSweepEntries) + pos / kSweepEntries) * kSweepEntries;
+    return Share{sparse + (size_t)list * cap_w + start, max(0, min(c - start, kSweepEntries)), list};
+  };
+  auto load_share = [&](const Share& sh, u32x4 (&e)[kSweepLoads]) {
+#pragma unroll
+    for (int u = 0; u < kSweepLoads; ++u)
+      if (2 * u < sh.nvalid) e[u] = gload128(sh.src + 2 * u);
+  };
+  auto entry = [](const u32x4 (&e)[kSweepLoads], int i) { return (i & 1) ? make_uint2(e[i >> 1].z, e[i >> 1].w) : make_uint2(e[i >> 1].x, e[i >> 1].y); };
+
+  // ---- candidate count, overflow depth (and, on a threshold miss, the rescan) ---------------------------
+  bool have_e0 = true;
+  int n_sweeps = 0;
+  for (int attempt = 0;; ++attempt) {
+    if (tid == 0) { sh_total = 0u; sh_ovp = 0u; }
+    __syncthreads();
+    uint32_t tot = 0, ovp = 0;
+    for (int r = 0; r < rounds; ++r) {
+      const int s = kSweepEntries * (tid + kSelThreads * r), list = s / T;
+      if (s % T == 0 && list < n_reg) {               // the thread that owns the head of a list counts it
+        const uint32_t c = min((r == 0 && have_e0) ? c0 : ccount[list], cap_w);
+        tot += c;
+        if (c > (uint32_t)T) ovp = max(ovp, (c - T + T - 1) / T);
+      }
+    }
+    if (tot) atomicAdd(&sh_total, tot);
+    if (ovp) atomicMax(&sh_ovp, ovp);
+    __syncthreads();
+    max_passes = (int)sh_ovp;
+    n_sweeps = rounds + rounds * max_passes;
+    if (sh_total >= (uint32_t)Ksel || attempt > 0) break;
+    __syncthreads();
+    // (every workgroup of the head rescans and writes the same lists: identical values, no ordering needed)
+    rescan_head<D, TPI>(g, pr, blk, gq, n, n_chunks);
+    have_e0 = false;
+    __syncthreads();
+  }
+  const uint32_t total = sh_total;
+  TKPHI_PHASE(ws, 11);
+  if (total < (uint32_t)Ksel) {                     // cannot happen after a rescan (every mid token is a candidate)
+    if (tid == 0 && part == 0) *plan = SelPlan{-1, 0, 0, 0, 0};
+    return;
+  }
+
+  // ---- pass A: histogram of the candidates' fine bins ----------------------------------------------------------
+  for (int i = tid; i < kFineBins; i += kSelThreads) sh_hist[i] = 0u;
+  if (tid == 0) { sh_bstar = -1; sh_krem = 0; sh_chi = 0; sh_nb = 0; sh_nbc = 0; sh_thr = 0ull; }
+  __syncthreads();
+  for (int sw = 0; sw < n_sweeps; ++sw) {
+    const Share sh = share_of(sw, tid, (sw == 0 && have_e0) ? (int)min(c0, cap_w) : -1);
+    u32x4 e[kSweepLoads];
+    if (sw == 0 && have_e0) {
+#pragma unroll
+      for (int u = 0; u < kSweepLoads; ++u) e[u] = e0[u];
+    } else {
+      load_share(sh, e);
+      if (sw == 0) {
+#pragma unroll
+        for (int u = 0; u < kSweepLoads; ++u) e0[u] = e[u];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < kSweepEntries; ++i)
+      if (i < sh.nvalid) atomicAdd(&sh_hist[fine_bin(score_key(__uint_as_float(entry(e, i).x)))], 1u);
+  }
+  __syncthreads();
+  TKPHI_PHASE(ws, 12);
+  {
+    // thread t looks at bins kFineBins - 1 - 2t and kFineBins - 2 - 2t: a prefix scan over t is a suffix scan over the bins
+    const int b1 = kFineBins - 1 - 2 * tid, b2 = b1 - 1;
+    const int c1 = (int)sh_hist[b1], c2 = (int)sh_hist[b2];
+    const int incl = sel_scan_incl(c1 + c2, sh_scan);
+    const int gt1 = incl - c1 - c2, ge1 = gt1 + c1, ge2 = incl;
+    if (ge1 >= Ksel && gt1 < Ksel) { sh_bstar = b1; sh_krem = Ksel - gt1; sh_chi = gt1; sh_nb = c1; }
+    if (ge2 >= Ksel && ge1 < Ksel) { sh_bstar = b2; sh_krem = Ksel - ge1; sh_chi = ge1; sh_nb = c2; }
+    __syncthreads();
+  }
+  const int bstar = sh_bstar, krem = sh_krem, c_hi = sh_chi, nb = sh_nb;
+  if (bstar < 0) {                                  // cannot happen: total >= Ksel
+    if (tid == 0 && part == 0) *plan = SelPlan{-1, 0, 0, 0, 0};
+    return;
+  }
+  TKPHI_PHASE(ws, 13);
+
+  // ---- thr: the K_rem-th best composite of the boundary bin ------------------------------------------------
+  if (nb <= kBCap) {
+    // stage the boundary candidates (any order: ranks do not depend on it), then rank by counting the larger
+    // composites, 8 lanes per candidate; the candidate of rank K_rem - 1 is the threshold
+    for (int sw = 0; sw < n_sweeps; ++sw) {
+      const Share sh = share_of(sw, tid, (sw == 0 && have_e0) ? (int)min(c0, cap_w) : -1);
+      u32x4 e[kSweepLoads];
+      if (sw == 0) {
+#pragma unroll
+        for (int u = 0; u < kSweepLoads; ++u) e[u] = e0[u];
+      } else {
+        load_share(sh, e);
+      }
+#pragma unroll
+      for (int i = 0; i < kSweepEntries; ++i) {
+        if (i < sh.nvalid) {
+          const uint2 en = entry(e, i);
+          const uint32_t key = score_key(__uint_as_float(en.x));
+          if (fine_bin(key) == bstar) {
+            const int at = atomicAdd(&sh_nbc, 1);
+            if (at < kBCap) bcand[at] = composite(key, en.y);
+          }
+        }
+      }
+    }
+    __syncthreads();
+    const int sub = tid & 7, slot = tid >> 3;
+    for (int k0 = 0; k0 < nb; k0 += kSelThreads / 8) {
+      const int j = k0 + slot;
+      const bool valid = j < nb;
+      const uint64_t mine = valid ? bcand[j] : ~0ull;
+      int rank = 0;
+      int i = sub;
+      for (; i + 24 < nb; i += 32) {
+        const uint64_t x0 = bcand[i], x1 = bcand[i + 8], x2 = bcand[i + 16], x3 = bcand[i + 24];
+        rank += (x0 > mine ? 1 : 0) + (x1 > mine ? 1 : 0) + (x2 > mine ? 1 : 0) + (x3 > mine ? 1 : 0);
+      }
+      for (; i < nb; i += 8) rank += bcand[i] > mine ? 1 : 0;
+      rank += __shfl_xor(rank, 1);
+      rank += __shfl_xor(rank, 2);
+      rank += __shfl_xor(rank, 4);
+      if (valid && sub == 0 && rank == krem - 1) sh_thr = mine;
+    }
+    __syncthreads();
+  } else {
+    // the slot (sweep, thread, entry) as one index for the radix passes (e.g. all scores equal)
+    auto get = [&](int j, uint64_t* v) {
+      const int sw = j / (kSelThreads * kSweepEntries), rem = j % (kSelThreads * kSweepEntries);
+      const Share sh = share_of(sw, rem / kSweepEntries);
+      const int i = rem % kSweepEntries;
+      if (i >= sh.nvalid) return false;
+      const uint2 e = sh.src[i];
+      const uint32_t key = score_key(__uint_as_float(e.x));
+      *v = composite(key, e.y);
+      return fine_bin(key) == bstar;
+    };
+    const uint64_t t = radix_select_desc(n_sweeps * kSelThreads * kSweepEntries, krem, get, sh_hist, sh_scan, &sh_prefix, &sh_want);
+    if (tid == 0) sh_thr = t;
+    __syncthreads();
+  }
+  const uint64_t thr = sh_thr;
+  TKPHI_PHASE(ws, 14);
+  if (tid == 0 && part == 0) *plan = SelPlan{bstar, krem, c_hi, nb, Ksel};
+
+  // ---- this workgroup's winners: lists [l0, l1), in list order -----------------------------------------------
+  const int split = (int)gridDim.x;
+  const int per_part = (n_reg + split - 1) / split;
+  const int l0 = part * per_part, l1 = min(n_reg, l0 + per_part);
+  int my_base = 0, my_count = 0;                    // winners in earlier lists; winners of this workgroup seen so far
+  for (int sw = 0; sw < n_sweeps; ++sw) {
+    const Share sh = share_of(sw, tid, (sw == 0 && have_e0) ? (int)min(c0, cap_w) : -1);
+    u32x4 e[kSweepLoads];
+    if (sw == 0) {
+#pragma unroll
+      for (int u = 0; u < kSweepLoads; ++u) e[u] = e0[u];
+    } else {
+      load_share(sh, e);
+    }
+    uint32_t fw = 0;                                // bit i: entry i is retrieved
+#pragma unroll
+    for (int i = 0; i < kSweepEntries; ++i) {
+      if (i < sh.nvalid) {
+        const uint2 en = entry(e, i);
+        if (composite(score_key(__uint_as_float(en.x)), en.y) >= thr) fw |= 1u << i;
+      }
+    }
+    const int nw = __popc(fw);
+    const bool mine = sh.list >= l0 && sh.list < l1;
+    // (winners of one sweep: <= 12288 mine, <= 12288 before: 16 bits each)
+    const int packed = (mine ? nw : 0) | ((sh.list < l0 ? nw : 0) << 16);
+    const int incl = sel_scan_incl(packed, sh_scan);
+    if (tid == kSelThreads - 1) sh_tot = incl;
+    int at = my_count + ((incl - packed) & 0xffff);   // rank among this workgroup's winners
+    __syncthreads();
+    const int tot = sh_tot;
+    if (mine) {
+#pragma unroll
+      for (int i = 0; i < kSweepEntries; ++i) {
+        if (fw & (1u << i)) {
+          const uint2 en = entry(e, i);
+          if (at < kWinLds) { w_tok[at] = (int)en.y; w_s[at] = __uint_as_float(en.x); }
+          // (global position: filled in below, once the winners of earlier lists in later sweeps are known)
+          ++at;
+        }
+      }
+    }
+    my_count += tot & 0xffff;
+    my_base += tot >> 16;
+    __syncthreads();
+  }
+  // the retrieved list of the head, for the exports of the merge kernel and for winners beyond the LDS stage:
+  // a second pass writes this workgroup's winners at my_base + rank (list positions never leave [0, Ksel))
+  {
+    int seen = 0;
+    const bool need_global = my_count > kWinLds;
+    for (int sw = 0; sw < n_sweeps; ++sw) {
+      const Share sh = share_of(sw, tid, (sw == 0 && have_e0) ? (int)min(c0, cap_w) : -1);
+      const bool mine = sh.list >= l0 && sh.list < l1;
+      if (n_sweeps == 1 && !need_global && !pr.topk_idx) break;     // (nothing reads the list)
+      u32x4 e[kSweepLoads];
+      if (sw == 0) {
+#pragma unroll
+        for (int u = 0; u < kSweepLoads; ++u) e[u] = e0[u];
+      } else {
+        load_share(sh, e);
+      }
+      uint32_t fw = 0;
+#pragma unroll
+      for (int i = 0; i < kSweepEntries; ++i) {
+        if (mine && i < sh.nvalid) {
+          const uint2 en = entry(e, i);
+          if (composite(score_key(__uint_as_float(en.x)), en.y) >= thr) fw |= 1u << i;
+        }
+      }
+      const int nw = __popc(fw);
+      const int incl = sel_scan_incl(nw, sh_scan);
+      if (tid == kSelThreads - 1) sh_tot = incl;
+      int at = my_base + seen + incl - nw;
+#pragma unroll
+      for (int i = 0; i < kSweepEntries; ++i) {
+        if (fw & (1u << i)) {
+          const uint2 en = entry(e, i);
+          if (at < min(Ksel, g.max_K)) { sel_idx[at] = (int32_t)en.y; sel_score[at] = __uint_as_float(en.x); }
+          ++at;
+        }
+      }
+      __syncthreads();
+      seen += sh_tot;
+      __syncthreads();
+    }
+  }
+  TKPHI_PHASE(ws, 15);
+
+  // ---- gather: 256 winners per round, 16 per wavefront ---------------------------------------------------------
+  const int r = lane & 15, kg = lane >> 4;
+  const int64_t head_off = (int64_t)h * pr.stride_head;
+  const float* phiq = (const float*)(blk + g.off_phiq) + (size_t)gq * D;
+  constexpr int LPR = D / 8;                        // lanes per value row (16 bytes each)
+  constexpr int RPP = kSelThreads / LPR;            // rows per pass (64 or 128)
+  constexpr int NPASS = kBatch / RPP;               // 4 or 2
+  const int seg = tid % LPR, rsub = tid / LPR;
+  float run_m = -INFINITY, run_Z = 0.f, run_zs = 0.f, run_nu = 0.f, run_zv = 0.f;   // (nu, zv: channel tid < D)
+  __syncthreads();                                  // lds_a changes hands; the staged Wk is complete
+  for (int b0 = 0; b0 < my_count; b0 += kBatch) {
+    const int cnt = min(kBatch, my_count - b0);
+    // this thread's token of the batch (thread t < 256 <-> winner b0 + t)
+    auto winner = [&](int j, int* tok, float* s) {
+      const int i = b0 + min(j, cnt - 1);
+      if (i < kWinLds) { *tok = w_tok[i]; *s = w_s[i]; }
+      else { *tok = sel_idx[min(my_base + i, g.max_K - 1)]; *s = sel_score[min(my_base + i, g.max_K - 1)]; }
+      *tok = g.n_sink + min(max(*tok, 0), n - 1);
+    };
+    // value rows: all passes' loads in flight (they only need the token indices)
+    u32x4 vrow[NPASS];
+    int vtok;
+    float vs;
+#pragma unroll
+    for (int ps = 0; ps < NPASS; ++ps) {
+      if (ps * RPP < cnt) {
+        winner(ps * RPP + rsub, &vtok, &vs);
+        vrow[ps] = gload128((const char*)pr.V + (head_off + (int64_t)vtok * pr.stride_tok + seg * 8) * 2);
+      }
+    }
+    // batch maximum of the scores
+    if (tid < kBatch) {
+      int tk; float s;
+      winner(tid, &tk, &s);
+      b_w[tid] = tid < cnt ? s : -INFINITY;         // (scores for now)
+    }
+    __syncthreads();
+    if (wv == 0) {
+      float mloc = fmaxf(fmaxf(b_w[lane], b_w[lane + 64]), fmaxf(b_w[lane + 128], b_w[lane + 192]));
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) mloc = fmaxf(mloc, __shfl_xor(mloc, o));
+      if (lane == 0) sh_m = mloc;
+    }
+    // z_i of this wavefront's 16 tokens
+    if (wv * 16 < cnt) {
+      int tk; float s;
+      winner(wv * 16 + r, &tk, &s);
+      const char* rp = (const char*)pr.K + (head_off + (int64_t)tk * pr.stride_tok) * 2 + kg * 16;
+      GatherFrag a[KS];
+#pragma unroll
+      for (int j = 0; j < KS; ++j) a[j].u = gload128(rp + j * 64);
+      float z[4];
+      wave_feature_dots<D>(a, wk_lds, pr.bk + (size_t)h * D, phiq, g.a, g.c, z);
+      if (r == 0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) b_z[wv * 16 + 4 * kg + i] = (wv * 16 + 4 * kg + i < cnt) ? z[i] : 0.f;
+      }
+    } else if (lane < 16) {
+      b_z[wv * 16 + lane] = 0.f;
+    }
+    __syncthreads();
+    const float mloc = sh_m;
+    if (tid < kBatch) b_w[tid] = tid < cnt ? __expf(b_w[tid] - mloc) : 0.f;
+    __syncthreads();
+    // weighted value sums: rows of one wavefront that share a segment, then the 16 wavefronts
+    float an[8], az[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { an[e] = 0.f; az[e] = 0.f; }
+#pragma unroll
+    for (int ps = 0; ps < NPASS; ++ps) {
+      const int i = ps * RPP + rsub;
+      if (ps * RPP < cnt && i < cnt) {
+        float x[8];
+        Elem<uint16_t>::unpack(make_uint4(vrow[ps].x, vrow[ps].y, vrow[ps].z, vrow[ps].w), x);
+        const float wi = b_w[i], zi = b_z[i];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { an[e] = fmaf(wi, x[e], an[e]); az[e] = fmaf(zi, x[e], az[e]); }
+      }
+    }
+    for (int o = LPR; o < 64; o <<= 1) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { an[e] += __shfl_xor(an[e], o); az[e] += __shfl_xor(az[e], o); }
+    }
+    if (lane < LPR) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { red[(wv * 2 + 0) * 128 + lane * 8 + e] = an[e]; red[(wv * 2 + 1) * 128 + lane * 8 + e] = az[e]; }
+    }
+    if (wv == 1) {                                  // Z_loc and zsum of the batch, in a fixed order
+      float Zb = (b_w[lane] + b_w[lane + 64]) + (b_w[lane + 128] + b_w[lane + 192]);
+      float zb = (b_z[lane] + b_z[lane + 64]) + (b_z[lane + 128] + b_z[lane + 192]);
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) { Zb += __shfl_xor(Zb, o); zb += __shfl_xor(zb, o); }
+      if (lane == 0) { sh_Z = Zb; sh_zs = zb; }
+    }
+    __syncthreads();
+    {
+      float nu_b = 0.f, zv_b = 0.f;
+      if (tid < D) {
+        for (int k = 0; k < kSelWaves; ++k) { nu_b += red[(k * 2 + 0) * 128 + tid]; zv_b += red[(k * 2 + 1) * 128 + tid]; }
+      }
+      // running combination with the earlier batches (log-sum-exp rescaling)
+      const float m_new = fmaxf(run_m, mloc);
+      const float so = run_m > -INFINITY ? __expf(run_m - m_new) : 0.f, sb = __expf(mloc - m_new);
+      run_nu = run_nu * so + nu_b * sb;
+      run_Z = run_Z * so + sh_Z * sb;
+      run_zv += zv_b;
+      run_zs += sh_zs;
+      run_m = m_new;
+    }
+    __syncthreads();                                // red, b_w, b_z are rewritten by the next batch
+  }
+  float* partial = (float*)(blk + g.off_part) + ((size_t)gq * (g.n_tiles + g.n_atiles) + part) * g.part_stride;
+  if (tid == 0) { partial[0] = run_m; partial[1] = run_Z; partial[2] = run_zs; partial[3] = (float)my_count; }
+  if (tid < D) { partial[4 + tid] = run_nu; partial[4 + D + tid] = run_zv; }
+  TKPHI_PHASE(ws, 16);
+}
+
+void launch_select_gather(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
+  dim3 grid(g.n_tiles, g.Hq, g.n_problems);        // (filtered pipeline: n_tiles = workgroups per query head)
+  if (g.d == 128) TKPHI_LAUNCH(ST_SELECT, (select_gather_kernel<128, 4>), grid, dim3(kSelThreads), 0, s, g, probs, ws);
+  else TKPHI_LAUNCH(ST_SELECT, (select_gather_kernel<64, 8>), grid, dim3(kSelThreads), 0, s, g, probs, ws);
+}
+
+}  // namespace tkphi

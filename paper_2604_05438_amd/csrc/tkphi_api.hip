@@ -65,12 +65,13 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   const tkphi_tuning& tn = cfg->tuning;
   if (tn.force_generic < 0 || tn.force_generic > 1 || tn.scan_chunk < 0 || tn.scan_chunk > 32768 || tn.interleave < 0 ||
       tn.interleave > 2 || tn.build_chunk < 0 || tn.build_chunk > (1 << 20) || tn.mlp_block < 0 || tn.mlp_block > 8192 ||
-      tn.mlp_mode < 0 || tn.mlp_mode > 2) {
-    set_error("tuning field out of range (force_generic=%d scan_chunk=%d interleave=%d build_chunk=%d mlp_block=%d mlp_mode=%d)",
-              tn.force_generic, tn.scan_chunk, tn.interleave, tn.build_chunk, tn.mlp_block, tn.mlp_mode);
+      tn.mlp_mode < 0 || tn.mlp_mode > 2 || tn.select_mode < 0 || tn.select_mode > 2 || tn.select_test < 0 || tn.select_test > 2) {
+    set_error("tuning field out of range (force_generic=%d scan_chunk=%d interleave=%d build_chunk=%d mlp_block=%d mlp_mode=%d "
+              "select_mode=%d select_test=%d)", tn.force_generic, tn.scan_chunk, tn.interleave, tn.build_chunk, tn.mlp_block,
+              tn.mlp_mode, tn.select_mode, tn.select_test);
     return TKPHI_EINVAL;
   }
-  for (int i = 0; i < 6; ++i)
+  for (int i = 0; i < 4; ++i)
     if (tn.reserved[i] != 0) { set_error("tuning.reserved[%d] must be 0", i); return TKPHI_EINVAL; }
   if (n_problems > 65535) { set_error("n_problems=%d exceeds 65535", n_problems); return TKPHI_ESHAPE; }
   if (cfg->n_sink < 0 || cfg->n_tail < 0) {
@@ -112,8 +113,16 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   // (many problems) contiguous ranges are faster
   g->interleave = tn.interleave ? (tn.interleave == 1 ? 1 : 0) : (g->use_mfma && g->scan_unit < g->scan_chunk && g->n_scan_chunks >= 64) ? 1 : 0;
   if (!g->use_mfma || g->scan_unit >= g->scan_chunk) g->interleave = 0;
+  // filtered pipeline: where the matrix-core score kernel applies and the budget is a small share of the
+  // mid-region (with a large share nearly every score would be a candidate and the lists cost more than the spill)
+  g->filtered = (g->use_mfma && cfg->phi_kind == TKPHI_PHI_EXP_AFFINE && !g->cache && tn.select_mode != 1 &&
+                 (tn.select_mode == 2 || (int64_t)max_K * 8 <= g->max_mid)) ? 1 : 0;
+  g->sel_test = tn.select_test;
   // gather: tiles of kPairsPerWG retrieved tokens per query head
   g->n_tiles = (int)ceil_div(std::min<int64_t>(max_K, g->max_mid), kPairsPerWG);
+  // (filtered pipeline: the workgroups that share a query head in the fused select + gather kernel, one
+  // partial each: about one workgroup per CU for a single layer, one per head in big batches)
+  g->sg_split = g->filtered ? std::clamp(256 / std::max(1, g->Hq * std::max(n_problems, 1)), 1, 16) : 0;
   g->n_atiles = (int)std::max<int64_t>(1, ceil_div(std::min<int64_t>((int64_t)cfg->n_sink + cfg->n_tail, max_L) + cfg->max_gen, 64));
   // summary_build: 512 workgroups fill the chip (2 per CU); larger jobs get about 2048 chunks of at
   // least 2048 tokens so that the last, partly filled round of workgroups stays a small share
@@ -127,10 +136,22 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
 
   // workspace layout
   size_t off = 0;
-  g->off_status = off; off += 256;
+  g->off_status = off; off += 4096;
   g->off_problem0 = off;
   size_t p = 0;
-  g->off_scores = p;  p = align_up(p + (size_t)g->Hq * g->mid_stride * sizeof(float), 256);
+  g->off_scores = p;
+  g->off_candf = p;     // (the two pipelines never run in the same call)
+  p = align_up(p + std::max((size_t)g->Hq * g->mid_stride * sizeof(float),
+                            g->filtered ? (size_t)g->Hq * g->n_scan_chunks * g->scan_chunk * sizeof(uint2) : (size_t)0), 256);
+  // compact part of a candidate list: 24 entries, or 3/32 of the list's capacity if that is more (about three
+  // times the expected length); with 128 chunks per head the compact lists of a head are one sweep of the
+  // fused select + gather kernel
+  g->cand_T = (int)align_up((size_t)std::max(24, g->scan_chunk / 4 * 3 / 32), 12);
+  g->off_candc = p;   p = align_up(p + (g->filtered ? (size_t)g->Hq * g->n_scan_chunks * 4 * g->cand_T * sizeof(uint2) : (size_t)0), 256);
+  g->off_ccount = p;  p = align_up(p + (g->filtered ? (size_t)g->Hq * g->n_scan_chunks * 4 * sizeof(uint32_t) : (size_t)0), 256);
+  g->off_thr = p;     p = align_up(p + (size_t)g->Hq * sizeof(uint32_t), 256);
+  g->off_sphi = p;    p = align_up(p + (size_t)g->Hq * g->d * sizeof(float), 256);
+  g->off_uphi = p;    p = align_up(p + (size_t)g->Hq * sizeof(float), 256);
   g->off_hist = p;    p = align_up(p + (size_t)g->n_scan_chunks * g->Hq * kBins * sizeof(uint16_t), 256);
   g->off_plan = p;    p = align_up(p + (size_t)g->Hq * sizeof(SelPlan), 256);
   g->off_diag = p;    p = align_up(p + (size_t)g->n_scan_chunks * g->Hq * 4 * sizeof(float), 256);
@@ -141,7 +162,7 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   g->off_phiq = p;    p = align_up(p + (size_t)g->Hq * g->dphi * sizeof(float), 256);
   g->off_mlpq = p;    p = align_up(p + (size_t)g->Hq * 2 * g->d_emb * sizeof(float), 256);
   g->off_part = p;
-  p = align_up(p + (size_t)g->Hq * (g->n_tiles + g->n_atiles) * g->part_stride * sizeof(float), 256);
+  p = align_up(p + (size_t)g->Hq * (std::max(g->n_tiles, g->sg_split) + g->n_atiles) * g->part_stride * sizeof(float), 256);
   g->per_problem = p;
   const size_t decode_total = g->off_problem0 + (size_t)std::max(n_problems, 1) * g->per_problem;
   g->decode_bytes = align_up(decode_total, 256);
@@ -164,6 +185,7 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
     build_all = g->off_wpack + (size_t)g->Hkv * ((size_t)g->d_emb * g->d + (size_t)2 * g->d_emb * g->d_emb +
                                                  (size_t)g->dphi * g->d_emb) * 2;
   }
+  g->build_bytes = align_up(build_all, 256);
   g->total_bytes = align_up(std::max(decode_total, build_all), 256);
   return TKPHI_OK;
 }
@@ -206,7 +228,7 @@ tkphi_status tkphi_build_summaries(const tkphi_config* cfg, const tkphi_problem*
   Geom g;
   tkphi_status st = make_geom(cfg, n_problems, max_L, 0, &g);
   if (st != TKPHI_OK) return st;
-  st = check_call(problems, n_problems, workspace, workspace_bytes, g);
+  st = check_call(problems, n_problems, workspace, workspace_bytes, g, g.build_bytes);   // (the decode scratch depends on max_K)
   if (st != TKPHI_OK) return st;
   if (n_problems == 0) return TKPHI_OK;
   hipStream_t s = (hipStream_t)hip_stream;
@@ -253,11 +275,20 @@ static tkphi_status side_stream(SideStream** out) {
 }
 
 static tkphi_status enqueue_decode(const Geom& g, const tkphi_problem* problems, char* ws, int acct, hipStream_t s) {
+  if (g.filtered && !g.diag) {         // (the diagnostics are by-products of the spill pipeline's emit pass)
+    Geom gf = g;
+    gf.n_tiles = g.sg_split;           // one partial per workgroup of the fused select + gather kernel
+    launch_prep(gf, problems, ws, s);
+    launch_score_filtered(gf, problems, ws, s);
+    launch_select_gather(gf, problems, ws, s);
+    launch_merge(gf, problems, ws, acct, true, s);
+    return TKPHI_OK;
+  }
   if (g.phi_kind != TKPHI_PHI_MLP) {
     launch_score_mid(g, problems, ws, s);
     launch_select(g, problems, ws, s);
     launch_gather(g, problems, ws, s);
-    launch_merge(g, problems, ws, acct, s);
+    launch_merge(g, problems, ws, acct, false, s);
     return TKPHI_OK;
   }
   std::lock_guard<std::mutex> lock(g_side_mutex);
@@ -276,7 +307,7 @@ static tkphi_status enqueue_decode(const Geom& g, const tkphi_problem* problems,
   if (st != TKPHI_OK) return st;
   if (st2 != TKPHI_OK) return st2;
   launch_gather(g, problems, ws, s);
-  launch_merge(g, problems, ws, acct, s);
+  launch_merge(g, problems, ws, acct, false, s);
   return TKPHI_OK;
 }
 
@@ -292,7 +323,7 @@ tkphi_status tkphi_decode(const tkphi_config* cfg, const tkphi_problem* problems
   tkphi_status st = make_geom(cfg, n_problems, max_L, max_K, &g);
   g.diag = (mode & TKPHI_FLAG_DIAG) ? 1 : 0;
   if (st != TKPHI_OK) return st;
-  st = check_call(problems, n_problems, workspace, workspace_bytes, g);
+  st = check_call(problems, n_problems, workspace, workspace_bytes, g, g.decode_bytes);
   if (st != TKPHI_OK) return st;
   if (n_problems == 0) return TKPHI_OK;
   hipStream_t s = (hipStream_t)hip_stream;
@@ -376,7 +407,7 @@ tkphi_status tkphi_decode_stage_times(const tkphi_config* cfg, const tkphi_probl
   tkphi_status st = make_geom(cfg, n_problems, max_L, max_K, &g);
   g.diag = (mode & TKPHI_FLAG_DIAG) ? 1 : 0;
   if (st != TKPHI_OK) return st;
-  st = check_call(problems, n_problems, workspace, workspace_bytes, g);
+  st = check_call(problems, n_problems, workspace, workspace_bytes, g, g.decode_bytes);
   if (st != TKPHI_OK) return st;
   for (int i = 0; i < TKPHI_N_STAGES; ++i) stage_ms_out[i] = 0.f;
   if (n_problems == 0) return TKPHI_OK;

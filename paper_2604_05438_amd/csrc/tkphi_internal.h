@@ -42,7 +42,13 @@ struct Geom {
   int diag;              // 1: the select emit pass also reduces the entropy / mass diagnostics
   int interleave;        // 1: chunk c owns the units c, c + n_chunks, c + 2 n_chunks, ... of its problem
                          // (all workgroups sweep the key cache together); 0: one contiguous range
-  int n_tiles;           // gather: ceil(max_K / kPairsPerWG) retrieved-token tiles per query head
+  int filtered;          // 1: decode may run the filtered pipeline (prep, score_filtered, select_gather, merge):
+                         // bf16 matrix-core shapes, exp-affine maps, budgets well below the mid-region size
+  int cand_T;            // filtered pipeline: entries of a candidate list kept in the compact array (multiple of 12)
+  int sel_test;          // tkphi_tuning::select_test (0 unless a test forces the rescan or the no-pruning path)
+  int n_tiles;           // gather: ceil(max_K / kPairsPerWG) retrieved-token tiles per query head; one partial each
+  int sg_split;          // filtered pipeline: workgroups per query head of the fused select + gather kernel (0 if it cannot run);
+                         // that pipeline's launchers get a Geom whose n_tiles is this number
   int n_atiles;          // gather: ceil((n_sink + n_tail + max_gen) / 64) tiles of exact anchors + generated tokens per query head (>= 1)
   int build_chunk, n_build_chunks;   // summary_build: mid tokens per workgroup
   int part_stride;       // floats per partial: 2*d + 4
@@ -52,7 +58,15 @@ struct Geom {
   size_t off_problem0;   // first per-problem block
   size_t per_problem;    // bytes per problem block
   // offsets inside a per-problem block
-  size_t off_scores;     // float    [Hq][mid_stride]            mid-region scores
+  size_t off_scores;     // float    [Hq][mid_stride]            mid-region scores (spill pipeline)
+  size_t off_candf;      // uint2    [Hq][n_scan_chunks][4][scan_chunk/4]  candidate lists (score bits, mid index) of the filtered
+                         //                                       pipeline at full capacity (entries past the first cand_T of a
+                         //                                       list land here); shares its memory with off_scores
+  size_t off_candc;      // uint2    [Hq][n_scan_chunks][4][cand_T]  the first cand_T entries of every list
+  size_t off_ccount;     // uint32   [Hq][n_scan_chunks][4]      lengths of the candidate lists
+  size_t off_thr;        // uint32   [Hq]                        lower bound of the score key per query head
+  size_t off_sphi;       // float    [Hq][d]                     S_M^T phi_q
+  size_t off_uphi;       // float    [Hq]                        phi_q . u_M
   size_t off_hist;       // uint16   [n_scan_chunks][Hq][kBins]  per-chunk histograms
   size_t off_plan;       // SelPlan  [Hq]
   size_t off_diag;       // float    [n_scan_chunks][Hq][4]      per-chunk (max, sum exp, sum (s-max) exp) of the scores
@@ -67,6 +81,7 @@ struct Geom {
   size_t off_act;        // float    2 x [Hkv][mlp_block][d_emb]          (MLP build only: activations g, h of a token block)
   size_t off_wpack;      // bf16     [Hkv][Ws | W1 | W2 | Wo]        (MLP build only: one problem's key-side weights in MFMA-fragment order)
   size_t decode_bytes;   // what a decode call alone uses (status word + per-problem blocks)
+  size_t build_bytes;    // what a summary build alone uses
   size_t total_bytes;    // the larger of decode and build
 };
 
@@ -76,7 +91,7 @@ void set_error(const char* fmt, ...);
 
 // Optional per-kernel timing: while g_kernel_timer is set (by tkphi_decode_stage_times, on
 // the calling thread) a launch records the kernel's own begin / end on the two events.
-enum Stage { ST_SCORE = 0, ST_PLAN, ST_EMIT, ST_RESOLVE, ST_GATHER, ST_MERGE, ST_PHIQ, ST_COUNT, ST_UNTIMED = -1 };
+enum Stage { ST_SCORE = 0, ST_PLAN, ST_EMIT, ST_RESOLVE, ST_GATHER, ST_MERGE, ST_PHIQ, ST_PREP, ST_SELECT, ST_COUNT, ST_UNTIMED = -1 };
 struct KernelTimer {
   hipEvent_t start[ST_COUNT], stop[ST_COUNT];
   bool used[ST_COUNT];
@@ -107,8 +122,12 @@ constexpr int kMaxScanChunks = 2048;   // chunk offsets are scanned in LDS by `p
 // kernel launchers (each defined next to its kernels)
 void launch_score_mid(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
 void launch_select(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
+void launch_prep(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);              // filtered pipeline
+void launch_score_filtered(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
+void launch_select_gather(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
 void launch_gather(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
-void launch_merge(const Geom& g, const tkphi_problem* probs, char* ws, int mode, hipStream_t s);
+// `pre`: the prep kernel has already produced the anchor partials and the summary terms S_M^T phi_q, phi_q . u_M
+void launch_merge(const Geom& g, const tkphi_problem* probs, char* ws, int mode, bool pre, hipStream_t s);
 void launch_build(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
 void launch_mlp_features(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);     // -> phi_cache
 void launch_mlp_phi_q(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);        // -> phi_q of every query head
@@ -330,6 +349,20 @@ __device__ __forceinline__ void write_device_status(const Geom& g, const tkphi_p
   bad = __syncthreads_or(bad);
   if (threadIdx.x == 0) *(uint32_t*)(ws + g.off_status) = bad ? TKPHI_DEV_BAD_LENGTH : 0u;
 }
+
+// Development aid (compiled in only with -DTKPHI_PHASE_CLOCK): thread 0 of workgroup (0, 0, 0) stores the
+// 100 MHz wall clock at numbered points of a kernel behind the status word (ws + 16 + 8 slot).
+#ifdef TKPHI_PHASE_CLOCK
+#define TKPHI_PHASE(ws, slot)                                                                                   \
+  do {                                                                                                          \
+    if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)                              \
+      ((unsigned long long*)((ws) + 16))[(slot)] = wall_clock64();                                              \
+  } while (0)
+#define TKPHI_PHASE_VALUE(ws, slot, v) (((unsigned long long*)((ws) + 16))[(slot)] = (unsigned long long)(v))
+#else
+#define TKPHI_PHASE(ws, slot) do {} while (0)
+#define TKPHI_PHASE_VALUE(ws, slot, v) do {} while (0)
+#endif
 
 // mid-region size of a problem; 0 if the anchors cover everything
 __device__ __forceinline__ int mid_size(int L, int n_sink, int n_tail) {

@@ -19,66 +19,10 @@
 // Ties go to the lower index.  If the boundary bin holds more than kCandCap tokens (e.g. all
 // scores equal) `resolve` falls back to radix passes over the score row in global memory:
 // slower, same result.  The ascending export of the retrieved set is written by the merge kernel.
+#include "select_utils.h"
 #include "tkphi_internal.h"
 
 namespace tkphi {
-
-constexpr int kSelWaves = kSelThreads / 64;
-
-// inclusive prefix sum over the 1024 threads; sh must hold >= 16 ints; two barriers
-__device__ __forceinline__ int sel_scan_incl(int v, int* sh) {
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  int x = v;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int y = __shfl_up(x, o);
-    if (lane >= o) x += y;
-  }
-  if (lane == 63) sh[w] = x;
-  __syncthreads();
-  int add = 0;
-  for (int i = 0; i < w; ++i) add += sh[i];
-  __syncthreads();
-  return x + add;
-}
-
-__device__ __forceinline__ uint64_t composite(uint32_t key, uint32_t row) {
-  return ((uint64_t)key << 32) | (uint64_t)(0xffffffffu - row);
-}
-
-// `want`-th largest (1-based) 64-bit composite among `count` elements delivered by
-// get(j, &composite) -> bool (false: element does not take part).  8 radix passes of 8
-// bits.  All threads must call; returns the composite in every thread.
-template <typename Get>
-__device__ uint64_t radix_select_desc(int count, int want, Get get, uint32_t* sh_hist /*[256]*/,
-                                      int* sh_scan /*[16]*/, uint64_t* sh_prefix, int* sh_want) {
-  const int tid = threadIdx.x;
-  if (tid == 0) { *sh_prefix = 0ull; *sh_want = want; }
-  __syncthreads();
-  for (int shift = 56; shift >= 0; shift -= 8) {
-    if (tid < 256) sh_hist[tid] = 0u;
-    __syncthreads();
-    const uint64_t prefix = *sh_prefix;
-    const int w = *sh_want;
-    const uint64_t himask = shift == 56 ? 0ull : (~0ull << (shift + 8));
-    for (int j = tid; j < count; j += kSelThreads) {
-      uint64_t v;
-      if (get(j, &v) && (v & himask) == prefix) atomicAdd(&sh_hist[(uint32_t)(v >> shift) & 255u], 1u);
-    }
-    __syncthreads();
-    // thread t < 256 looks at digit 255 - t: prefix scan over t == suffix scan over digits
-    const int digit = 255 - tid;
-    const int c = tid < 256 ? (int)sh_hist[digit] : 0;
-    const int incl = sel_scan_incl(c, sh_scan);
-    const int excl = incl - c;
-    if (tid < 256 && excl < w && w <= incl) {
-      *sh_prefix = prefix | ((uint64_t)digit << shift);
-      *sh_want = w - excl;
-    }
-    __syncthreads();
-  }
-  return *sh_prefix;
-}
 
 // the 8 uint16 counts a lane holds after a 16-byte load of a chunk histogram row
 __device__ __forceinline__ void unpack_counts(const u32x4& v, uint32_t* c) {

@@ -23,7 +23,7 @@ def config_of(w: Workload, cache_features: bool = False, d_emb: int = 0, max_gen
     generated tokens a problem may append after its prefill rows; tuning: tkphi_tuning fields."""
     return B.make_config(w.n_q_heads, w.n_kv_heads, w.d_head, w.d_phi, w.n_sink, w.n_tail, w.dtype,
                          w.score_scale, w.phi_in_scale, w.phi_norm_coef, int(cache_features or d_emb > 0),
-                         B.TKPHI_PHI_MLP if d_emb > 0 else B.TKPHI_PHI_EXP_AFFINE, d_emb, max_gen)
+                         B.TKPHI_PHI_MLP if d_emb > 0 else B.TKPHI_PHI_EXP_AFFINE, d_emb, max_gen, tuning=tuning)
 
 
 class Batch:

@@ -54,7 +54,7 @@ def test_tuning_overrides_are_validated_and_change_the_geometry():
     base = B.tkphi_workspace_bytes(_cfg(), 1, 32768, 327)
     assert B.tkphi_workspace_bytes(_cfg(tuning={"build_chunk": 64}), 1, 32768, 327) > base   # more chunk partials
     for bad in ({"scan_chunk": -1}, {"scan_chunk": 1 << 20}, {"interleave": 3}, {"force_generic": 2}, {"mlp_mode": 5},
-                {"build_chunk": -64}):
+                {"build_chunk": -64}, {"select_mode": 3}, {"select_test": -1}):
         assert B.tkphi_workspace_bytes(_cfg(tuning=bad), 1, 32768, 327) == 0
         assert "tuning" in B.tkphi_last_error()
     cfg = _cfg()
