@@ -42,16 +42,10 @@ constexpr int kPrepWaves = kPrepThreads / 64;
 // tokens; beyond that n / 64 rows (at least 512, at most 1024) in evenly spaced groups of 16 consecutive rows
 // (one matrix-core tile, one 4 KB page of 256-byte rows: scattered single rows cost a page walk each).
 __device__ __forceinline__ int sample_size(int n) {
-#ifdef TKPHI_SAMPLE_M
-  return min(n, TKPHI_SAMPLE_M);
-#endif
   return n <= 1024 ? n : min(1024, max(512, n / 64)) / 16 * 16;
 }
 // mid row of sample si (0 <= si < m)
 __device__ __forceinline__ int sample_row(int si, int n, int m) {
-#ifdef TKPHI_SAMPLE_CONTIG
-  return si;
-#endif
   return m >= n ? si : (si >> 4) * (n / (m >> 4)) + (si & 15);
 }
 

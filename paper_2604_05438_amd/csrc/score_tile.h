@@ -39,20 +39,22 @@ __device__ __forceinline__ size_t cand_region(const Geom& g, int gq, int chunk, 
 // One wavefront: slot `wslot` of chunk `chunk` of KV head h (n mid tokens, n_chunks chunks).
 //   edge_r   lower bound of the score key for the query head of this lane's column r (ignored for r >= G)
 //   only_gl  -1: every head of the group; else only head h G + only_gl is written
+//   rescan   write the rescan set of lists, compact heads and counts (the select kernel's second attempt reads
+//            only that set, so what a first attempt reads is never overwritten while another workgroup reads it)
 // Lane (r, kg) ends up with the scores of head r for tokens base + t 16 + 4 kg + i, so each list is
 // written by the four lanes of its column, in the order (unit, t, i, kg).
 template <int D, int TPI, int SUB = TPI>   // SUB: 16-token tiles whose loads are in flight together (the rescan keeps registers low)
 __device__ __forceinline__ void scan_wave_slot(const Geom& g, const tkphi_problem& pr, char* blk, int h, int n, int n_chunks,
                                                int chunk, int wslot, const ScoreFrag (&bq)[D / 32], uint32_t edge_r,
-                                               int only_gl) {
+                                               int only_gl, bool rescan = false) {
   constexpr int KS = D / 32;
   constexpr int TOK = TPI * 16;         // tokens per wavefront and unit
   const int lane = threadIdx.x & 63, r = lane & 15, kg = lane >> 4;
   const int G = g.G;
   const bool col_live = r < G && (only_gl < 0 || r == only_gl);
   const int gq = h * G + min(r, G - 1);
-  uint2* list = (uint2*)(blk + g.off_candf) + cand_region(g, gq, chunk, wslot);
-  uint2* head = (uint2*)(blk + g.off_candc) + (((size_t)gq * g.n_scan_chunks + chunk) * 4 + wslot) * (size_t)g.cand_T;
+  uint2* list = (uint2*)(blk + (rescan ? g.off_resf : g.off_candf)) + cand_region(g, gq, chunk, wslot);
+  uint2* head = (uint2*)(blk + (rescan ? g.off_resc : g.off_candc)) + (((size_t)gq * g.n_scan_chunks + chunk) * 4 + wslot) * (size_t)g.cand_T;
   const int cap = g.scan_chunk / 4, T = g.cand_T;
   const uint64_t col_lanes = 0x0001000100010001ull << r;     // the four lanes of this column
   const uint64_t lanes_below = (1ull << lane) - 1ull;
@@ -108,7 +110,7 @@ __device__ __forceinline__ void scan_wave_slot(const Geom& g, const tkphi_proble
     }
   }
   if (col_live && kg == 0)
-    ((uint32_t*)(blk + g.off_ccount))[((size_t)gq * g.n_scan_chunks + chunk) * 4 + wslot] = (uint32_t)min(cnt, cap);
+    ((uint32_t*)(blk + (rescan ? g.off_rescount : g.off_ccount)))[((size_t)gq * g.n_scan_chunks + chunk) * 4 + wslot] = (uint32_t)min(cnt, cap);
 }
 
 // Smallest score key whose first-level bin is >= t (key_bin is monotone in the key), so that

@@ -38,7 +38,8 @@ constexpr int kSweepLoads = kSweepEntries / 2;
 constexpr int kBatch = 256;            // winners gathered per round: 16 per wavefront
 constexpr int kWinLds = 512;           // winners of a workgroup kept in LDS (the rest are re-read from the retrieved list)
 
-// every mid token of query head gq becomes a candidate: the head's lists are rewritten with no bound
+// every mid token of query head gq becomes a candidate: the head's lists are written again with no bound, into
+// the rescan set (what the score pass wrote stays as it is: other workgroups of the head may still be reading it)
 // (one 16-token tile in flight per wavefront: the rare path must not cost the common one registers)
 template <int D, int TPI>
 __device__ __forceinline__ void rescan_head(const Geom& g, const tkphi_problem& pr, char* blk, int gq, int n, int n_chunks) {
@@ -46,7 +47,7 @@ __device__ __forceinline__ void rescan_head(const Geom& g, const tkphi_problem& 
   ScoreFrag bq[D / 32];
   load_query_frags<D>(g, pr, h, bq);
   for (int reg = wv; reg < n_chunks * 4; reg += kSelWaves)
-    scan_wave_slot<D, TPI, 1>(g, pr, blk, h, n, n_chunks, reg >> 2, reg & 3, bq, 0u, gq % g.G);
+    scan_wave_slot<D, TPI, 1>(g, pr, blk, h, n, n_chunks, reg >> 2, reg & 3, bq, 0u, gq % g.G, true);
 }
 
 template <int D, int TPI>
@@ -77,6 +78,7 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, cons
   const int T = g.cand_T;
   const int n_reg_max = g.n_scan_chunks * 4;
   const uint32_t cap_w = (uint32_t)(g.scan_chunk / 4);
+  // (after a rescan these three point at the rescan set)
   const uint32_t* ccount = (const uint32_t*)(blk + g.off_ccount) + (size_t)gq * n_reg_max;
   const uint2* compact = (const uint2*)(blk + g.off_candc) + (size_t)gq * n_reg_max * T;
   const uint2* sparse = (const uint2*)(blk + g.off_candf) + (size_t)gq * n_reg_max * cap_w;
@@ -151,8 +153,12 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, cons
     n_sweeps = rounds + rounds * max_passes;
     if (sh_total >= (uint32_t)Ksel || attempt > 0) break;
     __syncthreads();
-    // (every workgroup of the head rescans and writes the same lists: identical values, no ordering needed)
+    // (every workgroup of the head takes this branch, the counts it depends on being the score pass's, and writes
+    // the same values to the rescan set: no ordering between them is needed)
     rescan_head<D, TPI>(g, pr, blk, gq, n, n_chunks);
+    ccount = (const uint32_t*)(blk + g.off_rescount) + (size_t)gq * n_reg_max;
+    compact = (const uint2*)(blk + g.off_resc) + (size_t)gq * n_reg_max * T;
+    sparse = (const uint2*)(blk + g.off_resf) + (size_t)gq * n_reg_max * cap_w;
     have_e0 = false;
     __syncthreads();
   }

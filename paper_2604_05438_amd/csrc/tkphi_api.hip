@@ -149,6 +149,9 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   g->cand_T = (int)align_up((size_t)std::max(24, g->scan_chunk / 4 * 3 / 32), 12);
   g->off_candc = p;   p = align_up(p + (g->filtered ? (size_t)g->Hq * g->n_scan_chunks * 4 * g->cand_T * sizeof(uint2) : (size_t)0), 256);
   g->off_ccount = p;  p = align_up(p + (g->filtered ? (size_t)g->Hq * g->n_scan_chunks * 4 * sizeof(uint32_t) : (size_t)0), 256);
+  g->off_resf = p;    p = align_up(p + (g->filtered ? (size_t)g->Hq * g->n_scan_chunks * g->scan_chunk * sizeof(uint2) : (size_t)0), 256);
+  g->off_resc = p;    p = align_up(p + (g->filtered ? (size_t)g->Hq * g->n_scan_chunks * 4 * g->cand_T * sizeof(uint2) : (size_t)0), 256);
+  g->off_rescount = p; p = align_up(p + (g->filtered ? (size_t)g->Hq * g->n_scan_chunks * 4 * sizeof(uint32_t) : (size_t)0), 256);
   g->off_thr = p;     p = align_up(p + (size_t)g->Hq * sizeof(uint32_t), 256);
   g->off_sphi = p;    p = align_up(p + (size_t)g->Hq * g->d * sizeof(float), 256);
   g->off_uphi = p;    p = align_up(p + (size_t)g->Hq * sizeof(float), 256);

@@ -64,6 +64,8 @@ struct Geom {
                          //                                       list land here); shares its memory with off_scores
   size_t off_candc;      // uint2    [Hq][n_scan_chunks][4][cand_T]  the first cand_T entries of every list
   size_t off_ccount;     // uint32   [Hq][n_scan_chunks][4]      lengths of the candidate lists
+  size_t off_resf, off_resc, off_rescount;  // the rescan set: a second candf / candc / ccount, written when the select kernel
+                         //                                       rescans a head without a bound, read by its second attempt
   size_t off_thr;        // uint32   [Hq]                        lower bound of the score key per query head
   size_t off_sphi;       // float    [Hq][d]                     S_M^T phi_q
   size_t off_uphi;       // float    [Hq]                        phi_q . u_M
