@@ -4,8 +4,8 @@
 Workload: the Llama-3.2-3B-shaped single layer at 128K context and a 1 % budget
 (24 query / 8 KV heads, head_dim 128, d_phi 128, 4 sink + 64 tail anchors, K = 1310), bf16
 K/V with fp32 accumulation, synthetic seeded inputs.  One "step" is one tkphi_decode call
-on one layer (score_mid, topk_select + phi_q, gather = exact branch + subtraction
-sums, merge).  The steps rotate over several distinct resident layers so that the keys
+on one layer (score pass over the mid-region, Top-K selection, exact branch + subtraction sums
+over the retrieved tokens, phi_q and the summary terms, merge).  The steps rotate over several distinct resident layers so that the keys
 are really streamed from HBM and not served by the 256 MB last-level cache.  The summary
 build (prefill side, once per prefix) is timed separately and reported under "build".
 
@@ -24,11 +24,23 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
-# HBM bytes per score_mid launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a
-# plain 256 MiB copy on the same counters), see profiles/decode_and_build_l3b_128k.md.
-# key: (workload, budget_bp) -> fetched + written bytes
-MEASURED_TRAFFIC = {("l3b_128k", 100): 269.02e6 + 15.72e6}
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+PROFILE = os.path.join(ROOT, "profiles", "decode_and_build_l3b_128k.md")
+
+
+def measured_traffic(workload: str, budget_bp: int, kernel: str):
+    """HBM bytes per launch of the dominant kernel as the tracked rocprofv3 --pmc summary states them (a line
+    `TRAFFIC <workload> <budget_bp> <kernel> fetched=<bytes> written=<bytes>`), or None if it has no such line."""
+    try:
+        with open(PROFILE) as f:
+            for line in f:
+                t = line.split()
+                if len(t) >= 6 and t[0] == "TRAFFIC" and t[1] == workload and t[2] == str(budget_bp) and t[3] == kernel:
+                    kv = dict(x.split("=") for x in t[4:6])
+                    return float(kv["fetched"]) + float(kv["written"])
+    except (OSError, ValueError, KeyError):
+        pass
+    return None
 
 
 def main() -> int:
@@ -143,6 +155,41 @@ def main() -> int:
     ms_per_step = e0.elapsed_time(e1) / args.steps
     assert all(b.status() == 0 for b in batches)
 
+    # ---- spread of single steps (each between its own pair of events; not what `value` is made of) ------
+    pairs_ev = [(ev(), ev()) for _ in range(args.steps)]
+    for i, (a, b_) in enumerate(pairs_ev):
+        a.record(stream)
+        batches[i % len(batches)].decode()
+        b_.record(stream)
+    torch.cuda.synchronize()
+    single = np.array([a.elapsed_time(b_) * 1e3 for a, b_ in pairs_ev])
+    step_us_dist = {"median": float(np.median(single)), "p10": float(np.percentile(single, 10)),
+                    "p90": float(np.percentile(single, 90)), "n": int(single.size)}
+
+    # ---- the same steps replayed from HIP graphs (one graph per resident batch) -------------------------
+    graph_replay_us = None
+    try:
+        graphs = []
+        for b in batches:
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr):
+                b.decode()
+            graphs.append(gr)
+        for i in range(max(args.warmup, len(graphs))):
+            graphs[i % len(graphs)].replay()
+        torch.cuda.synchronize()
+        g0, g1 = ev(), ev()
+        g0.record(stream)
+        for i in range(args.steps):
+            graphs[i % len(graphs)].replay()
+        g1.record(stream)
+        torch.cuda.synchronize()
+        graph_replay_us = g0.elapsed_time(g1) / args.steps * 1e3
+        assert all(b.status() == 0 for b in batches)
+        del graphs
+    except RuntimeError as exc:                        # (capture refused: reported, not fatal)
+        print(f"bench.py: graph capture failed: {exc}", file=sys.stderr)
+
     # ---- per-stage kernel durations: HIP events on the launch stream, same steps ---------
     stage = np.zeros(len(B.STAGES))
     for i in range(args.steps):
@@ -165,6 +212,7 @@ def main() -> int:
     bytes_const = probs_per_step * (w.n_kv_heads * w.d_phi * (w.d_head + 1) * 4          # S, u
                                     + (w.n_q_heads + w.n_kv_heads) * w.d_phi * w.d_head * esz)   # Wq, Wk
     bytes_step = bytes_scan + bytes_gather + bytes_anchor + bytes_const
+    scan_kernel = "score_filtered_kernel" if stage_us.get("prep", 0.0) > 0 else "score_mid_kernel"
     scan_s = stage_us["score_mid"] * 1e-6
     achieved = bytes_scan / scan_s / 1e9
 
@@ -175,6 +223,8 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "decode_step_us": ms_per_step * 1e3,
+        "step_us_dist": step_us_dist,
+        "graph_replay_us": graph_replay_us,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.n_q_heads}q/{w.n_kv_heads}kv heads, head_dim {w.d_head}, "
@@ -190,9 +240,9 @@ def main() -> int:
                      "frac_of_peak": bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "stage_us": stage_us,
         "wall_ms_per_step": wall_ms / args.steps,
-        "roofline": {"kernel": "score_mid", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"kernel": scan_kernel, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC.get((w.name, args.budget_bp)),
+                     "traffic": measured_traffic(w.name, args.budget_bp, scan_kernel),
                      "algorithmic_bytes_per_launch": bytes_scan},
         "build": {"ms_per_call": build_ms, "problems_per_call": probs_per_step, "algorithmic_bytes": build_bytes, "flops": build_flops,
                   "hbm_GBs": build_bytes / (build_ms * 1e-3) / 1e9,

@@ -153,6 +153,40 @@ def test_select_pipelines(shape, L, k, variant):
         PU.check_layer(w, P, kk, b, i, heads=[0, w.n_q_heads // 2, w.n_q_heads - 1])
 
 
+@pytest.mark.parametrize("variant", ["spill", "filtered"])
+def test_graph_replay_matches_eager(variant):
+    """A decode call captured into a HIP graph (it allocates nothing, synchronises nothing and records no
+    memset) replayed several times, with eager decodes and synchronisations in between and the query changed
+    between replays: every replay must reproduce the eager result bit for bit."""
+    import torch
+    from paper_2604_05438_amd import harness as H
+    w = I.WORKLOADS["l3b_128k"]
+    Ls, ks = [6000, 2100], [240, 60]
+    layers = [I.make_layer(w, L=l, seq=i) for i, l in enumerate(Ls)]
+    b = _batch(w, layers, ks, tuning=SELECT_VARIANTS[variant])
+    b.build(); b.decode()
+    torch.cuda.synchronize()
+    assert b.status() == 0
+    gr = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(gr):
+        b.decode()
+    for rnd in range(4):
+        for i, l in enumerate(Ls):                     # a new query for every problem, written in place
+            q = H.to_device(I.make_layer(w, L=l, seq=i, query_index=rnd + 1, with_kv=False)["q"])
+            b.dev[i]["q"].copy_(q)
+        b.decode()
+        torch.cuda.synchronize()
+        eager = [b.result(i, "out").copy() for i in range(len(Ls))]
+        for i in range(len(Ls)):
+            b.dev[i]["out"].zero_()
+        torch.cuda.synchronize()
+        gr.replay()
+        torch.cuda.synchronize()
+        assert b.status() == 0
+        for i in range(len(Ls)):
+            assert np.array_equal(b.result(i, "out"), eager[i]), f"replay {rnd}, problem {i}"
+
+
 @pytest.mark.parametrize("variant", list(SELECT_VARIANTS))
 def test_exact_ties_take_lower_index(variant):
     """Duplicated keys give bit-equal scores on both sides: the index sets must match exactly."""
