@@ -397,7 +397,11 @@ __global__ __launch_bounds__(kThreads) void gather_cached_kernel(Geom g, const t
     while (LPR * 2 <= min(dphi / 4, 64)) LPR *= 2;
     const int RPP = kThreads / LPR, seg = tid % LPR, rsub = tid / LPR;
     const float* phiq = (const float*)(blk + g.off_phiq) + (size_t)gq * dphi;
-    const float* cache_h = pr.phi_cache + (size_t)h * n * dphi;
+    // feature row of tile entry `row`: the cached row of its token, or (MLP maps without a cache) row i0 + row of
+    // the features the step recomputed for this head's retrieved list
+    const float* cache_h = g.sel_feat ? (const float*)(blk + g.off_selphi) + ((size_t)gq * g.max_K + i0) * dphi
+                                      : pr.phi_cache + (size_t)h * n * dphi;
+    auto feat_row = [&](int row) -> size_t { return g.sel_feat ? (size_t)min(row, cnt - 1) : (size_t)(p_tok[row] - g.n_sink); };
     for (int r0 = 0; r0 < kPairsPerWG; r0 += RPP * 4) {
       float zz[4] = {0.f, 0.f, 0.f, 0.f};
       for (int c4 = seg; c4 < dphi / 4; c4 += LPR) {        // (one round when d_phi <= 256)
@@ -406,7 +410,7 @@ __global__ __launch_bounds__(kThreads) void gather_cached_kernel(Geom g, const t
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
           const int row = min(r0 + k * RPP + rsub, kPairsPerWG - 1);
-          const u32x4 t = gload128(cache_h + (size_t)(p_tok[row] - g.n_sink) * dphi + c4 * 4);
+          const u32x4 t = gload128(cache_h + feat_row(row) * dphi + c4 * 4);
           f[k] = make_float4(__uint_as_float(t.x), __uint_as_float(t.y), __uint_as_float(t.z), __uint_as_float(t.w));
         }
 #pragma unroll
@@ -665,7 +669,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Geom g, const tkphi_pro
 
 void launch_gather(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
   dim3 grid(g.n_tiles + g.n_atiles, g.Hq, g.n_problems);
-  if (g.cache) {
+  if (g.cache || g.sel_feat) {
     if (g.dtype == TKPHI_BF16) TKPHI_LAUNCH(ST_GATHER, gather_cached_kernel<uint16_t>, grid, dim3(kThreads), 0, s, g, probs, ws);
     else TKPHI_LAUNCH(ST_GATHER, gather_cached_kernel<float>, grid, dim3(kThreads), 0, s, g, probs, ws);
   } else if (g.use_mfma) {

@@ -9,9 +9,12 @@
 //   res   G = G + alpha (H W2^T + b2)    (in place: a tile reads only its own G entries)
 //   out   Phi = exp(G Wo^T + bo)     -> tkphi_problem::phi_cache
 // with one tiled matrix-core GEMM (mlp_gemm_tile).  A tile's layers depend only on the tile's own
-// rows: by default one persistent launch per problem takes each workgroup's tiles through stem,
-// hid and res + out (g1 stays on chip); widths that do not fuse run the layers as separate launches
-// per block of Geom::mlp_block tokens.
+// rows: by default one persistent launch per group of up to Geom::mlp_group problems takes each
+// workgroup's tiles through stem, hid and res + out (g1 stays on chip); widths that do not fuse run
+// the layers as separate launches per problem and block of Geom::mlp_block tokens.
+// Without cfg.cache_features the features of a group go to a workspace buffer that the summary
+// contraction of the group consumes, and decode recomputes the features of the retrieved keys
+// (Sec. "Retrieved-token subtraction") by sending their rows through the same chain.
 // Activations are fp32 in the workspace; as MFMA operands they are split into a bf16 hi + lo
 // pair (16 significant bits, two MFMAs per product), weights are bf16 as stored, accumulation
 // is fp32.  With ~1.3 MFLOP per token and KV head against 256 bytes of key the chain is bound by
@@ -37,24 +40,35 @@ enum { EPI_STEM = 0, EPI_HID = 1, EPI_RES = 2, EPI_OUT = 3, EPI_RESOUT = 4 };
 // outputs x 32 inputs; block (ct, ks) is stored as the 1 KB a wavefront loads as one operand:
 // lane (r, kg) -> the 16 bytes W[16 ct + r][32 ks + 8 kg .. + 7], at byte ((ct Kd/32 + ks) 64 + lane) 16.
 // The GEMM's operand loads then are whole 1 KB lines instead of 16 pieces of 64 B (measured 19 %
-// faster).  One launch per problem packs the four matrices of every KV head into the workspace:
-// grid (ceil(pieces / 256), Hkv); per head Ws | W1 | W2 | Wo, in this order.
+// faster).  One launch packs the four matrices of every KV head of the problems p0 .. p0 + gridDim.z - 1
+// into the workspace, problem p0 + z into slot z: grid (ceil(pieces / 256), Hkv, problems); per head
+// Ws | W1 | W2 | Wo, in this order.
 // ------------------------------------------------------------------------------------
 __device__ __forceinline__ size_t packed_bytes_per_head(const Geom& g) {
   return ((size_t)g.d_emb * g.d + (size_t)2 * g.d_emb * g.d_emb + (size_t)g.dphi * g.d_emb) * 2;
 }
 
+__device__ __forceinline__ const char* packed_weights(const Geom& g, const char* ws, int slot, int h) {
+  return ws + g.off_wpack + ((size_t)slot * g.Hkv + h) * packed_bytes_per_head(g);
+}
+// Where the key features of KV head h of a problem (n mid tokens) live: the caller's cache, or, without one, the
+// workspace buffer of the problem's slot in the group being built.
+__device__ __forceinline__ float* key_feature_rows(const Geom& g, const tkphi_problem& pr, char* ws, int slot, int h, int n) {
+  if (g.cache) return pr.phi_cache + (size_t)h * n * g.dphi;
+  return (float*)(ws + g.off_feat) + ((size_t)slot * g.Hkv + h) * (size_t)g.max_mid * g.dphi;
+}
+
 __global__ __launch_bounds__(kThreads) void mlp_pack_weights_kernel(Geom g, const tkphi_problem* __restrict__ probs,
-                                                                    char* __restrict__ ws, int p) {
-  const int h = blockIdx.y;
-  const tkphi_problem pr = probs[p];
+                                                                    char* __restrict__ ws, int p0) {
+  const int h = blockIdx.y, slot = blockIdx.z;
+  const tkphi_problem pr = probs[p0 + slot];
   if (pr.L < 1 || pr.L > g.max_L) return;
   const tkphi_mlp mp = pr.mlp_k[h];
   const int E = g.d_emb;
   const size_t n_s = (size_t)E * g.d / 8, n_1 = (size_t)E * E / 8, n_o = (size_t)g.dphi * E / 8;   // 16-byte pieces
   size_t q = (size_t)blockIdx.x * kThreads + threadIdx.x;
   if (q >= n_s + 2 * n_1 + n_o) return;
-  char* dst = ws + g.off_wpack + (size_t)h * packed_bytes_per_head(g) + q * 16;
+  char* dst = ws + g.off_wpack + ((size_t)slot * g.Hkv + h) * packed_bytes_per_head(g) + q * 16;
   const char* W;
   int Kd;
   if (q < n_s) { W = (const char*)mp.Ws; Kd = g.d; }
@@ -89,13 +103,16 @@ constexpr int mlp_lds_bytes() {
   return stage > planes ? stage : planes;
 }
 
-// One 64-token tile of one layer.  tok0: first mid-region token of the tile; Gt, Ht: the tile's fp32
+// One 64-token tile of one layer.  tok0: first row of the tile; Gt, Ht: the tile's fp32
 // activations g and h, [64][d_emb]; lds_raw: mlp_lds_bytes<NT>() bytes, free on entry (the caller
 // puts a barrier between two calls); n0: first output of the workgroup (0 unless the layer is wider
-// than 64 NT).
+// than 64 NT).  Row tok0 + i is mid token tok0 + i, or, with a row map, mid token rowmap[tok0 + i]
+// (decode: the retrieved list of a query head); feat: where row 0's features go (row-major, d_phi floats
+// per row); slot: which packed weights.
 template <int EPI, int NT, int NTO>
 __device__ __forceinline__ void mlp_gemm_tile(const Geom& g, const tkphi_problem& pr, const tkphi_mlp& mp, char* __restrict__ ws,
-                                              char* lds_raw, int h, int n, int tok0, int rows_valid, float* Gt, float* Ht, int n0) {
+                                              char* lds_raw, int h, int n, int tok0, int rows_valid, float* Gt, float* Ht, int n0,
+                                              int slot, float* feat, const int32_t* rowmap = nullptr) {
   constexpr int BM = 64, KB = 32;
   constexpr int AROW = KB * 2 + 16;
   constexpr bool A_BF16 = EPI == EPI_STEM;
@@ -112,14 +129,17 @@ __device__ __forceinline__ void mlp_gemm_tile(const Geom& g, const tkphi_problem
   // fragment-packed weights of this head: Ws | W1 | W2 | Wo
   const size_t w_off = EPI_W == EPI_STEM ? 0 : EPI_W == EPI_HID ? (size_t)E * g.d : EPI_W == EPI_RES ? (size_t)E * g.d + (size_t)E * E
                                                                                                    : (size_t)E * g.d + (size_t)2 * E * E;
-  const char* W = ws + g.off_wpack + (size_t)h * packed_bytes_per_head(g) + w_off * 2;
+  const char* W = packed_weights(g, ws, slot, h) + w_off * 2;
   const float* bias = EPI_W == EPI_STEM ? mp.bs : EPI_W == EPI_HID ? mp.b1 : EPI_W == EPI_RES ? mp.b2 : mp.bo;
 
   // A rows: thread (srow = tid / 4, sseg = tid % 4) stages 8 consecutive inputs of row srow
   const int srow = tid >> 2, sseg = tid & 3;
   const int arow = min(srow, rows_valid - 1);          // clamped: rows past the end repeat the last one
   const char* a_src;
-  if (A_BF16) a_src = (const char*)pr.K + ((size_t)h * pr.stride_head + (size_t)(g.n_sink + tok0 + arow) * pr.stride_tok + sseg * 8) * 2;
+  if (A_BF16) {
+    const int tok = rowmap ? min(max(rowmap[tok0 + arow], 0), n - 1) : tok0 + arow;
+    a_src = (const char*)pr.K + ((size_t)h * pr.stride_head + (size_t)(g.n_sink + tok) * pr.stride_tok + sseg * 8) * 2;
+  }
   else a_src = (const char*)((EPI_W == EPI_RES ? Ht : Gt) + (size_t)arow * E + sseg * 8);
   // weight operands: the NT output tiles of this wavefront (clamped to the last tile: every lane loads)
   const int colw = n0 + wv * NT * 16;
@@ -186,7 +206,7 @@ __device__ __forceinline__ void mlp_gemm_tile(const Geom& g, const tkphi_problem
   }
 
   // ---- epilogue: acc[mt][nt][i] <-> token row mt*16 + r, output colw + nt*16 + 4kg + i --------------
-  float* cache_h = pr.phi_cache + ((size_t)h * n + tok0) * g.dphi;
+  float* cache_h = feat + (size_t)tok0 * g.dphi;
   auto g_ptr = [&](int mt, int nt) { return Gt + (size_t)min(mt * 16 + r, rows_valid - 1) * E + colw + nt * 16 + 4 * kg; };
   if constexpr (EPI == EPI_RESOUT) {
     // g1 in place of the accumulators (the old residual stream is loaded a few tiles at a time)
@@ -212,7 +232,7 @@ __device__ __forceinline__ void mlp_gemm_tile(const Geom& g, const tkphi_problem
     }
     char* const p_hi = lds_raw;
     char* const p_lo = lds_raw + BM * RS;
-    const char* Wo = ws + g.off_wpack + (size_t)h * packed_bytes_per_head(g) + ((size_t)E * g.d + (size_t)2 * E * E) * 2;
+    const char* Wo = packed_weights(g, ws, slot, h) + ((size_t)E * g.d + (size_t)2 * E * E) * 2;
     const int n_otiles = g.dphi / 16;
     floatx4 acco[4][NTO];
 #pragma unroll
@@ -329,36 +349,73 @@ __global__ __launch_bounds__(kThreads, 2) void mlp_gemm_kernel(Geom g, const tkp
   float* Gb = (float*)(ws + g.off_act) + (size_t)h * g.mlp_block * g.d_emb;
   float* Hb = Gb + (size_t)g.Hkv * g.mlp_block * g.d_emb;
   mlp_gemm_tile<EPI, NT, NTO>(g, pr, mp, ws, lds_raw, h, n, t0 + row0, rows_valid, Gb + (size_t)row0 * g.d_emb,
-                              Hb + (size_t)row0 * g.d_emb, (int)blockIdx.y * 64 * NT);
+                              Hb + (size_t)row0 * g.d_emb, (int)blockIdx.y * 64 * NT, 0, key_feature_rows(g, pr, ws, 0, h, n));
 }
 
 // The whole chain in one launch (d_emb == 64 NT, d_phi == 64 NTO): a tile's layers depend only on the
 // tile's own rows, so a persistent workgroup takes a 64-token tile through stem, hidden layer and
 // residual + output with workgroup barriers in between; its activations (2 x 64 x d_emb floats of the
-// workspace per workgroup) never leave L2.  grid (n_wg), tile T = blockIdx.x + k n_wg -> KV head
-// T % Hkv, tokens [64 (T / Hkv), + 64).  No launch gaps and one cold start per workgroup (4 % faster
-// than the layer-wise launches; holding back every other workgroup at the start so that neighbours on a
-// CU run different phases was measured to change nothing).
+// workspace per workgroup) never leave L2.  grid (n_wg); the tiles of the np problems p0 .. p0 + np - 1:
+// tile T = blockIdx.x + k n_wg -> problem slot T / tpp, KV head (T % tpp) % Hkv, tokens
+// [64 ((T % tpp) / Hkv), + 64), tpp = Hkv ceil(max_mid / 64) (tiles past a shorter problem's end are skipped).
+// No launch gaps and one cold start per workgroup (4 % faster than the layer-wise launches; holding back
+// every other workgroup at the start so that neighbours on a CU run different phases was measured to
+// change nothing).
 template <int NT, int NTO>
 __global__ __launch_bounds__(kThreads, 2) void mlp_chain_kernel(Geom g, const tkphi_problem* __restrict__ probs,
-                                                                char* __restrict__ ws, int p) {
+                                                                char* __restrict__ ws, int p0, int np) {
   __shared__ __attribute__((aligned(16))) char lds_raw[mlp_lds_bytes<NT>()];
-  const tkphi_problem pr = probs[p];
-  if (pr.L < 1 || pr.L > g.max_L) return;
-  const int n = mid_size(pr.L, g.n_sink, g.n_tail);
-  const int total = ((n + 63) / 64) * g.Hkv;
+  const int tpp = ((g.max_mid + 63) / 64) * g.Hkv;
   float* Gt = (float*)(ws + g.off_act) + (size_t)blockIdx.x * 2 * 64 * g.d_emb;
   float* Ht = Gt + (size_t)64 * g.d_emb;
-  for (int T = blockIdx.x; T < total; T += gridDim.x) {
-    const int h = T % g.Hkv, tok0 = (T / g.Hkv) * 64;
+  for (int T = blockIdx.x; T < tpp * np; T += gridDim.x) {
+    const int slot = T / tpp, rem = T % tpp;
+    const tkphi_problem pr = probs[p0 + slot];
+    if (pr.L < 1 || pr.L > g.max_L) continue;          // (uniform over the workgroup)
+    const int n = mid_size(pr.L, g.n_sink, g.n_tail);
+    const int h = rem % g.Hkv, tok0 = (rem / g.Hkv) * 64;
+    if (tok0 >= n) continue;
     const int rows_valid = min(64, n - tok0);
     const tkphi_mlp mp = pr.mlp_k[h];
-    mlp_gemm_tile<EPI_STEM, NT, 0>(g, pr, mp, ws, lds_raw, h, n, tok0, rows_valid, Gt, Ht, 0);
+    float* feat = key_feature_rows(g, pr, ws, slot, h, n);
+    mlp_gemm_tile<EPI_STEM, NT, 0>(g, pr, mp, ws, lds_raw, h, n, tok0, rows_valid, Gt, Ht, 0, slot, feat);
     __syncthreads();                                   // g0 of the tile is visible to the workgroup; LDS is free
-    mlp_gemm_tile<EPI_HID, NT, 0>(g, pr, mp, ws, lds_raw, h, n, tok0, rows_valid, Gt, Ht, 0);
+    mlp_gemm_tile<EPI_HID, NT, 0>(g, pr, mp, ws, lds_raw, h, n, tok0, rows_valid, Gt, Ht, 0, slot, feat);
     __syncthreads();
-    mlp_gemm_tile<EPI_RESOUT, NT, NTO>(g, pr, mp, ws, lds_raw, h, n, tok0, rows_valid, Gt, Ht, 0);
+    mlp_gemm_tile<EPI_RESOUT, NT, NTO>(g, pr, mp, ws, lds_raw, h, n, tok0, rows_valid, Gt, Ht, 0, slot, feat);
     __syncthreads();                                   // the next tile overwrites g, h and the planes
+  }
+}
+
+// Decode without a feature cache: the same chain over the retrieved keys.  Tile T -> problem slot T / tpp, query
+// head (T % tpp) % Hq, entries [64 ((T % tpp) / Hq), + 64) of that head's retrieved list (tpp = Hq ceil(max_K / 64));
+// row i of a head is mid token sel_idx[i], its features go to row i of the head's block of Geom::off_selphi.
+template <int NT, int NTO>
+__global__ __launch_bounds__(kThreads, 2) void mlp_chain_sel_kernel(Geom g, const tkphi_problem* __restrict__ probs,
+                                                                    char* __restrict__ ws, int p0, int np) {
+  __shared__ __attribute__((aligned(16))) char lds_raw[mlp_lds_bytes<NT>()];
+  const int tpp = ((g.max_K + 63) / 64) * g.Hq;
+  float* Gt = (float*)(ws + g.off_act) + (size_t)blockIdx.x * 2 * 64 * g.d_emb;
+  float* Ht = Gt + (size_t)64 * g.d_emb;
+  for (int T = blockIdx.x; T < tpp * np; T += gridDim.x) {
+    const int slot = T / tpp, rem = T % tpp;
+    const tkphi_problem pr = probs[p0 + slot];
+    if (pr.L < 1 || pr.L > g.max_L) continue;
+    const int n = mid_size(pr.L, g.n_sink, g.n_tail);
+    const int gq = rem % g.Hq, tok0 = (rem / g.Hq) * 64, h = gq / g.G;
+    char* blk = problem_block(g, ws, p0 + slot);
+    const int Ksel = min(((const SelPlan*)(blk + g.off_plan))[gq].n_sel, g.max_K);
+    if (n == 0 || tok0 >= Ksel) continue;
+    const int rows_valid = min(64, Ksel - tok0);
+    const tkphi_mlp mp = pr.mlp_k[h];
+    const int32_t* rowmap = (const int32_t*)(blk + g.off_selidx) + (size_t)gq * g.max_K;
+    float* feat = (float*)(blk + g.off_selphi) + (size_t)gq * g.max_K * g.dphi;
+    mlp_gemm_tile<EPI_STEM, NT, 0>(g, pr, mp, ws, lds_raw, h, n, tok0, rows_valid, Gt, Ht, 0, slot, feat, rowmap);
+    __syncthreads();
+    mlp_gemm_tile<EPI_HID, NT, 0>(g, pr, mp, ws, lds_raw, h, n, tok0, rows_valid, Gt, Ht, 0, slot, feat, rowmap);
+    __syncthreads();
+    mlp_gemm_tile<EPI_RESOUT, NT, NTO>(g, pr, mp, ws, lds_raw, h, n, tok0, rows_valid, Gt, Ht, 0, slot, feat, rowmap);
+    __syncthreads();
   }
 }
 
@@ -389,49 +446,78 @@ static void launch_mlp_resout_nt(const Geom& g, const tkphi_problem* probs, char
 }
 
 template <int NT>
-static void launch_mlp_chain_nt(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s, int p) {
-  const int tiles = (g.max_mid + 63) / 64 * g.Hkv;
-  dim3 grid(std::min(tiles, kMlpChainWGs));
-  if (g.dphi == 64) hipLaunchKernelGGL((mlp_chain_kernel<NT, 1>), grid, dim3(kThreads), 0, s, g, probs, ws, p);
-  else if (g.dphi == 128) hipLaunchKernelGGL((mlp_chain_kernel<NT, 2>), grid, dim3(kThreads), 0, s, g, probs, ws, p);
-  else hipLaunchKernelGGL((mlp_chain_kernel<NT, 4>), grid, dim3(kThreads), 0, s, g, probs, ws, p);
+static void launch_mlp_chain_nt(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s, int p0, int np, bool sel) {
+  const int64_t tiles = sel ? (int64_t)(g.max_K + 63) / 64 * g.Hq * np : (int64_t)(g.max_mid + 63) / 64 * g.Hkv * np;
+  dim3 grid((unsigned)std::min<int64_t>(tiles, kMlpChainWGs));
+  if (sel) {
+    if (g.dphi == 64) hipLaunchKernelGGL((mlp_chain_sel_kernel<NT, 1>), grid, dim3(kThreads), 0, s, g, probs, ws, p0, np);
+    else if (g.dphi == 128) hipLaunchKernelGGL((mlp_chain_sel_kernel<NT, 2>), grid, dim3(kThreads), 0, s, g, probs, ws, p0, np);
+    else hipLaunchKernelGGL((mlp_chain_sel_kernel<NT, 4>), grid, dim3(kThreads), 0, s, g, probs, ws, p0, np);
+  } else {
+    if (g.dphi == 64) hipLaunchKernelGGL((mlp_chain_kernel<NT, 1>), grid, dim3(kThreads), 0, s, g, probs, ws, p0, np);
+    else if (g.dphi == 128) hipLaunchKernelGGL((mlp_chain_kernel<NT, 2>), grid, dim3(kThreads), 0, s, g, probs, ws, p0, np);
+    else hipLaunchKernelGGL((mlp_chain_kernel<NT, 4>), grid, dim3(kThreads), 0, s, g, probs, ws, p0, np);
+  }
 }
 
-// the key features of every problem's mid-region -> phi_cache
-void launch_mlp_features(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
-  if (g.max_mid == 0) return;
+static void launch_mlp_chain(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s, int p0, int np, bool sel) {
+  if (g.d_emb == 512) launch_mlp_chain_nt<8>(g, probs, ws, s, p0, np, sel);
+  else if (g.d_emb == 256) launch_mlp_chain_nt<4>(g, probs, ws, s, p0, np, sel);
+  else launch_mlp_chain_nt<2>(g, probs, ws, s, p0, np, sel);
+}
+
+static void launch_mlp_pack(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s, int p0, int np) {
   const size_t pieces = ((size_t)g.d_emb * g.d + (size_t)2 * g.d_emb * g.d_emb + (size_t)g.dphi * g.d_emb) / 8;
-  // tkphi_tuning::mlp_mode 1: layer-wise launches per token block; 2: also residual and output apart
+  hipLaunchKernelGGL(mlp_pack_weights_kernel, dim3((unsigned)((pieces + kThreads - 1) / kThreads), g.Hkv, np), dim3(kThreads), 0, s,
+                     g, probs, ws, p0);
+}
+
+// Build with the MLP maps: the key features of every problem's mid-region (-> phi_cache, or the workspace buffer of
+// the group) and their summary contraction (-> chunk partials), group of problems by group.
+void launch_mlp_build(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
+  if (g.max_mid == 0) return;
+  // tkphi_tuning::mlp_mode 1: layer-wise launches per problem and token block; 2: also residual and output apart
   const bool fusable = resout_fusable(g) && g.mlp_mode != 2;
   const bool chain = fusable && g.mlp_mode != 1;
-  for (int p = 0; p < g.n_problems; ++p) {
-    hipLaunchKernelGGL(mlp_pack_weights_kernel, dim3((unsigned)((pieces + kThreads - 1) / kThreads), g.Hkv), dim3(kThreads), 0, s,
-                       g, probs, ws, p);
+  const int group = chain ? g.mlp_group : 1;
+  for (int p0 = 0; p0 < g.n_problems; p0 += group) {
+    const int np = std::min(group, g.n_problems - p0);
+    launch_mlp_pack(g, probs, ws, s, p0, np);
     if (chain) {
-      if (g.d_emb == 512) launch_mlp_chain_nt<8>(g, probs, ws, s, p);
-      else if (g.d_emb == 256) launch_mlp_chain_nt<4>(g, probs, ws, s, p);
-      else launch_mlp_chain_nt<2>(g, probs, ws, s, p);
-      continue;
-    }
-    for (int t0 = 0; t0 < g.max_mid; t0 += g.mlp_block) {
-      const int rows = std::min(g.mlp_block, g.max_mid - t0);
-      launch_mlp_gemm<EPI_STEM>(g, probs, ws, s, rows, g.d_emb, p, t0);
-      launch_mlp_gemm<EPI_HID>(g, probs, ws, s, rows, g.d_emb, p, t0);
-      if (fusable) {
-        if (g.d_emb == 512) launch_mlp_resout_nt<8>(g, probs, ws, s, rows, p, t0);
-        else if (g.d_emb == 256) launch_mlp_resout_nt<4>(g, probs, ws, s, rows, p, t0);
-        else launch_mlp_resout_nt<2>(g, probs, ws, s, rows, p, t0);
-      } else {
-        launch_mlp_gemm<EPI_RES>(g, probs, ws, s, rows, g.d_emb, p, t0);
-        launch_mlp_gemm<EPI_OUT>(g, probs, ws, s, rows, g.dphi, p, t0);
+      launch_mlp_chain(g, probs, ws, s, p0, np, false);
+    } else {
+      for (int t0 = 0; t0 < g.max_mid; t0 += g.mlp_block) {
+        const int rows = std::min(g.mlp_block, g.max_mid - t0);
+        launch_mlp_gemm<EPI_STEM>(g, probs, ws, s, rows, g.d_emb, p0, t0);
+        launch_mlp_gemm<EPI_HID>(g, probs, ws, s, rows, g.d_emb, p0, t0);
+        if (fusable) {
+          if (g.d_emb == 512) launch_mlp_resout_nt<8>(g, probs, ws, s, rows, p0, t0);
+          else if (g.d_emb == 256) launch_mlp_resout_nt<4>(g, probs, ws, s, rows, p0, t0);
+          else launch_mlp_resout_nt<2>(g, probs, ws, s, rows, p0, t0);
+        } else {
+          launch_mlp_gemm<EPI_RES>(g, probs, ws, s, rows, g.d_emb, p0, t0);
+          launch_mlp_gemm<EPI_OUT>(g, probs, ws, s, rows, g.dphi, p0, t0);
+        }
       }
     }
+    launch_summary_from_cache(g, probs, ws, s, p0, np);
+  }
+}
+
+// Decode without a feature cache: phi_k of every query head's retrieved keys -> Geom::off_selphi (after the select)
+void launch_mlp_sel_features(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
+  if (g.max_mid == 0 || g.max_K == 0) return;
+  for (int p0 = 0; p0 < g.n_problems; p0 += g.mlp_group) {
+    const int np = std::min(g.mlp_group, g.n_problems - p0);
+    launch_mlp_pack(g, probs, ws, s, p0, np);
+    launch_mlp_chain(g, probs, ws, s, p0, np, true);
   }
 }
 
 // ------------------------------------------------------------------------------------
-// summary contraction from stored features: grid (n_build_chunks, Hkv, n_problems), 256
-// threads; writes the same chunk partials as the other build kernels.
+// summary contraction from stored features: grid (n_build_chunks, Hkv, problems of the group), 256
+// threads; problem p0 + blockIdx.z, whose features are in its cache or in slot blockIdx.z of the workspace
+// buffer; writes the same chunk partials as the other build kernels.
 // Tiles of 64 tokens: the feature rows (fp32) are split into bf16 hi / lo and transposed
 // in registers (4 tokens x 4 features per load group) into feature-major LDS planes, the
 // value tile is transposed as in the fused build; wavefront w owns the feature tiles
@@ -439,12 +525,12 @@ void launch_mlp_features(const Geom& g, const tkphi_problem* probs, char* ws, hi
 // ------------------------------------------------------------------------------------
 template <int D, int FTW>
 __global__ __launch_bounds__(kThreads) void summary_from_cache_kernel(Geom g, const tkphi_problem* __restrict__ probs,
-                                                                      char* __restrict__ ws) {
+                                                                      char* __restrict__ ws, int p0) {
   constexpr int CT = D / 16, SEGS = D / 8;
   constexpr int TROW = 64 * 2 + 16;                // bytes per staged row of 64 tokens
   constexpr int QMAX = FTW * 4 / 4;                // feature quads per thread: dphi / 4 / 16 <= FTW
   extern __shared__ __attribute__((aligned(16))) char lds[];   // f_hi [dphi][TROW], f_lo [dphi][TROW], v_t [D][TROW]
-  const int ch = blockIdx.x, h = blockIdx.y, p = blockIdx.z, tid = threadIdx.x;
+  const int ch = blockIdx.x, h = blockIdx.y, p = p0 + blockIdx.z, tid = threadIdx.x;
   const tkphi_problem pr = probs[p];
   if (pr.L < 1 || pr.L > g.max_L) return;
   const int n = mid_size(pr.L, g.n_sink, g.n_tail);
@@ -469,7 +555,7 @@ __global__ __launch_bounds__(kThreads) void summary_from_cache_kernel(Geom g, co
     for (int e = 0; e < 4; ++e) usum[k][e] = 0.f;
 
   const int tq = tid % 16, fs = tid / 16;          // tokens 4tq .. 4tq+3 of the tile; feature quads fs, fs + 16, ...
-  const float* cache_h = pr.phi_cache + (size_t)h * n * dphi;
+  const float* cache_h = key_feature_rows(g, pr, ws, (int)blockIdx.z, h, n);
   const size_t row_bytes = (size_t)pr.stride_tok * 2;
   const bool v_active = tid < 16 * SEGS;
   const int sg = tid / 16;
@@ -644,22 +730,22 @@ void launch_mlp_phi_q(const Geom& g, const tkphi_problem* probs, char* ws, hipSt
 }
 
 template <int D, int FTW>
-static void launch_sfc(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
-  dim3 grid(g.n_build_chunks, g.Hkv, g.n_problems);
+static void launch_sfc(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s, int p0, int np) {
+  dim3 grid(g.n_build_chunks, g.Hkv, np);
   const size_t lds = (size_t)(2 * g.dphi + g.d) * (64 * 2 + 16);
   if (lds > 48 * 1024) {
     const hipError_t e = hipFuncSetAttribute((const void*)summary_from_cache_kernel<D, FTW>,
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) { set_error("hipFuncSetAttribute(%zu bytes of LDS): %s", lds, hipGetErrorString(e)); return; }
   }
-  hipLaunchKernelGGL((summary_from_cache_kernel<D, FTW>), grid, dim3(kThreads), lds, s, g, probs, ws);
+  hipLaunchKernelGGL((summary_from_cache_kernel<D, FTW>), grid, dim3(kThreads), lds, s, g, probs, ws, p0);
 }
 
-void launch_summary_from_cache(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
+void launch_summary_from_cache(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s, int p0, int np) {
   if (g.max_mid == 0) return;
   const int ftw = (g.dphi + 63) / 64;              // feature tiles per wavefront: 1, 2 or (3, 4 ->) 4
-  if (g.d == 128) { if (ftw <= 1) launch_sfc<128, 1>(g, probs, ws, s); else if (ftw == 2) launch_sfc<128, 2>(g, probs, ws, s); else launch_sfc<128, 4>(g, probs, ws, s); }
-  else { if (ftw <= 1) launch_sfc<64, 1>(g, probs, ws, s); else if (ftw == 2) launch_sfc<64, 2>(g, probs, ws, s); else launch_sfc<64, 4>(g, probs, ws, s); }
+  if (g.d == 128) { if (ftw <= 1) launch_sfc<128, 1>(g, probs, ws, s, p0, np); else if (ftw == 2) launch_sfc<128, 2>(g, probs, ws, s, p0, np); else launch_sfc<128, 4>(g, probs, ws, s, p0, np); }
+  else { if (ftw <= 1) launch_sfc<64, 1>(g, probs, ws, s, p0, np); else if (ftw == 2) launch_sfc<64, 2>(g, probs, ws, s, p0, np); else launch_sfc<64, 4>(g, probs, ws, s, p0, np); }
 }
 
 }  // namespace tkphi

@@ -22,13 +22,29 @@ union Frag {
   bf16x8 v;
 };
 
+// Sum over the N (power of two, <= 16) consecutive lanes that hold one row, by data-parallel-primitive
+// moves inside a row of 16 lanes: the same butterfly as xor-shuffles by 1, 2, 4, 8 (lanes that mirror
+// each other across a quad pair / a half row hold equal partial sums after the earlier steps), every
+// lane ends with the total.
+template <int N>
+__device__ __forceinline__ float row_lanes_sum(float s) {
+  auto dpp = [](float v, auto ctrl) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), decltype(ctrl)::value, 0xf, 0xf, false));
+  };
+  if (N >= 2) s += dpp(s, std::integral_constant<int, 0xB1>{});    // quad_perm [1, 0, 3, 2]
+  if (N >= 4) s += dpp(s, std::integral_constant<int, 0x4E>{});    // quad_perm [2, 3, 0, 1]
+  if (N >= 8) s += dpp(s, std::integral_constant<int, 0x141>{});   // row_half_mirror
+  if (N >= 16) s += dpp(s, std::integral_constant<int, 0x140>{});  // row_mirror
+  return s;
+}
+
 // ------------------------------------------------------------------------------------
 // bf16 on the matrix cores: grid (n_build_chunks, Hkv, n_problems); D == d_head == d_phi.
 //
 // Tiles of 64 tokens; the key and value tiles are staged in LDS once per workgroup (keys
 // row-major, values transposed in registers - 4 tokens x 8 channels per lane - and stored
 // channel-major), |k|^2 is reduced while staging.  Wavefront w owns the features
-// [w*D/4, (w+1)*D/4): its slice of Wk stays in registers for the whole chunk.
+// [w*D/NW, (w+1)*D/NW): its slice of Wk stays in registers for the whole chunk.
 //   GEMM1  P[64 tokens][own features] = K Wk^T : A = key rows from LDS, B = Wk slice
 //          -> exp -> bf16 hi + lo; the result registers (4 consecutive tokens per lane and
 //          16-token tile) are already the A operand of GEMM2 over a fixed permutation of
@@ -38,14 +54,19 @@ union Frag {
 // u is summed from the same features.  Two LDS tile buffers: tile t+1 is staged (and the
 // global loads of tile t+2 are issued) before tile t is contracted: one barrier per tile.
 // ------------------------------------------------------------------------------------
-template <int D, bool CACHE>        // CACHE: also store the contracted features in pr.phi_cache
-__global__ __launch_bounds__(kThreads, 2) void build_mfma_kernel(Geom g, const tkphi_problem* __restrict__ probs,
+// NW wavefronts per workgroup (4 or 8), each owning D / NW features.  The LDS tiles allow two workgroups per CU
+// at D = 128 and four at D = 64, so NW = 8 resp. 4 puts four wavefronts on a SIMD: one's exponentials and staging
+// hide behind another's MFMAs.
+template <int D, bool CACHE, int NW>  // CACHE: also store the contracted features in pr.phi_cache
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4 : NW / 2, D == 64 ? 4 : NW / 2))) void build_mfma_kernel(Geom g, const tkphi_problem* __restrict__ probs,
                                                                  char* __restrict__ ws) {
   constexpr int KS = D / 32;            // k-steps of GEMM1 (over channels)
-  constexpr int FT = D / 64;            // feature tiles per wavefront
+  constexpr int NT = 64 * NW;           // threads
+  constexpr int FT = D / (16 * NW);     // feature tiles per wavefront
+  static_assert(FT >= 1, "at least 16 features per wavefront");
   constexpr int CT = D / 16;            // channel tiles of S
   constexpr int SEGS = D / 8;           // 16-byte segments per row
-  constexpr int KLD = 64 * SEGS / kThreads;   // key-row loads per thread and tile (4 or 2)
+  constexpr int KLD = 64 * SEGS / NT;   // key-row loads per thread and tile (4 or 2)
   constexpr int KROW = D * 2 + 16;      // bytes per staged key row
   constexpr int TROW = 64 * 2 + 16;     // bytes per staged value-channel row (64 tokens)
   // two tile buffers: tile t+1 is staged while tile t is contracted, one barrier per tile
@@ -70,7 +91,7 @@ __global__ __launch_bounds__(kThreads, 2) void build_mfma_kernel(Geom g, const t
     const uint16_t* wsrc = (const uint16_t*)pr.Wk + (size_t)h * D * D;
 #pragma unroll
     for (int ft = 0; ft < FT; ++ft) {
-      const int feat = wv * (D / 4) + ft * 16 + r;
+      const int feat = wv * (D / NW) + ft * 16 + r;
 #pragma unroll
       for (int j = 0; j < KS; ++j) wk[ft][j].u = gload128(wsrc + (size_t)feat * D + j * 32 + kg * 8);
       bias[ft] = pr.bk[(size_t)h * D + feat] * kLog2e;
@@ -89,30 +110,49 @@ __global__ __launch_bounds__(kThreads, 2) void build_mfma_kernel(Geom g, const t
   const size_t base_off = ((size_t)h * pr.stride_head + (size_t)g.n_sink * pr.stride_tok) * 2;
   // key loads: thread (krow = tid / SEGS, seg = tid % SEGS) takes rows krow + i * (256 / SEGS)
   const int kseg = tid % SEGS, krow = tid / SEGS;
-  constexpr int KRP = kThreads / SEGS;  // key rows per pass
-  const char* Kb = (const char*)pr.K + base_off + (size_t)kseg * 16;
+  constexpr int KRP = NT / SEGS;  // key rows per pass
   // value loads: thread (tq, sg) takes tokens 4*tq .. 4*tq+3 of the tile, 16-byte segment sg
   const bool v_active = tid < 16 * SEGS;
   const int tq = tid % 16, sg = tid / 16;
-  const char* Vb = (const char*)pr.V + base_off + (size_t)sg * 16;
+  // A tile's rows start at a uniform address; a thread's byte offsets inside a full tile never change
+  // (32 bits: a tile spans 64 rows), so the loads of a full tile are base + offset with no per-row arithmetic.
+  const char* Kt = (const char*)pr.K + base_off;
+  const char* Vt = (const char*)pr.V + base_off;
+  uint32_t koff[KLD], voff[4];
+#pragma unroll
+  for (int i = 0; i < KLD; ++i) koff[i] = (uint32_t)((krow + i * KRP) * row_bytes) + kseg * 16;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) voff[i] = (uint32_t)((tq * 4 + i) * row_bytes) + sg * 16;
 
   u32x4 kk[KLD], vv[4];
   auto issue_loads = [&](int t0) {
+    const char* kt = Kt + (size_t)t0 * row_bytes;
+    const char* vt = Vt + (size_t)t0 * row_bytes;
+    if (t0 + 64 <= c1) {                 // full tile
 #pragma unroll
-    for (int i = 0; i < KLD; ++i) {
-      const int row = min(t0 + krow + i * KRP, c1 - 1);
-      kk[i] = gload128_stream(Kb + (size_t)row * row_bytes);
-    }
-    if (v_active) {
+      for (int i = 0; i < KLD; ++i) kk[i] = gload128_stream(kt + koff[i]);
+      if (v_active) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int vrow = min(t0 + tq * 4 + i, c1 - 1);
-        vv[i] = gload128_stream(Vb + (size_t)vrow * row_bytes);
+        for (int i = 0; i < 4; ++i) vv[i] = gload128_stream(vt + voff[i]);
+      }
+    } else {                             // last tile of the mid-region: rows past the end re-read the last row
+#pragma unroll
+      for (int i = 0; i < KLD; ++i) {
+        const int row = min(krow + i * KRP, c1 - 1 - t0);
+        kk[i] = gload128_stream(kt + (size_t)row * row_bytes + kseg * 16);
+      }
+      if (v_active) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int vrow = min(tq * 4 + i, c1 - 1 - t0);
+          vv[i] = gload128_stream(vt + (size_t)vrow * row_bytes + sg * 16);
+        }
       }
     }
   };
 
   auto stage = [&](int t0, char* k_t, char* v_t, float* nrm_t) {
+    const bool full = t0 + 64 <= c1;     // (uniform) no row of the tile lies past the end
     // ---- stage the tile: keys row-major (+ norms), values channel-major ---------------------
 #pragma unroll
     for (int i = 0; i < KLD; ++i) {
@@ -123,22 +163,21 @@ __global__ __launch_bounds__(kThreads, 2) void build_mfma_kernel(Geom g, const t
       float s = 0.f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) s = fmaf(x[e], x[e], s);
-#pragma unroll
-      for (int o = SEGS / 2; o >= 1; o >>= 1) s += __shfl_xor(s, o);
-      if (kseg == 0) nrm_t[row] = (t0 + row < c1) ? c2 * s : INFINITY;
+      s = row_lanes_sum<SEGS>(s);        // over the SEGS lanes that share the row
+      if (kseg == 0) nrm_t[row] = (full || t0 + row < c1) ? c2 * s : INFINITY;
     }
     if (v_active) {
-      const bool vok[4] = {t0 + tq * 4 + 0 < c1, t0 + tq * 4 + 1 < c1, t0 + tq * 4 + 2 < c1, t0 + tq * 4 + 3 < c1};
       uint32_t w[4][4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        w[i][0] = vok[i] ? vv[i].x : 0u; w[i][1] = vok[i] ? vv[i].y : 0u;
-        w[i][2] = vok[i] ? vv[i].z : 0u; w[i][3] = vok[i] ? vv[i].w : 0u;
+        const bool ok = full || t0 + tq * 4 + i < c1;
+        w[i][0] = ok ? vv[i].x : 0u; w[i][1] = ok ? vv[i].y : 0u;
+        w[i][2] = ok ? vv[i].z : 0u; w[i][3] = ok ? vv[i].w : 0u;
       }
 #pragma unroll
       for (int q = 0; q < 4; ++q) {      // dword q of a token holds channels 2q (low half) and 2q+1 (high half)
-        const u32x2 even = (u32x2){(w[0][q] & 0xffffu) | (w[1][q] << 16), (w[2][q] & 0xffffu) | (w[3][q] << 16)};
-        const u32x2 odd = (u32x2){(w[0][q] >> 16) | (w[1][q] & 0xffff0000u), (w[2][q] >> 16) | (w[3][q] & 0xffff0000u)};
+        const u32x2 even = (u32x2){__builtin_amdgcn_perm(w[1][q], w[0][q], 0x05040100u), __builtin_amdgcn_perm(w[3][q], w[2][q], 0x05040100u)};
+        const u32x2 odd = (u32x2){__builtin_amdgcn_perm(w[1][q], w[0][q], 0x07060302u), __builtin_amdgcn_perm(w[3][q], w[2][q], 0x07060302u)};
         *(u32x2*)(v_t + (sg * 8 + 2 * q) * TROW + tq * 8) = even;
         *(u32x2*)(v_t + (sg * 8 + 2 * q + 1) * TROW + tq * 8) = odd;
       }
@@ -173,7 +212,7 @@ __global__ __launch_bounds__(kThreads, 2) void build_mfma_kernel(Geom g, const t
         phi_lo[mt][ft] = (u32x2){l01, l23};
         if (CACHE) {                     // the 16-bit values GEMM2 contracts, as fp32
           const int tok = t0 + mt * 16 + 4 * kg;
-          float* cp = cache_h + (size_t)tok * D + wv * (D / 4) + ft * 16 + r;
+          float* cp = cache_h + (size_t)tok * D + wv * (D / NW) + ft * 16 + r;
           if (tok + 0 < c1) cp[0] = join_bf16_lo(h01, l01);
           if (tok + 1 < c1) cp[D] = join_bf16_hi(h01, l01);
           if (tok + 2 < c1) cp[2 * D] = join_bf16_lo(h23, l23);
@@ -234,11 +273,11 @@ __global__ __launch_bounds__(kThreads, 2) void build_mfma_kernel(Geom g, const t
     for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        bp[(size_t)(wv * (D / 4) + ft * 16 + 4 * kg + i) * D + ct * 16 + r] = sacc[ft][ct][i];
+        bp[(size_t)(wv * (D / NW) + ft * 16 + 4 * kg + i) * D + ct * 16 + r] = sacc[ft][ct][i];
     float x = uacc[ft];
     x += __shfl_xor(x, 16);
     x += __shfl_xor(x, 32);
-    if (kg == 0) bp[(size_t)D * D + wv * (D / 4) + ft * 16 + r] = x;
+    if (kg == 0) bp[(size_t)D * D + wv * (D / NW) + ft * 16 + r] = x;
   }
 }
 
@@ -394,13 +433,12 @@ void launch_build(const Geom& g, const tkphi_problem* probs, char* ws, hipStream
   if (g.max_mid > 0) {
     dim3 grid(g.n_build_chunks, g.Hkv, g.n_problems);
     if (g.phi_kind == TKPHI_PHI_MLP) {
-      launch_mlp_features(g, probs, ws, s);         // phi_k of the mid-region -> phi_cache
-      launch_summary_from_cache(g, probs, ws, s);   // S, u chunk partials from the stored features
+      launch_mlp_build(g, probs, ws, s);            // phi_k of the mid-region, then S, u chunk partials from the features
     } else if (g.use_mfma) {
-      if (g.d == 128 && g.cache) TKPHI_LAUNCH(ST_UNTIMED, (build_mfma_kernel<128, true>), grid, dim3(kThreads), 0, s, g, probs, ws);
-      else if (g.d == 128) TKPHI_LAUNCH(ST_UNTIMED, (build_mfma_kernel<128, false>), grid, dim3(kThreads), 0, s, g, probs, ws);
-      else if (g.cache) TKPHI_LAUNCH(ST_UNTIMED, (build_mfma_kernel<64, true>), grid, dim3(kThreads), 0, s, g, probs, ws);
-      else TKPHI_LAUNCH(ST_UNTIMED, (build_mfma_kernel<64, false>), grid, dim3(kThreads), 0, s, g, probs, ws);
+      if (g.d == 128 && g.cache) TKPHI_LAUNCH(ST_UNTIMED, (build_mfma_kernel<128, true, 4>), grid, dim3(kThreads), 0, s, g, probs, ws);
+      else if (g.d == 128) TKPHI_LAUNCH(ST_UNTIMED, (build_mfma_kernel<128, false, 4>), grid, dim3(kThreads), 0, s, g, probs, ws);
+      else if (g.cache) TKPHI_LAUNCH(ST_UNTIMED, (build_mfma_kernel<64, true, 4>), grid, dim3(kThreads), 0, s, g, probs, ws);
+      else TKPHI_LAUNCH(ST_UNTIMED, (build_mfma_kernel<64, false, 4>), grid, dim3(kThreads), 0, s, g, probs, ws);
     } else if (g.dtype == TKPHI_BF16) {
       TKPHI_LAUNCH(ST_UNTIMED, build_kernel<uint16_t>, grid, dim3(kThreads), 0, s, g, probs, ws);
     } else {

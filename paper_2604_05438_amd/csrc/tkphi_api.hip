@@ -52,13 +52,20 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
     return TKPHI_EINVAL;
   }
   if (cfg->phi_kind == TKPHI_PHI_MLP) {
-    if (cfg->kv_dtype != TKPHI_BF16 || !cfg->cache_features) {
-      set_error("the MLP feature maps need bf16 storage and cache_features = 1");
+    if (cfg->kv_dtype != TKPHI_BF16) {
+      set_error("the MLP feature maps need bf16 storage");
       return TKPHI_EUNSUPPORTED;
     }
     if (cfg->d_emb < 64 || cfg->d_emb > 1024 || (cfg->d_emb & (cfg->d_emb - 1)) != 0) {
       set_error("d_emb=%d unsupported (a power of two in [64, 1024])", cfg->d_emb);
       return TKPHI_ESHAPE;
+    }
+    // decode recomputes retrieved-key features with the one-launch chain only (the widths it is built for)
+    const bool chain_widths = (cfg->d_emb == 128 || cfg->d_emb == 256 || cfg->d_emb == 512) && cfg->d_phi <= 256;
+    if (!cfg->cache_features && !chain_widths) {
+      set_error("the MLP feature maps without cache_features need d_emb in {128, 256, 512} and d_phi <= 256 "
+                "(d_emb=%d, d_phi=%d)", cfg->d_emb, cfg->d_phi);
+      return TKPHI_EUNSUPPORTED;
     }
   }
   if (cfg->max_gen < 0 || cfg->max_gen > (1 << 20)) { set_error("max_gen=%d out of range [0, 2^20]", cfg->max_gen); return TKPHI_EINVAL; }
@@ -164,11 +171,13 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   g->off_selscore = p; p = align_up(p + (size_t)g->Hq * std::max(max_K, 1) * sizeof(float), 256);
   g->off_phiq = p;    p = align_up(p + (size_t)g->Hq * g->dphi * sizeof(float), 256);
   g->off_mlpq = p;    p = align_up(p + (size_t)g->Hq * 2 * g->d_emb * sizeof(float), 256);
+  g->sel_feat = cfg->phi_kind == TKPHI_PHI_MLP && !g->cache;
+  g->off_selphi = p;  p = align_up(p + (g->sel_feat ? (size_t)g->Hq * std::max(max_K, 1) * g->dphi * sizeof(float) : (size_t)0), 256);
   g->off_part = p;
   p = align_up(p + (size_t)g->Hq * (std::max(g->n_tiles, g->sg_split) + g->n_atiles) * g->part_stride * sizeof(float), 256);
   g->per_problem = p;
   const size_t decode_total = g->off_problem0 + (size_t)std::max(n_problems, 1) * g->per_problem;
-  g->decode_bytes = align_up(decode_total, 256);
+  size_t decode_all = decode_total;
   g->off_bpart = g->off_problem0;
   const size_t build_total = g->off_bpart + (size_t)std::max(n_problems, 1) * g->Hkv * g->n_build_chunks *
                                                 (size_t)g->dphi * (g->d + 1) * sizeof(float);
@@ -181,15 +190,26 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
     const int64_t blk = std::max<int64_t>(((int64_t)64 << 20) / ((int64_t)2 * g->Hkv * g->d_emb * sizeof(float)),
                                           (int64_t)512 * 64 / g->Hkv);
     g->mlp_block = (int)std::clamp<int64_t>((tn.mlp_block > 0 ? tn.mlp_block : (int)blk) / 64 * 64, 64, 8192);
-    g->off_act = align_up(build_total, 256);
+    // (the activations, the packed weights and the feature buffer lie behind the decode blocks as well: a decode
+    // without a feature cache sends the retrieved keys through the same chain)
+    g->off_act = align_up(std::max(build_total, decode_total), 256);
     // (or, for the one-launch build, 2 x 64 x d_emb floats per persistent workgroup)
     const size_t act_bytes = std::max((size_t)2 * g->Hkv * g->mlp_block, (size_t)2 * 64 * kMlpChainWGs) * g->d_emb * sizeof(float);
     g->off_wpack = align_up(g->off_act + act_bytes, 256);
-    build_all = g->off_wpack + (size_t)g->Hkv * ((size_t)g->d_emb * g->d + (size_t)2 * g->d_emb * g->d_emb +
-                                                 (size_t)g->dphi * g->d_emb) * 2;
+    // Problems per chain launch: their packed weights (and, without a feature cache, the features of their
+    // mid-regions, fp32) are held together; up to 16 problems, the feature buffer at most 1 GiB (one problem if a
+    // single one is larger).
+    const size_t wpack_one = (size_t)g->Hkv * ((size_t)g->d_emb * g->d + (size_t)2 * g->d_emb * g->d_emb + (size_t)g->dphi * g->d_emb) * 2;
+    const size_t feat_one = g->cache ? 0 : (size_t)g->Hkv * std::max<int64_t>(g->max_mid, 1) * g->dphi * sizeof(float);
+    g->mlp_group = std::clamp(n_problems, 1, 16);
+    if (feat_one > 0) g->mlp_group = (int)std::clamp<size_t>(((size_t)1 << 30) / feat_one, 1, (size_t)g->mlp_group);
+    g->off_feat = align_up(g->off_wpack + (size_t)g->mlp_group * wpack_one, 256);
+    build_all = g->off_feat + (size_t)g->mlp_group * feat_one;
+    if (g->sel_feat) decode_all = g->off_feat;          // activations and packed weights
   }
+  g->decode_bytes = align_up(decode_all, 256);
   g->build_bytes = align_up(build_all, 256);
-  g->total_bytes = align_up(std::max(decode_total, build_all), 256);
+  g->total_bytes = align_up(std::max(decode_all, build_all), 256);
   return TKPHI_OK;
 }
 
@@ -305,6 +325,7 @@ static tkphi_status enqueue_decode(const Geom& g, const tkphi_problem* problems,
   st = hip_ok(hipEventRecord(ss->join, ss->stream), "hipEventRecord");
   launch_score_mid(g, problems, ws, s);
   launch_select(g, problems, ws, s);
+  if (g.sel_feat) launch_mlp_sel_features(g, problems, ws, s);    // no feature cache: phi_k of the retrieved keys
   // (the join is enqueued even after an error above: the side stream must not be left forked)
   const tkphi_status st2 = hip_ok(hipStreamWaitEvent(s, ss->join, 0), "hipStreamWaitEvent");
   if (st != TKPHI_OK) return st;

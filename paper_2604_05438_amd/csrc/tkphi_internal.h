@@ -38,6 +38,8 @@ struct Geom {
   int max_gen;           // bound of tkphi_problem::n_gen (generated tokens, exact)
   int mlp_mode;          // MLP build: tkphi_tuning::mlp_mode
   int mlp_block;         // MLP build: tokens per KV head whose activations are held at once (multiple of 64)
+  int mlp_group;         // MLP maps: problems per chain launch (their packed weights are held together)
+  int sel_feat;          // 1: MLP maps without a feature cache: decode recomputes the features of the retrieved keys
   int cache;             // 1: key features are stored by the build and gathered by decode (cfg.cache_features)
   int diag;              // 1: the select emit pass also reduces the entropy / mass diagnostics
   int interleave;        // 1: chunk c owns the units c, c + n_chunks, c + 2 n_chunks, ... of its problem
@@ -78,10 +80,13 @@ struct Geom {
   size_t off_selscore;   // float    [Hq][max_K]                 their scores
   size_t off_phiq;       // float    [Hq][dphi]
   size_t off_mlpq;       // float    [Hq][2][d_emb]                  MLP phi_q: stem / residual stream g, hidden h
+  size_t off_selphi;     // float    [Hq][max_K][d_phi]              MLP maps without a feature cache: phi_k of the retrieved keys,
+                         //                                       in the order of the retrieved list
   size_t off_part;       // float    [Hq][n_tiles + n_atiles][part_stride]  (retrieved tiles, then anchor tiles)
   size_t off_bpart;      // float    [Hkv][n_build_chunks][dphi*(d+1)]   (build only; aliases the block)
   size_t off_act;        // float    2 x [Hkv][mlp_block][d_emb]          (MLP build only: activations g, h of a token block)
-  size_t off_wpack;      // bf16     [Hkv][Ws | W1 | W2 | Wo]        (MLP build only: one problem's key-side weights in MFMA-fragment order)
+  size_t off_wpack;      // bf16     [mlp_group][Hkv][Ws | W1 | W2 | Wo]  (MLP maps: a group's key-side weights in MFMA-fragment order)
+  size_t off_feat;       // float    [mlp_group][Hkv][max_mid][d_phi]     (MLP build without a feature cache: a group's key features)
   size_t decode_bytes;   // what a decode call alone uses (status word + per-problem blocks)
   size_t build_bytes;    // what a summary build alone uses
   size_t total_bytes;    // the larger of decode and build
@@ -131,9 +136,10 @@ void launch_gather(const Geom& g, const tkphi_problem* probs, char* ws, hipStrea
 // `pre`: the prep kernel has already produced the anchor partials and the summary terms S_M^T phi_q, phi_q . u_M
 void launch_merge(const Geom& g, const tkphi_problem* probs, char* ws, int mode, bool pre, hipStream_t s);
 void launch_build(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
-void launch_mlp_features(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);     // -> phi_cache
+void launch_mlp_build(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);        // key features + chunk partials
+void launch_mlp_sel_features(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);  // -> off_selphi
 void launch_mlp_phi_q(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);        // -> phi_q of every query head
-void launch_summary_from_cache(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s); // -> chunk partials
+void launch_summary_from_cache(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s, int p0, int np); // -> chunk partials
 
 #ifdef __HIPCC__
 // ---- device helpers ------------------------------------------------------------------

@@ -18,11 +18,14 @@ def to_device(a: np.ndarray, device="cuda") -> torch.Tensor:
     return t.to(device)
 
 
-def config_of(w: Workload, cache_features: bool = False, d_emb: int = 0, max_gen: int = 0, tuning: dict | None = None) -> B.tkphi_config:
-    """d_emb > 0 selects the MLP feature maps (which need the feature cache); max_gen bounds the
-    generated tokens a problem may append after its prefill rows; tuning: tkphi_tuning fields."""
+def config_of(w: Workload, cache_features: bool | None = None, d_emb: int = 0, max_gen: int = 0,
+              tuning: dict | None = None) -> B.tkphi_config:
+    """d_emb > 0 selects the MLP feature maps; cache_features None: the feature cache is on for the MLP maps and
+    off for the exp-affine ones; max_gen bounds the generated tokens a problem may append after its prefill
+    rows; tuning: tkphi_tuning fields."""
+    cache = (d_emb > 0) if cache_features is None else bool(cache_features)
     return B.make_config(w.n_q_heads, w.n_kv_heads, w.d_head, w.d_phi, w.n_sink, w.n_tail, w.dtype,
-                         w.score_scale, w.phi_in_scale, w.phi_norm_coef, int(cache_features or d_emb > 0),
+                         w.score_scale, w.phi_in_scale, w.phi_norm_coef, int(cache),
                          B.TKPHI_PHI_MLP if d_emb > 0 else B.TKPHI_PHI_EXP_AFFINE, d_emb, max_gen, tuning=tuning)
 
 

@@ -67,8 +67,10 @@ def test_mlp_feature_map_config_validation():
     base = B.tkphi_workspace_bytes(_cfg(cache_features=1), 1, 32768, 327)
     with_mlp = B.tkphi_workspace_bytes(_cfg(**mlp), 1, 32768, 327)
     assert with_mlp > base > 0                     # activation block + packed weights of the MLP build
-    for bad in (dict(mlp, d_emb=96), dict(mlp, d_emb=32), dict(mlp, d_emb=2048), dict(mlp, cache_features=0),
-                dict(mlp, dtype="f32"), dict(phi_kind=7)):
+    # without a feature cache the build holds the features of a group of problems in the workspace
+    assert B.tkphi_workspace_bytes(_cfg(**dict(mlp, cache_features=0)), 1, 32768, 327) > with_mlp
+    assert B.tkphi_workspace_bytes(_cfg(**dict(mlp, cache_features=0, d_emb=64)), 1, 4096, 40) == 0   # (not a width that fuses)
+    for bad in (dict(mlp, d_emb=96), dict(mlp, d_emb=32), dict(mlp, d_emb=2048), dict(mlp, dtype="f32"), dict(phi_kind=7)):
         assert B.tkphi_workspace_bytes(_cfg(**bad), 1, 4096, 40) == 0
         assert B.tkphi_last_error() != ""
     # the problem table must carry the MLP tables instead of Wq / Wk
@@ -82,6 +84,10 @@ def test_mlp_feature_map_config_validation():
         setattr(q, field, 0)
         with pytest.raises(B.TkphiError):
             B.tkphi_check_problems(cfg, (B.tkphi_problem * 1)(q), 1, 1000, 9, True)
+    # ... and no cache where the configuration has none
+    q = B.tkphi_problem.from_buffer_copy(p)
+    q.phi_cache = 0
+    B.tkphi_check_problems(_cfg(**dict(mlp, cache_features=0)), (B.tkphi_problem * 1)(q), 1, 1000, 9, True)
 
 
 def test_generated_token_bounds_are_validated():

@@ -419,10 +419,11 @@ def test_cached_key_features(shape, L, k):
     assert rel.max() <= (2.0 ** -15 if w.dtype == "bf16" else 2e-5), f"cache rel err {rel.max():.3e}"
 
 
+@pytest.mark.parametrize("cache", [True, False])
 @pytest.mark.parametrize("shape,d_emb,L,k,mode", [("l3b_128k", 512, 9000, 360, ""), ("l1b_32k", 128, 10000, 49, ""),
                                                   ("bf16_wide_phi", 256, 1500, 33, ""), ("l1b_32k", 128, 10000, 49, "blocks"),
                                                   ("l3b_128k", 512, 4500, 45, "unfused")])
-def test_mlp_feature_maps(shape, d_emb, L, k, mode):
+def test_mlp_feature_maps(shape, d_emb, L, k, mode, cache):
     """Learned feature maps (App. "Head-wise phi architecture"): the build evaluates the one-block
     ReZero MLP phi_k on the mid-region keys with the tiled matrix-core GEMM chain, stores the
     features and contracts them into S, u; decode evaluates phi_q per query head with the GEMV
@@ -430,7 +431,9 @@ def test_mlp_feature_maps(shape, d_emb, L, k, mode):
     both sides: stored features, summaries, index sets, outputs; single problem and ragged batch
     (the 10000-token case crosses the 8192-token activation block).  The build runs as one
     persistent launch per problem by default; "blocks" forces the layer-wise launches per token block
-    (residual + output fused), "unfused" all four layers apart (the path of widths that do not fuse)."""
+    (residual + output fused), "unfused" all four layers apart (the path of widths that do not fuse).
+    cache = False: no feature cache (Sec. "Retrieved-token subtraction": retrieved-key features recomputed at
+    decode): the build keeps a group's features in the workspace, decode sends the retrieved rows through the chain."""
     import parity_utils as PU
     from oracle import tkphi_oracle as orc
     from paper_2604_05438_amd import harness as H
@@ -447,24 +450,25 @@ def test_mlp_feature_maps(shape, d_emb, L, k, mode):
         P["mlp"] = I.make_mlp_phi(w, layer=i, d_emb=d_emb)
         layers.append(P)
     from paper_2604_05438_amd import binding as B
-    b = H.Batch(H.config_of(w, d_emb=d_emb, tuning={"mlp_mode": B.MLP_MODES[mode]}), layers, ks, debug=True)
+    b = H.Batch(H.config_of(w, d_emb=d_emb, cache_features=cache, tuning={"mlp_mode": B.MLP_MODES[mode]}), layers, ks, debug=True)
     b.build(); b.decode()
     assert b.status() == 0
     for i, (P, kk) in enumerate(zip(layers, ks)):
         rep = PU.check_layer(w, P, kk, b, i, heads=sorted({0, w.n_q_heads // 2, w.n_q_heads - 1}))
         print(f"mlp {shape} problem {i}: {rep}", flush=True)
-    # stored features of problem 0 against the oracle's, every KV head
-    O = PU.oracle_inputs(layers[0])
-    _, fk = PU.mlp_feature_fns(layers[0])
-    _, M = orc.partition(Ls[0], w.n_sink, w.n_tail)
-    C = b.result(0, "phi_cache").astype(np.float64)
-    worst = 0.0
-    for h in range(w.n_kv_heads):
-        F = fk[h](O["K"][h, M])
-        assert C[h].shape == F.shape
-        worst = max(worst, float((np.abs(C[h] - F) / F).max()))
-    print(f"mlp {shape}: stored features, worst relative error {worst:.3e}", flush=True)
-    assert worst <= PU.MLP_FEATURE_EPS
+    if cache:
+        # stored features of problem 0 against the oracle's, every KV head
+        O = PU.oracle_inputs(layers[0])
+        _, fk = PU.mlp_feature_fns(layers[0])
+        _, M = orc.partition(Ls[0], w.n_sink, w.n_tail)
+        C = b.result(0, "phi_cache").astype(np.float64)
+        worst = 0.0
+        for h in range(w.n_kv_heads):
+            F = fk[h](O["K"][h, M])
+            assert C[h].shape == F.shape
+            worst = max(worst, float((np.abs(C[h] - F) / F).max()))
+        print(f"mlp {shape}: stored features, worst relative error {worst:.3e}", flush=True)
+        assert worst <= PU.MLP_FEATURE_EPS
     # the other accounting modes and the diagnostics run on the same summaries
     from paper_2604_05438_amd import binding as B
     y_sub = b.result(0, "out").copy()
