@@ -58,6 +58,8 @@ def main() -> int:
                          "exp-affine maps of the headline.  Implies the feature cache unless --mlp-recompute")
     ap.add_argument("--mlp-recompute", action="store_true",
                     help="MLP maps without a feature cache: decode recomputes the features of the retrieved keys")
+    ap.add_argument("--select-mode", type=int, default=0, choices=[0, 1, 2],
+                    help="tkphi_tuning::select_mode: 0 = the library's choice, 1 = spill pipeline, 2 = filtered pipeline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 256 MiB device copies (a known-size kernel to scale rocprofv3's "
@@ -77,7 +79,8 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     w = I.WORKLOADS[args.workload]
-    cfg = H.config_of(w, cache_features=(not args.mlp_recompute) if args.mlp_d_emb else args.cache_features, d_emb=args.mlp_d_emb)
+    cfg = H.config_of(w, cache_features=(not args.mlp_recompute) if args.mlp_d_emb else args.cache_features, d_emb=args.mlp_d_emb,
+                      tuning={"select_mode": args.select_mode} if args.select_mode else None)
     esz = 2 if w.dtype == "bf16" else 4
 
     # ---- inputs, resident in HBM before anything is timed --------------------------------
@@ -250,6 +253,7 @@ def main() -> int:
                                   if model_level else f"L {L}, K {K}, one layer per step"),
                    "rotating_layers": 0 if model_level else args.rotate, "problems_per_step": probs_per_step,
                    "budget_bp": args.budget_bp, "K": K, "L": L, "cache_features": bool(cfg.cache_features),
+                   "select_mode": args.select_mode,
                    "phi": f"one-block ReZero MLP, d_emb {args.mlp_d_emb}" if args.mlp_d_emb else "exp-affine"},
         "step_hbm": {"algorithmic_bytes": bytes_step, "achieved_GBs": bytes_step / (ms_per_step * 1e-3) / 1e9,
                      "frac_of_peak": bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},

@@ -89,10 +89,16 @@ typedef enum tkphi_mode { TKPHI_MODE_SUB = 0, TKPHI_MODE_NOSUB = 1, TKPHI_MODE_T
  *                 g0 = Ws x + bs;  Delta = W2 GeLU(W1 g0 + b1) + b2;  g1 = g0 + alpha Delta;
  *                 phi(x) = exp(Wo g1 + bo)
  *               with internal width cfg.d_emb (the paper: 512), one tkphi_mlp per query head
- *               (tkphi_problem::mlp_q) and per KV head (mlp_k).  Requires bf16 storage and
- *               cfg.cache_features = 1: the key features are evaluated once, at build time
- *               (a chain of matrix-core GEMMs whose fp32 activations enter as bf16 hi + lo
- *               pairs; GeLU uses erfc to 1.5e-7 absolute).  tkphi_decode evaluates phi_q with
+ *               (tkphi_problem::mlp_q) and per KV head (mlp_k).  Requires bf16 storage.  The key
+ *               features of the mid-region are evaluated at build time by a chain of
+ *               matrix-core GEMMs whose fp32 activations enter as bf16 hi + lo pairs (GeLU
+ *               uses erfc to 1.5e-7 absolute), groups of up to 16 problems per launch.  With
+ *               cfg.cache_features = 1 they are stored in phi_cache and decode gathers them;
+ *               with cfg.cache_features = 0 (d_emb in {128, 256, 512} and d_phi <= 256 only)
+ *               the build keeps a group's features in the workspace until they are contracted
+ *               into S, u, and every decode step sends the retrieved key rows through the same
+ *               chain (Sec. "Retrieved-token subtraction": retrieved-key feature
+ *               recomputation).  tkphi_decode evaluates phi_q with
  *               three small launches on a second stream that the library creates per device
  *               on first use (default priority, kept until the process ends): forked from the
  *               caller's stream at the start of the call and joined to it before the gather, so

@@ -18,8 +18,33 @@ union GatherFrag {
 
 constexpr int wk_row_bytes(int D) { return D * 2 + 16; }   // staged Wk rows are padded by 16 B: conflict-free 16-byte reads
 
-// Stages Wk[h] ([D features][D channels] bf16) into LDS with padded rows; every thread of the workgroup
-// takes part; the caller puts a barrier before the first use.
+// Stages Wk[h] ([D features][D channels] bf16) into LDS with padded rows in two steps, so that a caller with NT
+// threads can put other work between the request and the LDS stores: wk_request loads the thread's pieces
+// (piece i of the matrix = 16 bytes; thread t holds pieces t, t + NT, ...), wk_commit stores them; a barrier
+// before the first use.
+template <int D, int NT>
+struct WkPieces {
+  static constexpr int SEGS = D * 2 / 16, N = (D * SEGS + NT - 1) / NT;
+  u32x4 t[N];
+  __device__ __forceinline__ void request(const void* Wk, int h) {
+    const char* wsrc = (const char*)Wk + (size_t)h * D * D * 2;
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+      const int i = min((int)threadIdx.x + k * NT, D * SEGS - 1);
+      t[k] = gload128(wsrc + (size_t)(i / SEGS) * D * 2 + (i % SEGS) * 16);
+    }
+  }
+  __device__ __forceinline__ void commit(char* wk_lds) const {
+    constexpr int WROW = wk_row_bytes(D);
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+      const int i = (int)threadIdx.x + k * NT;
+      if (i < D * SEGS) *(u32x4*)(wk_lds + (i / SEGS) * WROW + (i % SEGS) * 16) = t[k];
+    }
+  }
+};
+
+// The same in one step; every thread of the workgroup takes part; the caller puts a barrier before the first use.
 template <int D>
 __device__ __forceinline__ void stage_wk(const void* Wk, int h, char* wk_lds) {
   constexpr int WROW = wk_row_bytes(D), SEGS = D * 2 / 16;

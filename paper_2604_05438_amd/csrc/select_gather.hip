@@ -61,6 +61,7 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, cons
   __shared__ int w_tok[kWinLds];
   __shared__ float w_s[kWinLds];
   __shared__ float b_w[kBatch], b_z[kBatch];
+  __shared__ float sh_bk[D], sh_pq[D];              // bk[h] and phi_q of the head, staged with Wk
   __shared__ int sh_scan[kSelWaves];
   __shared__ uint64_t sh_prefix, sh_thr;
   __shared__ int sh_want, sh_tot;
@@ -104,7 +105,6 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, cons
     return;
   }
   const int h = gq / g.G;
-  stage_wk<D>(pr.Wk, h, wk_lds);                    // (visible after the barriers of the select phase)
   const int n_chunks = (n + g.scan_chunk - 1) / g.scan_chunk;
   const int n_reg = n_chunks * 4;
   const int rounds = (n_reg * T + kSelThreads * kSweepEntries - 1) / (kSelThreads * kSweepEntries);
@@ -168,6 +168,12 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, cons
     if (tid == 0 && part == 0) *plan = SelPlan{-1, 0, 0, 0, 0};
     return;
   }
+  // Wk[h] for the gather phase: requested now (the first sweep has arrived, nothing else is in flight), stored
+  // to LDS after the histogram pass
+  WkPieces<D, kSelThreads> wkp;
+  wkp.request(pr.Wk, h);
+  float bk_t = 0.f, pq_t = 0.f;
+  if (tid < D) { bk_t = pr.bk[(size_t)h * D + tid]; pq_t = ((const float*)(blk + g.off_phiq))[(size_t)gq * D + tid]; }
 
   // ---- pass A: histogram of the candidates' fine bins ----------------------------------------------------------
   for (int i = tid; i < kFineBins; i += kSelThreads) sh_hist[i] = 0u;
@@ -190,6 +196,8 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, cons
     for (int i = 0; i < kSweepEntries; ++i)
       if (i < sh.nvalid) atomicAdd(&sh_hist[fine_bin(score_key(__uint_as_float(entry(e, i).x)))], 1u);
   }
+  wkp.commit(wk_lds);                               // (visible after the barriers that follow)
+  if (tid < D) { sh_bk[tid] = bk_t; sh_pq[tid] = pq_t; }
   __syncthreads();
   TKPHI_PHASE(ws, 12);
   {
@@ -365,13 +373,13 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, cons
   // ---- gather: 256 winners per round, 16 per wavefront ---------------------------------------------------------
   const int r = lane & 15, kg = lane >> 4;
   const int64_t head_off = (int64_t)h * pr.stride_head;
-  const float* phiq = (const float*)(blk + g.off_phiq) + (size_t)gq * D;
   constexpr int LPR = D / 8;                        // lanes per value row (16 bytes each)
   constexpr int RPP = kSelThreads / LPR;            // rows per pass (64 or 128)
   constexpr int NPASS = kBatch / RPP;               // 4 or 2
   const int seg = tid % LPR, rsub = tid / LPR;
   float run_m = -INFINITY, run_Z = 0.f, run_zs = 0.f, run_nu = 0.f, run_zv = 0.f;   // (nu, zv: channel tid < D)
   __syncthreads();                                  // lds_a changes hands; the staged Wk is complete
+  // (inside the loop the wavefronts exchange data through LDS only: its barriers leave the key and value loads in flight)
   for (int b0 = 0; b0 < my_count; b0 += kBatch) {
     const int cnt = min(kBatch, my_count - b0);
     // this thread's token of the batch (thread t < 256 <-> winner b0 + t)
@@ -381,7 +389,16 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, cons
       else { *tok = sel_idx[min(my_base + i, g.max_K - 1)]; *s = sel_score[min(my_base + i, g.max_K - 1)]; }
       *tok = g.n_sink + min(max(*tok, 0), n - 1);
     };
-    // value rows: all passes' loads in flight (they only need the token indices)
+    // key rows of this wavefront's 16 tokens and the value rows of all passes: every load in flight together (they
+    // only need the token indices)
+    GatherFrag a[KS];
+    if (wv * 16 < cnt) {
+      int tk; float s;
+      winner(wv * 16 + r, &tk, &s);
+      const char* rp = (const char*)pr.K + (head_off + (int64_t)tk * pr.stride_tok) * 2 + kg * 16;
+#pragma unroll
+      for (int j = 0; j < KS; ++j) a[j].u = gload128(rp + j * 64);
+    }
     u32x4 vrow[NPASS];
     int vtok;
     float vs;
@@ -398,7 +415,7 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, cons
       winner(tid, &tk, &s);
       b_w[tid] = tid < cnt ? s : -INFINITY;         // (scores for now)
     }
-    __syncthreads();
+    lds_barrier();
     if (wv == 0) {
       float mloc = fmaxf(fmaxf(b_w[lane], b_w[lane + 64]), fmaxf(b_w[lane + 128], b_w[lane + 192]));
 #pragma unroll
@@ -407,14 +424,8 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, cons
     }
     // z_i of this wavefront's 16 tokens
     if (wv * 16 < cnt) {
-      int tk; float s;
-      winner(wv * 16 + r, &tk, &s);
-      const char* rp = (const char*)pr.K + (head_off + (int64_t)tk * pr.stride_tok) * 2 + kg * 16;
-      GatherFrag a[KS];
-#pragma unroll
-      for (int j = 0; j < KS; ++j) a[j].u = gload128(rp + j * 64);
       float z[4];
-      wave_feature_dots<D>(a, wk_lds, pr.bk + (size_t)h * D, phiq, g.a, g.c, z);
+      wave_feature_dots<D>(a, wk_lds, sh_bk, sh_pq, g.a, g.c, z);
       if (r == 0) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) b_z[wv * 16 + 4 * kg + i] = (wv * 16 + 4 * kg + i < cnt) ? z[i] : 0.f;
@@ -422,10 +433,10 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, cons
     } else if (lane < 16) {
       b_z[wv * 16 + lane] = 0.f;
     }
-    __syncthreads();
+    lds_barrier();
     const float mloc = sh_m;
     if (tid < kBatch) b_w[tid] = tid < cnt ? __expf(b_w[tid] - mloc) : 0.f;
-    __syncthreads();
+    lds_barrier();
     // weighted value sums: rows of one wavefront that share a segment, then the 16 wavefronts
     float an[8], az[8];
 #pragma unroll
@@ -456,7 +467,7 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, cons
       for (int o = 32; o >= 1; o >>= 1) { Zb += __shfl_xor(Zb, o); zb += __shfl_xor(zb, o); }
       if (lane == 0) { sh_Z = Zb; sh_zs = zb; }
     }
-    __syncthreads();
+    lds_barrier();
     {
       float nu_b = 0.f, zv_b = 0.f;
       if (tid < D) {
@@ -471,7 +482,7 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, cons
       run_zs += sh_zs;
       run_m = m_new;
     }
-    __syncthreads();                                // red, b_w, b_z are rewritten by the next batch
+    lds_barrier();                                // red, b_w, b_z are rewritten by the next batch
   }
   float* partial = (float*)(blk + g.off_part) + ((size_t)gq * (g.n_tiles + g.n_atiles) + part) * g.part_stride;
   if (tid == 0) { partial[0] = run_m; partial[1] = run_Z; partial[2] = run_zs; partial[3] = (float)my_count; }

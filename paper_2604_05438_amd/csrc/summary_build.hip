@@ -253,7 +253,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D == 64
   issue_loads(c0);
   stage(c0, k_tb[0], v_tb[0], nrm_tb[0]);
   if (c0 + 64 < c1) issue_loads(c0 + 64);
-  __syncthreads();
+  lds_barrier();                         // (LDS only: the loads of the next tile stay in flight)
   int cur = 0;
   for (int t0 = c0; t0 < c1; t0 += 64) {
     if (t0 + 64 < c1) {                  // next tile: registers -> the other buffer, then refill the registers
@@ -261,7 +261,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D == 64
       if (t0 + 128 < c1) issue_loads(t0 + 128);
     }
     contract(t0, k_tb[cur], v_tb[cur], nrm_tb[cur]);
-    __syncthreads();                     // the other buffer is complete, this one is free
+    lds_barrier();                       // the other buffer is complete, this one is free
     cur ^= 1;
   }
 

@@ -372,6 +372,16 @@ __device__ __forceinline__ void write_device_status(const Geom& g, const tkphi_p
 #define TKPHI_PHASE_VALUE(ws, slot, v) do {} while (0)
 #endif
 
+// Workgroup barrier that orders LDS accesses only.  __syncthreads() also waits for every global load the wavefront
+// has in flight (its fences cover global memory); where a barrier only hands LDS data from one wavefront to
+// another, this one lets prefetched global loads stay in flight across it.  Not for data exchanged through
+// global memory.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // mid-region size of a problem; 0 if the anchors cover everything
 __device__ __forceinline__ int mid_size(int L, int n_sink, int n_tail) {
   const int n = L - n_sink - n_tail;
