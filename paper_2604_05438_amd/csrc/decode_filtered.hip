@@ -357,6 +357,8 @@ __global__ __launch_bounds__(kPrepThreads) void decode_prep_kernel(Geom g, const
     if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) ((unsigned long long*)(ws + 16))[27] = clock64();
 #endif
   } else if (job <= g.G) {
+    // (also: nobody has arrived yet at this head's merge, see the fused select + gather kernel)
+    if (threadIdx.x == 0) ((uint32_t*)(blk + g.off_mcount))[h * g.G + job - 1] = 0u;
     prep_phi(g, pr, blk, h * g.G + job - 1, sh_a, sh_b, sh_dyn);
   } else {
     const int j = job - 1 - g.G;

@@ -26,6 +26,7 @@
 // into one partial per workgroup, [m, Z, zsum, count, nu[d], zv[d]], which the merge kernel combines in
 // part order.  No atomics on global memory; every sum runs in a fixed order.
 #include "gather_tile.h"
+#include "merge_head.h"
 #include "score_tile.h"
 #include "select_utils.h"
 #include "tkphi_internal.h"
@@ -50,9 +51,10 @@ __device__ __forceinline__ void rescan_head(const Geom& g, const tkphi_problem& 
     scan_wave_slot<D, TPI, 1>(g, pr, blk, h, n, n_chunks, reg >> 2, reg & 3, bq, 0u, gq % g.G, true);
 }
 
+// The selecting and gathering work of workgroup (part, gq, p); returns early where there is nothing to retrieve
 template <int D, int TPI>
-__global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, const tkphi_problem* __restrict__ probs,
-                                                                    char* __restrict__ ws) {
+__device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_problem* __restrict__ probs, char* __restrict__ ws,
+                                                   int part, int gq, int p) {
   constexpr int KS = D / 32;
   constexpr int WROW = wk_row_bytes(D);
   // select phase: histogram (8 KB) + boundary candidates (8 KB); gather phase: reduction scratch of the value sums
@@ -72,7 +74,7 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, cons
   uint64_t* bcand = (uint64_t*)(lds_a + 8192);
   float* red = (float*)lds_a;                       // [16 wavefronts][2][128]
 
-  const int part = blockIdx.x, gq = blockIdx.y, p = blockIdx.z, tid = threadIdx.x;
+  const int tid = threadIdx.x;
   const int lane = tid & 63, wv = tid >> 6;
   TKPHI_PHASE(ws, 10);
   char* blk = problem_block(g, ws, p);
@@ -164,8 +166,14 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, cons
   }
   const uint32_t total = sh_total;
   TKPHI_PHASE(ws, 11);
+  float* partial = (float*)(blk + g.off_part) + ((size_t)gq * (g.n_tiles + g.n_atiles) + part) * g.part_stride;
+  auto empty_partial = [&]() {
+    if (tid == 0) { store_agent(partial, -INFINITY); store_agent(partial + 1, 0.f); store_agent(partial + 2, 0.f); store_agent(partial + 3, 0.f); }
+    if (tid < D) { store_agent(partial + 4 + tid, 0.f); store_agent(partial + 4 + D + tid, 0.f); }
+  };
   if (total < (uint32_t)Ksel) {                     // cannot happen after a rescan (every mid token is a candidate)
     if (tid == 0 && part == 0) *plan = SelPlan{-1, 0, 0, 0, 0};
+    empty_partial();
     return;
   }
   // Wk[h] for the gather phase: requested now (the first sweep has arrived, nothing else is in flight), stored
@@ -213,6 +221,7 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, cons
   const int bstar = sh_bstar, krem = sh_krem, c_hi = sh_chi, nb = sh_nb;
   if (bstar < 0) {                                  // cannot happen: total >= Ksel
     if (tid == 0 && part == 0) *plan = SelPlan{-1, 0, 0, 0, 0};
+    empty_partial();
     return;
   }
   TKPHI_PHASE(ws, 13);
@@ -282,7 +291,7 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, cons
   if (tid == 0 && part == 0) *plan = SelPlan{bstar, krem, c_hi, nb, Ksel};
 
   // ---- this workgroup's winners: lists [l0, l1), in list order -----------------------------------------------
-  const int split = (int)gridDim.x;
+  const int split = g.sg_split;
   const int per_part = (n_reg + split - 1) / split;
   const int l0 = part * per_part, l1 = min(n_reg, l0 + per_part);
   int my_base = 0, my_count = 0;                    // winners in earlier lists; winners of this workgroup seen so far
@@ -484,16 +493,46 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, cons
     }
     lds_barrier();                                // red, b_w, b_z are rewritten by the next batch
   }
-  float* partial = (float*)(blk + g.off_part) + ((size_t)gq * (g.n_tiles + g.n_atiles) + part) * g.part_stride;
-  if (tid == 0) { partial[0] = run_m; partial[1] = run_Z; partial[2] = run_zs; partial[3] = (float)my_count; }
-  if (tid < D) { partial[4 + tid] = run_nu; partial[4 + D + tid] = run_zv; }
+  // (GPU-coherent stores: the workgroup that merges the head may run on another XCD)
+  if (tid == 0) { store_agent(partial, run_m); store_agent(partial + 1, run_Z); store_agent(partial + 2, run_zs); store_agent(partial + 3, (float)my_count); }
+  if (tid < D) { store_agent(partial + 4 + tid, run_nu); store_agent(partial + 4 + D + tid, run_zv); }
   TKPHI_PHASE(ws, 16);
 }
 
-void launch_select_gather(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
-  dim3 grid(g.n_tiles, g.Hq, g.n_problems);        // (filtered pipeline: n_tiles = workgroups per query head)
-  if (g.d == 128) TKPHI_LAUNCH(ST_SELECT, (select_gather_kernel<128, 4>), grid, dim3(kSelThreads), 0, s, g, probs, ws);
-  else TKPHI_LAUNCH(ST_SELECT, (select_gather_kernel<64, 8>), grid, dim3(kSelThreads), 0, s, g, probs, ws);
+// grid (sg_split, Hq, n_problems).  After its own share every workgroup of a head counts itself in (its partial made
+// visible first); the one that arrives last finds all partials of the head complete and merges them (merge_head.h)
+// with its first 256 threads: no separate merge launch.  The counters are cleared by the prep kernel of the same
+// call.  (The other wavefronts of that workgroup end before the merge's barriers: a barrier waits only for the
+// wavefronts of the workgroup that are still running.)
+template <int D, int TPI>
+__global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, const tkphi_problem* __restrict__ probs,
+                                                                    char* __restrict__ ws, int mode) {
+  __shared__ int sh_last;
+  const int part = blockIdx.x, gq = blockIdx.y, p = blockIdx.z;
+  select_gather_body<D, TPI>(g, probs, ws, part, gq, p);
+  const int L = probs[p].L;
+  if (L < 1 || L > g.max_L) return;                 // (the merge writes nothing for such a problem either)
+  // The partial went out with GPU-coherent stores and the merge reads the partials with GPU-coherent loads; the
+  // barrier below waits for this workgroup's stores to complete before thread 0 counts it in.  Only the optional
+  // export of the retrieved indices reads what ordinary stores of other workgroups wrote (the retrieved list): then,
+  // and only then, device-wide fences (each writes back / invalidates a whole L2) bracket the count.
+  const bool exports = probs[p].topk_idx != nullptr;
+  if (exports) __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t* arrived = (uint32_t*)(problem_block(g, ws, p) + g.off_mcount) + gq;
+    sh_last = atomicAdd(arrived, 1u) == (uint32_t)g.sg_split - 1u ? 1 : 0;
+  }
+  __syncthreads();
+  if (!sh_last || threadIdx.x >= kThreads) return;
+  if (exports) __threadfence();
+  merge_head<true, true>(g, probs, ws, gq, p, mode);
+}
+
+void launch_select_gather(const Geom& g, const tkphi_problem* probs, char* ws, int mode, hipStream_t s) {
+  dim3 grid(g.sg_split, g.Hq, g.n_problems);       // (Geom::n_tiles of this pipeline: one partial per workgroup)
+  if (g.d == 128) TKPHI_LAUNCH(ST_SELECT, (select_gather_kernel<128, 4>), grid, dim3(kSelThreads), 0, s, g, probs, ws, mode);
+  else TKPHI_LAUNCH(ST_SELECT, (select_gather_kernel<64, 8>), grid, dim3(kSelThreads), 0, s, g, probs, ws, mode);
 }
 
 }  // namespace tkphi

@@ -160,6 +160,7 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   g->off_resc = p;    p = align_up(p + (g->filtered ? (size_t)g->Hq * g->n_scan_chunks * 4 * g->cand_T * sizeof(uint2) : (size_t)0), 256);
   g->off_rescount = p; p = align_up(p + (g->filtered ? (size_t)g->Hq * g->n_scan_chunks * 4 * sizeof(uint32_t) : (size_t)0), 256);
   g->off_thr = p;     p = align_up(p + (size_t)g->Hq * sizeof(uint32_t), 256);
+  g->off_mcount = p;  p = align_up(p + (size_t)g->Hq * sizeof(uint32_t), 256);
   g->off_sphi = p;    p = align_up(p + (size_t)g->Hq * g->d * sizeof(float), 256);
   g->off_uphi = p;    p = align_up(p + (size_t)g->Hq * sizeof(float), 256);
   g->off_hist = p;    p = align_up(p + (size_t)g->n_scan_chunks * g->Hq * kBins * sizeof(uint16_t), 256);
@@ -303,8 +304,7 @@ static tkphi_status enqueue_decode(const Geom& g, const tkphi_problem* problems,
     gf.n_tiles = g.sg_split;           // one partial per workgroup of the fused select + gather kernel
     launch_prep(gf, problems, ws, s);
     launch_score_filtered(gf, problems, ws, s);
-    launch_select_gather(gf, problems, ws, s);
-    launch_merge(gf, problems, ws, acct, true, s);
+    launch_select_gather(gf, problems, ws, acct, s);   // (its last workgroup per head merges)
     return TKPHI_OK;
   }
   if (g.phi_kind != TKPHI_PHI_MLP) {

@@ -69,6 +69,8 @@ struct Geom {
   size_t off_resf, off_resc, off_rescount;  // the rescan set: a second candf / candc / ccount, written when the select kernel
                          //                                       rescans a head without a bound, read by its second attempt
   size_t off_thr;        // uint32   [Hq]                        lower bound of the score key per query head
+  size_t off_mcount;     // uint32   [Hq]                        filtered pipeline: workgroups of the fused select + gather kernel
+                         //                                       that have finished their share of the head (cleared by prep)
   size_t off_sphi;       // float    [Hq][d]                     S_M^T phi_q
   size_t off_uphi;       // float    [Hq]                        phi_q . u_M
   size_t off_hist;       // uint16   [n_scan_chunks][Hq][kBins]  per-chunk histograms
@@ -131,7 +133,7 @@ void launch_score_mid(const Geom& g, const tkphi_problem* probs, char* ws, hipSt
 void launch_select(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
 void launch_prep(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);              // filtered pipeline
 void launch_score_filtered(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
-void launch_select_gather(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
+void launch_select_gather(const Geom& g, const tkphi_problem* probs, char* ws, int mode, hipStream_t s);  // includes the merge
 void launch_gather(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s);
 // `pre`: the prep kernel has already produced the anchor partials and the summary terms S_M^T phi_q, phi_q . u_M
 void launch_merge(const Geom& g, const tkphi_problem* probs, char* ws, int mode, bool pre, hipStream_t s);
@@ -381,6 +383,13 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
+
+// Stores and loads that are coherent across the whole GPU (the 8 XCDs have separate L2 caches; ordinary accesses may
+// stay in, or be served from, the L2 of the XCD they were issued on until a kernel boundary).  For the few words
+// one workgroup hands to another inside a launch: much cheaper than a device-wide fence, which writes back a
+// whole L2.
+__device__ __forceinline__ void store_agent(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float load_agent(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
 // mid-region size of a problem; 0 if the anchors cover everything
 __device__ __forceinline__ int mid_size(int L, int n_sink, int n_tail) {
