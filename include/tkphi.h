@@ -138,8 +138,9 @@ typedef struct tkphi_tuning {
   int32_t mlp_mode;       /* MLP build: 0 = one persistent launch where the widths allow it,
                              1 = layer-wise launches per token block (residual + output fused),
                              2 = all four layers as separate launches                                    */
-  int32_t select_mode;    /* decode pipeline of the bf16 matrix-core shapes: 0 = by the bounds (filtered unless
-                             max_K exceeds an eighth of the largest mid-region), 1 = spill (score_mid writes
+  int32_t select_mode;    /* decode pipeline of the bf16 matrix-core shapes: 0 = by the bounds (filtered where it
+                             measured faster: d_head = 128 and max_K at most 1/64 of the largest mid-region),
+                             1 = spill (score_mid writes
                              every score and chunk histograms; plan / emit / resolve select from them),
                              2 = filtered (a sampled lower bound of the K-th score prunes what the score pass
                              writes; one select kernel per step).  Ignored where only the spill pipeline applies

@@ -51,7 +51,10 @@ def test_random_configurations(seed):
         b = H.Batch(H.config_of(w, cache_features=cache, d_emb=d_emb, max_gen=max_gen), layers, ks, debug=True)
         b.build()
         b.decode(modes[mode])
-        assert b.status() in (0, B.TKPHI_DEV_CLAMPED)      # (a clamp is checked per head by check_layer)
+        st = b.status()
+        assert st in (0, B.TKPHI_DEV_CLAMPED)               # (a clamp is checked per head by check_layer)
+        if st == B.TKPHI_DEV_CLAMPED:
+            print(f"seed {seed} case {case}: residual clamp fired", flush=True)
         for i, (P, k) in enumerate(zip(layers, ks)):
             heads = sorted(set(int(x) for x in rng.integers(0, w.n_q_heads, size=2)))
             PU.check_layer(w, P, k, b, i, heads=heads, mode=mode)
