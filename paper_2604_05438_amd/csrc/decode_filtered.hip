@@ -55,8 +55,12 @@ constexpr int kInBin = 256;
 constexpr int kSigmas = 4;             // margin of the sampled bound in standard deviations (a miss costs one rescan)
 template <int D, int TPI>
 __device__ __forceinline__ void prep_sample(const Geom& g, const tkphi_problem& pr, char* blk, int h, float* sc, uint32_t* hist,
-                                            uint32_t* inb, int* nin) {
+                                            uint32_t* inb, int* nin, char* stage_all) {
   constexpr int KS = D / 32, TOK = TPI * 16;
+  // The sampled key rows are loaded whole-row-wise (a load instruction covers 64 / LPRW complete rows: one
+  // workgroup pulls 2.6 times the bytes per second that it gets with the 16 rows x 64 bytes of the MFMA operand
+  // layout) and pass through a wavefront-private LDS strip of one 16-row tile into the operand layout.
+  constexpr int LPRW = D / 8, RPI = 64 / LPRW, NLD = TOK / RPI, ROWP = D * 2 + 16;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, r = lane & 15, kg = lane >> 4;
   const int G = g.G;
   const int n = mid_size(pr.L, g.n_sink, g.n_tail);
@@ -78,16 +82,15 @@ __device__ __forceinline__ void prep_sample(const Geom& g, const tkphi_problem& 
   ScoreFrag bq[KS];
   load_query_frags<D>(g, pr, h, bq);
   const size_t row_bytes = (size_t)pr.stride_tok * 2;
-  const char* Kb = (const char*)pr.K + ((size_t)h * pr.stride_head + (size_t)g.n_sink * pr.stride_tok) * 2 + (size_t)kg * 16;
+  const char* K0 = (const char*)pr.K + ((size_t)h * pr.stride_head + (size_t)g.n_sink * pr.stride_tok) * 2 + (size_t)(lane % LPRW) * 16;
+  char* stage = stage_all + (size_t)wv * 16 * ROWP;
   TKPHI_WAVE_MARK((blk - g.off_problem0), 80);       // before the key loads
   for (int i0 = wv * TOK; i0 < m; i0 += kPrepWaves * TOK) {
-    ScoreFrag a[TPI][KS];
+    u32x4 raw[NLD];
 #pragma unroll
-    for (int t = 0; t < TPI; ++t) {
-      const int si = min(i0 + t * 16 + r, m - 1);
-      const char* rp = Kb + (size_t)sample_row(si, n, m) * row_bytes;
-#pragma unroll
-      for (int j = 0; j < KS; ++j) a[t][j].u = gload128(rp + j * 64);
+    for (int u = 0; u < NLD; ++u) {
+      const int si = min(i0 + u * RPI + lane / LPRW, m - 1);
+      raw[u] = gload128(K0 + (size_t)sample_row(si, n, m) * row_bytes);
     }
     __builtin_amdgcn_sched_barrier(0);
     TKPHI_WAVE_MARK((blk - g.off_problem0), 96);     // loads issued
@@ -97,9 +100,17 @@ __device__ __forceinline__ void prep_sample(const Geom& g, const tkphi_problem& 
     TKPHI_WAVE_MARK((blk - g.off_problem0), 112);    // loads complete
 #pragma unroll
     for (int t = 0; t < TPI; ++t) {
+      // tile t = rows 16 t .. 16 t + 15 of the wavefront's share = load instructions 16 t / RPI .. ; LDS operations of
+      // one wavefront execute in order, so the strip needs no barrier
+#pragma unroll
+      for (int u = t * 16 / RPI; u < (t + 1) * 16 / RPI; ++u)
+        *(u32x4*)(stage + (u * RPI + lane / LPRW - t * 16) * ROWP + (lane % LPRW) * 16) = raw[u];
+      ScoreFrag a[KS];
+#pragma unroll
+      for (int j = 0; j < KS; ++j) a[j].u = *(const u32x4*)(stage + r * ROWP + j * 64 + kg * 16);
       st_floatx4 acc = (st_floatx4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int j = 0; j < KS; ++j) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t][j].v, bq[j].v, acc, 0, 0, 0);
+      for (int j = 0; j < KS; ++j) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[j].v, bq[j].v, acc, 0, 0, 0);
       // lane (r < G, kg) holds head r's scores of samples i0 + t 16 + 4 kg + {0..3}: to LDS, so that every lane
       // takes part in what follows (12 of 64 lanes hold all the scores here)
       if (r < G) *(st_floatx4*)(sc + r * 1024 + i0 + t * 16 + 4 * kg) = acc;
@@ -331,8 +342,8 @@ __device__ __forceinline__ void prep_anchor(const Geom& g, const tkphi_problem& 
 template <int D, int TPI>
 __global__ __launch_bounds__(kPrepThreads) void decode_prep_kernel(Geom g, const tkphi_problem* __restrict__ probs,
                                                                    char* __restrict__ ws) {
-  // sample job: sc [G][1024] floats + hist [G][kBins] + inb [G][kInBin] (G (4096 + 2048 + 1024) bytes);
-  // phi / anchor jobs: 16 KB of reduction scratch
+  // sample job: sc [G][1024] floats + hist [G][kBins] + inb [G][kInBin] (G (4096 + 2048 + 1024) bytes), then the
+  // staging strips, 16 wavefronts x 16 rows x (2 D + 16) bytes; phi / anchor jobs: 16 KB of reduction scratch
   extern __shared__ __attribute__((aligned(16))) float sh_dyn[];
   __shared__ float sh_a[kMaxDim], sh_b[kMaxDim];
   __shared__ int sh_nin[kMaxGroup];
@@ -351,7 +362,7 @@ __global__ __launch_bounds__(kPrepThreads) void decode_prep_kernel(Geom g, const
 #endif
   if (job == 0) {
     uint32_t* hist = (uint32_t*)(sh_dyn + g.G * 1024);
-    prep_sample<D, TPI>(g, pr, blk, h, sh_dyn, hist, hist + g.G * kBins, sh_nin);
+    prep_sample<D, TPI>(g, pr, blk, h, sh_dyn, hist, hist + g.G * kBins, sh_nin, (char*)(hist + g.G * (kBins + kInBin)));
     TKPHI_PHASE(ws, 2);
 #ifdef TKPHI_PHASE_CLOCK
     if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) ((unsigned long long*)(ws + 16))[27] = clock64();
@@ -389,7 +400,11 @@ __global__ __launch_bounds__(kThreads) void score_filtered_kernel(Geom g, const 
 
 void launch_prep(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
   dim3 grid(1 + g.G * (1 + g.n_atiles), g.Hkv, g.n_problems);
-  const size_t lds = std::max((size_t)g.G * (1024 + kBins + kInBin) * 4, (size_t)16384);    // <= 56 KB at G = 8
+  // <= 56 KB at G = 8, plus 68 KB (d = 128) / 36 KB (d = 64) of staging strips
+  const size_t lds = std::max((size_t)g.G * (1024 + kBins + kInBin) * 4 + (size_t)kPrepWaves * 16 * (g.d * 2 + 16), (size_t)16384);
+  const void* fn = g.d == 128 ? (const void*)decode_prep_kernel<128, 4> : (const void*)decode_prep_kernel<64, 8>;
+  const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) { set_error("hipFuncSetAttribute(%zu bytes of LDS): %s", lds, hipGetErrorString(e)); return; }
   if (g.d == 128) TKPHI_LAUNCH(ST_PREP, (decode_prep_kernel<128, 4>), grid, dim3(kPrepThreads), lds, s, g, probs, ws);
   else TKPHI_LAUNCH(ST_PREP, (decode_prep_kernel<64, 8>), grid, dim3(kPrepThreads), lds, s, g, probs, ws);
 }
