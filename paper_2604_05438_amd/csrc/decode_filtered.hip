@@ -395,7 +395,10 @@ __global__ __launch_bounds__(kThreads) void score_filtered_kernel(Geom g, const 
   ScoreFrag bq[D / 32];
   load_query_frags<D>(g, pr, h, bq);
   const uint32_t edge_r = r < g.G ? ((const uint32_t*)(blk + g.off_thr))[h * g.G + r] : 0xffffffffu;
-  scan_wave_slot<D, TPI>(g, pr, blk, h, n, n_chunks, chunk, (int)(threadIdx.x >> 6), bq, edge_r, -1);
+  extern __shared__ __attribute__((aligned(16))) uint2 sh_heads[];      // [4 wavefronts][G][cand_T]
+  const int wv = (int)(threadIdx.x >> 6);
+  scan_wave_slot<D, TPI>(g, pr, blk, h, n, n_chunks, chunk, wv, bq, edge_r, -1, false,
+                         g.head_strip ? sh_heads + (size_t)wv * g.G * g.cand_T : nullptr);
 }
 
 void launch_prep(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
@@ -412,8 +415,9 @@ void launch_prep(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_
 void launch_score_filtered(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
   if (g.max_mid == 0) return;
   dim3 grid(g.n_scan_chunks, g.Hkv, g.n_problems);
-  if (g.d == 128) TKPHI_LAUNCH(ST_SCORE, (score_filtered_kernel<128, 4>), grid, dim3(kThreads), 0, s, g, probs, ws);
-  else TKPHI_LAUNCH(ST_SCORE, (score_filtered_kernel<64, 8>), grid, dim3(kThreads), 0, s, g, probs, ws);
+  const size_t lds = g.head_strip ? (size_t)4 * g.G * g.cand_T * sizeof(uint2) : 0;   // the wavefronts' strips of list heads
+  if (g.d == 128) TKPHI_LAUNCH(ST_SCORE, (score_filtered_kernel<128, 4>), grid, dim3(kThreads), lds, s, g, probs, ws);
+  else TKPHI_LAUNCH(ST_SCORE, (score_filtered_kernel<64, 8>), grid, dim3(kThreads), lds, s, g, probs, ws);
 }
 
 }  // namespace tkphi

@@ -39,6 +39,10 @@ __device__ __forceinline__ size_t cand_region(const Geom& g, int gq, int chunk, 
 // One wavefront: slot `wslot` of chunk `chunk` of KV head h (n mid tokens, n_chunks chunks).
 //   edge_r   lower bound of the score key for the query head of this lane's column r (ignored for r >= G)
 //   only_gl  -1: every head of the group; else only head h G + only_gl is written
+//   strip    null, or this wavefront's LDS strip of G x cand_T entries: the compact heads of the G lists are
+//            collected there and go to memory at the end as whole lines (a head is cand_T contiguous entries, the
+//            four slots of a chunk adjoin), instead of one 8-byte store per candidate scattered through the scan:
+//            fewer partly written lines for the L2 to write back in the middle of the read stream
 //   rescan   write the rescan set of lists, compact heads and counts (the select kernel's second attempt reads
 //            only that set, so what a first attempt reads is never overwritten while another workgroup reads it)
 // Lane (r, kg) ends up with the scores of head r for tokens base + t 16 + 4 kg + i, so each list is
@@ -46,7 +50,7 @@ __device__ __forceinline__ size_t cand_region(const Geom& g, int gq, int chunk, 
 template <int D, int TPI, int SUB = TPI>   // SUB: 16-token tiles whose loads are in flight together (the rescan keeps registers low)
 __device__ __forceinline__ void scan_wave_slot(const Geom& g, const tkphi_problem& pr, char* blk, int h, int n, int n_chunks,
                                                int chunk, int wslot, const ScoreFrag (&bq)[D / 32], uint32_t edge_r,
-                                               int only_gl, bool rescan = false) {
+                                               int only_gl, bool rescan = false, uint2* strip = nullptr) {
   constexpr int KS = D / 32;
   constexpr int TOK = TPI * 16;         // tokens per wavefront and unit
   const int lane = threadIdx.x & 63, r = lane & 15, kg = lane >> 4;
@@ -101,12 +105,20 @@ __device__ __forceinline__ void scan_wave_slot(const Geom& g, const tkphi_proble
             const int at = cnt + __popcll(mine & lanes_below);
             if (pass) {
               const uint2 e = make_uint2(__float_as_uint(s), (uint32_t)tok);
-              if (at < T) head[at] = e; else if (at < cap) list[at] = e;
+              if (at < T) { if (strip) strip[min(r, G - 1) * T + at] = e; else head[at] = e; }
+              else if (at < cap) list[at] = e;
             }
             cnt += __popcll(mine);
           }
         }
       }
+    }
+  }
+  if (strip) {                          // (LDS operations of one wavefront execute in order: no barrier)
+    for (int gl = 0; gl < G; ++gl) {
+      const int c = min(__shfl(cnt, gl), T);          // lane gl is lane (r = gl, kg = 0) of column gl
+      uint2* hd = (uint2*)(blk + (rescan ? g.off_resc : g.off_candc)) + (((size_t)(h * G + gl) * g.n_scan_chunks + chunk) * 4 + wslot) * (size_t)T;
+      for (int i = lane; i < c; i += 64) hd[i] = strip[gl * T + i];
     }
   }
   if (col_live && kg == 0)

@@ -157,6 +157,7 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   // times the expected length); with 128 chunks per head the compact lists of a head are one sweep of the
   // fused select + gather kernel
   g->cand_T = (int)align_up((size_t)std::max(24, g->scan_chunk / 4 * 3 / 32), 12);
+  g->head_strip = (size_t)4 * g->G * g->cand_T * sizeof(uint2) <= 32768 ? 1 : 0;
   g->off_candc = p;   p = align_up(p + (g->filtered ? (size_t)g->Hq * g->n_scan_chunks * 4 * g->cand_T * sizeof(uint2) : (size_t)0), 256);
   g->off_ccount = p;  p = align_up(p + (g->filtered ? (size_t)g->Hq * g->n_scan_chunks * 4 * sizeof(uint32_t) : (size_t)0), 256);
   g->off_resf = p;    p = align_up(p + (g->filtered ? (size_t)g->Hq * g->n_scan_chunks * g->scan_chunk * sizeof(uint2) : (size_t)0), 256);
