@@ -89,6 +89,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
   // ---- first sweep, speculatively: addresses depend on the launch geometry only --------------------------
   u32x4 e0[kSweepLoads];
   uint32_t c0 = 0;
+  const uint32_t edge0 = ((const uint32_t*)(blk + g.off_thr))[gq];   // the bound the score pass pruned this head with
   {
     const int s = kSweepEntries * tid, list = s / T;
     if (list < n_reg_max) {
@@ -177,12 +178,15 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
     return;
   }
   // Wk[h] for the gather phase: requested now (the first sweep has arrived, nothing else is in flight), stored
-  // to LDS after the histogram pass
+  // to LDS right before the gather (the barrier after the histogram pass orders LDS only, so it does not wait
+  // for these loads)
   WkPieces<D, kSelThreads> wkp;
   wkp.request(pr.Wk, h);
   float bk_t = 0.f, pq_t = 0.f;
   if (tid < D) { bk_t = pr.bk[(size_t)h * D + tid]; pq_t = ((const float*)(blk + g.off_phiq))[(size_t)gq * D + tid]; }
 
+  // (have_e0 is false exactly after a rescan: those lists were written without a bound)
+  const SelBins bin_of{edge0, have_e0 && edge0 != 0u && edge0 != 0xffffffffu};
   // ---- pass A: histogram of the candidates' fine bins ----------------------------------------------------------
   for (int i = tid; i < kFineBins; i += kSelThreads) sh_hist[i] = 0u;
   if (tid == 0) { sh_bstar = -1; sh_krem = 0; sh_chi = 0; sh_nb = 0; sh_nbc = 0; sh_thr = 0ull; }
@@ -202,11 +206,9 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
     }
 #pragma unroll
     for (int i = 0; i < kSweepEntries; ++i)
-      if (i < sh.nvalid) atomicAdd(&sh_hist[fine_bin(score_key(__uint_as_float(entry(e, i).x)))], 1u);
+      if (i < sh.nvalid) atomicAdd(&sh_hist[bin_of(score_key(__uint_as_float(entry(e, i).x)))], 1u);
   }
-  wkp.commit(wk_lds);                               // (visible after the barriers that follow)
-  if (tid < D) { sh_bk[tid] = bk_t; sh_pq[tid] = pq_t; }
-  __syncthreads();
+  lds_barrier();                                    // (the histogram is LDS traffic; the Wk loads stay in flight)
   TKPHI_PHASE(ws, 12);
   {
     // thread t looks at bins kFineBins - 1 - 2t and kFineBins - 2 - 2t: a prefix scan over t is a suffix scan over the bins
@@ -216,7 +218,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
     const int gt1 = incl - c1 - c2, ge1 = gt1 + c1, ge2 = incl;
     if (ge1 >= Ksel && gt1 < Ksel) { sh_bstar = b1; sh_krem = Ksel - gt1; sh_chi = gt1; sh_nb = c1; }
     if (ge2 >= Ksel && ge1 < Ksel) { sh_bstar = b2; sh_krem = Ksel - ge1; sh_chi = ge1; sh_nb = c2; }
-    __syncthreads();
+    lds_barrier();
   }
   const int bstar = sh_bstar, krem = sh_krem, c_hi = sh_chi, nb = sh_nb;
   if (bstar < 0) {                                  // cannot happen: total >= Ksel
@@ -244,14 +246,14 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
         if (i < sh.nvalid) {
           const uint2 en = entry(e, i);
           const uint32_t key = score_key(__uint_as_float(en.x));
-          if (fine_bin(key) == bstar) {
+          if (bin_of(key) == bstar) {
             const int at = atomicAdd(&sh_nbc, 1);
             if (at < kBCap) bcand[at] = composite(key, en.y);
           }
         }
       }
     }
-    __syncthreads();
+    lds_barrier();
     const int sub = tid & 7, slot = tid >> 3;
     for (int k0 = 0; k0 < nb; k0 += kSelThreads / 8) {
       const int j = k0 + slot;
@@ -269,7 +271,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
       rank += __shfl_xor(rank, 4);
       if (valid && sub == 0 && rank == krem - 1) sh_thr = mine;
     }
-    __syncthreads();
+    lds_barrier();
   } else {
     // the slot (sweep, thread, entry) as one index for the radix passes (e.g. all scores equal)
     auto get = [&](int j, uint64_t* v) {
@@ -280,7 +282,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
       const uint2 e = sh.src[i];
       const uint32_t key = score_key(__uint_as_float(e.x));
       *v = composite(key, e.y);
-      return fine_bin(key) == bstar;
+      return bin_of(key) == bstar;
     };
     const uint64_t t = radix_select_desc(n_sweeps * kSelThreads * kSweepEntries, krem, get, sh_hist, sh_scan, &sh_prefix, &sh_want);
     if (tid == 0) sh_thr = t;
@@ -319,7 +321,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
     const int incl = sel_scan_incl(packed, sh_scan);
     if (tid == kSelThreads - 1) sh_tot = incl;
     int at = my_count + ((incl - packed) & 0xffff);   // rank among this workgroup's winners
-    __syncthreads();
+    lds_barrier();
     const int tot = sh_tot;
     if (mine) {
 #pragma unroll
@@ -334,7 +336,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
     }
     my_count += tot & 0xffff;
     my_base += tot >> 16;
-    __syncthreads();
+    lds_barrier();
   }
   // the retrieved list of the head, for the exports of the merge kernel and for winners beyond the LDS stage:
   // a second pass writes this workgroup's winners at my_base + rank (list positions never leave [0, Ksel))
@@ -387,6 +389,8 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
   constexpr int NPASS = kBatch / RPP;               // 4 or 2
   const int seg = tid % LPR, rsub = tid / LPR;
   float run_m = -INFINITY, run_Z = 0.f, run_zs = 0.f, run_nu = 0.f, run_zv = 0.f;   // (nu, zv: channel tid < D)
+  wkp.commit(wk_lds);                               // (requested before the histogram pass: long since arrived)
+  if (tid < D) { sh_bk[tid] = bk_t; sh_pq[tid] = pq_t; }
   __syncthreads();                                  // lds_a changes hands; the staged Wk is complete
   // (inside the loop the wavefronts exchange data through LDS only: its barriers leave the key and value loads in flight)
   for (int b0 = 0; b0 < my_count; b0 += kBatch) {

@@ -10,7 +10,7 @@ namespace tkphi {
 
 constexpr int kSelWaves = kSelThreads / 64;
 
-// inclusive prefix sum over the 1024 threads; sh must hold >= 16 ints; two barriers
+// inclusive prefix sum over the 1024 threads; sh must hold >= 16 ints; two barriers (ordering LDS only)
 __device__ __forceinline__ int sel_scan_incl(int v, int* sh) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   int x = v;
@@ -20,10 +20,10 @@ __device__ __forceinline__ int sel_scan_incl(int v, int* sh) {
     if (lane >= o) x += y;
   }
   if (lane == 63) sh[w] = x;
-  __syncthreads();
+  lds_barrier();
   int add = 0;
   for (int i = 0; i < w; ++i) add += sh[i];
-  __syncthreads();
+  lds_barrier();
   return x + add;
 }
 
@@ -78,5 +78,19 @@ __device__ __forceinline__ int fine_bin(uint32_t key) {
   const int mb = e < kExpLo ? 0 : e > kExpHi ? half - 1 : (e - kExpLo) * 64 + m6;
   return pos ? half + mb : half - 1 - mb;
 }
+
+// The binning the fused select kernel uses.  All candidates of a head have keys >= the head's sampled bound, and
+// most lie within an octave above it: measured from the bound, 2^13 key units (1024 bins per octave of the score)
+// per bin spread them over about a thousand bins, so the histogram's LDS atomics rarely collide and the
+// boundary bin holds a handful of candidates instead of ~100.  Keys further up share the top bin.  Without a
+// usable bound (no pruning, or after a rescan) the fixed map applies.  Monotone in the key either way.
+struct SelBins {
+  uint32_t edge;
+  bool relative;
+  __device__ __forceinline__ int operator()(uint32_t key) const {
+    if (!relative) return fine_bin(key);
+    return key >= edge ? (int)min((key - edge) >> 13, (uint32_t)(kFineBins - 1)) : 0;
+  }
+};
 
 }  // namespace tkphi
