@@ -37,6 +37,7 @@ constexpr int kBCap = 1024;            // boundary-bin candidates ranked in LDS
 constexpr int kSweepEntries = 12;      // entries per thread and sweep (Geom::cand_T is a multiple)
 constexpr int kSweepLoads = kSweepEntries / 2;
 constexpr int kBatch = 256;            // winners gathered per round: 16 per wavefront
+constexpr int kDense = 8192;           // candidates of a head that the select phase packs into LDS
 constexpr int kWinLds = 512;           // winners of a workgroup kept in LDS (the rest are re-read from the retrieved list)
 
 // every mid token of query head gq becomes a candidate: the head's lists are written again with no bound, into
@@ -60,13 +61,14 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
   // select phase: histogram (8 KB) + boundary candidates (8 KB); gather phase: reduction scratch of the value sums
   __shared__ __attribute__((aligned(16))) char lds_a[16384];
   __shared__ __attribute__((aligned(16))) char wk_lds[D * WROW];
+  __shared__ uint2 dense[kDense];                   // the candidates of the head, packed (select phase)
   __shared__ int w_tok[kWinLds];
   __shared__ float w_s[kWinLds];
   __shared__ float b_w[kBatch], b_z[kBatch];
   __shared__ float sh_bk[D], sh_pq[D];              // bk[h] and phi_q of the head, staged with Wk
   __shared__ int sh_scan[kSelWaves];
   __shared__ uint64_t sh_prefix, sh_thr;
-  __shared__ int sh_want, sh_tot;
+  __shared__ int sh_want, sh_tot, sh_r0, sh_r1;
   __shared__ int sh_bstar, sh_krem, sh_chi, sh_nb, sh_nbc;
   __shared__ uint32_t sh_total, sh_ovp;
   __shared__ float sh_m, sh_Z, sh_zs;
@@ -187,196 +189,300 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
 
   // (have_e0 is false exactly after a rescan: those lists were written without a bound)
   const SelBins bin_of{edge0, have_e0 && edge0 != 0u && edge0 != 0xffffffffu};
-  // ---- pass A: histogram of the candidates' fine bins ----------------------------------------------------------
-  for (int i = tid; i < kFineBins; i += kSelThreads) sh_hist[i] = 0u;
-  if (tid == 0) { sh_bstar = -1; sh_krem = 0; sh_chi = 0; sh_nb = 0; sh_nbc = 0; sh_thr = 0ull; }
-  __syncthreads();
-  for (int sw = 0; sw < n_sweeps; ++sw) {
-    const Share sh = share_of(sw, tid, (sw == 0 && have_e0) ? (int)min(c0, cap_w) : -1);
-    u32x4 e[kSweepLoads];
-    if (sw == 0 && have_e0) {
-#pragma unroll
-      for (int u = 0; u < kSweepLoads; ++u) e[u] = e0[u];
-    } else {
-      load_share(sh, e);
-      if (sw == 0) {
-#pragma unroll
-        for (int u = 0; u < kSweepLoads; ++u) e0[u] = e[u];
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < kSweepEntries; ++i)
-      if (i < sh.nvalid) atomicAdd(&sh_hist[bin_of(score_key(__uint_as_float(entry(e, i).x)))], 1u);
-  }
-  lds_barrier();                                    // (the histogram is LDS traffic; the Wk loads stay in flight)
-  TKPHI_PHASE(ws, 12);
-  {
-    // thread t looks at bins kFineBins - 1 - 2t and kFineBins - 2 - 2t: a prefix scan over t is a suffix scan over the bins
-    const int b1 = kFineBins - 1 - 2 * tid, b2 = b1 - 1;
-    const int c1 = (int)sh_hist[b1], c2 = (int)sh_hist[b2];
-    const int incl = sel_scan_incl(c1 + c2, sh_scan);
-    const int gt1 = incl - c1 - c2, ge1 = gt1 + c1, ge2 = incl;
-    if (ge1 >= Ksel && gt1 < Ksel) { sh_bstar = b1; sh_krem = Ksel - gt1; sh_chi = gt1; sh_nb = c1; }
-    if (ge2 >= Ksel && ge1 < Ksel) { sh_bstar = b2; sh_krem = Ksel - ge1; sh_chi = ge1; sh_nb = c2; }
-    lds_barrier();
-  }
-  const int bstar = sh_bstar, krem = sh_krem, c_hi = sh_chi, nb = sh_nb;
-  if (bstar < 0) {                                  // cannot happen: total >= Ksel
-    if (tid == 0 && part == 0) *plan = SelPlan{-1, 0, 0, 0, 0};
-    empty_partial();
-    return;
-  }
-  TKPHI_PHASE(ws, 13);
-
-  // ---- thr: the K_rem-th best composite of the boundary bin ------------------------------------------------
-  if (nb <= kBCap) {
-    // stage the boundary candidates (any order: ranks do not depend on it), then rank by counting the larger
-    // composites, 8 lanes per candidate; the candidate of rank K_rem - 1 is the threshold
-    for (int sw = 0; sw < n_sweeps; ++sw) {
-      const Share sh = share_of(sw, tid, (sw == 0 && have_e0) ? (int)min(c0, cap_w) : -1);
-      u32x4 e[kSweepLoads];
-      if (sw == 0) {
-#pragma unroll
-        for (int u = 0; u < kSweepLoads; ++u) e[u] = e0[u];
-      } else {
-        load_share(sh, e);
-      }
-#pragma unroll
-      for (int i = 0; i < kSweepEntries; ++i) {
-        if (i < sh.nvalid) {
-          const uint2 en = entry(e, i);
-          const uint32_t key = score_key(__uint_as_float(en.x));
-          if (bin_of(key) == bstar) {
-            const int at = atomicAdd(&sh_nbc, 1);
-            if (at < kBCap) bcand[at] = composite(key, en.y);
-          }
-        }
-      }
-    }
-    lds_barrier();
-    const int sub = tid & 7, slot = tid >> 3;
-    for (int k0 = 0; k0 < nb; k0 += kSelThreads / 8) {
-      const int j = k0 + slot;
-      const bool valid = j < nb;
-      const uint64_t mine = valid ? bcand[j] : ~0ull;
-      int rank = 0;
-      int i = sub;
-      for (; i + 24 < nb; i += 32) {
-        const uint64_t x0 = bcand[i], x1 = bcand[i + 8], x2 = bcand[i + 16], x3 = bcand[i + 24];
-        rank += (x0 > mine ? 1 : 0) + (x1 > mine ? 1 : 0) + (x2 > mine ? 1 : 0) + (x3 > mine ? 1 : 0);
-      }
-      for (; i < nb; i += 8) rank += bcand[i] > mine ? 1 : 0;
-      rank += __shfl_xor(rank, 1);
-      rank += __shfl_xor(rank, 2);
-      rank += __shfl_xor(rank, 4);
-      if (valid && sub == 0 && rank == krem - 1) sh_thr = mine;
-    }
-    lds_barrier();
-  } else {
-    // the slot (sweep, thread, entry) as one index for the radix passes (e.g. all scores equal)
-    auto get = [&](int j, uint64_t* v) {
-      const int sw = j / (kSelThreads * kSweepEntries), rem = j % (kSelThreads * kSweepEntries);
-      const Share sh = share_of(sw, rem / kSweepEntries);
-      const int i = rem % kSweepEntries;
-      if (i >= sh.nvalid) return false;
-      const uint2 e = sh.src[i];
-      const uint32_t key = score_key(__uint_as_float(e.x));
-      *v = composite(key, e.y);
-      return bin_of(key) == bstar;
-    };
-    const uint64_t t = radix_select_desc(n_sweeps * kSelThreads * kSweepEntries, krem, get, sh_hist, sh_scan, &sh_prefix, &sh_want);
-    if (tid == 0) sh_thr = t;
-    __syncthreads();
-  }
-  const uint64_t thr = sh_thr;
-  TKPHI_PHASE(ws, 14);
-  if (tid == 0 && part == 0) *plan = SelPlan{bstar, krem, c_hi, nb, Ksel};
-
-  // ---- this workgroup's winners: lists [l0, l1), in list order -----------------------------------------------
+  // This workgroup's share of the gather: the winners of lists [l0, l1), in list order
   const int split = g.sg_split;
   const int per_part = (n_reg + split - 1) / split;
   const int l0 = part * per_part, l1 = min(n_reg, l0 + per_part);
-  int my_base = 0, my_count = 0;                    // winners in earlier lists; winners of this workgroup seen so far
-  for (int sw = 0; sw < n_sweeps; ++sw) {
-    const Share sh = share_of(sw, tid, (sw == 0 && have_e0) ? (int)min(c0, cap_w) : -1);
-    u32x4 e[kSweepLoads];
-    if (sw == 0) {
-#pragma unroll
-      for (int u = 0; u < kSweepLoads; ++u) e[u] = e0[u];
-    } else {
-      load_share(sh, e);
+  int my_base = 0, my_count = 0;                    // winners in earlier lists; winners of this workgroup
+  // Common case: one sweep holds every candidate and there are at most kDense of them (about 2.5 K per head at a
+  // 1 % budget, against 12 K list slots).  They are first packed, in list order, into an LDS array (64 KB that
+  // is otherwise unused: a workgroup of 1024 threads has a CU to itself); histogram, threshold and winners then
+  // walk 3-4 entries per thread instead of 12 slots.
+  if (n_sweeps == 1 && have_e0 && total <= (uint32_t)kDense) {
+    const int n_cand = (int)total;
+    const Share sh0 = share_of(0, tid, (int)min(c0, cap_w));
+    const int nv = sh0.nvalid;
+    for (int i = tid; i < kFineBins; i += kSelThreads) sh_hist[i] = 0u;
+    if (tid == 0) {
+      sh_bstar = -1; sh_krem = 0; sh_chi = 0; sh_nb = 0; sh_nbc = 0; sh_thr = 0ull;
+      sh_r0 = l0 < n_reg ? 0 : n_cand; sh_r1 = n_cand;
     }
-    uint32_t fw = 0;                                // bit i: entry i is retrieved
+    const int off = sel_scan_incl(nv, sh_scan) - nv;       // (its barriers also publish the initial values above)
 #pragma unroll
-    for (int i = 0; i < kSweepEntries; ++i) {
-      if (i < sh.nvalid) {
-        const uint2 en = entry(e, i);
-        if (composite(score_key(__uint_as_float(en.x)), en.y) >= thr) fw |= 1u << i;
+    for (int i = 0; i < kSweepEntries; ++i)
+      if (i < nv) dense[off + i] = entry(e0, i);
+    {
+      const int s0 = kSweepEntries * tid, list = s0 / T;
+      if (s0 % T == 0 && list < n_reg) {               // first slot of a list: where the list starts in the packed array
+        if (list == l0) sh_r0 = off;
+        if (list == l1) sh_r1 = off;
       }
     }
-    const int nw = __popc(fw);
-    const bool mine = sh.list >= l0 && sh.list < l1;
-    // (winners of one sweep: <= 12288 mine, <= 12288 before: 16 bits each)
-    const int packed = (mine ? nw : 0) | ((sh.list < l0 ? nw : 0) << 16);
-    const int incl = sel_scan_incl(packed, sh_scan);
-    if (tid == kSelThreads - 1) sh_tot = incl;
-    int at = my_count + ((incl - packed) & 0xffff);   // rank among this workgroup's winners
     lds_barrier();
-    const int tot = sh_tot;
-    if (mine) {
-#pragma unroll
-      for (int i = 0; i < kSweepEntries; ++i) {
-        if (fw & (1u << i)) {
-          const uint2 en = entry(e, i);
-          if (at < kWinLds) { w_tok[at] = (int)en.y; w_s[at] = __uint_as_float(en.x); }
-          // (global position: filled in below, once the winners of earlier lists in later sweeps are known)
-          ++at;
+    const int r0 = sh_r0, r1 = sh_r1;
+    // ---- histogram -> boundary bin ----------------------------------------------------------------------------
+    for (int idx = tid; idx < n_cand; idx += kSelThreads) atomicAdd(&sh_hist[bin_of(score_key(__uint_as_float(dense[idx].x)))], 1u);
+    lds_barrier();
+    TKPHI_PHASE(ws, 12);
+    {
+      const int b1 = kFineBins - 1 - 2 * tid, b2 = b1 - 1;
+      const int c1 = (int)sh_hist[b1], c2 = (int)sh_hist[b2];
+      const int incl = sel_scan_incl(c1 + c2, sh_scan);
+      const int gt1 = incl - c1 - c2, ge1 = gt1 + c1, ge2 = incl;
+      if (ge1 >= Ksel && gt1 < Ksel) { sh_bstar = b1; sh_krem = Ksel - gt1; sh_chi = gt1; sh_nb = c1; }
+      if (ge2 >= Ksel && ge1 < Ksel) { sh_bstar = b2; sh_krem = Ksel - ge1; sh_chi = ge1; sh_nb = c2; }
+      lds_barrier();
+    }
+    const int bstar = sh_bstar, krem = sh_krem, c_hi = sh_chi, nb = sh_nb;
+    if (bstar < 0) {                                  // cannot happen: total >= Ksel
+      if (tid == 0 && part == 0) *plan = SelPlan{-1, 0, 0, 0, 0};
+      empty_partial();
+      return;
+    }
+    TKPHI_PHASE(ws, 13);
+    // ---- thr: the K_rem-th best composite of the boundary bin -------------------------------------------------
+    if (nb <= kBCap) {
+      for (int idx = tid; idx < n_cand; idx += kSelThreads) {
+        const uint2 en = dense[idx];
+        const uint32_t key = score_key(__uint_as_float(en.x));
+        if (bin_of(key) == bstar) {
+          const int at = atomicAdd(&sh_nbc, 1);
+          if (at < kBCap) bcand[at] = composite(key, en.y);
         }
       }
-    }
-    my_count += tot & 0xffff;
-    my_base += tot >> 16;
-    lds_barrier();
-  }
-  // the retrieved list of the head, for the exports of the merge kernel and for winners beyond the LDS stage:
-  // a second pass writes this workgroup's winners at my_base + rank (list positions never leave [0, Ksel))
-  {
-    int seen = 0;
-    const bool need_global = my_count > kWinLds;
-    for (int sw = 0; sw < n_sweeps; ++sw) {
-      const Share sh = share_of(sw, tid, (sw == 0 && have_e0) ? (int)min(c0, cap_w) : -1);
-      const bool mine = sh.list >= l0 && sh.list < l1;
-      if (n_sweeps == 1 && !need_global && !pr.topk_idx) break;     // (nothing reads the list)
-      u32x4 e[kSweepLoads];
-      if (sw == 0) {
-#pragma unroll
-        for (int u = 0; u < kSweepLoads; ++u) e[u] = e0[u];
-      } else {
-        load_share(sh, e);
+      lds_barrier();
+      const int sub = tid & 7, slot = tid >> 3;
+      for (int k0 = 0; k0 < nb; k0 += kSelThreads / 8) {
+        const int j = k0 + slot;
+        const bool valid = j < nb;
+        const uint64_t mine = valid ? bcand[j] : ~0ull;
+        int rank = 0;
+        for (int i = sub; i < nb; i += 8) rank += bcand[i] > mine ? 1 : 0;
+        rank += __shfl_xor(rank, 1);
+        rank += __shfl_xor(rank, 2);
+        rank += __shfl_xor(rank, 4);
+        if (valid && sub == 0 && rank == krem - 1) sh_thr = mine;
       }
-      uint32_t fw = 0;
+      lds_barrier();
+    } else {                                          // (e.g. all scores equal) radix passes over the packed array
+      auto get = [&](int j, uint64_t* v) {
+        const uint2 en = dense[j];
+        const uint32_t key = score_key(__uint_as_float(en.x));
+        *v = composite(key, en.y);
+        return bin_of(key) == bstar;
+      };
+      const uint64_t t = radix_select_desc(n_cand, krem, get, sh_hist, sh_scan, &sh_prefix, &sh_want);
+      if (tid == 0) sh_thr = t;
+      __syncthreads();
+    }
+    const uint64_t thr = sh_thr;
+    TKPHI_PHASE(ws, 14);
+    if (tid == 0 && part == 0) *plan = SelPlan{bstar, krem, c_hi, nb, Ksel};
+    // ---- winners of the packed range [r0, r1) --------------------------------------------------------------------
+    auto is_winner = [&](int idx, int lim, uint2* en) {
+      if (idx >= lim) return false;
+      *en = dense[idx];
+      return composite(score_key(__uint_as_float(en->x)), en->y) >= thr;
+    };
+    for (int base = r0; base < r1; base += kSelThreads) {
+      uint2 en = make_uint2(0u, 0u);
+      const int flag = is_winner(base + tid, r1, &en) ? 1 : 0;
+      const int incl = sel_scan_incl(flag, sh_scan);
+      if (tid == kSelThreads - 1) sh_tot = incl;
+      const int at = my_count + incl - flag;
+      lds_barrier();
+      if (flag && at < kWinLds) { w_tok[at] = (int)en.y; w_s[at] = __uint_as_float(en.x); }
+      my_count += sh_tot;
+      lds_barrier();
+    }
+    // the retrieved list of the head, for the export of the merge and for winners beyond the LDS stage
+    if (my_count > kWinLds || pr.topk_idx) {
+      int before = 0;
+      for (int idx = tid; idx < r0; idx += kSelThreads) { uint2 en; before += is_winner(idx, r0, &en) ? 1 : 0; }
+      const int incl_b = sel_scan_incl(before, sh_scan);
+      if (tid == kSelThreads - 1) sh_tot = incl_b;
+      lds_barrier();
+      my_base = sh_tot;
+      lds_barrier();
+      int seen = 0;
+      for (int base = r0; base < r1; base += kSelThreads) {
+        uint2 en = make_uint2(0u, 0u);
+        const int flag = is_winner(base + tid, r1, &en) ? 1 : 0;
+        const int incl = sel_scan_incl(flag, sh_scan);
+        if (tid == kSelThreads - 1) sh_tot = incl;
+        const int at = my_base + seen + incl - flag;
+        if (flag && at < min(Ksel, g.max_K)) { sel_idx[at] = (int32_t)en.y; sel_score[at] = __uint_as_float(en.x); }
+        __syncthreads();
+        seen += sh_tot;
+        __syncthreads();
+      }
+    }
+  } else {
+    // (the general path: several sweeps, more candidates than the packed array holds, or the lists of a rescan;
+    // every phase reads its entries from the lists again)
+    // ---- pass A: histogram of the candidates' fine bins ----------------------------------------------------------
+    for (int i = tid; i < kFineBins; i += kSelThreads) sh_hist[i] = 0u;
+    if (tid == 0) { sh_bstar = -1; sh_krem = 0; sh_chi = 0; sh_nb = 0; sh_nbc = 0; sh_thr = 0ull; }
+    __syncthreads();
+    for (int sw = 0; sw < n_sweeps; ++sw) {
+      const Share sh = share_of(sw, tid);
+      u32x4 e[kSweepLoads];
+      load_share(sh, e);
+#pragma unroll
+      for (int i = 0; i < kSweepEntries; ++i)
+        if (i < sh.nvalid) atomicAdd(&sh_hist[bin_of(score_key(__uint_as_float(entry(e, i).x)))], 1u);
+    }
+    lds_barrier();                                    // (the histogram is LDS traffic; the Wk loads stay in flight)
+    TKPHI_PHASE(ws, 12);
+    {
+      // thread t looks at bins kFineBins - 1 - 2t and kFineBins - 2 - 2t: a prefix scan over t is a suffix scan over the bins
+      const int b1 = kFineBins - 1 - 2 * tid, b2 = b1 - 1;
+      const int c1 = (int)sh_hist[b1], c2 = (int)sh_hist[b2];
+      const int incl = sel_scan_incl(c1 + c2, sh_scan);
+      const int gt1 = incl - c1 - c2, ge1 = gt1 + c1, ge2 = incl;
+      if (ge1 >= Ksel && gt1 < Ksel) { sh_bstar = b1; sh_krem = Ksel - gt1; sh_chi = gt1; sh_nb = c1; }
+      if (ge2 >= Ksel && ge1 < Ksel) { sh_bstar = b2; sh_krem = Ksel - ge1; sh_chi = ge1; sh_nb = c2; }
+      lds_barrier();
+    }
+    const int bstar = sh_bstar, krem = sh_krem, c_hi = sh_chi, nb = sh_nb;
+    if (bstar < 0) {                                  // cannot happen: total >= Ksel
+      if (tid == 0 && part == 0) *plan = SelPlan{-1, 0, 0, 0, 0};
+      empty_partial();
+      return;
+    }
+    TKPHI_PHASE(ws, 13);
+
+    // ---- thr: the K_rem-th best composite of the boundary bin ------------------------------------------------
+    if (nb <= kBCap) {
+      // stage the boundary candidates (any order: ranks do not depend on it), then rank by counting the larger
+      // composites, 8 lanes per candidate; the candidate of rank K_rem - 1 is the threshold
+      for (int sw = 0; sw < n_sweeps; ++sw) {
+        const Share sh = share_of(sw, tid);
+        u32x4 e[kSweepLoads];
+        load_share(sh, e);
+#pragma unroll
+        for (int i = 0; i < kSweepEntries; ++i) {
+          if (i < sh.nvalid) {
+            const uint2 en = entry(e, i);
+            const uint32_t key = score_key(__uint_as_float(en.x));
+            if (bin_of(key) == bstar) {
+              const int at = atomicAdd(&sh_nbc, 1);
+              if (at < kBCap) bcand[at] = composite(key, en.y);
+            }
+          }
+        }
+      }
+      lds_barrier();
+      const int sub = tid & 7, slot = tid >> 3;
+      for (int k0 = 0; k0 < nb; k0 += kSelThreads / 8) {
+        const int j = k0 + slot;
+        const bool valid = j < nb;
+        const uint64_t mine = valid ? bcand[j] : ~0ull;
+        int rank = 0;
+        int i = sub;
+        for (; i + 24 < nb; i += 32) {
+          const uint64_t x0 = bcand[i], x1 = bcand[i + 8], x2 = bcand[i + 16], x3 = bcand[i + 24];
+          rank += (x0 > mine ? 1 : 0) + (x1 > mine ? 1 : 0) + (x2 > mine ? 1 : 0) + (x3 > mine ? 1 : 0);
+        }
+        for (; i < nb; i += 8) rank += bcand[i] > mine ? 1 : 0;
+        rank += __shfl_xor(rank, 1);
+        rank += __shfl_xor(rank, 2);
+        rank += __shfl_xor(rank, 4);
+        if (valid && sub == 0 && rank == krem - 1) sh_thr = mine;
+      }
+      lds_barrier();
+    } else {
+      // the slot (sweep, thread, entry) as one index for the radix passes (e.g. all scores equal)
+      auto get = [&](int j, uint64_t* v) {
+        const int sw = j / (kSelThreads * kSweepEntries), rem = j % (kSelThreads * kSweepEntries);
+        const Share sh = share_of(sw, rem / kSweepEntries);
+        const int i = rem % kSweepEntries;
+        if (i >= sh.nvalid) return false;
+        const uint2 e = sh.src[i];
+        const uint32_t key = score_key(__uint_as_float(e.x));
+        *v = composite(key, e.y);
+        return bin_of(key) == bstar;
+      };
+      const uint64_t t = radix_select_desc(n_sweeps * kSelThreads * kSweepEntries, krem, get, sh_hist, sh_scan, &sh_prefix, &sh_want);
+      if (tid == 0) sh_thr = t;
+      __syncthreads();
+    }
+    const uint64_t thr = sh_thr;
+    TKPHI_PHASE(ws, 14);
+    if (tid == 0 && part == 0) *plan = SelPlan{bstar, krem, c_hi, nb, Ksel};
+
+    // ---- this workgroup's winners: lists [l0, l1), in list order -----------------------------------------------
+    for (int sw = 0; sw < n_sweeps; ++sw) {
+      const Share sh = share_of(sw, tid);
+      u32x4 e[kSweepLoads];
+      load_share(sh, e);
+      uint32_t fw = 0;                                // bit i: entry i is retrieved
 #pragma unroll
       for (int i = 0; i < kSweepEntries; ++i) {
-        if (mine && i < sh.nvalid) {
+        if (i < sh.nvalid) {
           const uint2 en = entry(e, i);
           if (composite(score_key(__uint_as_float(en.x)), en.y) >= thr) fw |= 1u << i;
         }
       }
       const int nw = __popc(fw);
-      const int incl = sel_scan_incl(nw, sh_scan);
+      const bool mine = sh.list >= l0 && sh.list < l1;
+      // (winners of one sweep: <= 12288 mine, <= 12288 before: 16 bits each)
+      const int packed = (mine ? nw : 0) | ((sh.list < l0 ? nw : 0) << 16);
+      const int incl = sel_scan_incl(packed, sh_scan);
       if (tid == kSelThreads - 1) sh_tot = incl;
-      int at = my_base + seen + incl - nw;
+      int at = my_count + ((incl - packed) & 0xffff);   // rank among this workgroup's winners
+      lds_barrier();
+      const int tot = sh_tot;
+      if (mine) {
 #pragma unroll
-      for (int i = 0; i < kSweepEntries; ++i) {
-        if (fw & (1u << i)) {
-          const uint2 en = entry(e, i);
-          if (at < min(Ksel, g.max_K)) { sel_idx[at] = (int32_t)en.y; sel_score[at] = __uint_as_float(en.x); }
-          ++at;
+        for (int i = 0; i < kSweepEntries; ++i) {
+          if (fw & (1u << i)) {
+            const uint2 en = entry(e, i);
+            if (at < kWinLds) { w_tok[at] = (int)en.y; w_s[at] = __uint_as_float(en.x); }
+            // (global position: filled in below, once the winners of earlier lists in later sweeps are known)
+            ++at;
+          }
         }
       }
-      __syncthreads();
-      seen += sh_tot;
-      __syncthreads();
+      my_count += tot & 0xffff;
+      my_base += tot >> 16;
+      lds_barrier();
+    }
+    // the retrieved list of the head, for the exports of the merge kernel and for winners beyond the LDS stage:
+    // a second pass writes this workgroup's winners at my_base + rank (list positions never leave [0, Ksel))
+    {
+      int seen = 0;
+      const bool need_global = my_count > kWinLds;
+      for (int sw = 0; sw < n_sweeps; ++sw) {
+        const Share sh = share_of(sw, tid);
+        const bool mine = sh.list >= l0 && sh.list < l1;
+        if (n_sweeps == 1 && !need_global && !pr.topk_idx) break;     // (nothing reads the list)
+        u32x4 e[kSweepLoads];
+        load_share(sh, e);
+        uint32_t fw = 0;
+#pragma unroll
+        for (int i = 0; i < kSweepEntries; ++i) {
+          if (mine && i < sh.nvalid) {
+            const uint2 en = entry(e, i);
+            if (composite(score_key(__uint_as_float(en.x)), en.y) >= thr) fw |= 1u << i;
+          }
+        }
+        const int nw = __popc(fw);
+        const int incl = sel_scan_incl(nw, sh_scan);
+        if (tid == kSelThreads - 1) sh_tot = incl;
+        int at = my_base + seen + incl - nw;
+#pragma unroll
+        for (int i = 0; i < kSweepEntries; ++i) {
+          if (fw & (1u << i)) {
+            const uint2 en = entry(e, i);
+            if (at < min(Ksel, g.max_K)) { sel_idx[at] = (int32_t)en.y; sel_score[at] = __uint_as_float(en.x); }
+            ++at;
+          }
+        }
+        __syncthreads();
+        seen += sh_tot;
+        __syncthreads();
+      }
     }
   }
   TKPHI_PHASE(ws, 15);

@@ -209,12 +209,13 @@ def test_exact_ties_take_lower_index(variant):
 
 
 @pytest.mark.parametrize("variant", list(SELECT_VARIANTS))
-def test_all_scores_equal_slow_path(variant):
+@pytest.mark.parametrize("shape,L", [("l1b_32k", 7000), ("l3b_128k", 3000)])
+def test_all_scores_equal_slow_path(variant, shape, L):
     """Every key identical: the boundary bin holds the whole mid-region (more than the
-    in-LDS candidate capacity), so the global-memory radix passes run; Top-K = first K."""
+    in-LDS candidate capacity), so the radix passes run (7000 tokens: over the lists in global memory;
+    3000 tokens at head dimension 128: over the candidates packed in LDS); Top-K = first K."""
     from paper_2604_05438_amd import harness as H
-    w = I.WORKLOADS["l1b_32k"]
-    L = 7000
+    w = I.WORKLOADS[shape]
     P = I.make_layer(w, L=L)
     P["K"][:, :, :] = P["K"][:, 100:101, :]
     k = 61
