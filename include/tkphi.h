@@ -139,7 +139,7 @@ typedef struct tkphi_tuning {
                              1 = layer-wise launches per token block (residual + output fused),
                              2 = all four layers as separate launches                                    */
   int32_t select_mode;    /* decode pipeline of the bf16 matrix-core shapes: 0 = by the bounds (filtered where it
-                             measured faster: d_head = 128 and max_K at most 1/64 of the largest mid-region),
+                             measured faster: max_K at most 1/64 of the largest mid-region),
                              1 = spill (score_mid writes
                              every score and chunk histograms; plan / emit / resolve select from them),
                              2 = filtered (a sampled lower bound of the K-th score prunes what the score pass
@@ -315,10 +315,11 @@ tkphi_status tkphi_decode_static(const tkphi_config* cfg /*HOST*/,
  * stream synchronisation; stage_ms_out (HOST, TKPHI_N_STAGES floats) receives the
  * duration in milliseconds of each stage:
  *   score_mid (either pipeline's score pass), select_plan (+ the exp-affine phi_q), select_emit,
- *   select_resolve, gather (exact branch + subtraction sums), merge, the three phi_q launches of
- *   the MLP feature maps (they run first; begin of the first to end of the third), and the two
- *   kernels only the filtered pipeline has: prep (sampled score bound, phi_q and the summary terms,
- *   anchors; runs first) and select
+ *   select_resolve, gather (exact branch + subtraction sums), merge (spill pipeline), phi_q (the
+ *   three phi_q launches of the MLP feature maps, begin of the first to end of the third; or, for a
+ *   batch on the filtered pipeline, the phi / anchor jobs of prep as a launch of their own), and the
+ *   two kernels only the filtered pipeline has: prep (sampled score bound; for a few problems also phi_q,
+ *   the summary terms and the anchors; runs first) and select (selection, gather and merge)
  * (0 for a stage that the given configuration and bounds do not launch).  Same validation and results as
  * tkphi_decode; creates and destroys HIP events (no device memory). */
 #define TKPHI_N_STAGES 9

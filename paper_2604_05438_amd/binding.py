@@ -176,7 +176,7 @@ def tkphi_decode_static(cfg: tkphi_config, problems_dev_ptr: int, n_problems: in
 STATIC_SCRATCH_BYTES = 32 << 20
 
 
-STAGES = ("score_mid", "select_plan", "select_emit", "select_resolve", "gather", "merge", "phi_q_mlp", "prep", "select")
+STAGES = ("score_mid", "select_plan", "select_emit", "select_resolve", "gather", "merge", "phi_q", "prep", "select")
 SELECT_SPILL, SELECT_FILTERED = 1, 2          # tkphi_tuning::select_mode
 
 

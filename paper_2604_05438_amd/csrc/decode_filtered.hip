@@ -20,6 +20,7 @@
 //                   (about 2-3 K tokens per head instead of |M|), appended to per-wavefront lists.
 #include <algorithm>
 
+#include "decode_side.h"
 #include "score_tile.h"
 #include "tkphi_internal.h"
 
@@ -337,17 +338,19 @@ __device__ __forceinline__ void prep_anchor(const Geom& g, const tkphi_problem& 
   }
 }
 
-// grid (1 + G (1 + n_atiles), Hkv, n_problems), 1024 threads.  Job 0: sample; jobs 1 .. G: phi of the
-// group's query heads; then n_atiles anchor tiles per query head.
+// grid (jobs, Hkv, n_problems), 1024 threads; job = job0 + blockIdx.x of 1 + G (1 + n_atiles).  Job 0: sample; jobs
+// 1 .. G: phi of the group's query heads; then n_atiles anchor tiles per query head.  One launch for a few
+// problems; for batches the sample jobs (which need ~90 KB of LDS: one workgroup per CU) and the rest (16 KB) are
+// two launches, so that the many small jobs are not held to one workgroup per CU.
 template <int D, int TPI>
 __global__ __launch_bounds__(kPrepThreads) void decode_prep_kernel(Geom g, const tkphi_problem* __restrict__ probs,
-                                                                   char* __restrict__ ws) {
+                                                                   char* __restrict__ ws, int job0) {
   // sample job: sc [G][1024] floats + hist [G][kBins] + inb [G][kInBin] (G (4096 + 2048 + 1024) bytes), then the
   // staging strips, 16 wavefronts x 16 rows x (2 D + 16) bytes; phi / anchor jobs: 16 KB of reduction scratch
   extern __shared__ __attribute__((aligned(16))) float sh_dyn[];
   __shared__ float sh_a[kMaxDim], sh_b[kMaxDim];
   __shared__ int sh_nin[kMaxGroup];
-  const int job = blockIdx.x, h = blockIdx.y, p = blockIdx.z;
+  const int job = job0 + (int)blockIdx.x, h = blockIdx.y, p = blockIdx.z;
   TKPHI_PHASE(ws, 0);
   TKPHI_WAVE_MARK(ws, 32);                           // kernel entered
 
@@ -401,6 +404,23 @@ __global__ __launch_bounds__(kThreads) void score_filtered_kernel(Geom g, const 
                          g.head_strip ? sh_heads + (size_t)wv * g.G * g.cand_T : nullptr);
 }
 
+// The phi and anchor jobs of a batch: grid (G (1 + n_atiles), Hkv, n_problems), 256 threads; job j < G: phi of query
+// head h G + j (and that head's arrival counter <- 0), then n_atiles anchor tiles per query head.
+__global__ __launch_bounds__(kThreads) void decode_side_kernel(Geom g, const tkphi_problem* __restrict__ probs, char* __restrict__ ws) {
+  __shared__ __attribute__((aligned(16))) float sh_f[2 * kMaxDim + 1024];
+  const int job = blockIdx.x, h = blockIdx.y, p = blockIdx.z;
+  const tkphi_problem pr = probs[p];
+  if (pr.L < 1 || pr.L > g.max_L) return;
+  char* blk = problem_block(g, ws, p);
+  if (job < g.G) {
+    if (threadIdx.x == 0) ((uint32_t*)(blk + g.off_mcount))[h * g.G + job] = 0u;
+    side_phi(g, pr, blk, h * g.G + job, sh_f, sh_f + kMaxDim, sh_f + 2 * kMaxDim);
+  } else {
+    const int j = job - g.G;
+    side_anchor(g, pr, blk, h * g.G + j / g.n_atiles, j % g.n_atiles, sh_f, sh_f + 64, sh_f + 128);
+  }
+}
+
 void launch_prep(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
   dim3 grid(1 + g.G * (1 + g.n_atiles), g.Hkv, g.n_problems);
   // <= 56 KB at G = 8, plus 68 KB (d = 128) / 36 KB (d = 64) of staging strips
@@ -408,8 +428,16 @@ void launch_prep(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_
   const void* fn = g.d == 128 ? (const void*)decode_prep_kernel<128, 4> : (const void*)decode_prep_kernel<64, 8>;
   const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) { set_error("hipFuncSetAttribute(%zu bytes of LDS): %s", lds, hipGetErrorString(e)); return; }
-  if (g.d == 128) TKPHI_LAUNCH(ST_PREP, (decode_prep_kernel<128, 4>), grid, dim3(kPrepThreads), lds, s, g, probs, ws);
-  else TKPHI_LAUNCH(ST_PREP, (decode_prep_kernel<64, 8>), grid, dim3(kPrepThreads), lds, s, g, probs, ws);
+  const int n_jobs = 1 + g.G * (1 + g.n_atiles);
+  if ((long)n_jobs * g.Hkv * g.n_problems <= 1024) {
+    if (g.d == 128) TKPHI_LAUNCH(ST_PREP, (decode_prep_kernel<128, 4>), grid, dim3(kPrepThreads), lds, s, g, probs, ws, 0);
+    else TKPHI_LAUNCH(ST_PREP, (decode_prep_kernel<64, 8>), grid, dim3(kPrepThreads), lds, s, g, probs, ws, 0);
+    return;
+  }
+  dim3 grid_a(1, g.Hkv, g.n_problems), grid_b(n_jobs - 1, g.Hkv, g.n_problems);
+  if (g.d == 128) TKPHI_LAUNCH(ST_PREP, (decode_prep_kernel<128, 4>), grid_a, dim3(kPrepThreads), lds, s, g, probs, ws, 0);
+  else TKPHI_LAUNCH(ST_PREP, (decode_prep_kernel<64, 8>), grid_a, dim3(kPrepThreads), lds, s, g, probs, ws, 0);
+  TKPHI_LAUNCH(ST_PHIQ, decode_side_kernel, grid_b, dim3(kThreads), 0, s, g, probs, ws);
 }
 
 void launch_score_filtered(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {

@@ -121,12 +121,12 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   g->interleave = tn.interleave ? (tn.interleave == 1 ? 1 : 0) : (g->use_mfma && g->scan_unit < g->scan_chunk && g->n_scan_chunks >= 64) ? 1 : 0;
   if (!g->use_mfma || g->scan_unit >= g->scan_chunk) g->interleave = 0;
   // filtered pipeline: where the matrix-core score kernel applies.  Chosen by default where it measured faster
-  // than the spill pipeline: head dimension 128 and a budget of at most 1/64 of the mid-region (128K layer: 94 / 97
-  // against 95 / 100 us per step at 0.5 / 1 %, 28 layers per call 1.79 against 1.87 ms; at 2 % and 4 % the longer
-  // candidate lists make the fused select slower than the spill's three select kernels, 116 / 134 against 108 /
-  // 122 us; at head dimension 64 the two are level on one layer and the spill is 2 % faster on the ragged batch)
+  // than the spill pipeline: a budget of at most 1/64 of the mid-region (128K layer: 86 / 89 against 95 / 100 us
+  // per step at 0.5 / 1 %; 32K layer 42.5 against 44.5 us; 28 layers per call 1.62 against 1.87 ms; the ragged
+  // 256-problem batch 3.36 against 3.65 ms).  At 2 % and 4 % candidate lists overflow their compact heads and the
+  // fused select falls back to its general path: 112 / 128 against 108 / 122 us
   g->filtered = (g->use_mfma && cfg->phi_kind == TKPHI_PHI_EXP_AFFINE && !g->cache && tn.select_mode != 1 &&
-                 (tn.select_mode == 2 || (g->d == 128 && (int64_t)max_K * 64 <= g->max_mid))) ? 1 : 0;
+                 (tn.select_mode == 2 || (int64_t)max_K * 64 <= g->max_mid)) ? 1 : 0;
   g->sel_test = tn.select_test;
   // gather: tiles of kPairsPerWG retrieved tokens per query head
   g->n_tiles = (int)ceil_div(std::min<int64_t>(max_K, g->max_mid), kPairsPerWG);
