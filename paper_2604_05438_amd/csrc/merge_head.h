@@ -86,18 +86,30 @@ __device__ __forceinline__ void merge_head(const Geom& g, const tkphi_problem* _
       vz[k] = ldp(pp + 4 + d + c);
     }
   };
-  if (grp * UN < n_parts) load_batch(grp * UN);
-  float ml = -INFINITY;
-  for (int k = tid; k < n_parts; k += kThreads) ml = fmaxf(ml, ldp(part_ptr(k)));
-  float m = block_max(ml, red_f);
+  // At most UN partials (the usual case: a dozen): every thread takes all of them, finds the shift itself and
+  // needs no exchange with other threads; the sums are those of group 0 of the general scheme, bit for bit.
+  const bool few = n_parts <= UN;
+  float m = -INFINITY;
+  if (few) {
+    load_batch(0);
+#pragma unroll
+    for (int k = 0; k < UN; ++k)
+      if (k < n_parts) m = fmaxf(m, hm[k]);
+  } else {
+    if (grp * UN < n_parts) load_batch(grp * UN);
+    float ml = -INFINITY;
+    for (int k = tid; k < n_parts; k += kThreads) ml = fmaxf(ml, ldp(part_ptr(k)));
+    m = block_max(ml, red_f);
+  }
   const bool empty_E = !(m > -INFINITY);
   if (empty_E) m = 0.f;
 
   // ---- combine the partials in a fixed order ---------------------------------------------------
   float nu = 0.f, zv = 0.f, Z = 0.f, zsum = 0.f;
   float ZA = 0.f;                        // anchor share of Z (diagnostics only)
-  for (int t0 = grp * UN; t0 < n_parts; t0 += NGRP * UN) {
-    if (t0 != grp * UN) load_batch(t0);
+  const int first = few ? 0 : grp * UN;
+  for (int t0 = first; t0 < n_parts; t0 += NGRP * UN) {
+    if (t0 != first) load_batch(t0);
 #pragma unroll
     for (int k = 0; k < UN; ++k) {
       if (t0 + k < n_parts) {
@@ -110,7 +122,7 @@ __device__ __forceinline__ void merge_head(const Geom& g, const tkphi_problem* _
       }
     }
   }
-  {
+  if (!few) {
     // sh_grp is free until the residual sums below: [0] nu, [1] zv per (group, channel); [2] Z, zsum, ZA per group
     float* cmb = &sh_grp[0][0];
     __syncthreads();
