@@ -39,40 +39,75 @@ __device__ __forceinline__ float row_lanes_sum(float s) {
 }
 
 // ------------------------------------------------------------------------------------
-// bf16 on the matrix cores: grid (n_build_chunks, Hkv, n_problems); D == d_head == d_phi.
+// bf16 on the matrix cores: grid (n_build_chunks, Hkv, n_problems), 4 wavefronts,
+// D == d_head == d_phi.  Wavefront w owns the features [w D/4, (w+1) D/4): its slice of Wk
+// stays in registers for the whole chunk.
 //
-// Tiles of 64 tokens; the key and value tiles are staged in LDS once per workgroup (keys
-// row-major, values transposed in registers - 4 tokens x 8 channels per lane - and stored
-// channel-major), |k|^2 is reduced while staging.  Wavefront w owns the features
-// [w*D/NW, (w+1)*D/NW): its slice of Wk stays in registers for the whole chunk.
-//   GEMM1  P[64 tokens][own features] = K Wk^T : A = key rows from LDS, B = Wk slice
+// The chunk is cut into tiles of 32 tokens.  A stage of LDS holds one tile of keys and one of
+// values, both row-major as they lie in the cache, brought in by loads that write LDS
+// directly; NS stages form a ring, so NS - 1 tiles are on their way from HBM while one is
+// contracted, and no register is spent on data in flight.  Per tile:
+//   GEMM1  P[32 tokens][own features] = K Wk^T : A = key rows from LDS, B = Wk slice
 //          -> exp -> bf16 hi + lo; the result registers (4 consecutive tokens per lane and
 //          16-token tile) are already the A operand of GEMM2 over a fixed permutation of
-//          the 32 tokens of a k-step, so the features never touch LDS
-//   GEMM2  S[own features][all channels] += Phi^T V : B = transposed value tile from LDS
-//          (two 8-byte reads per operand, same token permutation), hi and lo as two MFMAs
-// u is summed from the same features.  Two LDS tile buffers: tile t+1 is staged (and the
-// global loads of tile t+2 are issued) before tile t is contracted: one barrier per tile.
+//          the 32 tokens, so the features never touch LDS
+//   GEMM2  S[own features][all channels] += Phi^T V : B = value tile read through the
+//          transposing LDS read (same token permutation), hi and lo as two MFMAs
+// u is summed from the same features.
+//
+// Each load instruction moves 64 x 16 bytes into 1 KB of consecutive LDS (lane l -> bytes
+// 16 l ..), so a lane picks WHICH 16-byte granule of its row it fetches: granule slot s of row
+// r holds granule s ^ f(r) of that row, with f chosen per tensor so that the reads spread
+// over all banks:
+//   keys    read as the A operand of GEMM1 (16 lanes = 16 rows, same granule): f = row mod 16
+//           (rows of 256 bytes), (row / 2) mod 8 (rows of 128 bytes)
+//   values  read by the transposing LDS read (16 lanes take 8 bytes each of 4 rows x 16
+//           channels; lane j receives the 4 tokens of channel j): f = 2 (row mod 8) resp.
+//           2 ((row / 2) mod 4)
+// |k|^2: a wavefront reads back the rows its own loads brought (its own wait covers them), sums
+// the squares with 16-bit dot products and leaves c |k|^2 per row in LDS before the tile's
+// barrier: one barrier per tile.
 // ------------------------------------------------------------------------------------
-// NW wavefronts per workgroup (4 or 8), each owning D / NW features.  The LDS tiles allow two workgroups per CU
-// at D = 128 and four at D = 64, so NW = 8 resp. 4 puts four wavefronts on a SIMD: one's exponentials and staging
-// hide behind another's MFMAs.
-template <int D, bool CACHE, int NW>  // CACHE: also store the contracted features in pr.phi_cache
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4 : NW / 2, D == 64 ? 4 : NW / 2))) void build_mfma_kernel(Geom g, const tkphi_problem* __restrict__ probs,
-                                                                 char* __restrict__ ws) {
+typedef short short4v __attribute__((ext_vector_type(4)));
+
+// 64 lanes x 16 bytes from global memory into LDS at lds_addr (uniform) + 16 * lane; counted by vmcnt.
+// (M0 is not on the clobber list - the compiler reserves it; nothing else in these kernels uses it)
+__device__ __forceinline__ void load_to_lds16(const void* gsrc, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt" : : "v"(gsrc), "s"(lds_addr) : "memory");
+}
+// the same with the address as a uniform base plus a 32-bit offset per lane
+__device__ __forceinline__ void load_to_lds16(const void* base, uint32_t off, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt" : : "v"(off), "s"(base), "s"(lds_addr) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm_loads() {   // at most N vector memory operations still in flight
+  static_assert(N >= 0 && N < 64, "vmcnt has 6 bits");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+  asm volatile("" ::: "memory");                    // no LDS read moves above the wait
+}
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {   // a.lo b.lo + a.hi b.hi + c
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  union { uint32_t u; bf16x2 v; } x, y;
+  x.u = a; y.u = b;
+  return __builtin_amdgcn_fdot2_f32_bf16(x.v, y.v, c, false);
+}
+
+template <int D, bool CACHE, int NS>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4 : 2, D == 64 ? 4 : 2)))
+void build_mfma_kernel(Geom g, const tkphi_problem* __restrict__ probs, char* __restrict__ ws) {
+  constexpr int NW = 4;
   constexpr int KS = D / 32;            // k-steps of GEMM1 (over channels)
-  constexpr int NT = 64 * NW;           // threads
   constexpr int FT = D / (16 * NW);     // feature tiles per wavefront
-  static_assert(FT >= 1, "at least 16 features per wavefront");
   constexpr int CT = D / 16;            // channel tiles of S
-  constexpr int SEGS = D / 8;           // 16-byte segments per row
-  constexpr int KLD = 64 * SEGS / NT;   // key-row loads per thread and tile (4 or 2)
-  constexpr int KROW = D * 2 + 16;      // bytes per staged key row
-  constexpr int TROW = 64 * 2 + 16;     // bytes per staged value-channel row (64 tokens)
-  // two tile buffers: tile t+1 is staged while tile t is contracted, one barrier per tile
-  __shared__ __attribute__((aligned(16))) char k_tb[2][64 * KROW];    // [token][channel]
-  __shared__ __attribute__((aligned(16))) char v_tb[2][D * TROW];     // [channel][token]
-  __shared__ __attribute__((aligned(16))) float nrm_tb[2][64];        // c |k|^2 log2(e); +inf past the chunk end
+  constexpr int GR = D / 8;             // 16-byte granules per row
+  constexpr int TT = 32;                // tokens per tile
+  constexpr int ROWB = D * 2;           // bytes per row
+  constexpr int TILEB = TT * ROWB;      // bytes per key (or value) tile
+  constexpr int RPI = 64 / GR;          // rows one load instruction covers
+  constexpr int NLD = TT / (RPI * NW);  // load instructions per wavefront, tile and tensor
+  static_assert(NLD >= 1 && NS >= 3 && NS <= 6, "ring shape");
+  extern __shared__ __attribute__((aligned(1024))) char ring[];   // [NS][keys, values][TT][ROWB], then norms [NS][TT]
+  float* nrm_all = (float*)(ring + NS * 2 * TILEB);               // c |k|^2 log2(e); +inf past the chunk end
 
   const int ch = blockIdx.x, h = blockIdx.y, p = blockIdx.z, tid = threadIdx.x;
   const tkphi_problem pr = probs[p];
@@ -81,10 +116,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D == 64
   const int c0 = ch * g.build_chunk;
   if (c0 >= n) return;
   const int c1 = min(n, c0 + g.build_chunk);
-  const int lane = tid & 63, wv = tid >> 6, r = lane & 15, kg = lane >> 4;
+  const int lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), r = lane & 15, kg = lane >> 4;
   const float a2 = g.a * kLog2e, c2 = g.c * kLog2e;
 
-  // Wk slice: wk[ft][j] = Wk[h][feature wv*D/4 + ft*16 + r][channels j*32 + kg*8 .. +8]
   Frag wk[FT][KS];
   float bias[FT];
   {
@@ -97,6 +131,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D == 64
       bias[ft] = pr.bk[(size_t)h * D + feat] * kLog2e;
     }
   }
+  wait_vm_loads<0>();                    // (the tile loads below are counted by hand)
   floatx4 sacc[FT][CT];
 #pragma unroll
   for (int ft = 0; ft < FT; ++ft)
@@ -108,93 +143,91 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D == 64
 
   const size_t row_bytes = (size_t)pr.stride_tok * 2;
   const size_t base_off = ((size_t)h * pr.stride_head + (size_t)g.n_sink * pr.stride_tok) * 2;
-  // key loads: thread (krow = tid / SEGS, seg = tid % SEGS) takes rows krow + i * (256 / SEGS)
-  const int kseg = tid % SEGS, krow = tid / SEGS;
-  constexpr int KRP = NT / SEGS;  // key rows per pass
-  // value loads: thread (tq, sg) takes tokens 4*tq .. 4*tq+3 of the tile, 16-byte segment sg
-  const bool v_active = tid < 16 * SEGS;
-  const int tq = tid % 16, sg = tid / 16;
-  // A tile's rows start at a uniform address; a thread's byte offsets inside a full tile never change
-  // (32 bits: a tile spans 64 rows), so the loads of a full tile are base + offset with no per-row arithmetic.
   const char* Kt = (const char*)pr.K + base_off;
   const char* Vt = (const char*)pr.V + base_off;
-  uint32_t koff[KLD], voff[4];
-#pragma unroll
-  for (int i = 0; i < KLD; ++i) koff[i] = (uint32_t)((krow + i * KRP) * row_bytes) + kseg * 16;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) voff[i] = (uint32_t)((tq * 4 + i) * row_bytes) + sg * 16;
+  const uint32_t ring_addr = (uint32_t)(size_t)(__attribute__((address_space(3))) char*)ring;
 
-  u32x4 kk[KLD], vv[4];
-  auto issue_loads = [&](int t0) {
-    const char* kt = Kt + (size_t)t0 * row_bytes;
-    const char* vt = Vt + (size_t)t0 * row_bytes;
-    if (t0 + 64 <= c1) {                 // full tile
+  auto f_key = [](int row) { return GR == 16 ? (row & 15) : ((row >> 1) & 7); };
+  auto f_val = [](int row) { return GR == 16 ? ((row & 7) << 1) : (((row >> 1) & 3) << 1); };
+  // loads: instruction i of wavefront wv fills rows (wv * NLD + i) * RPI .. + RPI of a tile
+  int ld_row[NLD], ld_kg[NLD], ld_vg[NLD];
 #pragma unroll
-      for (int i = 0; i < KLD; ++i) kk[i] = gload128_stream(kt + koff[i]);
-      if (v_active) {
+  for (int i = 0; i < NLD; ++i) {
+    ld_row[i] = (wv * NLD + i) * RPI + lane / GR;
+    ld_kg[i] = ((lane % GR) ^ f_key(ld_row[i])) * 16;
+    ld_vg[i] = ((lane % GR) ^ f_val(ld_row[i])) * 16;
+  }
+  const int n_tiles = (c1 - c0 + TT - 1) / TT;
+  // a full tile is fetched as uniform tile base + a lane's constant 32-bit offset (when a tile's rows span < 2 GiB)
+  const bool near = (uint64_t)TT * row_bytes < (1ull << 31);
+  uint32_t ld_ko[NLD], ld_vo[NLD];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) vv[i] = gload128_stream(vt + voff[i]);
+  for (int i = 0; i < NLD; ++i) {
+    ld_ko[i] = near ? (uint32_t)(ld_row[i] * row_bytes) + ld_kg[i] : 0u;
+    ld_vo[i] = near ? (uint32_t)(ld_row[i] * row_bytes) + ld_vg[i] : 0u;
+  }
+  auto issue = [&](int ti) {             // tile ti of the chunk -> stage ti % NS
+    const int t0 = c0 + ti * TT;
+    const uint32_t st = ring_addr + (uint32_t)(ti % NS) * (2 * TILEB) + (uint32_t)(wv * NLD) * 1024;
+    if (near && t0 + TT <= c1) {
+      const char* kb = Kt + (size_t)t0 * row_bytes;
+      const char* vb = Vt + (size_t)t0 * row_bytes;
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) {
+        load_to_lds16(kb, ld_ko[i], st + i * 1024);
+        load_to_lds16(vb, ld_vo[i], st + TILEB + i * 1024);
       }
-    } else {                             // last tile of the mid-region: rows past the end re-read the last row
+    } else {                             // rows past the end re-read the last row
 #pragma unroll
-      for (int i = 0; i < KLD; ++i) {
-        const int row = min(krow + i * KRP, c1 - 1 - t0);
-        kk[i] = gload128_stream(kt + (size_t)row * row_bytes + kseg * 16);
-      }
-      if (v_active) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int vrow = min(tq * 4 + i, c1 - 1 - t0);
-          vv[i] = gload128_stream(vt + (size_t)vrow * row_bytes + sg * 16);
-        }
+      for (int i = 0; i < NLD; ++i) {
+        const size_t ro = (size_t)min(t0 + ld_row[i], c1 - 1) * row_bytes;
+        load_to_lds16(Kt + ro + ld_kg[i], st + i * 1024);
+        load_to_lds16(Vt + ro + ld_vg[i], st + TILEB + i * 1024);
       }
     }
   };
-
-  auto stage = [&](int t0, char* k_t, char* v_t, float* nrm_t) {
-    const bool full = t0 + 64 <= c1;     // (uniform) no row of the tile lies past the end
-    // ---- stage the tile: keys row-major (+ norms), values channel-major ---------------------
+  // |k|^2 of the rows this wavefront loaded (lane l holds 16 bytes of row l / GR of each of its blocks)
+  auto own_norms = [&](int ti) {
+    const int t0 = c0 + ti * TT;
+    const char* k_t = ring + (size_t)(ti % NS) * (2 * TILEB);
+    float* nrm_t = nrm_all + (ti % NS) * TT;
 #pragma unroll
-    for (int i = 0; i < KLD; ++i) {
-      const int row = krow + i * KRP;
-      *(u32x4*)(k_t + row * KROW + kseg * 16) = kk[i];
-      float x[8];
-      Elem<uint16_t>::unpack(make_uint4(kk[i].x, kk[i].y, kk[i].z, kk[i].w), x);
-      float s = 0.f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) s = fmaf(x[e], x[e], s);
-      s = row_lanes_sum<SEGS>(s);        // over the SEGS lanes that share the row
-      if (kseg == 0) nrm_t[row] = (full || t0 + row < c1) ? c2 * s : INFINITY;
-    }
-    if (v_active) {
-      uint32_t w[4][4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const bool ok = full || t0 + tq * 4 + i < c1;
-        w[i][0] = ok ? vv[i].x : 0u; w[i][1] = ok ? vv[i].y : 0u;
-        w[i][2] = ok ? vv[i].z : 0u; w[i][3] = ok ? vv[i].w : 0u;
-      }
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {      // dword q of a token holds channels 2q (low half) and 2q+1 (high half)
-        const u32x2 even = (u32x2){__builtin_amdgcn_perm(w[1][q], w[0][q], 0x05040100u), __builtin_amdgcn_perm(w[3][q], w[2][q], 0x05040100u)};
-        const u32x2 odd = (u32x2){__builtin_amdgcn_perm(w[1][q], w[0][q], 0x07060302u), __builtin_amdgcn_perm(w[3][q], w[2][q], 0x07060302u)};
-        *(u32x2*)(v_t + (sg * 8 + 2 * q) * TROW + tq * 8) = even;
-        *(u32x2*)(v_t + (sg * 8 + 2 * q + 1) * TROW + tq * 8) = odd;
-      }
+    for (int i = 0; i < NLD; ++i) {
+      const u32x4 w = *(const u32x4*)(k_t + (wv * NLD + i) * 1024 + lane * 16);
+      float sq = dot2_bf16(w.x, w.x, 0.f);
+      sq = dot2_bf16(w.y, w.y, sq);
+      sq = dot2_bf16(w.z, w.z, sq);
+      sq = dot2_bf16(w.w, w.w, sq);
+      sq = row_lanes_sum<GR>(sq);
+      if (lane % GR == 0) nrm_t[ld_row[i]] = t0 + ld_row[i] < c1 ? c2 * sq : INFINITY;
     }
   };
+  // reads: per-lane byte offsets inside a key tile (A operand of GEMM1, row r of a 16-token tile) and
+  // inside a value tile (8 bytes of row 4 kg + s / 4, channels 16 ct + 4 (s mod 4) .., s = lane mod 16)
+  uint32_t a_off[KS], v_off[CT];
+#pragma unroll
+  for (int j = 0; j < KS; ++j) a_off[j] = (uint32_t)(r * ROWB + (((j * 4 + kg) ^ f_key(r)) * 16));
+  {
+    const int vrow = 4 * kg + (r >> 2), b = r & 3, fv2 = f_val(vrow) >> 1;
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) v_off[ct] = (uint32_t)(vrow * ROWB + ((ct ^ fv2) << 5) + b * 8);
+  }
   float* cache_h = CACHE ? pr.phi_cache + (size_t)h * n * D : nullptr;   // [token of M][feature]
-  auto contract = [&](int t0, const char* k_t, const char* v_t, const float* nrm_t) {
-    // ---- GEMM1 + exponent: all 64 tokens x this wavefront's features --------------------------
-    u32x2 phi_hi[4][FT], phi_lo[4][FT];            // [16-token tile][feature tile]: tokens 4kg .. 4kg+3
-    float ut[FT];                                  // this tile's share of u, added to the running sum once
+
+  auto contract = [&](int ti) {
+    const int t0 = c0 + ti * TT;
+    const char* k_t = ring + (size_t)(ti % NS) * (2 * TILEB);
+    const char* v_t = k_t + TILEB;
+    const float* nrm_t = nrm_all + (ti % NS) * TT;
+    u32x2 phi_hi[2][FT], phi_lo[2][FT];
+    float ut[FT];
 #pragma unroll
     for (int ft = 0; ft < FT; ++ft) ut[ft] = 0.f;
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
+    for (int mt = 0; mt < 2; ++mt) {
       Frag a[KS];
 #pragma unroll
-      for (int j = 0; j < KS; ++j) a[j].u = *(const u32x4*)(k_t + (mt * 16 + r) * KROW + j * 64 + kg * 16);
+      for (int j = 0; j < KS; ++j) a[j].u = *(const u32x4*)(k_t + mt * 16 * ROWB + a_off[j]);
       const floatx4 cn = *(const floatx4*)(nrm_t + mt * 16 + 4 * kg);
 #pragma unroll
       for (int ft = 0; ft < FT; ++ft) {
@@ -220,52 +253,50 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D == 64
         }
       }
     }
-
 #pragma unroll
     for (int ft = 0; ft < FT; ++ft) uacc[ft] += ut[ft];
 
-    // ---- GEMM2: S[own features][all channels] += Phi^T V ------------------------------------------
-    // k-step ks contracts the 32 tokens of tiles 2ks and 2ks+1; lane (., kg) holds tokens
-    // 32ks + 4kg + {0..3} and 32ks + 16 + 4kg + {0..3} in both operands
+    // GEMM2, one k-step: lane (., kg) holds tokens 4 kg + {0..3} and 16 + 4 kg + {0..3} in both operands
+    Frag ahi[FT], alo[FT];
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      Frag ahi[FT], alo[FT];
+    for (int ft = 0; ft < FT; ++ft) {
+      ahi[ft].u = (u32x4){phi_hi[0][ft].x, phi_hi[0][ft].y, phi_hi[1][ft].x, phi_hi[1][ft].y};
+      alo[ft].u = (u32x4){phi_lo[0][ft].x, phi_lo[0][ft].y, phi_lo[1][ft].x, phi_lo[1][ft].y};
+    }
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+      typedef short4v __attribute__((address_space(3)))* lds_s4;
+      union { short4v s; u32x2 u; } b0, b1;
+      b0.s = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(v_t + v_off[ct]));
+      b1.s = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(v_t + 16 * ROWB + v_off[ct]));
+      Frag vb;
+      vb.u = (u32x4){b0.u.x, b0.u.y, b1.u.x, b1.u.y};
 #pragma unroll
       for (int ft = 0; ft < FT; ++ft) {
-        ahi[ft].u = (u32x4){phi_hi[2 * ks][ft].x, phi_hi[2 * ks][ft].y, phi_hi[2 * ks + 1][ft].x, phi_hi[2 * ks + 1][ft].y};
-        alo[ft].u = (u32x4){phi_lo[2 * ks][ft].x, phi_lo[2 * ks][ft].y, phi_lo[2 * ks + 1][ft].x, phi_lo[2 * ks + 1][ft].y};
-      }
-#pragma unroll
-      for (int ct = 0; ct < CT; ++ct) {
-        const char* vp = v_t + (ct * 16 + r) * TROW + (32 * ks + 4 * kg) * 2;
-        const u32x2 b0 = *(const u32x2*)vp, b1 = *(const u32x2*)(vp + 32);
-        Frag vb;
-        vb.u = (u32x4){b0.x, b0.y, b1.x, b1.y};
-#pragma unroll
-        for (int ft = 0; ft < FT; ++ft) {
-          sacc[ft][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(alo[ft].v, vb.v, sacc[ft][ct], 0, 0, 0);
-          sacc[ft][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ahi[ft].v, vb.v, sacc[ft][ct], 0, 0, 0);
-        }
+        sacc[ft][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(alo[ft].v, vb.v, sacc[ft][ct], 0, 0, 0);
+        sacc[ft][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ahi[ft].v, vb.v, sacc[ft][ct], 0, 0, 0);
       }
     }
   };
 
-  issue_loads(c0);
-  stage(c0, k_tb[0], v_tb[0], nrm_tb[0]);
-  if (c0 + 64 < c1) issue_loads(c0 + 64);
-  lds_barrier();                         // (LDS only: the loads of the next tile stay in flight)
-  int cur = 0;
-  for (int t0 = c0; t0 < c1; t0 += 64) {
-    if (t0 + 64 < c1) {                  // next tile: registers -> the other buffer, then refill the registers
-      stage(t0 + 64, k_tb[cur ^ 1], v_tb[cur ^ 1], nrm_tb[cur ^ 1]);
-      if (t0 + 128 < c1) issue_loads(t0 + 128);
-    }
-    contract(t0, k_tb[cur], v_tb[cur], nrm_tb[cur]);
-    lds_barrier();                       // the other buffer is complete, this one is free
-    cur ^= 1;
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < n_tiles) issue(s);
+  constexpr int PER = 2 * NLD;           // load instructions per wavefront and tile
+  for (int ti = 0; ti < n_tiles; ++ti) {
+    // this wavefront's share of tile ti has landed once at most min(NS - 2, tiles issued after ti) tiles are in flight
+    const int after = min(NS - 2, n_tiles - 1 - ti);
+    if (after >= NS - 2) wait_vm_loads<(NS - 2) * PER>();
+    else if (after == 3) wait_vm_loads<3 * PER>();
+    else if (after == 2) wait_vm_loads<2 * PER>();
+    else if (after == 1) wait_vm_loads<PER>();
+    else wait_vm_loads<0>();
+    own_norms(ti);
+    lds_barrier();                       // every share of tile ti is in LDS; stage (ti - 1) % NS is free
+    if (ti + NS - 1 < n_tiles) issue(ti + NS - 1);
+    contract(ti);
   }
 
-  // ---- write the chunk partial: S part [D][D] then u part [D] ----------------------------------
   float* bp = (float*)(ws + g.off_bpart) + ((size_t)(p * g.Hkv + h) * g.n_build_chunks + ch) * ((size_t)D * (D + 1));
 #pragma unroll
   for (int ft = 0; ft < FT; ++ft) {
@@ -429,16 +460,28 @@ __global__ __launch_bounds__(kThreads) void build_reduce_kernel(Geom g, const tk
   else *(float4*)(probs[p].u + (size_t)h * dphi + (e - (size_t)dphi * d)) = s;
 }
 
+template <int D, bool CACHE, int NS>
+static void launch_build_mfma_as(const Geom& g, const tkphi_problem* probs, char* ws, dim3 grid, hipStream_t s) {
+  const size_t lds = (size_t)NS * (2 * 32 * D * 2 + 32 * 4);
+  const hipError_t e = hipFuncSetAttribute((const void*)build_mfma_kernel<D, CACHE, NS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) { set_error("hipFuncSetAttribute(%zu bytes of LDS): %s", lds, hipGetErrorString(e)); return; }
+  TKPHI_LAUNCH(ST_UNTIMED, (build_mfma_kernel<D, CACHE, NS>), grid, dim3(256), lds, s, g, probs, ws);
+}
+static void launch_build_mfma(const Geom& g, const tkphi_problem* probs, char* ws, dim3 grid, hipStream_t s) {
+  constexpr int NS = 4;                  // ring stages: three tiles on their way while one is contracted
+  if (g.d == 128 && g.cache) launch_build_mfma_as<128, true, NS>(g, probs, ws, grid, s);
+  else if (g.d == 128) launch_build_mfma_as<128, false, NS>(g, probs, ws, grid, s);
+  else if (g.cache) launch_build_mfma_as<64, true, NS>(g, probs, ws, grid, s);
+  else launch_build_mfma_as<64, false, NS>(g, probs, ws, grid, s);
+}
+
 void launch_build(const Geom& g, const tkphi_problem* probs, char* ws, hipStream_t s) {
   if (g.max_mid > 0) {
     dim3 grid(g.n_build_chunks, g.Hkv, g.n_problems);
     if (g.phi_kind == TKPHI_PHI_MLP) {
       launch_mlp_build(g, probs, ws, s);            // phi_k of the mid-region, then S, u chunk partials from the features
     } else if (g.use_mfma) {
-      if (g.d == 128 && g.cache) TKPHI_LAUNCH(ST_UNTIMED, (build_mfma_kernel<128, true, 4>), grid, dim3(kThreads), 0, s, g, probs, ws);
-      else if (g.d == 128) TKPHI_LAUNCH(ST_UNTIMED, (build_mfma_kernel<128, false, 4>), grid, dim3(kThreads), 0, s, g, probs, ws);
-      else if (g.cache) TKPHI_LAUNCH(ST_UNTIMED, (build_mfma_kernel<64, true, 4>), grid, dim3(kThreads), 0, s, g, probs, ws);
-      else TKPHI_LAUNCH(ST_UNTIMED, (build_mfma_kernel<64, false, 4>), grid, dim3(kThreads), 0, s, g, probs, ws);
+      launch_build_mfma(g, probs, ws, grid, s);
     } else if (g.dtype == TKPHI_BF16) {
       TKPHI_LAUNCH(ST_UNTIMED, build_kernel<uint16_t>, grid, dim3(kThreads), 0, s, g, probs, ws);
     } else {
