@@ -70,21 +70,6 @@ __device__ __forceinline__ float row_lanes_sum(float s) {
 // ------------------------------------------------------------------------------------
 typedef short short4v __attribute__((ext_vector_type(4)));
 
-// 64 lanes x 16 bytes from global memory into LDS at lds_addr (uniform) + 16 * lane; counted by vmcnt.
-// (M0 is not on the clobber list - the compiler reserves it; nothing else in these kernels uses it)
-__device__ __forceinline__ void load_to_lds16(const void* gsrc, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt" : : "v"(gsrc), "s"(lds_addr) : "memory");
-}
-// the same with the address as a uniform base plus a 32-bit offset per lane
-__device__ __forceinline__ void load_to_lds16(const void* base, uint32_t off, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt" : : "v"(off), "s"(base), "s"(lds_addr) : "memory");
-}
-template <int N>
-__device__ __forceinline__ void wait_vm_loads() {   // at most N vector memory operations still in flight
-  static_assert(N >= 0 && N < 64, "vmcnt has 6 bits");
-  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
-  asm volatile("" ::: "memory");                    // no LDS read moves above the wait
-}
 __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {   // a.lo b.lo + a.hi b.hi + c
   typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
   union { uint32_t u; bf16x2 v; } x, y;
@@ -174,15 +159,15 @@ void build_mfma_kernel(Geom g, const tkphi_problem* __restrict__ probs, char* __
       const char* vb = Vt + (size_t)t0 * row_bytes;
 #pragma unroll
       for (int i = 0; i < NLD; ++i) {
-        load_to_lds16(kb, ld_ko[i], st + i * 1024);
-        load_to_lds16(vb, ld_vo[i], st + TILEB + i * 1024);
+        load_to_lds16_stream(kb, ld_ko[i], st + i * 1024);
+        load_to_lds16_stream(vb, ld_vo[i], st + TILEB + i * 1024);
       }
     } else {                             // rows past the end re-read the last row
 #pragma unroll
       for (int i = 0; i < NLD; ++i) {
         const size_t ro = (size_t)min(t0 + ld_row[i], c1 - 1) * row_bytes;
-        load_to_lds16(Kt + ro + ld_kg[i], st + i * 1024);
-        load_to_lds16(Vt + ro + ld_vg[i], st + TILEB + i * 1024);
+        load_to_lds16_stream(Kt + ro + ld_kg[i], st + i * 1024);
+        load_to_lds16_stream(Vt + ro + ld_vg[i], st + TILEB + i * 1024);
       }
     }
   };

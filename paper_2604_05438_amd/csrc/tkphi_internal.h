@@ -385,6 +385,33 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// Loads that write LDS directly.  The compiler cannot tell which LDS bytes a pending one will touch and would
+// wait for all of them before every LDS read, so they are issued from inline assembly and counted by hand:
+// wait_vm_loads<N>() returns when at most N vector memory operations of the wavefront are still in flight
+// (they complete in order), and a barrier after it makes every wavefront's share visible to the workgroup.
+// 64 lanes x 16 bytes from global memory into LDS at lds_addr (uniform) + 16 * lane; counted by vmcnt.
+// (M0 is not on the clobber list - the compiler reserves it; nothing else in these kernels uses it)
+// _stream: data read once (non-temporal); the plain form for data other workgroups read again from L2.
+__device__ __forceinline__ void load_to_lds16(const void* gsrc, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gsrc), "s"(lds_addr) : "memory");
+}
+__device__ __forceinline__ void load_to_lds16_stream(const void* gsrc, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt" : : "v"(gsrc), "s"(lds_addr) : "memory");
+}
+// the same with the address as a uniform base plus a 32-bit offset per lane
+__device__ __forceinline__ void load_to_lds16(const void* base, uint32_t off, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(off), "s"(base), "s"(lds_addr) : "memory");
+}
+__device__ __forceinline__ void load_to_lds16_stream(const void* base, uint32_t off, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt" : : "v"(off), "s"(base), "s"(lds_addr) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm_loads() {   // at most N vector memory operations still in flight
+  static_assert(N >= 0 && N < 64, "vmcnt has 6 bits");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+  asm volatile("" ::: "memory");                    // no LDS read moves above the wait
+}
+
 // Stores and loads that are coherent across the whole GPU (the 8 XCDs have separate L2 caches; ordinary accesses may
 // stay in, or be served from, the L2 of the XCD they were issued on until a kernel boundary).  For the few words
 // one workgroup hands to another inside a launch: much cheaper than a device-wide fence, which writes back a
