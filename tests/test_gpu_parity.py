@@ -53,6 +53,34 @@ def test_l3b_shape_small(L, k):
     print("l3b", L, k, rep)
 
 
+@pytest.mark.parametrize("shape,L,k,d_emb", [("l3b_128k", 9000, 90, 0), ("l3b_128k", 5000, 600, 0), ("l1b_32k", 5000, 49, 0),
+                                             ("f32_gqa", 2000, 20, 0), ("l1b_32k", 3000, 29, 128)])
+def test_token_major_cache_layout(shape, L, k, d_emb):
+    """K and V stored token-major ([token][KV head][channel], the layout of a cache that appends one row of all
+    heads per step): the library sees it through stride_head = d and stride_tok = Hkv d.  Every kernel that walks
+    key or value rows (build tiles, score scan, sample, gather, anchors, the MLP stem) takes the strides from the
+    problem record; results must equal the head-major run of the same data, which the oracle checks."""
+    import torch
+    import parity_utils as PU
+    from paper_2604_05438_amd import harness as H
+    if shape == "f32_gqa":                                       # generic kernels: fp32 storage, GQA 2:1, d_phi != d_head
+        w = dataclasses.replace(I.WORKLOADS["tiny_f32"], n_q_heads=4, n_kv_heads=2, d_head=128, d_phi=48, name="f32_gqa", seed=79)
+    else:
+        w = I.WORKLOADS[shape]
+    P = I.make_layer(w, L=L)
+    if d_emb:
+        P["mlp"] = I.make_mlp_phi(w, layer=0, d_emb=d_emb)
+    dev = dict(P)
+    for name in ("K", "V"):
+        hm = H.to_device(P[name])                               # [Hkv][L][d]
+        dev[name] = hm.permute(1, 0, 2).contiguous().permute(1, 0, 2)
+        assert dev[name].stride() == (w.d_head, w.n_kv_heads * w.d_head, 1) and torch.equal(dev[name], hm)
+    b = H.Batch(H.config_of(w, d_emb=d_emb), [dev], [k], debug=True)
+    b.build(); b.decode()
+    assert b.status() == 0
+    print("token-major", shape, L, k, PU.check_layer(w, P, k, b, 0), flush=True)
+
+
 @pytest.mark.parametrize("shape,L,k,chunk", [("l3b_128k", 20011, 200, 1024), ("l1b_32k", 9000, 90, 2048),
                                              ("l3b_128k", 5000, 600, 512)])
 def test_interleaved_chunks(shape, L, k, chunk):
