@@ -20,7 +20,7 @@
 //     which makes every mid token a candidate
 // Then workgroup `part` takes the lists [part, part + 1) n_lists / split: their winners (composite >=
 // thr), in list order, are written to the head's retrieved list at the offset given by the winners in
-// earlier lists, and gathered 256 at a time (16 tokens per wavefront):
+// earlier lists, and gathered 256 or 512 at a time (16-token tiles, one or two per wavefront):
 //     m_loc = max s_i,  Z_loc = sum exp(s_i - m_loc),  nu_loc = sum exp(s_i - m_loc) v_i     (eq. (exact_terms))
 //     zsum = sum z_i,  zv = sum z_i v_i,  z_i = phi_q . phi_k(k_i) recomputed                (eq. (subtraction))
 // into one partial per workgroup, [m, Z, zsum, count, nu[d], zv[d]], which the merge kernel combines in
@@ -36,7 +36,10 @@ namespace tkphi {
 constexpr int kBCap = 1024;            // boundary-bin candidates ranked in LDS
 constexpr int kSweepEntries = 12;      // entries per thread and sweep (Geom::cand_T is a multiple)
 constexpr int kSweepLoads = kSweepEntries / 2;
-constexpr int kBatch = 256;            // winners gathered per round: 16 per wavefront
+// winners gathered per round: 16-token tile t of a round goes to wavefront t mod 16.  Two tiles per wavefront at
+// d = 64 (one round for most heads of a batch of short sequences); at d = 128 the second tile's rows do not fit
+// the registers
+template <int D> constexpr int kBatchOf = D == 64 ? 512 : 256;
 constexpr int kDense = 8192;           // candidates of a head that the select phase packs into LDS
 constexpr int kWinLds = 512;           // winners of a workgroup kept in LDS (the rest are re-read from the retrieved list)
 
@@ -64,6 +67,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
   __shared__ uint2 dense[kDense];                   // the candidates of the head, packed (select phase)
   __shared__ int w_tok[kWinLds];
   __shared__ float w_s[kWinLds];
+  constexpr int kBatch = kBatchOf<D>;
   __shared__ float b_w[kBatch], b_z[kBatch];
   __shared__ float sh_bk[D], sh_pq[D];              // bk[h] and phi_q of the head, staged with Wk
   __shared__ int sh_scan[kSelWaves];
@@ -487,12 +491,13 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
   }
   TKPHI_PHASE(ws, 15);
 
-  // ---- gather: 256 winners per round, 16 per wavefront ---------------------------------------------------------
+  // ---- gather: kBatch winners per round, one or two 16-token tiles per wavefront -----------------------------
   const int r = lane & 15, kg = lane >> 4;
   const int64_t head_off = (int64_t)h * pr.stride_head;
   constexpr int LPR = D / 8;                        // lanes per value row (16 bytes each)
   constexpr int RPP = kSelThreads / LPR;            // rows per pass (64 or 128)
-  constexpr int NPASS = kBatch / RPP;               // 4 or 2
+  constexpr int NPASS = kBatch / RPP;               // value rows per thread and round (4)
+  constexpr int NTW = kBatch / (16 * kSelWaves);    // 16-token tiles per wavefront and round
   const int seg = tid % LPR, rsub = tid / LPR;
   float run_m = -INFINITY, run_Z = 0.f, run_zs = 0.f, run_nu = 0.f, run_zv = 0.f;   // (nu, zv: channel tid < D)
   wkp.commit(wk_lds);                               // (requested before the histogram pass: long since arrived)
@@ -501,7 +506,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
   // (inside the loop the wavefronts exchange data through LDS only: its barriers leave the key and value loads in flight)
   for (int b0 = 0; b0 < my_count; b0 += kBatch) {
     const int cnt = min(kBatch, my_count - b0);
-    // this thread's token of the batch (thread t < 256 <-> winner b0 + t)
+    // this thread's token of the batch (thread t < kBatch <-> winner b0 + t)
     auto winner = [&](int j, int* tok, float* s) {
       const int i = b0 + min(j, cnt - 1);
       if (i < kWinLds) { *tok = w_tok[i]; *s = w_s[i]; }
@@ -510,13 +515,17 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
     };
     // key rows of this wavefront's 16 tokens and the value rows of all passes: every load in flight together (they
     // only need the token indices)
-    GatherFrag a[KS];
-    if (wv * 16 < cnt) {
-      int tk; float s;
-      winner(wv * 16 + r, &tk, &s);
-      const char* rp = (const char*)pr.K + (head_off + (int64_t)tk * pr.stride_tok) * 2 + kg * 16;
+    GatherFrag a[NTW][KS];
 #pragma unroll
-      for (int j = 0; j < KS; ++j) a[j].u = gload128(rp + j * 64);
+    for (int u = 0; u < NTW; ++u) {
+      const int t16 = (wv + u * kSelWaves) * 16;      // first token of this wavefront's u-th tile
+      if (t16 < cnt) {
+        int tk; float s;
+        winner(t16 + r, &tk, &s);
+        const char* rp = (const char*)pr.K + (head_off + (int64_t)tk * pr.stride_tok) * 2 + kg * 16;
+#pragma unroll
+        for (int j = 0; j < KS; ++j) a[u][j].u = gload128(rp + j * 64);
+      }
     }
     u32x4 vrow[NPASS];
     int vtok;
@@ -536,21 +545,27 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
     }
     lds_barrier();
     if (wv == 0) {
-      float mloc = fmaxf(fmaxf(b_w[lane], b_w[lane + 64]), fmaxf(b_w[lane + 128], b_w[lane + 192]));
+      float mloc = -INFINITY;
+#pragma unroll
+      for (int k = 0; k < kBatch / 64; ++k) mloc = fmaxf(mloc, b_w[lane + 64 * k]);
 #pragma unroll
       for (int o = 32; o >= 1; o >>= 1) mloc = fmaxf(mloc, __shfl_xor(mloc, o));
       if (lane == 0) sh_m = mloc;
     }
-    // z_i of this wavefront's 16 tokens
-    if (wv * 16 < cnt) {
-      float z[4];
-      wave_feature_dots<D>(a, wk_lds, sh_bk, sh_pq, g.a, g.c, z);
-      if (r == 0) {
+    // z_i of this wavefront's tokens
 #pragma unroll
-        for (int i = 0; i < 4; ++i) b_z[wv * 16 + 4 * kg + i] = (wv * 16 + 4 * kg + i < cnt) ? z[i] : 0.f;
+    for (int u = 0; u < NTW; ++u) {
+      const int t16 = (wv + u * kSelWaves) * 16;
+      if (t16 < cnt) {
+        float z[4];
+        wave_feature_dots<D>(a[u], wk_lds, sh_bk, sh_pq, g.a, g.c, z);
+        if (r == 0) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) b_z[t16 + 4 * kg + i] = (t16 + 4 * kg + i < cnt) ? z[i] : 0.f;
+        }
+      } else if (lane < 16) {
+        b_z[t16 + lane] = 0.f;
       }
-    } else if (lane < 16) {
-      b_z[wv * 16 + lane] = 0.f;
     }
     lds_barrier();
     const float mloc = sh_m;
@@ -582,6 +597,11 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
     if (wv == 1) {                                  // Z_loc and zsum of the batch, in a fixed order
       float Zb = (b_w[lane] + b_w[lane + 64]) + (b_w[lane + 128] + b_w[lane + 192]);
       float zb = (b_z[lane] + b_z[lane + 64]) + (b_z[lane + 128] + b_z[lane + 192]);
+#pragma unroll
+      for (int k = 4; k < kBatch / 64; k += 4) {    // (all zero in a round of at most 256 winners)
+        Zb += (b_w[lane + 64 * k] + b_w[lane + 64 * (k + 1)]) + (b_w[lane + 64 * (k + 2)] + b_w[lane + 64 * (k + 3)]);
+        zb += (b_z[lane + 64 * k] + b_z[lane + 64 * (k + 1)]) + (b_z[lane + 64 * (k + 2)] + b_z[lane + 64 * (k + 3)]);
+      }
 #pragma unroll
       for (int o = 32; o >= 1; o >>= 1) { Zb += __shfl_xor(Zb, o); zb += __shfl_xor(zb, o); }
       if (lane == 0) { sh_Z = Zb; sh_zs = zb; }
