@@ -381,7 +381,7 @@ __global__ __launch_bounds__(kPrepThreads) void decode_prep_kernel(Geom g, const
 }
 
 // grid (n_scan_chunks, Hkv, n_problems), 256 threads: wavefront w is slot w of the workgroup's chunk.
-template <int D, int TPI>
+template <int D, int TPI, bool STREAM>
 __global__ __launch_bounds__(kThreads) void score_filtered_kernel(Geom g, const tkphi_problem* __restrict__ probs,
                                                                   char* __restrict__ ws) {
   const int p = blockIdx.z, h = blockIdx.y;
@@ -400,7 +400,7 @@ __global__ __launch_bounds__(kThreads) void score_filtered_kernel(Geom g, const 
   const uint32_t edge_r = r < g.G ? ((const uint32_t*)(blk + g.off_thr))[h * g.G + r] : 0xffffffffu;
   extern __shared__ __attribute__((aligned(16))) uint2 sh_heads[];      // [4 wavefronts][G][cand_T]
   const int wv = (int)(threadIdx.x >> 6);
-  scan_wave_slot<D, TPI>(g, pr, blk, h, n, n_chunks, chunk, wv, bq, edge_r, -1, false,
+  scan_wave_slot<D, TPI, TPI, STREAM>(g, pr, blk, h, n, n_chunks, chunk, wv, bq, edge_r, -1, false,
                          g.head_strip ? sh_heads + (size_t)wv * g.G * g.cand_T : nullptr);
 }
 
@@ -444,8 +444,9 @@ void launch_score_filtered(const Geom& g, const tkphi_problem* probs, char* ws, 
   if (g.max_mid == 0) return;
   dim3 grid(g.n_scan_chunks, g.Hkv, g.n_problems);
   const size_t lds = g.head_strip ? (size_t)4 * g.G * g.cand_T * sizeof(uint2) : 0;   // the wavefronts' strips of list heads
-  if (g.d == 128) TKPHI_LAUNCH(ST_SCORE, (score_filtered_kernel<128, 4>), grid, dim3(kThreads), lds, s, g, probs, ws);
-  else TKPHI_LAUNCH(ST_SCORE, (score_filtered_kernel<64, 8>), grid, dim3(kThreads), lds, s, g, probs, ws);
+  if (g.d == 128 && g.stream_keys) TKPHI_LAUNCH(ST_SCORE, (score_filtered_kernel<128, 4, true>), grid, dim3(kThreads), lds, s, g, probs, ws);
+  else if (g.d == 128) TKPHI_LAUNCH(ST_SCORE, (score_filtered_kernel<128, 4, false>), grid, dim3(kThreads), lds, s, g, probs, ws);
+  else TKPHI_LAUNCH(ST_SCORE, (score_filtered_kernel<64, 8, false>), grid, dim3(kThreads), lds, s, g, probs, ws);
 }
 
 }  // namespace tkphi

@@ -47,7 +47,8 @@ __device__ __forceinline__ size_t cand_region(const Geom& g, int gq, int chunk, 
 //            only that set, so what a first attempt reads is never overwritten while another workgroup reads it)
 // Lane (r, kg) ends up with the scores of head r for tokens base + t 16 + 4 kg + i, so each list is
 // written by the four lanes of its column, in the order (unit, t, i, kg).
-template <int D, int TPI, int SUB = TPI>   // SUB: 16-token tiles whose loads are in flight together (the rescan keeps registers low)
+// SUB: 16-token tiles whose loads are in flight together (the rescan keeps registers low); STREAM: non-temporal key loads
+template <int D, int TPI, int SUB = TPI, bool STREAM = false>
 __device__ __forceinline__ void scan_wave_slot(const Geom& g, const tkphi_problem& pr, char* blk, int h, int n, int n_chunks,
                                                int chunk, int wslot, const ScoreFrag (&bq)[D / 32], uint32_t edge_r,
                                                int only_gl, bool rescan = false, uint2* strip = nullptr) {
@@ -80,7 +81,7 @@ __device__ __forceinline__ void scan_wave_slot(const Geom& g, const tkphi_proble
         const int row = min(base + (t0 + t) * 16 + r, n - 1);
         const char* rp = Kb + (size_t)row * row_bytes;
 #pragma unroll
-        for (int j = 0; j < KS; ++j) a[t][j].u = gload128(rp + j * 64);
+        for (int j = 0; j < KS; ++j) a[t][j].u = STREAM ? gload128_stream(rp + j * 64) : gload128(rp + j * 64);
       }
       __builtin_amdgcn_sched_barrier(0);   // all loads of the group are in flight before the first MFMA
       st_floatx4 acc[SUB];

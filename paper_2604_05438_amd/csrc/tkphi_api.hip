@@ -158,6 +158,11 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   // fused select + gather kernel
   g->cand_T = (int)align_up((size_t)std::max(24, g->scan_chunk / 4 * 3 / 32), 12);
   g->head_strip = (size_t)4 * g->G * g->cand_T * sizeof(uint2) <= 32768 ? 1 : 0;
+  // Non-temporal key loads leave the candidate lists, phi_q and the problem record in the caches for the select kernel
+  // (l3b_128k: score pass unchanged, select 25.5 -> 24.9 us, step -1.4 us).  Only for one problem of 256-byte rows:
+  // with 128-byte rows the two loads that share a cache line fetch it twice (ragged batch: score pass +20 %), and
+  // the 28-layer call measured 2 % slower
+  g->stream_keys = (n_problems == 1 && g->d == 128) ? 1 : 0;
   g->off_candc = p;   p = align_up(p + (g->filtered ? (size_t)g->Hq * g->n_scan_chunks * 4 * g->cand_T * sizeof(uint2) : (size_t)0), 256);
   g->off_ccount = p;  p = align_up(p + (g->filtered ? (size_t)g->Hq * g->n_scan_chunks * 4 * sizeof(uint32_t) : (size_t)0), 256);
   g->off_resf = p;    p = align_up(p + (g->filtered ? (size_t)g->Hq * g->n_scan_chunks * g->scan_chunk * sizeof(uint2) : (size_t)0), 256);

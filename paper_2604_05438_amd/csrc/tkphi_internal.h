@@ -48,6 +48,7 @@ struct Geom {
                          // bf16 matrix-core shapes, exp-affine maps, budgets well below the mid-region size
   int cand_T;            // filtered pipeline: entries of a candidate list kept in the compact array (multiple of 12)
   int head_strip;        // 1: the score pass collects the compact list heads in LDS (4 G cand_T entries fit 32 KB)
+  int stream_keys;       // 1: the filtered score pass reads the keys with non-temporal loads
   int sel_test;          // tkphi_tuning::select_test (0 unless a test forces the rescan or the no-pruning path)
   int n_tiles;           // gather: ceil(max_K / kPairsPerWG) retrieved-token tiles per query head; one partial each
   int sg_split;          // filtered pipeline: workgroups per query head of the fused select + gather kernel (0 if it cannot run);
