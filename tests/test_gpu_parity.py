@@ -53,6 +53,32 @@ def test_l3b_shape_small(L, k):
     print("l3b", L, k, rep)
 
 
+@pytest.mark.parametrize("shape", ["l3b_128k", "l1b_32k"])
+@pytest.mark.parametrize("chunk", [64, 128, 2048])
+def test_build_tile_and_chunk_boundaries(shape, chunk):
+    """Summary build alone (eq. (natural_cache)) at mid-region sizes around the boundaries of its tiling: one token,
+    one short of / exactly / one past a 32-token tile, the same around the chunk size (a workgroup then sees 1 to 5
+    tiles: fewer than, as many as and more than the stages of its LDS ring) and several chunks with a ragged last
+    one; chunk = 64 and 128 force those small chunks, 2048 is the size long sequences use.  A batch of all lengths
+    in one call; S and u of every KV head against the oracle under the bf16-feature bound."""
+    import parity_utils as PU
+    from oracle import tkphi_oracle as orc
+    from paper_2604_05438_amd import harness as H
+    w = I.WORKLOADS[shape]
+    edge = w.n_sink + w.n_tail
+    mids = sorted({1, 31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128, 129, 160, 161, 4 * chunk - 1, 4 * chunk, 4 * chunk + 33})
+    mids = [m for m in mids if m <= 8300]
+    layers = [I.make_layer(w, L=edge + m, seq=i) for i, m in enumerate(mids)]
+    b = H.Batch(H.config_of(w, tuning={"build_chunk": chunk}), layers, [1] * len(layers), debug=True)
+    b.build()
+    assert b.status() == 0
+    for i, (P, m) in enumerate(zip(layers, mids)):
+        O = PU.oracle_inputs(P)
+        S_or, u_or = orc.build_summaries(O["K"], O["V"], O["Wk"], O["bk"], w.phi_in_scale, w.phi_norm_coef, w.n_sink, w.n_tail)
+        PU.check_summaries(b.result(i, "S"), b.result(i, "u"), S_or, u_or, 2e-3, w=w, O=O)
+    print("build boundaries", shape, chunk, mids, flush=True)
+
+
 @pytest.mark.parametrize("shape,L,k,d_emb", [("l3b_128k", 9000, 90, 0), ("l3b_128k", 5000, 600, 0), ("l1b_32k", 5000, 49, 0),
                                              ("f32_gqa", 2000, 20, 0), ("l1b_32k", 3000, 29, 128)])
 def test_token_major_cache_layout(shape, L, k, d_emb):
