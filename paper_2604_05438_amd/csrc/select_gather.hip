@@ -504,43 +504,51 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
   if (tid < D) { sh_bk[tid] = bk_t; sh_pq[tid] = pq_t; }
   __syncthreads();                                  // lds_a changes hands; the staged Wk is complete
   // (inside the loop the wavefronts exchange data through LDS only: its barriers leave the key and value loads in flight)
-  for (int b0 = 0; b0 < my_count; b0 += kBatch) {
+  // winner j of the round that starts at b0 (thread t < kBatch <-> winner b0 + t)
+  auto winner = [&](int b0, int j, int* tok, float* s) {
+    const int i = b0 + min(j, min(kBatch, my_count - b0) - 1);
+    if (i < kWinLds) { *tok = w_tok[i]; *s = w_s[i]; }
+    else { *tok = sel_idx[min(my_base + i, g.max_K - 1)]; *s = sel_score[min(my_base + i, g.max_K - 1)]; }
+    *tok = g.n_sink + min(max(*tok, 0), n - 1);
+  };
+  // The key rows of this wavefront's tiles and the value rows of all passes only need the token indices.  The rows
+  // of round b + 1 are requested inside round b, each set into the registers round b has just finished with (keys
+  // after the feature dots, values after the weighted sums): a round trip to memory per workgroup, not per round.
+  GatherFrag a[NTW][KS];
+  u32x4 vrow[NPASS];
+  auto load_keys = [&](int b0) {
     const int cnt = min(kBatch, my_count - b0);
-    // this thread's token of the batch (thread t < kBatch <-> winner b0 + t)
-    auto winner = [&](int j, int* tok, float* s) {
-      const int i = b0 + min(j, cnt - 1);
-      if (i < kWinLds) { *tok = w_tok[i]; *s = w_s[i]; }
-      else { *tok = sel_idx[min(my_base + i, g.max_K - 1)]; *s = sel_score[min(my_base + i, g.max_K - 1)]; }
-      *tok = g.n_sink + min(max(*tok, 0), n - 1);
-    };
-    // key rows of this wavefront's 16 tokens and the value rows of all passes: every load in flight together (they
-    // only need the token indices)
-    GatherFrag a[NTW][KS];
 #pragma unroll
     for (int u = 0; u < NTW; ++u) {
       const int t16 = (wv + u * kSelWaves) * 16;      // first token of this wavefront's u-th tile
       if (t16 < cnt) {
         int tk; float s;
-        winner(t16 + r, &tk, &s);
+        winner(b0, t16 + r, &tk, &s);
         const char* rp = (const char*)pr.K + (head_off + (int64_t)tk * pr.stride_tok) * 2 + kg * 16;
 #pragma unroll
         for (int j = 0; j < KS; ++j) a[u][j].u = gload128(rp + j * 64);
       }
     }
-    u32x4 vrow[NPASS];
-    int vtok;
-    float vs;
+  };
+  auto load_values = [&](int b0) {
+    const int cnt = min(kBatch, my_count - b0);
 #pragma unroll
     for (int ps = 0; ps < NPASS; ++ps) {
       if (ps * RPP < cnt) {
-        winner(ps * RPP + rsub, &vtok, &vs);
+        int vtok; float vs;
+        winner(b0, ps * RPP + rsub, &vtok, &vs);
         vrow[ps] = gload128((const char*)pr.V + (head_off + (int64_t)vtok * pr.stride_tok + seg * 8) * 2);
       }
     }
+  };
+  if (my_count > 0) { load_keys(0); load_values(0); }
+  for (int b0 = 0; b0 < my_count; b0 += kBatch) {
+    const int cnt = min(kBatch, my_count - b0);
+    const bool more = b0 + kBatch < my_count;
     // batch maximum of the scores
     if (tid < kBatch) {
       int tk; float s;
-      winner(tid, &tk, &s);
+      winner(b0, tid, &tk, &s);
       b_w[tid] = tid < cnt ? s : -INFINITY;         // (scores for now)
     }
     lds_barrier();
@@ -567,6 +575,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
         b_z[t16 + lane] = 0.f;
       }
     }
+    if (more) load_keys(b0 + kBatch);
     lds_barrier();
     const float mloc = sh_m;
     if (tid < kBatch) b_w[tid] = tid < cnt ? __expf(b_w[tid] - mloc) : 0.f;
@@ -586,6 +595,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
         for (int e = 0; e < 8; ++e) { an[e] = fmaf(wi, x[e], an[e]); az[e] = fmaf(zi, x[e], az[e]); }
       }
     }
+    if (more) load_values(b0 + kBatch);
     for (int o = LPR; o < 64; o <<= 1) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) { an[e] += __shfl_xor(an[e], o); az[e] += __shfl_xor(az[e], o); }
