@@ -124,7 +124,7 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   // than the spill pipeline: a budget of at most 1/64 of the mid-region (128K layer: 86 / 89 against 95 / 100 us
   // per step at 0.5 / 1 %; 32K layer 42.5 against 44.5 us; 28 layers per call 1.62 against 1.87 ms; the ragged
   // 256-problem batch 3.36 against 3.65 ms).  At 2 % and 4 % candidate lists overflow their compact heads and the
-  // fused select falls back to its general path: 112 / 128 against 108 / 122 us
+  // fused select falls back to its general path: 110 / 124 against 108 / 123 us
   g->filtered = (g->use_mfma && cfg->phi_kind == TKPHI_PHI_EXP_AFFINE && !g->cache && tn.select_mode != 1 &&
                  (tn.select_mode == 2 || (int64_t)max_K * 64 <= g->max_mid)) ? 1 : 0;
   g->sel_test = tn.select_test;
