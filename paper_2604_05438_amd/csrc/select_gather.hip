@@ -41,7 +41,7 @@ constexpr int kSweepLoads = kSweepEntries / 2;
 // the registers
 template <int D> constexpr int kBatchOf = D == 64 ? 512 : 256;
 constexpr int kDense = 8192;           // candidates of a head that the select phase packs into LDS
-constexpr int kWinLds = 512;           // winners of a workgroup kept in LDS (the rest are re-read from the retrieved list)
+constexpr int kWinLds = 1536;          // winners of a workgroup kept in LDS (the rest are re-read from the retrieved list)
 
 // every mid token of query head gq becomes a candidate: the head's lists are written again with no bound, into
 // the rescan set (what the score pass wrote stays as it is: other workgroups of the head may still be reading it)
