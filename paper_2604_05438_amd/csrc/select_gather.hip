@@ -1,6 +1,6 @@
 // Fused Top-K select + gather of the filtered pipeline (bf16 caches on the matrix cores):
 // topk_select, exact_branch and residual_correct for the retrieved tokens in one launch.
-// grid (split, Hq, n_problems), 1024 threads: `split` workgroups share a query head.
+// grid (split, Hq, n_problems), NTHR = 1024 or 512 threads: `split` workgroups share a query head.
 //
 // The score pass left, per query head, every token whose score key reaches the head's lower bound, in
 // per-wavefront lists (score_tile.h): the first cand_T entries of a list in a compact array, the rest in
@@ -39,24 +39,26 @@ constexpr int kSweepLoads = kSweepEntries / 2;
 // winners gathered per round: 16-token tile t of a round goes to wavefront t mod 16.  Two tiles per wavefront at
 // d = 64 (one round for most heads of a batch of short sequences); at d = 128 the second tile's rows do not fit
 // the registers
-template <int D> constexpr int kBatchOf = D == 64 ? 512 : 256;
-constexpr int kDense = 8192;           // candidates of a head that the select phase packs into LDS
-constexpr int kWinLds = 1536;          // winners of a workgroup kept in LDS (the rest are re-read from the retrieved list)
+template <int D, int NTHR> constexpr int kBatchOf = (D == 64 && NTHR == 1024) ? 512 : 256;
+// candidates of a head that the select phase packs into LDS
+template <int NTHR> constexpr int kDenseOf = NTHR == 1024 ? 8192 : 4096;
+// winners of a workgroup kept in LDS (the rest are re-read from the retrieved list)
+template <int NTHR> constexpr int kWinLdsOf = NTHR == 1024 ? 1536 : 1024;
 
 // every mid token of query head gq becomes a candidate: the head's lists are written again with no bound, into
 // the rescan set (what the score pass wrote stays as it is: other workgroups of the head may still be reading it)
 // (one 16-token tile in flight per wavefront: the rare path must not cost the common one registers)
-template <int D, int TPI>
+template <int D, int TPI, int NTHR>
 __device__ __forceinline__ void rescan_head(const Geom& g, const tkphi_problem& pr, char* blk, int gq, int n, int n_chunks) {
   const int h = gq / g.G, wv = threadIdx.x >> 6;
   ScoreFrag bq[D / 32];
   load_query_frags<D>(g, pr, h, bq);
-  for (int reg = wv; reg < n_chunks * 4; reg += kSelWaves)
+  for (int reg = wv; reg < n_chunks * 4; reg += NTHR / 64)
     scan_wave_slot<D, TPI, 1>(g, pr, blk, h, n, n_chunks, reg >> 2, reg & 3, bq, 0u, gq % g.G, true);
 }
 
 // The selecting and gathering work of workgroup (part, gq, p); returns early where there is nothing to retrieve
-template <int D, int TPI>
+template <int D, int TPI, int NTHR>
 __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_problem* __restrict__ probs, char* __restrict__ ws,
                                                    int part, int gq, int p) {
   constexpr int KS = D / 32;
@@ -64,13 +66,14 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
   // select phase: histogram (8 KB) + boundary candidates (8 KB); gather phase: reduction scratch of the value sums
   __shared__ __attribute__((aligned(16))) char lds_a[16384];
   __shared__ __attribute__((aligned(16))) char wk_lds[D * WROW];
+  constexpr int kDense = kDenseOf<NTHR>, kWinLds = kWinLdsOf<NTHR>, NWV = NTHR / 64;
   __shared__ uint2 dense[kDense];                   // the candidates of the head, packed (select phase)
   __shared__ int w_tok[kWinLds];
   __shared__ float w_s[kWinLds];
-  constexpr int kBatch = kBatchOf<D>;
+  constexpr int kBatch = kBatchOf<D, NTHR>;
   __shared__ float b_w[kBatch], b_z[kBatch];
   __shared__ float sh_bk[D], sh_pq[D];              // bk[h] and phi_q of the head, staged with Wk
-  __shared__ int sh_scan[kSelWaves];
+  __shared__ int sh_scan[NWV];
   __shared__ uint64_t sh_prefix, sh_thr;
   __shared__ int sh_want, sh_tot, sh_r0, sh_r1;
   __shared__ int sh_bstar, sh_krem, sh_chi, sh_nb, sh_nbc;
@@ -116,7 +119,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
   const int h = gq / g.G;
   const int n_chunks = (n + g.scan_chunk - 1) / g.scan_chunk;
   const int n_reg = n_chunks * 4;
-  const int rounds = (n_reg * T + kSelThreads * kSweepEntries - 1) / (kSelThreads * kSweepEntries);
+  const int rounds = (n_reg * T + NTHR * kSweepEntries - 1) / (NTHR * kSweepEntries);
   int32_t* sel_idx = (int32_t*)(blk + g.off_selidx) + (size_t)gq * g.max_K;
   float* sel_score = (float*)(blk + g.off_selscore) + (size_t)gq * g.max_K;
 
@@ -125,7 +128,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
   int max_passes = 0;                               // overflow sweeps per round (set below)
   auto share_of = [&](int sw, int t, int known = -1) -> Share {   // known: the list's length if the caller has it
     const int r = sw < rounds ? sw : (sw - rounds) / max_passes;
-    const int s = kSweepEntries * (t + kSelThreads * r), list = s / T, pos = s % T;
+    const int s = kSweepEntries * (t + NTHR * r), list = s / T, pos = s % T;
     if (list >= n_reg) return Share{compact, 0, list};
     const int c = (int)min(known >= 0 ? (uint32_t)known : ccount[list], cap_w);
     if (sw < rounds) return Share{compact + s, max(0, min(min(c, T) - pos, kSweepEntries)), list};
@@ -148,7 +151,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
     __syncthreads();
     uint32_t tot = 0, ovp = 0;
     for (int r = 0; r < rounds; ++r) {
-      const int s = kSweepEntries * (tid + kSelThreads * r), list = s / T;
+      const int s = kSweepEntries * (tid + NTHR * r), list = s / T;
       if (s % T == 0 && list < n_reg) {               // the thread that owns the head of a list counts it
         const uint32_t c = min((r == 0 && have_e0) ? c0 : ccount[list], cap_w);
         tot += c;
@@ -164,7 +167,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
     __syncthreads();
     // (every workgroup of the head takes this branch, the counts it depends on being the score pass's, and writes
     // the same values to the rescan set: no ordering between them is needed)
-    rescan_head<D, TPI>(g, pr, blk, gq, n, n_chunks);
+    rescan_head<D, TPI, NTHR>(g, pr, blk, gq, n, n_chunks);
     ccount = (const uint32_t*)(blk + g.off_rescount) + (size_t)gq * n_reg_max;
     compact = (const uint2*)(blk + g.off_resc) + (size_t)gq * n_reg_max * T;
     sparse = (const uint2*)(blk + g.off_resf) + (size_t)gq * n_reg_max * cap_w;
@@ -186,7 +189,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
   // Wk[h] for the gather phase: requested now (the first sweep has arrived, nothing else is in flight), stored
   // to LDS right before the gather (the barrier after the histogram pass orders LDS only, so it does not wait
   // for these loads)
-  WkPieces<D, kSelThreads> wkp;
+  WkPieces<D, NTHR> wkp;
   wkp.request(pr.Wk, h);
   float bk_t = 0.f, pq_t = 0.f;
   if (tid < D) { bk_t = pr.bk[(size_t)h * D + tid]; pq_t = ((const float*)(blk + g.off_phiq))[(size_t)gq * D + tid]; }
@@ -206,7 +209,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
     const int n_cand = (int)total;
     const Share sh0 = share_of(0, tid, (int)min(c0, cap_w));
     const int nv = sh0.nvalid;
-    for (int i = tid; i < kFineBins; i += kSelThreads) sh_hist[i] = 0u;
+    for (int i = tid; i < kFineBins; i += NTHR) sh_hist[i] = 0u;
     if (tid == 0) {
       sh_bstar = -1; sh_krem = 0; sh_chi = 0; sh_nb = 0; sh_nbc = 0; sh_thr = 0ull;
       sh_r0 = l0 < n_reg ? 0 : n_cand; sh_r1 = n_cand;
@@ -225,16 +228,22 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
     lds_barrier();
     const int r0 = sh_r0, r1 = sh_r1;
     // ---- histogram -> boundary bin ----------------------------------------------------------------------------
-    for (int idx = tid; idx < n_cand; idx += kSelThreads) atomicAdd(&sh_hist[bin_of(score_key(__uint_as_float(dense[idx].x)))], 1u);
+    for (int idx = tid; idx < n_cand; idx += NTHR) atomicAdd(&sh_hist[bin_of(score_key(__uint_as_float(dense[idx].x)))], 1u);
     lds_barrier();
     TKPHI_PHASE(ws, 12);
     {
-      const int b1 = kFineBins - 1 - 2 * tid, b2 = b1 - 1;
-      const int c1 = (int)sh_hist[b1], c2 = (int)sh_hist[b2];
-      const int incl = sel_scan_incl(c1 + c2, sh_scan);
-      const int gt1 = incl - c1 - c2, ge1 = gt1 + c1, ge2 = incl;
-      if (ge1 >= Ksel && gt1 < Ksel) { sh_bstar = b1; sh_krem = Ksel - gt1; sh_chi = gt1; sh_nb = c1; }
-      if (ge2 >= Ksel && ge1 < Ksel) { sh_bstar = b2; sh_krem = Ksel - ge1; sh_chi = ge1; sh_nb = c2; }
+      // thread t takes the BPT bins below kFineBins - BPT t, highest first: a prefix sum over the threads is a
+      // suffix sum over the bins
+      constexpr int BPT = kFineBins / NTHR;
+      int cb[BPT], own = 0;
+#pragma unroll
+      for (int e = 0; e < BPT; ++e) { cb[e] = (int)sh_hist[kFineBins - 1 - BPT * tid - e]; own += cb[e]; }
+      int gt = sel_scan_incl(own, sh_scan) - own;          // candidates in bins above this thread's
+#pragma unroll
+      for (int e = 0; e < BPT; ++e) {
+        if (gt + cb[e] >= Ksel && gt < Ksel) { sh_bstar = kFineBins - 1 - BPT * tid - e; sh_krem = Ksel - gt; sh_chi = gt; sh_nb = cb[e]; }
+        gt += cb[e];
+      }
       lds_barrier();
     }
     const int bstar = sh_bstar, krem = sh_krem, c_hi = sh_chi, nb = sh_nb;
@@ -246,7 +255,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
     TKPHI_PHASE(ws, 13);
     // ---- thr: the K_rem-th best composite of the boundary bin -------------------------------------------------
     if (nb <= kBCap) {
-      for (int idx = tid; idx < n_cand; idx += kSelThreads) {
+      for (int idx = tid; idx < n_cand; idx += NTHR) {
         const uint2 en = dense[idx];
         const uint32_t key = score_key(__uint_as_float(en.x));
         if (bin_of(key) == bstar) {
@@ -256,7 +265,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
       }
       lds_barrier();
       const int sub = tid & 7, slot = tid >> 3;
-      for (int k0 = 0; k0 < nb; k0 += kSelThreads / 8) {
+      for (int k0 = 0; k0 < nb; k0 += NTHR / 8) {
         const int j = k0 + slot;
         const bool valid = j < nb;
         const uint64_t mine = valid ? bcand[j] : ~0ull;
@@ -288,11 +297,11 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
       *en = dense[idx];
       return composite(score_key(__uint_as_float(en->x)), en->y) >= thr;
     };
-    for (int base = r0; base < r1; base += kSelThreads) {
+    for (int base = r0; base < r1; base += NTHR) {
       uint2 en = make_uint2(0u, 0u);
       const int flag = is_winner(base + tid, r1, &en) ? 1 : 0;
       const int incl = sel_scan_incl(flag, sh_scan);
-      if (tid == kSelThreads - 1) sh_tot = incl;
+      if (tid == NTHR - 1) sh_tot = incl;
       const int at = my_count + incl - flag;
       lds_barrier();
       if (flag && at < kWinLds) { w_tok[at] = (int)en.y; w_s[at] = __uint_as_float(en.x); }
@@ -302,18 +311,18 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
     // the retrieved list of the head, for the export of the merge and for winners beyond the LDS stage
     if (my_count > kWinLds || pr.topk_idx) {
       int before = 0;
-      for (int idx = tid; idx < r0; idx += kSelThreads) { uint2 en; before += is_winner(idx, r0, &en) ? 1 : 0; }
+      for (int idx = tid; idx < r0; idx += NTHR) { uint2 en; before += is_winner(idx, r0, &en) ? 1 : 0; }
       const int incl_b = sel_scan_incl(before, sh_scan);
-      if (tid == kSelThreads - 1) sh_tot = incl_b;
+      if (tid == NTHR - 1) sh_tot = incl_b;
       lds_barrier();
       my_base = sh_tot;
       lds_barrier();
       int seen = 0;
-      for (int base = r0; base < r1; base += kSelThreads) {
+      for (int base = r0; base < r1; base += NTHR) {
         uint2 en = make_uint2(0u, 0u);
         const int flag = is_winner(base + tid, r1, &en) ? 1 : 0;
         const int incl = sel_scan_incl(flag, sh_scan);
-        if (tid == kSelThreads - 1) sh_tot = incl;
+        if (tid == NTHR - 1) sh_tot = incl;
         const int at = my_base + seen + incl - flag;
         if (flag && at < min(Ksel, g.max_K)) { sel_idx[at] = (int32_t)en.y; sel_score[at] = __uint_as_float(en.x); }
         __syncthreads();
@@ -325,7 +334,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
     // (the general path: several sweeps, more candidates than the packed array holds, or the lists of a rescan;
     // every phase reads its entries from the lists again)
     // ---- pass A: histogram of the candidates' fine bins ----------------------------------------------------------
-    for (int i = tid; i < kFineBins; i += kSelThreads) sh_hist[i] = 0u;
+    for (int i = tid; i < kFineBins; i += NTHR) sh_hist[i] = 0u;
     if (tid == 0) { sh_bstar = -1; sh_krem = 0; sh_chi = 0; sh_nb = 0; sh_nbc = 0; sh_thr = 0ull; }
     __syncthreads();
     for (int sw = 0; sw < n_sweeps; ++sw) {
@@ -339,13 +348,18 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
     lds_barrier();                                    // (the histogram is LDS traffic; the Wk loads stay in flight)
     TKPHI_PHASE(ws, 12);
     {
-      // thread t looks at bins kFineBins - 1 - 2t and kFineBins - 2 - 2t: a prefix scan over t is a suffix scan over the bins
-      const int b1 = kFineBins - 1 - 2 * tid, b2 = b1 - 1;
-      const int c1 = (int)sh_hist[b1], c2 = (int)sh_hist[b2];
-      const int incl = sel_scan_incl(c1 + c2, sh_scan);
-      const int gt1 = incl - c1 - c2, ge1 = gt1 + c1, ge2 = incl;
-      if (ge1 >= Ksel && gt1 < Ksel) { sh_bstar = b1; sh_krem = Ksel - gt1; sh_chi = gt1; sh_nb = c1; }
-      if (ge2 >= Ksel && ge1 < Ksel) { sh_bstar = b2; sh_krem = Ksel - ge1; sh_chi = ge1; sh_nb = c2; }
+      // thread t takes the BPT bins below kFineBins - BPT t, highest first: a prefix sum over the threads is a
+      // suffix sum over the bins
+      constexpr int BPT = kFineBins / NTHR;
+      int cb[BPT], own = 0;
+#pragma unroll
+      for (int e = 0; e < BPT; ++e) { cb[e] = (int)sh_hist[kFineBins - 1 - BPT * tid - e]; own += cb[e]; }
+      int gt = sel_scan_incl(own, sh_scan) - own;          // candidates in bins above this thread's
+#pragma unroll
+      for (int e = 0; e < BPT; ++e) {
+        if (gt + cb[e] >= Ksel && gt < Ksel) { sh_bstar = kFineBins - 1 - BPT * tid - e; sh_krem = Ksel - gt; sh_chi = gt; sh_nb = cb[e]; }
+        gt += cb[e];
+      }
       lds_barrier();
     }
     const int bstar = sh_bstar, krem = sh_krem, c_hi = sh_chi, nb = sh_nb;
@@ -378,7 +392,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
       }
       lds_barrier();
       const int sub = tid & 7, slot = tid >> 3;
-      for (int k0 = 0; k0 < nb; k0 += kSelThreads / 8) {
+      for (int k0 = 0; k0 < nb; k0 += NTHR / 8) {
         const int j = k0 + slot;
         const bool valid = j < nb;
         const uint64_t mine = valid ? bcand[j] : ~0ull;
@@ -398,7 +412,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
     } else {
       // the slot (sweep, thread, entry) as one index for the radix passes (e.g. all scores equal)
       auto get = [&](int j, uint64_t* v) {
-        const int sw = j / (kSelThreads * kSweepEntries), rem = j % (kSelThreads * kSweepEntries);
+        const int sw = j / (NTHR * kSweepEntries), rem = j % (NTHR * kSweepEntries);
         const Share sh = share_of(sw, rem / kSweepEntries);
         const int i = rem % kSweepEntries;
         if (i >= sh.nvalid) return false;
@@ -407,7 +421,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
         *v = composite(key, e.y);
         return bin_of(key) == bstar;
       };
-      const uint64_t t = radix_select_desc(n_sweeps * kSelThreads * kSweepEntries, krem, get, sh_hist, sh_scan, &sh_prefix, &sh_want);
+      const uint64_t t = radix_select_desc(n_sweeps * NTHR * kSweepEntries, krem, get, sh_hist, sh_scan, &sh_prefix, &sh_want);
       if (tid == 0) sh_thr = t;
       __syncthreads();
     }
@@ -433,7 +447,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
       // (winners of one sweep: <= 12288 mine, <= 12288 before: 16 bits each)
       const int packed = (mine ? nw : 0) | ((sh.list < l0 ? nw : 0) << 16);
       const int incl = sel_scan_incl(packed, sh_scan);
-      if (tid == kSelThreads - 1) sh_tot = incl;
+      if (tid == NTHR - 1) sh_tot = incl;
       int at = my_count + ((incl - packed) & 0xffff);   // rank among this workgroup's winners
       lds_barrier();
       const int tot = sh_tot;
@@ -473,7 +487,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
         }
         const int nw = __popc(fw);
         const int incl = sel_scan_incl(nw, sh_scan);
-        if (tid == kSelThreads - 1) sh_tot = incl;
+        if (tid == NTHR - 1) sh_tot = incl;
         int at = my_base + seen + incl - nw;
 #pragma unroll
         for (int i = 0; i < kSweepEntries; ++i) {
@@ -495,9 +509,9 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
   const int r = lane & 15, kg = lane >> 4;
   const int64_t head_off = (int64_t)h * pr.stride_head;
   constexpr int LPR = D / 8;                        // lanes per value row (16 bytes each)
-  constexpr int RPP = kSelThreads / LPR;            // rows per pass (64 or 128)
+  constexpr int RPP = NTHR / LPR;            // rows per pass (64 or 128)
   constexpr int NPASS = kBatch / RPP;               // value rows per thread and round (4)
-  constexpr int NTW = kBatch / (16 * kSelWaves);    // 16-token tiles per wavefront and round
+  constexpr int NTW = kBatch / (16 * NWV);    // 16-token tiles per wavefront and round
   const int seg = tid % LPR, rsub = tid / LPR;
   float run_m = -INFINITY, run_Z = 0.f, run_zs = 0.f, run_nu = 0.f, run_zv = 0.f;   // (nu, zv: channel tid < D)
   wkp.commit(wk_lds);                               // (requested before the histogram pass: long since arrived)
@@ -520,7 +534,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
     const int cnt = min(kBatch, my_count - b0);
 #pragma unroll
     for (int u = 0; u < NTW; ++u) {
-      const int t16 = (wv + u * kSelWaves) * 16;      // first token of this wavefront's u-th tile
+      const int t16 = (wv + u * NWV) * 16;      // first token of this wavefront's u-th tile
       if (t16 < cnt) {
         int tk; float s;
         winner(b0, t16 + r, &tk, &s);
@@ -563,7 +577,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
     // z_i of this wavefront's tokens
 #pragma unroll
     for (int u = 0; u < NTW; ++u) {
-      const int t16 = (wv + u * kSelWaves) * 16;
+      const int t16 = (wv + u * NWV) * 16;
       if (t16 < cnt) {
         float z[4];
         wave_feature_dots<D>(a[u], wk_lds, sh_bk, sh_pq, g.a, g.c, z);
@@ -620,7 +634,7 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
     {
       float nu_b = 0.f, zv_b = 0.f;
       if (tid < D) {
-        for (int k = 0; k < kSelWaves; ++k) { nu_b += red[(k * 2 + 0) * 128 + tid]; zv_b += red[(k * 2 + 1) * 128 + tid]; }
+        for (int k = 0; k < NWV; ++k) { nu_b += red[(k * 2 + 0) * 128 + tid]; zv_b += red[(k * 2 + 1) * 128 + tid]; }
       }
       // running combination with the earlier batches (log-sum-exp rescaling)
       const float m_new = fmaxf(run_m, mloc);
@@ -644,12 +658,12 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
 // with its first 256 threads: no separate merge launch.  The counters are cleared by the prep kernel of the same
 // call.  (The other wavefronts of that workgroup end before the merge's barriers: a barrier waits only for the
 // wavefronts of the workgroup that are still running.)
-template <int D, int TPI>
-__global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, const tkphi_problem* __restrict__ probs,
+template <int D, int TPI, int NTHR>
+__global__ __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(4, 4))) void select_gather_kernel(Geom g, const tkphi_problem* __restrict__ probs,
                                                                     char* __restrict__ ws, int mode) {
   __shared__ int sh_last;
   const int part = blockIdx.x, gq = blockIdx.y, p = blockIdx.z;
-  select_gather_body<D, TPI>(g, probs, ws, part, gq, p);
+  select_gather_body<D, TPI, NTHR>(g, probs, ws, part, gq, p);
   const int L = probs[p].L;
   if (L < 1 || L > g.max_L) return;                 // (the merge writes nothing for such a problem either)
   // The partial went out with GPU-coherent stores and the merge reads the partials with GPU-coherent loads; the
@@ -671,8 +685,12 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(Geom g, cons
 
 void launch_select_gather(const Geom& g, const tkphi_problem* probs, char* ws, int mode, hipStream_t s) {
   dim3 grid(g.sg_split, g.Hq, g.n_problems);       // (Geom::n_tiles of this pipeline: one partial per workgroup)
-  if (g.d == 128) TKPHI_LAUNCH(ST_SELECT, (select_gather_kernel<128, 4>), grid, dim3(kSelThreads), 0, s, g, probs, ws, mode);
-  else TKPHI_LAUNCH(ST_SELECT, (select_gather_kernel<64, 8>), grid, dim3(kSelThreads), 0, s, g, probs, ws, mode);
+  // Batches of short sequences at d = 64 (one workgroup per head, at least two heads per CU): 512-thread workgroups,
+  // two per CU, so that one head's memory round trips hide behind the other's arithmetic
+  const bool small_wg = g.d == 64 && g.sg_split == 1 && (long)g.Hq * g.n_problems >= 512 && g.max_K <= 1024;
+  if (g.d == 128) TKPHI_LAUNCH(ST_SELECT, (select_gather_kernel<128, 4, 1024>), grid, dim3(1024), 0, s, g, probs, ws, mode);
+  else if (small_wg) TKPHI_LAUNCH(ST_SELECT, (select_gather_kernel<64, 8, 512>), grid, dim3(512), 0, s, g, probs, ws, mode);
+  else TKPHI_LAUNCH(ST_SELECT, (select_gather_kernel<64, 8, 1024>), grid, dim3(1024), 0, s, g, probs, ws, mode);
 }
 
 }  // namespace tkphi

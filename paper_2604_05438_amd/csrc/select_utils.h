@@ -1,6 +1,6 @@
 // Workgroup-level pieces of the Top-K selection shared by the spill pipeline's kernels
 // (topk_select.hip) and the fused select + gather kernel of the filtered pipeline
-// (select_gather.hip): 1024-thread prefix sums, the (score key, lower index first) composite and
+// (select_gather.hip): workgroup-wide prefix sums, the (score key, lower index first) composite and
 // the radix search for the n-th largest composite.
 #pragma once
 
@@ -10,7 +10,7 @@ namespace tkphi {
 
 constexpr int kSelWaves = kSelThreads / 64;
 
-// inclusive prefix sum over the 1024 threads; sh must hold >= 16 ints; two barriers (ordering LDS only)
+// inclusive prefix sum over the threads of the workgroup; sh must hold one int per wavefront; two barriers (ordering LDS only)
 __device__ __forceinline__ int sel_scan_incl(int v, int* sh) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   int x = v;
@@ -46,7 +46,7 @@ __device__ uint64_t radix_select_desc(int count, int want, Get get, uint32_t* sh
     const uint64_t prefix = *sh_prefix;
     const int w = *sh_want;
     const uint64_t himask = shift == 56 ? 0ull : (~0ull << (shift + 8));
-    for (int j = tid; j < count; j += kSelThreads) {
+    for (int j = tid; j < count; j += (int)blockDim.x) {
       uint64_t v;
       if (get(j, &v) && (v & himask) == prefix) atomicAdd(&sh_hist[(uint32_t)(v >> shift) & 255u], 1u);
     }
