@@ -263,18 +263,23 @@ def test_exact_ties_take_lower_index(variant):
 
 
 @pytest.mark.parametrize("variant", ["filtered", "rescan", "no_pruning"])
-def test_batch_of_many_heads_uses_small_workgroups(variant):
+@pytest.mark.parametrize("shape", ["l1b_32k", "l3b_128k"])
+def test_batch_of_many_heads_uses_small_workgroups(shape, variant):
     """A batch with at least 512 query heads at head dimension 64 (16 problems x 32 heads) runs the fused select +
-    gather kernel with 512-thread workgroups, two per CU; fewer heads run it with 1024 threads.  Same checks as for
-    one problem: index sets, scores, outputs of several heads of every kind of problem against the oracle, through
-    the common path, the rescan of every head and the path without pruning; one problem has identical keys (the
-    radix passes), some have tiny budgets, one has no mid-region."""
+    gather kernel with 512-thread workgroups, two per CU; fewer heads, and head dimension 128 (22 problems x 24 heads
+    here), run it with 1024 threads and one workgroup per head.  Same checks as for one problem: index sets, scores, outputs of several heads of every kind of problem against the
+    oracle, through the common path, the rescan of every head and the path without pruning; one problem has identical
+    keys (the radix passes), some have tiny budgets, one has no mid-region, one retrieves more than a gather round
+    and more winners than stay in LDS."""
     import parity_utils as PU
     from paper_2604_05438_amd import harness as H
-    w = I.WORKLOADS["l1b_32k"]
+    w = I.WORKLOADS[shape]
     edge = w.n_sink + w.n_tail
     Ls = [5000, 2500, 777, 4229, 9000, edge + 1, edge, 40, 3001, 6000, 1500, 2048 + edge, 8192, 700, 12000, 4097]
     ks = [49, 24, 7, 300, 90, 1, 0, 3, 1, 600, 15, 20, 81, 700, 120, 40]
+    if shape == "l3b_128k":
+        Ls += [3000, 2000, 1000, 5000, 2500, 4000]
+        ks += [30, 20, 10, 1400, 25, 40]
     layers = [I.make_layer(w, L=l, seq=i) for i, l in enumerate(Ls)]
     layers[8]["K"][:, :, :] = layers[8]["K"][:, 100:101, :]           # every score of problem 8 equal: Top-1 = first mid token
     b = H.Batch(H.config_of(w, tuning=SELECT_VARIANTS[variant]), layers, ks, debug=True)
@@ -282,9 +287,9 @@ def test_batch_of_many_heads_uses_small_workgroups(variant):
     b.build(); b.decode()
     assert b.status() == 0
     assert b.result(8, "topk_idx")[:, 0].tolist() == [w.n_sink] * w.n_q_heads
-    for i in (0, 2, 3, 4, 5, 7, 9, 13, 14):
+    for i in (0, 2, 3, 4, 5, 7, 9, 13, 14) + ((19,) if shape == "l3b_128k" else ()):
         rep = PU.check_layer(w, layers[i], ks[i], b, i, heads=[0, 13, w.n_q_heads - 1])
-        print("many heads", variant, "problem", i, Ls[i], ks[i], rep, flush=True)
+        print("many heads", shape, variant, "problem", i, Ls[i], ks[i], rep, flush=True)
 
 
 @pytest.mark.parametrize("variant", list(SELECT_VARIANTS))
