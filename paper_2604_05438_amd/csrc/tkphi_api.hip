@@ -1,6 +1,7 @@
 // Host layer of libtkphi: argument validation, launch geometry / workspace planning and
 // the extern "C" entry points declared in include/tkphi.h.
 #include <algorithm>
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -139,6 +140,26 @@ tkphi_status make_geom(const tkphi_config* cfg, int n_problems, int max_L, int m
   const int64_t bc_small = std::clamp<int64_t>(ceil_div(units, 512), 256, 2048);
   int bc = (int)align_up((size_t)std::clamp<int64_t>(ceil_div(units, 2048), bc_small, 1 << 20), 64);
   if (!g->use_mfma) bc = std::min(bc, 4096);    // fp32 FMA chains stay short on the generic kernel
+  // Several resident rounds of the matrix-core kernel (512 workgroup slots at d = 128, 1024 at d = 64): among the
+  // chunk counts within two of that guess, the one whose last round is fullest (28 layers of 128K: 9 chunks per head
+  // = 2016 workgroups = 3.94 rounds instead of 10 = 4.375, which pays for 5)
+  if (g->use_mfma && cfg->phi_kind == TKPHI_PHI_EXP_AFFINE && g->max_mid > 0) {
+    const int64_t slots = g->d == 64 ? 1024 : 512, heads = (int64_t)g->Hkv * std::max(n_problems, 1);
+    const int64_t c0 = ceil_div(g->max_mid, bc);
+    if (c0 * heads > slots) {
+      double best_fill = -1.0;
+      int best_bc = bc;
+      for (int64_t c = std::max<int64_t>(1, c0 - 2); c <= c0 + 2; ++c) {
+        const int cand = (int)align_up((size_t)std::max<int64_t>(256, ceil_div(g->max_mid, c)), 64);
+        const int64_t wgs = ceil_div(g->max_mid, cand) * heads;
+        const double fill = (double)wgs / (double)(ceil_div(wgs, slots) * slots);
+        if (fill > best_fill + 1e-9 || (std::fabs(fill - best_fill) <= 1e-9 && std::abs(cand - bc) < std::abs(best_bc - bc))) {
+          best_fill = fill; best_bc = cand;
+        }
+      }
+      bc = best_bc;
+    }
+  }
   if (tn.build_chunk > 0) bc = tn.build_chunk;
   g->build_chunk = std::max(64, bc / 64 * 64);
   g->n_build_chunks = (int)std::max<int64_t>(1, ceil_div(g->max_mid, g->build_chunk));
