@@ -297,16 +297,23 @@ __device__ __forceinline__ void select_gather_body(const Geom& g, const tkphi_pr
       *en = dense[idx];
       return composite(score_key(__uint_as_float(en->x)), en->y) >= thr;
     };
-    for (int base = r0; base < r1; base += NTHR) {
-      uint2 en = make_uint2(0u, 0u);
-      const int flag = is_winner(base + tid, r1, &en) ? 1 : 0;
-      const int incl = sel_scan_incl(flag, sh_scan);
+    {
+      // thread t owns the `per` consecutive entries from r0 + t per: one prefix sum over the threads keeps list order
+      const int per = (r1 - r0 + NTHR - 1) / NTHR, first = r0 + tid * per;
+      int mine = 0;
+      for (int e = 0; e < per; ++e) { uint2 en; mine += is_winner(first + e, r1, &en) ? 1 : 0; }
+      const int incl = sel_scan_incl(mine, sh_scan);
       if (tid == NTHR - 1) sh_tot = incl;
-      const int at = my_count + incl - flag;
+      int at = incl - mine;
+      for (int e = 0; e < per; ++e) {
+        uint2 en;
+        if (is_winner(first + e, r1, &en)) {
+          if (at < kWinLds) { w_tok[at] = (int)en.y; w_s[at] = __uint_as_float(en.x); }
+          ++at;
+        }
+      }
       lds_barrier();
-      if (flag && at < kWinLds) { w_tok[at] = (int)en.y; w_s[at] = __uint_as_float(en.x); }
-      my_count += sh_tot;
-      lds_barrier();
+      my_count = sh_tot;
     }
     // the retrieved list of the head, for the export of the merge and for winners beyond the LDS stage
     if (my_count > kWinLds || pr.topk_idx) {
